@@ -1,0 +1,141 @@
+"""ctypes front end of the fp64 patch-by-patch oracle (`mpcnn_oracle.c`).
+
+TEST INFRASTRUCTURE ONLY: imported by `tests/`, by the smoke check and by the
+bench's cpu_baseline leg.  It imports nothing from the HIP package, and the HIP
+package imports nothing from here.
+
+Network description: a list of (kind, maps, k) integer triples, kind 0 = C
+(maps, kernel side), 1 = MP (k = pooling side), 2 = FC (maps); plus the number
+of input channels and the patch side P.  Parameters are one flat fp64 vector,
+layer by layer W[o][c][u][v] then b[o] (Background, layer definitions).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mpcnn_oracle.c")
+_LIB = os.path.join(_HERE, "liborc.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP over patches)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_param_count.restype = C.c_long
+    return _lib
+
+
+def _desc(layers):
+    arr = np.asarray(layers, dtype=np.int32).reshape(-1, 3)
+    kinds = np.ascontiguousarray(arr[:, 0])
+    maps = np.ascontiguousarray(arr[:, 1])
+    ks = np.ascontiguousarray(arr[:, 2])
+    return kinds, maps, ks, len(arr)
+
+
+def _p(a, ct):
+    return None if a is None else a.ctypes.data_as(C.POINTER(ct))
+
+
+def threads() -> int:
+    return int(_load().orc_threads())
+
+
+def param_count(layers, in_ch: int, patch: int) -> int:
+    kinds, maps, ks, n = _desc(layers)
+    r = _load().orc_param_count(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n,
+                                in_ch, patch)
+    if r < 0:
+        raise ValueError("bad network description (code %d)" % r)
+    return int(r)
+
+
+def run(layers, in_ch, patch, params, image, labels=None, pixw=None, sel=None,
+        want_probs=True, want_grads=False, want_dimage=False):
+    """Patch-by-patch forward (and backward).  Returns a dict with probs, loss,
+    grads, dimage (those asked for).  probs is [B,n_cls,Ho,Wo], or [n_sel,n_cls]
+    when `sel` (flat indices into [B,Ho,Wo]) is given."""
+    lib = _load()
+    kinds, maps, ks, n = _desc(layers)
+    params = np.ascontiguousarray(params, dtype=np.float64)
+    image = np.ascontiguousarray(image, dtype=np.float64)
+    B, Cc, H, W = image.shape
+    assert Cc == in_ch
+    npar = param_count(layers, in_ch, patch)
+    assert params.size == npar, (params.size, npar)
+    n_cls = int(maps[-1])
+    Ho, Wo = H - patch + 1, W - patch + 1
+    if labels is not None:
+        labels = np.ascontiguousarray(labels, dtype=np.int32)
+        assert labels.shape == (B, H, W)
+    if pixw is not None:
+        pixw = np.ascontiguousarray(pixw, dtype=np.float64)
+        assert pixw.shape == (B, H, W)
+    n_sel = 0
+    if sel is not None:
+        sel = np.ascontiguousarray(sel, dtype=np.int64)
+        n_sel = sel.size
+        assert sel.min() >= 0 and sel.max() < B * Ho * Wo
+    probs = None
+    if want_probs:
+        probs = np.zeros((n_sel, n_cls) if sel is not None else (B, n_cls, Ho, Wo))
+    loss = C.c_double(0.0)
+    grads = np.zeros(npar) if want_grads else None
+    dimage = np.zeros_like(image) if want_dimage else None
+    rc = lib.orc_run(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch, patch,
+                     _p(params, C.c_double), _p(image, C.c_double), B, H, W,
+                     _p(labels, C.c_int32), _p(pixw, C.c_double), _p(sel, C.c_int64),
+                     C.c_long(n_sel), _p(probs, C.c_double),
+                     C.byref(loss) if labels is not None else None,
+                     _p(grads, C.c_double), _p(dimage, C.c_double))
+    if rc != 0:
+        raise ValueError("orc_run failed (code %d)" % rc)
+    return {"probs": probs, "loss": loss.value if labels is not None else None,
+            "grads": grads, "dimage": dimage}
+
+
+def dense_layer(layers, in_ch, patch, params, image, layer):
+    """Outputs of layer `layer` of every patch laid over the image.  Returns
+    dict(act [B,ch,ny,nx], codes, gap (MP layers, else None), covered [B,ny,nx],
+    stride)."""
+    lib = _load()
+    kinds, maps, ks, n = _desc(layers)
+    params = np.ascontiguousarray(params, dtype=np.float64)
+    image = np.ascontiguousarray(image, dtype=np.float64)
+    B, Cc, H, W = image.shape
+    ny, nx, ch, st = C.c_int(), C.c_int(), C.c_int(), C.c_int()
+    rc = lib.orc_dense_shape(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch,
+                             patch, H, W, layer, C.byref(ny), C.byref(nx), C.byref(ch),
+                             C.byref(st))
+    if rc != 0:
+        raise ValueError("orc_dense_shape failed (code %d)" % rc)
+    shape = (B, ch.value, ny.value, nx.value)
+    is_mp = int(kinds[layer]) == 1
+    act = np.zeros(shape)
+    codes = np.zeros(shape, dtype=np.uint8) if is_mp else None
+    gap = np.zeros(shape) if is_mp else None
+    covered = np.zeros((B, ny.value, nx.value), dtype=np.uint8)
+    rc = lib.orc_dense_layer(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch,
+                             patch, _p(params, C.c_double), _p(image, C.c_double), B, H, W,
+                             layer, _p(act, C.c_double), _p(codes, C.c_uint8),
+                             _p(gap, C.c_double), _p(covered, C.c_uint8))
+    if rc != 0:
+        raise ValueError("orc_dense_layer failed (code %d)" % rc)
+    return {"act": act, "codes": codes, "gap": gap, "covered": covered.astype(bool),
+            "stride": st.value}
