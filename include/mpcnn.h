@@ -1,0 +1,162 @@
+/*
+ * mpcnn.h - C ABI of libmpcnn: whole-image forward / backward of a MaxPooling
+ * Convolutional Network (MPCNN) for per-pixel classification on one MI355X.
+ *
+ * What the library computes (Masci, Giusti, Ciresan, Fricout, Schmidhuber,
+ * "A Fast Learning Algorithm for Image Segmentation with Max-Pooling
+ * Convolutional Networks"):  a net made of C / MP / FC layers (Background) is
+ * defined on a P x P patch and labels the patch's centre pixel.  Instead of
+ * running it on every patch, the whole image is pushed through once (Method,
+ * "The MaxPoolingFragment (MPF) layer", Alg. 1 and 3) and the per-pixel errors
+ * are pushed back once (Method, "Back-propagation through an MPF layer",
+ * Alg. 2 and 4).  Outputs equal, up to floating-point rounding, what the patch
+ * net gives on the patch around every pixel, and the parameter gradient equals
+ * the sum over all patches.
+ *
+ * Conventions
+ *   - "host" / "dev" in a parameter name says where the pointer must live.
+ *     All device memory except parameters and gradients belongs to the caller.
+ *   - Image layout [B][C0][H][W] fp32 (planar).  Output pixel (i,j) of image b is
+ *     the patch whose top-left corner is (i,j); there are (H-P+1) x (W-P+1) of
+ *     them.  Its label and loss weight are read at image pixel (i+c, j+c),
+ *     c = (P-1)/2 rounded down.
+ *   - Parameter vectors on the host are flat fp32, layer by layer
+ *     W[o][c][u][v] then b[o]; MP layers have none.  The first FC layer sees the
+ *     remaining q x q maps flattened [c][r][s], i.e. its W is [o][c][q][q];
+ *     later FC layers have 1 x 1 kernels.  Filtering is correlation (no flip).
+ *   - C layers and all FC layers but the last apply tanh; the last FC layer
+ *     feeds a softmax; the loss is the cross-entropy SUMMED over pixels
+ *     (Results: multi-class cross-entropy, each pixel on its own).
+ *   - Every call returns a status; nothing throws or aborts.  After an error,
+ *     outputs are unspecified but nothing is written out of bounds.
+ *     mpcnn_last_error() gives the calling thread's last message.
+ *   - Calls that take a stream only enqueue work on it (they do not wait).
+ *     One net must not be used from two streams at once.
+ */
+#ifndef MPCNN_H
+#define MPCNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mpcnn_net mpcnn_net; /* opaque: layer plan, parameters, gradients */
+
+typedef enum {
+    MPCNN_OK = 0,
+    MPCNN_EINVAL = 1,       /* null pointer, bad count, bad enum */
+    MPCNN_ESHAPE = 2,       /* layer list does not fit the patch, or image smaller than the patch */
+    MPCNN_EWORKSPACE = 3,   /* workspace smaller than mpcnn_workspace_bytes() */
+    MPCNN_EUNSUPPORTED = 4, /* valid per the paper but not built (see each call) */
+    MPCNN_EHIP = 5,         /* a HIP runtime call failed */
+    MPCNN_ENOMEM = 6
+} mpcnn_status;
+
+typedef enum { MPCNN_C = 0, MPCNN_MP = 1, MPCNN_FC = 2 } mpcnn_kind;
+
+/* Storage type of activations and weights; accumulation is always fp32. */
+typedef enum { MPCNN_F32 = 0, MPCNN_BF16 = 1 } mpcnn_dtype;
+
+/* One layer (Background, layer kinds).  C: `maps` output maps, k x k filters.
+ * MP: non-overlapping k x k max-pooling (maps ignored).  FC: `maps` units
+ * (k ignored); the last layer must be FC and its `maps` is the class count. */
+typedef struct {
+    int kind; /* mpcnn_kind */
+    int maps;
+    int k;
+} mpcnn_layer_desc;
+
+/*
+ * Build the layer plan for a net that sees a `patch` x `patch` window of an
+ * image with `in_channels` channels.  Host-only: allocates no device memory
+ * (parameters are allocated on the current device by mpcnn_set_params).
+ * Errors: EINVAL (null / counts / kinds), ESHAPE (a layer does not fit; no FC
+ * at the end; C or MP after an FC), EUNSUPPORTED (a pool whose input side, in
+ * patch coordinates, is not a multiple of k; k*k > 255; more than 16 classes;
+ * dtype other than MPCNN_F32).
+ */
+mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers_host, int n_layers, int in_channels,
+                              int patch, mpcnn_dtype dtype, mpcnn_net** out);
+void mpcnn_net_destroy(mpcnn_net* net); /* frees parameters and gradients; NULL is allowed */
+
+int mpcnn_net_patch(const mpcnn_net* net);      /* P */
+int mpcnn_net_classes(const mpcnn_net* net);    /* maps of the last FC */
+size_t mpcnn_param_count(const mpcnn_net* net); /* length of the flat parameter vector */
+
+/*
+ * Shape of the whole-image ("dense") map that layer `layer` produces for an
+ * H x W image: rows, columns, channels, and the spacing in image pixels
+ * between elements that are neighbours inside one patch (the product of the
+ * pooling factors so far; the MPF offsets of Alg. 3 are the residues modulo
+ * this spacing).  Host-only.
+ */
+mpcnn_status mpcnn_layer_shape(const mpcnn_net* net, int H, int W, int layer, int* rows, int* cols,
+                               int* channels, int* spacing);
+
+/* Copy the flat fp32 parameter vector from / to the host (synchronous).
+ * n must equal mpcnn_param_count().  The first mpcnn_set_params allocates the
+ * parameter and gradient buffers on the current device. */
+mpcnn_status mpcnn_set_params(mpcnn_net* net, const float* params_host, size_t n);
+mpcnn_status mpcnn_get_params(const mpcnn_net* net, float* params_host, size_t n);
+/* Gradient of the summed loss left by the last mpcnn_seg_backward, same order
+ * as the parameters (Alg. 2: the sum over all fragments / pixels). */
+mpcnn_status mpcnn_get_grads(const mpcnn_net* net, float* grads_host, size_t n);
+
+/* Bytes of caller-owned device workspace a call with these sizes needs
+ * (training != 0: mpcnn_seg_backward; 0: mpcnn_seg_forward).  0 on bad input. */
+size_t mpcnn_workspace_bytes(const mpcnn_net* net, int B, int H, int W, int training);
+
+/*
+ * Whole-image forward (Alg. 1 / Alg. 3 over all layers):
+ *   image_dev [B][C0][H][W] fp32  ->  probs_dev [B][n_classes][H-P+1][W-P+1] fp32,
+ * the softmax output of the patch net for every pixel.  ws_dev: 256-byte
+ * aligned scratch of at least mpcnn_workspace_bytes(net,B,H,W,0).
+ * Errors: EINVAL, ESHAPE (H or W < P), EWORKSPACE, EHIP.
+ */
+mpcnn_status mpcnn_seg_forward(mpcnn_net* net, const float* image_dev, int B, int H, int W,
+                               float* probs_dev, void* ws_dev, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Whole-image forward + backward (Alg. 1-4): computes the loss
+ *   L = sum over b,i,j of w * -log p[b, t, i, j],  t = labels[b][i+c][j+c],
+ *   w = pixw[b][i+c][j+c] (1 if pixw_dev is NULL); pixels with t < 0 or
+ *   t >= n_classes add nothing;
+ * and leaves dL/dW, dL/db of every layer in the net (read with mpcnn_get_grads,
+ * consumed by mpcnn_sgd_step).
+ *   labels_dev [B][H][W] int32, pixw_dev [B][H][W] fp32 or NULL,
+ *   probs_dev  as in mpcnn_seg_forward, or NULL,
+ *   loss_dev   one fp64 on the device, or NULL,
+ *   ws_dev     at least mpcnn_workspace_bytes(net,B,H,W,1); it holds every
+ *              layer's activations and argmax maps until the next call.
+ * The result does not depend on launch timing: no floating-point atomics are
+ * used, reductions have a fixed order.
+ */
+mpcnn_status mpcnn_seg_backward(mpcnn_net* net, const float* image_dev, const int32_t* labels_dev,
+                                const float* pixw_dev, int B, int H, int W, float* probs_dev,
+                                double* loss_dev, void* ws_dev, size_t ws_bytes, void* hip_stream);
+
+/* Plain gradient step on every parameter: theta -= lr * grad_scale * g
+ * (Results, "Membrane Segmentation": weights updated after every image). */
+mpcnn_status mpcnn_sgd_step(mpcnn_net* net, float lr, float grad_scale, void* hip_stream);
+
+/*
+ * Test hooks: read back what the last forward/backward left in the workspace
+ * (which must still be alive).  Synchronous.
+ *   mpcnn_get_activation: output of layer `layer`, [B][rows][cols][channels] fp32.
+ *   mpcnn_get_argmax:     for MP layer `layer`, the tap code u*k+v of the first
+ *                         maximum in row-major (u,v) order of every pooled
+ *                         element (the mpIDXS of Alg. 3), [B][rows][cols][channels].
+ * n = number of elements the host buffer holds; must match.
+ */
+mpcnn_status mpcnn_get_activation(const mpcnn_net* net, int layer, float* host, size_t n);
+mpcnn_status mpcnn_get_argmax(const mpcnn_net* net, int layer, uint8_t* host, size_t n);
+
+const char* mpcnn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPCNN_H */

@@ -67,10 +67,15 @@ def param_count(layers, in_ch: int, patch: int) -> int:
 
 
 def run(layers, in_ch, patch, params, image, labels=None, pixw=None, sel=None,
-        want_probs=True, want_grads=False, want_dimage=False):
+        want_probs=True, want_grads=False, want_dimage=False, tie_tau=0.0, alt=None):
     """Patch-by-patch forward (and backward).  Returns a dict with probs, loss,
     grads, dimage (those asked for).  probs is [B,n_cls,Ho,Wo], or [n_sel,n_cls]
-    when `sel` (flat indices into [B,Ho,Wo]) is given."""
+    when `sel` (flat indices into [B,Ho,Wo]) is given.
+
+    tie_tau > 0: also returns `near_ties`, an int64 array [n,4] of (window key,
+    chosen tap, runner-up tap, layer) for every pooling window whose two largest
+    values are within tie_tau; `alt`: keys of such windows whose runner-up tap is
+    to receive the gradient instead (see orc_ties in the C source)."""
     lib = _load()
     kinds, maps, ks, n = _desc(layers)
     params = np.ascontiguousarray(params, dtype=np.float64)
@@ -98,16 +103,50 @@ def run(layers, in_ch, patch, params, image, labels=None, pixw=None, sel=None,
     loss = C.c_double(0.0)
     grads = np.zeros(npar) if want_grads else None
     dimage = np.zeros_like(image) if want_dimage else None
+    amb_cap = 1 << 20
+    amb = np.zeros((amb_cap, 4), dtype=np.int64) if tie_tau > 0 else None
+    amb_n = C.c_long(0)
+    n_alt = 0
+    if alt is not None:
+        alt = np.ascontiguousarray(np.unique(np.asarray(alt, dtype=np.int64)))
+        n_alt = alt.size
     rc = lib.orc_run(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch, patch,
                      _p(params, C.c_double), _p(image, C.c_double), B, H, W,
                      _p(labels, C.c_int32), _p(pixw, C.c_double), _p(sel, C.c_int64),
                      C.c_long(n_sel), _p(probs, C.c_double),
                      C.byref(loss) if labels is not None else None,
-                     _p(grads, C.c_double), _p(dimage, C.c_double))
+                     _p(grads, C.c_double), _p(dimage, C.c_double),
+                     C.c_double(tie_tau), _p(alt, C.c_int64), C.c_long(n_alt),
+                     _p(amb, C.c_int64), C.c_long(amb_cap if amb is not None else 0),
+                     C.byref(amb_n))
     if rc != 0:
         raise ValueError("orc_run failed (code %d)" % rc)
+    near = None
+    if amb is not None:
+        if amb_n.value > amb_cap:
+            raise ValueError("more than %d near-tie records" % amb_cap)
+        near = np.unique(amb[:amb_n.value], axis=0)
     return {"probs": probs, "loss": loss.value if labels is not None else None,
-            "grads": grads, "dimage": dimage}
+            "grads": grads, "dimage": dimage, "near_ties": near}
+
+
+def window_key(layers, in_ch, patch, B, H, W, layer, b, c, y, x):
+    """Key of a pooling window in the whole-image map of MP layer `layer` (see orc_ties)."""
+    _, ch, ny, nx = dense_shape(layers, in_ch, patch, B, H, W, layer)[:4]
+    return (((layer * B + b) * ch + c) * ny + y) * nx + x
+
+
+def dense_shape(layers, in_ch, patch, B, H, W, layer):
+    """(B, channels, rows, cols, stride) of layer `layer`'s whole-image map."""
+    lib = _load()
+    kinds, maps, ks, n = _desc(layers)
+    ny, nx, ch, st = C.c_int(), C.c_int(), C.c_int(), C.c_int()
+    rc = lib.orc_dense_shape(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch,
+                             patch, H, W, layer, C.byref(ny), C.byref(nx), C.byref(ch),
+                             C.byref(st))
+    if rc != 0:
+        raise ValueError("orc_dense_shape failed (code %d)" % rc)
+    return B, ch.value, ny.value, nx.value, st.value
 
 
 def dense_layer(layers, in_ch, patch, params, image, layer):

@@ -95,11 +95,44 @@ static int orc_make_plan(orc_plan *pl, const int *kinds, const int *maps, const 
     return 0;
 }
 
+/*
+ * Near-ties.  The argmax of a pooling window is an integer decided by floating
+ * point; a path that computes the same map in another precision can rank two
+ * candidates closer than its rounding error the other way round, and both
+ * rankings are then valid sub-gradients of the max.  So that such a result can
+ * be checked exactly, the oracle can (a) report every window whose two largest
+ * values are within `tau` of each other, with the tap it chose and the
+ * runner-up tap, and (b) re-run with a list `alt` of such windows in which the
+ * runner-up tap receives the back-propagated value instead (the forward value
+ * stays the true maximum).  A window is named by its position in the
+ * whole-image map of that MP layer: key = (((layer*B + b)*C + c)*ny + y)*nx + x.
+ * With tau = 0 and no list this is the plain first-maximum rule.
+ */
+typedef struct {
+    double tau;
+    const int64_t *alt; long n_alt;          /* sorted keys */
+    int64_t *amb; long amb_cap; long *amb_n; /* records of 4: key, chosen tap, runner-up tap, layer */
+    int B, H, W;                             /* image batch and size, for the keys */
+} orc_ties;
+
+static int orc_key_listed(const orc_ties *t, int64_t key)
+{
+    long lo = 0, hi = t->n_alt - 1;
+    while (lo <= hi) {
+        long mid = (lo + hi) / 2;
+        if (t->alt[mid] == key) return 1;
+        if (t->alt[mid] < key) lo = mid + 1; else hi = mid - 1;
+    }
+    return 0;
+}
+
 /* Forward of ONE patch.  act: all layer outputs; idx: argmax codes u*p+v of
  * every pooled element; gap (optional): largest minus second largest value of
- * every pooling window (0 on an exact tie).  probs: softmax of the last FC. */
+ * every pooling window (0 on an exact tie).  probs: softmax of the last FC.
+ * ties (optional) with the patch's image index b and corner (pi,pj): see above. */
 static void orc_patch_forward(const orc_plan *pl, const double *par, double *act,
-                              uint8_t *idx, double *gap, double *probs)
+                              uint8_t *idx, double *gap, double *probs,
+                              const orc_ties *ties, int pb, int pi, int pj)
 {
     for (int l = 0; l < pl->n_layers; ++l) {
         const double *x = act + pl->act_off[l];
@@ -110,16 +143,34 @@ static void orc_patch_forward(const orc_plan *pl, const double *par, double *act
             for (int c = 0; c < co; ++c)
                 for (int r = 0; r < m; ++r)
                     for (int s = 0; s < m; ++s) {
-                        double best = 0, second = 0; int code = -1;
+                        double best = 0, second = 0; int code = -1, code2 = -1;
                         for (int u = 0; u < k; ++u)
                             for (int v = 0; v < k; ++v) {
                                 double a = x[((long)c * n + (k * r + u)) * n + (k * s + v)];
                                 if (code < 0) { best = a; code = 0; second = -INFINITY; }
-                                else if (a > best) { second = best; best = a; code = u * k + v; }
-                                else if (a > second) second = a;
+                                else if (a > best) { second = best; code2 = code; best = a; code = u * k + v; }
+                                else if (a > second) { second = a; code2 = u * k + v; }
                             }
                         long e = ((long)c * m + r) * m + s;
                         y[e] = best;
+                        if (ties && code2 >= 0 && best - second <= ties->tau) {
+                            const int st = pl->stride_out[l];
+                            const long ny = ties->H - pl->patch + pl->reach_out[l] + 1;
+                            const long nx = ties->W - pl->patch + pl->reach_out[l] + 1;
+                            int64_t key = ((((int64_t)l * ties->B + pb) * co + c) * ny + (pi + r * st)) * nx
+                                          + (pj + s * st);
+                            if (ties->amb) {
+#pragma omp critical(orc_amb)
+                                {
+                                    long q = (*ties->amb_n)++;
+                                    if (q < ties->amb_cap) {
+                                        ties->amb[4 * q] = key; ties->amb[4 * q + 1] = code;
+                                        ties->amb[4 * q + 2] = code2; ties->amb[4 * q + 3] = l;
+                                    }
+                                }
+                            }
+                            if (ties->n_alt > 0 && orc_key_listed(ties, key)) code = code2;
+                        }
                         idx[pl->idx_off[l] + e] = (uint8_t)code;
                         if (gap) gap[pl->idx_off[l] + e] = (k * k > 1) ? best - second : INFINITY;
                     }
@@ -238,11 +289,16 @@ int orc_threads(void)
  *   dimage  [B][in_ch][H][W] dL/d(image), sum over patches (may be NULL; small inputs)
  * Output pixel (i,j) is the patch with top-left corner (i,j); its label and
  * weight are read at image pixel (i+c, j+c), c = (P-1)/2 rounded down.
+ *   tie_tau, alt, amb: near-tie reporting / alternative routing (see orc_ties);
+ *   amb receives up to amb_cap records of 4 int64, *amb_n the number met (the
+ *   same window is reported once per patch that contains it).
  */
 int orc_run(const int *kinds, const int *maps, const int *ks, int n_layers, int in_ch, int patch,
             const double *params, const double *image, int B, int H, int W,
             const int32_t *labels, const double *pixw, const int64_t *sel, long n_sel,
-            double *probs, double *loss, double *grads, double *dimage)
+            double *probs, double *loss, double *grads, double *dimage,
+            double tie_tau, const int64_t *alt, long n_alt,
+            int64_t *amb, long amb_cap, long *amb_n)
 {
     orc_plan pl;
     int rc = orc_make_plan(&pl, kinds, maps, ks, n_layers, in_ch, patch);
@@ -257,6 +313,10 @@ int orc_run(const int *kinds, const int *maps, const int *ks, int n_layers, int 
     double *di_all = dimage ? calloc((size_t)nt * n_img, sizeof(double)) : NULL;
     double *loss_all = calloc((size_t)nt, sizeof(double));
     int fail = 0;
+    long amb_dummy = 0;
+    orc_ties ties = { tie_tau, alt, alt ? n_alt : 0, amb, amb_cap, amb_n ? amb_n : &amb_dummy, B, H, W };
+    const orc_ties *tp = (tie_tau > 0 || ties.n_alt > 0) ? &ties : NULL;
+    if (amb_n) *amb_n = 0;
 #pragma omp parallel num_threads(nt)
     {
 #ifdef _OPENMP
@@ -278,7 +338,7 @@ int orc_run(const int *kinds, const int *maps, const int *ks, int n_layers, int 
                 int b = (int)(f / ((long)Ho * Wo));
                 int i = (int)((f / Wo) % Ho), j = (int)(f % Wo);
                 orc_crop(&pl, image, H, W, b, i, j, act);
-                orc_patch_forward(&pl, params, act, idx, NULL, pr);
+                orc_patch_forward(&pl, params, act, idx, NULL, pr, tp, b, i, j);
                 if (probs) {
                     for (int o = 0; o < nc; ++o) {
                         if (sel) probs[q * nc + o] = pr[o];
@@ -381,7 +441,7 @@ int orc_dense_layer(const int *kinds, const int *maps, const int *ks, int n_laye
                 int b = (int)(q / ((long)Ho * Wo));
                 int i = (int)((q / Wo) % Ho), j = (int)(q % Wo);
                 orc_crop(&pl, image, H, W, b, i, j, act);
-                orc_patch_forward(&pl, params, act, idx, gp, pr);
+                orc_patch_forward(&pl, params, act, idx, gp, pr, NULL, b, i, j);
                 const double *y = act + pl.act_off[layer + 1];
                 for (int r = 0; r < m; ++r) {
                     if (!(r == m - 1 || i < st)) continue;

@@ -1,0 +1,284 @@
+// Direct (one thread per output element) kernels for every step of the whole-image
+// pass.  They accept any layer shape and serve the layers that are not shaped for
+// the matrix cores (first layer with 1-3 input channels, class layer with 2-3
+// outputs, odd channel counts); the MFMA kernels take the rest.
+//
+// Tensors are dense whole-image maps in channels-last order [B][rows][cols][C].
+// A layer that follows pooling by a cumulative factor d reads taps d elements
+// apart (Method, MPF layer: the k*k pooling offsets become the residues mod d).
+// Weights are stored [tap = u*k+v][c][o] followed by the bias row [o].
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mpcnn {
+
+// a0: planar [B][C][H][W] -> channels-last [B][H][W][C]
+__global__ void stage_input_kernel(const float* __restrict__ src, float* __restrict__ dst, int B,
+                                   int C, int H, int W)
+{
+    long total = (long)B * C * H * W;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long)gridDim.x * blockDim.x) {
+        int c = (int)(e % C);
+        long p = e / C;
+        int x = (int)(p % W);
+        long q = p / W;
+        int y = (int)(q % H);
+        int b = (int)(q / H);
+        dst[e] = src[(((long)b * C + c) * H + y) * W + x];
+    }
+}
+
+// a1: Y[b,y,x,o] = act(bias[o] + sum_{u,v,c} W[u,v,c,o] * A[b, y+u*d, x+v*d, c])
+// (Background, "Convolutional Layer"; applied to the whole image, Alg. 1.)
+template <bool TANH>
+__global__ void conv_fwd_direct_kernel(const float* __restrict__ A, const float* __restrict__ Wk,
+                                       float* __restrict__ Y, int B, int Hi, int Wi, int Ci, int Ho,
+                                       int Wo, int Co, int k, int d)
+{
+    long total = (long)B * Ho * Wo * Co;
+    const float* bias = Wk + (long)k * k * Ci * Co;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long)gridDim.x * blockDim.x) {
+        int o = (int)(e % Co);
+        long p = e / Co;
+        int x = (int)(p % Wo);
+        long q = p / Wo;
+        int y = (int)(q % Ho);
+        int b = (int)(q / Ho);
+        float acc = bias[o];
+        for (int u = 0; u < k; ++u)
+            for (int v = 0; v < k; ++v) {
+                const float* a = A + (((long)b * Hi + (y + u * d)) * Wi + (x + v * d)) * Ci;
+                const float* w = Wk + (long)(u * k + v) * Ci * Co + o;
+                for (int c = 0; c < Ci; ++c) acc = fmaf(a[c], w[(long)c * Co], acc);
+            }
+        Y[e] = TANH ? tanhf(acc) : acc;
+    }
+}
+
+// a6: dA[b,y,x,c] = sum_{u,v,o} W[u,v,c,o] * dY[b, y-u*d, x-v*d, o]  (terms outside dY dropped),
+// times (1 - A^2) when A is the tanh output of the layer below.
+template <bool TANHP>
+__global__ void conv_dgrad_direct_kernel(const float* __restrict__ dY, const float* __restrict__ Wk,
+                                         const float* __restrict__ A, float* __restrict__ dA, int B,
+                                         int Hi, int Wi, int Ci, int Ho, int Wo, int Co, int k, int d)
+{
+    long total = (long)B * Hi * Wi * Ci;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long)gridDim.x * blockDim.x) {
+        int c = (int)(e % Ci);
+        long p = e / Ci;
+        int x = (int)(p % Wi);
+        long q = p / Wi;
+        int y = (int)(q % Hi);
+        int b = (int)(q / Hi);
+        float acc = 0.f;
+        for (int u = 0; u < k; ++u) {
+            int yy = y - u * d;
+            if (yy < 0 || yy >= Ho) continue;
+            for (int v = 0; v < k; ++v) {
+                int xx = x - v * d;
+                if (xx < 0 || xx >= Wo) continue;
+                const float* g = dY + (((long)b * Ho + yy) * Wo + xx) * Co;
+                const float* w = Wk + ((long)(u * k + v) * Ci + c) * Co;
+                for (int o = 0; o < Co; ++o) acc = fmaf(g[o], w[o], acc);
+            }
+        }
+        if (TANHP) {
+            float a = A[e];
+            acc *= 1.f - a * a;
+        }
+        dA[e] = acc;
+    }
+}
+
+// a5: partial[chunk][(tap*Ci + c)*Co + o] = sum over the chunk's rows of
+//     dY[b,y,x,o] * A[b, y+u*d, x+v*d, c];  row kk = k*k*Ci is the bias row (A = 1).
+// One chunk = `rows_per_chunk` output rows (b,y); a later pass adds the chunks
+// in index order (Alg. 2: the gradient is the sum over all fragments).
+__global__ void conv_wgrad_direct_kernel(const float* __restrict__ A, const float* __restrict__ dY,
+                                         float* __restrict__ partial, int B, int Hi, int Wi, int Ci,
+                                         int Ho, int Wo, int Co, int k, int d, int rows_per_chunk)
+{
+    const long KN = ((long)k * k * Ci + 1) * Co;
+    long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= KN) return;
+    int o = (int)(e % Co);
+    int kk = (int)(e / Co);
+    const bool is_bias = kk == k * k * Ci;
+    int c = kk % Ci, tap = kk / Ci;
+    int u = tap / k, v = tap % k;
+    long row0 = (long)blockIdx.y * rows_per_chunk;
+    long row1 = row0 + rows_per_chunk;
+    if (row1 > (long)B * Ho) row1 = (long)B * Ho;
+    float acc = 0.f;
+    for (long r = row0; r < row1; ++r) {
+        int b = (int)(r / Ho), y = (int)(r % Ho);
+        const float* g = dY + (r * Wo) * Co + o;
+        if (is_bias) {
+            for (int x = 0; x < Wo; ++x) acc += g[(long)x * Co];
+        } else {
+            const float* a = A + (((long)b * Hi + (y + u * d)) * Wi + v * d) * Ci + c;
+            for (int x = 0; x < Wo; ++x) acc = fmaf(g[(long)x * Co], a[(long)x * Ci], acc);
+        }
+    }
+    partial[(long)blockIdx.y * KN + e] = acc;
+}
+
+// Second stage of every split reduction: out[e] = sum_{i<n} partial[i][e], i ascending.
+__global__ void reduce_partials_kernel(const float* __restrict__ partial, float* __restrict__ out,
+                                       long len, int n)
+{
+    long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= len) return;
+    double s = 0.0;
+    for (int i = 0; i < n; ++i) s += (double)partial[(long)i * len + e];
+    out[e] = (float)s;
+}
+
+// a2: stride-1 max filter with taps d apart, plus the argmax tap code of the FIRST
+// maximum in row-major (u,v) order (Alg. 3: MP_fwd on every offset, mpIDXS).
+__global__ void maxfilter_fwd_direct_kernel(const float* __restrict__ A, float* __restrict__ O,
+                                            uint8_t* __restrict__ code, int B, int Hi, int Wi, int C,
+                                            int Ho, int Wo, int p, int d)
+{
+    long total = (long)B * Ho * Wo * C;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long)gridDim.x * blockDim.x) {
+        int c = (int)(e % C);
+        long q = e / C;
+        int x = (int)(q % Wo);
+        long r = q / Wo;
+        int y = (int)(r % Ho);
+        int b = (int)(r / Ho);
+        float best = 0.f;
+        int bi = -1;
+        for (int u = 0; u < p; ++u)
+            for (int v = 0; v < p; ++v) {
+                float a = A[(((long)b * Hi + (y + u * d)) * Wi + (x + v * d)) * C + c];
+                if (bi < 0 || a > best) {
+                    best = a;
+                    bi = u * p + v;
+                }
+            }
+        O[e] = best;
+        if (code) code[e] = (uint8_t)bi;
+    }
+}
+
+// a7: routing by argmax as a gather (Alg. 4): an input element collects dO of every
+// window that chose it, in fixed (u,v) order; times (1 - A^2) when A is a tanh output.
+template <bool TANHP>
+__global__ void maxfilter_bwd_direct_kernel(const float* __restrict__ dO,
+                                            const uint8_t* __restrict__ code,
+                                            const float* __restrict__ A, float* __restrict__ dA,
+                                            int B, int Hi, int Wi, int C, int Ho, int Wo, int p, int d)
+{
+    long total = (long)B * Hi * Wi * C;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long)gridDim.x * blockDim.x) {
+        int c = (int)(e % C);
+        long q = e / C;
+        int x = (int)(q % Wi);
+        long r = q / Wi;
+        int y = (int)(r % Hi);
+        int b = (int)(r / Hi);
+        float acc = 0.f;
+        for (int u = 0; u < p; ++u) {
+            int yy = y - u * d;
+            if (yy < 0 || yy >= Ho) continue;
+            for (int v = 0; v < p; ++v) {
+                int xx = x - v * d;
+                if (xx < 0 || xx >= Wo) continue;
+                long s = (((long)b * Ho + yy) * Wo + xx) * C + c;
+                if (code[s] == (uint8_t)(u * p + v)) acc += dO[s];
+            }
+        }
+        if (TANHP) {
+            float a = A[e];
+            acc *= 1.f - a * a;
+        }
+        dA[e] = acc;
+    }
+}
+
+constexpr int kMaxClasses = 16;
+
+// a3 (second half): softmax over the class logits of every pixel, probabilities out in
+// planar [B][n_cls][Ho][Wo]; with labels: delta = w (p - onehot) and the block's share of
+// the summed cross-entropy (Results: MCCE per pixel; Method: first step of back-prop).
+__global__ void softmax_ce_kernel(const float* __restrict__ Z, float* __restrict__ probs,
+                                  const int32_t* __restrict__ labels, const float* __restrict__ pixw,
+                                  float* __restrict__ dZ, double* __restrict__ loss_partial, int B,
+                                  int Ho, int Wo, int H, int W, int ctr, int n_cls)
+{
+    __shared__ double red[256];
+    long total = (long)B * Ho * Wo;
+    double my_loss = 0.0;
+    for (long m = (long)blockIdx.x * blockDim.x + threadIdx.x; m < total;
+         m += (long)gridDim.x * blockDim.x) {
+        int j = (int)(m % Wo);
+        long q = m / Wo;
+        int i = (int)(q % Ho);
+        int b = (int)(q / Ho);
+        float z[kMaxClasses];
+        float zmax = -INFINITY;
+        for (int o = 0; o < n_cls; ++o) {
+            z[o] = Z[m * n_cls + o];
+            zmax = fmaxf(zmax, z[o]);
+        }
+        float sum = 0.f;
+        float zt = 0.f;  // logit of the labelled class, relative to the maximum
+        for (int o = 0; o < n_cls; ++o) {
+            z[o] -= zmax;
+            sum += expf(z[o]);
+        }
+        float inv = 1.f / sum;
+        int t = -1;
+        float w = 0.f;
+        if (labels) {
+            long lp = ((long)b * H + (i + ctr)) * W + (j + ctr);
+            t = labels[lp];
+            if (t < 0 || t >= n_cls) t = -1;
+            else w = pixw ? pixw[lp] : 1.f;
+        }
+        for (int o = 0; o < n_cls; ++o) {
+            float p = expf(z[o]) * inv;
+            if (probs) probs[(((long)b * n_cls + o) * Ho + i) * Wo + j] = p;
+            if (dZ) dZ[m * n_cls + o] = (t >= 0) ? w * (p - (o == t ? 1.f : 0.f)) : 0.f;
+            if (o == t) zt = z[o];
+        }
+        if (t >= 0) my_loss += (double)w * ((double)logf(sum) - (double)zt);  // -log p[t]
+    }
+    if (loss_partial) {
+        red[threadIdx.x] = my_loss;
+        __syncthreads();
+        for (int s = blockDim.x / 2; s > 0; s >>= 1) {
+            if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) loss_partial[blockIdx.x] = red[0];
+    }
+}
+
+__global__ void loss_reduce_kernel(const double* __restrict__ partial, int n,
+                                   double* __restrict__ loss)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        double s = 0.0;
+        for (int i = 0; i < n; ++i) s += partial[i];
+        *loss = s;
+    }
+}
+
+// a8: theta -= step * g
+__global__ void sgd_kernel(float* __restrict__ theta, const float* __restrict__ g, float step,
+                           long n)
+{
+    long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < n) theta[e] = fmaf(-step, g[e], theta[e]);
+}
+
+}  // namespace mpcnn

@@ -1,0 +1,211 @@
+"""Thin ctypes binding over libmpcnn.so (the C ABI declared in include/mpcnn.h).
+
+Argument marshalling only: every step of the whole-image forward / backward
+runs in the library's HIP kernels.  PyTorch supplies device memory (tensors'
+`data_ptr()`) and the stream.  There is no fallback: if the library has not
+been built, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmpcnn.so")
+
+KIND_C, KIND_MP, KIND_FC = 0, 1, 2
+F32, BF16 = 0, 1
+
+STATUS = {0: "MPCNN_OK", 1: "MPCNN_EINVAL", 2: "MPCNN_ESHAPE", 3: "MPCNN_EWORKSPACE",
+          4: "MPCNN_EUNSUPPORTED", 5: "MPCNN_EHIP", 6: "MPCNN_ENOMEM"}
+
+# every symbol include/mpcnn.h declares
+SYMBOLS = [
+    "mpcnn_net_create", "mpcnn_net_destroy", "mpcnn_net_patch", "mpcnn_net_classes",
+    "mpcnn_param_count", "mpcnn_layer_shape", "mpcnn_set_params", "mpcnn_get_params",
+    "mpcnn_get_grads", "mpcnn_workspace_bytes", "mpcnn_seg_forward", "mpcnn_seg_backward",
+    "mpcnn_sgd_step", "mpcnn_get_activation", "mpcnn_get_argmax", "mpcnn_last_error",
+]
+
+
+class MpcnnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("%s: %s" % (STATUS.get(status, status), message))
+        self.status = status
+
+
+class _LayerDesc(C.Structure):
+    _fields_ = [("kind", C.c_int), ("maps", C.c_int), ("k", C.c_int)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libmpcnn.so (built by `python -m paper_1302_1690_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libmpcnn.so is not built: run `python -m paper_1302_1690_amd.build` "
+                              "(there is no fallback path)")
+        # torch ships its own copy of the HIP runtime (same soname as the system one):
+        # it must be loaded first so that the library binds to it and both share one
+        # runtime, hence one set of device allocations and streams.
+        import torch  # noqa: F401
+        L = C.CDLL(LIB_PATH)
+        vp, sz, i = C.c_void_p, C.c_size_t, C.c_int
+        L.mpcnn_net_create.argtypes = [C.POINTER(_LayerDesc), i, i, i, i, C.POINTER(vp)]
+        L.mpcnn_net_destroy.argtypes = [vp]
+        L.mpcnn_net_destroy.restype = None
+        L.mpcnn_net_patch.argtypes = [vp]
+        L.mpcnn_net_classes.argtypes = [vp]
+        L.mpcnn_param_count.argtypes = [vp]
+        L.mpcnn_param_count.restype = sz
+        L.mpcnn_layer_shape.argtypes = [vp, i, i, i] + [C.POINTER(i)] * 4
+        L.mpcnn_set_params.argtypes = [vp, vp, sz]
+        L.mpcnn_get_params.argtypes = [vp, vp, sz]
+        L.mpcnn_get_grads.argtypes = [vp, vp, sz]
+        L.mpcnn_workspace_bytes.argtypes = [vp, i, i, i, i]
+        L.mpcnn_workspace_bytes.restype = sz
+        L.mpcnn_seg_forward.argtypes = [vp, vp, i, i, i, vp, vp, sz, vp]
+        L.mpcnn_seg_backward.argtypes = [vp, vp, vp, vp, i, i, i, vp, vp, vp, sz, vp]
+        L.mpcnn_sgd_step.argtypes = [vp, C.c_float, C.c_float, vp]
+        L.mpcnn_get_activation.argtypes = [vp, i, vp, sz]
+        L.mpcnn_get_argmax.argtypes = [vp, i, vp, sz]
+        L.mpcnn_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(st: int):
+    if st != 0:
+        raise MpcnnError(st, lib().mpcnn_last_error().decode())
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+class Net:
+    """mpcnn_net handle.  `layers`: (kind, maps, k) triples; see include/mpcnn.h."""
+
+    def __init__(self, layers: Sequence[Tuple[int, int, int]], in_channels: int, patch: int,
+                 dtype: int = F32):
+        arr = (_LayerDesc * len(layers))(*[_LayerDesc(int(a), int(b), int(c)) for a, b, c in layers])
+        h = C.c_void_p()
+        _check(lib().mpcnn_net_create(arr, len(layers), in_channels, patch, dtype, C.byref(h)))
+        self._h = h
+        self.layers = [tuple(int(v) for v in l) for l in layers]
+        self.in_channels = in_channels
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().mpcnn_net_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    # ---- host-only queries
+    @property
+    def patch(self) -> int:
+        return lib().mpcnn_net_patch(self._h)
+
+    @property
+    def n_classes(self) -> int:
+        return lib().mpcnn_net_classes(self._h)
+
+    @property
+    def param_count(self) -> int:
+        return lib().mpcnn_param_count(self._h)
+
+    def layer_shape(self, H: int, W: int, layer: int):
+        r, c, ch, sp = C.c_int(), C.c_int(), C.c_int(), C.c_int()
+        _check(lib().mpcnn_layer_shape(self._h, H, W, layer, C.byref(r), C.byref(c), C.byref(ch),
+                                       C.byref(sp)))
+        return r.value, c.value, ch.value, sp.value
+
+    def workspace_bytes(self, B: int, H: int, W: int, training: bool) -> int:
+        return lib().mpcnn_workspace_bytes(self._h, B, H, W, 1 if training else 0)
+
+    # ---- parameters
+    def set_params(self, params: np.ndarray):
+        p = np.ascontiguousarray(params, dtype=np.float32)
+        _check(lib().mpcnn_set_params(self._h, p.ctypes.data, p.size))
+
+    def get_params(self) -> np.ndarray:
+        out = np.empty(self.param_count, dtype=np.float32)
+        _check(lib().mpcnn_get_params(self._h, out.ctypes.data, out.size))
+        return out
+
+    def get_grads(self) -> np.ndarray:
+        out = np.empty(self.param_count, dtype=np.float32)
+        _check(lib().mpcnn_get_grads(self._h, out.ctypes.data, out.size))
+        return out
+
+    # ---- device calls (torch tensors carry the memory)
+    def alloc_workspace(self, B: int, H: int, W: int, training: bool):
+        import torch
+        need = self.workspace_bytes(B, H, W, training)
+        if need == 0:
+            raise MpcnnError(2, "image %dx%d does not fit the net" % (H, W))
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        return self._ws
+
+    def seg_forward(self, image, probs=None, ws=None, stream=None):
+        """image [B,C0,H,W] fp32 cuda tensor -> probs [B,n_cls,H-P+1,W-P+1]."""
+        import torch
+        B, _, H, W = image.shape
+        assert image.is_cuda and image.dtype == torch.float32 and image.is_contiguous()
+        if ws is None:
+            ws = self.alloc_workspace(B, H, W, False)
+        if probs is None:
+            probs = torch.empty((B, self.n_classes, H - self.patch + 1, W - self.patch + 1),
+                                dtype=torch.float32, device=image.device)
+        _check(lib().mpcnn_seg_forward(self._h, _ptr(image), B, H, W, _ptr(probs), _ptr(ws),
+                                       ws.numel(), _stream_handle(stream)))
+        return probs
+
+    def seg_backward(self, image, labels, pixw=None, probs=None, loss=None, ws=None, stream=None):
+        """Forward + backward; gradients stay in the net.  Returns (probs, loss) as given."""
+        import torch
+        B, _, H, W = image.shape
+        assert image.is_cuda and image.dtype == torch.float32 and image.is_contiguous()
+        assert labels.dtype == torch.int32 and labels.is_contiguous() and tuple(labels.shape) == (B, H, W)
+        if pixw is not None:
+            assert pixw.dtype == torch.float32 and pixw.is_contiguous() and tuple(pixw.shape) == (B, H, W)
+        if loss is not None:
+            assert loss.dtype == torch.float64 and loss.numel() == 1
+        if ws is None:
+            ws = self.alloc_workspace(B, H, W, True)
+        _check(lib().mpcnn_seg_backward(self._h, _ptr(image), _ptr(labels), _ptr(pixw), B, H, W,
+                                        _ptr(probs), _ptr(loss), _ptr(ws), ws.numel(),
+                                        _stream_handle(stream)))
+        return probs, loss
+
+    def sgd_step(self, lr: float, grad_scale: float = 1.0, stream=None):
+        _check(lib().mpcnn_sgd_step(self._h, lr, grad_scale, _stream_handle(stream)))
+
+    # ---- test hooks
+    def get_activation(self, B: int, H: int, W: int, layer: int) -> np.ndarray:
+        r, c, ch, _ = self.layer_shape(H, W, layer)
+        out = np.empty((B, r, c, ch), dtype=np.float32)
+        _check(lib().mpcnn_get_activation(self._h, layer, out.ctypes.data, out.size))
+        return out
+
+    def get_argmax(self, B: int, H: int, W: int, layer: int) -> np.ndarray:
+        r, c, ch, _ = self.layer_shape(H, W, layer)
+        out = np.empty((B, r, c, ch), dtype=np.uint8)
+        _check(lib().mpcnn_get_argmax(self._h, layer, out.ctypes.data, out.size))
+        return out

@@ -88,7 +88,7 @@ CONFIGS: List[Workload] = [
 ]
 
 
-def param_count(layers, patch: int, in_channels: int) -> int:
+def param_count(layers, in_channels: int, patch: int) -> int:
     """Number of parameters (all W then b, layer by layer) - bookkeeping only."""
     side, ch, total, seen_fc = patch, in_channels, 0, False
     for kind, maps, k in layers:
@@ -106,7 +106,7 @@ def param_count(layers, patch: int, in_channels: int) -> int:
 
 def make_params(wl: Workload, dtype=np.float32) -> np.ndarray:
     """Flat parameter vector, per layer W[o][c][u][v] then b[o], all ~ U[-a, a]."""
-    n = param_count(wl.layers, wl.patch, wl.in_channels)
+    n = param_count(wl.layers, wl.in_channels, wl.patch)
     rng = np.random.default_rng(wl.seed_param)
     return rng.uniform(-wl.weight_amp, wl.weight_amp, size=n).astype(dtype)
 

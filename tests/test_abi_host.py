@@ -1,0 +1,84 @@
+"""Host-side checks of libmpcnn that need no GPU: the library loads, exports every
+symbol include/mpcnn.h declares, and its layer plan (shapes, parameter counts,
+errors) agrees with the paper's definitions and with the oracle's bookkeeping."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1302_1690_amd import mpcnn, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+C, MP, FC = 0, 1, 2
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "mpcnn.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(mpcnn_[a-z_]+)\s*\(", hdr))
+    assert declared == set(mpcnn.SYMBOLS), declared ^ set(mpcnn.SYMBOLS)
+    lib = ctypes.CDLL(mpcnn.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("cfg", wl.CONFIGS[:4], ids=lambda c: c.name)
+def test_plan_matches_configs(cfg):
+    net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch)
+    assert net.patch == cfg.patch
+    assert net.n_classes == cfg.n_classes
+    assert net.param_count == wl.param_count(cfg.layers, cfg.in_channels, cfg.patch)
+    assert net.param_count == oracle.param_count(cfg.layers, cfg.in_channels, cfg.patch)
+    last = len(cfg.layers) - 1
+    r, c, ch, sp = net.layer_shape(cfg.height, cfg.width, last)
+    assert (r, c, ch) == (cfg.out_h, cfg.out_w, cfg.n_classes)
+    assert net.workspace_bytes(cfg.batch, cfg.height, cfg.width, True) > \
+        net.workspace_bytes(cfg.batch, cfg.height, cfg.width, False) > 0
+    net.close()
+
+
+def test_dense_shapes_follow_fragment_rule():
+    """Each MPF layer multiplies the spacing by k (k^2 fragments, Method, MPF layer);
+    the dense map of a layer is what the oracle gets by laying all patches out."""
+    cfg = wl.CONFIGS[0]
+    net = mpcnn.Net(cfg.layers, 1, cfg.patch)
+    img = np.zeros((1, 1, 40, 36))
+    params = np.zeros(net.param_count)
+    for layer in range(len(cfg.layers)):
+        d = oracle.dense_layer(cfg.layers, 1, cfg.patch, params, img, layer)
+        r, c, ch, sp = net.layer_shape(40, 36, layer)
+        assert d["act"].shape == (1, ch, r, c)
+        assert d["stride"] == sp
+    spacings = [net.layer_shape(40, 36, l)[3] for l in range(len(cfg.layers))]
+    assert spacings == [1, 2, 2, 4, 4, 4]
+
+
+def test_errors():
+    with pytest.raises(mpcnn.MpcnnError) as e:
+        mpcnn.Net(((C, 2, 3), (MP, 0, 2)), 1, 8)
+    assert e.value.status == 2                       # must end with FC
+    with pytest.raises(mpcnn.MpcnnError) as e:
+        mpcnn.Net(((C, 2, 9), (FC, 2, 0)), 1, 8)
+    assert e.value.status == 2                       # filter larger than the map
+    with pytest.raises(mpcnn.MpcnnError) as e:
+        mpcnn.Net(((C, 2, 2), (MP, 0, 2), (FC, 2, 0)), 1, 8)
+    assert e.value.status == 4                       # 7 is not a multiple of 2
+    with pytest.raises(mpcnn.MpcnnError) as e:
+        mpcnn.Net(((FC, 4, 0), (C, 2, 1), (FC, 2, 0)), 1, 8)
+    assert e.value.status == 2
+    with pytest.raises(mpcnn.MpcnnError) as e:
+        mpcnn.Net(((FC, 2, 0),), 1, 8, dtype=7)
+    assert e.value.status == 1
+    with pytest.raises(mpcnn.MpcnnError) as e:
+        mpcnn.Net(((FC, 2, 0),), 0, 8)
+    assert e.value.status == 1
+    net = mpcnn.Net(wl.CONFIGS[0].layers, 1, 18)
+    assert net.workspace_bytes(1, 17, 64, True) == 0  # image smaller than the patch
+    with pytest.raises(mpcnn.MpcnnError):
+        net.layer_shape(64, 64, 99)
+    with pytest.raises(mpcnn.MpcnnError):
+        net.get_params()                              # never set
+    assert "never set" in mpcnn.lib().mpcnn_last_error().decode()

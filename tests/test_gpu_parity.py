@@ -1,0 +1,319 @@
+"""GPU parity: the HIP whole-image path (through the C ABI) against the fp64
+patch-by-patch oracle, element by element, on the same seeded inputs.
+
+Bars: argmax tap codes bit-exact (see `check_argmax`), probabilities within 1e-4
+absolute, gradients within 1e-4 of the tensor's largest entry and in L2 norm,
+per parameter tensor; loss within 1e-5 relative.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1302_1690_amd import mpcnn, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+C, MP, FC = 0, 1, 2
+TOL = 1e-4
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def param_tensors(layers, in_ch, patch):
+    """(name, slice) of every W and b in the flat parameter vector."""
+    out, side, ch, off, seen_fc = [], patch, in_ch, 0, False
+    for li, (kind, maps, k) in enumerate(layers):
+        if kind == MP:
+            side //= k
+            continue
+        kk = k if kind == C else (1 if seen_fc else side)
+        nw = maps * ch * kk * kk
+        out.append(("W%d" % li, slice(off, off + nw)))
+        out.append(("b%d" % li, slice(off + nw, off + nw + maps)))
+        off += nw + maps
+        side, ch = side - kk + 1, maps
+        seen_fc = seen_fc or kind == FC
+    return out
+
+
+def check_grads(cfg, g_gpu, g_ref, tol=TOL):
+    worst, report = 0.0, []
+    for name, sl in param_tensors(cfg.layers, cfg.in_channels, cfg.patch):
+        a, r = g_gpu[sl].astype(np.float64), g_ref[sl]
+        scale = np.abs(r).max()
+        e_max = np.abs(a - r).max() / max(scale, 1e-30)
+        e_l2 = np.linalg.norm(a - r) / max(np.linalg.norm(r), 1e-30)
+        worst = max(worst, e_max, e_l2)
+        report.append("%s max %.2e l2 %.2e" % (name, e_max, e_l2))
+    assert worst <= tol, (cfg.name, report)
+    return worst
+
+
+def run_gpu(cfg, img, lab, params, pixw=None, net=None):
+    own = net is None
+    if own:
+        net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch)
+        net.set_params(params)
+    B, _, H, W = img.shape
+    d_img = torch.from_numpy(img).cuda()
+    d_lab = torch.from_numpy(lab).cuda()
+    d_pw = None if pixw is None else torch.from_numpy(pixw.astype(np.float32)).cuda()
+    probs = torch.full((B, cfg.n_classes, H - cfg.patch + 1, W - cfg.patch + 1), -1.0,
+                       dtype=torch.float32, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    net.seg_backward(d_img, d_lab, d_pw, probs, loss)
+    torch.cuda.synchronize()
+    return net, probs.cpu().numpy(), float(loss.item()), net.get_grads()
+
+
+def first_max_codes(a, p, d):
+    """CPU scan of [B,r,c,ch] values: tap code of the first maximum, row-major taps."""
+    B, r, c, ch = a.shape
+    ro, co = r - (p - 1) * d, c - (p - 1) * d
+    taps = np.stack([a[:, u * d:u * d + ro, v * d:v * d + co, :] for u in range(p) for v in range(p)])
+    return np.argmax(taps, axis=0).astype(np.uint8), taps.max(axis=0)
+
+
+TIE_TAU = 1e-5   # activations lie in [-1, 1]: about 100 fp32 ulps
+
+
+def oracle_run_valid_ties(cfg, params, img, lab, pixw, sel, net):
+    """Oracle result to compare with.  Where the oracle's own two best candidates of a
+    pooling window are within TIE_TAU, either may legitimately win in fp32; the GPU's
+    choice among those two (and only those) is adopted and the oracle re-evaluated."""
+    kw = dict(labels=lab, pixw=None if pixw is None else pixw.astype(np.float64), sel=sel,
+              want_grads=True, tie_tau=TIE_TAU)
+    args = (cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64), img.astype(np.float64))
+    ref = oracle.run(*args, **kw)
+    near = ref["near_ties"]
+    B, _, H, W = img.shape
+    alt = []
+    for layer in np.unique(near[:, 3]) if len(near) else []:
+        rows = near[near[:, 3] == layer]
+        _, ch, ny, nx, _ = oracle.dense_shape(cfg.layers, cfg.in_channels, cfg.patch, B, H, W, int(layer))
+        key = rows[:, 0]
+        x, t = key % nx, key // nx
+        y, t = t % ny, t // ny
+        c, t = t % ch, t // ch
+        b = t % B
+        assert (t // B == layer).all()
+        got = net.get_argmax(B, H, W, int(layer))[b, y, x, c]
+        assert ((got == rows[:, 1]) | (got == rows[:, 2])).all(), "GPU chose neither near-tie candidate"
+        alt += key[got == rows[:, 2]].tolist()
+    if alt:
+        ref = oracle.run(*args, alt=alt, **kw)
+    return ref, len(near), len(alt)
+
+
+def check_argmax(cfg, net, img, params, with_oracle=True):
+    """(i) The stored tap codes equal a CPU scan, lowest tap first, over the GPU's own
+    pre-pool values, bit for bit.  (ii) They equal the fp64 oracle's codes wherever
+    the oracle's top-2 gap exceeds TIE_TAU (rounding can flip closer calls)."""
+    B, _, H, W = img.shape
+    excused = 0
+    dil = 1
+    for li, (kind, maps, k) in enumerate(cfg.layers):
+        if kind != MP:
+            continue
+        pre = (np.ascontiguousarray(img.transpose(0, 2, 3, 1)) if li == 0
+               else net.get_activation(B, H, W, li - 1))
+        codes = net.get_argmax(B, H, W, li)
+        post = net.get_activation(B, H, W, li)
+        ref_codes, ref_max = first_max_codes(pre, k, dil)
+        assert codes.shape == ref_codes.shape
+        assert np.array_equal(codes, ref_codes), (cfg.name, li, "codes differ from the scan of the GPU's own values")
+        assert np.array_equal(post, ref_max), (cfg.name, li, "pooled values")
+        if with_oracle:
+            d = oracle.dense_layer(cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64),
+                                   img.astype(np.float64), li)
+            o_codes = d["codes"].transpose(0, 2, 3, 1)
+            o_gap = d["gap"].transpose(0, 2, 3, 1)
+            cov = d["covered"][..., None]
+            bad = (codes != o_codes) & cov
+            assert not (bad & (o_gap > TIE_TAU)).any(), (cfg.name, li, int((bad & (o_gap > TIE_TAU)).sum()))
+            excused += int(bad.sum())
+        dil *= k
+    return excused
+
+
+def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_layers=True):
+    img, lab = wl.make_inputs(cfg)
+    params = wl.make_params(cfg)
+    pixw = None
+    if with_pixw:
+        pixw = np.random.default_rng(77).uniform(0.25, 2.0, lab.shape).astype(np.float32)
+    if ignore_some:
+        lab = lab.copy()
+        lab[np.random.default_rng(78).random(lab.shape) < 0.1] = -1
+    say("case %s B=%d %dx%d" % (cfg.name, cfg.batch, cfg.height, cfg.width))
+    net, probs, loss, grads = run_gpu(cfg, img, lab, params, pixw)
+    ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, pixw, None, net)
+    say("  near-tie windows %d, resolved the other way on the GPU %d" % (n_near, n_alt))
+    e_p = np.abs(probs - ref["probs"]).max()
+    assert e_p <= TOL, (cfg.name, "probs", e_p)
+    assert abs(loss - ref["loss"]) <= 1e-5 * abs(ref["loss"]), (loss, ref["loss"])
+    excused = check_argmax(cfg, net, img, params) if check_layers else -1
+    say("  argmax excused %d" % excused)
+    if check_layers:
+        B, _, H, W = img.shape
+        for li, (kind, maps, k) in enumerate(cfg.layers[:-1]):
+            if kind == MP:
+                continue
+            d = oracle.dense_layer(cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64),
+                                   img.astype(np.float64), li)
+            a = net.get_activation(B, H, W, li).transpose(0, 3, 1, 2)
+            cov = d["covered"][:, None]
+            err = np.abs(a - d["act"])[np.broadcast_to(cov, a.shape)].max()
+            assert err <= 2e-5, (cfg.name, "activation of layer", li, err)
+    e_g = check_grads(cfg, grads, ref["grads"])
+    say("  probs err %.2e  grads err %.2e  loss %.6f  argmax excused %d" % (e_p, e_g, loss, excused))
+    net.close()
+
+
+def test_cfg0_full():
+    full_parity(wl.CONFIGS[0])
+
+
+def test_cfg0_batch_ragged_weights_ignored_labels():
+    full_parity(wl.crop(wl.CONFIGS[0], 3, 37, 45), with_pixw=True, ignore_some=True)
+
+
+def test_cfg0_single_patch_image():
+    """Smallest legal input: the image is one patch."""
+    full_parity(wl.crop(wl.CONFIGS[0], 2, 18, 18), check_layers=False)
+
+
+def test_cfg1_net_crop_full_oracle():
+    full_parity(wl.crop(wl.CONFIGS[1], 1, 100, 93))
+
+
+def test_cfg3_net_crop_full_oracle():
+    full_parity(wl.crop(wl.CONFIGS[3], 1, 78 + 17, 78 + 12))
+
+
+def test_generic_net_rgb_three_classes_pool3():
+    """3 input channels, 3 classes, 3x3 pooling, C directly after C, two hidden FCs."""
+    from dataclasses import replace
+    # patch 26 -> 25 -> 24 -> (MP3) 8 -> 6 -> (MP2) 3 -> FC over 3x3
+    layers = ((C, 5, 2), (C, 6, 2), (MP, 0, 3), (C, 7, 3), (MP, 0, 2), (FC, 9, 0), (FC, 6, 0), (FC, 3, 0))
+    cfg = replace(wl.CONFIGS[4], name="generic_rgb", layers=layers, patch=26, batch=2, height=39,
+                  width=33, dtype="f32", weight_amp=0.3)
+    full_parity(cfg, with_pixw=True)
+
+
+def test_pool_first_and_fc_only_nets():
+    from dataclasses import replace
+    cfg = replace(wl.CONFIGS[0], name="pool_first", layers=((MP, 0, 2), (C, 3, 2), (FC, 2, 0)),
+                  patch=6, batch=1, height=19, width=23, weight_amp=0.5)     # 6 -> 3 -> 2 -> FC
+    full_parity(cfg)
+    cfg = replace(wl.CONFIGS[0], name="fc_only", layers=((FC, 2, 0),), patch=5, batch=2, height=9,
+                  width=8, weight_amp=0.5)
+    full_parity(cfg, check_layers=False)
+
+
+def test_exact_ties_constant_image():
+    """Constant image: every pooling window is an exact tie in fp32 and fp64 alike,
+    so every code must be tap 0 (first in row-major order)."""
+    cfg = wl.crop(wl.CONFIGS[0], 1, 30, 31)
+    img = np.full((1, 1, 30, 31), 0.5, dtype=np.float32)
+    lab = np.ones((1, 30, 31), dtype=np.int32)
+    params = wl.make_params(cfg)
+    net, probs, loss, grads = run_gpu(cfg, img, lab, params)
+    for li, (kind, _, _) in enumerate(cfg.layers):
+        if kind == MP:
+            assert (net.get_argmax(1, 30, 31, li) == 0).all()
+    ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, None, None, net)
+    assert n_near > 0 and n_alt == 0          # exact ties: both sides take the first tap
+    assert np.abs(probs - ref["probs"]).max() <= TOL
+    check_grads(cfg, grads, ref["grads"])
+    assert check_argmax(cfg, net, img, params) == 0
+    net.close()
+
+
+def sampled_parity(cfg, n_sel, seed):
+    """Full-size input; the oracle evaluates a seeded subset S of the output pixels.
+    Probabilities are compared at S; gradients by giving the GPU the indicator of S
+    as per-pixel loss weights, which makes its summed gradient the sum over S."""
+    img, lab = wl.make_inputs(cfg)
+    params = wl.make_params(cfg)
+    sel = wl.sample_pixels(cfg, n_sel, seed)
+    say("case %s sampled %d of %d pixels" % (cfg.name, sel.size, cfg.valid_pixels))
+    c = (cfg.patch - 1) // 2
+    b, rem = np.divmod(sel, cfg.out_h * cfg.out_w)
+    i, j = np.divmod(rem, cfg.out_w)
+    mask = np.zeros(lab.shape, dtype=np.float32)
+    mask[b, i + c, j + c] = 1.0
+    net, probs, loss, grads = run_gpu(cfg, img, lab, params, mask)
+    ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, None, sel, net)
+    say("  near-tie windows %d, resolved the other way on the GPU %d" % (n_near, n_alt))
+    e_p = np.abs(probs[b, :, i, j] - ref["probs"]).max()
+    assert e_p <= TOL, e_p
+    assert abs(loss - ref["loss"]) <= 1e-5 * abs(ref["loss"]), (loss, ref["loss"])
+    e_g = check_grads(cfg, grads, ref["grads"])
+    # properties that hold at any size
+    assert np.isfinite(probs).all() and np.abs(probs.sum(1) - 1).max() < 1e-5
+    excused = check_argmax(cfg, net, img, params, with_oracle=False)
+    say("  probs err %.2e  grads err %.2e  loss %.6f" % (e_p, e_g, loss))
+    return net, img, lab, params
+
+
+def test_cfg1_full_size_sampled():
+    net, img, lab, params = sampled_parity(wl.CONFIGS[1], 384, 11)
+    net.close()
+
+
+def test_cfg2_full_size_sampled_and_sgd():
+    cfg = wl.CONFIGS[2]
+    net, img, lab, params = sampled_parity(cfg, 256, 12)
+    # one SGD step on the mean loss of the sampled pixels: theta' = theta - lr * scale * g
+    g = net.get_grads()
+    net.sgd_step(cfg.lr, 1.0 / 256)
+    torch.cuda.synchronize()
+    expect = params.astype(np.float64) - (cfg.lr / 256) * g.astype(np.float64)
+    np.testing.assert_allclose(net.get_params(), expect, rtol=0, atol=1e-8)   # one fp32 ulp at 0.05 is 3.7e-9
+    assert np.abs(net.get_params() - params).max() > 0
+    net.close()
+
+
+def test_cfg3_full_size_sampled():
+    net, img, lab, params = sampled_parity(wl.CONFIGS[3], 48, 13)
+    net.close()
+
+
+def test_forward_only_matches_and_is_deterministic():
+    cfg = wl.crop(wl.CONFIGS[1], 2, 80, 75)
+    img, lab = wl.make_inputs(cfg)
+    params = wl.make_params(cfg)
+    net, probs, loss, grads = run_gpu(cfg, img, lab, params)
+    p2 = net.seg_forward(torch.from_numpy(img).cuda()).cpu().numpy()
+    assert np.array_equal(p2, probs)
+    _, probs3, loss3, grads3 = run_gpu(cfg, img, lab, params, net=net)
+    assert np.array_equal(probs3, probs) and loss3 == loss
+    assert np.array_equal(grads3, grads)      # fixed-order reductions: bitwise repeatable
+    net.close()
+
+
+def test_error_paths_on_device():
+    cfg = wl.CONFIGS[0]
+    net = mpcnn.Net(cfg.layers, 1, cfg.patch)
+    img = torch.zeros((1, 1, 32, 32), device="cuda")
+    lab = torch.zeros((1, 32, 32), dtype=torch.int32, device="cuda")
+    ws = torch.empty(net.workspace_bytes(1, 32, 32, True), dtype=torch.uint8, device="cuda")
+    with pytest.raises(mpcnn.MpcnnError) as e:
+        net.seg_backward(img, lab, ws=ws)
+    assert e.value.status == 1                      # parameters never set
+    net.set_params(wl.make_params(cfg))
+    with pytest.raises(mpcnn.MpcnnError) as e:
+        net.seg_backward(img, lab, ws=ws[:1024])
+    assert e.value.status == 3
+    small = torch.zeros((1, 1, 17, 32), device="cuda")
+    with pytest.raises(mpcnn.MpcnnError) as e:
+        net.seg_backward(small, lab[:, :17].contiguous(), ws=ws)
+    assert e.value.status == 2
+    net.seg_backward(img, lab, ws=ws)               # and a good call still works afterwards
+    torch.cuda.synchronize()
+    assert np.isfinite(net.get_grads()).all()
+    net.close()

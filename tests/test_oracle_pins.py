@@ -277,6 +277,31 @@ def test_shared_maximum_receives_sum_of_deltas():
     assert abs(r["loss"] - (-3 * np.log(p[0]) - np.log(p[1]))) < 1e-13
 
 
+def test_near_tie_report_and_alternative_routing():
+    """A window whose two largest values are within tau is reported with both taps;
+    listing it sends the back-propagated value to the runner-up instead, and
+    nothing else changes (both are valid sub-gradients of the max)."""
+    layers = ((MP, 0, 2), (FC, 2, 0))
+    x = np.array([[1.0, 1.0 - 1e-9, 0.2], [0.1, 0.3, 0.4]])[None, None]   # two 2x2 windows
+    params = np.array([0.7, -0.3, 0.1, 0.0])
+    lab = np.ones((1, 2, 3), dtype=np.int32)
+    r0 = oracle.run(layers, 1, 2, params, x, lab, want_grads=True, want_dimage=True, tie_tau=1e-6)
+    assert r0["near_ties"].tolist() == [[oracle.window_key(layers, 1, 2, 1, 2, 3, 0, 0, 0, 0, 0), 0, 1, 0]]
+    assert r0["dimage"][0, 0, 0, 0] != 0 and r0["dimage"][0, 0, 0, 1] != 0   # window 2 picks x[0][1]
+    plain = oracle.run(layers, 1, 2, params, x, lab, want_grads=True, want_dimage=True)
+    np.testing.assert_array_equal(plain["dimage"], r0["dimage"])              # reporting changes nothing
+    r1 = oracle.run(layers, 1, 2, params, x, lab, want_grads=True, want_dimage=True, tie_tau=1e-6,
+                    alt=r0["near_ties"][:, 0])
+    d0, d1 = r0["dimage"][0, 0], r1["dimage"][0, 0]
+    assert d1[0, 0] == 0.0 and abs(d1[0, 1] - (d0[0, 0] + d0[0, 1])) < 1e-15   # moved to the runner-up
+    np.testing.assert_array_equal(r1["probs"], r0["probs"])                   # forward value unchanged
+    np.testing.assert_array_equal(r1["grads"], r0["grads"])                   # FC sees the same maximum
+    # a window that is not a near-tie cannot be rerouted
+    r2 = oracle.run(layers, 1, 2, params, x, lab, want_dimage=True, tie_tau=1e-6,
+                    alt=[oracle.window_key(layers, 1, 2, 1, 2, 3, 0, 0, 0, 0, 1)])
+    np.testing.assert_array_equal(r2["dimage"], r0["dimage"])
+
+
 def test_softmax_cross_entropy_closed_forms():
     """Zero last layer -> p = 1/n, L = N log n, delta = 1/n - onehot; deltas sum
     to zero over classes; db_last = sum of deltas (Results: MCCE, per pixel)."""
