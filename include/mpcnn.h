@@ -154,6 +154,31 @@ mpcnn_status mpcnn_sgd_step(mpcnn_net* net, float lr, float grad_scale, void* hi
 mpcnn_status mpcnn_get_activation(const mpcnn_net* net, int layer, float* host, size_t n);
 mpcnn_status mpcnn_get_argmax(const mpcnn_net* net, int layer, uint8_t* host, size_t n);
 
+/*
+ * Per-kernel timing for the bench.  While enabled, every kernel launch of
+ * mpcnn_seg_forward / mpcnn_seg_backward / mpcnn_sgd_step is bracketed by HIP
+ * events recorded on the call's stream.  mpcnn_profile_read waits for them and
+ * returns one record per launch site (kernel x layer), summed since the last
+ * read: kernel name, layer index, step of the path (1 = conv fwd, 2 = max filter,
+ * 3 = class layer + softmax-CE, 4 = class layer backward, 5 = wgrad, 6 = dgrad,
+ * 7 = routing, 8 = SGD, 0 = staging / reductions), launches, total milliseconds,
+ * and the ALGORITHMIC work of one launch: flops = 2*M*N*K of the contraction
+ * with the real N and K, bytes = each tensor the step must read or write
+ * counted once.  Writes at most `cap` records, *n = number of sites.
+ */
+typedef struct {
+    char name[48];
+    int layer;
+    int step;
+    int launches;
+    double ms_total;
+    double flops;
+    double bytes;
+} mpcnn_kernel_stat;
+
+mpcnn_status mpcnn_profile_enable(mpcnn_net* net, int on);
+mpcnn_status mpcnn_profile_read(mpcnn_net* net, mpcnn_kernel_stat* out_host, int cap, int* n);
+
 const char* mpcnn_last_error(void);
 
 #ifdef __cplusplus

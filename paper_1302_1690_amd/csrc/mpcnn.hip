@@ -18,6 +18,7 @@
 
 #include "../../include/mpcnn.h"
 #include "kernels_direct.hpp"
+#include "kernels_mfma.hpp"
 
 namespace {
 
@@ -40,6 +41,29 @@ mpcnn_status fail(mpcnn_status st, const char* fmt, ...)
                         __FILE__, __LINE__);                                               \
     } while (0)
 
+constexpr int kLossBlocks = 256;
+constexpr int kDirectWgradChunks = 512;   // split of the position reduction, direct kernel
+constexpr size_t kConvLdsCap = 64 * 1024; // halo bytes per workgroup (two workgroups per CU)
+constexpr size_t kWgradLdsCap = 144 * 1024;
+constexpr int kNumCU = 256;
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Output-channel tiling of the MFMA kernels: OT tiles of 16 per workgroup, `split` groups.
+struct ChanTiling { int OT, split, pad; };
+ChanTiling chan_tiling(int channels)
+{
+    static const int allowed[] = {1, 2, 4, 7, 8};
+    const int tiles = ceil_div(channels, 16);
+    const int split = ceil_div(tiles, 8);
+    const int per = ceil_div(tiles, split);
+    int OT = 8;
+    for (int v : allowed) if (v >= per) { OT = v; break; }
+    return {OT, split, OT * split * 16};
+}
+int wgrad_np(int OT) { return OT <= 4 ? 16 : (OT == 7 ? 9 : 8); }
+
 struct Layer {
     int kind;     // mpcnn_kind
     int k;        // kernel side (C, FC) or pooling side (MP)
@@ -48,15 +72,32 @@ struct Layer {
     bool tanh_out;
     size_t p_off; // offset of this layer's [(k*k*cin + 1) x cout] block in the parameter buffer
     size_t p_len;
+    // matrix-core paths (decided once from the channel counts)
+    bool fwd_mfma = false, dgrad_mfma = false, wgrad_mfma = false;
+    ChanTiling fwd_ct{}, dgrad_ct{}, wgrad_ct{};
+    int fwd_rpad = 0, dgrad_rpad = 0;     // reduced channels padded to 16
+    size_t fwd_pack_off = 0, fwd_pack_len = 0, dgrad_pack_off = 0, dgrad_pack_len = 0;
 };
 
-// Per-call geometry: dense map sizes and workspace offsets.
+struct TilePlan { int PT = 0, Ty = 0, Tx = 0, nty = 0, ntx = 0; size_t lds = 0; bool ok = false; };
+struct WgradPlan {
+    bool ok = false;
+    int Ty = 0, Tx = 0, nty = 0, ntx = 0, tiles_total = 0, tiles_per_slab = 0, slabs = 0;
+    int pairs_total = 0, pairs_per_group = 0, groups = 0, NP = 0;
+    size_t lds = 0;
+    // direct kernel fallback
+    int rows_per_chunk = 0, chunks = 0;
+};
+
+// Per-call geometry: dense map sizes, launch plans and workspace offsets.
 struct Geom {
     int B = 0, H = 0, W = 0;
     bool training = false;
     std::vector<int> rows, cols;      // output map of layer l
     std::vector<size_t> act_off;      // byte offset of layer l's output in the workspace
     std::vector<size_t> code_off;     // MP layers: byte offset of the argmax map
+    std::vector<TilePlan> fwd, dgrad;
+    std::vector<WgradPlan> wgrad;
     size_t staged_off = 0;            // channels-last copy of the image (C0 > 1 only)
     size_t delta_off[2] = {0, 0};     // two delta buffers, each as large as the largest map
     size_t partial_off = 0, partial_bytes = 0;
@@ -64,26 +105,154 @@ struct Geom {
     size_t total = 0;
 };
 
-constexpr int kLossBlocks = 256;
-constexpr int kWgradChunkTarget = 512;  // split of the position reduction
-
-inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+struct ProfSite {
+    char name[48];
+    int layer, step, launches;
+    double ms, flops, bytes;
+};
+struct ProfPending { int site; hipEvent_t e0, e1; };
 
 }  // namespace
 
 struct mpcnn_net {
     std::vector<Layer> layers;
     int in_ch = 0, patch = 0, n_cls = 0;
-    size_t n_params = 0;
+    size_t n_params = 0, pack_len = 0;
     float* d_params = nullptr;
     float* d_grads = nullptr;
+    float* d_packs = nullptr;
+    bool packs_stale = true;
     int device = -1;
+    bool lds_attr_set = false;
     // what the last forward / backward left behind (for the test hooks)
     Geom last;
     void* last_ws = nullptr;
+    // profiling
+    bool prof_on = false;
+    std::vector<ProfSite> sites;
+    std::vector<ProfPending> pending;
+    std::vector<hipEvent_t> pool;
 };
 
 namespace {
+
+// ------------------------------------------------------------------ profiling
+struct ProfScope {
+    mpcnn_net* net;
+    hipStream_t st;
+    hipEvent_t e1 = nullptr;
+    ProfScope(mpcnn_net* n, hipStream_t s, const char* name, int layer, int step, double flops,
+              double bytes) : net(n), st(s)
+    {
+        if (!net->prof_on) return;
+        int site = -1;
+        for (size_t i = 0; i < net->sites.size(); ++i)
+            if (net->sites[i].layer == layer && strcmp(net->sites[i].name, name) == 0) { site = (int)i; break; }
+        if (site < 0) {
+            ProfSite ps{};
+            snprintf(ps.name, sizeof ps.name, "%s", name);
+            ps.layer = layer; ps.step = step;
+            net->sites.push_back(ps);
+            site = (int)net->sites.size() - 1;
+        }
+        net->sites[site].flops = flops;
+        net->sites[site].bytes = bytes;
+        hipEvent_t e0 = take(), e = take();
+        if (!e0 || !e) return;
+        (void)hipEventRecord(e0, st);
+        e1 = e;
+        net->pending.push_back({site, e0, e1});
+    }
+    ~ProfScope() { if (e1) (void)hipEventRecord(e1, st); }
+    hipEvent_t take()
+    {
+        if (!net->pool.empty()) { hipEvent_t e = net->pool.back(); net->pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+};
+#define LAUNCH(name, layer, step, flops, bytes, ...)                                  \
+    do {                                                                              \
+        ProfScope ps_(net, st, name, (int)(layer), step, (double)(flops), (double)(bytes)); \
+        __VA_ARGS__;                                                                  \
+    } while (0)
+
+// ------------------------------------------------------------------ planning
+// Ty x Tx tile (<= max_pos positions) of a residue class with extents fh x fw: fewest
+// tiles first, then the smallest halo; the halo must fit `lds_cap`.
+bool choose_tile(int fh, int fw, int max_pos, int k, size_t pitch_bytes, size_t extra_bytes,
+                 size_t lds_cap, int* Ty, int* Tx)
+{
+    long best_tiles = -1, best_halo = 0;
+    for (int ty = 1; ty <= std::min(fh, max_pos); ++ty) {
+        for (int tx = 1; tx <= std::min(fw, max_pos / ty); ++tx) {
+            long halo = (long)(ty + k - 1) * (tx + k - 1);
+            if ((size_t)halo * pitch_bytes + extra_bytes > lds_cap) continue;
+            long tiles = (long)ceil_div(fh, ty) * ceil_div(fw, tx);
+            if (best_tiles < 0 || tiles < best_tiles || (tiles == best_tiles && halo < best_halo)) {
+                best_tiles = tiles; best_halo = halo; *Ty = ty; *Tx = tx;
+            }
+        }
+    }
+    return best_tiles > 0;
+}
+
+// Tile plan of conv_mfma_kernel for a map of out_r x out_c positions at tap spacing d.
+TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, const ChanTiling& ct)
+{
+    TilePlan best;
+    double best_cost = 0;
+    const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
+    const size_t pitch = sizeof(float) * (rpad + 4);
+    for (int PT : {4, 8}) {
+        if (PT == 8 && ct.OT > 4) continue;
+        TilePlan p;
+        p.PT = PT;
+        if (!choose_tile(fh, fw, 16 * PT, k, pitch, 0, kConvLdsCap, &p.Ty, &p.Tx)) continue;
+        p.nty = ceil_div(fh, p.Ty); p.ntx = ceil_div(fw, p.Tx);
+        size_t halo = (size_t)(p.Ty + k - 1) * (p.Tx + k - 1) * pitch;
+        p.lds = std::max(halo, (size_t)4 * ct.OT * 1024);
+        p.ok = true;
+        // rounds of workgroups over the chip (two per CU) times the work of one workgroup
+        double wgs = (double)B * d * d * p.nty * p.ntx * ct.split;
+        double rounds = std::ceil(wgs / (2.0 * kNumCU));
+        double cost = rounds * (PT + 1.0);
+        if (!best.ok || cost < best_cost) { best = p; best_cost = cost; }
+    }
+    return best;
+}
+
+WgradPlan plan_wgrad(const Layer& ly, int B, int out_r, int out_c)
+{
+    WgradPlan w;
+    if (ly.wgrad_mfma) {
+        const int d = ly.dil, k = ly.k;
+        const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
+        const int cipad = ceil_div(ly.cin, 16) * 16;
+        const size_t pitch = sizeof(float) * (cipad + 1);
+        const size_t extra = sizeof(float) * (64 * (16 * ly.wgrad_ct.OT + 1) + 64);
+        if (choose_tile(fh, fw, 64, k, pitch, extra, kWgradLdsCap, &w.Ty, &w.Tx)) {
+            w.nty = ceil_div(fh, w.Ty); w.ntx = ceil_div(fw, w.Tx);
+            w.tiles_total = B * d * d * w.nty * w.ntx;
+            w.NP = wgrad_np(ly.wgrad_ct.OT);
+            w.pairs_total = k * k * (cipad / 16);
+            w.groups = ceil_div(w.pairs_total, 4 * w.NP);
+            w.pairs_per_group = ceil_div(ceil_div(w.pairs_total, w.groups), 4) * 4;
+            w.groups = ceil_div(w.pairs_total, w.pairs_per_group);
+            int target = std::max(1, kNumCU / (w.groups * ly.wgrad_ct.split));
+            w.tiles_per_slab = ceil_div(w.tiles_total, target);
+            w.slabs = ceil_div(w.tiles_total, w.tiles_per_slab);
+            w.lds = (size_t)(w.Ty + k - 1) * (w.Tx + k - 1) * pitch + extra;
+            w.ok = true;
+            return w;
+        }
+    }
+    long rows_total = (long)B * out_r;
+    w.rows_per_chunk = (int)std::max<long>(1, (rows_total + kDirectWgradChunks - 1) / kDirectWgradChunks);
+    w.chunks = (int)((rows_total + w.rows_per_chunk - 1) / w.rows_per_chunk);
+    return w;
+}
 
 bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g)
 {
@@ -92,6 +261,7 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
     g->B = B; g->H = H; g->W = W; g->training = training;
     g->rows.assign(L, 0); g->cols.assign(L, 0);
     g->act_off.assign(L, 0); g->code_off.assign(L, 0);
+    g->fwd.assign(L, TilePlan()); g->dgrad.assign(L, TilePlan()); g->wgrad.assign(L, WgradPlan());
     size_t off = 0, max_act = 0, max_partial = 0;
     if (net->in_ch > 1) {
         g->staged_off = off;
@@ -100,17 +270,22 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
     int r = H, c = W;
     for (size_t l = 0; l < L; ++l) {
         const Layer& ly = net->layers[l];
+        const int in_r = r, in_c = c;
         r -= (ly.k - 1) * ly.dil;
         c -= (ly.k - 1) * ly.dil;
         if (r < 1 || c < 1) return false;
         g->rows[l] = r; g->cols[l] = c;
         size_t bytes = sizeof(float) * (size_t)B * r * c * ly.cout;
         max_act = std::max(max_act, bytes);
-        if (ly.kind != MPCNN_MP) {
-            long rows_total = (long)B * r;
-            long rpc = std::max<long>(1, (rows_total + kWgradChunkTarget - 1) / kWgradChunkTarget);
-            long chunks = (rows_total + rpc - 1) / rpc;
-            max_partial = std::max(max_partial, sizeof(float) * (size_t)chunks * ly.p_len);
+        if (ly.kind == MPCNN_MP) continue;
+        if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.k, ly.fwd_rpad, ly.fwd_ct);
+        if (training) {
+            if (ly.dgrad_mfma && l > 0)
+                g->dgrad[l] = plan_conv_tiles(B, in_r, in_c, ly.dil, ly.k, ly.dgrad_rpad, ly.dgrad_ct);
+            g->wgrad[l] = plan_wgrad(ly, B, r, c);
+            const WgradPlan& w = g->wgrad[l];
+            size_t n = w.ok ? (size_t)w.slabs : (size_t)w.chunks;
+            max_partial = std::max(max_partial, sizeof(float) * n * ly.p_len);
         }
     }
     if (r != H - net->patch + 1 || c != W - net->patch + 1) return false;
@@ -146,19 +321,85 @@ inline int grid_for(long total, int block = 256, int cap = 1 << 20)
     return (int)std::min<long>(std::max<long>(g, 1), cap);
 }
 
+// ------------------------------------------------------------------ MFMA launches
+template <int OT, int PT>
+void launch_conv_inst(const mpcnn::ConvArgs& a, dim3 grid, size_t lds, hipStream_t st)
+{
+    mpcnn::conv_mfma_kernel<OT, PT><<<grid, 256, lds, st>>>(a);
+}
+void launch_conv_mfma(const mpcnn::ConvArgs& a, int OT, int PT, dim3 grid, size_t lds, hipStream_t st)
+{
+#define CASE(o, p) if (OT == o && PT == p) return launch_conv_inst<o, p>(a, grid, lds, st)
+    CASE(1, 4); CASE(2, 4); CASE(4, 4); CASE(7, 4); CASE(8, 4);
+    CASE(1, 8); CASE(2, 8); CASE(4, 8);
+#undef CASE
+}
+template <int NP, int OT>
+void launch_wgrad_inst(const mpcnn::WgradArgs& a, dim3 grid, size_t lds, hipStream_t st)
+{
+    mpcnn::wgrad_mfma_kernel<NP, OT><<<grid, 256, lds, st>>>(a);
+}
+void launch_wgrad_mfma(const mpcnn::WgradArgs& a, int OT, dim3 grid, size_t lds, hipStream_t st)
+{
+    switch (OT) {
+    case 1: return launch_wgrad_inst<16, 1>(a, grid, lds, st);
+    case 2: return launch_wgrad_inst<16, 2>(a, grid, lds, st);
+    case 4: return launch_wgrad_inst<16, 4>(a, grid, lds, st);
+    case 7: return launch_wgrad_inst<9, 7>(a, grid, lds, st);
+    case 8: return launch_wgrad_inst<8, 8>(a, grid, lds, st);
+    }
+}
+// Kernels that may ask for more than 64 KiB of dynamic LDS must say so once.
+mpcnn_status set_lds_attrs()
+{
+#define ATTR(fn) HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fn), \
+                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024))
+    ATTR((mpcnn::wgrad_mfma_kernel<16, 1>)); ATTR((mpcnn::wgrad_mfma_kernel<16, 2>));
+    ATTR((mpcnn::wgrad_mfma_kernel<16, 4>)); ATTR((mpcnn::wgrad_mfma_kernel<9, 7>));
+    ATTR((mpcnn::wgrad_mfma_kernel<8, 8>));
+#undef ATTR
+    return MPCNN_OK;
+}
+
+mpcnn_status refresh_packs(mpcnn_net* net, hipStream_t st)
+{
+    if (!net->packs_stale || !net->d_packs) { net->packs_stale = false; return MPCNN_OK; }
+    for (size_t l = 0; l < net->layers.size(); ++l) {
+        const Layer& ly = net->layers[l];
+        if (ly.kind == MPCNN_MP) continue;
+        const float* Wc = net->d_params + ly.p_off;
+        if (ly.fwd_mfma)
+            LAUNCH("pack_weights", l, 0, 0, 8.0 * ly.fwd_pack_len,
+                   mpcnn::pack_weights_kernel<<<grid_for((long)ly.fwd_pack_len), 256, 0, st>>>(
+                       Wc, net->d_packs + ly.fwd_pack_off, ly.k * ly.k, ly.cin, ly.cout, ly.fwd_rpad,
+                       ly.fwd_ct.pad, 0));
+        if (ly.dgrad_mfma && l > 0)
+            LAUNCH("pack_weights", l, 0, 0, 8.0 * ly.dgrad_pack_len,
+                   mpcnn::pack_weights_kernel<<<grid_for((long)ly.dgrad_pack_len), 256, 0, st>>>(
+                       Wc, net->d_packs + ly.dgrad_pack_off, ly.k * ly.k, ly.cin, ly.cout,
+                       ly.dgrad_rpad, ly.dgrad_ct.pad, 1));
+    }
+    HIP_TRY(hipGetLastError());
+    net->packs_stale = false;
+    return MPCNN_OK;
+}
+
 // Forward through every layer; in training mode everything is kept for the backward.
 mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char* ws,
                          const int32_t* labels, const float* pixw, float* probs, float* dZ,
                          double* loss_dev, hipStream_t st)
 {
     using namespace mpcnn;
+    mpcnn_status rc = refresh_packs(net, st);
+    if (rc != MPCNN_OK) return rc;
     const int B = g.B;
     const float* in = image;
     int Hi = g.H, Wi = g.W, Ci = net->in_ch;
     if (net->in_ch > 1) {
         float* staged = (float*)(ws + g.staged_off);
         long total = (long)B * Ci * Hi * Wi;
-        stage_input_kernel<<<grid_for(total), 256, 0, st>>>(image, staged, B, Ci, Hi, Wi);
+        LAUNCH("stage_input", -1, 0, 0, 8.0 * total,
+               stage_input_kernel<<<grid_for(total), 256, 0, st>>>(image, staged, B, Ci, Hi, Wi));
         in = staged;
     }
     const size_t L = net->layers.size();
@@ -166,20 +407,42 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
         const Layer& ly = net->layers[l];
         float* out = (float*)(ws + g.act_off[l]);
         const int Ho = g.rows[l], Wo = g.cols[l];
+        const double n_in = (double)B * Hi * Wi * Ci, n_out = (double)B * Ho * Wo * ly.cout;
         if (ly.kind == MPCNN_MP) {
             uint8_t* code = g.training ? (uint8_t*)(ws + g.code_off[l]) : nullptr;
             long total = (long)B * Ho * Wo * ly.cout;
-            maxfilter_fwd_direct_kernel<<<grid_for(total), 256, 0, st>>>(in, out, code, B, Hi, Wi,
-                                                                        ly.cout, Ho, Wo, ly.k, ly.dil);
+            LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (code ? 9.0 : 8.0),
+                   maxfilter_fwd_direct_kernel<<<grid_for(total), 256, 0, st>>>(
+                       in, out, code, B, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil));
         } else {
             const float* Wk = net->d_params + ly.p_off;
-            long total = (long)B * Ho * Wo * ly.cout;
-            if (ly.tanh_out)
-                conv_fwd_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
-                    in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil);
-            else
-                conv_fwd_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
-                    in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil);
+            const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k * Ci;
+            const double bytes = 4.0 * (n_in + n_out + ly.p_len);
+            const int step = (l == L - 1) ? 3 : 1;
+            if (ly.fwd_mfma && g.fwd[l].ok) {
+                const TilePlan& tp = g.fwd[l];
+                ConvArgs a{};
+                a.in = in; a.wpack = (const v4f*)(net->d_packs + ly.fwd_pack_off);
+                a.bias = Wk + (size_t)ly.k * ly.k * Ci * ly.cout; a.act = nullptr; a.out = out;
+                a.B = B; a.Hi = Hi; a.Wi = Wi; a.Cr = Ci; a.CrPad = ly.fwd_rpad;
+                a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout; a.CoPad = ly.fwd_ct.pad;
+                a.k = ly.k; a.d = ly.dil; a.origin = 0;
+                a.Ty = tp.Ty; a.Tx = tp.Tx; a.nty = tp.nty; a.ntx = tp.ntx;
+                a.mode = ly.tanh_out ? kFwdTanh : kFwdLinear;
+                dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
+                LAUNCH("conv_fwd_mfma", l, step, flops, bytes,
+                       launch_conv_mfma(a, ly.fwd_ct.OT, tp.PT, grid, tp.lds, st));
+            } else {
+                long total = (long)B * Ho * Wo * ly.cout;
+                if (ly.tanh_out)
+                    LAUNCH("conv_fwd_direct", l, step, flops, bytes,
+                           conv_fwd_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
+                               in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil));
+                else
+                    LAUNCH("conv_fwd_direct", l, step, flops, bytes,
+                           conv_fwd_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
+                               in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil));
+            }
         }
         in = out; Hi = Ho; Wi = Wo; Ci = ly.cout;
     }
@@ -187,10 +450,14 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
     double* lp = (double*)(ws + g.loss_partial_off);
     const bool want_loss = labels && loss_dev;
     long total = (long)B * Hi * Wi;
-    int blocks = std::min<long>(kLossBlocks, (total + 255) / 256);
-    softmax_ce_kernel<<<blocks, 256, 0, st>>>(in, probs, labels, pixw, dZ, want_loss ? lp : nullptr,
-                                              B, Hi, Wi, g.H, g.W, (net->patch - 1) / 2, net->n_cls);
-    if (want_loss) loss_reduce_kernel<<<1, 64, 0, st>>>(lp, blocks, loss_dev);
+    int blocks = (int)std::min<long>(kLossBlocks, (total + 255) / 256);
+    LAUNCH("softmax_ce", L - 1, 3, 0, 4.0 * total * (3.0 * net->n_cls + 2.0),
+           softmax_ce_kernel<<<blocks, 256, 0, st>>>(in, probs, labels, pixw, dZ,
+                                                     want_loss ? lp : nullptr, B, Hi, Wi, g.H, g.W,
+                                                     (net->patch - 1) / 2, net->n_cls));
+    if (want_loss)
+        LAUNCH("loss_reduce", L - 1, 0, 0, 8.0 * blocks,
+               loss_reduce_kernel<<<1, 64, 0, st>>>(lp, blocks, loss_dev));
     HIP_TRY(hipGetLastError());
     return MPCNN_OK;
 }
@@ -214,35 +481,76 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
         const bool below_tanh = li > 0 && net->layers[li - 1].tanh_out;
         const float* dY = dbuf[cur];
         float* dA = dbuf[cur ^ 1];
+        const double n_in = (double)B * Hi * Wi * Ci, n_out = (double)B * Ho * Wo * ly.cout;
         if (ly.kind == MPCNN_MP) {
             if (li == 0) break;  // nothing below has parameters
             const uint8_t* code = (const uint8_t*)(ws + g.code_off[li]);
             long total = (long)B * Hi * Wi * Ci;
+            const double bytes = n_out * 5.0 + n_in * (below_tanh ? 8.0 : 4.0);
             if (below_tanh)
-                maxfilter_bwd_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
-                    dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil);
+                LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
+                       maxfilter_bwd_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
+                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
             else
-                maxfilter_bwd_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
-                    dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil);
+                LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
+                       maxfilter_bwd_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
+                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
         } else {
-            // parameter gradient: split over output rows, then a fixed-order sum
-            long rows_total = (long)B * Ho;
-            long rpc = std::max<long>(1, (rows_total + kWgradChunkTarget - 1) / kWgradChunkTarget);
-            int chunks = (int)((rows_total + rpc - 1) / rpc);
-            dim3 grid((unsigned)((ly.p_len + 255) / 256), (unsigned)chunks);
-            conv_wgrad_direct_kernel<<<grid, 256, 0, st>>>(A, dY, partial, B, Hi, Wi, Ci, Ho, Wo,
-                                                           ly.cout, ly.k, ly.dil, (int)rpc);
-            reduce_partials_kernel<<<(unsigned)((ly.p_len + 255) / 256), 256, 0, st>>>(
-                partial, net->d_grads + ly.p_off, (long)ly.p_len, chunks);
+            const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k * Ci;
+            const int wstep = (li == L - 1) ? 4 : 5, dstep = (li == L - 1) ? 4 : 6;
+            // parameter gradient: partial sums over slabs of positions, then a fixed-order sum
+            const WgradPlan& wp = g.wgrad[li];
+            int n_partial;
+            if (wp.ok) {
+                WgradArgs a{};
+                a.in = A; a.dY = dY; a.partial = partial;
+                a.B = B; a.Hi = Hi; a.Wi = Wi; a.Ci = Ci; a.CiPad = ceil_div(Ci, 16) * 16;
+                a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout; a.k = ly.k; a.d = ly.dil;
+                a.Ty = wp.Ty; a.Tx = wp.Tx; a.nty = wp.nty; a.ntx = wp.ntx;
+                a.tiles_total = wp.tiles_total; a.tiles_per_slab = wp.tiles_per_slab;
+                a.pairs_total = wp.pairs_total; a.pairs_per_group = wp.pairs_per_group;
+                dim3 grid((unsigned)wp.slabs, (unsigned)wp.groups, (unsigned)ly.wgrad_ct.split);
+                LAUNCH("wgrad_mfma", li, wstep, flops, 4.0 * (n_in + n_out + ly.p_len),
+                       launch_wgrad_mfma(a, ly.wgrad_ct.OT, grid, wp.lds, st));
+                n_partial = wp.slabs;
+            } else {
+                dim3 grid((unsigned)((ly.p_len + 255) / 256), (unsigned)wp.chunks);
+                LAUNCH("wgrad_direct", li, wstep, flops, 4.0 * (n_in + n_out + ly.p_len),
+                       conv_wgrad_direct_kernel<<<grid, 256, 0, st>>>(A, dY, partial, B, Hi, Wi, Ci, Ho,
+                                                                      Wo, ly.cout, ly.k, ly.dil,
+                                                                      wp.rows_per_chunk));
+                n_partial = wp.chunks;
+            }
+            LAUNCH("reduce_partials", li, 0, 0, 4.0 * ly.p_len * (n_partial + 1.0),
+                   reduce_partials_kernel<<<(unsigned)((ly.p_len + 255) / 256), 256, 0, st>>>(
+                       partial, net->d_grads + ly.p_off, (long)ly.p_len, n_partial));
             if (li == 0) break;  // the image needs no gradient
             const float* Wk = net->d_params + ly.p_off;
-            long total = (long)B * Hi * Wi * Ci;
-            if (below_tanh)
-                conv_dgrad_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
-                    dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil);
-            else
-                conv_dgrad_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
-                    dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil);
+            const double dbytes = 4.0 * (n_in * (below_tanh ? 2.0 : 1.0) + n_out + ly.p_len);
+            if (ly.dgrad_mfma && g.dgrad[li].ok) {
+                const TilePlan& tp = g.dgrad[li];
+                ConvArgs a{};
+                a.in = dY; a.wpack = (const v4f*)(net->d_packs + ly.dgrad_pack_off);
+                a.bias = nullptr; a.act = A; a.out = dA;
+                a.B = B; a.Hi = Ho; a.Wi = Wo; a.Cr = ly.cout; a.CrPad = ly.dgrad_rpad;
+                a.Ho = Hi; a.Wo = Wi; a.Co = Ci; a.CoPad = ly.dgrad_ct.pad;
+                a.k = ly.k; a.d = ly.dil; a.origin = -(ly.k - 1);
+                a.Ty = tp.Ty; a.Tx = tp.Tx; a.nty = tp.nty; a.ntx = tp.ntx;
+                a.mode = below_tanh ? kDgradTanh : kDgradPlain;
+                dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.dgrad_ct.split);
+                LAUNCH("conv_dgrad_mfma", li, dstep, flops, dbytes,
+                       launch_conv_mfma(a, ly.dgrad_ct.OT, tp.PT, grid, tp.lds, st));
+            } else {
+                long total = (long)B * Hi * Wi * Ci;
+                if (below_tanh)
+                    LAUNCH("conv_dgrad_direct", li, dstep, flops, dbytes,
+                           conv_dgrad_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
+                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil));
+                else
+                    LAUNCH("conv_dgrad_direct", li, dstep, flops, dbytes,
+                           conv_dgrad_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
+                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil));
+            }
         }
         cur ^= 1;
     }
@@ -316,7 +624,7 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
     net->in_ch = in_channels; net->patch = patch;
     int side = patch, ch = in_channels, dil = 1;
     bool seen_fc = false;
-    size_t off = 0;
+    size_t off = 0, pack = 0;
     mpcnn_status st = MPCNN_OK;
     for (int l = 0; l < n_layers && st == MPCNN_OK; ++l) {
         const mpcnn_layer_desc& d = layers[l];
@@ -343,6 +651,25 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
             ly.p_off = off;
             ly.p_len = ((size_t)ly.k * ly.k * ly.cin + 1) * ly.cout;
             off += ly.p_len;
+            // matrix cores take layers whose reduced channel count is a multiple of 4 and at
+            // least 8, and that produce at least 8 channels; the rest run on the direct kernels
+            const bool last = l == n_layers - 1;
+            ly.fwd_mfma = !last && ly.cin % 4 == 0 && ly.cin >= 8 && ly.cout >= 8;
+            ly.dgrad_mfma = l > 0 && ly.cout % 4 == 0 && ly.cout >= 8 && ly.cin >= 8;
+            ly.wgrad_mfma = ly.cin >= 8 && ly.cout >= 8;
+            if (ly.fwd_mfma) {
+                ly.fwd_ct = chan_tiling(ly.cout);
+                ly.fwd_rpad = ceil_div(ly.cin, 16) * 16;
+                ly.fwd_pack_len = (size_t)ly.k * ly.k * ly.fwd_rpad * ly.fwd_ct.pad;
+                ly.fwd_pack_off = pack; pack += ly.fwd_pack_len;
+            }
+            if (ly.dgrad_mfma) {
+                ly.dgrad_ct = chan_tiling(ly.cin);
+                ly.dgrad_rpad = ceil_div(ly.cout, 16) * 16;
+                ly.dgrad_pack_len = (size_t)ly.k * ly.k * ly.dgrad_rpad * ly.dgrad_ct.pad;
+                ly.dgrad_pack_off = pack; pack += ly.dgrad_pack_len;
+            }
+            if (ly.wgrad_mfma) ly.wgrad_ct = chan_tiling(ly.cout);
         }
         ch = ly.cout;
         net->layers.push_back(ly);
@@ -352,7 +679,7 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
     if (st == MPCNN_OK && ch > mpcnn::kMaxClasses)
         st = fail(MPCNN_EUNSUPPORTED, "%d classes, at most %d are built", ch, mpcnn::kMaxClasses);
     if (st != MPCNN_OK) { delete net; return st; }
-    net->n_cls = ch; net->n_params = off;
+    net->n_cls = ch; net->n_params = off; net->pack_len = pack;
     *out = net;
     return MPCNN_OK;
 }
@@ -360,11 +687,15 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
 void mpcnn_net_destroy(mpcnn_net* net)
 {
     if (!net) return;
-    if (net->d_params || net->d_grads) {
+    if (net->d_params || net->d_grads || net->d_packs) {
         (void)hipSetDevice(net->device);
+        (void)hipDeviceSynchronize();
         (void)hipFree(net->d_params);
         (void)hipFree(net->d_grads);
+        (void)hipFree(net->d_packs);
     }
+    for (auto& p : net->pending) { (void)hipEventDestroy(p.e0); (void)hipEventDestroy(p.e1); }
+    for (auto e : net->pool) (void)hipEventDestroy(e);
     delete net;
 }
 
@@ -396,12 +727,16 @@ mpcnn_status mpcnn_set_params(mpcnn_net* net, const float* params_host, size_t n
         HIP_TRY(hipMalloc((void**)&net->d_params, sizeof(float) * n));
         HIP_TRY(hipMalloc((void**)&net->d_grads, sizeof(float) * n));
         HIP_TRY(hipMemset(net->d_grads, 0, sizeof(float) * n));
+        if (net->pack_len) HIP_TRY(hipMalloc((void**)&net->d_packs, sizeof(float) * net->pack_len));
+        mpcnn_status rc = set_lds_attrs();
+        if (rc != MPCNN_OK) return rc;
     }
     std::vector<float> tmp(n);
     to_device_order(net, params_host, tmp.data());
     HIP_TRY(hipSetDevice(net->device));
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipMemcpy(net->d_params, tmp.data(), sizeof(float) * n, hipMemcpyHostToDevice));
+    net->packs_stale = true;
     return MPCNN_OK;
 }
 
@@ -434,6 +769,7 @@ static mpcnn_status check_call(mpcnn_net* net, const float* image, int B, int H,
     if (!make_geom(net, B, H, W, training, g)) return fail(MPCNN_ESHAPE, "layer plan does not fit a %dx%d image", H, W);
     if (ws_bytes < g->total) return fail(MPCNN_EWORKSPACE, "workspace %zu bytes, need %zu", ws_bytes, g->total);
     if (((uintptr_t)ws & 255u) != 0) return fail(MPCNN_EINVAL, "workspace must be 256-byte aligned");
+    if (((uintptr_t)image & 15u) != 0) return fail(MPCNN_EINVAL, "image must be 16-byte aligned");
     return MPCNN_OK;
 }
 
@@ -472,9 +808,12 @@ mpcnn_status mpcnn_sgd_step(mpcnn_net* net, float lr, float grad_scale, void* hi
     if (!net) return fail(MPCNN_EINVAL, "null net");
     if (!net->d_params) return fail(MPCNN_EINVAL, "parameters were never set");
     long n = (long)net->n_params;
-    mpcnn::sgd_kernel<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)hip_stream>>>(
-        net->d_params, net->d_grads, lr * grad_scale, n);
+    hipStream_t st = (hipStream_t)hip_stream;
+    LAUNCH("sgd", -1, 8, 2.0 * n, 12.0 * n,
+           mpcnn::sgd_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(net->d_params, net->d_grads,
+                                                                          lr * grad_scale, n));
     HIP_TRY(hipGetLastError());
+    net->packs_stale = true;
     return MPCNN_OK;
 }
 
@@ -504,6 +843,39 @@ mpcnn_status mpcnn_get_argmax(const mpcnn_net* net, int layer, uint8_t* host, si
     HIP_TRY(hipSetDevice(net->device));
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipMemcpy(host, (char*)net->last_ws + g.code_off[layer], elems, hipMemcpyDeviceToHost));
+    return MPCNN_OK;
+}
+
+mpcnn_status mpcnn_profile_enable(mpcnn_net* net, int on)
+{
+    if (!net) return fail(MPCNN_EINVAL, "null net");
+    net->prof_on = on != 0;
+    return MPCNN_OK;
+}
+
+mpcnn_status mpcnn_profile_read(mpcnn_net* net, mpcnn_kernel_stat* out_host, int cap, int* n)
+{
+    if (!net || !n || (cap > 0 && !out_host)) return fail(MPCNN_EINVAL, "null argument");
+    for (auto& p : net->pending) {
+        HIP_TRY(hipEventSynchronize(p.e1));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, p.e0, p.e1));
+        net->sites[p.site].ms += ms;
+        net->sites[p.site].launches += 1;
+        net->pool.push_back(p.e0);
+        net->pool.push_back(p.e1);
+    }
+    net->pending.clear();
+    *n = (int)net->sites.size();
+    for (int i = 0; i < *n && i < cap; ++i) {
+        const ProfSite& s = net->sites[i];
+        mpcnn_kernel_stat& o = out_host[i];
+        memset(&o, 0, sizeof o);
+        snprintf(o.name, sizeof o.name, "%s", s.name);
+        o.layer = s.layer; o.step = s.step; o.launches = s.launches;
+        o.ms_total = s.ms; o.flops = s.flops; o.bytes = s.bytes;
+    }
+    for (auto& s : net->sites) { s.ms = 0; s.launches = 0; }
     return MPCNN_OK;
 }
 

@@ -28,6 +28,7 @@ SYMBOLS = [
     "mpcnn_param_count", "mpcnn_layer_shape", "mpcnn_set_params", "mpcnn_get_params",
     "mpcnn_get_grads", "mpcnn_workspace_bytes", "mpcnn_seg_forward", "mpcnn_seg_backward",
     "mpcnn_sgd_step", "mpcnn_get_activation", "mpcnn_get_argmax", "mpcnn_last_error",
+    "mpcnn_profile_enable", "mpcnn_profile_read",
 ]
 
 
@@ -39,6 +40,13 @@ class MpcnnError(RuntimeError):
 
 class _LayerDesc(C.Structure):
     _fields_ = [("kind", C.c_int), ("maps", C.c_int), ("k", C.c_int)]
+
+
+class KernelStat(C.Structure):
+    """mpcnn_kernel_stat: one launch site (kernel x layer) of the profiled calls."""
+    _fields_ = [("name", C.c_char * 48), ("layer", C.c_int), ("step", C.c_int),
+                ("launches", C.c_int), ("ms_total", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
 
 
 _lib = None
@@ -76,6 +84,8 @@ def lib():
         L.mpcnn_get_activation.argtypes = [vp, i, vp, sz]
         L.mpcnn_get_argmax.argtypes = [vp, i, vp, sz]
         L.mpcnn_last_error.restype = C.c_char_p
+        L.mpcnn_profile_enable.argtypes = [vp, i]
+        L.mpcnn_profile_read.argtypes = [vp, C.POINTER(KernelStat), i, C.POINTER(i)]
         _lib = L
     return _lib
 
@@ -196,6 +206,20 @@ class Net:
 
     def sgd_step(self, lr: float, grad_scale: float = 1.0, stream=None):
         _check(lib().mpcnn_sgd_step(self._h, lr, grad_scale, _stream_handle(stream)))
+
+    # ---- per-kernel timing
+    def profile_enable(self, on: bool):
+        _check(lib().mpcnn_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self):
+        """List of dicts (name, layer, step, launches, ms_total, flops, bytes), waits for the GPU."""
+        cap = 256
+        arr = (KernelStat * cap)()
+        n = C.c_int(0)
+        _check(lib().mpcnn_profile_read(self._h, arr, cap, C.byref(n)))
+        return [dict(name=arr[k].name.decode(), layer=arr[k].layer, step=arr[k].step,
+                     launches=arr[k].launches, ms_total=arr[k].ms_total, flops=arr[k].flops,
+                     bytes=arr[k].bytes) for k in range(min(n.value, cap))]
 
     # ---- test hooks
     def get_activation(self, B: int, H: int, W: int, layer: int) -> np.ndarray:
