@@ -1,7 +1,6 @@
-// Direct (one thread per output element) kernels for every step of the whole-image
-// pass.  They accept any layer shape and serve the layers that are not shaped for
-// the matrix cores (first layer with 1-3 input channels, class layer with 2-3
-// outputs, odd channel counts); the MFMA kernels take the rest.
+// Direct (one thread per output element) kernels: the fallbacks that accept any layer
+// shape (channel counts that are not multiples of 4, class layers the fused kernel does
+// not cover, tiles that do not fit LDS), plus the staging, softmax and SGD kernels.
 //
 // Tensors are dense whole-image maps in channels-last order [B][rows][cols][C].
 // A layer that follows pooling by a cumulative factor d reads taps d elements
@@ -27,34 +26,6 @@ __global__ void stage_input_kernel(const float* __restrict__ src, float* __restr
         int y = (int)(q % H);
         int b = (int)(q / H);
         dst[e] = src[(((long)b * C + c) * H + y) * W + x];
-    }
-}
-
-// a1: Y[b,y,x,o] = act(bias[o] + sum_{u,v,c} W[u,v,c,o] * A[b, y+u*d, x+v*d, c])
-// (Background, "Convolutional Layer"; applied to the whole image, Alg. 1.)
-template <bool TANH>
-__global__ void conv_fwd_direct_kernel(const float* __restrict__ A, const float* __restrict__ Wk,
-                                       float* __restrict__ Y, int B, int Hi, int Wi, int Ci, int Ho,
-                                       int Wo, int Co, int k, int d)
-{
-    long total = (long)B * Ho * Wo * Co;
-    const float* bias = Wk + (long)k * k * Ci * Co;
-    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
-         e += (long)gridDim.x * blockDim.x) {
-        int o = (int)(e % Co);
-        long p = e / Co;
-        int x = (int)(p % Wo);
-        long q = p / Wo;
-        int y = (int)(q % Ho);
-        int b = (int)(q / Ho);
-        float acc = bias[o];
-        for (int u = 0; u < k; ++u)
-            for (int v = 0; v < k; ++v) {
-                const float* a = A + (((long)b * Hi + (y + u * d)) * Wi + (x + v * d)) * Ci;
-                const float* w = Wk + (long)(u * k + v) * Ci * Co + o;
-                for (int c = 0; c < Ci; ++c) acc = fmaf(a[c], w[(long)c * Co], acc);
-            }
-        Y[e] = TANH ? tanhf(acc) : acc;
     }
 }
 
@@ -125,17 +96,6 @@ __global__ void conv_wgrad_direct_kernel(const float* __restrict__ A, const floa
         }
     }
     partial[(long)blockIdx.y * KN + e] = acc;
-}
-
-// Second stage of every split reduction: out[e] = sum_{i<n} partial[i][e], i ascending.
-__global__ void reduce_partials_kernel(const float* __restrict__ partial, float* __restrict__ out,
-                                       long len, int n)
-{
-    long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= len) return;
-    double s = 0.0;
-    for (int i = 0; i < n; ++i) s += (double)partial[(long)i * len + e];
-    out[e] = (float)s;
 }
 
 // a2: stride-1 max filter with taps d apart, plus the argmax tap code of the FIRST
@@ -260,16 +220,6 @@ __global__ void softmax_ce_kernel(const float* __restrict__ Z, float* __restrict
             __syncthreads();
         }
         if (threadIdx.x == 0) loss_partial[blockIdx.x] = red[0];
-    }
-}
-
-__global__ void loss_reduce_kernel(const double* __restrict__ partial, int n,
-                                   double* __restrict__ loss)
-{
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        double s = 0.0;
-        for (int i = 0; i < n; ++i) s += partial[i];
-        *loss = s;
     }
 }
 

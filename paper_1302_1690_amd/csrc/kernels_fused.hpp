@@ -1,0 +1,306 @@
+// Bandwidth-bound steps of the whole-image pass, each written so that every tensor is
+// read or written once, in channels-last order [B][rows][cols][C]:
+//   first_layer_kernel   conv + bias + tanh for a layer with very few input channels
+//   maxfilter_fwd4 / maxfilter_bwd4   stride-1 max filter / routing by argmax, 4 channels per thread
+//   class_layer_kernel   last FC (1x1) + softmax + cross-entropy + its own backward
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels_mfma.hpp"
+
+namespace mpcnn {
+
+// Conv + bias + tanh when the input has too few channels for the matrix cores (the image
+// itself: 1 or 3 channels).  One thread = one position x 16 output channels; weights are
+// wave-uniform (scalar loads), the output is written as four 128-bit stores.
+__global__ __launch_bounds__(256) void first_layer_kernel(const float* __restrict__ A,
+                                                          const float* __restrict__ Wk,
+                                                          float* __restrict__ Y, int B, int Hi, int Wi,
+                                                          int Ci, int Ho, int Wo, int Co, int k, int d,
+                                                          int tanh_out)
+{
+    const long total = (long)B * Ho * Wo;
+    const long m = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int o0 = blockIdx.y * 16;
+    if (m >= total) return;
+    const int x = (int)(m % Wo);
+    const long q = m / Wo;
+    const int y = (int)(q % Ho), b = (int)(q / Ho);
+    float acc[16];
+#pragma unroll
+    for (int o = 0; o < 16; ++o) acc[o] = 0.f;
+    const float* bias = Wk + (long)k * k * Ci * Co;
+    for (int u = 0; u < k; ++u)
+        for (int v = 0; v < k; ++v) {
+            const float* a = A + (((long)b * Hi + (y + u * d)) * Wi + (x + v * d)) * Ci;
+            const float* w = Wk + (long)(u * k + v) * Ci * Co + o0;
+            for (int c = 0; c < Ci; ++c) {
+                const float av = a[c];
+#pragma unroll
+                for (int o = 0; o < 16; ++o)
+                    if (o0 + o < Co) acc[o] = fmaf(av, w[(long)c * Co + o], acc[o]);
+            }
+        }
+    float* out = Y + m * Co + o0;
+#pragma unroll
+    for (int o = 0; o < 16; ++o) {
+        if (o0 + o < Co) {
+            float r = acc[o] + bias[o0 + o];
+            acc[o] = tanh_out ? tanhf(r) : r;
+        }
+    }
+    if ((Co & 3) == 0) {
+#pragma unroll
+        for (int o = 0; o < 16; o += 4)
+            if (o0 + o < Co) *reinterpret_cast<v4f*>(out + o) = (v4f){acc[o], acc[o + 1], acc[o + 2], acc[o + 3]};
+    } else {
+#pragma unroll
+        for (int o = 0; o < 16; ++o)
+            if (o0 + o < Co) out[o] = acc[o];
+    }
+}
+
+// a2, four channels per thread (C % 4 == 0): O = max over the p*p taps d apart, code = tap of
+// the FIRST maximum in row-major (u,v) order (strict > while scanning), packed 4 codes / store.
+__global__ __launch_bounds__(256) void maxfilter_fwd4_kernel(const float* __restrict__ A,
+                                                             float* __restrict__ O,
+                                                             uint8_t* __restrict__ code, int B, int Hi,
+                                                             int Wi, int C, int Ho, int Wo, int p, int d)
+{
+    const int C4 = C >> 2;
+    const long total = (long)B * Ho * Wo * C4;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long)gridDim.x * blockDim.x) {
+        const int c4 = (int)(e % C4);
+        long q = e / C4;
+        const int x = (int)(q % Wo); q /= Wo;
+        const int y = (int)(q % Ho);
+        const int b = (int)(q / Ho);
+        const float* base = A + (((long)b * Hi + y) * Wi + x) * C + 4 * c4;
+        v4f best = *reinterpret_cast<const v4f*>(base);
+        uint32_t bi[4] = {0, 0, 0, 0};
+        for (int u = 0; u < p; ++u)
+            for (int v = (u == 0 ? 1 : 0); v < p; ++v) {
+                const v4f a = *reinterpret_cast<const v4f*>(base + ((long)u * d * Wi + v * d) * C);
+                const uint32_t t = u * p + v;
+#pragma unroll
+                for (int z = 0; z < 4; ++z)
+                    if (a[z] > best[z]) { best[z] = a[z]; bi[z] = t; }
+            }
+        *reinterpret_cast<v4f*>(O + e * 4) = best;
+        if (code) *reinterpret_cast<uint32_t*>(code + e * 4) = bi[0] | (bi[1] << 8) | (bi[2] << 16) | (bi[3] << 24);
+    }
+}
+
+// a7, four channels per thread: dA = sum over the windows that chose this element (gather in
+// fixed (u,v) order, no atomics), times (1 - A^2) when A is a tanh output.
+template <bool TANHP>
+__global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const float* __restrict__ dO,
+                                                             const uint8_t* __restrict__ code,
+                                                             const float* __restrict__ A,
+                                                             float* __restrict__ dA, int B, int Hi,
+                                                             int Wi, int C, int Ho, int Wo, int p, int d)
+{
+    const int C4 = C >> 2;
+    const long total = (long)B * Hi * Wi * C4;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long)gridDim.x * blockDim.x) {
+        const int c4 = (int)(e % C4);
+        long q = e / C4;
+        const int x = (int)(q % Wi); q /= Wi;
+        const int y = (int)(q % Hi);
+        const int b = (int)(q / Hi);
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+        for (int u = 0; u < p; ++u) {
+            const int yy = y - u * d;
+            if (yy < 0 || yy >= Ho) continue;
+            for (int v = 0; v < p; ++v) {
+                const int xx = x - v * d;
+                if (xx < 0 || xx >= Wo) continue;
+                const long s = (((long)b * Ho + yy) * Wo + xx) * C + 4 * c4;
+                const uint32_t cd = *reinterpret_cast<const uint32_t*>(code + s);
+                const v4f g = *reinterpret_cast<const v4f*>(dO + s);
+                const uint32_t t = u * p + v;
+#pragma unroll
+                for (int z = 0; z < 4; ++z)
+                    if (((cd >> (8 * z)) & 255u) == t) acc[z] += g[z];
+            }
+        }
+        if (TANHP) {
+            const v4f a = *reinterpret_cast<const v4f*>(A + e * 4);
+#pragma unroll
+            for (int z = 0; z < 4; ++z) acc[z] *= 1.f - a[z] * a[z];
+        }
+        *reinterpret_cast<v4f*>(dA + e * 4) = acc;
+    }
+}
+
+struct ClassArgs {
+    const float* h;        // [M][K] input of the class layer
+    const float* Wk;       // [K][NCLS] then bias [NCLS]
+    float* probs;          // [B][NCLS][Ho][Wo] or null
+    const int32_t* labels; // [B][H][W]      (training)
+    const float* pixw;     // [B][H][W] or null
+    float* dH;             // [M][K]         (training) delta w.r.t. the pre-activation below
+    float* partial;        // [blocks][(K+1)*NCLS]  (training) this block's share of dW, db
+    double* loss_partial;  // [blocks] or null
+    int B, Ho, Wo, H, W, ctr, K, tanh_below;
+};
+
+// a3 + a4 in one pass over h: class logits z = W h + b, softmax, probabilities out; in
+// training also delta_z = w (p - onehot), the block's share of the summed cross-entropy,
+// dW += h delta_z^T, db += delta_z, and dH = (W^T delta_z) (1 - h^2)   (Results: MCCE per
+// pixel; Method: first step of back-propagation; Alg. 2 for the sums).
+// 16 lanes share one position: lane j holds channels 4(j+16v)..+3, v < KV; dot products meet
+// by xor-shuffles in a fixed order.  A workgroup walks 16 positions at a time.
+template <int NCLS, int KV, bool TRAIN>
+__global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
+{
+    __shared__ float red[4][KV * 4 * NCLS + NCLS][16];
+    __shared__ double lred[16];
+    const int tid = threadIdx.x, j = tid & 15, grp = tid >> 4, wave = tid >> 6;
+    const long M = (long)a.B * a.Ho * a.Wo;
+    float w[KV][4][NCLS];
+    float gw[KV][4][NCLS];
+    float gb[NCLS], bias[NCLS];
+#pragma unroll
+    for (int v = 0; v < KV; ++v)
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int o = 0; o < NCLS; ++o) {
+                const int c = 4 * (j + 16 * v) + s;
+                w[v][s][o] = c < a.K ? a.Wk[(long)c * NCLS + o] : 0.f;
+                gw[v][s][o] = 0.f;
+            }
+#pragma unroll
+    for (int o = 0; o < NCLS; ++o) { bias[o] = a.Wk[(long)a.K * NCLS + o]; gb[o] = 0.f; }
+    double my_loss = 0.0;
+
+    for (long m = (long)blockIdx.x * 16 + grp; m < M; m += (long)gridDim.x * 16) {
+        v4f hv[KV];
+        float z[NCLS];
+#pragma unroll
+        for (int o = 0; o < NCLS; ++o) z[o] = 0.f;
+#pragma unroll
+        for (int v = 0; v < KV; ++v) {
+            const int c = 4 * (j + 16 * v);
+            hv[v] = c < a.K ? *reinterpret_cast<const v4f*>(a.h + m * a.K + c) : (v4f){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int o = 0; o < NCLS; ++o) z[o] = fmaf(hv[v][s], w[v][s][o], z[o]);
+        }
+#pragma unroll
+        for (int o = 0; o < NCLS; ++o) {
+            z[o] += __shfl_xor(z[o], 8, 16);
+            z[o] += __shfl_xor(z[o], 4, 16);
+            z[o] += __shfl_xor(z[o], 2, 16);
+            z[o] += __shfl_xor(z[o], 1, 16);
+            z[o] += bias[o];
+        }
+        float zmax = z[0];
+#pragma unroll
+        for (int o = 1; o < NCLS; ++o) zmax = fmaxf(zmax, z[o]);
+        float sum = 0.f, pr[NCLS];
+#pragma unroll
+        for (int o = 0; o < NCLS; ++o) { z[o] -= zmax; pr[o] = expf(z[o]); sum += pr[o]; }
+        const float inv = 1.f / sum;
+        const int jx = (int)(m % a.Wo);
+        const long qq = m / a.Wo;
+        const int iy = (int)(qq % a.Ho), b = (int)(qq / a.Ho);
+#pragma unroll
+        for (int o = 0; o < NCLS; ++o) {
+            pr[o] *= inv;
+            if (a.probs && j == o) a.probs[(((long)b * NCLS + o) * a.Ho + iy) * a.Wo + jx] = pr[o];
+        }
+        if (TRAIN) {
+            const long lp = ((long)b * a.H + (iy + a.ctr)) * a.W + (jx + a.ctr);
+            int t = a.labels[lp];
+            float wt = 0.f;
+            if (t < 0 || t >= NCLS) t = -1;
+            else wt = a.pixw ? a.pixw[lp] : 1.f;
+            float dz[NCLS];
+            float zt = 0.f;
+#pragma unroll
+            for (int o = 0; o < NCLS; ++o) {
+                dz[o] = t >= 0 ? wt * (pr[o] - (o == t ? 1.f : 0.f)) : 0.f;
+                if (o == t) zt = z[o];
+                gb[o] += dz[o];
+            }
+            if (t >= 0 && j == 0) my_loss += (double)wt * ((double)logf(sum) - (double)zt);
+#pragma unroll
+            for (int v = 0; v < KV; ++v) {
+                const int c = 4 * (j + 16 * v);
+                v4f dh;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    float g = 0.f;
+#pragma unroll
+                    for (int o = 0; o < NCLS; ++o) {
+                        g = fmaf(w[v][s][o], dz[o], g);
+                        gw[v][s][o] = fmaf(hv[v][s], dz[o], gw[v][s][o]);
+                    }
+                    dh[s] = a.tanh_below ? g * (1.f - hv[v][s] * hv[v][s]) : g;
+                }
+                if (c < a.K) *reinterpret_cast<v4f*>(a.dH + m * a.K + c) = dh;
+            }
+        }
+    }
+    if (TRAIN) {
+        // sum the 16 position groups of the workgroup: 4 per wave by shuffles, waves through LDS
+        constexpr int NV = KV * 4 * NCLS + NCLS;
+        float vals[NV];
+#pragma unroll
+        for (int v = 0; v < KV; ++v)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int o = 0; o < NCLS; ++o) vals[(v * 4 + s) * NCLS + o] = gw[v][s][o];
+#pragma unroll
+        for (int o = 0; o < NCLS; ++o) vals[KV * 4 * NCLS + o] = gb[o];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            vals[i] += __shfl_xor(vals[i], 16, 64);
+            vals[i] += __shfl_xor(vals[i], 32, 64);
+            if ((tid & 63) < 16) red[wave][i][j] = vals[i];
+        }
+        my_loss += __shfl_xor(my_loss, 16, 64);   // only lanes with j == 0 hold a share
+        my_loss += __shfl_xor(my_loss, 32, 64);
+        if ((tid & 63) == 0) lred[wave] = my_loss;
+        __syncthreads();
+        float* out = a.partial + (long)blockIdx.x * ((long)a.K + 1) * NCLS;
+        for (int e = tid; e < NV * 16; e += 256) {
+            const int i = e >> 4, jj = e & 15;
+            const float s = (red[0][i][jj] + red[1][i][jj]) + (red[2][i][jj] + red[3][i][jj]);
+            if (i < KV * 4 * NCLS) {
+                const int o = i % NCLS, vs = i / NCLS, sidx = vs & 3, v = vs >> 2;
+                const int c = 4 * (jj + 16 * v) + sidx;
+                if (c < a.K) out[(long)c * NCLS + o] = s;
+            } else if (jj == 0) {
+                out[(long)a.K * NCLS + (i - KV * 4 * NCLS)] = s;
+            }
+        }
+        if (tid == 0 && a.loss_partial)
+            a.loss_partial[blockIdx.x] = (lred[0] + lred[1]) + (lred[2] + lred[3]);
+    }
+}
+
+// Sum of the per-block loss shares in a fixed (tree) order.
+__global__ __launch_bounds__(256) void loss_tree_kernel(const double* __restrict__ partial, int n,
+                                                        double* __restrict__ loss)
+{
+    __shared__ double red[256];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += 256) s += partial[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = red[0];
+}
+
+}  // namespace mpcnn

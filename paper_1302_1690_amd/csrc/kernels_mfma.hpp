@@ -207,22 +207,22 @@ struct WgradArgs {
     const float* in;     // [B][Hi][Wi][Ci]  layer input (activations)
     const float* dY;     // [B][Ho][Wo][Co]  delta w.r.t. the layer's pre-activation
     float* partial;      // [slabs][(k*k*Ci + 1) * Co]
-    int B, Hi, Wi, Ci, CiPad;
+    int B, Hi, Wi, Ci;
     int Ho, Wo, Co;
     int k, d;
     int Ty, Tx, nty, ntx;  // Ty*Tx <= 64
     int tiles_total, tiles_per_slab;
-    int pairs_total;       // k*k * CiPad/16   (tap, channel-tile) pairs
-    int pairs_per_group;   // pairs handled by one blockIdx.y
+    int rtiles_total;      // ceil(k*k*Ci / 16) tiles of 16 gradient rows, row = tap*Ci + c
+    int rtiles_per_group;  // row tiles handled by one blockIdx.y
 };
 
 // Weight gradient dW[tap][c][o] = sum over positions of in[pos + tap][c] * dY[pos][o]
 // (Alg. 2: the same gradient function applied to every fragment, results summed).
-// MFMA rows = 16 input channels of one tap, columns = 16 output channels, contraction over
-// positions.  blockIdx.x = slab of position tiles (partial sums, added later in slab order),
-// blockIdx.y = group of (tap, channel-tile) pairs, blockIdx.z = group of OT output tiles.
-// Inside a workgroup the pairs are dealt round-robin to the 4 waves; each wave keeps
-// NP x OT accumulator tiles in registers across its whole slab.
+// MFMA rows = 16 consecutive gradient rows (tap, c) in parameter order, columns = 16 output
+// channels, contraction over positions.  blockIdx.x = slab of position tiles (partial sums,
+// added later in slab order), blockIdx.y = group of row tiles, blockIdx.z = group of OT
+// output tiles.  Inside a workgroup the row tiles are dealt round-robin to the 4 waves; each
+// wave keeps NP x OT accumulator tiles in registers across its whole slab.
 template <int NP, int OT>
 __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
 {
@@ -230,29 +230,32 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
     const int hw = a.Tx + a.k - 1, hh = a.Ty + a.k - 1;
-    const int Cs = a.CiPad + 1;        // halo pitch (floats): odd pitch spreads the 4 positions read together
+    const int Cs = a.Ci | 1;           // halo pitch (floats): odd, spreads the 4 positions read together
     const int Ds = 16 * OT + 1;        // delta tile pitch
     float* halo = lds;
     float* dtile = halo + hh * hw * Cs;
     int* hbt = reinterpret_cast<int*>(dtile + 64 * Ds);  // position -> halo index
 
-    const int ct_n = a.CiPad >> 4;
+    const int rows_total = a.k * a.k * a.Ci;
     const int ot0 = blockIdx.z * OT;
-    const int pair0 = blockIdx.y * a.pairs_per_group;
-    int pend = pair0 + a.pairs_per_group;
-    if (pend > a.pairs_total) pend = a.pairs_total;
-    // this wave's pairs: pair0 + wave + 4*p
-    int poff[NP];   // LDS offset of the pair's (tap, channel tile) relative to a position's halo slot
+    const int rt0 = blockIdx.y * a.rtiles_per_group;
+    int rend = rt0 + a.rtiles_per_group;
+    if (rend > a.rtiles_total) rend = a.rtiles_total;
+    // this wave's row tiles: rt0 + wave + 4*p; this lane feeds row 16*tile + li of each
+    int poff[NP];   // LDS offset of that row's (tap, c) relative to a position's halo slot
     int np = 0;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-        int q = pair0 + wave + 4 * p;
+        const int q = rt0 + wave + 4 * p;
         poff[p] = 0;
-        if (q < pend) {
-            int tap = q / ct_n, ct = q - tap * ct_n;
-            int ta = tap / a.k, tb = tap - ta * a.k;
-            poff[p] = (ta * hw + tb) * Cs + 16 * ct + li;
+        if (q < rend) {
             np = p + 1;
+            const int row = 16 * q + li;
+            if (row < rows_total) {
+                const int tap = row / a.Ci, c = row - tap * a.Ci;
+                const int ta = tap / a.k, tb = tap - ta * a.k;
+                poff[p] = (ta * hw + tb) * Cs + c;
+            }
         }
     }
     if (tid < 64) {
@@ -272,7 +275,8 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
     const int tile_begin = blockIdx.x * a.tiles_per_slab;
     int tile_end = tile_begin + a.tiles_per_slab;
     if (tile_end > a.tiles_total) tile_end = a.tiles_total;
-    const int cq = a.CiPad >> 2;
+    const int cq = (a.Ci + 3) >> 2;
+    const bool vec_in = (a.Ci & 3) == 0, vec_dy = (a.Co & 3) == 0;
 
     for (int tile = tile_begin; tile < tile_end; ++tile) {
         int bid = tile;
@@ -286,19 +290,24 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
         const int ty0 = tyi * a.Ty, tx0 = txi * a.Tx;
         if (ty0 >= fh || tx0 >= fw) continue;  // uniform
         __syncthreads();                        // previous tile fully consumed
-        // input halo (always inside the input tensor where the delta is valid; zero elsewhere)
+        // input halo: zero outside the input tensor
         for (int it = tid; it < hh * hw * cq; it += 256) {
             const int pos = it / cq, q = it - pos * cq;
             const int ha = pos / hw, hb = pos - ha * hw;
             const int iy = (ty0 + ha) * a.d + ry, ix = (tx0 + hb) * a.d + rx;
-            v4f v = {0.f, 0.f, 0.f, 0.f};
-            if (iy < a.Hi && ix < a.Wi && 4 * q < a.Ci) {
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            const int nv = a.Ci - 4 * q < 4 ? a.Ci - 4 * q : 4;
+            if (iy < a.Hi && ix < a.Wi) {
                 const float* src = a.in + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Ci + 4 * q;
-                if ((a.Ci & 3) == 0) v = *reinterpret_cast<const v4f*>(src);
-                else for (int z = 0; z < 4; ++z) if (4 * q + z < a.Ci) v[z] = src[z];
+                if (vec_in) {
+                    v4f t = *reinterpret_cast<const v4f*>(src);
+                    v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+                } else {
+                    for (int z = 0; z < nv; ++z) v[z] = src[z];
+                }
             }
             float* dst = halo + pos * Cs + 4 * q;
-            dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
+            for (int z = 0; z < nv; ++z) dst[z] = v[z];
         }
         // delta tile: zero for padding positions and padding channels
         for (int it = tid; it < 64 * 4 * OT; it += 256) {
@@ -306,11 +315,15 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
             const int ty = m / a.Tx, tx = m - ty * a.Tx;
             const int fy = ty0 + ty, fx = tx0 + tx;
             const int oc = 16 * ot0 + 4 * q;
-            v4f v = {0.f, 0.f, 0.f, 0.f};
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
             if (ty < a.Ty && fy < fh && fx < fw && oc < a.Co) {
                 const float* src = a.dY + (((long)b * a.Ho + (fy * a.d + ry)) * a.Wo + (fx * a.d + rx)) * a.Co + oc;
-                if ((a.Co & 3) == 0) v = *reinterpret_cast<const v4f*>(src);
-                else for (int z = 0; z < 4; ++z) if (oc + z < a.Co) v[z] = src[z];
+                if (vec_dy) {
+                    v4f t = *reinterpret_cast<const v4f*>(src);
+                    v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+                } else {
+                    for (int z = 0; z < 4; ++z) if (oc + z < a.Co) v[z] = src[z];
+                }
             }
             float* dst = dtile + m * Ds + 4 * q;
             dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
@@ -338,26 +351,25 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
         }
     }
 
-    // ---- write this slab's partial sums in parameter order [tap][c][o], bias row last
-    const long plen = ((long)a.k * a.k * a.Ci + 1) * a.Co;
+    // ---- write this slab's partial sums in parameter order (row-major [tap*Ci + c][o]), bias row last
+    const long plen = ((long)rows_total + 1) * a.Co;
     float* out = a.partial + (long)blockIdx.x * plen;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
         if (p < np) {
-            const int q = pair0 + wave + 4 * p;
-            const int tap = q / ct_n, ct = q - tap * ct_n;
+            const int q = rt0 + wave + 4 * p;
 #pragma unroll
             for (int o = 0; o < OT; ++o) {
                 const int oc = 16 * (ot0 + o) + li;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int c = 16 * ct + 4 * lg + r;
-                    if (c < a.Ci && oc < a.Co) out[((long)tap * a.Ci + c) * a.Co + oc] = acc[p][o][r];
+                    const int row = 16 * q + 4 * lg + r;
+                    if (row < rows_total && oc < a.Co) out[(long)row * a.Co + oc] = acc[p][o][r];
                 }
             }
         }
     }
-    // bias gradient = column sums of the delta tile; one wave of one pair group owns it
+    // bias gradient = column sums of the delta tiles; one wave of the first row group owns it
     if (blockIdx.y == 0) {
         __syncthreads();
         float* red = lds;  // [4 lane groups][16*OT]
@@ -369,10 +381,39 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
         if (tid < 16 * OT) {
             const int oc = 16 * ot0 + tid;
             if (oc < a.Co)
-                out[(long)a.k * a.k * a.Ci * a.Co + oc] =
+                out[(long)rows_total * a.Co + oc] =
                     (red[tid] + red[16 * OT + tid]) + (red[32 * OT + tid] + red[48 * OT + tid]);
         }
     }
+}
+
+// Second stage of the split reductions: out[e] = sum_{i<n} partial[i][e].  64 columns per
+// workgroup, the n rows dealt to 4 thread rows; each adds its rows in ascending order, then
+// the 4 sums are added in a fixed order - the result does not depend on timing.
+__global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restrict__ partial,
+                                                          float* __restrict__ out, long len, int n)
+{
+    __shared__ double red[4][64];
+    const int col = threadIdx.x & 63, row = threadIdx.x >> 6;
+    const long e = (long)blockIdx.x * 64 + col;
+    double s = 0.0;
+    if (e < len) {
+        const int per = (n + 3) >> 2;
+        const int i0 = row * per, i1 = (i0 + per < n) ? i0 + per : n;
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;  // independent chains: loads in flight
+        int i = i0;
+        for (; i + 3 < i1; i += 4) {
+            s0 += (double)partial[(long)i * len + e];
+            s1 += (double)partial[(long)(i + 1) * len + e];
+            s2 += (double)partial[(long)(i + 2) * len + e];
+            s3 += (double)partial[(long)(i + 3) * len + e];
+        }
+        for (; i < i1; ++i) s0 += (double)partial[(long)i * len + e];
+        s = (s0 + s1) + (s2 + s3);
+    }
+    red[row][col] = s;
+    __syncthreads();
+    if (row == 0 && e < len) out[e] = (float)((red[0][col] + red[1][col]) + (red[2][col] + red[3][col]));
 }
 
 }  // namespace mpcnn

@@ -19,6 +19,7 @@
 #include "../../include/mpcnn.h"
 #include "kernels_direct.hpp"
 #include "kernels_mfma.hpp"
+#include "kernels_fused.hpp"
 
 namespace {
 
@@ -41,7 +42,7 @@ mpcnn_status fail(mpcnn_status st, const char* fmt, ...)
                         __FILE__, __LINE__);                                               \
     } while (0)
 
-constexpr int kLossBlocks = 256;
+constexpr int kLossBlocks = 512;          // also the most workgroups of the class-layer kernel
 constexpr int kDirectWgradChunks = 512;   // split of the position reduction, direct kernel
 constexpr size_t kConvLdsCap = 64 * 1024; // halo bytes per workgroup (two workgroups per CU)
 constexpr size_t kWgradLdsCap = 144 * 1024;
@@ -74,6 +75,7 @@ struct Layer {
     size_t p_len;
     // matrix-core paths (decided once from the channel counts)
     bool fwd_mfma = false, dgrad_mfma = false, wgrad_mfma = false;
+    bool class_fused = false;             // last FC handled by class_layer_kernel
     ChanTiling fwd_ct{}, dgrad_ct{}, wgrad_ct{};
     int fwd_rpad = 0, dgrad_rpad = 0;     // reduced channels padded to 16
     size_t fwd_pack_off = 0, fwd_pack_len = 0, dgrad_pack_off = 0, dgrad_pack_len = 0;
@@ -83,7 +85,7 @@ struct TilePlan { int PT = 0, Ty = 0, Tx = 0, nty = 0, ntx = 0; size_t lds = 0; 
 struct WgradPlan {
     bool ok = false;
     int Ty = 0, Tx = 0, nty = 0, ntx = 0, tiles_total = 0, tiles_per_slab = 0, slabs = 0;
-    int pairs_total = 0, pairs_per_group = 0, groups = 0, NP = 0;
+    int rtiles_total = 0, rtiles_per_group = 0, groups = 0, NP = 0;
     size_t lds = 0;
     // direct kernel fallback
     int rows_per_chunk = 0, chunks = 0;
@@ -229,17 +231,16 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int out_r, int out_c)
     if (ly.wgrad_mfma) {
         const int d = ly.dil, k = ly.k;
         const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
-        const int cipad = ceil_div(ly.cin, 16) * 16;
-        const size_t pitch = sizeof(float) * (cipad + 1);
+        const size_t pitch = sizeof(float) * (ly.cin | 1);
         const size_t extra = sizeof(float) * (64 * (16 * ly.wgrad_ct.OT + 1) + 64);
         if (choose_tile(fh, fw, 64, k, pitch, extra, kWgradLdsCap, &w.Ty, &w.Tx)) {
             w.nty = ceil_div(fh, w.Ty); w.ntx = ceil_div(fw, w.Tx);
             w.tiles_total = B * d * d * w.nty * w.ntx;
             w.NP = wgrad_np(ly.wgrad_ct.OT);
-            w.pairs_total = k * k * (cipad / 16);
-            w.groups = ceil_div(w.pairs_total, 4 * w.NP);
-            w.pairs_per_group = ceil_div(ceil_div(w.pairs_total, w.groups), 4) * 4;
-            w.groups = ceil_div(w.pairs_total, w.pairs_per_group);
+            w.rtiles_total = ceil_div(k * k * ly.cin, 16);
+            w.groups = ceil_div(w.rtiles_total, 4 * w.NP);
+            w.rtiles_per_group = ceil_div(ceil_div(w.rtiles_total, w.groups), 4) * 4;
+            w.groups = ceil_div(w.rtiles_total, w.rtiles_per_group);
             int target = std::max(1, kNumCU / (w.groups * ly.wgrad_ct.split));
             w.tiles_per_slab = ceil_div(w.tiles_total, target);
             w.slabs = ceil_div(w.tiles_total, w.tiles_per_slab);
@@ -253,6 +254,8 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int out_r, int out_c)
     w.chunks = (int)((rows_total + w.rows_per_chunk - 1) / w.rows_per_chunk);
     return w;
 }
+
+int class_blocks(long positions) { return (int)std::min<long>(kLossBlocks, (positions + 15) / 16); }
 
 bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g)
 {
@@ -279,7 +282,9 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         max_act = std::max(max_act, bytes);
         if (ly.kind == MPCNN_MP) continue;
         if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.k, ly.fwd_rpad, ly.fwd_ct);
-        if (training) {
+        if (training && ly.class_fused) {
+            max_partial = std::max(max_partial, sizeof(float) * class_blocks((long)B * r * c) * ly.p_len);
+        } else if (training) {
             if (ly.dgrad_mfma && l > 0)
                 g->dgrad[l] = plan_conv_tiles(B, in_r, in_c, ly.dil, ly.k, ly.dgrad_rpad, ly.dgrad_ct);
             g->wgrad[l] = plan_wgrad(ly, B, r, c);
@@ -361,6 +366,19 @@ mpcnn_status set_lds_attrs()
     return MPCNN_OK;
 }
 
+template <int NCLS, int KV>
+void launch_class_inst(const mpcnn::ClassArgs& a, bool train, int blocks, hipStream_t st)
+{
+    if (train) mpcnn::class_layer_kernel<NCLS, KV, true><<<blocks, 256, 0, st>>>(a);
+    else mpcnn::class_layer_kernel<NCLS, KV, false><<<blocks, 256, 0, st>>>(a);
+}
+void launch_class(const mpcnn::ClassArgs& a, int ncls, int KV, bool train, int blocks, hipStream_t st)
+{
+#define CASE(n, v) if (ncls == n && KV == v) return launch_class_inst<n, v>(a, train, blocks, st)
+    CASE(2, 2); CASE(3, 2); CASE(4, 2); CASE(2, 4); CASE(3, 4); CASE(4, 4);
+#undef CASE
+}
+
 mpcnn_status refresh_packs(mpcnn_net* net, hipStream_t st)
 {
     if (!net->packs_stale || !net->d_packs) { net->packs_stale = false; return MPCNN_OK; }
@@ -403,6 +421,8 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
         in = staged;
     }
     const size_t L = net->layers.size();
+    double* lp = (double*)(ws + g.loss_partial_off);
+    const bool want_loss = labels && loss_dev;
     for (size_t l = 0; l < L; ++l) {
         const Layer& ly = net->layers[l];
         float* out = (float*)(ws + g.act_off[l]);
@@ -411,9 +431,37 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
         if (ly.kind == MPCNN_MP) {
             uint8_t* code = g.training ? (uint8_t*)(ws + g.code_off[l]) : nullptr;
             long total = (long)B * Ho * Wo * ly.cout;
-            LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (code ? 9.0 : 8.0),
-                   maxfilter_fwd_direct_kernel<<<grid_for(total), 256, 0, st>>>(
-                       in, out, code, B, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil));
+            if (ly.cout % 4 == 0)
+                LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (code ? 9.0 : 8.0),
+                       maxfilter_fwd4_kernel<<<grid_for(total / 4), 256, 0, st>>>(
+                           in, out, code, B, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil));
+            else
+                LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (code ? 9.0 : 8.0),
+                       maxfilter_fwd_direct_kernel<<<grid_for(total), 256, 0, st>>>(
+                           in, out, code, B, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil));
+        } else if (ly.class_fused) {
+            // last FC + softmax + cross-entropy (+ its own backward when labels are given)
+            const long M = (long)B * Ho * Wo;
+            ClassArgs a{};
+            a.h = in; a.Wk = net->d_params + ly.p_off; a.probs = probs;
+            a.labels = labels; a.pixw = pixw; a.dH = dZ; a.partial = (float*)(ws + g.partial_off);
+            a.loss_partial = want_loss ? lp : nullptr;
+            a.B = B; a.Ho = Ho; a.Wo = Wo; a.H = g.H; a.W = g.W; a.ctr = (net->patch - 1) / 2;
+            a.K = Ci; a.tanh_below = (l > 0 && net->layers[l - 1].tanh_out) ? 1 : 0;
+            const int blocks = class_blocks(M);
+            const bool train = labels != nullptr;
+            const double flops = 2.0 * M * Ci * ly.cout * (train ? 3.0 : 1.0);
+            const double bytes = 4.0 * (n_in * (train ? 2.0 : 1.0) + n_out);
+            LAUNCH("class_layer", l, train ? 4 : 3, flops, bytes,
+                   launch_class(a, ly.cout, Ci <= 128 ? 2 : 4, train, blocks, st));
+            if (train) {
+                LAUNCH("reduce_rows", l, 0, 0, 4.0 * ly.p_len * (blocks + 1.0),
+                       reduce_rows_kernel<<<(unsigned)((ly.p_len + 63) / 64), 256, 0, st>>>(
+                           a.partial, net->d_grads + ly.p_off, (long)ly.p_len, blocks));
+                if (want_loss)
+                    LAUNCH("loss_tree", l, 0, 0, 8.0 * blocks,
+                           loss_tree_kernel<<<1, 256, 0, st>>>(lp, blocks, loss_dev));
+            }
         } else {
             const float* Wk = net->d_params + ly.p_off;
             const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k * Ci;
@@ -433,31 +481,27 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 LAUNCH("conv_fwd_mfma", l, step, flops, bytes,
                        launch_conv_mfma(a, ly.fwd_ct.OT, tp.PT, grid, tp.lds, st));
             } else {
-                long total = (long)B * Ho * Wo * ly.cout;
-                if (ly.tanh_out)
-                    LAUNCH("conv_fwd_direct", l, step, flops, bytes,
-                           conv_fwd_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
-                               in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil));
-                else
-                    LAUNCH("conv_fwd_direct", l, step, flops, bytes,
-                           conv_fwd_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
-                               in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil));
+                long total = (long)B * Ho * Wo;
+                dim3 grid((unsigned)((total + 255) / 256), (unsigned)ceil_div(ly.cout, 16));
+                LAUNCH("first_layer", l, step, flops, bytes,
+                       first_layer_kernel<<<grid, 256, 0, st>>>(in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout,
+                                                               ly.k, ly.dil, ly.tanh_out ? 1 : 0));
             }
         }
         in = out; Hi = Ho; Wi = Wo; Ci = ly.cout;
     }
-    // class logits -> probabilities, deltas, loss
-    double* lp = (double*)(ws + g.loss_partial_off);
-    const bool want_loss = labels && loss_dev;
-    long total = (long)B * Hi * Wi;
-    int blocks = (int)std::min<long>(kLossBlocks, (total + 255) / 256);
-    LAUNCH("softmax_ce", L - 1, 3, 0, 4.0 * total * (3.0 * net->n_cls + 2.0),
-           softmax_ce_kernel<<<blocks, 256, 0, st>>>(in, probs, labels, pixw, dZ,
-                                                     want_loss ? lp : nullptr, B, Hi, Wi, g.H, g.W,
-                                                     (net->patch - 1) / 2, net->n_cls));
-    if (want_loss)
-        LAUNCH("loss_reduce", L - 1, 0, 0, 8.0 * blocks,
-               loss_reduce_kernel<<<1, 64, 0, st>>>(lp, blocks, loss_dev));
+    if (!net->layers[L - 1].class_fused) {
+        // class logits -> probabilities, deltas, loss
+        long total = (long)B * Hi * Wi;
+        int blocks = (int)std::min<long>(kLossBlocks, (total + 255) / 256);
+        LAUNCH("softmax_ce", L - 1, 3, 0, 4.0 * total * (3.0 * net->n_cls + 2.0),
+               softmax_ce_kernel<<<blocks, 256, 0, st>>>(in, probs, labels, pixw, dZ,
+                                                         want_loss ? lp : nullptr, B, Hi, Wi, g.H, g.W,
+                                                         (net->patch - 1) / 2, net->n_cls));
+        if (want_loss)
+            LAUNCH("loss_tree", L - 1, 0, 0, 8.0 * blocks,
+                   loss_tree_kernel<<<1, 256, 0, st>>>(lp, blocks, loss_dev));
+    }
     HIP_TRY(hipGetLastError());
     return MPCNN_OK;
 }
@@ -472,7 +516,8 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
     float* dbuf[2] = {(float*)(ws + g.delta_off[0]), (float*)(ws + g.delta_off[1])};
     float* partial = (float*)(ws + g.partial_off);
     int cur = 0;  // dbuf[cur] holds dL/d(pre-activation) of layer l's output (dL/d(output) for MP)
-    for (size_t li = L; li-- > 0;) {
+    // a fused class layer has already done its own backward and left the delta below it
+    for (size_t li = net->layers[L - 1].class_fused ? L - 1 : L; li-- > 0;) {
         const Layer& ly = net->layers[li];
         const int Ho = g.rows[li], Wo = g.cols[li];
         const float* A = li == 0 ? in0 : (const float*)(ws + g.act_off[li - 1]);
@@ -487,7 +532,15 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
             const uint8_t* code = (const uint8_t*)(ws + g.code_off[li]);
             long total = (long)B * Hi * Wi * Ci;
             const double bytes = n_out * 5.0 + n_in * (below_tanh ? 8.0 : 4.0);
-            if (below_tanh)
+            if (Ci % 4 == 0 && below_tanh)
+                LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
+                       maxfilter_bwd4_kernel<true><<<grid_for(total / 4), 256, 0, st>>>(
+                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
+            else if (Ci % 4 == 0)
+                LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
+                       maxfilter_bwd4_kernel<false><<<grid_for(total / 4), 256, 0, st>>>(
+                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
+            else if (below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        maxfilter_bwd_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
                            dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
@@ -504,11 +557,11 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
             if (wp.ok) {
                 WgradArgs a{};
                 a.in = A; a.dY = dY; a.partial = partial;
-                a.B = B; a.Hi = Hi; a.Wi = Wi; a.Ci = Ci; a.CiPad = ceil_div(Ci, 16) * 16;
+                a.B = B; a.Hi = Hi; a.Wi = Wi; a.Ci = Ci;
                 a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout; a.k = ly.k; a.d = ly.dil;
                 a.Ty = wp.Ty; a.Tx = wp.Tx; a.nty = wp.nty; a.ntx = wp.ntx;
                 a.tiles_total = wp.tiles_total; a.tiles_per_slab = wp.tiles_per_slab;
-                a.pairs_total = wp.pairs_total; a.pairs_per_group = wp.pairs_per_group;
+                a.rtiles_total = wp.rtiles_total; a.rtiles_per_group = wp.rtiles_per_group;
                 dim3 grid((unsigned)wp.slabs, (unsigned)wp.groups, (unsigned)ly.wgrad_ct.split);
                 LAUNCH("wgrad_mfma", li, wstep, flops, 4.0 * (n_in + n_out + ly.p_len),
                        launch_wgrad_mfma(a, ly.wgrad_ct.OT, grid, wp.lds, st));
@@ -521,8 +574,8 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                                                                       wp.rows_per_chunk));
                 n_partial = wp.chunks;
             }
-            LAUNCH("reduce_partials", li, 0, 0, 4.0 * ly.p_len * (n_partial + 1.0),
-                   reduce_partials_kernel<<<(unsigned)((ly.p_len + 255) / 256), 256, 0, st>>>(
+            LAUNCH("reduce_rows", li, 0, 0, 4.0 * ly.p_len * (n_partial + 1.0),
+                   reduce_rows_kernel<<<(unsigned)((ly.p_len + 63) / 64), 256, 0, st>>>(
                        partial, net->d_grads + ly.p_off, (long)ly.p_len, n_partial));
             if (li == 0) break;  // the image needs no gradient
             const float* Wk = net->d_params + ly.p_off;
@@ -654,9 +707,11 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
             // matrix cores take layers whose reduced channel count is a multiple of 4 and at
             // least 8, and that produce at least 8 channels; the rest run on the direct kernels
             const bool last = l == n_layers - 1;
+            ly.class_fused = last && ly.k == 1 && ly.cin % 4 == 0 && ly.cin <= 256 &&
+                             ly.cout >= 2 && ly.cout <= 4;
             ly.fwd_mfma = !last && ly.cin % 4 == 0 && ly.cin >= 8 && ly.cout >= 8;
             ly.dgrad_mfma = l > 0 && ly.cout % 4 == 0 && ly.cout >= 8 && ly.cin >= 8;
-            ly.wgrad_mfma = ly.cin >= 8 && ly.cout >= 8;
+            ly.wgrad_mfma = !ly.class_fused;   // any shape: gradient rows are tiled in parameter order
             if (ly.fwd_mfma) {
                 ly.fwd_ct = chan_tiling(ly.cout);
                 ly.fwd_rpad = ceil_div(ly.cin, 16) * 16;

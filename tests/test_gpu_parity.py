@@ -204,6 +204,29 @@ def test_generic_net_rgb_three_classes_pool3():
     full_parity(cfg, with_pixw=True)
 
 
+def test_class_layer_variants():
+    """Class layer shapes: 3 and 4 classes on 12 / 20 hidden units (fused kernel, ragged
+    channel tail), 6 classes (generic path), hidden width above 128 (wide fused variant)."""
+    from dataclasses import replace
+    for n_cls, hidden in ((3, 12), (4, 20), (6, 8), (2, 132)):
+        layers = ((C, 4, 3), (MP, 0, 2), (FC, hidden, 0), (FC, n_cls, 0))       # 8 -> 6 -> 3 -> FC
+        cfg = replace(wl.CONFIGS[0], name="class_%d_%d" % (n_cls, hidden), layers=layers, patch=8,
+                      n_classes=n_cls, batch=2, height=21, width=26, weight_amp=0.4)
+        img, lab = wl.make_inputs(cfg)
+        lab = np.random.default_rng(5).integers(0, n_cls, lab.shape).astype(np.int32)
+        params = wl.make_params(cfg)
+        pixw = np.random.default_rng(6).uniform(0.5, 1.5, lab.shape).astype(np.float32)
+        say("case %s" % cfg.name)
+        net, probs, loss, grads = run_gpu(cfg, img, lab, params, pixw)
+        ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, pixw, None, net)
+        assert np.abs(probs - ref["probs"]).max() <= TOL
+        assert abs(loss - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+        check_grads(cfg, grads, ref["grads"])
+        p2 = net.seg_forward(torch.from_numpy(img).cuda()).cpu().numpy()
+        assert np.array_equal(p2, probs)
+        net.close()
+
+
 def test_pool_first_and_fc_only_nets():
     from dataclasses import replace
     cfg = replace(wl.CONFIGS[0], name="pool_first", layers=((MP, 0, 2), (C, 3, 2), (FC, 2, 0)),
