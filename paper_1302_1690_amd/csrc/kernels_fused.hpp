@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) void first_layer_kernel(const float* __restric
     for (int o = 0; o < 16; ++o) {
         if (o0 + o < Co) {
             float r = acc[o] + bias[o0 + o];
-            acc[o] = tanh_out ? tanhf(r) : r;
+            acc[o] = tanh_out ? fast_tanh(r) : r;
         }
     }
     if ((Co & 3) == 0) {

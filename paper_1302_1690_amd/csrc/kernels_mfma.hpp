@@ -8,10 +8,16 @@
 // input halo is staged once in LDS, each element a contiguous channel vector in the
 // channels-last tensor, and is reused by all k*k taps.
 //
-// MFMA operand layout (v_mfma_f32_16x16x4_f32, 64 lanes): lane l supplies A[l%16][l/16] and
-// B[l/16][l%16], and receives D[4*(l/16)+r][l%16] in register r.  The contraction index may
-// be permuted freely as long as A and B agree, so every lane fetches FOUR consecutive
-// channels with one 128-bit load and feeds them to four successive MFMAs.
+// MFMA operand layouts (64 lanes, W = tile side, G = 64 / W lane groups):
+//   v_mfma_f32_32x32x2_f32: lane l supplies A[l%32][l/32], B[l/32][l%32]; register r of the
+//     result is D[8*(r/4) + 4*(l/32) + r%4][l%32]              (W = 32, G = 2, 16 registers)
+//   v_mfma_f32_16x16x4_f32: lane l supplies A[l%16][l/16], B[l/16][l%16]; register r is
+//     D[4*(l/16) + r][l%16]                                     (W = 16, G = 4, 4 registers)
+// The contraction index may be permuted freely as long as A and B agree, so every lane
+// fetches FOUR consecutive channels with one 128-bit load and feeds them to four successive
+// MFMAs; one reduction step therefore covers 4*G channels of one tap.  The 32-wide form
+// sustains the full fp32 matrix rate, the 16-wide one about 0.87 of it; the 16-wide form is
+// kept for channel counts that would waste more than that in 32-wide tiles.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -19,16 +25,25 @@
 namespace mpcnn {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// tanh(x) = 1 - 2 / (exp(2x) + 1) with the hardware exp2 and reciprocal: absolute error
+// about 1e-7; saturates correctly (exp -> inf gives 1, exp -> 0 gives -1).
+__device__ __forceinline__ float fast_tanh(float x)
+{
+    const float e = __expf(2.f * x);
+    return 1.f - 2.f * __frcp_rn(e + 1.f);
+}
 
 enum ConvMode { kFwdTanh = 0, kFwdLinear = 1, kDgradTanh = 2, kDgradPlain = 3 };
 
 struct ConvArgs {
     const float* in;     // [B][Hi][Wi][Cr]   tensor the taps read (activations, or deltas for dgrad)
-    const v4f* wpack;    // [steps][4][CoPad] x 4 channels, steps = k*k*CrPad/16
+    const v4f* wpack;    // [steps][G][CoPad] x 4 channels, steps = k*k*CrPad/(4G)
     const float* bias;   // [Co]   (forward modes)
     const float* act;    // [B][Ho][Wo][Co] tanh output at the positions written (kDgradTanh)
     float* out;          // [B][Ho][Wo][Co]
-    int B, Hi, Wi, Cr, CrPad;
+    int B, Hi, Wi, Cr, CrPad;   // CrPad: Cr rounded up to a multiple of 16
     int Ho, Wo, Co, CoPad;
     int k, d;
     int origin;          // halo origin in fragment units relative to the tile: 0 forward, -(k-1) dgrad
@@ -36,24 +51,24 @@ struct ConvArgs {
     int mode;
 };
 
-// Repack W[tap][c][o] (+ bias row) into the operand order of conv_mfma_kernel.
-//   forward : reduce over c, outputs o:  P[tap*nch + ch][g][o][s]  = W[tap][16ch+4g+s][o]
-//   dgrad   : reduce over o, outputs c:  P[tap'*nch + ch][g][c][s] = W[k*k-1-tap'][c][16ch+4g+s]
+// Repack W[tap][c][o] (+ bias row) into the operand order of conv_mfma_kernel, G lane groups:
+//   forward : reduce over c, outputs o:  P[tap*nch + ch][g][o][s]  = W[tap][4G*ch+4g+s][o]
+//   dgrad   : reduce over o, outputs c:  P[tap'*nch + ch][g][c][s] = W[k*k-1-tap'][c][4G*ch+4g+s]
 // (taps reversed: the data gradient at x collects deltas at x - u*d).  Padding is zero.
 __global__ void pack_weights_kernel(const float* __restrict__ W, float* __restrict__ P, int kk,
-                                    int Ci, int Co, int RPad, int OPad, int dgrad)
+                                    int Ci, int Co, int RPad, int OPad, int G, int dgrad)
 {
-    const int nch = RPad / 16;
-    long total = (long)kk * nch * 4 * OPad * 4;
+    const int nch = RPad / (4 * G);
+    long total = (long)kk * nch * G * OPad * 4;
     for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
          e += (long)gridDim.x * blockDim.x) {
         int s = (int)(e & 3);
         long q = e >> 2;
         int oo = (int)(q % OPad); q /= OPad;
-        int g = (int)(q & 3); q >>= 2;
+        int g = (int)(q % G); q /= G;
         int ch = (int)(q % nch);
         int tap = (int)(q / nch);
-        int r = 16 * ch + 4 * g + s;  // index along the reduced dimension
+        int r = 4 * G * ch + 4 * g + s;  // index along the reduced dimension
         float v = 0.f;
         if (!dgrad) {
             if (r < Ci && oo < Co) v = W[((long)tap * Ci + r) * Co + oo];
@@ -64,19 +79,37 @@ __global__ void pack_weights_kernel(const float* __restrict__ W, float* __restri
     }
 }
 
+template <int W> struct MfmaAcc;
+template <> struct MfmaAcc<16> { typedef v4f type; };
+template <> struct MfmaAcc<32> { typedef v16f type; };
+
+template <int W>
+__device__ __forceinline__ typename MfmaAcc<W>::type mfma_f32(float a, float b, typename MfmaAcc<W>::type c)
+{
+    if constexpr (W == 32) return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
 // Forward / data gradient of one dilated convolution as an implicit GEMM.
-// Workgroup = 256 threads = 4 waves; tile = 16*PT positions of one residue class x 16*OT
+// Workgroup = 256 threads = 4 waves; tile = W*PT positions of one residue class x W*OT
 // output channels (blockIdx.y selects the group of OT channel tiles).  All four waves hold
-// the full tile in accumulators and each sums a quarter of the k*k*CrPad/16 reduction
-// steps; the four partial tiles meet in LDS, where all 256 threads add them in wave order,
-// apply the epilogue and store.  Summation order is the same for every position, so equal
-// inputs give bit-equal outputs (exact pooling ties stay exact).
-template <int OT, int PT>
+// the full tile in accumulators and each sums a quarter of the reduction steps; the four
+// partial tiles meet in LDS, where all 256 threads add them in wave order, apply the
+// epilogue and store.  Summation order is the same for every position, so equal inputs
+// give bit-equal outputs (exact pooling ties stay exact).
+template <int W, int OT, int PT>
 __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
 {
+    constexpr int G = 64 / W;          // lane groups = contraction index of one MFMA
+    constexpr int QT = W / 4;          // 4-channel quads per output tile
+    constexpr int NQ = W * W / 256;    // quads one lane holds of one result tile
+    constexpr int ITEMS = OT * W * QT; // (position, quad) items of one epilogue round
+    constexpr int NIT = (ITEMS + 255) / 256;
+    typedef typename MfmaAcc<W>::type acc_t;
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int li = lane & 15, lg = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: loop control stays scalar
+    const int lt = lane % W, lg = lane / W;
 
     int bid = blockIdx.x;
     const int txi = bid % a.ntx; bid /= a.ntx;
@@ -90,115 +123,180 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
     if (ty0 >= fh || tx0 >= fw) return;  // uniform for the workgroup
 
     const int hw = a.Tx + a.k - 1, hh = a.Ty + a.k - 1;
-    const int Cs = a.CrPad + 4;  // row pitch of the halo in floats (pad: bank spread)
+    const int Cs4 = (a.CrPad >> 2) + 1;  // pitch of one halo position in 128-bit units (+1: bank spread)
     const int cq = a.CrPad >> 2;
+    const int ot0 = blockIdx.y * OT;
+    v4f* lds4 = reinterpret_cast<v4f*>(lds);
 
-    // ---- stage the halo: zero outside the tensor and in the channel padding
-    for (int it = tid; it < hh * hw * cq; it += 256) {
-        const int pos = it / cq, q = it - pos * cq;
-        const int ha = pos / hw, hb = pos - ha * hw;
-        const int fy = ty0 + ha + a.origin, fx = tx0 + hb + a.origin;
-        const int iy = fy * a.d + ry, ix = fx * a.d + rx;
-        v4f v = {0.f, 0.f, 0.f, 0.f};
-        if (fy >= 0 && fx >= 0 && iy < a.Hi && ix < a.Wi && 4 * q < a.Cr)
-            v = *reinterpret_cast<const v4f*>(a.in + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + 4 * q);
-        *reinterpret_cast<v4f*>(lds + pos * Cs + 4 * q) = v;
+    // ---- stage the halo: zero outside the tensor and in the channel padding.  Eight loads
+    // per thread are issued before the first is stored, so their latencies overlap.
+    {
+        const int total = hh * hw * cq;
+        constexpr int U = 8;
+        for (int base = tid; base < total; base += 256 * U) {
+            v4f v[U];
+            int dst[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int it = base + 256 * u;
+                v[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+                dst[u] = -1;
+                if (it < total) {
+                    const int pos = it / cq, q = it - pos * cq;
+                    const int ha = pos / hw, hb = pos - ha * hw;
+                    const int fy = ty0 + ha + a.origin, fx = tx0 + hb + a.origin;
+                    const int iy = fy * a.d + ry, ix = fx * a.d + rx;
+                    dst[u] = pos * Cs4 + q;
+                    if (fy >= 0 && fx >= 0 && iy < a.Hi && ix < a.Wi && 4 * q < a.Cr)
+                        v[u] = *reinterpret_cast<const v4f*>(
+                            a.in + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + 4 * q);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (dst[u] >= 0) lds4[dst[u]] = v[u];
+        }
+    }
+
+    // ---- what each thread will need in the epilogue, fetched now: the bias of its quads
+    // (clamped addresses instead of branches, so that the loads are issued back to back)
+    v4f bias4[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) bias4[it] = (v4f){0.f, 0.f, 0.f, 0.f};
+    if (a.mode <= kFwdLinear) {
+        constexpr int SLOTS_ = W * QT, TPS_ = 256 / SLOTS_ > 0 ? 256 / SLOTS_ : 1;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int oc = W * (ot0 + tid / SLOTS_ + TPS_ * it) + 4 * ((tid % SLOTS_) % QT);
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+                const int c = oc + z < a.Co ? oc + z : a.Co - 1;
+                bias4[it][z] = a.bias[c];
+            }
+        }
     }
 
     // ---- per-lane halo offsets of the PT positions this lane feeds as the B operand
     int lbase[PT];
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt) {
-        int m = 16 * pt + li;
+        int m = W * pt + lt;
         int ty = m / a.Tx, tx = m - ty * a.Tx;
         if (ty >= a.Ty) { ty = 0; tx = 0; }  // padding position: any in-bounds address
-        lbase[pt] = (ty * hw + tx) * Cs + 4 * lg;
+        lbase[pt] = (ty * hw + tx) * Cs4 + lg;
     }
 
-    const int nch = a.CrPad >> 4;
+    const int nch = a.CrPad / (4 * G);
     const int steps = a.k * a.k * nch;
     const int t0 = (steps * wave) >> 2, t1 = (steps * (wave + 1)) >> 2;
-    const int ot0 = blockIdx.y * OT;
-    const v4f* wp = a.wpack + (long)lg * a.CoPad + 16 * ot0 + li;
+    const int lane_w = lg * a.CoPad + W * ot0 + lt;   // this lane's offset inside one step of the pack
 
-    v4f acc[OT][PT];
+    // MFMA results kept in AccVGPRs: an (empty) asm operand in an AccVGPR makes the compiler
+    // select the AccVGPR form of the MFMAs.
+    { float agpr_hint = 0.f; asm volatile("" : "+a"(agpr_hint)); }
+    acc_t acc[OT][PT];
 #pragma unroll
     for (int o = 0; o < OT; ++o)
 #pragma unroll
-        for (int p = 0; p < PT; ++p) acc[o][p] = (v4f){0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < PT; ++p)
+#pragma unroll
+            for (int r = 0; r < 4 * NQ; ++r) acc[o][p][r] = 0.f;
 
     __syncthreads();
 
     // step t = tap * nch + chunk; the running tap offset avoids divisions
     int tap = t0 / nch, chunk = t0 - tap * nch;
     int ta = tap / a.k, tb = tap - ta * a.k;
-    // weights come from global memory (long latency): fetched one step ahead into a second
-    // register set; activations come from LDS and are fetched just before use
-    v4f wv[OT], wn[OT], av[PT];
+    // Operands are fetched one step ahead into one of two register sets (A, B) that the loop
+    // alternates between, so no register is copied and the loop holds next to no vector-ALU
+    // work: on this chip such instructions are not overlapped with the MFMAs of the same
+    // wave.  Weights come from global memory, activations from LDS.
+    v4f wA[OT], wB[OT], aA[PT], aB[PT];
+    auto fetch = [&](v4f (&wr)[OT], v4f (&ar)[PT], int t) {
+        const v4f* wq = a.wpack + (long)t * G * a.CoPad;   // uniform part of the address
 #pragma unroll
-    for (int o = 0; o < OT; ++o) wn[o] = wv[o] = (v4f){0.f, 0.f, 0.f, 0.f};
-    if (t0 < t1) {
+        for (int o = 0; o < OT; ++o) wr[o] = wq[lane_w + W * o];
+        const int soff = (ta * hw + tb) * Cs4 + G * chunk;
 #pragma unroll
-        for (int o = 0; o < OT; ++o) wv[o] = wp[(long)t0 * 4 * a.CoPad + 16 * o];
-    }
-    for (int t = t0; t < t1; ++t) {
-        if (t + 1 < t1) {
-#pragma unroll
-            for (int o = 0; o < OT; ++o) wn[o] = wp[(long)(t + 1) * 4 * a.CoPad + 16 * o];
-        }
-        const int soff = (ta * hw + tb) * Cs + 16 * chunk;
-#pragma unroll
-        for (int p = 0; p < PT; ++p) av[p] = *reinterpret_cast<const v4f*>(lds + lbase[p] + soff);
+        for (int p = 0; p < PT; ++p) ar[p] = lds4[lbase[p] + soff];
         if (++chunk == nch) { chunk = 0; if (++tb == a.k) { tb = 0; ++ta; } }
+    };
+    auto mfmas = [&](const v4f (&wr)[OT], const v4f (&ar)[PT]) {
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
             for (int o = 0; o < OT; ++o)
 #pragma unroll
-                for (int p = 0; p < PT; ++p)
-                    acc[o][p] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[o][s], av[p][s], acc[o][p], 0, 0, 0);
+                for (int p = 0; p < PT; ++p) acc[o][p] = mfma_f32<W>(wr[o][s], ar[p][s], acc[o][p]);
+    };
 #pragma unroll
-        for (int o = 0; o < OT; ++o) wv[o] = wn[o];
+    for (int o = 0; o < OT; ++o) wA[o] = wB[o] = (v4f){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int p = 0; p < PT; ++p) aA[p] = aB[p] = (v4f){0.f, 0.f, 0.f, 0.f};
+    if (t0 < t1) fetch(wA, aA, t0);
+    int t = t0;
+    for (; t + 2 <= t1; t += 2) {
+        fetch(wB, aB, t + 1);
+        mfmas(wA, aA);
+        if (t + 2 < t1) fetch(wA, aA, t + 2);
+        mfmas(wB, aB);
     }
+    if (t < t1) mfmas(wA, aA);
 
-    // ---- meet in LDS: part[wave][ot][pos li][quad lg] as 128-bit items, one position tile per round
-    v4f* part = reinterpret_cast<v4f*>(lds);
+    // ---- meet in LDS, one position tile per round: part[wave][ot][quad][position] as 128-bit
+    // items with a pitch of W+1 positions, which keeps both the writes (a lane group writes
+    // consecutive positions) and the reads (consecutive threads read consecutive quads of one
+    // position, so that the global stores are contiguous) free of bank conflicts.  This
+    // lane's n-th quad of a tile is quad n*G + lg of position lt.  Every thread then owns
+    // one (position, quad) slot per group of 256 items and walks the output tiles.
+    constexpr int WP = W + 1;
+    constexpr int SLOTS = W * QT;              // (position, quad) slots of one output tile
+    constexpr int TPS = 256 / SLOTS > 0 ? 256 / SLOTS : 1;   // output tiles covered by 256 threads at once
+    const int slot = tid % SLOTS, osub = tid / SLOTS;
+    const int ei = slot / QT, eq = slot % QT;  // position in tile, quad
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt) {
         __syncthreads();  // halo (or the previous round) no longer needed
 #pragma unroll
-        for (int o = 0; o < OT; ++o) part[((wave * OT + o) * 16 + li) * 4 + lg] = acc[o][pt];
+        for (int o = 0; o < OT; ++o)
+#pragma unroll
+            for (int n = 0; n < NQ; ++n)
+                lds4[((wave * OT + o) * QT + n * G + lg) * WP + lt] =
+                    (v4f){acc[o][pt][4 * n], acc[o][pt][4 * n + 1], acc[o][pt][4 * n + 2], acc[o][pt][4 * n + 3]};
         __syncthreads();
-        for (int e = tid; e < OT * 64; e += 256) {
-            const int o = e >> 6, rem = e & 63, i = rem >> 2, g = rem & 3;
-            const int m = 16 * pt + i;
-            const int ty = m / a.Tx, tx = m - ty * a.Tx;
-            const int fy = ty0 + ty, fx = tx0 + tx;
-            if (ty >= a.Ty || fy >= fh || fx >= fw) continue;
-            v4f s = part[((0 * OT + o) * 16 + i) * 4 + g];
-            s += part[((1 * OT + o) * 16 + i) * 4 + g];
-            s += part[((2 * OT + o) * 16 + i) * 4 + g];
-            s += part[((3 * OT + o) * 16 + i) * 4 + g];
-            const int oc = 16 * (ot0 + o) + 4 * g;
-            if (oc >= a.Co) continue;
-            const long off = (((long)b * a.Ho + (fy * a.d + ry)) * a.Wo + (fx * a.d + rx)) * a.Co + oc;
+        const int m = W * pt + ei;
+        const int ty = m / a.Tx, tx = m - ty * a.Tx;
+        const int fy = ty0 + ty, fx = tx0 + tx;
+        const bool pos_ok = ty < a.Ty && fy < fh && fx < fw;
+        const long pos_off = (((long)b * a.Ho + (fy * a.d + ry)) * a.Wo + (fx * a.d + rx)) * a.Co;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int o = osub + TPS * it;
+            const int oc = W * (ot0 + o) + 4 * eq;
+            if (o >= OT || !pos_ok || oc >= a.Co) continue;
+            const long off = pos_off + oc;
             const int nv = a.Co - oc < 4 ? a.Co - oc : 4;
-            float r[4] = {s[0], s[1], s[2], s[3]};
+            const bool vec = nv == 4 && (a.Co & 3) == 0;
+            v4f y = {0.f, 0.f, 0.f, 0.f};
+            if (a.mode == kDgradTanh) {
+                if (vec) y = *reinterpret_cast<const v4f*>(a.act + off);
+                else for (int z = 0; z < nv; ++z) y[z] = a.act[off + z];
+            }
+            v4f s = lds4[((0 * OT + o) * QT + eq) * WP + ei];
+            s += lds4[((1 * OT + o) * QT + eq) * WP + ei];
+            s += lds4[((2 * OT + o) * QT + eq) * WP + ei];
+            s += lds4[((3 * OT + o) * QT + eq) * WP + ei];
             if (a.mode == kFwdTanh) {
-                for (int q = 0; q < nv; ++q) r[q] = tanhf(r[q] + a.bias[oc + q]);
+#pragma unroll
+                for (int z = 0; z < 4; ++z) s[z] = fast_tanh(s[z] + bias4[it][z]);
             } else if (a.mode == kFwdLinear) {
-                for (int q = 0; q < nv; ++q) r[q] += a.bias[oc + q];
+                s += bias4[it];
             } else if (a.mode == kDgradTanh) {
-                for (int q = 0; q < nv; ++q) {
-                    float y = a.act[off + q];
-                    r[q] *= 1.f - y * y;
-                }
+#pragma unroll
+                for (int z = 0; z < 4; ++z) s[z] *= 1.f - y[z] * y[z];
             }
-            if (nv == 4 && (a.Co & 3) == 0) {
-                *reinterpret_cast<v4f*>(a.out + off) = (v4f){r[0], r[1], r[2], r[3]};
-            } else {
-                for (int q = 0; q < nv; ++q) a.out[off + q] = r[q];
-            }
+            if (vec) *reinterpret_cast<v4f*>(a.out + off) = s;
+            else for (int z = 0; z < nv; ++z) a.out[off + z] = s[z];
         }
     }
 }

@@ -51,17 +51,35 @@ constexpr int kNumCU = 256;
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Output-channel tiling of the MFMA kernels: OT tiles of 16 per workgroup, `split` groups.
-struct ChanTiling { int OT, split, pad; };
-ChanTiling chan_tiling(int channels)
+// Output-channel tiling of the MFMA kernels: tiles of W channels, OT tiles per workgroup,
+// `split` groups of them (blockIdx.y / z), `pad` = channels covered.
+struct ChanTiling { int W, OT, split, pad; };
+ChanTiling tile_channels(int channels, int W, const int* allowed, int n_allowed)
+{
+    const int max_ot = allowed[n_allowed - 1];
+    const int tiles = ceil_div(channels, W);
+    const int split = ceil_div(tiles, max_ot);
+    const int per = ceil_div(tiles, split);
+    int OT = max_ot;
+    for (int i = 0; i < n_allowed; ++i) if (allowed[i] >= per) { OT = allowed[i]; break; }
+    return {W, OT, split, OT * split * W};
+}
+ChanTiling chan_tiling_w(int channels, int W)   // forward / data-gradient kernel instances
+{
+    static const int allowed[] = {1, 2, 4};
+    return tile_channels(channels, W, allowed, 3);
+}
+ChanTiling wgrad_tiling(int channels)           // weight-gradient kernel instances (16-wide)
 {
     static const int allowed[] = {1, 2, 4, 7, 8};
-    const int tiles = ceil_div(channels, 16);
-    const int split = ceil_div(tiles, 8);
-    const int per = ceil_div(tiles, split);
-    int OT = 8;
-    for (int v : allowed) if (v >= per) { OT = v; break; }
-    return {OT, split, OT * split * 16};
+    return tile_channels(channels, 16, allowed, 5);
+}
+// 32-wide MFMA tiles run at the full fp32 matrix rate, 16-wide ones at about 0.87 of it:
+// take whichever wastes less once its padding is counted.
+ChanTiling chan_tiling(int channels)
+{
+    const ChanTiling a = chan_tiling_w(channels, 16), b = chan_tiling_w(channels, 32);
+    return (a.pad / 0.87 < b.pad) ? a : b;
 }
 int wgrad_np(int OT) { return OT <= 4 ? 16 : (OT == 7 ? 9 : 8); }
 
@@ -207,19 +225,20 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, co
     double best_cost = 0;
     const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
     const size_t pitch = sizeof(float) * (rpad + 4);
-    for (int PT : {4, 8}) {
-        if (PT == 8 && ct.OT > 4) continue;
+    const int regs_per_tile = ct.W * ct.W / 64;
+    for (int PT : {64 / ct.W, 128 / ct.W}) {            // 64 or 128 positions per workgroup
+        if (ct.OT * PT * regs_per_tile > (ct.W == 16 ? 64 : 128)) continue;  // accumulator registers per lane
         TilePlan p;
         p.PT = PT;
-        if (!choose_tile(fh, fw, 16 * PT, k, pitch, 0, kConvLdsCap, &p.Ty, &p.Tx)) continue;
+        if (!choose_tile(fh, fw, ct.W * PT, k, pitch, 0, kConvLdsCap, &p.Ty, &p.Tx)) continue;
         p.nty = ceil_div(fh, p.Ty); p.ntx = ceil_div(fw, p.Tx);
         size_t halo = (size_t)(p.Ty + k - 1) * (p.Tx + k - 1) * pitch;
-        p.lds = std::max(halo, (size_t)4 * ct.OT * 1024);
+        p.lds = std::max(halo, (size_t)4 * ct.OT * (ct.W / 4) * (ct.W + 1) * 4 * sizeof(float));
         p.ok = true;
         // rounds of workgroups over the chip (two per CU) times the work of one workgroup
         double wgs = (double)B * d * d * p.nty * p.ntx * ct.split;
         double rounds = std::ceil(wgs / (2.0 * kNumCU));
-        double cost = rounds * (PT + 1.0);
+        double cost = rounds * (ct.W * PT / 16 + 1.0);
         if (!best.ok || cost < best_cost) { best = p; best_cost = cost; }
     }
     return best;
@@ -327,17 +346,19 @@ inline int grid_for(long total, int block = 256, int cap = 1 << 20)
 }
 
 // ------------------------------------------------------------------ MFMA launches
-template <int OT, int PT>
+template <int W, int OT, int PT>
 void launch_conv_inst(const mpcnn::ConvArgs& a, dim3 grid, size_t lds, hipStream_t st)
 {
-    mpcnn::conv_mfma_kernel<OT, PT><<<grid, 256, lds, st>>>(a);
+    mpcnn::conv_mfma_kernel<W, OT, PT><<<grid, 256, lds, st>>>(a);
 }
-void launch_conv_mfma(const mpcnn::ConvArgs& a, int OT, int PT, dim3 grid, size_t lds, hipStream_t st)
+bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, int PT, dim3 grid, size_t lds,
+                      hipStream_t st)
 {
-#define CASE(o, p) if (OT == o && PT == p) return launch_conv_inst<o, p>(a, grid, lds, st)
-    CASE(1, 4); CASE(2, 4); CASE(4, 4); CASE(7, 4); CASE(8, 4);
-    CASE(1, 8); CASE(2, 8); CASE(4, 8);
+#define CASE(w, o, p) if (ct.W == w && ct.OT == o && PT == p) { launch_conv_inst<w, o, p>(a, grid, lds, st); return true; }
+    CASE(16, 1, 4) CASE(16, 2, 4) CASE(16, 4, 4) CASE(16, 1, 8) CASE(16, 2, 8)
+    CASE(32, 1, 2) CASE(32, 2, 2) CASE(32, 4, 2) CASE(32, 1, 4) CASE(32, 2, 4)
 #undef CASE
+    return false;
 }
 template <int NP, int OT>
 void launch_wgrad_inst(const mpcnn::WgradArgs& a, dim3 grid, size_t lds, hipStream_t st)
@@ -390,12 +411,12 @@ mpcnn_status refresh_packs(mpcnn_net* net, hipStream_t st)
             LAUNCH("pack_weights", l, 0, 0, 8.0 * ly.fwd_pack_len,
                    mpcnn::pack_weights_kernel<<<grid_for((long)ly.fwd_pack_len), 256, 0, st>>>(
                        Wc, net->d_packs + ly.fwd_pack_off, ly.k * ly.k, ly.cin, ly.cout, ly.fwd_rpad,
-                       ly.fwd_ct.pad, 0));
+                       ly.fwd_ct.pad, 64 / ly.fwd_ct.W, 0));
         if (ly.dgrad_mfma && l > 0)
             LAUNCH("pack_weights", l, 0, 0, 8.0 * ly.dgrad_pack_len,
                    mpcnn::pack_weights_kernel<<<grid_for((long)ly.dgrad_pack_len), 256, 0, st>>>(
                        Wc, net->d_packs + ly.dgrad_pack_off, ly.k * ly.k, ly.cin, ly.cout,
-                       ly.dgrad_rpad, ly.dgrad_ct.pad, 1));
+                       ly.dgrad_rpad, ly.dgrad_ct.pad, 64 / ly.dgrad_ct.W, 1));
     }
     HIP_TRY(hipGetLastError());
     net->packs_stale = false;
@@ -479,7 +500,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 a.mode = ly.tanh_out ? kFwdTanh : kFwdLinear;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
                 LAUNCH("conv_fwd_mfma", l, step, flops, bytes,
-                       launch_conv_mfma(a, ly.fwd_ct.OT, tp.PT, grid, tp.lds, st));
+                       launch_conv_mfma(a, ly.fwd_ct, tp.PT, grid, tp.lds, st));
             } else {
                 long total = (long)B * Ho * Wo;
                 dim3 grid((unsigned)((total + 255) / 256), (unsigned)ceil_div(ly.cout, 16));
@@ -592,7 +613,7 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.mode = below_tanh ? kDgradTanh : kDgradPlain;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.dgrad_ct.split);
                 LAUNCH("conv_dgrad_mfma", li, dstep, flops, dbytes,
-                       launch_conv_mfma(a, ly.dgrad_ct.OT, tp.PT, grid, tp.lds, st));
+                       launch_conv_mfma(a, ly.dgrad_ct, tp.PT, grid, tp.lds, st));
             } else {
                 long total = (long)B * Hi * Wi * Ci;
                 if (below_tanh)
@@ -724,7 +745,7 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
                 ly.dgrad_pack_len = (size_t)ly.k * ly.k * ly.dgrad_rpad * ly.dgrad_ct.pad;
                 ly.dgrad_pack_off = pack; pack += ly.dgrad_pack_len;
             }
-            if (ly.wgrad_mfma) ly.wgrad_ct = chan_tiling(ly.cout);
+            if (ly.wgrad_mfma) ly.wgrad_ct = wgrad_tiling(ly.cout);
         }
         ch = ly.cout;
         net->layers.push_back(ly);
