@@ -81,7 +81,7 @@ ChanTiling chan_tiling(int channels)
     const ChanTiling a = chan_tiling_w(channels, 16), b = chan_tiling_w(channels, 32);
     return (a.pad / 0.87 < b.pad) ? a : b;
 }
-int wgrad_np(int OT) { return OT <= 4 ? 16 : (OT == 7 ? 9 : 8); }
+int wgrad_np(int OT) { return OT <= 2 ? 16 : (OT == 4 ? 12 : 6); }   // accumulator tiles per wave <= 48
 
 struct Layer {
     int kind;     // mpcnn_kind
@@ -102,7 +102,7 @@ struct Layer {
 struct TilePlan { int PT = 0, Ty = 0, Tx = 0, nty = 0, ntx = 0; size_t lds = 0; bool ok = false; };
 struct WgradPlan {
     bool ok = false;
-    int Ty = 0, Tx = 0, nty = 0, ntx = 0, tiles_total = 0, tiles_per_slab = 0, slabs = 0;
+    int Tx = 0, TxP = 0, nty = 0, ntx = 0, tiles_total = 0, tiles_per_slab = 0, slabs = 0;
     int rtiles_total = 0, rtiles_per_group = 0, groups = 0, NP = 0;
     size_t lds = 0;
     // direct kernel fallback
@@ -120,7 +120,8 @@ struct Geom {
     std::vector<WgradPlan> wgrad;
     size_t staged_off = 0;            // channels-last copy of the image (C0 > 1 only)
     size_t delta_off[2] = {0, 0};     // two delta buffers, each as large as the largest map
-    size_t partial_off = 0, partial_bytes = 0;
+    std::vector<size_t> partial_off;  // per parametrised layer: its slab / block partial sums
+    std::vector<int> partial_n;
     size_t loss_partial_off = 0;
     size_t total = 0;
 };
@@ -248,14 +249,26 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int out_r, int out_c)
 {
     WgradPlan w;
     if (ly.wgrad_mfma) {
-        const int d = ly.dil, k = ly.k;
+        // tile = 4 rows x Tx columns of a residue class; the MFMA work of a tile grows with
+        // Tx rounded up to 4, so take the split of the class width that wastes least
+        const int d = ly.dil, k = ly.k, OT = ly.wgrad_ct.OT;
         const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
-        const size_t pitch = sizeof(float) * (ly.cin | 1);
-        const size_t extra = sizeof(float) * (64 * (16 * ly.wgrad_ct.OT + 1) + 64);
-        if (choose_tile(fh, fw, 64, k, pitch, extra, kWgradLdsCap, &w.Ty, &w.Tx)) {
-            w.nty = ceil_div(fh, w.Ty); w.ntx = ceil_div(fw, w.Tx);
+        const int cq = ceil_div(ly.cin, 4), hh = 4 + k - 1;
+        long best = -1;
+        for (int tx = 1; tx <= fw; ++tx) {
+            const int txp = ceil_div(tx, 4) * 4, hwp = txp + k - 1;
+            const size_t hp = (size_t)((hh * hwp + 4) | 1);
+            const size_t lds = sizeof(float) * (ly.cin * hp + (size_t)4 * txp * (16 * OT + 1));
+            if (hh * hwp * cq > mpcnn::kWgradStageH * 256 || 16 * txp * OT > mpcnn::kWgradStageD * 256 ||
+                lds > kWgradLdsCap)
+                continue;
+            const long cost = (long)ceil_div(fw, tx) * (txp + 6);   // + fixed cost of a tile
+            if (best < 0 || cost <= best) { best = cost; w.Tx = tx; w.TxP = txp; w.lds = lds; }
+        }
+        if (best >= 0) {
+            w.nty = ceil_div(fh, 4); w.ntx = ceil_div(fw, w.Tx);
             w.tiles_total = B * d * d * w.nty * w.ntx;
-            w.NP = wgrad_np(ly.wgrad_ct.OT);
+            w.NP = wgrad_np(OT);
             w.rtiles_total = ceil_div(k * k * ly.cin, 16);
             w.groups = ceil_div(w.rtiles_total, 4 * w.NP);
             w.rtiles_per_group = ceil_div(ceil_div(w.rtiles_total, w.groups), 4) * 4;
@@ -263,7 +276,6 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int out_r, int out_c)
             int target = std::max(1, kNumCU / (w.groups * ly.wgrad_ct.split));
             w.tiles_per_slab = ceil_div(w.tiles_total, target);
             w.slabs = ceil_div(w.tiles_total, w.tiles_per_slab);
-            w.lds = (size_t)(w.Ty + k - 1) * (w.Tx + k - 1) * pitch + extra;
             w.ok = true;
             return w;
         }
@@ -284,7 +296,8 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
     g->rows.assign(L, 0); g->cols.assign(L, 0);
     g->act_off.assign(L, 0); g->code_off.assign(L, 0);
     g->fwd.assign(L, TilePlan()); g->dgrad.assign(L, TilePlan()); g->wgrad.assign(L, WgradPlan());
-    size_t off = 0, max_act = 0, max_partial = 0;
+    g->partial_off.assign(L, 0); g->partial_n.assign(L, 0);
+    size_t off = 0, max_act = 0;
     if (net->in_ch > 1) {
         g->staged_off = off;
         off = align_up(off + sizeof(float) * (size_t)B * H * W * net->in_ch);
@@ -302,14 +315,13 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         if (ly.kind == MPCNN_MP) continue;
         if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.k, ly.fwd_rpad, ly.fwd_ct);
         if (training && ly.class_fused) {
-            max_partial = std::max(max_partial, sizeof(float) * class_blocks((long)B * r * c) * ly.p_len);
+            g->partial_n[l] = class_blocks((long)B * r * c);
         } else if (training) {
             if (ly.dgrad_mfma && l > 0)
                 g->dgrad[l] = plan_conv_tiles(B, in_r, in_c, ly.dil, ly.k, ly.dgrad_rpad, ly.dgrad_ct);
             g->wgrad[l] = plan_wgrad(ly, B, r, c);
             const WgradPlan& w = g->wgrad[l];
-            size_t n = w.ok ? (size_t)w.slabs : (size_t)w.chunks;
-            max_partial = std::max(max_partial, sizeof(float) * n * ly.p_len);
+            g->partial_n[l] = w.ok ? w.slabs : w.chunks;
         }
     }
     if (r != H - net->patch + 1 || c != W - net->patch + 1) return false;
@@ -326,7 +338,11 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         }
         g->delta_off[0] = off; off = align_up(off + max_act);
         g->delta_off[1] = off; off = align_up(off + max_act);
-        g->partial_off = off; g->partial_bytes = max_partial; off = align_up(off + max_partial);
+        for (size_t l = 0; l < L; ++l) {
+            if (!g->partial_n[l]) continue;
+            g->partial_off[l] = off;
+            off = align_up(off + sizeof(float) * (size_t)g->partial_n[l] * net->layers[l].p_len);
+        }
     } else {
         // forward only: layers alternate between two buffers, nothing is kept
         size_t buf[2];
@@ -370,9 +386,9 @@ void launch_wgrad_mfma(const mpcnn::WgradArgs& a, int OT, dim3 grid, size_t lds,
     switch (OT) {
     case 1: return launch_wgrad_inst<16, 1>(a, grid, lds, st);
     case 2: return launch_wgrad_inst<16, 2>(a, grid, lds, st);
-    case 4: return launch_wgrad_inst<16, 4>(a, grid, lds, st);
-    case 7: return launch_wgrad_inst<9, 7>(a, grid, lds, st);
-    case 8: return launch_wgrad_inst<8, 8>(a, grid, lds, st);
+    case 4: return launch_wgrad_inst<12, 4>(a, grid, lds, st);
+    case 7: return launch_wgrad_inst<6, 7>(a, grid, lds, st);
+    case 8: return launch_wgrad_inst<6, 8>(a, grid, lds, st);
     }
 }
 // Kernels that may ask for more than 64 KiB of dynamic LDS must say so once.
@@ -381,8 +397,8 @@ mpcnn_status set_lds_attrs()
 #define ATTR(fn) HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fn), \
                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024))
     ATTR((mpcnn::wgrad_mfma_kernel<16, 1>)); ATTR((mpcnn::wgrad_mfma_kernel<16, 2>));
-    ATTR((mpcnn::wgrad_mfma_kernel<16, 4>)); ATTR((mpcnn::wgrad_mfma_kernel<9, 7>));
-    ATTR((mpcnn::wgrad_mfma_kernel<8, 8>));
+    ATTR((mpcnn::wgrad_mfma_kernel<12, 4>)); ATTR((mpcnn::wgrad_mfma_kernel<6, 7>));
+    ATTR((mpcnn::wgrad_mfma_kernel<6, 8>));
 #undef ATTR
     return MPCNN_OK;
 }
@@ -465,7 +481,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             const long M = (long)B * Ho * Wo;
             ClassArgs a{};
             a.h = in; a.Wk = net->d_params + ly.p_off; a.probs = probs;
-            a.labels = labels; a.pixw = pixw; a.dH = dZ; a.partial = (float*)(ws + g.partial_off);
+            a.labels = labels; a.pixw = pixw; a.dH = dZ; a.partial = (float*)(ws + g.partial_off[l]);
             a.loss_partial = want_loss ? lp : nullptr;
             a.B = B; a.Ho = Ho; a.Wo = Wo; a.H = g.H; a.W = g.W; a.ctr = (net->patch - 1) / 2;
             a.K = Ci; a.tanh_below = (l > 0 && net->layers[l - 1].tanh_out) ? 1 : 0;
@@ -475,14 +491,9 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             const double bytes = 4.0 * (n_in * (train ? 2.0 : 1.0) + n_out);
             LAUNCH("class_layer", l, train ? 4 : 3, flops, bytes,
                    launch_class(a, ly.cout, Ci <= 128 ? 2 : 4, train, blocks, st));
-            if (train) {
-                LAUNCH("reduce_rows", l, 0, 0, 4.0 * ly.p_len * (blocks + 1.0),
-                       reduce_rows_kernel<<<(unsigned)((ly.p_len + 63) / 64), 256, 0, st>>>(
-                           a.partial, net->d_grads + ly.p_off, (long)ly.p_len, blocks));
-                if (want_loss)
-                    LAUNCH("loss_tree", l, 0, 0, 8.0 * blocks,
-                           loss_tree_kernel<<<1, 256, 0, st>>>(lp, blocks, loss_dev));
-            }
+            if (train && want_loss)
+                LAUNCH("loss_tree", l, 0, 0, 8.0 * blocks,
+                       loss_tree_kernel<<<1, 256, 0, st>>>(lp, blocks, loss_dev));
         } else {
             const float* Wk = net->d_params + ly.p_off;
             const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k * Ci;
@@ -535,7 +546,6 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
     const size_t L = net->layers.size();
     const float* in0 = net->in_ch > 1 ? (const float*)(ws + g.staged_off) : image;
     float* dbuf[2] = {(float*)(ws + g.delta_off[0]), (float*)(ws + g.delta_off[1])};
-    float* partial = (float*)(ws + g.partial_off);
     int cur = 0;  // dbuf[cur] holds dL/d(pre-activation) of layer l's output (dL/d(output) for MP)
     // a fused class layer has already done its own backward and left the delta below it
     for (size_t li = net->layers[L - 1].class_fused ? L - 1 : L; li-- > 0;) {
@@ -574,30 +584,25 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
             const int wstep = (li == L - 1) ? 4 : 5, dstep = (li == L - 1) ? 4 : 6;
             // parameter gradient: partial sums over slabs of positions, then a fixed-order sum
             const WgradPlan& wp = g.wgrad[li];
-            int n_partial;
+            float* partial = (float*)(ws + g.partial_off[li]);
             if (wp.ok) {
                 WgradArgs a{};
                 a.in = A; a.dY = dY; a.partial = partial;
                 a.B = B; a.Hi = Hi; a.Wi = Wi; a.Ci = Ci;
                 a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout; a.k = ly.k; a.d = ly.dil;
-                a.Ty = wp.Ty; a.Tx = wp.Tx; a.nty = wp.nty; a.ntx = wp.ntx;
+                a.Tx = wp.Tx; a.TxP = wp.TxP; a.nty = wp.nty; a.ntx = wp.ntx;
                 a.tiles_total = wp.tiles_total; a.tiles_per_slab = wp.tiles_per_slab;
                 a.rtiles_total = wp.rtiles_total; a.rtiles_per_group = wp.rtiles_per_group;
                 dim3 grid((unsigned)wp.slabs, (unsigned)wp.groups, (unsigned)ly.wgrad_ct.split);
                 LAUNCH("wgrad_mfma", li, wstep, flops, 4.0 * (n_in + n_out + ly.p_len),
                        launch_wgrad_mfma(a, ly.wgrad_ct.OT, grid, wp.lds, st));
-                n_partial = wp.slabs;
             } else {
                 dim3 grid((unsigned)((ly.p_len + 255) / 256), (unsigned)wp.chunks);
                 LAUNCH("wgrad_direct", li, wstep, flops, 4.0 * (n_in + n_out + ly.p_len),
                        conv_wgrad_direct_kernel<<<grid, 256, 0, st>>>(A, dY, partial, B, Hi, Wi, Ci, Ho,
                                                                       Wo, ly.cout, ly.k, ly.dil,
                                                                       wp.rows_per_chunk));
-                n_partial = wp.chunks;
             }
-            LAUNCH("reduce_rows", li, 0, 0, 4.0 * ly.p_len * (n_partial + 1.0),
-                   reduce_rows_kernel<<<(unsigned)((ly.p_len + 63) / 64), 256, 0, st>>>(
-                       partial, net->d_grads + ly.p_off, (long)ly.p_len, n_partial));
             if (li == 0) break;  // the image needs no gradient
             const float* Wk = net->d_params + ly.p_off;
             const double dbytes = 4.0 * (n_in * (below_tanh ? 2.0 : 1.0) + n_out + ly.p_len);
@@ -628,6 +633,21 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
         }
         cur ^= 1;
     }
+    // one launch adds the partial sums of every layer in a fixed order (Alg. 2)
+    ReduceArgs ra{};
+    double rbytes = 0;
+    for (size_t l = 0; l < L; ++l) {
+        if (!g.partial_n[l] || ra.n_seg >= kMaxReduceSegs) continue;
+        const Layer& ly = net->layers[l];
+        ReduceSeg& sg = ra.seg[ra.n_seg++];
+        sg.partial = (const float*)(ws + g.partial_off[l]);
+        sg.out = net->d_grads + ly.p_off;
+        sg.len = (int)ly.p_len; sg.n = g.partial_n[l];
+        sg.block0 = ra.total_blocks;
+        ra.total_blocks += (int)((ly.p_len + 63) / 64);
+        rbytes += 4.0 * ly.p_len * (sg.n + 1.0);
+    }
+    LAUNCH("reduce_all", -1, 0, 0, rbytes, reduce_all_kernel<<<(unsigned)ra.total_blocks, 256, 0, st>>>(ra));
     HIP_TRY(hipGetLastError());
     return MPCNN_OK;
 }
@@ -687,7 +707,7 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
 {
     if (!layers || !out) return fail(MPCNN_EINVAL, "null argument");
     *out = nullptr;
-    if (n_layers < 1 || n_layers > 64 || in_channels < 1 || patch < 1)
+    if (n_layers < 1 || n_layers > 48 || in_channels < 1 || patch < 1)
         return fail(MPCNN_EINVAL, "n_layers=%d in_channels=%d patch=%d", n_layers, in_channels, patch);
     if (dtype != MPCNN_F32) {
         if (dtype == MPCNN_BF16) return fail(MPCNN_EUNSUPPORTED, "bf16 storage is not built yet");
