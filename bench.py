@@ -24,6 +24,19 @@ if ROOT not in sys.path:
 PEAK = {"mfma": (157.3, "TFLOP/s"), "hbm": (8000.0, "GB/s")}   # MI355X: fp32 MFMA, HBM3E
 
 
+def read_traffic(path, kernel):
+    """HBM bytes per launch of `kernel` as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (two runs, scaled by a copy of known size); None if no such measurement is committed."""
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 2 and f[0] == kernel:
+                return float(f[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -32,6 +45,9 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload index (default: the metric's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain device copy of known size (to scale rocprofv3's FETCH_SIZE / "
+                         "WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not "
@@ -41,6 +57,17 @@ def main():
     import numpy as np
     import torch
     from paper_1302_1690_amd import mpcnn, workloads as wl
+
+    if args.copy_calibration:
+        n = 256 * 1024 * 1024 // 4                    # 256 MiB read + 256 MiB written per copy
+        src = torch.rand(n, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 4 * n, "copy_bytes_written": 4 * n, "copies": 5}))
+        return 0
 
     cfg = wl.CONFIGS[args.config]
     img, lab = wl.make_inputs(cfg)
@@ -97,8 +124,9 @@ def main():
     peak, unit = PEAK[bound]
     work = dom["flops"] if bound == "mfma" else dom["bytes"]
     achieved = work / (dom["ms"] * 1e-3) / (1e12 if bound == "mfma" else 1e9)
+    traffic = read_traffic(os.path.join(ROOT, "profiles", "traffic_%s.txt" % cfg.name), dom_name)
     roofline = {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": None, "kernel": dom_name,
+                "frac": round(achieved / peak, 4), "traffic": traffic, "kernel": dom_name,
                 "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
                 "launches_per_step": dom["launches"] // args.steps,
                 "share_of_step": round(dom["ms"] / args.steps / ms_per_step, 3)}
