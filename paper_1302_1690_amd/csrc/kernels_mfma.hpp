@@ -31,8 +31,8 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // about 1e-7; saturates correctly (exp -> inf gives 1, exp -> 0 gives -1).
 __device__ __forceinline__ float fast_tanh(float x)
 {
-    const float e = __expf(2.f * x);
-    return 1.f - 2.f * __frcp_rn(e + 1.f);
+    const float e = __builtin_amdgcn_exp2f(2.885390081777927f * x);   // e^(2x) = 2^(2x log2 e)
+    return fmaf(-2.f, __builtin_amdgcn_rcpf(e + 1.f), 1.f);
 }
 
 enum ConvMode { kFwdTanh = 0, kFwdLinear = 1, kDgradTanh = 2, kDgradPlain = 3 };
@@ -91,20 +91,21 @@ __device__ __forceinline__ typename MfmaAcc<W>::type mfma_f32(float a, float b, 
 }
 
 // Forward / data gradient of one dilated convolution as an implicit GEMM.
-// Workgroup = 256 threads = 4 waves; tile = W*PT positions of one residue class x W*OT
-// output channels (blockIdx.y selects the group of OT channel tiles).  All four waves hold
-// the full tile in accumulators and each sums a quarter of the reduction steps; the four
-// partial tiles meet in LDS, where all 256 threads add them in wave order, apply the
-// epilogue and store.  Summation order is the same for every position, so equal inputs
+// Workgroup = NW waves (4 or 8); tile = W*PT positions of one residue class x W*OT output
+// channels (blockIdx.y selects the group of OT channel tiles).  All waves hold the full
+// tile in accumulators and each sums 1/NW of the reduction steps; the partial tiles meet in
+// LDS, where all threads add them in wave order, apply the epilogue and store.  With 8
+// waves one workgroup fills a CU (two waves per SIMD that are always in the same phase).  Summation order is the same for every position, so equal inputs
 // give bit-equal outputs (exact pooling ties stay exact).
-template <int W, int OT, int PT>
-__global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
+template <int W, int OT, int PT, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
 {
     constexpr int G = 64 / W;          // lane groups = contraction index of one MFMA
     constexpr int QT = W / 4;          // 4-channel quads per output tile
     constexpr int NQ = W * W / 256;    // quads one lane holds of one result tile
     constexpr int ITEMS = OT * W * QT; // (position, quad) items of one epilogue round
-    constexpr int NIT = (ITEMS + 255) / 256;
+    constexpr int NT = 64 * NW;        // threads per workgroup
+    constexpr int NIT = (ITEMS + NT - 1) / NT;
     typedef typename MfmaAcc<W>::type acc_t;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -133,12 +134,12 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
     {
         const int total = hh * hw * cq;
         constexpr int U = 8;
-        for (int base = tid; base < total; base += 256 * U) {
+        for (int base = tid; base < total; base += NT * U) {
             v4f v[U];
             int dst[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int it = base + 256 * u;
+                const int it = base + NT * u;
                 v[u] = (v4f){0.f, 0.f, 0.f, 0.f};
                 dst[u] = -1;
                 if (it < total) {
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
 #pragma unroll
     for (int it = 0; it < NIT; ++it) bias4[it] = (v4f){0.f, 0.f, 0.f, 0.f};
     if (a.mode <= kFwdLinear) {
-        constexpr int SLOTS_ = W * QT, TPS_ = 256 / SLOTS_ > 0 ? 256 / SLOTS_ : 1;
+        constexpr int SLOTS_ = W * QT, TPS_ = NT / SLOTS_ > 0 ? NT / SLOTS_ : 1;
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int oc = W * (ot0 + tid / SLOTS_ + TPS_ * it) + 4 * ((tid % SLOTS_) % QT);
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
 
     const int nch = a.CrPad / (4 * G);
     const int steps = a.k * a.k * nch;
-    const int t0 = (steps * wave) >> 2, t1 = (steps * (wave + 1)) >> 2;
+    const int t0 = steps * wave / NW, t1 = steps * (wave + 1) / NW;
     const int lane_w = lg * a.CoPad + W * ot0 + lt;   // this lane's offset inside one step of the pack
 
     // MFMA results kept in AccVGPRs: an (empty) asm operand in an AccVGPR makes the compiler
@@ -251,7 +252,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
     // one (position, quad) slot per group of 256 items and walks the output tiles.
     constexpr int WP = W + 1;
     constexpr int SLOTS = W * QT;              // (position, quad) slots of one output tile
-    constexpr int TPS = 256 / SLOTS > 0 ? 256 / SLOTS : 1;   // output tiles covered by 256 threads at once
+    constexpr int TPS = NT / SLOTS > 0 ? NT / SLOTS : 1;   // output tiles covered by the workgroup at once
     const int slot = tid % SLOTS, osub = tid / SLOTS;
     const int ei = slot / QT, eq = slot % QT;  // position in tile, quad
 #pragma unroll
@@ -269,23 +270,34 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
         const int fy = ty0 + ty, fx = tx0 + tx;
         const bool pos_ok = ty < a.Ty && fy < fh && fx < fw;
         const long pos_off = (((long)b * a.Ho + (fy * a.d + ry)) * a.Wo + (fx * a.d + rx)) * a.Co;
+        // all LDS reads (and, for the data gradient, the activation loads) of this thread's
+        // items are issued before the first is used, so their latencies overlap
+        v4f part[NIT][NW], yv[NIT];
+        bool live[NIT];
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int o = osub + TPS * it;
             const int oc = W * (ot0 + o) + 4 * eq;
-            if (o >= OT || !pos_ok || oc >= a.Co) continue;
+            live[it] = o < OT && pos_ok && oc < a.Co;
+            const int oo = o < OT ? o : 0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) part[it][w] = lds4[((w * OT + oo) * QT + eq) * WP + ei];
+            yv[it] = (v4f){0.f, 0.f, 0.f, 0.f};
+            if (a.mode == kDgradTanh && live[it]) {
+                const long off = pos_off + oc;
+                if ((a.Co & 3) == 0) yv[it] = *reinterpret_cast<const v4f*>(a.act + off);
+                else for (int z = 0; z < 4; ++z) if (oc + z < a.Co) yv[it][z] = a.act[off + z];
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            if (!live[it]) continue;
+            const int oc = W * (ot0 + osub + TPS * it) + 4 * eq;
             const long off = pos_off + oc;
             const int nv = a.Co - oc < 4 ? a.Co - oc : 4;
-            const bool vec = nv == 4 && (a.Co & 3) == 0;
-            v4f y = {0.f, 0.f, 0.f, 0.f};
-            if (a.mode == kDgradTanh) {
-                if (vec) y = *reinterpret_cast<const v4f*>(a.act + off);
-                else for (int z = 0; z < nv; ++z) y[z] = a.act[off + z];
-            }
-            v4f s = lds4[((0 * OT + o) * QT + eq) * WP + ei];
-            s += lds4[((1 * OT + o) * QT + eq) * WP + ei];
-            s += lds4[((2 * OT + o) * QT + eq) * WP + ei];
-            s += lds4[((3 * OT + o) * QT + eq) * WP + ei];
+            v4f s = part[it][0];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) s += part[it][w];   // fixed wave order
             if (a.mode == kFwdTanh) {
 #pragma unroll
                 for (int z = 0; z < 4; ++z) s[z] = fast_tanh(s[z] + bias4[it][z]);
@@ -293,9 +305,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
                 s += bias4[it];
             } else if (a.mode == kDgradTanh) {
 #pragma unroll
-                for (int z = 0; z < 4; ++z) s[z] *= 1.f - y[z] * y[z];
+                for (int z = 0; z < 4; ++z) s[z] *= 1.f - yv[it][z] * yv[it][z];
             }
-            if (vec) *reinterpret_cast<v4f*>(a.out + off) = s;
+            if (nv == 4 && (a.Co & 3) == 0) *reinterpret_cast<v4f*>(a.out + off) = s;
             else for (int z = 0; z < nv; ++z) a.out[off + z] = s[z];
         }
     }

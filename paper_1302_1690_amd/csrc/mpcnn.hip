@@ -99,7 +99,7 @@ struct Layer {
     size_t fwd_pack_off = 0, fwd_pack_len = 0, dgrad_pack_off = 0, dgrad_pack_len = 0;
 };
 
-struct TilePlan { int PT = 0, Ty = 0, Tx = 0, nty = 0, ntx = 0; size_t lds = 0; bool ok = false; };
+struct TilePlan { int PT = 0, NW = 4, Ty = 0, Tx = 0, nty = 0, ntx = 0; size_t lds = 0; bool ok = false; };
 struct WgradPlan {
     bool ok = false;
     int Tx = 0, TxP = 0, nty = 0, ntx = 0, tiles_total = 0, tiles_per_slab = 0, slabs = 0;
@@ -229,18 +229,29 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, co
     const int regs_per_tile = ct.W * ct.W / 64;
     for (int PT : {64 / ct.W, 128 / ct.W}) {            // 64 or 128 positions per workgroup
         if (ct.OT * PT * regs_per_tile > (ct.W == 16 ? 64 : 128)) continue;  // accumulator registers per lane
-        TilePlan p;
-        p.PT = PT;
-        if (!choose_tile(fh, fw, ct.W * PT, k, pitch, 0, kConvLdsCap, &p.Ty, &p.Tx)) continue;
-        p.nty = ceil_div(fh, p.Ty); p.ntx = ceil_div(fw, p.Tx);
-        size_t halo = (size_t)(p.Ty + k - 1) * (p.Tx + k - 1) * pitch;
-        p.lds = std::max(halo, (size_t)4 * ct.OT * (ct.W / 4) * (ct.W + 1) * 4 * sizeof(float));
-        p.ok = true;
-        // rounds of workgroups over the chip (two per CU) times the work of one workgroup
-        double wgs = (double)B * d * d * p.nty * p.ntx * ct.split;
-        double rounds = std::ceil(wgs / (2.0 * kNumCU));
-        double cost = rounds * (ct.W * PT / 16 + 1.0);
-        if (!best.ok || cost < best_cost) { best = p; best_cost = cost; }
+        for (int NW : {4, 8}) {
+            TilePlan p;
+            p.PT = PT; p.NW = NW;
+            if (!choose_tile(fh, fw, ct.W * PT, k, pitch, 0, kConvLdsCap, &p.Ty, &p.Tx)) continue;
+            p.nty = ceil_div(fh, p.Ty); p.ntx = ceil_div(fw, p.Tx);
+            size_t halo = (size_t)(p.Ty + k - 1) * (p.Tx + k - 1) * pitch;
+            size_t part = (size_t)NW * ct.OT * (ct.W / 4) * (ct.W + 1) * 4 * sizeof(float);
+            p.lds = std::max(halo, part);
+            if (p.lds > 150 * 1024) continue;
+            if (NW == 8 && k * k * (rpad / (256 / ct.W)) < 16) continue;   // too few reduction steps to split 8 ways
+            p.ok = true;
+            // Measured: two co-resident 4-wave workgroups with large tiles (LDS allows no more than
+            // two) only overlap well once their phases have drifted apart, i.e. over many rounds;
+            // for a few rounds one 8-wave workgroup per CU is faster.  Small tiles: 4 waves.
+            const double wgs = (double)B * d * d * p.nty * p.ntx * ct.split;
+            const double per_cu = wgs / kNumCU;
+            const int steps = k * k * (rpad / (256 / ct.W));
+            const bool want8 = ct.W == 32 && ct.OT * PT >= 4 && steps >= 64 && per_cu < 8;
+            if ((NW == 8) != want8) continue;
+            const double rounds = NW == 8 ? std::ceil(per_cu) : std::ceil(per_cu / 2);
+            const double cost = rounds * (ct.W * PT / 16 + 1.0);
+            if (!best.ok || cost < best_cost) { best = p; best_cost = cost; }
+        }
     }
     return best;
 }
@@ -362,15 +373,20 @@ inline int grid_for(long total, int block = 256, int cap = 1 << 20)
 }
 
 // ------------------------------------------------------------------ MFMA launches
-template <int W, int OT, int PT>
+template <int W, int OT, int PT, int NW>
 void launch_conv_inst(const mpcnn::ConvArgs& a, dim3 grid, size_t lds, hipStream_t st)
 {
-    mpcnn::conv_mfma_kernel<W, OT, PT><<<grid, 256, lds, st>>>(a);
+    mpcnn::conv_mfma_kernel<W, OT, PT, NW><<<grid, 64 * NW, lds, st>>>(a);
 }
-bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, int PT, dim3 grid, size_t lds,
+bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, const TilePlan& tp, dim3 grid,
                       hipStream_t st)
 {
-#define CASE(w, o, p) if (ct.W == w && ct.OT == o && PT == p) { launch_conv_inst<w, o, p>(a, grid, lds, st); return true; }
+#define CASE(w, o, p)                                                                         \
+    if (ct.W == w && ct.OT == o && tp.PT == p) {                                                \
+        if (tp.NW == 8) launch_conv_inst<w, o, p, 8>(a, grid, tp.lds, st);                      \
+        else launch_conv_inst<w, o, p, 4>(a, grid, tp.lds, st);                                 \
+        return true;                                                                          \
+    }
     CASE(16, 1, 4) CASE(16, 2, 4) CASE(16, 4, 4) CASE(16, 1, 8) CASE(16, 2, 8)
     CASE(32, 1, 2) CASE(32, 2, 2) CASE(32, 4, 2) CASE(32, 1, 4) CASE(32, 2, 4)
 #undef CASE
@@ -396,6 +412,10 @@ mpcnn_status set_lds_attrs()
 {
 #define ATTR(fn) HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fn), \
                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024))
+    ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 4>)); ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 8>));
+    ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 8>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 8>));
+    ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 4>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 4, 8>));
+    ATTR((mpcnn::conv_mfma_kernel<16, 4, 4, 8>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 2, 8>));
     ATTR((mpcnn::wgrad_mfma_kernel<16, 1>)); ATTR((mpcnn::wgrad_mfma_kernel<16, 2>));
     ATTR((mpcnn::wgrad_mfma_kernel<12, 4>)); ATTR((mpcnn::wgrad_mfma_kernel<6, 7>));
     ATTR((mpcnn::wgrad_mfma_kernel<6, 8>));
@@ -511,7 +531,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 a.mode = ly.tanh_out ? kFwdTanh : kFwdLinear;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
                 LAUNCH("conv_fwd_mfma", l, step, flops, bytes,
-                       launch_conv_mfma(a, ly.fwd_ct, tp.PT, grid, tp.lds, st));
+                       launch_conv_mfma(a, ly.fwd_ct, tp, grid, st));
             } else {
                 long total = (long)B * Ho * Wo;
                 dim3 grid((unsigned)((total + 255) / 256), (unsigned)ceil_div(ly.cout, 16));
@@ -618,7 +638,7 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.mode = below_tanh ? kDgradTanh : kDgradPlain;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.dgrad_ct.split);
                 LAUNCH("conv_dgrad_mfma", li, dstep, flops, dbytes,
-                       launch_conv_mfma(a, ly.dgrad_ct, tp.PT, grid, tp.lds, st));
+                       launch_conv_mfma(a, ly.dgrad_ct, tp, grid, st));
             } else {
                 long total = (long)B * Hi * Wi * Ci;
                 if (below_tanh)
