@@ -1,5 +1,5 @@
-// Matrix-core (MFMA, fp32) kernels for the dilated convolutions of the whole-image pass:
-// forward and data gradient share one kernel, the weight gradient has its own.
+// Matrix-core (MFMA, fp32) kernel for the dilated convolutions of the whole-image pass:
+// forward and data gradient share it; the weight gradient has its own file.
 //
 // Tiling rule.  A layer whose taps are d elements apart never mixes the d*d residue
 // classes (y mod d, x mod d) of its dense map - each class is one "fragment" of the
@@ -311,291 +311,6 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
             else for (int z = 0; z < nv; ++z) a.out[off + z] = s[z];
         }
     }
-}
-
-struct WgradArgs {
-    const float* in;     // [B][Hi][Wi][Ci]  layer input (activations)
-    const float* dY;     // [B][Ho][Wo][Co]  delta w.r.t. the layer's pre-activation
-    float* partial;      // [slabs][(k*k*Ci + 1) * Co]
-    int B, Hi, Wi, Ci;
-    int Ho, Wo, Co;
-    int k, d;
-    int Tx, TxP;           // tile = 4 rows x Tx columns of one residue class; TxP = Tx rounded up to 4
-    int nty, ntx;
-    int tiles_total, tiles_per_slab;
-    int rtiles_total;      // ceil(k*k*Ci / 16) tiles of 16 gradient rows, row = tap*Ci + c
-    int rtiles_per_group;  // row tiles handled by one blockIdx.y
-};
-
-constexpr int kWgradStageH = 8;   // 128-bit items of the input halo one thread stages per tile
-constexpr int kWgradStageD = 8;   // ... of the delta tile
-
-// Weight gradient dW[tap][c][o] = sum over positions of in[pos + tap][c] * dY[pos][o]
-// (Alg. 2: the same gradient function applied to every fragment, results summed).
-// MFMA rows = 16 consecutive gradient rows (tap, c) in parameter order, columns = 16 output
-// channels, contraction over positions: one v_mfma_f32_16x16x4_f32 takes one column of a
-// 4-row tile (lane group g = tile row g).  blockIdx.x = slab of position tiles (partial
-// sums, added later in slab order), blockIdx.y = group of row tiles, blockIdx.z = group of
-// OT output tiles.  Row tiles are dealt round-robin to the 4 waves; each wave keeps NP x OT
-// accumulator tiles across its whole slab.
-// LDS: the halo is stored channel-major, [c][halo row][halo col], and the delta tile as
-// [tile row][col][o], so that a lane's operand addresses for successive columns differ by
-// compile-time constants: the inner loop holds no address arithmetic.  The next tile is
-// fetched from global memory into registers while the current one is multiplied.
-template <int NP, int OT>
-__global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
-{
-    constexpr int HL = kWgradStageH, DL = kWgradStageD;
-    constexpr int Ds = 16 * OT + 1;    // delta tile pitch per position (floats, odd)
-    extern __shared__ __attribute__((aligned(16))) float lds[];
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int li = lane & 15, lg = lane >> 4;
-    const int hwp = a.TxP + a.k - 1;            // halo row pitch (columns incl. the padding columns)
-    const int hh = 4 + a.k - 1;
-    const int HP = (hh * hwp + 4) | 1;          // channel pitch of the halo (floats, odd, + slack)
-    float* halo = lds;                          // [Ci][HP]
-    float* dtile = halo + a.Ci * HP;            // [4][TxP][Ds]
-
-    const int rows_total = a.k * a.k * a.Ci;
-    const int ot0 = blockIdx.z * OT;
-    const int rt0 = blockIdx.y * a.rtiles_per_group;
-    int rend = rt0 + a.rtiles_per_group;
-    if (rend > a.rtiles_total) rend = a.rtiles_total;
-    // this wave's row tiles: rt0 + wave + 4*p; this lane feeds row 16*tile + li of each
-    int aoff[NP];   // float offset in `halo` of that row's (tap, c) for this lane's tile row, column 0
-    int np = 0;
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-        const int q = rt0 + wave + 4 * p;
-        aoff[p] = lg * hwp;
-        if (q < rend) {
-            np = p + 1;
-            const int row = 16 * q + li;
-            if (row < rows_total) {
-                const int tap = row / a.Ci, c = row - tap * a.Ci;
-                const int ta = tap / a.k, tb = tap - ta * a.k;
-                aoff[p] = c * HP + (lg + ta) * hwp + tb;
-            }
-        }
-    }
-    np = __builtin_amdgcn_readfirstlane(np);
-    const float* bptr = dtile + (lg * a.TxP) * Ds + li;   // this lane's delta operand, column 0, tile 0
-
-    v4f acc[NP][OT];
-#pragma unroll
-    for (int p = 0; p < NP; ++p)
-#pragma unroll
-        for (int o = 0; o < OT; ++o) acc[p][o] = (v4f){0.f, 0.f, 0.f, 0.f};
-    float bsum[OT];
-#pragma unroll
-    for (int o = 0; o < OT; ++o) bsum[o] = 0.f;
-
-    const int tile_begin = blockIdx.x * a.tiles_per_slab;
-    int tile_end = tile_begin + a.tiles_per_slab;
-    if (tile_end > a.tiles_total) tile_end = a.tiles_total;
-    const int cq = (a.Ci + 3) >> 2;
-    const int h_items = hh * hwp * cq, d_items = 4 * a.TxP * 4 * OT;
-    const bool vec_in = (a.Ci & 3) == 0, vec_dy = (a.Co & 3) == 0;
-
-    // ---- staging: global -> registers (per tile), registers -> LDS.  Which halo / delta item a
-    // thread stages never changes, so its coordinates are decoded once (packed, -1 = none);
-    // per tile only the global address is formed.  Halo coordinates outside the input are
-    // clamped (any finite value will do there: the matching deltas are zero).
-    int hpk[HL], dpk[DL];
-#pragma unroll
-    for (int u = 0; u < HL; ++u) {
-        const int it = tid + 256 * u;
-        hpk[u] = -1;
-        if (it < h_items) {
-            const int pos = it / cq, q = it - pos * cq;
-            const int ha = pos / hwp, hb = pos - ha * hwp;
-            hpk[u] = (q << 16) | (ha << 8) | hb;
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < DL; ++u) {
-        const int it = tid + 256 * u;
-        dpk[u] = -1;
-        if (it < d_items) {
-            const int m = it / (4 * OT), q = it - m * (4 * OT);
-            const int ty = m / a.TxP, tx = m - ty * a.TxP;
-            dpk[u] = (q << 16) | (ty << 8) | tx;
-        }
-    }
-    v4f hr[HL], dr[DL];
-    auto gload = [&](int tile) {
-        int bid = tile;
-        const int txi = bid % a.ntx; bid /= a.ntx;
-        const int tyi = bid % a.nty; bid /= a.nty;
-        const int rx = bid % a.d; bid /= a.d;
-        const int ry = bid % a.d;
-        const int b = bid / a.d;
-        const int fh = ry < a.Ho ? (a.Ho - ry + a.d - 1) / a.d : 0;
-        const int fw = rx < a.Wo ? (a.Wo - rx + a.d - 1) / a.d : 0;
-        const int ty0 = tyi * 4, tx0 = txi * a.Tx;
-        const float* in_b = a.in + (long)b * a.Hi * a.Wi * a.Ci;
-        const float* dy_b = a.dY + (long)b * a.Ho * a.Wo * a.Co;
-#pragma unroll
-        for (int u = 0; u < HL; ++u) {
-            hr[u] = (v4f){0.f, 0.f, 0.f, 0.f};
-            if (hpk[u] >= 0) {
-                const int q = hpk[u] >> 16, ha = (hpk[u] >> 8) & 255, hb = hpk[u] & 255;
-                int iy = (ty0 + ha) * a.d + ry, ix = (tx0 + hb) * a.d + rx;
-                iy = iy < a.Hi ? iy : a.Hi - 1;
-                ix = ix < a.Wi ? ix : a.Wi - 1;
-                const float* src = in_b + ((long)iy * a.Wi + ix) * a.Ci + 4 * q;
-                if (vec_in) hr[u] = *reinterpret_cast<const v4f*>(src);
-                else for (int z = 0; z < 4; ++z) if (4 * q + z < a.Ci) hr[u][z] = src[z];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < DL; ++u) {
-            dr[u] = (v4f){0.f, 0.f, 0.f, 0.f};
-            if (dpk[u] >= 0) {
-                const int q = dpk[u] >> 16, ty = (dpk[u] >> 8) & 255, tx = dpk[u] & 255;
-                const int fy = ty0 + ty, fx = tx0 + tx;
-                const int oc = 16 * ot0 + 4 * q;
-                if (tx < a.Tx && fy < fh && fx < fw && oc < a.Co) {
-                    const float* src = dy_b + ((long)(fy * a.d + ry) * a.Wo + (fx * a.d + rx)) * a.Co + oc;
-                    if (vec_dy) dr[u] = *reinterpret_cast<const v4f*>(src);
-                    else for (int z = 0; z < 4; ++z) if (oc + z < a.Co) dr[u][z] = src[z];
-                }
-            }
-        }
-    };
-    auto lstore = [&]() {
-#pragma unroll
-        for (int u = 0; u < HL; ++u) {
-            if (hpk[u] >= 0) {
-                const int q = hpk[u] >> 16, ha = (hpk[u] >> 8) & 255, hb = hpk[u] & 255;
-                float* dst = halo + (4 * q) * HP + ha * hwp + hb;
-#pragma unroll
-                for (int z = 0; z < 4; ++z)
-                    if (4 * q + z < a.Ci) dst[z * HP] = hr[u][z];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < DL; ++u) {
-            if (dpk[u] >= 0) {
-                const int q = dpk[u] >> 16, ty = (dpk[u] >> 8) & 255, tx = dpk[u] & 255;
-                float* dst = dtile + (ty * a.TxP + tx) * Ds + 4 * q;
-                dst[0] = dr[u][0]; dst[1] = dr[u][1]; dst[2] = dr[u][2]; dst[3] = dr[u][3];
-            }
-        }
-    };
-
-    if (tile_begin < tile_end) gload(tile_begin);
-    for (int tile = tile_begin; tile < tile_end; ++tile) {
-        __syncthreads();   // previous tile fully consumed
-        lstore();
-        __syncthreads();
-        if (tile + 1 < tile_end) gload(tile + 1);   // in flight during the MFMAs below
-        // four columns per round; all operand addresses are lane constants + immediates
-        for (int c0 = 0; c0 < a.TxP; c0 += 4) {
-            float bop[OT][4];
-#pragma unroll
-            for (int o = 0; o < OT; ++o)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    bop[o][j] = bptr[(c0 + j) * Ds + 16 * o];
-                    bsum[o] += bop[o][j];
-                }
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                if (p < np) {
-                    const float* ap = halo + aoff[p] + c0;
-                    const float av[4] = {ap[0], ap[1], ap[2], ap[3]};
-                    // column-major order: MFMAs on the same accumulator are OT instructions apart
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-#pragma unroll
-                        for (int o = 0; o < OT; ++o)
-                            acc[p][o] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[j], bop[o][j], acc[p][o], 0, 0, 0);
-                }
-            }
-        }
-    }
-
-    // ---- write this slab's partial sums in parameter order (row-major [tap*Ci + c][o]), bias row last
-    const long plen = ((long)rows_total + 1) * a.Co;
-    float* out = a.partial + (long)blockIdx.x * plen;
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-        if (p < np) {
-            const int q = rt0 + wave + 4 * p;
-#pragma unroll
-            for (int o = 0; o < OT; ++o) {
-                const int oc = 16 * (ot0 + o) + li;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = 16 * q + 4 * lg + r;
-                    if (row < rows_total && oc < a.Co) out[(long)row * a.Co + oc] = acc[p][o][r];
-                }
-            }
-        }
-    }
-    // bias gradient = column sums of the delta tiles; one wave of the first row group owns it
-    if (blockIdx.y == 0) {
-        __syncthreads();
-        float* red = lds;  // [4 lane groups][16*OT]
-        if (wave == 0) {
-#pragma unroll
-            for (int o = 0; o < OT; ++o) red[lg * 16 * OT + 16 * o + li] = bsum[o];
-        }
-        __syncthreads();
-        if (tid < 16 * OT) {
-            const int oc = 16 * ot0 + tid;
-            if (oc < a.Co)
-                out[(long)rows_total * a.Co + oc] =
-                    (red[tid] + red[16 * OT + tid]) + (red[32 * OT + tid] + red[48 * OT + tid]);
-        }
-    }
-}
-
-// Second stage of the split reductions, all layers in one launch: out[e] = sum_{i<n}
-// partial[i][e].  64 columns per workgroup, the n rows dealt to 4 thread rows; each adds its
-// rows in ascending order, then the 4 sums are added in a fixed order - the result does
-// not depend on timing.
-constexpr int kMaxReduceSegs = 48;
-struct ReduceSeg {
-    const float* partial;
-    float* out;
-    int len, n, block0;
-};
-struct ReduceArgs {
-    ReduceSeg seg[kMaxReduceSegs];
-    int n_seg, total_blocks;
-};
-
-__global__ __launch_bounds__(256) void reduce_all_kernel(ReduceArgs a)
-{
-    __shared__ double red[4][64];
-    int si = 0;
-    while (si + 1 < a.n_seg && (int)blockIdx.x >= a.seg[si + 1].block0) ++si;
-    const float* __restrict__ partial = a.seg[si].partial;
-    const long len = a.seg[si].len;
-    const int n = a.seg[si].n;
-    const int col = threadIdx.x & 63, row = threadIdx.x >> 6;
-    const long e = (long)((int)blockIdx.x - a.seg[si].block0) * 64 + col;
-    double s = 0.0;
-    if (e < len) {
-        const int per = (n + 3) >> 2;
-        const int i0 = row * per, i1 = (i0 + per < n) ? i0 + per : n;
-        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;  // independent chains: loads in flight
-        int i = i0;
-        for (; i + 3 < i1; i += 4) {
-            s0 += (double)partial[(long)i * len + e];
-            s1 += (double)partial[(long)(i + 1) * len + e];
-            s2 += (double)partial[(long)(i + 2) * len + e];
-            s3 += (double)partial[(long)(i + 3) * len + e];
-        }
-        for (; i < i1; ++i) s0 += (double)partial[(long)i * len + e];
-        s = (s0 + s1) + (s2 + s3);
-    }
-    red[row][col] = s;
-    __syncthreads();
-    if (row == 0 && e < len) a.seg[si].out[e] = (float)((red[0][col] + red[1][col]) + (red[2][col] + red[3][col]));
 }
 
 }  // namespace mpcnn

@@ -19,6 +19,7 @@
 #include "../../include/mpcnn.h"
 #include "kernels_direct.hpp"
 #include "kernels_mfma.hpp"
+#include "kernels_wgrad.hpp"
 #include "kernels_fused.hpp"
 
 namespace {
@@ -69,11 +70,6 @@ ChanTiling chan_tiling_w(int channels, int W)   // forward / data-gradient kerne
     static const int allowed[] = {1, 2, 4};
     return tile_channels(channels, W, allowed, 3);
 }
-ChanTiling wgrad_tiling(int channels)           // weight-gradient kernel instances (16-wide)
-{
-    static const int allowed[] = {1, 2, 4, 7, 8};
-    return tile_channels(channels, 16, allowed, 5);
-}
 // 32-wide MFMA tiles run at the full fp32 matrix rate, 16-wide ones at about 0.87 of it:
 // take whichever wastes less once its padding is counted.
 ChanTiling chan_tiling(int channels)
@@ -81,7 +77,6 @@ ChanTiling chan_tiling(int channels)
     const ChanTiling a = chan_tiling_w(channels, 16), b = chan_tiling_w(channels, 32);
     return (a.pad / 0.87 < b.pad) ? a : b;
 }
-int wgrad_np(int OT) { return OT <= 2 ? 16 : (OT == 4 ? 12 : 6); }   // accumulator tiles per wave <= 48
 
 struct Layer {
     int kind;     // mpcnn_kind
@@ -94,7 +89,7 @@ struct Layer {
     // matrix-core paths (decided once from the channel counts)
     bool fwd_mfma = false, dgrad_mfma = false, wgrad_mfma = false;
     bool class_fused = false;             // last FC handled by class_layer_kernel
-    ChanTiling fwd_ct{}, dgrad_ct{}, wgrad_ct{};
+    ChanTiling fwd_ct{}, dgrad_ct{};
     int fwd_rpad = 0, dgrad_rpad = 0;     // reduced channels padded to 16
     size_t fwd_pack_off = 0, fwd_pack_len = 0, dgrad_pack_off = 0, dgrad_pack_len = 0;
 };
@@ -103,8 +98,9 @@ struct TilePlan { int PT = 0, NW = 4, Ty = 0, Tx = 0, nty = 0, ntx = 0; size_t l
 struct WgradPlan {
     bool ok = false;
     int Tx = 0, TxP = 0, nty = 0, ntx = 0, tiles_total = 0, tiles_per_slab = 0, slabs = 0;
-    int rtiles_total = 0, rtiles_per_group = 0, groups = 0, NP = 0;
+    int Mt = 0, Nt = 0, wm = 0, wn = 0, wk = 0, mw = 0, gm = 0, gn = 0;
     size_t lds = 0;
+    size_t plen = 0;      // floats per partial result (tiled layout)
     // direct kernel fallback
     int rows_per_chunk = 0, chunks = 0;
 };
@@ -122,6 +118,7 @@ struct Geom {
     size_t delta_off[2] = {0, 0};     // two delta buffers, each as large as the largest map
     std::vector<size_t> partial_off;  // per parametrised layer: its slab / block partial sums
     std::vector<int> partial_n;
+    std::vector<size_t> partial_len;  // floats per partial result
     size_t loss_partial_off = 0;
     size_t total = 0;
 };
@@ -256,35 +253,59 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, co
     return best;
 }
 
-WgradPlan plan_wgrad(const Layer& ly, int B, int out_r, int out_c)
+unsigned magic_of(unsigned x) { return x <= 1 ? 0u : (unsigned)(((1ull << 32) + x - 1) / x); }
+
+WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int out_c)
 {
     WgradPlan w;
-    if (ly.wgrad_mfma) {
-        // tile = 4 rows x Tx columns of a residue class; the MFMA work of a tile grows with
-        // Tx rounded up to 4, so take the split of the class width that wastes least
-        const int d = ly.dil, k = ly.k, OT = ly.wgrad_ct.OT;
-        const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
+    const int d = ly.dil, k = ly.k;
+    const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
+    const bool fits32 = (size_t)in_r * in_c * ly.cin * 4 < (1ull << 31) &&
+                        (size_t)out_r * out_c * ly.cout * 4 < (1ull << 31) && (k + 3) * d < 65536;
+    if (ly.wgrad_mfma && fits32) {
+        // split of the four waves over result rows / columns / tile rows: least padded work,
+        // then fewest workgroup groups (each group stages the tiles again)
+        const int Mt = ceil_div(k * k * ly.cin, 32), Nt = ceil_div(ly.cout, 32);
+        long best_pad = -1; int best_groups = 0;
+        for (int wn : {4, 2, 1})
+            for (int wm : {1, 2, 4}) {
+                if (wm * wn > 4) continue;
+                const int wk = 4 / (wm * wn);
+                const int gm = ceil_div(Mt, mpcnn::kWgMaxTiles * wm), mw = ceil_div(Mt, gm * wm);
+                const int gn = ceil_div(Nt, wn);
+                const long pad = (long)gm * wm * mw * gn * wn;
+                if (best_pad < 0 || pad < best_pad || (pad == best_pad && gm * gn < best_groups)) {
+                    best_pad = pad; best_groups = gm * gn;
+                    w.wm = wm; w.wn = wn; w.wk = wk; w.mw = mw; w.gm = gm; w.gn = gn;
+                }
+            }
+        w.Mt = Mt; w.Nt = Nt;
+        w.plen = (size_t)Mt * Nt * 1024 + (size_t)Nt * 32;
+        // tile = 4 rows x Tx columns of a residue class: fewest matrix-core ticks of the busiest
+        // workgroup (a tile's work grows with Tx rounded up to 4, plus a fixed cost per tile)
         const int cq = ceil_div(ly.cin, 4), hh = 4 + k - 1;
-        long best = -1;
+        const int target = std::max(1, kNumCU / (w.gm * w.gn));
+        const double col_ticks = (4.0 / w.wk) * w.mw * 32.0;
+        double best = -1;
         for (int tx = 1; tx <= fw; ++tx) {
             const int txp = ceil_div(tx, 4) * 4, hwp = txp + k - 1;
-            const size_t hp = (size_t)((hh * hwp + 4) | 1);
-            const size_t lds = sizeof(float) * (ly.cin * hp + (size_t)4 * txp * (16 * OT + 1));
-            if (hh * hwp * cq > mpcnn::kWgradStageH * 256 || 16 * txp * OT > mpcnn::kWgradStageD * 256 ||
+            const size_t buf = ((size_t)4 * w.wn * (txp * 32 + 32) + (size_t)ly.cin * ((hh * hwp) | 1) + 3) & ~(size_t)3;
+            size_t lds = 2 * buf * sizeof(float) + 64;   // slack: the operand prefetch runs one chunk ahead
+            if (w.wk > 1) lds = std::max(lds, (size_t)2 * w.mw * 4096);
+            lds = std::max(lds, (size_t)1024);
+            if (hh * hwp * cq > mpcnn::kWgStageH * 256 || 4 * txp * 8 * w.wn > mpcnn::kWgStageD * 256 ||
                 lds > kWgradLdsCap)
                 continue;
-            const long cost = (long)ceil_div(fw, tx) * (txp + 6);   // + fixed cost of a tile
+            const int ntx = ceil_div(fw, tx);
+            const long tiles = (long)B * d * d * ceil_div(fh, 4) * ntx;
+            if (tiles * std::max(std::max(ntx, ceil_div(fh, 4)), d) >= (1ll << 31)) continue;
+            const long tps = (tiles + target - 1) / target;
+            const double cost = (double)tps * (txp * col_ticks + 1500.0);
             if (best < 0 || cost <= best) { best = cost; w.Tx = tx; w.TxP = txp; w.lds = lds; }
         }
         if (best >= 0) {
             w.nty = ceil_div(fh, 4); w.ntx = ceil_div(fw, w.Tx);
             w.tiles_total = B * d * d * w.nty * w.ntx;
-            w.NP = wgrad_np(OT);
-            w.rtiles_total = ceil_div(k * k * ly.cin, 16);
-            w.groups = ceil_div(w.rtiles_total, 4 * w.NP);
-            w.rtiles_per_group = ceil_div(ceil_div(w.rtiles_total, w.groups), 4) * 4;
-            w.groups = ceil_div(w.rtiles_total, w.rtiles_per_group);
-            int target = std::max(1, kNumCU / (w.groups * ly.wgrad_ct.split));
             w.tiles_per_slab = ceil_div(w.tiles_total, target);
             w.slabs = ceil_div(w.tiles_total, w.tiles_per_slab);
             w.ok = true;
@@ -294,6 +315,7 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int out_r, int out_c)
     long rows_total = (long)B * out_r;
     w.rows_per_chunk = (int)std::max<long>(1, (rows_total + kDirectWgradChunks - 1) / kDirectWgradChunks);
     w.chunks = (int)((rows_total + w.rows_per_chunk - 1) / w.rows_per_chunk);
+    w.plen = ly.p_len;
     return w;
 }
 
@@ -307,7 +329,7 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
     g->rows.assign(L, 0); g->cols.assign(L, 0);
     g->act_off.assign(L, 0); g->code_off.assign(L, 0);
     g->fwd.assign(L, TilePlan()); g->dgrad.assign(L, TilePlan()); g->wgrad.assign(L, WgradPlan());
-    g->partial_off.assign(L, 0); g->partial_n.assign(L, 0);
+    g->partial_off.assign(L, 0); g->partial_n.assign(L, 0); g->partial_len.assign(L, 0);
     size_t off = 0, max_act = 0;
     if (net->in_ch > 1) {
         g->staged_off = off;
@@ -327,12 +349,14 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.k, ly.fwd_rpad, ly.fwd_ct);
         if (training && ly.class_fused) {
             g->partial_n[l] = class_blocks((long)B * r * c);
+            g->partial_len[l] = ly.p_len;
         } else if (training) {
             if (ly.dgrad_mfma && l > 0)
                 g->dgrad[l] = plan_conv_tiles(B, in_r, in_c, ly.dil, ly.k, ly.dgrad_rpad, ly.dgrad_ct);
-            g->wgrad[l] = plan_wgrad(ly, B, r, c);
+            g->wgrad[l] = plan_wgrad(ly, B, in_r, in_c, r, c);
             const WgradPlan& w = g->wgrad[l];
             g->partial_n[l] = w.ok ? w.slabs : w.chunks;
+            g->partial_len[l] = w.plen;
         }
     }
     if (r != H - net->patch + 1 || c != W - net->patch + 1) return false;
@@ -352,7 +376,7 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         for (size_t l = 0; l < L; ++l) {
             if (!g->partial_n[l]) continue;
             g->partial_off[l] = off;
-            off = align_up(off + sizeof(float) * (size_t)g->partial_n[l] * net->layers[l].p_len);
+            off = align_up(off + sizeof(float) * (size_t)g->partial_n[l] * g->partial_len[l]);
         }
     } else {
         // forward only: layers alternate between two buffers, nothing is kept
@@ -392,20 +416,13 @@ bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, const Tile
 #undef CASE
     return false;
 }
-template <int NP, int OT>
-void launch_wgrad_inst(const mpcnn::WgradArgs& a, dim3 grid, size_t lds, hipStream_t st)
+void launch_wgrad_mfma(const mpcnn::WgradArgs& a, dim3 grid, size_t lds, hipStream_t st)
 {
-    mpcnn::wgrad_mfma_kernel<NP, OT><<<grid, 256, lds, st>>>(a);
-}
-void launch_wgrad_mfma(const mpcnn::WgradArgs& a, int OT, dim3 grid, size_t lds, hipStream_t st)
-{
-    switch (OT) {
-    case 1: return launch_wgrad_inst<16, 1>(a, grid, lds, st);
-    case 2: return launch_wgrad_inst<16, 2>(a, grid, lds, st);
-    case 4: return launch_wgrad_inst<12, 4>(a, grid, lds, st);
-    case 7: return launch_wgrad_inst<6, 7>(a, grid, lds, st);
-    case 8: return launch_wgrad_inst<6, 8>(a, grid, lds, st);
+#define CASE(m) case m: mpcnn::wgrad_mfma_kernel<m><<<grid, 256, lds, st>>>(a); return;
+    switch (a.mw) {
+    CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12) CASE(13)
     }
+#undef CASE
 }
 // Kernels that may ask for more than 64 KiB of dynamic LDS must say so once.
 mpcnn_status set_lds_attrs()
@@ -416,9 +433,11 @@ mpcnn_status set_lds_attrs()
     ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 8>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 8>));
     ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 4>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 4, 8>));
     ATTR((mpcnn::conv_mfma_kernel<16, 4, 4, 8>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 2, 8>));
-    ATTR((mpcnn::wgrad_mfma_kernel<16, 1>)); ATTR((mpcnn::wgrad_mfma_kernel<16, 2>));
-    ATTR((mpcnn::wgrad_mfma_kernel<12, 4>)); ATTR((mpcnn::wgrad_mfma_kernel<6, 7>));
-    ATTR((mpcnn::wgrad_mfma_kernel<6, 8>));
+    ATTR(mpcnn::wgrad_mfma_kernel<1>); ATTR(mpcnn::wgrad_mfma_kernel<2>); ATTR(mpcnn::wgrad_mfma_kernel<3>);
+    ATTR(mpcnn::wgrad_mfma_kernel<4>); ATTR(mpcnn::wgrad_mfma_kernel<5>); ATTR(mpcnn::wgrad_mfma_kernel<6>);
+    ATTR(mpcnn::wgrad_mfma_kernel<7>); ATTR(mpcnn::wgrad_mfma_kernel<8>); ATTR(mpcnn::wgrad_mfma_kernel<9>);
+    ATTR(mpcnn::wgrad_mfma_kernel<10>); ATTR(mpcnn::wgrad_mfma_kernel<11>); ATTR(mpcnn::wgrad_mfma_kernel<12>);
+    ATTR(mpcnn::wgrad_mfma_kernel<13>);
 #undef ATTR
     return MPCNN_OK;
 }
@@ -612,10 +631,13 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout; a.k = ly.k; a.d = ly.dil;
                 a.Tx = wp.Tx; a.TxP = wp.TxP; a.nty = wp.nty; a.ntx = wp.ntx;
                 a.tiles_total = wp.tiles_total; a.tiles_per_slab = wp.tiles_per_slab;
-                a.rtiles_total = wp.rtiles_total; a.rtiles_per_group = wp.rtiles_per_group;
-                dim3 grid((unsigned)wp.slabs, (unsigned)wp.groups, (unsigned)ly.wgrad_ct.split);
+                a.Mt = wp.Mt; a.Nt = wp.Nt; a.wm = wp.wm; a.wn = wp.wn; a.wk = wp.wk; a.mw = wp.mw;
+                a.mg_cq = magic_of(ceil_div(Ci, 4)); a.mg_hwp = magic_of(wp.TxP + ly.k - 1);
+                a.mg_txp = magic_of(wp.TxP); a.mg_ci = magic_of(Ci); a.mg_k = magic_of(ly.k);
+                a.mg_ntx = magic_of(wp.ntx); a.mg_nty = magic_of(wp.nty); a.mg_d = magic_of(ly.dil);
+                dim3 grid((unsigned)wp.slabs, (unsigned)wp.gm, (unsigned)wp.gn);
                 LAUNCH("wgrad_mfma", li, wstep, flops, 4.0 * (n_in + n_out + ly.p_len),
-                       launch_wgrad_mfma(a, ly.wgrad_ct.OT, grid, wp.lds, st));
+                       launch_wgrad_mfma(a, grid, wp.lds, st));
             } else {
                 dim3 grid((unsigned)((ly.p_len + 255) / 256), (unsigned)wp.chunks);
                 LAUNCH("wgrad_direct", li, wstep, flops, 4.0 * (n_in + n_out + ly.p_len),
@@ -662,10 +684,14 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
         ReduceSeg& sg = ra.seg[ra.n_seg++];
         sg.partial = (const float*)(ws + g.partial_off[l]);
         sg.out = net->d_grads + ly.p_off;
-        sg.len = (int)ly.p_len; sg.n = g.partial_n[l];
+        sg.plen = (long)g.partial_len[l]; sg.n = g.partial_n[l];
+        const WgradPlan& wp = g.wgrad[l];
+        sg.tiled = wp.ok ? 1 : 0;
+        sg.items = wp.ok ? wp.Mt * wp.Nt * 256 + wp.Nt * 8 : (int)ly.p_len;
+        sg.Nt = wp.Nt; sg.rows_total = ly.k * ly.k * ly.cin; sg.Co = ly.cout;
         sg.block0 = ra.total_blocks;
-        ra.total_blocks += (int)((ly.p_len + 63) / 64);
-        rbytes += 4.0 * ly.p_len * (sg.n + 1.0);
+        ra.total_blocks += (sg.items + 63) / 64;
+        rbytes += 4.0 * ((double)sg.plen * sg.n + ly.p_len);
     }
     LAUNCH("reduce_all", -1, 0, 0, rbytes, reduce_all_kernel<<<(unsigned)ra.total_blocks, 256, 0, st>>>(ra));
     HIP_TRY(hipGetLastError());
@@ -785,7 +811,6 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
                 ly.dgrad_pack_len = (size_t)ly.k * ly.k * ly.dgrad_rpad * ly.dgrad_ct.pad;
                 ly.dgrad_pack_off = pack; pack += ly.dgrad_pack_len;
             }
-            if (ly.wgrad_mfma) ly.wgrad_ct = wgrad_tiling(ly.cout);
         }
         ch = ly.cout;
         net->layers.push_back(ly);
