@@ -19,15 +19,18 @@
 // that the multiply loop has no branches; tiles beyond the gradient's last row tile compute
 // on valid addresses and are never stored.  The four waves split the 32 x 32 result tiles along rows (wm),
 // columns (wn) and tile rows (wk, partial sums met in LDS at the end, fixed order).
-// LDS is double buffered: while tile t is multiplied, tile t+1 is written to the other
-// buffer from registers and tile t+2 is already being fetched from global memory.
+// A workgroup has eight waves, two per SIMD: waves 0-3 multiply, waves 4-7 only move data.
+// LDS is double buffered: while the multiplying waves work on tile t, the loading waves bring
+// tile t+1 from global memory into the other buffer; one barrier per tile.  The matrix cores
+// of a SIMD thus see nothing of the staging (a wave's own vector ALU and memory instructions
+// are not overlapped with its MFMAs, another wave's are).
 #pragma once
 #include "kernels_mfma.hpp"
 #include <type_traits>
 
 namespace mpcnn {
 
-constexpr int kWgMaxTiles = 13;   // 32x32 result tiles per wave (16 accumulator registers each)
+constexpr int kWgMaxTiles = 11;   // 32x32 result tiles per wave (16 accumulator registers each; two waves share a SIMD's 512)
 constexpr int kWgStageH = 8;      // 128-bit items of the input halo one thread stages per tile
 constexpr int kWgStageD = 8;      // ... of the delta tile
 
@@ -42,7 +45,7 @@ struct WgradArgs {
     int nty, ntx;
     int tiles_total, tiles_per_slab;
     int Mt, Nt;            // 32-row / 32-column tiles of the gradient matrix (row = tap*Ci + c)
-    int wm, wn, wk;        // waves along result rows, result columns, tile rows (wm*wn*wk = 4)
+    int wm, wn, wk;        // multiplying waves along result rows, result columns, tile rows (wm*wn*wk = 4)
     int mw;                // row tiles per wave (<= kWgMaxTiles); blockIdx.y covers wm*mw of them
     // ceil(2^32 / x): n / x == umulhi(n, magic) for n * x < 2^32, x > 1
     unsigned mg_cq, mg_hwp, mg_txp, mg_ci, mg_k, mg_ntx, mg_nty, mg_d;
@@ -54,12 +57,14 @@ __device__ __forceinline__ unsigned magic_div(unsigned n, unsigned magic, unsign
 }
 
 template <int MW>
-__global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
+__global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
 {
     constexpr int HL = kWgStageH, DL = kWgStageD;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool loader = wave8 >= 4;             // uniform per wave
+    const int wave = wave8 & 3, ltid = tid & 255;
     const int lm = lane & 31, lk = lane >> 5;
     // (uniform values that come out of a division are pinned to scalar registers by hand)
     const int wn = a.wn;                        // 1, 2 or 4
@@ -78,26 +83,12 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
     const int buf_f = (dt_f + a.Ci * HP + 3) & ~3;
 
     const int rows_total = a.k * a.k * a.Ci;
-    // ---- this wave's result tiles: rows 32*(mt0 + p), p < np; columns 32*nt
+    // ---- a multiplying wave's result tiles: rows 32*(mt0 + p), p < np; columns 32*nt
     const int mt0 = blockIdx.y * (a.wm * a.mw) + midx * a.mw;
     int np = a.Mt - mt0;
     np = __builtin_amdgcn_readfirstlane(np < 0 ? 0 : (np > a.mw ? a.mw : np));
     const int nt = blockIdx.z * wn + nidx;
-    const bool active = np > 0 && nt < a.Nt;
-    // byte offset in a buffer of this lane's A operand: its (tap, c) at tile row 0, column lk
-    unsigned aoff[MW];
-#pragma unroll
-    for (int p = 0; p < MW; ++p) {
-        const unsigned row = 32u * (mt0 + p) + lm;
-        unsigned o = dt_f + lk;
-        if (p < np && row < (unsigned)rows_total) {
-            const unsigned tap = magic_div(row, a.mg_ci, a.Ci), c = row - tap * a.Ci;
-            const unsigned ta = magic_div(tap, a.mg_k, a.k), tb = tap - ta * a.k;
-            o += c * HP + ta * hwp + tb;
-        }
-        aoff[p] = 4u * o;
-    }
-    const unsigned boff = 4u * (nidx * OB + lk * 32 + lm);   // B operand: column lk of row 0
+    const bool active = !loader && np > 0 && nt < a.Nt;
 
     v16f acc[MW];
 #pragma unroll
@@ -109,48 +100,6 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
     const int tile_begin = blockIdx.x * a.tiles_per_slab;
     int tile_end = tile_begin + a.tiles_per_slab;
     if (tile_end > a.tiles_total) tile_end = a.tiles_total;
-    const int cq = (a.Ci + 3) >> 2;
-    const int h_items = hh * hwp * cq;
-    const int dq_shift = 3 + (wn >> 1);         // 8 * wn 128-bit items per delta position
-    const int d_items = (4 * a.TxP) << dq_shift;
-    const bool vec_in = (a.Ci & 3) == 0, vec_dy = (a.Co & 3) == 0;
-    const int h_full = h_items >> 8, d_full = d_items >> 8;   // staging rounds in which every thread has an item
-
-    // ---- staging plan.  Which halo / delta item a thread stages never changes: decode once.
-    // Halo coordinates outside the input are clamped (any finite value will do there: the
-    // matching deltas are zero); delta items outside the class are loaded from a safe address
-    // and zeroed on the way to LDS.
-    unsigned h_yx[HL];
-    int h_dst[HL];      // channel 4q << 20 | float index in a buffer of that channel at this halo position, -1 = none
-    unsigned d_tyx[DL];
-    int d_rel[DL];      // float offset of the item relative to the tile's first delta
-    unsigned d_static = 0;   // bit u: item u is a real column of the tile and a real channel
-#pragma unroll
-    for (int u = 0; u < HL; ++u) {
-        const unsigned it = tid + 256 * u;
-        h_yx[u] = 0; h_dst[u] = -1;
-        if (it < (unsigned)h_items) {
-            const unsigned pos = magic_div(it, a.mg_cq, cq), q = it - pos * cq;
-            const unsigned ha = magic_div(pos, a.mg_hwp, hwp), hb = pos - ha * hwp;
-            h_yx[u] = ((ha * a.d) << 16) | (hb * a.d);
-            h_dst[u] = (int)((4 * q) << 20 | (dt_f + 4 * q * HP + ha * hwp + hb));
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < DL; ++u) {
-        const unsigned it = tid + 256 * u;
-        d_tyx[u] = 0; d_rel[u] = 0;
-        if (it < (unsigned)d_items) {
-            const unsigned m = it >> dq_shift, q = it - (m << dq_shift);
-            const unsigned ty = magic_div(m, a.mg_txp, a.TxP), tx = m - ty * a.TxP;
-            const int oc = 32 * blockIdx.z * wn + 4 * q;
-            d_tyx[u] = (ty << 16) | tx;
-            if (tx < (unsigned)a.Tx && oc < a.Co) {
-                d_static |= 1u << u;
-                d_rel[u] = (int)((ty * a.d * a.Wo + tx * a.d) * a.Co) + oc;
-            }
-        }
-    }
 
     struct TileGeom { int b, ry, rx, ty0, tx0, rows, cols; };
     auto decode = [&](int tile) {
@@ -173,71 +122,133 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
         return t;
     };
 
-    v4f hr[HL], dr[DL];
-    unsigned dmask = 0;   // bit u: delta item u of the tile in flight lies inside the class
-    auto gload = [&](int tile) {
-        const TileGeom t = decode(tile);
-        const char* in_b = (const char*)(a.in + (long)t.b * a.Hi * a.Wi * a.Ci);
-        const char* dy_b = (const char*)(a.dY + (long)t.b * a.Ho * a.Wo * a.Co);
-        const int y0 = t.ty0 * a.d + t.ry, x0 = t.tx0 * a.d + t.rx;
-        const int dbase = (y0 * a.Wo + x0) * a.Co;
-        dmask = 0;
+    if (loader) {
+        // ================= loading waves: global memory -> LDS, one tile ahead =================
+        const int cq = (a.Ci + 3) >> 2;
+        const int h_items = hh * hwp * cq;
+        const int dq_shift = 3 + (wn >> 1);     // 8 * wn 128-bit items per delta position
+        const int d_items = (4 * a.TxP) << dq_shift;
+        const bool vec_in = (a.Ci & 3) == 0, vec_dy = (a.Co & 3) == 0;
+        const int h_full = h_items >> 8, d_full = d_items >> 8;   // rounds in which every thread has an item
+        // Thread ltid stages the 128-bit items ltid + 256*u of the halo and of the delta tile.
+        // Which items those are never changes, so they are decoded once; per tile only the
+        // global addresses are formed (these waves share their SIMD's issue slots with the
+        // multiplying waves: the less vector ALU work here, the better).  Halo coordinates
+        // outside the input are clamped (any finite value will do there: the matching deltas
+        // are zero); delta items outside the class are loaded from a safe address and zeroed on
+        // the way to LDS.
+        unsigned h_yx[HL];   // (halo row * d) << 16 | halo col * d
+        int h_dst[HL];       // channel 4q << 20 | float index in a buffer of that channel at this position, -1 = none
+        unsigned d_tyx[DL];  // tile row << 16 | tile col
+        int d_rel[DL];       // float offset of the item from the tile's first delta, -1 = never inside
+        int d_dst[DL];       // float index in a buffer, -1 = none
 #pragma unroll
         for (int u = 0; u < HL; ++u) {
-            int iy = y0 + (int)(h_yx[u] >> 16), ix = x0 + (int)(h_yx[u] & 0xffffu);
-            iy = iy < a.Hi ? iy : a.Hi - 1;
-            ix = ix < a.Wi ? ix : a.Wi - 1;
-            const int q4 = h_dst[u] < 0 ? 0 : h_dst[u] >> 20;
-            const unsigned off = 4u * ((unsigned)(iy * a.Wi + ix) * a.Ci + q4);
-            if (vec_in) hr[u] = *reinterpret_cast<const v4f*>(in_b + off);
-            else {
-#pragma unroll
-                for (int z = 0; z < 4; ++z)
-                    hr[u][z] = q4 + z < a.Ci ? *reinterpret_cast<const float*>(in_b + off + 4 * z) : 0.f;
+            const unsigned it = ltid + 256 * u;
+            h_yx[u] = 0; h_dst[u] = -1;
+            if (it < (unsigned)h_items) {
+                const unsigned pos = magic_div(it, a.mg_cq, cq), q = it - pos * cq;
+                const unsigned ha = magic_div(pos, a.mg_hwp, hwp), hb = pos - ha * hwp;
+                h_yx[u] = ((ha * a.d) << 16) | (hb * a.d);
+                h_dst[u] = (int)((4 * q) << 20 | (dt_f + 4 * q * HP + ha * hwp + hb));
             }
         }
 #pragma unroll
         for (int u = 0; u < DL; ++u) {
-            const bool ok = ((d_static >> u) & 1u) && (int)(d_tyx[u] >> 16) < t.rows &&
-                            (int)(d_tyx[u] & 0xffffu) < t.cols;
-            dmask |= ok ? (1u << u) : 0u;
-            const unsigned off = ok ? 4u * (unsigned)(dbase + d_rel[u]) : 0u;
-            if (vec_dy) dr[u] = *reinterpret_cast<const v4f*>(dy_b + off);
-            else {
-                const int oc = d_rel[u] % a.Co;   // rare path: Co not a multiple of 4
-#pragma unroll
-                for (int z = 0; z < 4; ++z)
-                    dr[u][z] = (ok && oc + z < a.Co) ? *reinterpret_cast<const float*>(dy_b + off + 4 * z) : 0.f;
+            const unsigned it = ltid + 256 * u;
+            d_tyx[u] = 0; d_rel[u] = -1; d_dst[u] = -1;
+            if (it < (unsigned)d_items) {
+                const unsigned m = it >> dq_shift, q = it - (m << dq_shift);
+                const unsigned ty = magic_div(m, a.mg_txp, a.TxP), tx = m - ty * a.TxP;
+                const int oc = 32 * blockIdx.z * wn + 4 * q;
+                d_tyx[u] = (ty << 16) | tx;
+                d_dst[u] = (int)((q >> 3) * OB + 4 * (q & 7) + ty * RB + tx * 32);
+                if (tx < (unsigned)a.Tx && oc < a.Co) d_rel[u] = (int)((ty * a.d * a.Wo + tx * a.d) * a.Co) + oc;
             }
         }
-    };
-    const int d_q = tid & ((8 << (wn >> 1)) - 1);               // the same for all of a thread's delta items
-    const int d_dst0 = (d_q >> 3) * OB + 4 * (d_q & 7);
-    auto lstore = [&](float* buf) {
+        auto stage = [&](int tile, float* buf) {
+            const TileGeom t = decode(tile);
+            const char* in_b = (const char*)(a.in + (long)t.b * a.Hi * a.Wi * a.Ci);
+            const char* dy_b = (const char*)(a.dY + (long)t.b * a.Ho * a.Wo * a.Co);
+            const int y0 = t.ty0 * a.d + t.ry, x0 = t.tx0 * a.d + t.rx;
+            const int dbase = (y0 * a.Wo + x0) * a.Co;
+            v4f hr[HL], dr[DL];
+            unsigned okmask = 0;
+            // all loads of the tile first: one trip to memory
 #pragma unroll
-        for (int u = 0; u < HL; ++u) {
-            if (u < h_full || h_dst[u] >= 0) {      // first test is uniform: whole rounds store unmasked
-                float* dst = buf + (h_dst[u] & 0xfffff);
-                if (vec_in) {
-                    dst[0] = hr[u][0]; dst[HP] = hr[u][1]; dst[2 * HP] = hr[u][2]; dst[3 * HP] = hr[u][3];
-                } else {
-                    const int q4 = h_dst[u] >> 20;
+            for (int u = 0; u < HL; ++u) {
+                int iy = y0 + (int)(h_yx[u] >> 16), ix = x0 + (int)(h_yx[u] & 0xffffu);
+                iy = iy < a.Hi ? iy : a.Hi - 1;
+                ix = ix < a.Wi ? ix : a.Wi - 1;
+                const int q4 = h_dst[u] < 0 ? 0 : h_dst[u] >> 20;
+                const unsigned off = 4u * ((unsigned)(iy * a.Wi + ix) * a.Ci + q4);
+                if (vec_in) hr[u] = *reinterpret_cast<const v4f*>(in_b + off);
+                else {
 #pragma unroll
                     for (int z = 0; z < 4; ++z)
-                        if (q4 + z < a.Ci) dst[z * HP] = hr[u][z];
+                        hr[u][z] = q4 + z < a.Ci ? *reinterpret_cast<const float*>(in_b + off + 4 * z) : 0.f;
                 }
             }
-        }
 #pragma unroll
-        for (int u = 0; u < DL; ++u) {
-            const int it = tid + 256 * u;
-            if (u < d_full || it < d_items) {
-                const v4f z4 = {0.f, 0.f, 0.f, 0.f};
-                float* dst = buf + d_dst0 + (d_tyx[u] >> 16) * RB + (d_tyx[u] & 0xffffu) * 32;
-                *reinterpret_cast<v4f*>(dst) = ((dmask >> u) & 1u) ? dr[u] : z4;
+            for (int u = 0; u < DL; ++u) {
+                const bool ok = d_rel[u] >= 0 && (int)(d_tyx[u] >> 16) < t.rows && (int)(d_tyx[u] & 0xffffu) < t.cols;
+                okmask |= ok ? (1u << u) : 0u;
+                const unsigned off = ok ? 4u * (unsigned)(dbase + d_rel[u]) : 0u;
+                if (vec_dy) dr[u] = *reinterpret_cast<const v4f*>(dy_b + off);
+                else {
+                    const int oc = ok ? d_rel[u] % a.Co : 0;   // rare path: Co not a multiple of 4
+#pragma unroll
+                    for (int z = 0; z < 4; ++z)
+                        dr[u][z] = (ok && oc + z < a.Co) ? *reinterpret_cast<const float*>(dy_b + off + 4 * z) : 0.f;
+                }
             }
+#pragma unroll
+            for (int u = 0; u < HL; ++u) {
+                if (u < h_full || h_dst[u] >= 0) {      // first test is uniform: whole rounds store unmasked
+                    float* p = buf + (h_dst[u] & 0xfffff);
+                    if (vec_in) {
+                        p[0] = hr[u][0]; p[HP] = hr[u][1]; p[2 * HP] = hr[u][2]; p[3 * HP] = hr[u][3];
+                    } else {
+                        const int q4 = h_dst[u] >> 20;
+#pragma unroll
+                        for (int z = 0; z < 4; ++z)
+                            if (q4 + z < a.Ci) p[z * HP] = hr[u][z];
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < DL; ++u) {
+                if (u < d_full || d_dst[u] >= 0) {
+                    const v4f z4 = {0.f, 0.f, 0.f, 0.f};
+                    *reinterpret_cast<v4f*>(buf + d_dst[u]) = ((okmask >> u) & 1u) ? dr[u] : z4;
+                }
+            }
+        };
+        // these waves issue little and must not wait behind the MFMA stream of their SIMD
+        __builtin_amdgcn_s_setprio(3);
+        if (tile_begin < tile_end) stage(tile_begin, lds);
+        __syncthreads();
+        int cur = 0;
+        for (int tile = tile_begin; tile < tile_end; ++tile, cur ^= 1) {
+            if (tile + 1 < tile_end) stage(tile + 1, lds + (cur ^ 1) * buf_f);
+            __syncthreads();
         }
-    };
+    } else {
+    // ================= multiplying waves =================
+    // byte offset in a buffer of this lane's A operand: its (tap, c) at tile row 0, column lk
+    unsigned aoff[MW];
+#pragma unroll
+    for (int p = 0; p < MW; ++p) {
+        const unsigned row = 32u * (mt0 + p) + lm;
+        unsigned o = dt_f + lk;
+        if (p < np && row < (unsigned)rows_total) {
+            const unsigned tap = magic_div(row, a.mg_ci, a.Ci), c = row - tap * a.Ci;
+            const unsigned ta = magic_div(tap, a.mg_k, a.k), tb = tap - ta * a.k;
+            o += c * HP + ta * hwp + tb;
+        }
+        aoff[p] = 4u * o;
+    }
+    const unsigned boff = 4u * (nidx * OB + lk * 32 + lm);   // B operand: column lk of row 0
 
     // ---- one tile on the matrix cores: chunks of 2 columns (lane group lk takes column lk),
     // one MFMA per row tile and chunk; the operands of the next chunk are fetched while the
@@ -322,16 +333,9 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
         for (int p = 0; p < MW; ++p) aoff[p] -= moved;
     };
 
-    if (tile_begin < tile_end) {
-        gload(tile_begin);
-        lstore(lds);
-        if (tile_begin + 1 < tile_end) gload(tile_begin + 1);
-    }
-    __syncthreads();
+    __syncthreads();   // first tile staged
     int cur = 0;
     for (int tile = tile_begin; tile < tile_end; ++tile, cur ^= 1) {
-        if (tile + 1 < tile_end) lstore(lds + (cur ^ 1) * buf_f);   // fetched during the previous tile
-        if (tile + 2 < tile_end) gload(tile + 2);                   // in flight during the MFMAs below
         if (active) {
             const TileGeom t = decode(tile);
             const int rows_valid = t.rows < 4 ? t.rows : 4;
@@ -340,6 +344,7 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
         }
         __syncthreads();
     }
+    }   // multiplying waves
 
     // ---- partial sums of the waves that shared result tiles (wk > 1) meet in LDS: the upper
     // half of the tile-row groups hands its tiles to the lower half, twice if wk = 4
@@ -386,7 +391,7 @@ __global__ __launch_bounds__(256, 1) void wgrad_mfma_kernel(WgradArgs a)
     }
     // bias gradient = column sums of the delta tiles, from the waves of the first row group
     if (blockIdx.y == 0) {
-        lds[wave * 64 + lane] = bsum;
+        if (!loader) lds[wave * 64 + lane] = bsum;
         __syncthreads();
         if (tid < 32 * wn) {
             const int ni = tid >> 5, n = tid & 31;

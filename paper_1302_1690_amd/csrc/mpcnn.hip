@@ -418,9 +418,9 @@ bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, const Tile
 }
 void launch_wgrad_mfma(const mpcnn::WgradArgs& a, dim3 grid, size_t lds, hipStream_t st)
 {
-#define CASE(m) case m: mpcnn::wgrad_mfma_kernel<m><<<grid, 256, lds, st>>>(a); return;
+#define CASE(m) case m: mpcnn::wgrad_mfma_kernel<m><<<grid, 512, lds, st>>>(a); return;
     switch (a.mw) {
-    CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12) CASE(13)
+    CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11)
     }
 #undef CASE
 }
@@ -436,8 +436,7 @@ mpcnn_status set_lds_attrs()
     ATTR(mpcnn::wgrad_mfma_kernel<1>); ATTR(mpcnn::wgrad_mfma_kernel<2>); ATTR(mpcnn::wgrad_mfma_kernel<3>);
     ATTR(mpcnn::wgrad_mfma_kernel<4>); ATTR(mpcnn::wgrad_mfma_kernel<5>); ATTR(mpcnn::wgrad_mfma_kernel<6>);
     ATTR(mpcnn::wgrad_mfma_kernel<7>); ATTR(mpcnn::wgrad_mfma_kernel<8>); ATTR(mpcnn::wgrad_mfma_kernel<9>);
-    ATTR(mpcnn::wgrad_mfma_kernel<10>); ATTR(mpcnn::wgrad_mfma_kernel<11>); ATTR(mpcnn::wgrad_mfma_kernel<12>);
-    ATTR(mpcnn::wgrad_mfma_kernel<13>);
+    ATTR(mpcnn::wgrad_mfma_kernel<10>); ATTR(mpcnn::wgrad_mfma_kernel<11>);
 #undef ATTR
     return MPCNN_OK;
 }
