@@ -12,8 +12,11 @@
 namespace mpcnn {
 
 // Conv + bias + tanh when the input has too few channels for the matrix cores (the image
-// itself: 1 or 3 channels).  One thread = one position x 16 output channels; weights are
-// wave-uniform (scalar loads), the output is written as four 128-bit stores.
+// itself: 1 or 3 channels).  One thread = one position x 4 output channels (blockIdx.y picks
+// the 4): four times the waves of a 16-channel thread, which is what hides the latency of
+// the tap loads; the taps of one filter row are fetched together.  Weights are wave-uniform
+// (scalar loads).
+constexpr int kFirstLayerBatch = 8;   // taps of a filter row fetched together
 __global__ __launch_bounds__(256) void first_layer_kernel(const float* __restrict__ A,
                                                           const float* __restrict__ Wk,
                                                           float* __restrict__ Y, int B, int Hi, int Wi,
@@ -22,75 +25,115 @@ __global__ __launch_bounds__(256) void first_layer_kernel(const float* __restric
 {
     const long total = (long)B * Ho * Wo;
     const long m = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int o0 = blockIdx.y * 16;
+    const int o0 = blockIdx.y * 4;
     if (m >= total) return;
-    const int x = (int)(m % Wo);
-    const long q = m / Wo;
-    const int y = (int)(q % Ho), b = (int)(q / Ho);
-    float acc[16];
-#pragma unroll
-    for (int o = 0; o < 16; ++o) acc[o] = 0.f;
+    const int b = (int)(m / ((long)Ho * Wo));
+    const int r = (int)(m - (long)b * Ho * Wo);       // position within the image: 32-bit from here on
+    const int y = r / Wo, x = r - y * Wo;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
     const float* bias = Wk + (long)k * k * Ci * Co;
-    for (int u = 0; u < k; ++u)
-        for (int v = 0; v < k; ++v) {
-            const float* a = A + (((long)b * Hi + (y + u * d)) * Wi + (x + v * d)) * Ci;
-            const float* w = Wk + (long)(u * k + v) * Ci * Co + o0;
-            for (int c = 0; c < Ci; ++c) {
-                const float av = a[c];
+    const bool full = o0 + 4 <= Co;
+    for (int u = 0; u < k; ++u) {
+        const float* arow = A + (((long)b * Hi + (y + u * d)) * Wi + x) * Ci;
+        for (int c = 0; c < Ci; ++c)
+            for (int v0 = 0; v0 < k; v0 += kFirstLayerBatch) {
+                // no branches around the loads (they would be waited for one by one): taps past
+                // the filter's edge read the last tap again and count as zero
+                float av[kFirstLayerBatch];
+                const float* w[kFirstLayerBatch];
 #pragma unroll
-                for (int o = 0; o < 16; ++o)
-                    if (o0 + o < Co) acc[o] = fmaf(av, w[(long)c * Co + o], acc[o]);
+                for (int j = 0; j < kFirstLayerBatch; ++j) {
+                    const int v = v0 + j < k ? v0 + j : k - 1;
+                    av[j] = arow[(long)v * d * Ci + c];
+                    w[j] = Wk + ((long)(u * k + v) * Ci + c) * Co + (full ? o0 : 0);
+                }
+#pragma unroll
+                for (int j = 0; j < kFirstLayerBatch; ++j) {
+                    const float x = v0 + j < k ? av[j] : 0.f;
+                    if (full) {
+#pragma unroll
+                        for (int o = 0; o < 4; ++o) acc[o] = fmaf(x, w[j][o], acc[o]);
+                    } else {
+#pragma unroll
+                        for (int o = 0; o < 4; ++o)
+                            if (o0 + o < Co) acc[o] = fmaf(x, w[j][o0 + o], acc[o]);
+                    }
+                }
             }
-        }
+    }
     float* out = Y + m * Co + o0;
 #pragma unroll
-    for (int o = 0; o < 16; ++o) {
+    for (int o = 0; o < 4; ++o) {
         if (o0 + o < Co) {
-            float r = acc[o] + bias[o0 + o];
-            acc[o] = tanh_out ? fast_tanh(r) : r;
+            const float z = acc[o] + bias[o0 + o];
+            acc[o] = tanh_out ? fast_tanh(z) : z;
         }
     }
-    if ((Co & 3) == 0) {
+    if ((Co & 3) == 0) *reinterpret_cast<v4f*>(out) = (v4f){acc[0], acc[1], acc[2], acc[3]};
+    else {
 #pragma unroll
-        for (int o = 0; o < 16; o += 4)
-            if (o0 + o < Co) *reinterpret_cast<v4f*>(out + o) = (v4f){acc[o], acc[o + 1], acc[o + 2], acc[o + 3]};
-    } else {
-#pragma unroll
-        for (int o = 0; o < 16; ++o)
+        for (int o = 0; o < 4; ++o)
             if (o0 + o < Co) out[o] = acc[o];
     }
+}
+
+// Index plumbing of the two max-filter kernels.  A workgroup takes 256 consecutive
+// (column, channel quad) items of one map row.  Workgroups are handed to the 8 XCDs in
+// turn, so the launch index is first turned into a position in eight contiguous bands of
+// rows, one per XCD: the rows a window straddles (d apart) are then read through the same
+// L2 shortly after each other instead of being fetched from memory once per XCD.
+// All divisions are by launch constants: multiply-high with ceil(2^32 / x) (exact for
+// n * x < 2^32, x > 1).
+struct RowGrid {
+    int gx;            // workgroups per map row
+    int rows;          // B * (rows of the map the threads walk)
+    int h;             // rows per image
+    int C4;            // channel quads
+    unsigned mg_gx, mg_h, mg_c4;
+};
+__device__ __forceinline__ unsigned rg_div(unsigned n, unsigned magic, unsigned x)
+{
+    return x == 1 ? n : __umulhi(n, magic);
+}
+// -> false if this thread has no item; else image b, row y, column x, channel quad c4
+__device__ __forceinline__ bool rg_locate(const RowGrid& g, int width, int* b, int* y, int* x, int* c4)
+{
+    const unsigned nb = gridDim.x, i = blockIdx.x;
+    const unsigned q = nb >> 3, r = nb & 7, xcd = i & 7;
+    const unsigned lb = xcd * q + (xcd < r ? xcd : r) + (i >> 3);   // band of this XCD, then its turn
+    const unsigned row = rg_div(lb, g.mg_gx, g.gx), bx = lb - row * g.gx;
+    const unsigned it = bx * 256 + threadIdx.x;
+    if (it >= (unsigned)(width * g.C4)) return false;
+    const unsigned xx = rg_div(it, g.mg_c4, g.C4);
+    const unsigned bb = rg_div(row, g.mg_h, g.h);
+    *b = (int)bb; *y = (int)(row - bb * g.h); *x = (int)xx; *c4 = (int)(it - xx * g.C4);
+    return true;
 }
 
 // a2, four channels per thread (C % 4 == 0): O = max over the p*p taps d apart, code = tap of
 // the FIRST maximum in row-major (u,v) order (strict > while scanning), packed 4 codes / store.
 __global__ __launch_bounds__(256) void maxfilter_fwd4_kernel(const float* __restrict__ A,
                                                              float* __restrict__ O,
-                                                             uint8_t* __restrict__ code, int B, int Hi,
-                                                             int Wi, int C, int Ho, int Wo, int p, int d)
+                                                             uint8_t* __restrict__ code, RowGrid g,
+                                                             int Hi, int Wi, int C, int Ho, int Wo,
+                                                             int p, int d)
 {
-    const int C4 = C >> 2;
-    const long total = (long)B * Ho * Wo * C4;
-    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
-         e += (long)gridDim.x * blockDim.x) {
-        const int c4 = (int)(e % C4);
-        long q = e / C4;
-        const int x = (int)(q % Wo); q /= Wo;
-        const int y = (int)(q % Ho);
-        const int b = (int)(q / Ho);
-        const float* base = A + (((long)b * Hi + y) * Wi + x) * C + 4 * c4;
-        v4f best = *reinterpret_cast<const v4f*>(base);
-        uint32_t bi[4] = {0, 0, 0, 0};
-        for (int u = 0; u < p; ++u)
-            for (int v = (u == 0 ? 1 : 0); v < p; ++v) {
-                const v4f a = *reinterpret_cast<const v4f*>(base + ((long)u * d * Wi + v * d) * C);
-                const uint32_t t = u * p + v;
+    int b, y, x, c4;
+    if (!rg_locate(g, Wo, &b, &y, &x, &c4)) return;
+    const long e = (((long)b * Ho + y) * Wo + x) * g.C4 + c4;
+    const float* base = A + (((long)b * Hi + y) * Wi + x) * C + 4 * c4;
+    v4f best = *reinterpret_cast<const v4f*>(base);
+    uint32_t bi[4] = {0, 0, 0, 0};
+    for (int u = 0; u < p; ++u)
+        for (int v = (u == 0 ? 1 : 0); v < p; ++v) {
+            const v4f a = *reinterpret_cast<const v4f*>(base + ((long)u * d * Wi + v * d) * C);
+            const uint32_t t = u * p + v;
 #pragma unroll
-                for (int z = 0; z < 4; ++z)
-                    if (a[z] > best[z]) { best[z] = a[z]; bi[z] = t; }
-            }
-        *reinterpret_cast<v4f*>(O + e * 4) = best;
-        if (code) *reinterpret_cast<uint32_t*>(code + e * 4) = bi[0] | (bi[1] << 8) | (bi[2] << 16) | (bi[3] << 24);
-    }
+            for (int z = 0; z < 4; ++z)
+                if (a[z] > best[z]) { best[z] = a[z]; bi[z] = t; }
+        }
+    *reinterpret_cast<v4f*>(O + e * 4) = best;
+    if (code) *reinterpret_cast<uint32_t*>(code + e * 4) = bi[0] | (bi[1] << 8) | (bi[2] << 16) | (bi[3] << 24);
 }
 
 // a7, four channels per thread: dA = sum over the windows that chose this element (gather in
@@ -99,41 +142,35 @@ template <bool TANHP>
 __global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const float* __restrict__ dO,
                                                              const uint8_t* __restrict__ code,
                                                              const float* __restrict__ A,
-                                                             float* __restrict__ dA, int B, int Hi,
-                                                             int Wi, int C, int Ho, int Wo, int p, int d)
+                                                             float* __restrict__ dA, RowGrid g,
+                                                             int Hi, int Wi, int C, int Ho, int Wo,
+                                                             int p, int d)
 {
-    const int C4 = C >> 2;
-    const long total = (long)B * Hi * Wi * C4;
-    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
-         e += (long)gridDim.x * blockDim.x) {
-        const int c4 = (int)(e % C4);
-        long q = e / C4;
-        const int x = (int)(q % Wi); q /= Wi;
-        const int y = (int)(q % Hi);
-        const int b = (int)(q / Hi);
-        v4f acc = {0.f, 0.f, 0.f, 0.f};
-        for (int u = 0; u < p; ++u) {
-            const int yy = y - u * d;
-            if (yy < 0 || yy >= Ho) continue;
-            for (int v = 0; v < p; ++v) {
-                const int xx = x - v * d;
-                if (xx < 0 || xx >= Wo) continue;
-                const long s = (((long)b * Ho + yy) * Wo + xx) * C + 4 * c4;
-                const uint32_t cd = *reinterpret_cast<const uint32_t*>(code + s);
-                const v4f g = *reinterpret_cast<const v4f*>(dO + s);
-                const uint32_t t = u * p + v;
+    int b, y, x, c4;
+    if (!rg_locate(g, Wi, &b, &y, &x, &c4)) return;
+    const long e = (((long)b * Hi + y) * Wi + x) * g.C4 + c4;
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    for (int u = 0; u < p; ++u) {
+        const int yy = y - u * d;
+        if (yy < 0 || yy >= Ho) continue;
+        for (int v = 0; v < p; ++v) {
+            const int xx = x - v * d;
+            if (xx < 0 || xx >= Wo) continue;
+            const long s = (((long)b * Ho + yy) * Wo + xx) * C + 4 * c4;
+            const uint32_t cd = *reinterpret_cast<const uint32_t*>(code + s);
+            const v4f gr = *reinterpret_cast<const v4f*>(dO + s);
+            const uint32_t t = u * p + v;
 #pragma unroll
-                for (int z = 0; z < 4; ++z)
-                    if (((cd >> (8 * z)) & 255u) == t) acc[z] += g[z];
-            }
+            for (int z = 0; z < 4; ++z)
+                if (((cd >> (8 * z)) & 255u) == t) acc[z] += gr[z];
         }
-        if (TANHP) {
-            const v4f a = *reinterpret_cast<const v4f*>(A + e * 4);
-#pragma unroll
-            for (int z = 0; z < 4; ++z) acc[z] *= 1.f - a[z] * a[z];
-        }
-        *reinterpret_cast<v4f*>(dA + e * 4) = acc;
     }
+    if (TANHP) {
+        const v4f a = *reinterpret_cast<const v4f*>(A + e * 4);
+#pragma unroll
+        for (int z = 0; z < 4; ++z) acc[z] *= 1.f - a[z] * a[z];
+    }
+    *reinterpret_cast<v4f*>(dA + e * 4) = acc;
 }
 
 struct ClassArgs {

@@ -390,6 +390,20 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
     return true;
 }
 
+
+// Launch geometry of the max-filter kernels: 256 (column, channel quad) items of one map row
+// per workgroup.  False if the map is too large for their 32-bit index arithmetic.
+bool row_grid(int B, int h, int w, int C4, mpcnn::RowGrid* g)
+{
+    const long per_row = (long)w * C4, gx = (per_row + 255) / 256, rows = (long)B * h;
+    if (gx * rows >= (1l << 31) || gx * rows * gx >= (1l << 32) || (gx * 256) * C4 >= (1l << 32) ||
+        rows * h >= (1l << 32))
+        return false;
+    g->gx = (int)gx; g->rows = (int)rows; g->h = h; g->C4 = C4;
+    g->mg_gx = magic_of((unsigned)gx); g->mg_h = magic_of((unsigned)h); g->mg_c4 = magic_of((unsigned)C4);
+    return true;
+}
+
 inline int grid_for(long total, int block = 256, int cap = 1 << 20)
 {
     long g = (total + block - 1) / block;
@@ -506,10 +520,11 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
         if (ly.kind == MPCNN_MP) {
             uint8_t* code = g.training ? (uint8_t*)(ws + g.code_off[l]) : nullptr;
             long total = (long)B * Ho * Wo * ly.cout;
-            if (ly.cout % 4 == 0)
+            mpcnn::RowGrid rg;
+            if (ly.cout % 4 == 0 && row_grid(B, Ho, Wo, ly.cout / 4, &rg))
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (code ? 9.0 : 8.0),
-                       maxfilter_fwd4_kernel<<<grid_for(total / 4), 256, 0, st>>>(
-                           in, out, code, B, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil));
+                       maxfilter_fwd4_kernel<<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
+                           in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil));
             else
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (code ? 9.0 : 8.0),
                        maxfilter_fwd_direct_kernel<<<grid_for(total), 256, 0, st>>>(
@@ -552,7 +567,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                        launch_conv_mfma(a, ly.fwd_ct, tp, grid, st));
             } else {
                 long total = (long)B * Ho * Wo;
-                dim3 grid((unsigned)((total + 255) / 256), (unsigned)ceil_div(ly.cout, 16));
+                dim3 grid((unsigned)((total + 255) / 256), (unsigned)ceil_div(ly.cout, 4));
                 LAUNCH("first_layer", l, step, flops, bytes,
                        first_layer_kernel<<<grid, 256, 0, st>>>(in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout,
                                                                ly.k, ly.dil, ly.tanh_out ? 1 : 0));
@@ -601,14 +616,16 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
             const uint8_t* code = (const uint8_t*)(ws + g.code_off[li]);
             long total = (long)B * Hi * Wi * Ci;
             const double bytes = n_out * 5.0 + n_in * (below_tanh ? 8.0 : 4.0);
-            if (Ci % 4 == 0 && below_tanh)
+            mpcnn::RowGrid rg;
+            const bool quads = Ci % 4 == 0 && row_grid(B, Hi, Wi, Ci / 4, &rg);
+            if (quads && below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
-                       maxfilter_bwd4_kernel<true><<<grid_for(total / 4), 256, 0, st>>>(
-                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
-            else if (Ci % 4 == 0)
+                       maxfilter_bwd4_kernel<true><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
+                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
+            else if (quads)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
-                       maxfilter_bwd4_kernel<false><<<grid_for(total / 4), 256, 0, st>>>(
-                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
+                       maxfilter_bwd4_kernel<false><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
+                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
             else if (below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        maxfilter_bwd_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
