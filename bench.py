@@ -72,7 +72,8 @@ def main():
     cfg = wl.CONFIGS[args.config]
     img, lab = wl.make_inputs(cfg)
     params = wl.make_params(cfg)
-    net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch)
+    net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch,
+                    dtype=mpcnn.BF16 if cfg.dtype == "bf16" else mpcnn.F32)
     net.set_params(params)
     d_img = torch.from_numpy(img).cuda()
     d_lab = torch.from_numpy(lab).cuda()
@@ -165,6 +166,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "batch": cfg.batch, "height": cfg.height, "width": cfg.width,
                    "patch": cfg.patch, "valid_pixels_per_step": cfg.valid_pixels,
+                   "storage": cfg.dtype,
                    "step": "fwd+bwd" + ("+sgd" if do_sgd else ""), "loss": final_loss},
         "roofline": roofline, "cpu_baseline": cpu,
     }

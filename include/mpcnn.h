@@ -57,7 +57,12 @@ typedef enum {
 
 typedef enum { MPCNN_C = 0, MPCNN_MP = 1, MPCNN_FC = 2 } mpcnn_kind;
 
-/* Storage type of activations and weights; accumulation is always fp32. */
+/* Storage type of activations, deltas and (as read by the kernels) weights; all arithmetic,
+ * sums, the softmax, the loss and the parameter gradients are fp32 or wider.  MPCNN_BF16:
+ * every activation and delta tensor (the channels-last copy of the image included) is rounded
+ * to bf16, nearest-even, when it is stored; the kernels read the parameters rounded to bf16
+ * while the fp32 originals remain what mpcnn_sgd_step updates and mpcnn_get_params returns.
+ * Images, labels, weights, probabilities and gradients cross the boundary in fp32 either way. */
 typedef enum { MPCNN_F32 = 0, MPCNN_BF16 = 1 } mpcnn_dtype;
 
 /* One layer (Background, layer kinds).  C: `maps` output maps, k x k filters.
@@ -76,7 +81,9 @@ typedef struct {
  * Errors: EINVAL (null / counts / kinds), ESHAPE (a layer does not fit; no FC
  * at the end; C or MP after an FC), EUNSUPPORTED (a pool whose input side, in
  * patch coordinates, is not a multiple of k; k*k > 255; more than 16 classes;
- * dtype other than MPCNN_F32).
+ * MPCNN_BF16 with a layer the matrix-core and fused kernels do not take: channel
+ * counts must be multiples of 4 and, between layers, at least 8; the last FC must
+ * have 2-4 classes on at most 256 inputs that are a multiple of 4).
  */
 mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers_host, int n_layers, int in_channels,
                               int patch, mpcnn_dtype dtype, mpcnn_net** out);

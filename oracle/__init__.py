@@ -74,8 +74,10 @@ def run(layers, in_ch, patch, params, image, labels=None, pixw=None, sel=None,
 
     tie_tau > 0: also returns `near_ties`, an int64 array [n,4] of (window key,
     chosen tap, runner-up tap, layer) for every pooling window whose two largest
-    values are within tie_tau; `alt`: keys of such windows whose runner-up tap is
-    to receive the gradient instead (see orc_ties in the C source)."""
+    values are within tie_tau; `alt`: (window key, tap) pairs - in those windows
+    the named tap is to receive the gradient instead, which the oracle accepts only
+    if that tap's value is within tie_tau of the maximum; `alt_rejected` counts the
+    refusals, once per patch that contains the window (see orc_ties in the C source)."""
     lib = _load()
     kinds, maps, ks, n = _desc(layers)
     params = np.ascontiguousarray(params, dtype=np.float64)
@@ -100,40 +102,50 @@ def run(layers, in_ch, patch, params, image, labels=None, pixw=None, sel=None,
     probs = None
     if want_probs:
         probs = np.zeros((n_sel, n_cls) if sel is not None else (B, n_cls, Ho, Wo))
-    loss = C.c_double(0.0)
     grads = np.zeros(npar) if want_grads else None
     dimage = np.zeros_like(image) if want_dimage else None
-    amb_cap = 1 << 20
-    amb = np.zeros((amb_cap, 4), dtype=np.int64) if tie_tau > 0 else None
-    amb_n = C.c_long(0)
     n_alt = 0
-    if alt is not None:
-        alt = np.ascontiguousarray(np.unique(np.asarray(alt, dtype=np.int64)))
-        n_alt = alt.size
-    rc = lib.orc_run(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch, patch,
-                     _p(params, C.c_double), _p(image, C.c_double), B, H, W,
-                     _p(labels, C.c_int32), _p(pixw, C.c_double), _p(sel, C.c_int64),
-                     C.c_long(n_sel), _p(probs, C.c_double),
-                     C.byref(loss) if labels is not None else None,
-                     _p(grads, C.c_double), _p(dimage, C.c_double),
-                     C.c_double(tie_tau), _p(alt, C.c_int64), C.c_long(n_alt),
-                     _p(amb, C.c_int64), C.c_long(amb_cap if amb is not None else 0),
-                     C.byref(amb_n))
-    if rc != 0:
-        raise ValueError("orc_run failed (code %d)" % rc)
+    alt_key = alt_tap = None
+    if alt is not None and len(alt):
+        pairs = np.unique(np.asarray(alt, dtype=np.int64).reshape(-1, 2), axis=0)
+        assert np.unique(pairs[:, 0]).size == pairs.shape[0], "a window is listed with two taps"
+        alt_key = np.ascontiguousarray(pairs[:, 0])
+        alt_tap = np.ascontiguousarray(pairs[:, 1].astype(np.uint8))
+        n_alt = alt_key.size
+    amb_cap = 1 << 20
+    while True:
+        amb = np.zeros((amb_cap, 4), dtype=np.int64) if tie_tau > 0 else None
+        amb_n = C.c_long(0)
+        rejected = C.c_long(0)
+        loss = C.c_double(0.0)
+        for out in (probs, grads, dimage):
+            if out is not None:
+                out[...] = 0.0
+        rc = lib.orc_run(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch, patch,
+                         _p(params, C.c_double), _p(image, C.c_double), B, H, W,
+                         _p(labels, C.c_int32), _p(pixw, C.c_double), _p(sel, C.c_int64),
+                         C.c_long(n_sel), _p(probs, C.c_double),
+                         C.byref(loss) if labels is not None else None,
+                         _p(grads, C.c_double), _p(dimage, C.c_double),
+                         C.c_double(tie_tau), _p(alt_key, C.c_int64), _p(alt_tap, C.c_uint8), C.c_long(n_alt),
+                         _p(amb, C.c_int64), C.c_long(amb_cap if amb is not None else 0),
+                         C.byref(amb_n), C.byref(rejected))
+        if rc != 0:
+            raise ValueError("orc_run failed (code %d)" % rc)
+        if amb is None or amb_n.value <= amb_cap:
+            break
+        amb_cap = amb_n.value   # the record buffer was too small (a window is met once per patch): again
     near = None
     if amb is not None:
-        if amb_n.value > amb_cap:
-            raise ValueError("more than %d near-tie records" % amb_cap)
         near = np.unique(amb[:amb_n.value], axis=0)
     return {"probs": probs, "loss": loss.value if labels is not None else None,
-            "grads": grads, "dimage": dimage, "near_ties": near}
+            "grads": grads, "dimage": dimage, "near_ties": near, "alt_rejected": rejected.value}
 
 
 def window_key(layers, in_ch, patch, B, H, W, layer, b, c, y, x):
     """Key of a pooling window in the whole-image map of MP layer `layer` (see orc_ties)."""
     _, ch, ny, nx = dense_shape(layers, in_ch, patch, B, H, W, layer)[:4]
-    return (((layer * B + b) * ch + c) * ny + y) * nx + x
+    return (layer << 48) + ((b * ch + c) * ny + y) * nx + x
 
 
 def dense_shape(layers, in_ch, patch, B, H, W, layer):

@@ -102,28 +102,32 @@ static int orc_make_plan(orc_plan *pl, const int *kinds, const int *maps, const 
  * rankings are then valid sub-gradients of the max.  So that such a result can
  * be checked exactly, the oracle can (a) report every window whose two largest
  * values are within `tau` of each other, with the tap it chose and the
- * runner-up tap, and (b) re-run with a list `alt` of such windows in which the
- * runner-up tap receives the back-propagated value instead (the forward value
- * stays the true maximum).  A window is named by its position in the
- * whole-image map of that MP layer: key = (((layer*B + b)*C + c)*ny + y)*nx + x.
+ * runner-up tap, and (b) re-run with a list `alt` of (window, tap) pairs: in a
+ * listed window the named tap receives the back-propagated value instead,
+ * PROVIDED its value is within `tau` of the window's maximum (with coarse
+ * storage more than two taps can be that close); a pair that names a tap
+ * further away is counted in *rejected and ignored.  The forward value stays
+ * the true maximum.  A window is named by its position in the whole-image map
+ * of that MP layer: key = layer * 2^48 + ((b*C + c)*ny + y)*nx + x.
  * With tau = 0 and no list this is the plain first-maximum rule.
  */
 typedef struct {
     double tau;
-    const int64_t *alt; long n_alt;          /* sorted keys */
+    const int64_t *alt; const uint8_t *alt_tap; long n_alt;   /* sorted keys and their taps */
     int64_t *amb; long amb_cap; long *amb_n; /* records of 4: key, chosen tap, runner-up tap, layer */
+    long *rejected;                          /* listed pairs whose tap is not within tau of the maximum */
     int B, H, W;                             /* image batch and size, for the keys */
 } orc_ties;
 
-static int orc_key_listed(const orc_ties *t, int64_t key)
+static long orc_key_listed(const orc_ties *t, int64_t key)   /* index in alt, or -1 */
 {
     long lo = 0, hi = t->n_alt - 1;
     while (lo <= hi) {
         long mid = (lo + hi) / 2;
-        if (t->alt[mid] == key) return 1;
+        if (t->alt[mid] == key) return mid;
         if (t->alt[mid] < key) lo = mid + 1; else hi = mid - 1;
     }
-    return 0;
+    return -1;
 }
 
 /* Forward of ONE patch.  act: all layer outputs; idx: argmax codes u*p+v of
@@ -153,13 +157,13 @@ static void orc_patch_forward(const orc_plan *pl, const double *par, double *act
                             }
                         long e = ((long)c * m + r) * m + s;
                         y[e] = best;
-                        if (ties && code2 >= 0 && best - second <= ties->tau) {
+                        if (ties && code2 >= 0 && (best - second <= ties->tau || ties->n_alt > 0)) {
                             const int st = pl->stride_out[l];
                             const long ny = ties->H - pl->patch + pl->reach_out[l] + 1;
                             const long nx = ties->W - pl->patch + pl->reach_out[l] + 1;
-                            int64_t key = ((((int64_t)l * ties->B + pb) * co + c) * ny + (pi + r * st)) * nx
-                                          + (pj + s * st);
-                            if (ties->amb) {
+                            int64_t key = ((int64_t)l << 48) +
+                                          (((int64_t)pb * co + c) * ny + (pi + r * st)) * nx + (pj + s * st);
+                            if (ties->amb && best - second <= ties->tau) {
 #pragma omp critical(orc_amb)
                                 {
                                     long q = (*ties->amb_n)++;
@@ -169,7 +173,18 @@ static void orc_patch_forward(const orc_plan *pl, const double *par, double *act
                                     }
                                 }
                             }
-                            if (ties->n_alt > 0 && orc_key_listed(ties, key)) code = code2;
+                            const long at = ties->n_alt > 0 ? orc_key_listed(ties, key) : -1;
+                            if (at >= 0) {
+                                const int tap = ties->alt_tap[at];
+                                const int tu = tap / k, tv = tap % k;
+                                if (tap < k * k &&
+                                    best - x[((long)c * n + (k * r + tu)) * n + (k * s + tv)] <= ties->tau)
+                                    code = tap;
+                                else {
+#pragma omp atomic
+                                    (*ties->rejected)++;
+                                }
+                            }
                         }
                         idx[pl->idx_off[l] + e] = (uint8_t)code;
                         if (gap) gap[pl->idx_off[l] + e] = (k * k > 1) ? best - second : INFINITY;
@@ -289,16 +304,16 @@ int orc_threads(void)
  *   dimage  [B][in_ch][H][W] dL/d(image), sum over patches (may be NULL; small inputs)
  * Output pixel (i,j) is the patch with top-left corner (i,j); its label and
  * weight are read at image pixel (i+c, j+c), c = (P-1)/2 rounded down.
- *   tie_tau, alt, amb: near-tie reporting / alternative routing (see orc_ties);
- *   amb receives up to amb_cap records of 4 int64, *amb_n the number met (the
- *   same window is reported once per patch that contains it).
+ *   tie_tau, alt + alt_tap, amb, rejected: near-tie reporting / alternative routing (see
+ *   orc_ties); amb receives up to amb_cap records of 4 int64, *amb_n the number met, and
+ *   *rejected the number of refused pairs (a window is met once per patch that contains it).
  */
 int orc_run(const int *kinds, const int *maps, const int *ks, int n_layers, int in_ch, int patch,
             const double *params, const double *image, int B, int H, int W,
             const int32_t *labels, const double *pixw, const int64_t *sel, long n_sel,
             double *probs, double *loss, double *grads, double *dimage,
-            double tie_tau, const int64_t *alt, long n_alt,
-            int64_t *amb, long amb_cap, long *amb_n)
+            double tie_tau, const int64_t *alt, const uint8_t *alt_tap, long n_alt,
+            int64_t *amb, long amb_cap, long *amb_n, long *rejected)
 {
     orc_plan pl;
     int rc = orc_make_plan(&pl, kinds, maps, ks, n_layers, in_ch, patch);
@@ -313,8 +328,10 @@ int orc_run(const int *kinds, const int *maps, const int *ks, int n_layers, int 
     double *di_all = dimage ? calloc((size_t)nt * n_img, sizeof(double)) : NULL;
     double *loss_all = calloc((size_t)nt, sizeof(double));
     int fail = 0;
-    long amb_dummy = 0;
-    orc_ties ties = { tie_tau, alt, alt ? n_alt : 0, amb, amb_cap, amb_n ? amb_n : &amb_dummy, B, H, W };
+    long amb_dummy = 0, rej_dummy = 0;
+    orc_ties ties = { tie_tau, alt, alt_tap, (alt && alt_tap) ? n_alt : 0, amb, amb_cap,
+                      amb_n ? amb_n : &amb_dummy, rejected ? rejected : &rej_dummy, B, H, W };
+    if (rejected) *rejected = 0;
     const orc_ties *tp = (tie_tau > 0 || ties.n_alt > 0) ? &ties : NULL;
     if (amb_n) *amb_n = 0;
 #pragma omp parallel num_threads(nt)

@@ -10,10 +10,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "storage.hpp"
+
 namespace mpcnn {
 
-// a0: planar [B][C][H][W] -> channels-last [B][H][W][C]
-__global__ void stage_input_kernel(const float* __restrict__ src, float* __restrict__ dst, int B,
+// a0: planar fp32 [B][C][H][W] -> channels-last [B][H][W][C] in the storage type
+template <typename T>
+__global__ void stage_input_kernel(const float* __restrict__ src, T* __restrict__ dst, int B,
                                    int C, int H, int W)
 {
     long total = (long)B * C * H * W;
@@ -25,7 +28,7 @@ __global__ void stage_input_kernel(const float* __restrict__ src, float* __restr
         long q = p / W;
         int y = (int)(q % H);
         int b = (int)(q / H);
-        dst[e] = src[(((long)b * C + c) * H + y) * W + x];
+        store1(dst + e, src[(((long)b * C + c) * H + y) * W + x]);
     }
 }
 
@@ -229,6 +232,14 @@ __global__ void sgd_kernel(float* __restrict__ theta, const float* __restrict__ 
 {
     long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e < n) theta[e] = fmaf(-step, g[e], theta[e]);
+}
+
+// bf16 storage: the kernels read parameters rounded to bf16 (kept as fp32 values); the fp32
+// originals stay the optimiser's state.
+__global__ void round_params_kernel(const float* __restrict__ theta, float* __restrict__ rounded, long n)
+{
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (long)gridDim.x * blockDim.x)
+        rounded[e] = (float)(bf16)theta[e];
 }
 
 }  // namespace mpcnn

@@ -17,9 +17,10 @@ namespace mpcnn {
 // the tap loads; the taps of one filter row are fetched together.  Weights are wave-uniform
 // (scalar loads).
 constexpr int kFirstLayerBatch = 8;   // taps of a filter row fetched together
-__global__ __launch_bounds__(256) void first_layer_kernel(const float* __restrict__ A,
+template <typename T>
+__global__ __launch_bounds__(256) void first_layer_kernel(const T* __restrict__ A,
                                                           const float* __restrict__ Wk,
-                                                          float* __restrict__ Y, int B, int Hi, int Wi,
+                                                          T* __restrict__ Y, int B, int Hi, int Wi,
                                                           int Ci, int Ho, int Wo, int Co, int k, int d,
                                                           int tanh_out)
 {
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(256) void first_layer_kernel(const float* __restric
     const float* bias = Wk + (long)k * k * Ci * Co;
     const bool full = o0 + 4 <= Co;
     for (int u = 0; u < k; ++u) {
-        const float* arow = A + (((long)b * Hi + (y + u * d)) * Wi + x) * Ci;
+        const T* arow = A + (((long)b * Hi + (y + u * d)) * Wi + x) * Ci;
         for (int c = 0; c < Ci; ++c)
             for (int v0 = 0; v0 < k; v0 += kFirstLayerBatch) {
                 // no branches around the loads (they would be waited for one by one): taps past
@@ -44,7 +45,7 @@ __global__ __launch_bounds__(256) void first_layer_kernel(const float* __restric
 #pragma unroll
                 for (int j = 0; j < kFirstLayerBatch; ++j) {
                     const int v = v0 + j < k ? v0 + j : k - 1;
-                    av[j] = arow[(long)v * d * Ci + c];
+                    av[j] = load1(arow + (long)v * d * Ci + c);
                     w[j] = Wk + ((long)(u * k + v) * Ci + c) * Co + (full ? o0 : 0);
                 }
 #pragma unroll
@@ -61,7 +62,7 @@ __global__ __launch_bounds__(256) void first_layer_kernel(const float* __restric
                 }
             }
     }
-    float* out = Y + m * Co + o0;
+    T* out = Y + m * Co + o0;
 #pragma unroll
     for (int o = 0; o < 4; ++o) {
         if (o0 + o < Co) {
@@ -69,11 +70,11 @@ __global__ __launch_bounds__(256) void first_layer_kernel(const float* __restric
             acc[o] = tanh_out ? fast_tanh(z) : z;
         }
     }
-    if ((Co & 3) == 0) *reinterpret_cast<v4f*>(out) = (v4f){acc[0], acc[1], acc[2], acc[3]};
+    if ((Co & 3) == 0) store4(out, (v4f){acc[0], acc[1], acc[2], acc[3]});
     else {
 #pragma unroll
         for (int o = 0; o < 4; ++o)
-            if (o0 + o < Co) out[o] = acc[o];
+            if (o0 + o < Co) store1(out + o, acc[o]);
     }
 }
 
@@ -112,8 +113,9 @@ __device__ __forceinline__ bool rg_locate(const RowGrid& g, int width, int* b, i
 
 // a2, four channels per thread (C % 4 == 0): O = max over the p*p taps d apart, code = tap of
 // the FIRST maximum in row-major (u,v) order (strict > while scanning), packed 4 codes / store.
-__global__ __launch_bounds__(256) void maxfilter_fwd4_kernel(const float* __restrict__ A,
-                                                             float* __restrict__ O,
+template <typename T>
+__global__ __launch_bounds__(256) void maxfilter_fwd4_kernel(const T* __restrict__ A,
+                                                             T* __restrict__ O,
                                                              uint8_t* __restrict__ code, RowGrid g,
                                                              int Hi, int Wi, int C, int Ho, int Wo,
                                                              int p, int d)
@@ -121,28 +123,28 @@ __global__ __launch_bounds__(256) void maxfilter_fwd4_kernel(const float* __rest
     int b, y, x, c4;
     if (!rg_locate(g, Wo, &b, &y, &x, &c4)) return;
     const long e = (((long)b * Ho + y) * Wo + x) * g.C4 + c4;
-    const float* base = A + (((long)b * Hi + y) * Wi + x) * C + 4 * c4;
-    v4f best = *reinterpret_cast<const v4f*>(base);
+    const T* base = A + (((long)b * Hi + y) * Wi + x) * C + 4 * c4;
+    v4f best = load4(base);
     uint32_t bi[4] = {0, 0, 0, 0};
     for (int u = 0; u < p; ++u)
         for (int v = (u == 0 ? 1 : 0); v < p; ++v) {
-            const v4f a = *reinterpret_cast<const v4f*>(base + ((long)u * d * Wi + v * d) * C);
+            const v4f a = load4(base + ((long)u * d * Wi + v * d) * C);
             const uint32_t t = u * p + v;
 #pragma unroll
             for (int z = 0; z < 4; ++z)
                 if (a[z] > best[z]) { best[z] = a[z]; bi[z] = t; }
         }
-    *reinterpret_cast<v4f*>(O + e * 4) = best;
+    store4(O + e * 4, best);   // a value read back unchanged: exact in either storage type
     if (code) *reinterpret_cast<uint32_t*>(code + e * 4) = bi[0] | (bi[1] << 8) | (bi[2] << 16) | (bi[3] << 24);
 }
 
 // a7, four channels per thread: dA = sum over the windows that chose this element (gather in
 // fixed (u,v) order, no atomics), times (1 - A^2) when A is a tanh output.
-template <bool TANHP>
-__global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const float* __restrict__ dO,
+template <bool TANHP, typename T>
+__global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const T* __restrict__ dO,
                                                              const uint8_t* __restrict__ code,
-                                                             const float* __restrict__ A,
-                                                             float* __restrict__ dA, RowGrid g,
+                                                             const T* __restrict__ A,
+                                                             T* __restrict__ dA, RowGrid g,
                                                              int Hi, int Wi, int C, int Ho, int Wo,
                                                              int p, int d)
 {
@@ -158,7 +160,7 @@ __global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const float* __rest
             if (xx < 0 || xx >= Wo) continue;
             const long s = (((long)b * Ho + yy) * Wo + xx) * C + 4 * c4;
             const uint32_t cd = *reinterpret_cast<const uint32_t*>(code + s);
-            const v4f gr = *reinterpret_cast<const v4f*>(dO + s);
+            const v4f gr = load4(dO + s);
             const uint32_t t = u * p + v;
 #pragma unroll
             for (int z = 0; z < 4; ++z)
@@ -166,20 +168,20 @@ __global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const float* __rest
         }
     }
     if (TANHP) {
-        const v4f a = *reinterpret_cast<const v4f*>(A + e * 4);
+        const v4f a = load4(A + e * 4);
 #pragma unroll
         for (int z = 0; z < 4; ++z) acc[z] *= 1.f - a[z] * a[z];
     }
-    *reinterpret_cast<v4f*>(dA + e * 4) = acc;
+    store4(dA + e * 4, acc);
 }
 
 struct ClassArgs {
-    const float* h;        // [M][K] input of the class layer
+    const void* h;         // [M][K] input of the class layer (storage type T)
     const float* Wk;       // [K][NCLS] then bias [NCLS]
     float* probs;          // [B][NCLS][Ho][Wo] or null
     const int32_t* labels; // [B][H][W]      (training)
     const float* pixw;     // [B][H][W] or null
-    float* dH;             // [M][K]         (training) delta w.r.t. the pre-activation below
+    void* dH;              // [M][K]         (training) delta w.r.t. the pre-activation below (T)
     float* partial;        // [blocks][(K+1)*NCLS]  (training) this block's share of dW, db
     double* loss_partial;  // [blocks] or null
     int B, Ho, Wo, H, W, ctr, K, tanh_below;
@@ -191,9 +193,11 @@ struct ClassArgs {
 // pixel; Method: first step of back-propagation; Alg. 2 for the sums).
 // 16 lanes share one position: lane j holds channels 4(j+16v)..+3, v < KV; dot products meet
 // by xor-shuffles in a fixed order.  A workgroup walks 16 positions at a time.
-template <int NCLS, int KV, bool TRAIN>
+template <int NCLS, int KV, bool TRAIN, typename T>
 __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
 {
+    const T* h_t = static_cast<const T*>(a.h);
+    T* dh_t = static_cast<T*>(a.dH);
     __shared__ float red[4][KV * 4 * NCLS + NCLS][16];
     __shared__ double lred[16];
     const int tid = threadIdx.x, j = tid & 15, grp = tid >> 4, wave = tid >> 6;
@@ -223,7 +227,7 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
 #pragma unroll
         for (int v = 0; v < KV; ++v) {
             const int c = 4 * (j + 16 * v);
-            hv[v] = c < a.K ? *reinterpret_cast<const v4f*>(a.h + m * a.K + c) : (v4f){0.f, 0.f, 0.f, 0.f};
+            hv[v] = c < a.K ? load4(h_t + m * a.K + c) : (v4f){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
                     }
                     dh[s] = a.tanh_below ? g * (1.f - hv[v][s] * hv[v][s]) : g;
                 }
-                if (c < a.K) *reinterpret_cast<v4f*>(a.dH + m * a.K + c) = dh;
+                if (c < a.K) store4(dh_t + m * a.K + c, dh);
             }
         }
     }

@@ -22,10 +22,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-namespace mpcnn {
+#include "storage.hpp"
 
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef float v16f __attribute__((ext_vector_type(16)));
+namespace mpcnn {
 
 // tanh(x) = 1 - 2 / (exp(2x) + 1) with the hardware exp2 and reciprocal: absolute error
 // about 1e-7; saturates correctly (exp -> inf gives 1, exp -> 0 gives -1).
@@ -38,11 +37,12 @@ __device__ __forceinline__ float fast_tanh(float x)
 enum ConvMode { kFwdTanh = 0, kFwdLinear = 1, kDgradTanh = 2, kDgradPlain = 3 };
 
 struct ConvArgs {
-    const float* in;     // [B][Hi][Wi][Cr]   tensor the taps read (activations, or deltas for dgrad)
+    // tensors are fp32 or bf16 (the kernel's template parameter T)
+    const void* in;      // [B][Hi][Wi][Cr]   tensor the taps read (activations, or deltas for dgrad)
     const v4f* wpack;    // [steps][G][CoPad] x 4 channels, steps = k*k*CrPad/(4G)
     const float* bias;   // [Co]   (forward modes)
-    const float* act;    // [B][Ho][Wo][Co] tanh output at the positions written (kDgradTanh)
-    float* out;          // [B][Ho][Wo][Co]
+    const void* act;     // [B][Ho][Wo][Co] tanh output at the positions written (kDgradTanh)
+    void* out;           // [B][Ho][Wo][Co]
     int B, Hi, Wi, Cr, CrPad;   // CrPad: Cr rounded up to a multiple of 16
     int Ho, Wo, Co, CoPad;
     int k, d;
@@ -97,9 +97,12 @@ __device__ __forceinline__ typename MfmaAcc<W>::type mfma_f32(float a, float b, 
 // LDS, where all threads add them in wave order, apply the epilogue and store.  With 8
 // waves one workgroup fills a CU (two waves per SIMD that are always in the same phase).  Summation order is the same for every position, so equal inputs
 // give bit-equal outputs (exact pooling ties stay exact).
-template <int W, int OT, int PT, int NW>
+template <int W, int OT, int PT, int NW, typename T>
 __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
 {
+    const T* in_t = static_cast<const T*>(a.in);
+    const T* act_t = static_cast<const T*>(a.act);
+    T* out_t = static_cast<T*>(a.out);
     constexpr int G = 64 / W;          // lane groups = contraction index of one MFMA
     constexpr int QT = W / 4;          // 4-channel quads per output tile
     constexpr int NQ = W * W / 256;    // quads one lane holds of one result tile
@@ -149,8 +152,7 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
                     const int iy = fy * a.d + ry, ix = fx * a.d + rx;
                     dst[u] = pos * Cs4 + q;
                     if (fy >= 0 && fx >= 0 && iy < a.Hi && ix < a.Wi && 4 * q < a.Cr)
-                        v[u] = *reinterpret_cast<const v4f*>(
-                            a.in + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + 4 * q);
+                        v[u] = load4(in_t + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + 4 * q);
                 }
             }
 #pragma unroll
@@ -285,8 +287,8 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
             yv[it] = (v4f){0.f, 0.f, 0.f, 0.f};
             if (a.mode == kDgradTanh && live[it]) {
                 const long off = pos_off + oc;
-                if ((a.Co & 3) == 0) yv[it] = *reinterpret_cast<const v4f*>(a.act + off);
-                else for (int z = 0; z < 4; ++z) if (oc + z < a.Co) yv[it][z] = a.act[off + z];
+                if ((a.Co & 3) == 0) yv[it] = load4(act_t + off);
+                else for (int z = 0; z < 4; ++z) if (oc + z < a.Co) yv[it][z] = load1(act_t + off + z);
             }
         }
 #pragma unroll
@@ -307,8 +309,8 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
 #pragma unroll
                 for (int z = 0; z < 4; ++z) s[z] *= 1.f - yv[it][z] * yv[it][z];
             }
-            if (nv == 4 && (a.Co & 3) == 0) *reinterpret_cast<v4f*>(a.out + off) = s;
-            else for (int z = 0; z < nv; ++z) a.out[off + z] = s[z];
+            if (nv == 4 && (a.Co & 3) == 0) store4(out_t + off, s);
+            else for (int z = 0; z < nv; ++z) store1(out_t + off + z, s[z]);
         }
     }
 }

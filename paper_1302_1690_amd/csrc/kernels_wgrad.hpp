@@ -35,8 +35,8 @@ constexpr int kWgStageH = 8;      // 128-bit items of the input halo one thread 
 constexpr int kWgStageD = 8;      // ... of the delta tile
 
 struct WgradArgs {
-    const float* in;     // [B][Hi][Wi][Ci]  layer input (activations)
-    const float* dY;     // [B][Ho][Wo][Co]  delta w.r.t. the layer's pre-activation
+    const void* in;      // [B][Hi][Wi][Ci]  layer input (activations), fp32 or bf16 (template parameter T)
+    const void* dY;      // [B][Ho][Wo][Co]  delta w.r.t. the layer's pre-activation, same type
     float* partial;      // [slabs][Mt*Nt result tiles][4][64 lanes][4] then [Nt*32] bias sums
     int B, Hi, Wi, Ci;
     int Ho, Wo, Co;
@@ -56,7 +56,7 @@ __device__ __forceinline__ unsigned magic_div(unsigned n, unsigned magic, unsign
     return x == 1 ? n : __umulhi(n, magic);
 }
 
-template <int MW>
+template <int MW, typename T>
 __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
 {
     constexpr int HL = kWgStageH, DL = kWgStageD;
@@ -168,8 +168,8 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
         }
         auto stage = [&](int tile, float* buf) {
             const TileGeom t = decode(tile);
-            const char* in_b = (const char*)(a.in + (long)t.b * a.Hi * a.Wi * a.Ci);
-            const char* dy_b = (const char*)(a.dY + (long)t.b * a.Ho * a.Wo * a.Co);
+            const T* in_b = static_cast<const T*>(a.in) + (long)t.b * a.Hi * a.Wi * a.Ci;
+            const T* dy_b = static_cast<const T*>(a.dY) + (long)t.b * a.Ho * a.Wo * a.Co;
             const int y0 = t.ty0 * a.d + t.ry, x0 = t.tx0 * a.d + t.rx;
             const int dbase = (y0 * a.Wo + x0) * a.Co;
             v4f hr[HL], dr[DL];
@@ -181,25 +181,23 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                 iy = iy < a.Hi ? iy : a.Hi - 1;
                 ix = ix < a.Wi ? ix : a.Wi - 1;
                 const int q4 = h_dst[u] < 0 ? 0 : h_dst[u] >> 20;
-                const unsigned off = 4u * ((unsigned)(iy * a.Wi + ix) * a.Ci + q4);
-                if (vec_in) hr[u] = *reinterpret_cast<const v4f*>(in_b + off);
+                const unsigned off = (unsigned)(iy * a.Wi + ix) * a.Ci + q4;   // in elements
+                if (vec_in) hr[u] = load4(in_b + off);
                 else {
 #pragma unroll
-                    for (int z = 0; z < 4; ++z)
-                        hr[u][z] = q4 + z < a.Ci ? *reinterpret_cast<const float*>(in_b + off + 4 * z) : 0.f;
+                    for (int z = 0; z < 4; ++z) hr[u][z] = q4 + z < a.Ci ? load1(in_b + off + z) : 0.f;
                 }
             }
 #pragma unroll
             for (int u = 0; u < DL; ++u) {
                 const bool ok = d_rel[u] >= 0 && (int)(d_tyx[u] >> 16) < t.rows && (int)(d_tyx[u] & 0xffffu) < t.cols;
                 okmask |= ok ? (1u << u) : 0u;
-                const unsigned off = ok ? 4u * (unsigned)(dbase + d_rel[u]) : 0u;
-                if (vec_dy) dr[u] = *reinterpret_cast<const v4f*>(dy_b + off);
+                const unsigned off = ok ? (unsigned)(dbase + d_rel[u]) : 0u;   // in elements
+                if (vec_dy) dr[u] = load4(dy_b + off);
                 else {
                     const int oc = ok ? d_rel[u] % a.Co : 0;   // rare path: Co not a multiple of 4
 #pragma unroll
-                    for (int z = 0; z < 4; ++z)
-                        dr[u][z] = (ok && oc + z < a.Co) ? *reinterpret_cast<const float*>(dy_b + off + 4 * z) : 0.f;
+                    for (int z = 0; z < 4; ++z) dr[u][z] = (ok && oc + z < a.Co) ? load1(dy_b + off + z) : 0.f;
                 }
             }
 #pragma unroll

@@ -14,6 +14,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/mpcnn.h"
@@ -114,7 +115,8 @@ struct Geom {
     std::vector<size_t> code_off;     // MP layers: byte offset of the argmax map
     std::vector<TilePlan> fwd, dgrad;
     std::vector<WgradPlan> wgrad;
-    size_t staged_off = 0;            // channels-last copy of the image (C0 > 1 only)
+    bool staged = false;              // the image is copied to channels-last storage first
+    size_t staged_off = 0;            // that copy (C0 > 1, or bf16 storage)
     size_t delta_off[2] = {0, 0};     // two delta buffers, each as large as the largest map
     std::vector<size_t> partial_off;  // per parametrised layer: its slab / block partial sums
     std::vector<int> partial_n;
@@ -136,7 +138,10 @@ struct mpcnn_net {
     std::vector<Layer> layers;
     int in_ch = 0, patch = 0, n_cls = 0;
     size_t n_params = 0, pack_len = 0;
+    bool bf16 = false;            // activations and deltas stored in bf16 (arithmetic stays fp32)
     float* d_params = nullptr;
+    float* d_wread = nullptr;     // what the kernels read: d_params, or its copy rounded to bf16 values
+    bool wread_stale = true;
     float* d_grads = nullptr;
     float* d_packs = nullptr;
     bool packs_stale = true;
@@ -260,8 +265,9 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
     WgradPlan w;
     const int d = ly.dil, k = ly.k;
     const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
-    const bool fits32 = (size_t)in_r * in_c * ly.cin * 4 < (1ull << 31) &&
-                        (size_t)out_r * out_c * ly.cout * 4 < (1ull << 31) && (k + 3) * d < 65536;
+    // the kernel forms element offsets inside one image in 32 bits
+    const bool fits32 = (size_t)in_r * in_c * ly.cin < (1ull << 31) &&
+                        (size_t)out_r * out_c * ly.cout < (1ull << 31) && (k + 3) * d < 65536;
     if (ly.wgrad_mfma && fits32) {
         // split of the four waves over result rows / columns / tile rows: least padded work,
         // then fewest workgroup groups (each group stages the tiles again)
@@ -331,9 +337,11 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
     g->fwd.assign(L, TilePlan()); g->dgrad.assign(L, TilePlan()); g->wgrad.assign(L, WgradPlan());
     g->partial_off.assign(L, 0); g->partial_n.assign(L, 0); g->partial_len.assign(L, 0);
     size_t off = 0, max_act = 0;
-    if (net->in_ch > 1) {
+    const size_t es = net->bf16 ? 2 : 4;   // bytes per stored activation / delta element
+    g->staged = net->in_ch > 1 || net->bf16;
+    if (g->staged) {
         g->staged_off = off;
-        off = align_up(off + sizeof(float) * (size_t)B * H * W * net->in_ch);
+        off = align_up(off + es * (size_t)B * H * W * net->in_ch);
     }
     int r = H, c = W;
     for (size_t l = 0; l < L; ++l) {
@@ -343,7 +351,7 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         c -= (ly.k - 1) * ly.dil;
         if (r < 1 || c < 1) return false;
         g->rows[l] = r; g->cols[l] = c;
-        size_t bytes = sizeof(float) * (size_t)B * r * c * ly.cout;
+        size_t bytes = es * (size_t)B * r * c * ly.cout;
         max_act = std::max(max_act, bytes);
         if (ly.kind == MPCNN_MP) continue;
         if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.k, ly.fwd_rpad, ly.fwd_ct);
@@ -365,7 +373,7 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
             const Layer& ly = net->layers[l];
             size_t elems = (size_t)B * g->rows[l] * g->cols[l] * ly.cout;
             g->act_off[l] = off;
-            off = align_up(off + sizeof(float) * elems);
+            off = align_up(off + es * elems);
             if (ly.kind == MPCNN_MP) {
                 g->code_off[l] = off;
                 off = align_up(off + elems);
@@ -411,18 +419,19 @@ inline int grid_for(long total, int block = 256, int cap = 1 << 20)
 }
 
 // ------------------------------------------------------------------ MFMA launches
-template <int W, int OT, int PT, int NW>
+template <int W, int OT, int PT, int NW, typename T>
 void launch_conv_inst(const mpcnn::ConvArgs& a, dim3 grid, size_t lds, hipStream_t st)
 {
-    mpcnn::conv_mfma_kernel<W, OT, PT, NW><<<grid, 64 * NW, lds, st>>>(a);
+    mpcnn::conv_mfma_kernel<W, OT, PT, NW, T><<<grid, 64 * NW, lds, st>>>(a);
 }
+template <typename T>
 bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, const TilePlan& tp, dim3 grid,
                       hipStream_t st)
 {
 #define CASE(w, o, p)                                                                         \
     if (ct.W == w && ct.OT == o && tp.PT == p) {                                                \
-        if (tp.NW == 8) launch_conv_inst<w, o, p, 8>(a, grid, tp.lds, st);                      \
-        else launch_conv_inst<w, o, p, 4>(a, grid, tp.lds, st);                                 \
+        if (tp.NW == 8) launch_conv_inst<w, o, p, 8, T>(a, grid, tp.lds, st);                   \
+        else launch_conv_inst<w, o, p, 4, T>(a, grid, tp.lds, st);                              \
         return true;                                                                          \
     }
     CASE(16, 1, 4) CASE(16, 2, 4) CASE(16, 4, 4) CASE(16, 1, 8) CASE(16, 2, 8)
@@ -430,51 +439,66 @@ bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, const Tile
 #undef CASE
     return false;
 }
+template <typename T>
 void launch_wgrad_mfma(const mpcnn::WgradArgs& a, dim3 grid, size_t lds, hipStream_t st)
 {
-#define CASE(m) case m: mpcnn::wgrad_mfma_kernel<m><<<grid, 512, lds, st>>>(a); return;
+#define CASE(m) case m: mpcnn::wgrad_mfma_kernel<m, T><<<grid, 512, lds, st>>>(a); return;
     switch (a.mw) {
     CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11)
     }
 #undef CASE
 }
 // Kernels that may ask for more than 64 KiB of dynamic LDS must say so once.
-mpcnn_status set_lds_attrs()
+template <typename T>
+mpcnn_status set_lds_attrs_t()
 {
 #define ATTR(fn) HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fn), \
                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024))
-    ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 4>)); ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 8>));
-    ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 8>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 8>));
-    ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 4>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 4, 8>));
-    ATTR((mpcnn::conv_mfma_kernel<16, 4, 4, 8>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 2, 8>));
-    ATTR(mpcnn::wgrad_mfma_kernel<1>); ATTR(mpcnn::wgrad_mfma_kernel<2>); ATTR(mpcnn::wgrad_mfma_kernel<3>);
-    ATTR(mpcnn::wgrad_mfma_kernel<4>); ATTR(mpcnn::wgrad_mfma_kernel<5>); ATTR(mpcnn::wgrad_mfma_kernel<6>);
-    ATTR(mpcnn::wgrad_mfma_kernel<7>); ATTR(mpcnn::wgrad_mfma_kernel<8>); ATTR(mpcnn::wgrad_mfma_kernel<9>);
-    ATTR(mpcnn::wgrad_mfma_kernel<10>); ATTR(mpcnn::wgrad_mfma_kernel<11>);
+    ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 4, T>)); ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 8, T>));
+    ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 8, T>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 8, T>));
+    ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 4, T>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 4, 8, T>));
+    ATTR((mpcnn::conv_mfma_kernel<16, 4, 4, 8, T>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 2, 8, T>));
+    ATTR((mpcnn::wgrad_mfma_kernel<1, T>)); ATTR((mpcnn::wgrad_mfma_kernel<2, T>));
+    ATTR((mpcnn::wgrad_mfma_kernel<3, T>)); ATTR((mpcnn::wgrad_mfma_kernel<4, T>));
+    ATTR((mpcnn::wgrad_mfma_kernel<5, T>)); ATTR((mpcnn::wgrad_mfma_kernel<6, T>));
+    ATTR((mpcnn::wgrad_mfma_kernel<7, T>)); ATTR((mpcnn::wgrad_mfma_kernel<8, T>));
+    ATTR((mpcnn::wgrad_mfma_kernel<9, T>)); ATTR((mpcnn::wgrad_mfma_kernel<10, T>));
+    ATTR((mpcnn::wgrad_mfma_kernel<11, T>));
 #undef ATTR
     return MPCNN_OK;
 }
+mpcnn_status set_lds_attrs(bool bf16_storage)
+{
+    return bf16_storage ? set_lds_attrs_t<mpcnn::bf16>() : set_lds_attrs_t<float>();
+}
 
-template <int NCLS, int KV>
+template <int NCLS, int KV, typename T>
 void launch_class_inst(const mpcnn::ClassArgs& a, bool train, int blocks, hipStream_t st)
 {
-    if (train) mpcnn::class_layer_kernel<NCLS, KV, true><<<blocks, 256, 0, st>>>(a);
-    else mpcnn::class_layer_kernel<NCLS, KV, false><<<blocks, 256, 0, st>>>(a);
+    if (train) mpcnn::class_layer_kernel<NCLS, KV, true, T><<<blocks, 256, 0, st>>>(a);
+    else mpcnn::class_layer_kernel<NCLS, KV, false, T><<<blocks, 256, 0, st>>>(a);
 }
+template <typename T>
 void launch_class(const mpcnn::ClassArgs& a, int ncls, int KV, bool train, int blocks, hipStream_t st)
 {
-#define CASE(n, v) if (ncls == n && KV == v) return launch_class_inst<n, v>(a, train, blocks, st)
+#define CASE(n, v) if (ncls == n && KV == v) return launch_class_inst<n, v, T>(a, train, blocks, st)
     CASE(2, 2); CASE(3, 2); CASE(4, 2); CASE(2, 4); CASE(3, 4); CASE(4, 4);
 #undef CASE
 }
 
 mpcnn_status refresh_packs(mpcnn_net* net, hipStream_t st)
 {
+    if (net->bf16 && net->wread_stale) {
+        const long n = (long)net->n_params;
+        LAUNCH("round_params", -1, 0, 0, 8.0 * n,
+               mpcnn::round_params_kernel<<<grid_for(n), 256, 0, st>>>(net->d_params, net->d_wread, n));
+    }
+    net->wread_stale = false;
     if (!net->packs_stale || !net->d_packs) { net->packs_stale = false; return MPCNN_OK; }
     for (size_t l = 0; l < net->layers.size(); ++l) {
         const Layer& ly = net->layers[l];
         if (ly.kind == MPCNN_MP) continue;
-        const float* Wc = net->d_params + ly.p_off;
+        const float* Wc = net->d_wread + ly.p_off;
         if (ly.fwd_mfma)
             LAUNCH("pack_weights", l, 0, 0, 8.0 * ly.fwd_pack_len,
                    mpcnn::pack_weights_kernel<<<grid_for((long)ly.fwd_pack_len), 256, 0, st>>>(
@@ -492,29 +516,36 @@ mpcnn_status refresh_packs(mpcnn_net* net, hipStream_t st)
 }
 
 // Forward through every layer; in training mode everything is kept for the backward.
+// T = storage type of activations and deltas (float, or bf16 with fp32 arithmetic).
+template <typename T>
 mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char* ws,
-                         const int32_t* labels, const float* pixw, float* probs, float* dZ,
+                         const int32_t* labels, const float* pixw, float* probs, void* dZ_,
                          double* loss_dev, hipStream_t st)
 {
     using namespace mpcnn;
+    constexpr bool kF32 = std::is_same<T, float>::value;
+    constexpr double es = sizeof(T);
     mpcnn_status rc = refresh_packs(net, st);
     if (rc != MPCNN_OK) return rc;
     const int B = g.B;
-    const float* in = image;
+    T* dZ = static_cast<T*>(dZ_);
+    const T* in = nullptr;
     int Hi = g.H, Wi = g.W, Ci = net->in_ch;
-    if (net->in_ch > 1) {
-        float* staged = (float*)(ws + g.staged_off);
+    if (g.staged) {
+        T* staged = (T*)(ws + g.staged_off);
         long total = (long)B * Ci * Hi * Wi;
-        LAUNCH("stage_input", -1, 0, 0, 8.0 * total,
-               stage_input_kernel<<<grid_for(total), 256, 0, st>>>(image, staged, B, Ci, Hi, Wi));
+        LAUNCH("stage_input", -1, 0, 0, (4.0 + es) * total,
+               stage_input_kernel<T><<<grid_for(total), 256, 0, st>>>(image, staged, B, Ci, Hi, Wi));
         in = staged;
+    } else if constexpr (kF32) {
+        in = image;
     }
     const size_t L = net->layers.size();
     double* lp = (double*)(ws + g.loss_partial_off);
     const bool want_loss = labels && loss_dev;
     for (size_t l = 0; l < L; ++l) {
         const Layer& ly = net->layers[l];
-        float* out = (float*)(ws + g.act_off[l]);
+        T* out = (T*)(ws + g.act_off[l]);
         const int Ho = g.rows[l], Wo = g.cols[l];
         const double n_in = (double)B * Hi * Wi * Ci, n_out = (double)B * Ho * Wo * ly.cout;
         if (ly.kind == MPCNN_MP) {
@@ -522,18 +553,20 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             long total = (long)B * Ho * Wo * ly.cout;
             mpcnn::RowGrid rg;
             if (ly.cout % 4 == 0 && row_grid(B, Ho, Wo, ly.cout / 4, &rg))
-                LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (code ? 9.0 : 8.0),
-                       maxfilter_fwd4_kernel<<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
+                LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
+                       maxfilter_fwd4_kernel<T><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
                            in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil));
-            else
+            else if constexpr (kF32)
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (code ? 9.0 : 8.0),
                        maxfilter_fwd_direct_kernel<<<grid_for(total), 256, 0, st>>>(
                            in, out, code, B, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil));
+            else
+                return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", l);
         } else if (ly.class_fused) {
             // last FC + softmax + cross-entropy (+ its own backward when labels are given)
             const long M = (long)B * Ho * Wo;
             ClassArgs a{};
-            a.h = in; a.Wk = net->d_params + ly.p_off; a.probs = probs;
+            a.h = in; a.Wk = net->d_wread + ly.p_off; a.probs = probs;
             a.labels = labels; a.pixw = pixw; a.dH = dZ; a.partial = (float*)(ws + g.partial_off[l]);
             a.loss_partial = want_loss ? lp : nullptr;
             a.B = B; a.Ho = Ho; a.Wo = Wo; a.H = g.H; a.W = g.W; a.ctr = (net->patch - 1) / 2;
@@ -541,16 +574,16 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             const int blocks = class_blocks(M);
             const bool train = labels != nullptr;
             const double flops = 2.0 * M * Ci * ly.cout * (train ? 3.0 : 1.0);
-            const double bytes = 4.0 * (n_in * (train ? 2.0 : 1.0) + n_out);
+            const double bytes = es * n_in * (train ? 2.0 : 1.0) + 4.0 * n_out;
             LAUNCH("class_layer", l, train ? 4 : 3, flops, bytes,
-                   launch_class(a, ly.cout, Ci <= 128 ? 2 : 4, train, blocks, st));
+                   launch_class<T>(a, ly.cout, Ci <= 128 ? 2 : 4, train, blocks, st));
             if (train && want_loss)
                 LAUNCH("loss_tree", l, 0, 0, 8.0 * blocks,
                        loss_tree_kernel<<<1, 256, 0, st>>>(lp, blocks, loss_dev));
         } else {
-            const float* Wk = net->d_params + ly.p_off;
+            const float* Wk = net->d_wread + ly.p_off;
             const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k * Ci;
-            const double bytes = 4.0 * (n_in + n_out + ly.p_len);
+            const double bytes = es * (n_in + n_out) + 4.0 * ly.p_len;
             const int step = (l == L - 1) ? 3 : 1;
             if (ly.fwd_mfma && g.fwd[l].ok) {
                 const TilePlan& tp = g.fwd[l];
@@ -564,18 +597,21 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 a.mode = ly.tanh_out ? kFwdTanh : kFwdLinear;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
                 LAUNCH("conv_fwd_mfma", l, step, flops, bytes,
-                       launch_conv_mfma(a, ly.fwd_ct, tp, grid, st));
+                       launch_conv_mfma<T>(a, ly.fwd_ct, tp, grid, st));
             } else {
                 long total = (long)B * Ho * Wo;
                 dim3 grid((unsigned)((total + 255) / 256), (unsigned)ceil_div(ly.cout, 4));
                 LAUNCH("first_layer", l, step, flops, bytes,
-                       first_layer_kernel<<<grid, 256, 0, st>>>(in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout,
-                                                               ly.k, ly.dil, ly.tanh_out ? 1 : 0));
+                       first_layer_kernel<T><<<grid, 256, 0, st>>>(in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout,
+                                                                  ly.k, ly.dil, ly.tanh_out ? 1 : 0));
             }
         }
         in = out; Hi = Ho; Wi = Wo; Ci = ly.cout;
     }
-    if (!net->layers[L - 1].class_fused) {
+    if constexpr (!kF32) {
+        if (!net->layers[L - 1].class_fused)
+            return fail(MPCNN_EUNSUPPORTED, "the unfused class layer has an fp32-storage kernel only");
+    } else if (!net->layers[L - 1].class_fused) {
         // class logits -> probabilities, deltas, loss
         long total = (long)B * Hi * Wi;
         int blocks = (int)std::min<long>(kLossBlocks, (total + 255) / 256);
@@ -591,41 +627,48 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
     return MPCNN_OK;
 }
 
+template <typename T>
 mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, char* ws,
                           hipStream_t st)
 {
     using namespace mpcnn;
+    constexpr bool kF32 = std::is_same<T, float>::value;
+    constexpr double es = sizeof(T);
     const int B = g.B;
     const size_t L = net->layers.size();
-    const float* in0 = net->in_ch > 1 ? (const float*)(ws + g.staged_off) : image;
-    float* dbuf[2] = {(float*)(ws + g.delta_off[0]), (float*)(ws + g.delta_off[1])};
+    const T* in0 = nullptr;
+    if (g.staged) in0 = (const T*)(ws + g.staged_off);
+    else if constexpr (kF32) in0 = image;
+    T* dbuf[2] = {(T*)(ws + g.delta_off[0]), (T*)(ws + g.delta_off[1])};
     int cur = 0;  // dbuf[cur] holds dL/d(pre-activation) of layer l's output (dL/d(output) for MP)
     // a fused class layer has already done its own backward and left the delta below it
     for (size_t li = net->layers[L - 1].class_fused ? L - 1 : L; li-- > 0;) {
         const Layer& ly = net->layers[li];
         const int Ho = g.rows[li], Wo = g.cols[li];
-        const float* A = li == 0 ? in0 : (const float*)(ws + g.act_off[li - 1]);
+        const T* A = li == 0 ? in0 : (const T*)(ws + g.act_off[li - 1]);
         const int Hi = li == 0 ? g.H : g.rows[li - 1], Wi = li == 0 ? g.W : g.cols[li - 1];
         const int Ci = ly.cin;
         const bool below_tanh = li > 0 && net->layers[li - 1].tanh_out;
-        const float* dY = dbuf[cur];
-        float* dA = dbuf[cur ^ 1];
+        const T* dY = dbuf[cur];
+        T* dA = dbuf[cur ^ 1];
         const double n_in = (double)B * Hi * Wi * Ci, n_out = (double)B * Ho * Wo * ly.cout;
         if (ly.kind == MPCNN_MP) {
             if (li == 0) break;  // nothing below has parameters
             const uint8_t* code = (const uint8_t*)(ws + g.code_off[li]);
             long total = (long)B * Hi * Wi * Ci;
-            const double bytes = n_out * 5.0 + n_in * (below_tanh ? 8.0 : 4.0);
+            const double bytes = n_out * (es + 1.0) + n_in * es * (below_tanh ? 2.0 : 1.0);
             mpcnn::RowGrid rg;
             const bool quads = Ci % 4 == 0 && row_grid(B, Hi, Wi, Ci / 4, &rg);
             if (quads && below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
-                       maxfilter_bwd4_kernel<true><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
-                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
+                       (maxfilter_bwd4_kernel<true, T><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
+                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil)));
             else if (quads)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
-                       maxfilter_bwd4_kernel<false><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
-                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
+                       (maxfilter_bwd4_kernel<false, T><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
+                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil)));
+            else if constexpr (!kF32)
+                return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             else if (below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        maxfilter_bwd_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
@@ -652,8 +695,10 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.mg_txp = magic_of(wp.TxP); a.mg_ci = magic_of(Ci); a.mg_k = magic_of(ly.k);
                 a.mg_ntx = magic_of(wp.ntx); a.mg_nty = magic_of(wp.nty); a.mg_d = magic_of(ly.dil);
                 dim3 grid((unsigned)wp.slabs, (unsigned)wp.gm, (unsigned)wp.gn);
-                LAUNCH("wgrad_mfma", li, wstep, flops, 4.0 * (n_in + n_out + ly.p_len),
-                       launch_wgrad_mfma(a, grid, wp.lds, st));
+                LAUNCH("wgrad_mfma", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
+                       launch_wgrad_mfma<T>(a, grid, wp.lds, st));
+            } else if constexpr (!kF32) {
+                return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             } else {
                 dim3 grid((unsigned)((ly.p_len + 255) / 256), (unsigned)wp.chunks);
                 LAUNCH("wgrad_direct", li, wstep, flops, 4.0 * (n_in + n_out + ly.p_len),
@@ -662,8 +707,8 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                                                                       wp.rows_per_chunk));
             }
             if (li == 0) break;  // the image needs no gradient
-            const float* Wk = net->d_params + ly.p_off;
-            const double dbytes = 4.0 * (n_in * (below_tanh ? 2.0 : 1.0) + n_out + ly.p_len);
+            const float* Wk = net->d_wread + ly.p_off;
+            const double dbytes = es * (n_in * (below_tanh ? 2.0 : 1.0) + n_out) + 4.0 * ly.p_len;
             if (ly.dgrad_mfma && g.dgrad[li].ok) {
                 const TilePlan& tp = g.dgrad[li];
                 ConvArgs a{};
@@ -676,7 +721,9 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.mode = below_tanh ? kDgradTanh : kDgradPlain;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.dgrad_ct.split);
                 LAUNCH("conv_dgrad_mfma", li, dstep, flops, dbytes,
-                       launch_conv_mfma(a, ly.dgrad_ct, tp, grid, st));
+                       launch_conv_mfma<T>(a, ly.dgrad_ct, tp, grid, st));
+            } else if constexpr (!kF32) {
+                return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             } else {
                 long total = (long)B * Hi * Wi * Ci;
                 if (below_tanh)
@@ -771,13 +818,10 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
     *out = nullptr;
     if (n_layers < 1 || n_layers > 48 || in_channels < 1 || patch < 1)
         return fail(MPCNN_EINVAL, "n_layers=%d in_channels=%d patch=%d", n_layers, in_channels, patch);
-    if (dtype != MPCNN_F32) {
-        if (dtype == MPCNN_BF16) return fail(MPCNN_EUNSUPPORTED, "bf16 storage is not built yet");
-        return fail(MPCNN_EINVAL, "unknown dtype %d", (int)dtype);
-    }
+    if (dtype != MPCNN_F32 && dtype != MPCNN_BF16) return fail(MPCNN_EINVAL, "unknown dtype %d", (int)dtype);
     mpcnn_net* net = new (std::nothrow) mpcnn_net;
     if (!net) return fail(MPCNN_ENOMEM, "out of host memory");
-    net->in_ch = in_channels; net->patch = patch;
+    net->in_ch = in_channels; net->patch = patch; net->bf16 = dtype == MPCNN_BF16;
     int side = patch, ch = in_channels, dil = 1;
     bool seen_fc = false;
     size_t off = 0, pack = 0;
@@ -828,6 +872,17 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
                 ly.dgrad_pack_off = pack; pack += ly.dgrad_pack_len;
             }
         }
+        // bf16 storage is built for the main kernels only: every layer must take them
+        if (net->bf16) {
+            const bool last = l == n_layers - 1;
+            if (ly.kind == MPCNN_MP ? ly.cout % 4 != 0
+                                    : (last ? !ly.class_fused
+                                            : ((l > 0 && !ly.fwd_mfma) || (l > 0 && !ly.dgrad_mfma) || ly.cout % 4 != 0))) {
+                st = fail(MPCNN_EUNSUPPORTED, "layer %d: bf16 storage needs channel counts that are multiples of 4, "
+                          "at least 8 between layers, and a last FC of 2-4 classes on at most 256 inputs", l);
+                break;
+            }
+        }
         ch = ly.cout;
         net->layers.push_back(ly);
     }
@@ -847,6 +902,7 @@ void mpcnn_net_destroy(mpcnn_net* net)
     if (net->d_params || net->d_grads || net->d_packs) {
         (void)hipSetDevice(net->device);
         (void)hipDeviceSynchronize();
+        if (net->d_wread && net->d_wread != net->d_params) (void)hipFree(net->d_wread);
         (void)hipFree(net->d_params);
         (void)hipFree(net->d_grads);
         (void)hipFree(net->d_packs);
@@ -885,7 +941,9 @@ mpcnn_status mpcnn_set_params(mpcnn_net* net, const float* params_host, size_t n
         HIP_TRY(hipMalloc((void**)&net->d_grads, sizeof(float) * n));
         HIP_TRY(hipMemset(net->d_grads, 0, sizeof(float) * n));
         if (net->pack_len) HIP_TRY(hipMalloc((void**)&net->d_packs, sizeof(float) * net->pack_len));
-        mpcnn_status rc = set_lds_attrs();
+        if (net->bf16) HIP_TRY(hipMalloc((void**)&net->d_wread, sizeof(float) * n));
+        else net->d_wread = net->d_params;
+        mpcnn_status rc = set_lds_attrs(net->bf16);
         if (rc != MPCNN_OK) return rc;
     }
     std::vector<float> tmp(n);
@@ -893,7 +951,7 @@ mpcnn_status mpcnn_set_params(mpcnn_net* net, const float* params_host, size_t n
     HIP_TRY(hipSetDevice(net->device));
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipMemcpy(net->d_params, tmp.data(), sizeof(float) * n, hipMemcpyHostToDevice));
-    net->packs_stale = true;
+    net->packs_stale = true; net->wread_stale = true;
     return MPCNN_OK;
 }
 
@@ -937,8 +995,10 @@ mpcnn_status mpcnn_seg_forward(mpcnn_net* net, const float* image_dev, int B, in
     mpcnn_status st = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &g);
     if (st != MPCNN_OK) return st;
     if (!probs_dev) return fail(MPCNN_EINVAL, "null probs_dev");
-    st = run_forward(net, g, image_dev, (char*)ws_dev, nullptr, nullptr, probs_dev, nullptr, nullptr,
-                     (hipStream_t)hip_stream);
+    st = net->bf16 ? run_forward<mpcnn::bf16>(net, g, image_dev, (char*)ws_dev, nullptr, nullptr, probs_dev,
+                                              nullptr, nullptr, (hipStream_t)hip_stream)
+                   : run_forward<float>(net, g, image_dev, (char*)ws_dev, nullptr, nullptr, probs_dev, nullptr,
+                                        nullptr, (hipStream_t)hip_stream);
     net->last = g; net->last_ws = ws_dev;
     return st;
 }
@@ -953,11 +1013,13 @@ mpcnn_status mpcnn_seg_backward(mpcnn_net* net, const float* image_dev, const in
     if (!labels_dev) return fail(MPCNN_EINVAL, "null labels_dev");
     hipStream_t stream = (hipStream_t)hip_stream;
     char* ws = (char*)ws_dev;
-    float* dZ = (float*)(ws + g.delta_off[0]);
-    st = run_forward(net, g, image_dev, ws, labels_dev, pixw_dev, probs_dev, dZ, loss_dev, stream);
+    void* dZ = ws + g.delta_off[0];
+    st = net->bf16 ? run_forward<mpcnn::bf16>(net, g, image_dev, ws, labels_dev, pixw_dev, probs_dev, dZ, loss_dev, stream)
+                   : run_forward<float>(net, g, image_dev, ws, labels_dev, pixw_dev, probs_dev, dZ, loss_dev, stream);
     net->last = g; net->last_ws = ws_dev;
     if (st != MPCNN_OK) return st;
-    return run_backward(net, g, image_dev, ws, stream);
+    return net->bf16 ? run_backward<mpcnn::bf16>(net, g, image_dev, ws, stream)
+                     : run_backward<float>(net, g, image_dev, ws, stream);
 }
 
 mpcnn_status mpcnn_sgd_step(mpcnn_net* net, float lr, float grad_scale, void* hip_stream)
@@ -970,7 +1032,7 @@ mpcnn_status mpcnn_sgd_step(mpcnn_net* net, float lr, float grad_scale, void* hi
            mpcnn::sgd_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(net->d_params, net->d_grads,
                                                                           lr * grad_scale, n));
     HIP_TRY(hipGetLastError());
-    net->packs_stale = true;
+    net->packs_stale = true; net->wread_stale = true;
     return MPCNN_OK;
 }
 
@@ -984,7 +1046,17 @@ mpcnn_status mpcnn_get_activation(const mpcnn_net* net, int layer, float* host, 
     if (n != elems) return fail(MPCNN_EINVAL, "n = %zu, layer holds %zu elements", n, elems);
     HIP_TRY(hipSetDevice(net->device));
     HIP_TRY(hipDeviceSynchronize());
-    HIP_TRY(hipMemcpy(host, (char*)net->last_ws + g.act_off[layer], sizeof(float) * elems, hipMemcpyDeviceToHost));
+    const char* src = (const char*)net->last_ws + g.act_off[layer];
+    if (!net->bf16) {
+        HIP_TRY(hipMemcpy(host, src, sizeof(float) * elems, hipMemcpyDeviceToHost));
+    } else {
+        std::vector<uint16_t> tmp(elems);
+        HIP_TRY(hipMemcpy(tmp.data(), src, sizeof(uint16_t) * elems, hipMemcpyDeviceToHost));
+        for (size_t i = 0; i < elems; ++i) {
+            const uint32_t bits = (uint32_t)tmp[i] << 16;   // bf16 = the upper half of an fp32
+            memcpy(host + i, &bits, sizeof(float));
+        }
+    }
     return MPCNN_OK;
 }
 

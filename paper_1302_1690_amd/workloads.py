@@ -104,11 +104,23 @@ def param_count(layers, in_channels: int, patch: int) -> int:
     return total
 
 
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """fp32 values rounded to the nearest bf16 (ties to even), returned as fp32.  Inputs of a
+    bf16-storage workload are generated representable, so that rounding the stored weights and
+    image is not a source of difference between the two sides."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(np.shape(x))
+
+
 def make_params(wl: Workload, dtype=np.float32) -> np.ndarray:
     """Flat parameter vector, per layer W[o][c][u][v] then b[o], all ~ U[-a, a]."""
     n = param_count(wl.layers, wl.in_channels, wl.patch)
     rng = np.random.default_rng(wl.seed_param)
-    return rng.uniform(-wl.weight_amp, wl.weight_amp, size=n).astype(dtype)
+    p = rng.uniform(-wl.weight_amp, wl.weight_amp, size=n).astype(np.float32)
+    if wl.dtype == "bf16":
+        p = round_bf16(p)
+    return p.astype(dtype)
 
 
 def _rects(rng, img, lab):
@@ -173,6 +185,9 @@ def make_inputs(wl: Workload, dtype=np.float32):
             _ellipses(rng_l, img[b], lab[b])
         else:
             raise ValueError(wl.shapes)
+    img = img.astype(np.float32)
+    if wl.dtype == "bf16":
+        img = round_bf16(img)
     return img.astype(dtype), lab
 
 

@@ -3,7 +3,8 @@ patch-by-patch oracle, element by element, on the same seeded inputs.
 
 Bars: argmax tap codes bit-exact (see `check_argmax`), probabilities within 1e-4
 absolute, gradients within 1e-4 of the tensor's largest entry and in L2 norm,
-per parameter tensor; loss within 1e-5 relative.
+per parameter tensor; loss within 1e-5 relative.  With bf16 storage: 2e-2 / 2e-3, and a
+pooling window's two best candidates count as tied when within 2^-7.
 """
 import numpy as np
 import pytest
@@ -39,7 +40,18 @@ def param_tensors(layers, in_ch, patch):
     return out
 
 
-def check_grads(cfg, g_gpu, g_ref, tol=TOL):
+def tol_of(cfg):
+    """Bar on probabilities and gradients: 1e-4 relative with fp32 storage, 2e-2 with bf16."""
+    return TOL_BF16 if cfg.dtype == "bf16" else TOL
+
+
+def tau_of(cfg):
+    """Top-2 gap of a pooling window below which either candidate may win on the GPU."""
+    return TIE_TAU_BF16 if cfg.dtype == "bf16" else TIE_TAU
+
+
+def check_grads(cfg, g_gpu, g_ref, tol=None):
+    tol = tol_of(cfg) if tol is None else tol
     worst, report = 0.0, []
     for name, sl in param_tensors(cfg.layers, cfg.in_channels, cfg.patch):
         a, r = g_gpu[sl].astype(np.float64), g_ref[sl]
@@ -55,7 +67,8 @@ def check_grads(cfg, g_gpu, g_ref, tol=TOL):
 def run_gpu(cfg, img, lab, params, pixw=None, net=None):
     own = net is None
     if own:
-        net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch)
+        net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch,
+                        dtype=mpcnn.BF16 if cfg.dtype == "bf16" else mpcnn.F32)
         net.set_params(params)
     B, _, H, W = img.shape
     d_img = torch.from_numpy(img).cuda()
@@ -77,15 +90,18 @@ def first_max_codes(a, p, d):
     return np.argmax(taps, axis=0).astype(np.uint8), taps.max(axis=0)
 
 
-TIE_TAU = 1e-5   # activations lie in [-1, 1]: about 100 fp32 ulps
+TIE_TAU = 1e-5        # activations lie in [-1, 1]: about 100 fp32 ulps
+TIE_TAU_BF16 = 2.0 ** -7   # bf16 storage: two ulps at 1; values this close may round to a tie or swap
+TOL_BF16 = 2e-2
 
 
 def oracle_run_valid_ties(cfg, params, img, lab, pixw, sel, net):
     """Oracle result to compare with.  Where the oracle's own two best candidates of a
-    pooling window are within TIE_TAU, either may legitimately win in fp32; the GPU's
-    choice among those two (and only those) is adopted and the oracle re-evaluated."""
+    pooling window are within tau, the order may legitimately differ in the GPU's
+    precision; the GPU's choice is adopted there if (the oracle checks this) that tap's
+    value is within tau of the maximum, and the oracle re-evaluated."""
     kw = dict(labels=lab, pixw=None if pixw is None else pixw.astype(np.float64), sel=sel,
-              want_grads=True, tie_tau=TIE_TAU)
+              want_grads=True, tie_tau=tau_of(cfg))
     args = (cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64), img.astype(np.float64))
     ref = oracle.run(*args, **kw)
     near = ref["near_ties"]
@@ -95,20 +111,22 @@ def oracle_run_valid_ties(cfg, params, img, lab, pixw, sel, net):
         rows = near[near[:, 3] == layer]
         _, ch, ny, nx, _ = oracle.dense_shape(cfg.layers, cfg.in_channels, cfg.patch, B, H, W, int(layer))
         key = rows[:, 0]
-        x, t = key % nx, key // nx
+        assert (key >> 48 == layer).all()
+        t = key & ((1 << 48) - 1)
+        x, t = t % nx, t // nx
         y, t = t % ny, t // ny
-        c, t = t % ch, t // ch
-        b = t % B
-        assert (t // B == layer).all()
+        c, b = t % ch, t // ch
+        assert (b < B).all()
         got = net.get_argmax(B, H, W, int(layer))[b, y, x, c]
-        assert ((got == rows[:, 1]) | (got == rows[:, 2])).all(), "GPU chose neither near-tie candidate"
-        alt += key[got == rows[:, 2]].tolist()
+        other = got != rows[:, 1]
+        alt += list(zip(key[other].tolist(), got[other].tolist()))
     if alt:
         ref = oracle.run(*args, alt=alt, **kw)
+        assert ref["alt_rejected"] == 0, "the GPU routed to a tap that is not within tau of the window's maximum"
     return ref, len(near), len(alt)
 
 
-def check_argmax(cfg, net, img, params, with_oracle=True):
+def check_argmax(cfg, net, img, params, with_oracle=True, layers=None):
     """(i) The stored tap codes equal a CPU scan, lowest tap first, over the GPU's own
     pre-pool values, bit for bit.  (ii) They equal the fp64 oracle's codes wherever
     the oracle's top-2 gap exceeds TIE_TAU (rounding can flip closer calls)."""
@@ -117,6 +135,9 @@ def check_argmax(cfg, net, img, params, with_oracle=True):
     dil = 1
     for li, (kind, maps, k) in enumerate(cfg.layers):
         if kind != MP:
+            continue
+        if layers is not None and li not in layers:
+            dil *= k
             continue
         pre = (np.ascontiguousarray(img.transpose(0, 2, 3, 1)) if li == 0
                else net.get_activation(B, H, W, li - 1))
@@ -133,7 +154,8 @@ def check_argmax(cfg, net, img, params, with_oracle=True):
             o_gap = d["gap"].transpose(0, 2, 3, 1)
             cov = d["covered"][..., None]
             bad = (codes != o_codes) & cov
-            assert not (bad & (o_gap > TIE_TAU)).any(), (cfg.name, li, int((bad & (o_gap > TIE_TAU)).sum()))
+            tau = tau_of(cfg)
+            assert not (bad & (o_gap > tau)).any(), (cfg.name, li, int((bad & (o_gap > tau)).sum()))
             excused += int(bad.sum())
         dil *= k
     return excused
@@ -153,8 +175,8 @@ def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_lay
     ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, pixw, None, net)
     say("  near-tie windows %d, resolved the other way on the GPU %d" % (n_near, n_alt))
     e_p = np.abs(probs - ref["probs"]).max()
-    assert e_p <= TOL, (cfg.name, "probs", e_p)
-    assert abs(loss - ref["loss"]) <= 1e-5 * abs(ref["loss"]), (loss, ref["loss"])
+    assert e_p <= tol_of(cfg), (cfg.name, "probs", e_p)
+    assert abs(loss - ref["loss"]) <= 0.1 * tol_of(cfg) * abs(ref["loss"]), (loss, ref["loss"])
     excused = check_argmax(cfg, net, img, params) if check_layers else -1
     say("  argmax excused %d" % excused)
     if check_layers:
@@ -167,7 +189,9 @@ def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_lay
             a = net.get_activation(B, H, W, li).transpose(0, 3, 1, 2)
             cov = d["covered"][:, None]
             err = np.abs(a - d["act"])[np.broadcast_to(cov, a.shape)].max()
-            assert err <= 2e-5, (cfg.name, "activation of layer", li, err)
+            # fp32: a few ulps of tanh; bf16: each stored value is rounded (half an ulp = 2^-9 at 1)
+            # on top of the rounding inherited from the layers below
+            assert err <= (2e-2 if cfg.dtype == "bf16" else 2e-5), (cfg.name, "activation of layer", li, err)
     e_g = check_grads(cfg, grads, ref["grads"])
     say("  probs err %.2e  grads err %.2e  loss %.6f  argmax excused %d" % (e_p, e_g, loss, excused))
     net.close()
@@ -256,7 +280,7 @@ def test_exact_ties_constant_image():
     net.close()
 
 
-def sampled_parity(cfg, n_sel, seed):
+def sampled_parity(cfg, n_sel, seed, argmax_layers=None):
     """Full-size input; the oracle evaluates a seeded subset S of the output pixels.
     Probabilities are compared at S; gradients by giving the GPU the indicator of S
     as per-pixel loss weights, which makes its summed gradient the sum over S."""
@@ -273,12 +297,12 @@ def sampled_parity(cfg, n_sel, seed):
     ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, None, sel, net)
     say("  near-tie windows %d, resolved the other way on the GPU %d" % (n_near, n_alt))
     e_p = np.abs(probs[b, :, i, j] - ref["probs"]).max()
-    assert e_p <= TOL, e_p
-    assert abs(loss - ref["loss"]) <= 1e-5 * abs(ref["loss"]), (loss, ref["loss"])
+    assert e_p <= tol_of(cfg), e_p
+    assert abs(loss - ref["loss"]) <= 0.1 * tol_of(cfg) * abs(ref["loss"]), (loss, ref["loss"])
     e_g = check_grads(cfg, grads, ref["grads"])
     # properties that hold at any size
     assert np.isfinite(probs).all() and np.abs(probs.sum(1) - 1).max() < 1e-5
-    excused = check_argmax(cfg, net, img, params, with_oracle=False)
+    excused = check_argmax(cfg, net, img, params, with_oracle=False, layers=argmax_layers)
     say("  probs err %.2e  grads err %.2e  loss %.6f" % (e_p, e_g, loss))
     return net, img, lab, params
 
@@ -304,6 +328,32 @@ def test_cfg2_full_size_sampled_and_sgd():
 def test_cfg3_full_size_sampled():
     net, img, lab, params = sampled_parity(wl.CONFIGS[3], 48, 13)
     net.close()
+
+
+# ---- bf16 storage (activations and deltas rounded to bf16 when stored, arithmetic in fp32)
+_NET_BF16_SMALL = ((C, 8, 3), (MP, 0, 2), (C, 16, 3), (MP, 0, 2), (FC, 16, 0), (FC, 3, 0))
+
+
+def test_bf16_small_net_full_oracle():
+    cfg = wl.Workload("bf16_small", _NET_BF16_SMALL, 14, 3, 3, 2, 40, 44, 0.25, "ellipses", dtype="bf16",
+                      seed_image=1104, seed_label=2104, seed_param=3104)
+    full_parity(cfg, with_pixw=True)
+
+
+def test_cfg4_net_crop_full_oracle_bf16():
+    full_parity(wl.crop(wl.CONFIGS[4], 1, 100, 93), check_layers=False)
+
+
+def test_cfg4_full_size_sampled_bf16():
+    # the tap codes are checked against a scan of the GPU's own values on the deeper pooling
+    # layers (the first one alone would move 3 GB to the host)
+    net, img, lab, params = sampled_parity(wl.CONFIGS[4], 24, 14, argmax_layers=(5, 7))
+    net.close()
+
+
+def test_bf16_refuses_shapes_without_a_kernel():
+    with pytest.raises(mpcnn.MpcnnError):
+        mpcnn.Net(wl.CONFIGS[0].layers, 1, 18, dtype=mpcnn.BF16)
 
 
 def test_forward_only_matches_and_is_deterministic():

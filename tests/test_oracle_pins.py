@@ -279,8 +279,9 @@ def test_shared_maximum_receives_sum_of_deltas():
 
 def test_near_tie_report_and_alternative_routing():
     """A window whose two largest values are within tau is reported with both taps;
-    listing it sends the back-propagated value to the runner-up instead, and
-    nothing else changes (both are valid sub-gradients of the max)."""
+    listing it with a tap within tau of the maximum sends the back-propagated value
+    there instead, and nothing else changes (valid sub-gradients of the max); a tap
+    further from the maximum is refused and counted."""
     layers = ((MP, 0, 2), (FC, 2, 0))
     x = np.array([[1.0, 1.0 - 1e-9, 0.2], [0.1, 0.3, 0.4]])[None, None]   # two 2x2 windows
     params = np.array([0.7, -0.3, 0.1, 0.0])
@@ -291,15 +292,24 @@ def test_near_tie_report_and_alternative_routing():
     plain = oracle.run(layers, 1, 2, params, x, lab, want_grads=True, want_dimage=True)
     np.testing.assert_array_equal(plain["dimage"], r0["dimage"])              # reporting changes nothing
     r1 = oracle.run(layers, 1, 2, params, x, lab, want_grads=True, want_dimage=True, tie_tau=1e-6,
-                    alt=r0["near_ties"][:, 0])
+                    alt=r0["near_ties"][:, [0, 2]])
+    assert r1["alt_rejected"] == 0
     d0, d1 = r0["dimage"][0, 0], r1["dimage"][0, 0]
     assert d1[0, 0] == 0.0 and abs(d1[0, 1] - (d0[0, 0] + d0[0, 1])) < 1e-15   # moved to the runner-up
     np.testing.assert_array_equal(r1["probs"], r0["probs"])                   # forward value unchanged
     np.testing.assert_array_equal(r1["grads"], r0["grads"])                   # FC sees the same maximum
-    # a window that is not a near-tie cannot be rerouted
-    r2 = oracle.run(layers, 1, 2, params, x, lab, want_dimage=True, tie_tau=1e-6,
-                    alt=[oracle.window_key(layers, 1, 2, 1, 2, 3, 0, 0, 0, 0, 1)])
-    np.testing.assert_array_equal(r2["dimage"], r0["dimage"])
+    # a window that is not a near-tie cannot be rerouted, nor a near-tie to a distant tap
+    for key, tap in ((oracle.window_key(layers, 1, 2, 1, 2, 3, 0, 0, 0, 0, 1), 2),
+                     (oracle.window_key(layers, 1, 2, 1, 2, 3, 0, 0, 0, 0, 0), 3)):
+        r2 = oracle.run(layers, 1, 2, params, x, lab, want_dimage=True, tie_tau=1e-6, alt=[(key, tap)])
+        np.testing.assert_array_equal(r2["dimage"], r0["dimage"])
+        assert r2["alt_rejected"] == 1
+    # with a wide tau the third-best tap of a window qualifies too
+    r3 = oracle.run(layers, 1, 2, params, x, lab, want_dimage=True, tie_tau=0.75,
+                    alt=[(oracle.window_key(layers, 1, 2, 1, 2, 3, 0, 0, 0, 0, 0), 3)])
+    assert r3["alt_rejected"] == 0
+    d3 = r3["dimage"][0, 0]
+    assert d3[0, 0] == 0.0 and abs(d3[1, 1] - d0[0, 0]) < 1e-15
 
 
 def test_softmax_cross_entropy_closed_forms():
