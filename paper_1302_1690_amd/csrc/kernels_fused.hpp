@@ -12,28 +12,39 @@
 namespace mpcnn {
 
 // Conv + bias + tanh when the input has too few channels for the matrix cores (the image
-// itself: 1 or 3 channels).  One thread = one position x 4 output channels (blockIdx.y picks
-// the 4): four times the waves of a 16-channel thread, which is what hides the latency of
-// the tap loads; the taps of one filter row are fetched together.  Weights are wave-uniform
-// (scalar loads).
+// itself: 1 or 3 channels).  One thread = one position x 4 output channels, the quads of a
+// position in neighbouring lanes: a wave's stores are contiguous, its tap loads are shared
+// by the lanes of a position, and there are enough waves to hide the load latency.  The taps
+// of one filter row are fetched together, without branches.  The weights (a few KB) sit in
+// LDS, zero-padded to whole quads, bias row last; if they do not fit (`w_in_lds` = 0) they
+// are read from global memory.
 constexpr int kFirstLayerBatch = 8;   // taps of a filter row fetched together
 template <typename T>
 __global__ __launch_bounds__(256) void first_layer_kernel(const T* __restrict__ A,
                                                           const float* __restrict__ Wk,
                                                           T* __restrict__ Y, int B, int Hi, int Wi,
                                                           int Ci, int Ho, int Wo, int Co, int k, int d,
-                                                          int tanh_out)
+                                                          int tanh_out, int w_in_lds)
 {
-    const long total = (long)B * Ho * Wo;
-    const long m = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int o0 = blockIdx.y * 4;
-    if (m >= total) return;
+    extern __shared__ __attribute__((aligned(16))) float wl[];   // [(k*k*Ci + 1)][CoP]
+    const int OG = (Co + 3) >> 2, CoP = 4 * OG;
+    const int rows = k * k * Ci + 1;
+    if (w_in_lds) {
+        for (int e = threadIdx.x; e < rows * CoP; e += 256) {
+            const int r = e / CoP, o = e - r * CoP;
+            wl[e] = o < Co ? Wk[(long)r * Co + o] : 0.f;
+        }
+        __syncthreads();
+    }
+    const long total = (long)B * Ho * Wo * OG;
+    const long e = (long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const long m = e / OG;                            // position
+    const int o0 = 4 * (int)(e - m * OG);
     const int b = (int)(m / ((long)Ho * Wo));
     const int r = (int)(m - (long)b * Ho * Wo);       // position within the image: 32-bit from here on
     const int y = r / Wo, x = r - y * Wo;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    const float* bias = Wk + (long)k * k * Ci * Co;
-    const bool full = o0 + 4 <= Co;
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
     for (int u = 0; u < k; ++u) {
         const T* arow = A + (((long)b * Hi + (y + u * d)) * Wi + x) * Ci;
         for (int c = 0; c < Ci; ++c)
@@ -41,40 +52,38 @@ __global__ __launch_bounds__(256) void first_layer_kernel(const T* __restrict__ 
                 // no branches around the loads (they would be waited for one by one): taps past
                 // the filter's edge read the last tap again and count as zero
                 float av[kFirstLayerBatch];
-                const float* w[kFirstLayerBatch];
+                v4f w[kFirstLayerBatch];
 #pragma unroll
                 for (int j = 0; j < kFirstLayerBatch; ++j) {
                     const int v = v0 + j < k ? v0 + j : k - 1;
                     av[j] = load1(arow + (long)v * d * Ci + c);
-                    w[j] = Wk + ((long)(u * k + v) * Ci + c) * Co + (full ? o0 : 0);
+                    const int wr = (u * k + v) * Ci + c;
+                    if (w_in_lds) w[j] = *reinterpret_cast<const v4f*>(wl + wr * CoP + o0);
+                    else {
+#pragma unroll
+                        for (int z = 0; z < 4; ++z) w[j][z] = o0 + z < Co ? Wk[(long)wr * Co + o0 + z] : 0.f;
+                    }
                 }
 #pragma unroll
                 for (int j = 0; j < kFirstLayerBatch; ++j) {
-                    const float x = v0 + j < k ? av[j] : 0.f;
-                    if (full) {
+                    const float xj = v0 + j < k ? av[j] : 0.f;
 #pragma unroll
-                        for (int o = 0; o < 4; ++o) acc[o] = fmaf(x, w[j][o], acc[o]);
-                    } else {
-#pragma unroll
-                        for (int o = 0; o < 4; ++o)
-                            if (o0 + o < Co) acc[o] = fmaf(x, w[j][o0 + o], acc[o]);
-                    }
+                    for (int z = 0; z < 4; ++z) acc[z] = fmaf(xj, w[j][z], acc[z]);
                 }
             }
     }
-    T* out = Y + m * Co + o0;
 #pragma unroll
-    for (int o = 0; o < 4; ++o) {
-        if (o0 + o < Co) {
-            const float z = acc[o] + bias[o0 + o];
-            acc[o] = tanh_out ? fast_tanh(z) : z;
-        }
+    for (int z = 0; z < 4; ++z) {
+        const int o = o0 + z < Co ? o0 + z : Co - 1;
+        const float s = acc[z] + (w_in_lds ? wl[(rows - 1) * CoP + o] : Wk[(long)(rows - 1) * Co + o]);
+        acc[z] = tanh_out ? fast_tanh(s) : s;
     }
-    if ((Co & 3) == 0) store4(out, (v4f){acc[0], acc[1], acc[2], acc[3]});
+    T* out = Y + m * Co + o0;
+    if ((Co & 3) == 0) store4(out, acc);
     else {
 #pragma unroll
-        for (int o = 0; o < 4; ++o)
-            if (o0 + o < Co) store1(out + o, acc[o]);
+        for (int z = 0; z < 4; ++z)
+            if (o0 + z < Co) store1(out + z, acc[z]);
     }
 }
 

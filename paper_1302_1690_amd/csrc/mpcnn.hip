@@ -599,11 +599,14 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 LAUNCH("conv_fwd_mfma", l, step, flops, bytes,
                        launch_conv_mfma<T>(a, ly.fwd_ct, tp, grid, st));
             } else {
-                long total = (long)B * Ho * Wo;
-                dim3 grid((unsigned)((total + 255) / 256), (unsigned)ceil_div(ly.cout, 4));
+                const int og = ceil_div(ly.cout, 4);
+                const long total = (long)B * Ho * Wo * og;
+                const size_t wbytes = sizeof(float) * ((size_t)ly.k * ly.k * Ci + 1) * 4 * og;
+                const int w_in_lds = wbytes <= 48 * 1024;
                 LAUNCH("first_layer", l, step, flops, bytes,
-                       first_layer_kernel<T><<<grid, 256, 0, st>>>(in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout,
-                                                                  ly.k, ly.dil, ly.tanh_out ? 1 : 0));
+                       first_layer_kernel<T><<<(unsigned)((total + 255) / 256), 256, w_in_lds ? wbytes : 0, st>>>(
+                           in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil, ly.tanh_out ? 1 : 0,
+                           w_in_lds));
             }
         }
         in = out; Hi = Ho; Wi = Wo; Ci = ly.cout;
