@@ -145,6 +145,17 @@ def main():
                 print("  %-20s layer %2d  %8.1f us  %7.2f TFLOP/s %8.1f GB/s" % (
                     s["name"], s["layer"], us, s["flops"] / us / 1e6, s["bytes"] / us / 1e3), file=sys.stderr)
 
+    # ---- deployment forward of the same images (mirrored borders, output as large as the image;
+    # outside the timed training steps): seconds per image, the unit the paper quotes for it
+    net.seg_forward_same(d_img)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_fwd = max(5, args.steps // 2)
+    for _ in range(n_fwd):
+        net.seg_forward_same(d_img)
+    torch.cuda.synchronize()
+    fwd_ms_per_image = 1e3 * (time.perf_counter() - t0) / (n_fwd * cfg.batch)
+
     # ---- the oracle on the host cores, bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
@@ -169,6 +180,8 @@ def main():
                    "storage": cfg.dtype,
                    "step": "fwd+bwd" + ("+sgd" if do_sgd else ""), "loss": final_loss},
         "roofline": roofline, "cpu_baseline": cpu,
+        "deploy_forward": {"ms_per_image": round(fwd_ms_per_image, 4), "output": "%dx%d" % (cfg.height, cfg.width),
+                           "borders": "mirrored"},
     }
     print(json.dumps(out))
     net.close()

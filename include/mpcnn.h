@@ -127,6 +127,22 @@ mpcnn_status mpcnn_seg_forward(mpcnn_net* net, const float* image_dev, int B, in
                                float* probs_dev, void* ws_dev, size_t ws_bytes, void* hip_stream);
 
 /*
+ * Deployment forward that keeps the image size (Experiments, membrane segmentation:
+ * pixels outside the boundary of a test image are synthesised by mirroring, which
+ * preserves the size of the output):
+ *   image_dev [B][C0][H][W] fp32  ->  probs_dev [B][n_classes][H][W] fp32,
+ * output pixel (i,j) being the patch centred on input pixel (i,j) (c = (P-1)/2
+ * rounded down rows / columns above and to the left of it, P-1-c below and to the
+ * right).  The mirror repeats the edge pixel: index -1-i stands for i < 0 and
+ * 2n-1-i for i >= n.  Nothing is kept for a backward.  ws_dev: 256-byte aligned
+ * scratch of at least mpcnn_workspace_bytes_same(net,B,H,W) (0 on bad input).
+ * Errors: EINVAL, ESHAPE (H or W smaller than the widest border, P-1-c), EWORKSPACE, EHIP.
+ */
+size_t mpcnn_workspace_bytes_same(const mpcnn_net* net, int B, int H, int W);
+mpcnn_status mpcnn_seg_forward_same(mpcnn_net* net, const float* image_dev, int B, int H, int W,
+                                    float* probs_dev, void* ws_dev, size_t ws_bytes, void* hip_stream);
+
+/*
  * Whole-image forward + backward (Alg. 1-4): computes the loss
  *   L = sum over b,i,j of w * -log p[b, t, i, j],  t = labels[b][i+c][j+c],
  *   w = pixw[b][i+c][j+c] (1 if pixw_dev is NULL); pixels with t < 0 or

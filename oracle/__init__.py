@@ -142,6 +142,17 @@ def run(layers, in_ch, patch, params, image, labels=None, pixw=None, sel=None,
             "grads": grads, "dimage": dimage, "near_ties": near, "alt_rejected": rejected.value}
 
 
+def mirror_pad(image, patch):
+    """The image extended so that the patch net's output keeps the image size (Experiments,
+    membrane segmentation: pixels outside the boundary of a test image are synthesised by
+    mirroring).  c = (patch-1)//2 rows / columns are added above and to the left, patch-1-c
+    below and to the right; the mirror repeats the edge pixel (index -1-i stands for i < 0,
+    2n-1-i for i >= n), numpy's 'symmetric' mode."""
+    c = (patch - 1) // 2
+    image = np.asarray(image)
+    return np.pad(image, ((0, 0), (0, 0), (c, patch - 1 - c), (c, patch - 1 - c)), mode="symmetric")
+
+
 def window_key(layers, in_ch, patch, B, H, W, layer, b, c, y, x):
     """Key of a pooling window in the whole-image map of MP layer `layer` (see orc_ties)."""
     _, ch, ny, nx = dense_shape(layers, in_ch, patch, B, H, W, layer)[:4]

@@ -14,10 +14,13 @@
 
 namespace mpcnn {
 
-// a0: planar fp32 [B][C][H][W] -> channels-last [B][H][W][C] in the storage type
+// a0: planar fp32 [B][C][Hs][Ws] -> channels-last [B][H][W][C] in the storage type.  The
+// destination may be larger than the source: it then starts `top` rows above and `left`
+// columns left of it, and what lies outside the source is its mirror image with the edge
+// pixel repeated (Experiments: borders of test images synthesised by mirroring).
 template <typename T>
 __global__ void stage_input_kernel(const float* __restrict__ src, T* __restrict__ dst, int B,
-                                   int C, int H, int W)
+                                   int C, int H, int W, int Hs, int Ws, int top, int left)
 {
     long total = (long)B * C * H * W;
     for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
@@ -28,7 +31,10 @@ __global__ void stage_input_kernel(const float* __restrict__ src, T* __restrict_
         long q = p / W;
         int y = (int)(q % H);
         int b = (int)(q / H);
-        store1(dst + e, src[(((long)b * C + c) * H + y) * W + x]);
+        int ys = y - top, xs = x - left;
+        ys = ys < 0 ? -1 - ys : (ys >= Hs ? 2 * Hs - 1 - ys : ys);
+        xs = xs < 0 ? -1 - xs : (xs >= Ws ? 2 * Ws - 1 - xs : xs);
+        store1(dst + e, src[(((long)b * C + c) * Hs + ys) * Ws + xs]);
     }
 }
 

@@ -115,6 +115,8 @@ struct Geom {
     std::vector<size_t> code_off;     // MP layers: byte offset of the argmax map
     std::vector<TilePlan> fwd, dgrad;
     std::vector<WgradPlan> wgrad;
+    int pad_top = 0, pad_left = 0;    // same-size forward: H, W are the mirrored image's, which starts
+    int src_h = 0, src_w = 0;         //   this far above / left of the caller's src_h x src_w image
     bool staged = false;              // the image is copied to channels-last storage first
     size_t staged_off = 0;            // that copy (C0 > 1, or bf16 storage)
     size_t delta_off[2] = {0, 0};     // two delta buffers, each as large as the largest map
@@ -327,7 +329,7 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
 
 int class_blocks(long positions) { return (int)std::min<long>(kLossBlocks, (positions + 15) / 16); }
 
-bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g)
+bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g, bool mirrored = false)
 {
     if (B < 1 || H < net->patch || W < net->patch) return false;
     const size_t L = net->layers.size();
@@ -338,7 +340,8 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
     g->partial_off.assign(L, 0); g->partial_n.assign(L, 0); g->partial_len.assign(L, 0);
     size_t off = 0, max_act = 0;
     const size_t es = net->bf16 ? 2 : 4;   // bytes per stored activation / delta element
-    g->staged = net->in_ch > 1 || net->bf16;
+    g->src_h = H; g->src_w = W;
+    g->staged = net->in_ch > 1 || net->bf16 || mirrored;
     if (g->staged) {
         g->staged_off = off;
         off = align_up(off + es * (size_t)B * H * W * net->in_ch);
@@ -535,7 +538,8 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
         T* staged = (T*)(ws + g.staged_off);
         long total = (long)B * Ci * Hi * Wi;
         LAUNCH("stage_input", -1, 0, 0, (4.0 + es) * total,
-               stage_input_kernel<T><<<grid_for(total), 256, 0, st>>>(image, staged, B, Ci, Hi, Wi));
+               stage_input_kernel<T><<<grid_for(total), 256, 0, st>>>(image, staged, B, Ci, Hi, Wi, g.src_h,
+                                                                       g.src_w, g.pad_top, g.pad_left));
         in = staged;
     } else if constexpr (kF32) {
         in = image;
@@ -1002,6 +1006,44 @@ mpcnn_status mpcnn_seg_forward(mpcnn_net* net, const float* image_dev, int B, in
                                               nullptr, nullptr, (hipStream_t)hip_stream)
                    : run_forward<float>(net, g, image_dev, (char*)ws_dev, nullptr, nullptr, probs_dev, nullptr,
                                         nullptr, (hipStream_t)hip_stream);
+    net->last = g; net->last_ws = ws_dev;
+    return st;
+}
+
+// geometry of the same-size forward: the net runs on the image extended by P-1 mirrored rows / columns
+static bool make_geom_same(const mpcnn_net* net, int B, int H, int W, Geom* g)
+{
+    const int c = (net->patch - 1) / 2;
+    if (!make_geom(net, B, H + net->patch - 1, W + net->patch - 1, false, g, true)) return false;
+    g->pad_top = c; g->pad_left = c; g->src_h = H; g->src_w = W;
+    return true;
+}
+
+size_t mpcnn_workspace_bytes_same(const mpcnn_net* net, int B, int H, int W)
+{
+    if (!net || B < 1 || H < 1 || W < 1) return 0;
+    Geom g;
+    if (!make_geom_same(net, B, H, W, &g)) return 0;
+    return g.total;
+}
+
+mpcnn_status mpcnn_seg_forward_same(mpcnn_net* net, const float* image_dev, int B, int H, int W,
+                                    float* probs_dev, void* ws_dev, size_t ws_bytes, void* hip_stream)
+{
+    if (!net || !image_dev || !ws_dev || !probs_dev) return fail(MPCNN_EINVAL, "null argument");
+    if (!net->d_params) return fail(MPCNN_EINVAL, "parameters were never set");
+    if (B < 1) return fail(MPCNN_EINVAL, "B = %d", B);
+    const int widest = net->patch - 1 - (net->patch - 1) / 2;
+    if (H < 1 || W < 1 || H < widest || W < widest)
+        return fail(MPCNN_ESHAPE, "image %dx%d smaller than the %d-pixel mirrored border", H, W, widest);
+    Geom g;
+    if (!make_geom_same(net, B, H, W, &g)) return fail(MPCNN_ESHAPE, "layer plan does not fit a %dx%d image", H, W);
+    if (ws_bytes < g.total) return fail(MPCNN_EWORKSPACE, "workspace %zu bytes, need %zu", ws_bytes, g.total);
+    if (((uintptr_t)ws_dev & 255u) != 0) return fail(MPCNN_EINVAL, "workspace must be 256-byte aligned");
+    mpcnn_status st = net->bf16 ? run_forward<mpcnn::bf16>(net, g, image_dev, (char*)ws_dev, nullptr, nullptr,
+                                                           probs_dev, nullptr, nullptr, (hipStream_t)hip_stream)
+                                : run_forward<float>(net, g, image_dev, (char*)ws_dev, nullptr, nullptr, probs_dev,
+                                                     nullptr, nullptr, (hipStream_t)hip_stream);
     net->last = g; net->last_ws = ws_dev;
     return st;
 }

@@ -28,7 +28,7 @@ SYMBOLS = [
     "mpcnn_param_count", "mpcnn_layer_shape", "mpcnn_set_params", "mpcnn_get_params",
     "mpcnn_get_grads", "mpcnn_workspace_bytes", "mpcnn_seg_forward", "mpcnn_seg_backward",
     "mpcnn_sgd_step", "mpcnn_get_activation", "mpcnn_get_argmax", "mpcnn_last_error",
-    "mpcnn_profile_enable", "mpcnn_profile_read",
+    "mpcnn_profile_enable", "mpcnn_profile_read", "mpcnn_workspace_bytes_same", "mpcnn_seg_forward_same",
 ]
 
 
@@ -79,6 +79,9 @@ def lib():
         L.mpcnn_workspace_bytes.argtypes = [vp, i, i, i, i]
         L.mpcnn_workspace_bytes.restype = sz
         L.mpcnn_seg_forward.argtypes = [vp, vp, i, i, i, vp, vp, sz, vp]
+        L.mpcnn_workspace_bytes_same.argtypes = [vp, i, i, i]
+        L.mpcnn_workspace_bytes_same.restype = sz
+        L.mpcnn_seg_forward_same.argtypes = [vp, vp, i, i, i, vp, vp, sz, vp]
         L.mpcnn_seg_backward.argtypes = [vp, vp, vp, vp, i, i, i, vp, vp, vp, sz, vp]
         L.mpcnn_sgd_step.argtypes = [vp, C.c_float, C.c_float, vp]
         L.mpcnn_get_activation.argtypes = [vp, i, vp, sz]
@@ -185,6 +188,24 @@ class Net:
                                 dtype=torch.float32, device=image.device)
         _check(lib().mpcnn_seg_forward(self._h, _ptr(image), B, H, W, _ptr(probs), _ptr(ws),
                                        ws.numel(), _stream_handle(stream)))
+        return probs
+
+    def seg_forward_same(self, image, probs=None, ws=None, stream=None):
+        """Deployment forward with mirrored borders: image [B,C0,H,W] -> probs [B,n_cls,H,W]."""
+        import torch
+        B, _, H, W = image.shape
+        assert image.is_cuda and image.dtype == torch.float32 and image.is_contiguous()
+        if ws is None:
+            need = lib().mpcnn_workspace_bytes_same(self._h, B, H, W)
+            if need == 0:
+                raise MpcnnError(2, "image %dx%d does not fit the net" % (H, W))
+            if self._ws is None or self._ws.numel() < need:
+                self._ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+            ws = self._ws
+        if probs is None:
+            probs = torch.empty((B, self.n_classes, H, W), dtype=torch.float32, device=image.device)
+        _check(lib().mpcnn_seg_forward_same(self._h, _ptr(image), B, H, W, _ptr(probs), _ptr(ws),
+                                            ws.numel(), _stream_handle(stream)))
         return probs
 
     def seg_backward(self, image, labels, pixw=None, probs=None, loss=None, ws=None, stream=None):

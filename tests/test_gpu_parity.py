@@ -356,6 +356,56 @@ def test_bf16_refuses_shapes_without_a_kernel():
         mpcnn.Net(wl.CONFIGS[0].layers, 1, 18, dtype=mpcnn.BF16)
 
 
+def test_forward_same_size_mirrored_borders():
+    """Deployment forward: borders synthesised by mirroring, output as large as the image."""
+    for cfg in (wl.crop(wl.CONFIGS[0], 2, 31, 40), wl.crop(wl.CONFIGS[1], 1, 70, 61),
+                wl.Workload("bf16_small", _NET_BF16_SMALL, 14, 3, 3, 1, 33, 29, 0.25, "ellipses", dtype="bf16",
+                            seed_image=1105, seed_label=2105, seed_param=3105)):
+        img, lab = wl.make_inputs(cfg)
+        params = wl.make_params(cfg)
+        say("case %s same-size forward %dx%d" % (cfg.name, cfg.height, cfg.width))
+        net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch,
+                        dtype=mpcnn.BF16 if cfg.dtype == "bf16" else mpcnn.F32)
+        net.set_params(params)
+        probs = net.seg_forward_same(torch.from_numpy(img).cuda()).cpu().numpy()
+        ref = oracle.run(cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64),
+                         oracle.mirror_pad(img.astype(np.float64), cfg.patch))["probs"]
+        assert probs.shape == ref.shape == (cfg.batch, cfg.n_classes, cfg.height, cfg.width)
+        err = np.abs(probs - ref).max()
+        say("  probs err %.2e" % err)
+        assert err <= tol_of(cfg)
+        # the interior equals the plain valid-region forward, bit for bit
+        valid = net.seg_forward(torch.from_numpy(img).cuda()).cpu().numpy()
+        c = (cfg.patch - 1) // 2
+        np.testing.assert_array_equal(probs[:, :, c:c + valid.shape[2], c:c + valid.shape[3]], valid)
+        # images smaller than the widest border are refused
+        small = torch.zeros((1, cfg.in_channels, cfg.patch // 2 - 1, 40), device="cuda")
+        with pytest.raises(mpcnn.MpcnnError):
+            net.seg_forward_same(small)
+        net.close()
+
+
+def test_cfg1_full_size_forward_same_sampled():
+    cfg = wl.CONFIGS[1]
+    img, lab = wl.make_inputs(cfg)
+    params = wl.make_params(cfg)
+    net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch)
+    net.set_params(params)
+    probs = net.seg_forward_same(torch.from_numpy(img).cuda()).cpu().numpy()
+    rng = np.random.default_rng(15)
+    # seeded pixels, half of them within a patch of the border where the mirror matters
+    ii = np.concatenate([rng.integers(0, cfg.height, 96), rng.integers(0, 20, 48), rng.integers(cfg.height - 20, cfg.height, 48)])
+    jj = np.concatenate([rng.integers(0, cfg.width, 96), rng.integers(0, cfg.width, 48), rng.integers(0, 20, 48)])
+    sel = np.unique(ii * cfg.width + jj)
+    ref = oracle.run(cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64),
+                     oracle.mirror_pad(img.astype(np.float64), cfg.patch), sel=sel)["probs"]
+    err = np.abs(probs[0][:, sel // cfg.width, sel % cfg.width].T - ref).max()
+    say("cfg1 same-size forward, %d sampled pixels: probs err %.2e" % (sel.size, err))
+    assert err <= TOL
+    assert np.isfinite(probs).all() and np.abs(probs.sum(1) - 1).max() < 1e-5
+    net.close()
+
+
 def test_forward_only_matches_and_is_deterministic():
     cfg = wl.crop(wl.CONFIGS[1], 2, 80, 75)
     img, lab = wl.make_inputs(cfg)

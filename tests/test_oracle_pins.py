@@ -422,6 +422,31 @@ def test_translation_structure():
     np.testing.assert_array_equal(a[:, :, 1:, 1:], b[:, :, :-1, :-1])
 
 
+def test_mirror_pad_by_hand():
+    """Borders synthesised by mirroring, edge pixel repeated; c = (P-1)//2 above/left and
+    P-1-c below/right, so that output (i,j) is the patch centred on input (i,j)
+    (Experiments, membrane segmentation).  Written out for a 2x3 image and P = 4."""
+    x = np.array([[1., 2., 3.], [4., 5., 6.]])[None, None]
+    got = oracle.mirror_pad(x, 4)[0, 0]          # c = 1: one row/col before, two after
+    want = np.array([[1., 1., 2., 3., 3., 2.],
+                     [1., 1., 2., 3., 3., 2.],
+                     [4., 4., 5., 6., 6., 5.],
+                     [4., 4., 5., 6., 6., 5.],
+                     [1., 1., 2., 3., 3., 2.]])
+    np.testing.assert_array_equal(got, want)
+    # the patch net on the extended image gives one output per input pixel, and an interior
+    # output equals the plain valid-region output of the same patch
+    layers, in_ch, P = NETS["tiny18"]
+    rng = np.random.default_rng(21)
+    params = rand_params(layers, in_ch, P, 22)
+    img = rng.uniform(0, 1, (1, in_ch, 22, 25))
+    same = oracle.run(layers, in_ch, P, params, oracle.mirror_pad(img, P))["probs"]
+    valid = oracle.run(layers, in_ch, P, params, img)["probs"]
+    assert same.shape[2:] == img.shape[2:]
+    c = (P - 1) // 2
+    np.testing.assert_array_equal(same[:, :, c:c + valid.shape[2], c:c + valid.shape[3]], valid)
+
+
 def test_bad_descriptions_are_rejected():
     with pytest.raises(ValueError):
         oracle.param_count(((C, 2, 3), (MP, 0, 2)), 1, 8)          # must end with FC
