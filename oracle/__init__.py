@@ -67,10 +67,13 @@ def param_count(layers, in_ch: int, patch: int) -> int:
 
 
 def run(layers, in_ch, patch, params, image, labels=None, pixw=None, sel=None,
-        want_probs=True, want_grads=False, want_dimage=False, tie_tau=0.0, alt=None):
+        want_probs=True, want_grads=False, want_dimage=False, tie_tau=0.0, alt=None, loss_fn="mcce"):
     """Patch-by-patch forward (and backward).  Returns a dict with probs, loss,
     grads, dimage (those asked for).  probs is [B,n_cls,Ho,Wo], or [n_sel,n_cls]
     when `sel` (flat indices into [B,Ho,Wo]) is given.
+
+    loss_fn: "mcce" (softmax + cross-entropy) or "mse" (linear outputs, half the squared
+    error against the one-hot target; `probs` then holds the linear outputs).
 
     tie_tau > 0: also returns `near_ties`, an int64 array [n,4] of (window key,
     chosen tap, runner-up tap, layer) for every pooling window whose two largest
@@ -129,7 +132,7 @@ def run(layers, in_ch, patch, params, image, labels=None, pixw=None, sel=None,
                          _p(grads, C.c_double), _p(dimage, C.c_double),
                          C.c_double(tie_tau), _p(alt_key, C.c_int64), _p(alt_tap, C.c_uint8), C.c_long(n_alt),
                          _p(amb, C.c_int64), C.c_long(amb_cap if amb is not None else 0),
-                         C.byref(amb_n), C.byref(rejected))
+                         C.byref(amb_n), C.byref(rejected), {"mcce": 0, "mse": 1}[loss_fn])
         if rc != 0:
             raise ValueError("orc_run failed (code %d)" % rc)
         if amb is None or amb_n.value <= amb_cap:
@@ -151,6 +154,24 @@ def mirror_pad(image, patch):
     c = (patch - 1) // 2
     image = np.asarray(image)
     return np.pad(image, ((0, 0), (0, 0), (c, patch - 1 - c), (c, patch - 1 - c)), mode="symmetric")
+
+
+def class_balance_weights(labels, n_classes, patch):
+    """Per-pixel weights that make the summed loss the sum over classes of each class's MEAN
+    loss (Experiments, steel defects: the loss is minimised per class because the data set is
+    unbalanced): w = 1 / N_k at a pixel of class k, N_k = number of output pixels of class k
+    in the batch (labels are read at the patch centres, (i+c, j+c)); 0 elsewhere."""
+    labels = np.asarray(labels)
+    B, H, W = labels.shape
+    c = (patch - 1) // 2
+    Ho, Wo = H - patch + 1, W - patch + 1
+    w = np.zeros(labels.shape, dtype=np.float64)
+    centre = labels[:, c:c + Ho, c:c + Wo]
+    for k in range(n_classes):
+        n_k = int((centre == k).sum())
+        if n_k:
+            w[:, c:c + Ho, c:c + Wo][centre == k] = 1.0 / n_k
+    return w
 
 
 def window_key(layers, in_ch, patch, B, H, W, layer, b, c, y, x):

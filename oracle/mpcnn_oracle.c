@@ -20,6 +20,10 @@
  *       matrix * vector.  Hidden FCs apply tanh; the last FC feeds a softmax.
  * Loss (Results, first paragraph): multi-class cross-entropy, each pixel on its
  * own, here summed over pixels: L = sum_pix w_pix * -log p_pix[t_pix].
+ * Alternative (Method, before the MPF back-propagation): mean squared error with
+ * linear outputs, whose derivative w.r.t. the output image is x^ - t; here
+ * L = sum_pix w_pix * 1/2 * sum_o (x^_pix[o] - [o == t_pix])^2, the outputs being the
+ * last FC's values without the softmax.
  * Back-propagation is the textbook one the paper defers to (Background, end).
  *
  * Pins: see tests/test_oracle_pins.py (autograd in fp64 on single patches,
@@ -38,6 +42,7 @@
 
 #define ORC_MAXL 32
 enum { ORC_C = 0, ORC_MP = 1, ORC_FC = 2 };
+enum { ORC_LOSS_MCCE = 0, ORC_LOSS_MSE = 1 };
 
 typedef struct {
     int n_layers, in_ch, patch, n_classes;
@@ -51,6 +56,7 @@ typedef struct {
     long act_off[ORC_MAXL + 1];               /* act 0 = the patch itself, act l+1 = output of layer l */
     long idx_off[ORC_MAXL];
     long act_total, idx_total, n_params;
+    int loss_kind;                            /* ORC_LOSS_*: what follows the last FC */
 } orc_plan;
 
 /* Shape inference.  Returns 0, or a negative code naming the first problem. */
@@ -205,6 +211,10 @@ static void orc_patch_forward(const orc_plan *pl, const double *par, double *act
         }
     }
     const double *z = act + pl->act_off[pl->n_layers];
+    if (pl->loss_kind == ORC_LOSS_MSE) {   /* linear outputs */
+        for (int o = 0; o < pl->n_classes; ++o) probs[o] = z[o];
+        return;
+    }
     double zmax = z[0], sum = 0;
     for (int o = 1; o < pl->n_classes; ++o) if (z[o] > zmax) zmax = z[o];
     for (int o = 0; o < pl->n_classes; ++o) { probs[o] = exp(z[o] - zmax); sum += probs[o]; }
@@ -307,17 +317,21 @@ int orc_threads(void)
  *   tie_tau, alt + alt_tap, amb, rejected: near-tie reporting / alternative routing (see
  *   orc_ties); amb receives up to amb_cap records of 4 int64, *amb_n the number met, and
  *   *rejected the number of refused pairs (a window is met once per patch that contains it).
+ *   loss_kind  ORC_LOSS_MCCE: probs = softmax; ORC_LOSS_MSE: probs = the linear outputs.
+ *   (the delta at the outputs is w * (probs - onehot) in both cases)
  */
 int orc_run(const int *kinds, const int *maps, const int *ks, int n_layers, int in_ch, int patch,
             const double *params, const double *image, int B, int H, int W,
             const int32_t *labels, const double *pixw, const int64_t *sel, long n_sel,
             double *probs, double *loss, double *grads, double *dimage,
             double tie_tau, const int64_t *alt, const uint8_t *alt_tap, long n_alt,
-            int64_t *amb, long amb_cap, long *amb_n, long *rejected)
+            int64_t *amb, long amb_cap, long *amb_n, long *rejected, int loss_kind)
 {
     orc_plan pl;
     int rc = orc_make_plan(&pl, kinds, maps, ks, n_layers, in_ch, patch);
     if (rc < 0) return rc;
+    if (loss_kind != ORC_LOSS_MCCE && loss_kind != ORC_LOSS_MSE) return -12;
+    pl.loss_kind = loss_kind;
     const int P = patch, Ho = H - P + 1, Wo = W - P + 1, ctr = (P - 1) / 2, nc = pl.n_classes;
     if (Ho < 1 || Wo < 1 || B < 1) return -10;
     if ((grads || loss) && !labels) return -11;
@@ -367,7 +381,13 @@ int orc_run(const int *kinds, const int *maps, const int *ks, int n_layers, int 
                 int t_lab = labels[lp];
                 double w = pixw ? pixw[lp] : 1.0;
                 if (t_lab < 0 || t_lab >= nc) continue;
-                loss_all[t] += w * -log(pr[t_lab]);
+                if (pl.loss_kind == ORC_LOSS_MSE) {
+                    double sq = 0;
+                    for (int o = 0; o < nc; ++o) { double e = pr[o] - (o == t_lab ? 1.0 : 0.0); sq += e * e; }
+                    loss_all[t] += w * 0.5 * sq;
+                } else {
+                    loss_all[t] += w * -log(pr[t_lab]);
+                }
                 if (!grads && !dimage) continue;
                 double *g = grads ? g_all + (size_t)t * pl.n_params : NULL;
                 double *gtmp = g;

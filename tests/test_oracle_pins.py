@@ -422,6 +422,62 @@ def test_translation_structure():
     np.testing.assert_array_equal(a[:, :, 1:, 1:], b[:, :, :-1, :-1])
 
 
+@pytest.mark.parametrize("name", ["tiny18", "rgb_p3"])
+def test_mse_linear_outputs_vs_autograd_and_by_hand(name):
+    """Mean squared error with linear outputs: the derivative w.r.t. the output image is
+    x^ - t (Method, the first step of back-propagation).  Outputs = last FC without the
+    softmax; L = sum w/2 |x^ - onehot|^2; everything below the outputs as for the other loss."""
+    layers, in_ch, P = NETS[name]
+    rng = np.random.default_rng(31)
+    params = rand_params(layers, in_ch, P, 32)
+    img = rng.uniform(0, 1, (2, in_ch, P, P))
+    n_cls = layers[-1][1]
+    lab = rng.integers(0, n_cls, (2, P, P)).astype(np.int32)
+    pw = rng.uniform(0.5, 2.0, (2, P, P))
+    r = oracle.run(layers, in_ch, P, params, img, lab, pw, want_grads=True, want_dimage=True, loss_fn="mse")
+    pt = torch.tensor(params, dtype=torch.float64, requires_grad=True)
+    xt = torch.tensor(img, dtype=torch.float64, requires_grad=True)
+    z = torch_patch_net(layers, in_ch, P, pt, xt)
+    c = (P - 1) // 2
+    t = F.one_hot(torch.tensor(lab[:, c, c].astype(np.int64)), n_cls).to(torch.float64)
+    loss = (0.5 * ((z - t) ** 2).sum(1) * torch.tensor(pw[:, c, c])).sum()
+    loss.backward()
+    np.testing.assert_allclose(r["probs"].reshape(2, n_cls), z.detach().numpy(), rtol=1e-12, atol=1e-14)
+    assert abs(r["loss"] - loss.item()) <= 1e-12 * abs(loss.item())
+    np.testing.assert_allclose(r["grads"], pt.grad.numpy(), rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(r["dimage"], xt.grad.numpy(), rtol=1e-10, atol=1e-13)
+    # by hand, one FC on a 1x1 patch: z = W x + b = (0.25, 0.3), t = (0, 1)
+    r1 = oracle.run(((FC, 2, 0),), 1, 1, np.array([0.3, -0.2, 0.1, 0.4]), np.array([[[[0.5]]]]),
+                    np.array([[[1]]], dtype=np.int32), want_grads=True, loss_fn="mse")
+    np.testing.assert_allclose(r1["probs"].ravel(), [0.25, 0.3], rtol=0, atol=1e-15)
+    assert abs(r1["loss"] - 0.5 * (0.25 ** 2 + 0.7 ** 2)) < 1e-15
+    np.testing.assert_allclose(r1["grads"], [0.125, -0.35, 0.25, -0.7], rtol=0, atol=1e-15)
+
+
+def test_class_balance_weights_by_hand():
+    """Loss minimised per class: w = 1/N_k over the OUTPUT pixels (labels at patch centres),
+    so that each class contributes its mean loss (Experiments, steel defects)."""
+    lab = np.array([[[0, 0, 0, 0],
+                     [0, 1, 0, 9],
+                     [0, 0, 0, 0],
+                     [1, 1, 1, 1]]], dtype=np.int32)
+    w = oracle.class_balance_weights(lab, 2, 3)       # P = 3: outputs are the 2x2 centres (1..2, 1..2)
+    want = np.zeros((1, 4, 4))
+    want[0, 1, 1] = 1.0                                # the only class-1 centre
+    want[0, 1, 2] = want[0, 2, 1] = want[0, 2, 2] = 1.0 / 3
+    np.testing.assert_array_equal(w, want)
+    # with these weights the loss is the sum of the per-class mean losses
+    layers, in_ch, P = ((FC, 2, 0),), 1, 3
+    rng = np.random.default_rng(5)
+    params = rng.uniform(-0.5, 0.5, oracle.param_count(layers, in_ch, P))
+    img = rng.uniform(0, 1, (1, 1, 4, 4))
+    r = oracle.run(layers, in_ch, P, params, img, lab, w)
+    nll = -np.log(r["probs"][0])                       # [class][i][j]
+    centre = lab[0, 1:3, 1:3]
+    per_class = sum(nll[k][centre == k].mean() for k in (0, 1))
+    assert abs(r["loss"] - per_class) < 1e-13
+
+
 def test_mirror_pad_by_hand():
     """Borders synthesised by mirroring, edge pixel repeated; c = (P-1)//2 above/left and
     P-1-c below/right, so that output (i,j) is the patch centred on input (i,j)
