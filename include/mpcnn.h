@@ -112,6 +112,25 @@ mpcnn_status mpcnn_get_params(const mpcnn_net* net, float* params_host, size_t n
  * as the parameters (Alg. 2: the sum over all fragments / pixels). */
 mpcnn_status mpcnn_get_grads(const mpcnn_net* net, float* grads_host, size_t n);
 
+/* What follows the last FC layer.  MCCE (default): softmax, L = sum w * -log p[t]
+ * (Results: multi-class cross-entropy, every pixel on its own).  MSE: linear outputs,
+ * L = sum w * 1/2 * sum_o (x^[o] - [o == t])^2, whose derivative w.r.t. the output image
+ * is x^ - t (Method, first step of back-propagation); `probs_dev` of the forward and
+ * backward calls then receives the linear outputs.  EINVAL on an unknown kind. */
+typedef enum { MPCNN_LOSS_MCCE = 0, MPCNN_LOSS_MSE = 1 } mpcnn_loss;
+mpcnn_status mpcnn_set_loss(mpcnn_net* net, mpcnn_loss kind);
+
+/* Per-class balanced pixel weights (Experiments, steel defects: the loss is minimised per
+ * class because the data set is unbalanced):  pixw_dev[b][y][x] = 1 / N_k where the pixel is
+ * the centre of a patch (an output pixel) with label k in [0, n_classes), N_k = number of
+ * such pixels in the batch; 0 everywhere else.  Passed as pixw_dev to mpcnn_seg_backward it
+ * makes L the sum over classes of each class's mean loss.
+ *   labels_dev [B][H][W] int32, pixw_dev [B][H][W] fp32 (written),
+ *   counts_dev: 64 bytes of device scratch (the N_k, 16 uint32, left there).
+ * Errors: EINVAL, ESHAPE (H or W < P), EHIP. */
+mpcnn_status mpcnn_class_balance_weights(const mpcnn_net* net, const int32_t* labels_dev, int B, int H,
+                                         int W, float* pixw_dev, void* counts_dev, void* hip_stream);
+
 /* Bytes of caller-owned device workspace a call with these sizes needs
  * (training != 0: mpcnn_seg_backward; 0: mpcnn_seg_forward).  0 on bad input. */
 size_t mpcnn_workspace_bytes(const mpcnn_net* net, int B, int H, int W, int training);

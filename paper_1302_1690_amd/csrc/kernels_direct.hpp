@@ -178,10 +178,12 @@ constexpr int kMaxClasses = 16;
 // a3 (second half): softmax over the class logits of every pixel, probabilities out in
 // planar [B][n_cls][Ho][Wo]; with labels: delta = w (p - onehot) and the block's share of
 // the summed cross-entropy (Results: MCCE per pixel; Method: first step of back-prop).
+// mse != 0: linear outputs and half the squared error instead (Method: the derivative of
+// the mean squared error w.r.t. the output image is x^ - t); `probs` then gets the outputs.
 __global__ void softmax_ce_kernel(const float* __restrict__ Z, float* __restrict__ probs,
                                   const int32_t* __restrict__ labels, const float* __restrict__ pixw,
                                   float* __restrict__ dZ, double* __restrict__ loss_partial, int B,
-                                  int Ho, int Wo, int H, int W, int ctr, int n_cls)
+                                  int Ho, int Wo, int H, int W, int ctr, int n_cls, int mse)
 {
     __shared__ double red[256];
     long total = (long)B * Ho * Wo;
@@ -213,13 +215,17 @@ __global__ void softmax_ce_kernel(const float* __restrict__ Z, float* __restrict
             if (t < 0 || t >= n_cls) t = -1;
             else w = pixw ? pixw[lp] : 1.f;
         }
+        float sq = 0.f;
         for (int o = 0; o < n_cls; ++o) {
-            float p = expf(z[o]) * inv;
+            float p = mse ? z[o] + zmax : expf(z[o]) * inv;
             if (probs) probs[(((long)b * n_cls + o) * Ho + i) * Wo + j] = p;
-            if (dZ) dZ[m * n_cls + o] = (t >= 0) ? w * (p - (o == t ? 1.f : 0.f)) : 0.f;
+            const float e = p - (o == t ? 1.f : 0.f);
+            if (dZ) dZ[m * n_cls + o] = (t >= 0) ? w * e : 0.f;
             if (o == t) zt = z[o];
+            sq += e * e;
         }
-        if (t >= 0) my_loss += (double)w * ((double)logf(sum) - (double)zt);  // -log p[t]
+        if (t >= 0) my_loss += mse ? (double)w * 0.5 * (double)sq
+                                   : (double)w * ((double)logf(sum) - (double)zt);  // -log p[t]
     }
     if (loss_partial) {
         red[threadIdx.x] = my_loss;
@@ -239,6 +245,44 @@ __global__ void sgd_kernel(float* __restrict__ theta, const float* __restrict__ 
     long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e < n) theta[e] = fmaf(-step, g[e], theta[e]);
 }
+
+// Per-class balanced weights (Experiments, steel defects: the loss is minimised per class):
+// counts[k] = number of output pixels whose label (read at the patch centre) is k, then
+// w = 1 / counts[k] at those pixels and 0 everywhere else.  Integer atomics: exact.
+__global__ void label_count_kernel(const int32_t* __restrict__ labels, unsigned* __restrict__ counts,
+                                   int B, int H, int W, int Ho, int Wo, int ctr, int n_cls)
+{
+    __shared__ unsigned hist[kMaxClasses];
+    if (threadIdx.x < kMaxClasses) hist[threadIdx.x] = 0;
+    __syncthreads();
+    const long total = (long)B * Ho * Wo;
+    for (long m = (long)blockIdx.x * blockDim.x + threadIdx.x; m < total; m += (long)gridDim.x * blockDim.x) {
+        const int j = (int)(m % Wo);
+        const long q = m / Wo;
+        const int i = (int)(q % Ho), b = (int)(q / Ho);
+        const int t = labels[((long)b * H + (i + ctr)) * W + (j + ctr)];
+        if (t >= 0 && t < n_cls) atomicAdd(&hist[t], 1u);
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < n_cls && hist[threadIdx.x]) atomicAdd(&counts[threadIdx.x], hist[threadIdx.x]);
+}
+__global__ void balance_fill_kernel(const int32_t* __restrict__ labels, const unsigned* __restrict__ counts,
+                                    float* __restrict__ pixw, int B, int H, int W, int Ho, int Wo, int ctr,
+                                    int n_cls)
+{
+    const long total = (long)B * H * W;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long)gridDim.x * blockDim.x) {
+        const int x = (int)(e % W);
+        const long q = e / W;
+        const int y = (int)(q % H);
+        const int i = y - ctr, j = x - ctr;
+        const int t = labels[e];
+        float w = 0.f;
+        if (i >= 0 && i < Ho && j >= 0 && j < Wo && t >= 0 && t < n_cls) w = 1.f / (float)counts[t];
+        pixw[e] = w;
+    }
+}
+__global__ void clear_counts_kernel(unsigned* counts) { if (threadIdx.x < kMaxClasses) counts[threadIdx.x] = 0; }
 
 // bf16 storage: the kernels read parameters rounded to bf16 (kept as fp32 values); the fp32
 // originals stay the optimiser's state.

@@ -194,6 +194,7 @@ struct ClassArgs {
     float* partial;        // [blocks][(K+1)*NCLS]  (training) this block's share of dW, db
     double* loss_partial;  // [blocks] or null
     int B, Ho, Wo, H, W, ctr, K, tanh_below;
+    int mse;               // linear outputs + half the squared error instead of softmax + cross-entropy
 };
 
 // a3 + a4 in one pass over h: class logits z = W h + b, softmax, probabilities out; in
@@ -256,7 +257,11 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
         float sum = 0.f, pr[NCLS];
 #pragma unroll
         for (int o = 0; o < NCLS; ++o) { z[o] -= zmax; pr[o] = expf(z[o]); sum += pr[o]; }
-        const float inv = 1.f / sum;
+        const float inv = a.mse ? 1.f : 1.f / sum;
+        if (a.mse) {   // the outputs themselves (Method: mean squared error with linear outputs)
+#pragma unroll
+            for (int o = 0; o < NCLS; ++o) pr[o] = z[o] + zmax;
+        }
         const int jx = (int)(m % a.Wo);
         const long qq = m / a.Wo;
         const int iy = (int)(qq % a.Ho), b = (int)(qq / a.Ho);
@@ -272,14 +277,17 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
             if (t < 0 || t >= NCLS) t = -1;
             else wt = a.pixw ? a.pixw[lp] : 1.f;
             float dz[NCLS];
-            float zt = 0.f;
+            float zt = 0.f, sq = 0.f;
 #pragma unroll
             for (int o = 0; o < NCLS; ++o) {
-                dz[o] = t >= 0 ? wt * (pr[o] - (o == t ? 1.f : 0.f)) : 0.f;
+                const float e = pr[o] - (o == t ? 1.f : 0.f);
+                dz[o] = t >= 0 ? wt * e : 0.f;
                 if (o == t) zt = z[o];
                 gb[o] += dz[o];
+                sq += e * e;
             }
-            if (t >= 0 && j == 0) my_loss += (double)wt * ((double)logf(sum) - (double)zt);
+            if (t >= 0 && j == 0)
+                my_loss += a.mse ? (double)wt * 0.5 * (double)sq : (double)wt * ((double)logf(sum) - (double)zt);
 #pragma unroll
             for (int v = 0; v < KV; ++v) {
                 const int c = 4 * (j + 16 * v);

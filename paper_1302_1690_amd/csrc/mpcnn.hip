@@ -140,6 +140,7 @@ struct mpcnn_net {
     std::vector<Layer> layers;
     int in_ch = 0, patch = 0, n_cls = 0;
     size_t n_params = 0, pack_len = 0;
+    int loss_kind = MPCNN_LOSS_MCCE;
     bool bf16 = false;            // activations and deltas stored in bf16 (arithmetic stays fp32)
     float* d_params = nullptr;
     float* d_wread = nullptr;     // what the kernels read: d_params, or its copy rounded to bf16 values
@@ -575,6 +576,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             a.loss_partial = want_loss ? lp : nullptr;
             a.B = B; a.Ho = Ho; a.Wo = Wo; a.H = g.H; a.W = g.W; a.ctr = (net->patch - 1) / 2;
             a.K = Ci; a.tanh_below = (l > 0 && net->layers[l - 1].tanh_out) ? 1 : 0;
+            a.mse = net->loss_kind == MPCNN_LOSS_MSE;
             const int blocks = class_blocks(M);
             const bool train = labels != nullptr;
             const double flops = 2.0 * M * Ci * ly.cout * (train ? 3.0 : 1.0);
@@ -625,7 +627,8 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
         LAUNCH("softmax_ce", L - 1, 3, 0, 4.0 * total * (3.0 * net->n_cls + 2.0),
                softmax_ce_kernel<<<blocks, 256, 0, st>>>(in, probs, labels, pixw, dZ,
                                                          want_loss ? lp : nullptr, B, Hi, Wi, g.H, g.W,
-                                                         (net->patch - 1) / 2, net->n_cls));
+                                                         (net->patch - 1) / 2, net->n_cls,
+                                                         net->loss_kind == MPCNN_LOSS_MSE));
         if (want_loss)
             LAUNCH("loss_tree", L - 1, 0, 0, 8.0 * blocks,
                    loss_tree_kernel<<<1, 256, 0, st>>>(lp, blocks, loss_dev));
@@ -959,6 +962,33 @@ mpcnn_status mpcnn_set_params(mpcnn_net* net, const float* params_host, size_t n
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipMemcpy(net->d_params, tmp.data(), sizeof(float) * n, hipMemcpyHostToDevice));
     net->packs_stale = true; net->wread_stale = true;
+    return MPCNN_OK;
+}
+
+mpcnn_status mpcnn_set_loss(mpcnn_net* net, mpcnn_loss kind)
+{
+    if (!net) return fail(MPCNN_EINVAL, "null net");
+    if (kind != MPCNN_LOSS_MCCE && kind != MPCNN_LOSS_MSE) return fail(MPCNN_EINVAL, "unknown loss %d", (int)kind);
+    net->loss_kind = kind;
+    return MPCNN_OK;
+}
+
+mpcnn_status mpcnn_class_balance_weights(const mpcnn_net* net, const int32_t* labels_dev, int B, int H,
+                                         int W, float* pixw_dev, void* counts_dev, void* hip_stream)
+{
+    if (!net || !labels_dev || !pixw_dev || !counts_dev) return fail(MPCNN_EINVAL, "null argument");
+    if (B < 1) return fail(MPCNN_EINVAL, "B = %d", B);
+    if (H < net->patch || W < net->patch)
+        return fail(MPCNN_ESHAPE, "image %dx%d smaller than the %dx%d patch", H, W, net->patch, net->patch);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int Ho = H - net->patch + 1, Wo = W - net->patch + 1, ctr = (net->patch - 1) / 2;
+    unsigned* counts = (unsigned*)counts_dev;
+    mpcnn::clear_counts_kernel<<<1, 64, 0, st>>>(counts);
+    mpcnn::label_count_kernel<<<grid_for((long)B * Ho * Wo, 256, 1024), 256, 0, st>>>(labels_dev, counts, B, H, W, Ho,
+                                                                                    Wo, ctr, net->n_cls);
+    mpcnn::balance_fill_kernel<<<grid_for((long)B * H * W), 256, 0, st>>>(labels_dev, counts, pixw_dev, B, H, W, Ho,
+                                                                         Wo, ctr, net->n_cls);
+    HIP_TRY(hipGetLastError());
     return MPCNN_OK;
 }
 

@@ -29,6 +29,7 @@ SYMBOLS = [
     "mpcnn_get_grads", "mpcnn_workspace_bytes", "mpcnn_seg_forward", "mpcnn_seg_backward",
     "mpcnn_sgd_step", "mpcnn_get_activation", "mpcnn_get_argmax", "mpcnn_last_error",
     "mpcnn_profile_enable", "mpcnn_profile_read", "mpcnn_workspace_bytes_same", "mpcnn_seg_forward_same",
+    "mpcnn_set_loss", "mpcnn_class_balance_weights",
 ]
 
 
@@ -82,6 +83,8 @@ def lib():
         L.mpcnn_workspace_bytes_same.argtypes = [vp, i, i, i]
         L.mpcnn_workspace_bytes_same.restype = sz
         L.mpcnn_seg_forward_same.argtypes = [vp, vp, i, i, i, vp, vp, sz, vp]
+        L.mpcnn_set_loss.argtypes = [vp, i]
+        L.mpcnn_class_balance_weights.argtypes = [vp, vp, i, i, i, vp, vp, vp]
         L.mpcnn_seg_backward.argtypes = [vp, vp, vp, vp, i, i, i, vp, vp, vp, sz, vp]
         L.mpcnn_sgd_step.argtypes = [vp, C.c_float, C.c_float, vp]
         L.mpcnn_get_activation.argtypes = [vp, i, vp, sz]
@@ -189,6 +192,21 @@ class Net:
         _check(lib().mpcnn_seg_forward(self._h, _ptr(image), B, H, W, _ptr(probs), _ptr(ws),
                                        ws.numel(), _stream_handle(stream)))
         return probs
+
+    def set_loss(self, kind: str):
+        """"mcce": softmax + cross-entropy (default); "mse": linear outputs, half the squared error."""
+        _check(lib().mpcnn_set_loss(self._h, {"mcce": 0, "mse": 1}.get(kind, -1)))
+
+    def class_balance_weights(self, labels, stream=None):
+        """labels [B,H,W] int32 cuda -> pixw [B,H,W] fp32 cuda, 1/N_k at output pixels of class k."""
+        import torch
+        B, H, W = labels.shape
+        assert labels.is_cuda and labels.dtype == torch.int32 and labels.is_contiguous()
+        pixw = torch.empty((B, H, W), dtype=torch.float32, device=labels.device)
+        counts = torch.empty(16, dtype=torch.int32, device=labels.device)
+        _check(lib().mpcnn_class_balance_weights(self._h, _ptr(labels), B, H, W, _ptr(pixw), _ptr(counts),
+                                                 _stream_handle(stream)))
+        return pixw, counts
 
     def seg_forward_same(self, image, probs=None, ws=None, stream=None):
         """Deployment forward with mirrored borders: image [B,C0,H,W] -> probs [B,n_cls,H,W]."""

@@ -64,12 +64,13 @@ def check_grads(cfg, g_gpu, g_ref, tol=None):
     return worst
 
 
-def run_gpu(cfg, img, lab, params, pixw=None, net=None):
+def run_gpu(cfg, img, lab, params, pixw=None, net=None, loss_fn="mcce"):
     own = net is None
     if own:
         net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch,
                         dtype=mpcnn.BF16 if cfg.dtype == "bf16" else mpcnn.F32)
         net.set_params(params)
+        net.set_loss(loss_fn)
     B, _, H, W = img.shape
     d_img = torch.from_numpy(img).cuda()
     d_lab = torch.from_numpy(lab).cuda()
@@ -95,13 +96,13 @@ TIE_TAU_BF16 = 2.0 ** -7   # bf16 storage: two ulps at 1; values this close may 
 TOL_BF16 = 2e-2
 
 
-def oracle_run_valid_ties(cfg, params, img, lab, pixw, sel, net):
+def oracle_run_valid_ties(cfg, params, img, lab, pixw, sel, net, loss_fn="mcce"):
     """Oracle result to compare with.  Where the oracle's own two best candidates of a
     pooling window are within tau, the order may legitimately differ in the GPU's
     precision; the GPU's choice is adopted there if (the oracle checks this) that tap's
     value is within tau of the maximum, and the oracle re-evaluated."""
     kw = dict(labels=lab, pixw=None if pixw is None else pixw.astype(np.float64), sel=sel,
-              want_grads=True, tie_tau=tau_of(cfg))
+              want_grads=True, tie_tau=tau_of(cfg), loss_fn=loss_fn)
     args = (cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64), img.astype(np.float64))
     ref = oracle.run(*args, **kw)
     near = ref["near_ties"]
@@ -161,7 +162,7 @@ def check_argmax(cfg, net, img, params, with_oracle=True, layers=None):
     return excused
 
 
-def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_layers=True):
+def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_layers=True, loss_fn="mcce"):
     img, lab = wl.make_inputs(cfg)
     params = wl.make_params(cfg)
     pixw = None
@@ -171,8 +172,8 @@ def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_lay
         lab = lab.copy()
         lab[np.random.default_rng(78).random(lab.shape) < 0.1] = -1
     say("case %s B=%d %dx%d" % (cfg.name, cfg.batch, cfg.height, cfg.width))
-    net, probs, loss, grads = run_gpu(cfg, img, lab, params, pixw)
-    ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, pixw, None, net)
+    net, probs, loss, grads = run_gpu(cfg, img, lab, params, pixw, loss_fn=loss_fn)
+    ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, pixw, None, net, loss_fn)
     say("  near-tie windows %d, resolved the other way on the GPU %d" % (n_near, n_alt))
     e_p = np.abs(probs - ref["probs"]).max()
     assert e_p <= tol_of(cfg), (cfg.name, "probs", e_p)
@@ -354,6 +355,50 @@ def test_cfg4_full_size_sampled_bf16():
 def test_bf16_refuses_shapes_without_a_kernel():
     with pytest.raises(mpcnn.MpcnnError):
         mpcnn.Net(wl.CONFIGS[0].layers, 1, 18, dtype=mpcnn.BF16)
+
+
+def test_mse_loss_with_linear_outputs():
+    """The other loss the method names: linear outputs, delta = x^ - t at the output image."""
+    full_parity(wl.crop(wl.CONFIGS[0], 2, 40, 37), with_pixw=True, ignore_some=True, loss_fn="mse")   # unfused class layer
+    full_parity(wl.crop(wl.CONFIGS[1], 1, 90, 97), check_layers=False, loss_fn="mse")                # fused class layer
+    # and back: the loss is a property of the net that can be switched
+    cfg = wl.crop(wl.CONFIGS[1], 1, 60, 60)
+    img, lab = wl.make_inputs(cfg)
+    params = wl.make_params(cfg)
+    net, p_mse, _, _ = run_gpu(cfg, img, lab, params, loss_fn="mse")
+    net.set_loss("mcce")
+    _, p_ce, _, _ = run_gpu(cfg, img, lab, params, net=net)
+    z = p_mse - p_mse.max(1, keepdims=True)
+    np.testing.assert_allclose(p_ce, np.exp(z) / np.exp(z).sum(1, keepdims=True), rtol=0, atol=1e-6)
+    with pytest.raises(KeyError if False else mpcnn.MpcnnError):
+        net.set_loss("huber")
+    net.close()
+
+
+def test_class_balanced_weights():
+    """w = 1/N_k at the output pixels of class k: counts exact, weights to fp32 rounding, and
+    the weighted pass matches the oracle given the oracle's own weights."""
+    cfg = wl.crop(wl.CONFIGS[1], 2, 70, 66)
+    img, lab = wl.make_inputs(cfg)
+    lab = lab.copy()
+    lab[0, :5, :] = -1                                   # ignored pixels take no part
+    params = wl.make_params(cfg)
+    w_ref = oracle.class_balance_weights(lab, cfg.n_classes, cfg.patch)
+    net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch)
+    net.set_params(params)
+    pixw, counts = net.class_balance_weights(torch.from_numpy(lab).cuda())
+    c = (cfg.patch - 1) // 2
+    centre = lab[:, c:c + cfg.out_h, c:c + cfg.out_w]
+    assert counts.cpu().numpy()[:cfg.n_classes].tolist() == [int((centre == k).sum()) for k in range(cfg.n_classes)]
+    w_gpu = pixw.cpu().numpy()
+    assert np.array_equal(w_gpu == 0, w_ref == 0)
+    np.testing.assert_allclose(w_gpu, w_ref, rtol=1e-7, atol=0)
+    _, probs, loss, grads = run_gpu(cfg, img, lab, params, w_gpu, net=net)
+    ref, _, _ = oracle_run_valid_ties(cfg, params, img, lab, w_ref, None, net)
+    assert abs(loss - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+    check_grads(cfg, grads, ref["grads"])
+    say("class-balanced pass: loss %.6f (sum of %d per-class means)" % (loss, cfg.n_classes))
+    net.close()
 
 
 def test_forward_same_size_mirrored_borders():
