@@ -410,13 +410,13 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
 // the result does not depend on timing.  A flat segment's item is one float; a tiled
 // segment (written by wgrad_mfma_kernel) has 128-bit items = 4 consecutive rows of one
 // column, scattered to the parameter order [tap*Ci + c][o], bias row last.
-constexpr int kMaxReduceSegs = 48;
+constexpr int kMaxReduceSegs = 49;   // 48 layers and the loss
 struct ReduceSeg {
     const float* partial;
     float* out;
     long plen;          // floats per partial
     int items, n, block0;
-    int tiled, Nt, rows_total, Co;
+    int tiled, Nt, rows_total, Co;   // tiled: 0 flat, 1 tiled, 2 the per-workgroup loss shares (fp64)
 };
 struct ReduceArgs {
     ReduceSeg seg[kMaxReduceSegs];
@@ -433,6 +433,21 @@ __global__ __launch_bounds__(256) void reduce_all_kernel(ReduceArgs a)
     const long plen = sg.plen;
     const int n = sg.n;
     const int col = threadIdx.x & 63, row = threadIdx.x >> 6;
+    if (sg.tiled == 2) {
+        // the summed loss: one workgroup adds the n fp64 shares in a fixed (tree) order
+        double* tree = &red[0][0][0];   // 1024 doubles, 256 used
+        const double* share = reinterpret_cast<const double*>(partial);
+        double s = 0.0;
+        for (int i = threadIdx.x; i < n; i += 256) s += share[i];
+        tree[threadIdx.x] = s;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if ((int)threadIdx.x < w) tree[threadIdx.x] += tree[threadIdx.x + w];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) *reinterpret_cast<double*>(sg.out) = tree[0];
+        return;
+    }
     const int e = ((int)blockIdx.x - sg.block0) * 64 + col;
     const int per = (n + 3) >> 2;
     const int i0 = row * per, i1 = (i0 + per < n) ? i0 + per : n;

@@ -141,6 +141,8 @@ struct mpcnn_net {
     int in_ch = 0, patch = 0, n_cls = 0;
     size_t n_params = 0, pack_len = 0;
     int loss_kind = MPCNN_LOSS_MCCE;
+    int loss_shares = 0;          // per-workgroup loss shares the forward left for the closing reduce
+    double* loss_out = nullptr;   // where that reduce puts their sum
     bool bf16 = false;            // activations and deltas stored in bf16 (arithmetic stays fp32)
     float* d_params = nullptr;
     float* d_wread = nullptr;     // what the kernels read: d_params, or its copy rounded to bf16 values
@@ -548,6 +550,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
     const size_t L = net->layers.size();
     double* lp = (double*)(ws + g.loss_partial_off);
     const bool want_loss = labels && loss_dev;
+    net->loss_shares = 0; net->loss_out = loss_dev;
     for (size_t l = 0; l < L; ++l) {
         const Layer& ly = net->layers[l];
         T* out = (T*)(ws + g.act_off[l]);
@@ -583,9 +586,8 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             const double bytes = es * n_in * (train ? 2.0 : 1.0) + 4.0 * n_out;
             LAUNCH("class_layer", l, train ? 4 : 3, flops, bytes,
                    launch_class<T>(a, ly.cout, Ci <= 128 ? 2 : 4, train, blocks, st));
-            if (train && want_loss)
-                LAUNCH("loss_tree", l, 0, 0, 8.0 * blocks,
-                       loss_tree_kernel<<<1, 256, 0, st>>>(lp, blocks, loss_dev));
+            // (in training the shares are added by the reduce launch that ends the backward)
+            if (train && want_loss) net->loss_shares = blocks;
         } else {
             const float* Wk = net->d_wread + ly.p_off;
             const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k * Ci;
@@ -629,9 +631,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                                                          want_loss ? lp : nullptr, B, Hi, Wi, g.H, g.W,
                                                          (net->patch - 1) / 2, net->n_cls,
                                                          net->loss_kind == MPCNN_LOSS_MSE));
-        if (want_loss)
-            LAUNCH("loss_tree", L - 1, 0, 0, 8.0 * blocks,
-                   loss_tree_kernel<<<1, 256, 0, st>>>(lp, blocks, loss_dev));
+        if (want_loss) net->loss_shares = blocks;
     }
     HIP_TRY(hipGetLastError());
     return MPCNN_OK;
@@ -765,6 +765,14 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
         sg.block0 = ra.total_blocks;
         ra.total_blocks += (sg.items + 63) / 64;
         rbytes += 4.0 * ((double)sg.plen * sg.n + ly.p_len);
+    }
+    if (net->loss_shares > 0 && net->loss_out && ra.n_seg < kMaxReduceSegs) {
+        ReduceSeg& sg = ra.seg[ra.n_seg++];
+        sg.partial = (const float*)(ws + g.loss_partial_off);
+        sg.out = (float*)net->loss_out;
+        sg.plen = 0; sg.n = net->loss_shares; sg.tiled = 2; sg.items = 1;
+        sg.block0 = ra.total_blocks;
+        ra.total_blocks += 1;
     }
     LAUNCH("reduce_all", -1, 0, 0, rbytes, reduce_all_kernel<<<(unsigned)ra.total_blocks, 256, 0, st>>>(ra));
     HIP_TRY(hipGetLastError());
