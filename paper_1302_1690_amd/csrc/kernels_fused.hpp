@@ -345,20 +345,4 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
     }
 }
 
-// Sum of the per-block loss shares in a fixed (tree) order.
-__global__ __launch_bounds__(256) void loss_tree_kernel(const double* __restrict__ partial, int n,
-                                                        double* __restrict__ loss)
-{
-    __shared__ double red[256];
-    double s = 0.0;
-    for (int i = threadIdx.x; i < n; i += 256) s += partial[i];
-    red[threadIdx.x] = s;
-    __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) *loss = red[0];
-}
-
 }  // namespace mpcnn
