@@ -174,6 +174,27 @@ def class_balance_weights(labels, n_classes, patch):
     return w
 
 
+def armijo_step(f, theta, g, f0, alpha0, scale=1.0, c=1e-4, beta=0.5, max_trials=20):
+    """Gradient step safeguarded by the Armijo rule (Experiments, membrane segmentation: SGD
+    safeguarded by the Armijo rule, the weights updated after every image).  With the step
+    direction -scale*g the first alpha in alpha0, beta*alpha0, beta^2*alpha0, ... (at most
+    max_trials of them) is accepted for which
+        f(theta - alpha*scale*g) <= f0 - c * alpha * scale * |g|^2 ,
+    f0 = f(theta), f the summed loss.  Returns (new theta, alpha, f(new theta), trials);
+    if no trial passes the parameters stay as they are and alpha = 0."""
+    theta = np.asarray(theta, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    gg = float(np.dot(g, g))
+    alpha = float(alpha0)
+    for trial in range(1, max_trials + 1):
+        cand = theta - alpha * scale * g
+        fc = float(f(cand))
+        if fc <= f0 - c * alpha * scale * gg:
+            return cand, alpha, fc, trial
+        alpha *= beta
+    return theta.copy(), 0.0, float(f0), max_trials
+
+
 def window_key(layers, in_ch, patch, B, H, W, layer, b, c, y, x):
     """Key of a pooling window in the whole-image map of MP layer `layer` (see orc_ties)."""
     _, ch, ny, nx = dense_shape(layers, in_ch, patch, B, H, W, layer)[:4]

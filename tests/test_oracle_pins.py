@@ -478,6 +478,33 @@ def test_class_balance_weights_by_hand():
     assert abs(r["loss"] - per_class) < 1e-13
 
 
+def test_armijo_rule_by_hand():
+    """f = theta^2/2 at theta = 1 (g = 1, f0 = 1/2), c = 1e-4, halving: alpha = 4 gives f = 4.5 (too
+    large), alpha = 2 gives f = 1/2 > 1/2 - 2e-4 (no sufficient decrease), alpha = 1 gives f = 0."""
+    f = lambda th: 0.5 * float(th[0]) ** 2
+    th, alpha, fv, trials = oracle.armijo_step(f, [1.0], [1.0], 0.5, 4.0)
+    assert (th.tolist(), alpha, fv, trials) == ([0.0], 1.0, 0.0, 3)
+    # the accepted point satisfies the inequality, the one before does not (here with a scale)
+    th, alpha, fv, trials = oracle.armijo_step(f, [1.0], [2.0], 0.5, 4.0, scale=0.5)
+    assert (th.tolist(), alpha, trials) == ([0.0], 1.0, 3)
+    # nothing acceptable: parameters untouched, alpha = 0
+    up = lambda th: 1.0 + abs(float(th[0]) - 1.0)
+    th, alpha, fv, trials = oracle.armijo_step(up, [1.0], [1.0], 1.0, 1.0, max_trials=5)
+    assert (th.tolist(), alpha, fv, trials) == ([1.0], 0.0, 1.0, 5)
+    # on the real loss: the accepted step decreases it by at least c*alpha*|g|^2
+    layers, in_ch, P = NETS["tiny18"]
+    rng = np.random.default_rng(41)
+    params = rand_params(layers, in_ch, P, 42)
+    img = rng.uniform(0, 1, (1, in_ch, P + 2, P + 1))
+    lab = rng.integers(0, 2, (1, P + 2, P + 1)).astype(np.int32)
+    r = oracle.run(layers, in_ch, P, params, img, lab, want_grads=True)
+    loss = lambda th: oracle.run(layers, in_ch, P, th, img, lab, want_probs=False)["loss"]
+    th, alpha, fv, trials = oracle.armijo_step(loss, params, r["grads"], r["loss"], 64.0)
+    assert trials > 1 and alpha == 64.0 * 0.5 ** (trials - 1)
+    assert fv <= r["loss"] - 1e-4 * alpha * np.dot(r["grads"], r["grads"])
+    assert loss(params - 2 * alpha * r["grads"]) > r["loss"] - 1e-4 * 2 * alpha * np.dot(r["grads"], r["grads"])
+
+
 def test_mirror_pad_by_hand():
     """Borders synthesised by mirroring, edge pixel repeated; c = (P-1)//2 above/left and
     P-1-c below/right, so that output (i,j) is the patch centred on input (i,j)
