@@ -185,6 +185,35 @@ mpcnn_status mpcnn_seg_backward(mpcnn_net* net, const float* image_dev, const in
 mpcnn_status mpcnn_sgd_step(mpcnn_net* net, float lr, float grad_scale, void* hip_stream);
 
 /*
+ * The loss alone, L as in mpcnn_seg_backward for the current parameters: a forward pass that
+ * keeps nothing and computes no gradient (the evaluations of a line search).
+ *   loss_dev: one fp64 on the device.  ws_dev: at least mpcnn_workspace_bytes(net,B,H,W,0).
+ */
+mpcnn_status mpcnn_seg_loss(mpcnn_net* net, const float* image_dev, const int32_t* labels_dev,
+                            const float* pixw_dev, int B, int H, int W, double* loss_dev,
+                            void* ws_dev, size_t ws_bytes, void* hip_stream);
+
+/*
+ * One gradient step safeguarded by the Armijo rule (Experiments, membrane segmentation:
+ * stochastic gradient descent safeguarded by the Armijo rule, the weights updated after every
+ * image).  To be called after mpcnn_seg_backward on the same inputs, whose gradient g the net
+ * holds and whose loss the caller passes as f0.  Tries alpha = alpha0, beta*alpha0, ... (at most
+ * max_trials values) and keeps the first for which
+ *     L(theta - alpha*grad_scale*g) <= f0 - c * alpha * grad_scale * |g|^2 ;
+ * each trial costs one loss-only forward.  If none passes the parameters are left as they were
+ * and *alpha_host = 0.  Synchronous on hip_stream (every trial's loss is read back).
+ *   alpha_host, loss_host, trials_host: results on the host (accepted alpha, loss at the new
+ *   parameters, trials made); any may be NULL.  ws_dev as for mpcnn_seg_loss.
+ * Errors: EINVAL (also: alpha0 <= 0, beta outside (0,1), c outside [0,1), max_trials < 1), ESHAPE,
+ * EWORKSPACE, EHIP.
+ */
+mpcnn_status mpcnn_armijo_step(mpcnn_net* net, const float* image_dev, const int32_t* labels_dev,
+                               const float* pixw_dev, int B, int H, int W, double f0, float alpha0,
+                               float grad_scale, float c, float beta, int max_trials, void* ws_dev,
+                               size_t ws_bytes, void* hip_stream, float* alpha_host, double* loss_host,
+                               int* trials_host);
+
+/*
  * Test hooks: read back what the last forward/backward left in the workspace
  * (which must still be alive).  Synchronous.
  *   mpcnn_get_activation: output of layer `layer`, [B][rows][cols][channels] fp32.

@@ -246,6 +246,28 @@ __global__ void sgd_kernel(float* __restrict__ theta, const float* __restrict__ 
     if (e < n) theta[e] = fmaf(-step, g[e], theta[e]);
 }
 
+// Pieces of the safeguarded gradient step: |g|^2 in fp64 by one workgroup (fixed order), and
+// theta = theta0 - step * g from a kept copy of the parameters.
+__global__ __launch_bounds__(1024) void sqnorm_kernel(const float* __restrict__ g, long n, double* __restrict__ out)
+{
+    __shared__ double red[1024];
+    double s = 0.0;
+    for (long e = threadIdx.x; e < n; e += 1024) s += (double)g[e] * (double)g[e];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 512; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = red[0];
+}
+__global__ void step_from_kernel(float* __restrict__ theta, const float* __restrict__ theta0,
+                                 const float* __restrict__ g, float step, long n)
+{
+    long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < n) theta[e] = fmaf(-step, g[e], theta0[e]);
+}
+
 // Per-class balanced weights (Experiments, steel defects: the loss is minimised per class):
 // counts[k] = number of output pixels whose label (read at the patch centre) is k, then
 // w = 1 / counts[k] at those pixels and 0 everywhere else.  Integer atomics: exact.

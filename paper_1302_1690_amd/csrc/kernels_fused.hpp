@@ -302,7 +302,7 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
                     }
                     dh[s] = a.tanh_below ? g * (1.f - hv[v][s] * hv[v][s]) : g;
                 }
-                if (c < a.K) store4(dh_t + m * a.K + c, dh);
+                if (c < a.K && dh_t) store4(dh_t + m * a.K + c, dh);   // (no delta buffer: loss only)
             }
         }
     }
@@ -329,7 +329,7 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
         if ((tid & 63) == 0) lred[wave] = my_loss;
         __syncthreads();
         float* out = a.partial + (long)blockIdx.x * ((long)a.K + 1) * NCLS;
-        for (int e = tid; e < NV * 16; e += 256) {
+        for (int e = tid; a.partial && e < NV * 16; e += 256) {
             const int i = e >> 4, jj = e & 15;
             const float s = (red[0][i][jj] + red[1][i][jj]) + (red[2][i][jj] + red[3][i][jj]);
             if (i < KV * 4 * NCLS) {

@@ -145,6 +145,8 @@ struct mpcnn_net {
     double* loss_out = nullptr;   // where that reduce puts their sum
     bool bf16 = false;            // activations and deltas stored in bf16 (arithmetic stays fp32)
     float* d_params = nullptr;
+    float* d_params0 = nullptr;   // copy of the parameters a safeguarded step starts from
+    double* d_scalar = nullptr;   // two fp64 results of that step's reductions
     float* d_wread = nullptr;     // what the kernels read: d_params, or its copy rounded to bf16 values
     bool wread_stale = true;
     float* d_grads = nullptr;
@@ -575,7 +577,8 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             const long M = (long)B * Ho * Wo;
             ClassArgs a{};
             a.h = in; a.Wk = net->d_wread + ly.p_off; a.probs = probs;
-            a.labels = labels; a.pixw = pixw; a.dH = dZ; a.partial = (float*)(ws + g.partial_off[l]);
+            a.labels = labels; a.pixw = pixw; a.dH = dZ;
+            a.partial = g.training ? (float*)(ws + g.partial_off[l]) : nullptr;   // loss only: no gradient shares
             a.loss_partial = want_loss ? lp : nullptr;
             a.B = B; a.Ho = Ho; a.Wo = Wo; a.H = g.H; a.W = g.W; a.ctr = (net->patch - 1) / 2;
             a.K = Ci; a.tanh_below = (l > 0 && net->layers[l - 1].tanh_out) ? 1 : 0;
@@ -921,6 +924,8 @@ void mpcnn_net_destroy(mpcnn_net* net)
         (void)hipSetDevice(net->device);
         (void)hipDeviceSynchronize();
         if (net->d_wread && net->d_wread != net->d_params) (void)hipFree(net->d_wread);
+        (void)hipFree(net->d_params0);
+        (void)hipFree(net->d_scalar);
         (void)hipFree(net->d_params);
         (void)hipFree(net->d_grads);
         (void)hipFree(net->d_packs);
@@ -1103,6 +1108,87 @@ mpcnn_status mpcnn_seg_backward(mpcnn_net* net, const float* image_dev, const in
     if (st != MPCNN_OK) return st;
     return net->bf16 ? run_backward<mpcnn::bf16>(net, g, image_dev, ws, stream)
                      : run_backward<float>(net, g, image_dev, ws, stream);
+}
+
+// forward + summed loss, nothing kept (the workspace is a forward-only one)
+static mpcnn_status loss_only(mpcnn_net* net, const Geom& g, const float* image_dev, const int32_t* labels_dev,
+                              const float* pixw_dev, double* loss_dev, char* ws, hipStream_t st)
+{
+    mpcnn_status rc = net->bf16 ? run_forward<mpcnn::bf16>(net, g, image_dev, ws, labels_dev, pixw_dev, nullptr,
+                                                           nullptr, loss_dev, st)
+                                : run_forward<float>(net, g, image_dev, ws, labels_dev, pixw_dev, nullptr, nullptr,
+                                                     loss_dev, st);
+    if (rc != MPCNN_OK) return rc;
+    if (net->loss_shares < 1) return fail(MPCNN_EINVAL, "no loss was computed");
+    mpcnn::ReduceArgs ra{};
+    mpcnn::ReduceSeg& sg = ra.seg[ra.n_seg++];
+    sg.partial = (const float*)(ws + g.loss_partial_off);
+    sg.out = (float*)loss_dev;
+    sg.n = net->loss_shares; sg.tiled = 2; sg.items = 1; sg.block0 = 0;
+    ra.total_blocks = 1;
+    LAUNCH("reduce_all", -1, 0, 0, 8.0 * sg.n, mpcnn::reduce_all_kernel<<<1, 256, 0, st>>>(ra));
+    HIP_TRY(hipGetLastError());
+    return MPCNN_OK;
+}
+
+mpcnn_status mpcnn_seg_loss(mpcnn_net* net, const float* image_dev, const int32_t* labels_dev,
+                            const float* pixw_dev, int B, int H, int W, double* loss_dev,
+                            void* ws_dev, size_t ws_bytes, void* hip_stream)
+{
+    Geom g;
+    mpcnn_status st = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &g);
+    if (st != MPCNN_OK) return st;
+    if (!labels_dev || !loss_dev) return fail(MPCNN_EINVAL, "null argument");
+    return loss_only(net, g, image_dev, labels_dev, pixw_dev, loss_dev, (char*)ws_dev, (hipStream_t)hip_stream);
+}
+
+mpcnn_status mpcnn_armijo_step(mpcnn_net* net, const float* image_dev, const int32_t* labels_dev,
+                               const float* pixw_dev, int B, int H, int W, double f0, float alpha0,
+                               float grad_scale, float c, float beta, int max_trials, void* ws_dev,
+                               size_t ws_bytes, void* hip_stream, float* alpha_host, double* loss_host,
+                               int* trials_host)
+{
+    Geom g;
+    mpcnn_status rc = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &g);
+    if (rc != MPCNN_OK) return rc;
+    if (!labels_dev) return fail(MPCNN_EINVAL, "null labels_dev");
+    if (!(alpha0 > 0.f) || !(beta > 0.f && beta < 1.f) || !(c >= 0.f && c < 1.f) || max_trials < 1)
+        return fail(MPCNN_EINVAL, "alpha0 = %g, beta = %g, c = %g, max_trials = %d", alpha0, beta, c, max_trials);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const long n = (long)net->n_params;
+    if (!net->d_params0) HIP_TRY(hipMalloc((void**)&net->d_params0, sizeof(float) * n));
+    if (!net->d_scalar) HIP_TRY(hipMalloc((void**)&net->d_scalar, 2 * sizeof(double)));
+    HIP_TRY(hipMemcpyAsync(net->d_params0, net->d_params, sizeof(float) * n, hipMemcpyDeviceToDevice, st));
+    mpcnn::sqnorm_kernel<<<1, 1024, 0, st>>>(net->d_grads, n, net->d_scalar);
+    double gg = 0.0;
+    HIP_TRY(hipMemcpyAsync(&gg, net->d_scalar, sizeof(double), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    float alpha = alpha0;
+    double f = f0;
+    int trial = 0;
+    bool ok = false;
+    while (trial < max_trials) {
+        ++trial;
+        mpcnn::step_from_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(net->d_params, net->d_params0,
+                                                                              net->d_grads, alpha * grad_scale, n);
+        net->packs_stale = true; net->wread_stale = true;
+        rc = loss_only(net, g, image_dev, labels_dev, pixw_dev, net->d_scalar + 1, (char*)ws_dev, st);
+        if (rc != MPCNN_OK) break;
+        HIP_TRY(hipMemcpyAsync(&f, net->d_scalar + 1, sizeof(double), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        if (f <= f0 - (double)c * (double)alpha * (double)grad_scale * gg) { ok = true; break; }
+        alpha *= beta;
+    }
+    if (!ok) {   // also after an error: the parameters the call started from
+        HIP_TRY(hipMemcpyAsync(net->d_params, net->d_params0, sizeof(float) * n, hipMemcpyDeviceToDevice, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        net->packs_stale = true; net->wread_stale = true;
+        alpha = 0.f; f = f0;
+    }
+    if (alpha_host) *alpha_host = alpha;
+    if (loss_host) *loss_host = f;
+    if (trials_host) *trials_host = trial;
+    return rc;
 }
 
 mpcnn_status mpcnn_sgd_step(mpcnn_net* net, float lr, float grad_scale, void* hip_stream)

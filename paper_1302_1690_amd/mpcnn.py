@@ -29,7 +29,7 @@ SYMBOLS = [
     "mpcnn_get_grads", "mpcnn_workspace_bytes", "mpcnn_seg_forward", "mpcnn_seg_backward",
     "mpcnn_sgd_step", "mpcnn_get_activation", "mpcnn_get_argmax", "mpcnn_last_error",
     "mpcnn_profile_enable", "mpcnn_profile_read", "mpcnn_workspace_bytes_same", "mpcnn_seg_forward_same",
-    "mpcnn_set_loss", "mpcnn_class_balance_weights",
+    "mpcnn_set_loss", "mpcnn_class_balance_weights", "mpcnn_seg_loss", "mpcnn_armijo_step",
 ]
 
 
@@ -83,6 +83,10 @@ def lib():
         L.mpcnn_workspace_bytes_same.argtypes = [vp, i, i, i]
         L.mpcnn_workspace_bytes_same.restype = sz
         L.mpcnn_seg_forward_same.argtypes = [vp, vp, i, i, i, vp, vp, sz, vp]
+        L.mpcnn_seg_loss.argtypes = [vp, vp, vp, vp, i, i, i, vp, vp, sz, vp]
+        L.mpcnn_armijo_step.argtypes = [vp, vp, vp, vp, i, i, i, C.c_double, C.c_float, C.c_float, C.c_float,
+                                        C.c_float, i, vp, sz, vp, C.POINTER(C.c_float), C.POINTER(C.c_double),
+                                        C.POINTER(i)]
         L.mpcnn_set_loss.argtypes = [vp, i]
         L.mpcnn_class_balance_weights.argtypes = [vp, vp, i, i, i, vp, vp, vp]
         L.mpcnn_seg_backward.argtypes = [vp, vp, vp, vp, i, i, i, vp, vp, vp, sz, vp]
@@ -192,6 +196,29 @@ class Net:
         _check(lib().mpcnn_seg_forward(self._h, _ptr(image), B, H, W, _ptr(probs), _ptr(ws),
                                        ws.numel(), _stream_handle(stream)))
         return probs
+
+    def seg_loss(self, image, labels, pixw=None, ws=None, stream=None) -> float:
+        """Summed loss at the current parameters (forward only, nothing kept)."""
+        import torch
+        B, _, H, W = image.shape
+        if ws is None:
+            ws = self.alloc_workspace(B, H, W, False)
+        loss = torch.zeros(1, dtype=torch.float64, device=image.device)
+        _check(lib().mpcnn_seg_loss(self._h, _ptr(image), _ptr(labels), _ptr(pixw), B, H, W, _ptr(loss),
+                                    _ptr(ws), ws.numel(), _stream_handle(stream)))
+        return float(loss.item())
+
+    def armijo_step(self, image, labels, f0, alpha0, pixw=None, grad_scale=1.0, c=1e-4, beta=0.5,
+                    max_trials=20, ws=None, stream=None):
+        """Safeguarded gradient step after seg_backward on the same inputs -> (alpha, loss, trials)."""
+        B, _, H, W = image.shape
+        if ws is None:
+            ws = self.alloc_workspace(B, H, W, False)
+        a, f, t = C.c_float(0), C.c_double(0), C.c_int(0)
+        _check(lib().mpcnn_armijo_step(self._h, _ptr(image), _ptr(labels), _ptr(pixw), B, H, W, f0, alpha0,
+                                       grad_scale, c, beta, max_trials, _ptr(ws), ws.numel(),
+                                       _stream_handle(stream), C.byref(a), C.byref(f), C.byref(t)))
+        return a.value, f.value, t.value
 
     def set_loss(self, kind: str):
         """"mcce": softmax + cross-entropy (default); "mse": linear outputs, half the squared error."""

@@ -401,6 +401,40 @@ def test_class_balanced_weights():
     net.close()
 
 
+def test_loss_only_forward_and_armijo_step():
+    """Loss-only forward equals the loss of the training pass; the safeguarded step makes the
+    same number of trials as the fp64 rule and lands on the same parameters."""
+    for cfg, alpha0 in ((wl.crop(wl.CONFIGS[0], 2, 33, 30), 0.5), (wl.crop(wl.CONFIGS[1], 1, 64, 70), 0.125)):
+        img, lab = wl.make_inputs(cfg)
+        params = wl.make_params(cfg)
+        net, _, loss0, grads = run_gpu(cfg, img, lab, params)
+        d_img, d_lab = torch.from_numpy(img).cuda(), torch.from_numpy(lab).cuda()
+        assert abs(net.seg_loss(d_img, d_lab) - loss0) <= 1e-6 * abs(loss0)
+        args = (cfg.layers, cfg.in_channels, cfg.patch)
+        ref = oracle.run(*args, params.astype(np.float64), img.astype(np.float64), lab, want_grads=True)
+        f = lambda th: oracle.run(*args, th, img.astype(np.float64), lab, want_probs=False)["loss"]
+        th_ref, a_ref, f_ref, t_ref = oracle.armijo_step(f, params.astype(np.float64), ref["grads"], ref["loss"], alpha0)
+        # the comparison of trial counts is only meaningful if no trial was a close call
+        gg = float(np.dot(ref["grads"], ref["grads"]))
+        for k in range(t_ref):
+            a = alpha0 * 0.5 ** k
+            margin = f(params.astype(np.float64) - a * ref["grads"]) - (ref["loss"] - 1e-4 * a * gg)
+            assert abs(margin) > 1e-3 * abs(ref["loss"]), "pick another alpha0: trial %d is a close call" % k
+        alpha, f_new, trials = net.armijo_step(d_img, d_lab, loss0, alpha0)
+        say("case %s: %d trials, alpha %g, loss %.6f -> %.6f" % (cfg.name, trials, alpha, loss0, f_new))
+        assert t_ref > 1 and trials == t_ref and alpha == np.float32(a_ref)
+        assert abs(f_new - f_ref) <= 1e-4 * abs(f_ref)
+        step = np.abs(th_ref - params).max()
+        assert np.abs(net.get_params() - th_ref).max() <= 1e-4 * step + 1e-7
+        assert abs(net.seg_loss(d_img, d_lab) - f_new) <= 1e-6 * abs(f_new)
+        # a rule nothing can satisfy (c close to 1, steps that overshoot) leaves the parameters alone
+        before = net.get_params()
+        alpha, f_keep, trials = net.armijo_step(d_img, d_lab, f_new, 1e6, c=0.99, max_trials=3)
+        assert alpha == 0.0 and trials == 3 and f_keep == f_new
+        np.testing.assert_array_equal(net.get_params(), before)
+        net.close()
+
+
 def test_forward_same_size_mirrored_borders():
     """Deployment forward: borders synthesised by mirroring, output as large as the image."""
     for cfg in (wl.crop(wl.CONFIGS[0], 2, 31, 40), wl.crop(wl.CONFIGS[1], 1, 70, 61),
