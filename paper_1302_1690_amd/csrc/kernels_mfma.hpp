@@ -79,6 +79,33 @@ __global__ void pack_weights_kernel(const float* __restrict__ W, float* __restri
     }
 }
 
+// The same packs for the bf16 matrix instruction (v_mfma_f32_32x32x16_bf16: lane l supplies
+// 8 consecutive reduction indices, 8*(l/32) .. +7, of row / column l%32): 8 channels per item,
+//   P[tap*nch + ch][g][o][s] = W[..][16*ch + 8*g + s][..], s < 8, as bf16.
+__global__ void pack_weights_bf16_kernel(const float* __restrict__ W, bf16* __restrict__ P, int kk,
+                                         int Ci, int Co, int RPad, int OPad, int dgrad)
+{
+    const int nch = RPad / 16;
+    long total = (long)kk * nch * 2 * OPad * 8;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long)gridDim.x * blockDim.x) {
+        int s = (int)(e & 7);
+        long q = e >> 3;
+        int oo = (int)(q % OPad); q /= OPad;
+        int g = (int)(q & 1); q >>= 1;
+        int ch = (int)(q % nch);
+        int tap = (int)(q / nch);
+        int r = 16 * ch + 8 * g + s;  // index along the reduced dimension
+        float v = 0.f;
+        if (!dgrad) {
+            if (r < Ci && oo < Co) v = W[((long)tap * Ci + r) * Co + oo];
+        } else {
+            if (r < Co && oo < Ci) v = W[((long)(kk - 1 - tap) * Ci + oo) * Co + r];
+        }
+        P[e] = (bf16)v;
+    }
+}
+
 template <int W> struct MfmaAcc;
 template <> struct MfmaAcc<16> { typedef v4f type; };
 template <> struct MfmaAcc<32> { typedef v16f type; };
@@ -97,9 +124,14 @@ __device__ __forceinline__ typename MfmaAcc<W>::type mfma_f32(float a, float b, 
 // LDS, where all threads add them in wave order, apply the epilogue and store.  With 8
 // waves one workgroup fills a CU (two waves per SIMD that are always in the same phase).  Summation order is the same for every position, so equal inputs
 // give bit-equal outputs (exact pooling ties stay exact).
-template <int W, int OT, int PT, int NW, typename T>
+// BM (bf16 storage, 32-wide tiles, channel counts that are multiples of 8): the halo stays
+// bf16 in LDS, the pack is bf16, and one v_mfma_f32_32x32x16_bf16 per (output tile, position
+// tile) and step replaces four fp32 MFMAs; a step then covers 16 channels.
+template <int W, int OT, int PT, int NW, typename T, bool BM = false>
 __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
 {
+    static_assert(!BM || (W == 32 && sizeof(T) == 2), "bf16 MFMA: bf16 storage and 32-wide tiles");
+    constexpr int CU = BM ? 8 : 4;     // channels per 128-bit halo / pack item
     const T* in_t = static_cast<const T*>(a.in);
     const T* act_t = static_cast<const T*>(a.act);
     T* out_t = static_cast<T*>(a.out);
@@ -127,8 +159,8 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
     if (ty0 >= fh || tx0 >= fw) return;  // uniform for the workgroup
 
     const int hw = a.Tx + a.k - 1, hh = a.Ty + a.k - 1;
-    const int Cs4 = (a.CrPad >> 2) + 1;  // pitch of one halo position in 128-bit units (+1: bank spread)
-    const int cq = a.CrPad >> 2;
+    const int cq = a.CrPad / CU;
+    const int Cs4 = cq + 1;              // pitch of one halo position in 128-bit units (+1: bank spread)
     const int ot0 = blockIdx.y * OT;
     v4f* lds4 = reinterpret_cast<v4f*>(lds);
 
@@ -151,8 +183,11 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
                     const int fy = ty0 + ha + a.origin, fx = tx0 + hb + a.origin;
                     const int iy = fy * a.d + ry, ix = fx * a.d + rx;
                     dst[u] = pos * Cs4 + q;
-                    if (fy >= 0 && fx >= 0 && iy < a.Hi && ix < a.Wi && 4 * q < a.Cr)
-                        v[u] = load4(in_t + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + 4 * q);
+                    if (fy >= 0 && fx >= 0 && iy < a.Hi && ix < a.Wi && CU * q < a.Cr) {
+                        const T* src = in_t + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + CU * q;
+                        if constexpr (BM) v[u] = *reinterpret_cast<const v4f*>(src);   // 8 bf16, kept as they are
+                        else v[u] = load4(src);
+                    }
                 }
             }
 #pragma unroll
@@ -189,7 +224,7 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
         lbase[pt] = (ty * hw + tx) * Cs4 + lg;
     }
 
-    const int nch = a.CrPad / (4 * G);
+    const int nch = a.CrPad / (CU * G);
     const int steps = a.k * a.k * nch;
     const int t0 = steps * wave / NW, t1 = steps * (wave + 1) / NW;
     const int lane_w = lg * a.CoPad + W * ot0 + lt;   // this lane's offset inside one step of the pack
@@ -225,12 +260,23 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
         if (++chunk == nch) { chunk = 0; if (++tb == a.k) { tb = 0; ++ta; } }
     };
     auto mfmas = [&](const v4f (&wr)[OT], const v4f (&ar)[PT]) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
+        if constexpr (BM) {
+            typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 #pragma unroll
             for (int o = 0; o < OT; ++o)
 #pragma unroll
-                for (int p = 0; p < PT; ++p) acc[o][p] = mfma_f32<W>(wr[o][s], ar[p][s], acc[o][p]);
+                for (int p = 0; p < PT; ++p)
+                    acc[o][p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wr[o]),
+                                                                        __builtin_bit_cast(bf16x8, ar[p]),
+                                                                        acc[o][p], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int o = 0; o < OT; ++o)
+#pragma unroll
+                    for (int p = 0; p < PT; ++p) acc[o][p] = mfma_f32<W>(wr[o][s], ar[p][s], acc[o][p]);
+        }
     };
 #pragma unroll
     for (int o = 0; o < OT; ++o) wA[o] = wB[o] = (v4f){0.f, 0.f, 0.f, 0.f};

@@ -91,6 +91,7 @@ struct Layer {
     bool fwd_mfma = false, dgrad_mfma = false, wgrad_mfma = false;
     bool class_fused = false;             // last FC handled by class_layer_kernel
     ChanTiling fwd_ct{}, dgrad_ct{};
+    bool fwd_bm = false, dgrad_bm = false; // bf16 storage: multiply on the bf16 matrix instruction
     int fwd_rpad = 0, dgrad_rpad = 0;     // reduced channels padded to 16
     size_t fwd_pack_off = 0, fwd_pack_len = 0, dgrad_pack_off = 0, dgrad_pack_len = 0;
 };
@@ -229,12 +230,12 @@ bool choose_tile(int fh, int fw, int max_pos, int k, size_t pitch_bytes, size_t 
 }
 
 // Tile plan of conv_mfma_kernel for a map of out_r x out_c positions at tap spacing d.
-TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, const ChanTiling& ct)
+TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, const ChanTiling& ct, bool bm)
 {
     TilePlan best;
     double best_cost = 0;
     const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
-    const size_t pitch = sizeof(float) * (rpad + 4);
+    const size_t pitch = bm ? 16 * (size_t)(rpad / 8 + 1) : sizeof(float) * (rpad + 4);   // one halo position in LDS
     const int regs_per_tile = ct.W * ct.W / 64;
     for (int PT : {64 / ct.W, 128 / ct.W}) {            // 64 or 128 positions per workgroup
         if (ct.OT * PT * regs_per_tile > (ct.W == 16 ? 64 : 128)) continue;  // accumulator registers per lane
@@ -362,13 +363,13 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         size_t bytes = es * (size_t)B * r * c * ly.cout;
         max_act = std::max(max_act, bytes);
         if (ly.kind == MPCNN_MP) continue;
-        if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.k, ly.fwd_rpad, ly.fwd_ct);
+        if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.k, ly.fwd_rpad, ly.fwd_ct, ly.fwd_bm);
         if (training && ly.class_fused) {
             g->partial_n[l] = class_blocks((long)B * r * c);
             g->partial_len[l] = ly.p_len;
         } else if (training) {
             if (ly.dgrad_mfma && l > 0)
-                g->dgrad[l] = plan_conv_tiles(B, in_r, in_c, ly.dil, ly.k, ly.dgrad_rpad, ly.dgrad_ct);
+                g->dgrad[l] = plan_conv_tiles(B, in_r, in_c, ly.dil, ly.k, ly.dgrad_rpad, ly.dgrad_ct, ly.dgrad_bm);
             g->wgrad[l] = plan_wgrad(ly, B, in_r, in_c, r, c);
             const WgradPlan& w = g->wgrad[l];
             g->partial_n[l] = w.ok ? w.slabs : w.chunks;
@@ -432,10 +433,29 @@ void launch_conv_inst(const mpcnn::ConvArgs& a, dim3 grid, size_t lds, hipStream
 {
     mpcnn::conv_mfma_kernel<W, OT, PT, NW, T><<<grid, 64 * NW, lds, st>>>(a);
 }
+template <int OT, int PT, int NW>
+void launch_conv_bm_inst(const mpcnn::ConvArgs& a, dim3 grid, size_t lds, hipStream_t st)
+{
+    mpcnn::conv_mfma_kernel<32, OT, PT, NW, mpcnn::bf16, true><<<grid, 64 * NW, lds, st>>>(a);
+}
+// bf16 matrix instruction (32-wide tiles, bf16 storage)
+bool launch_conv_bm(const mpcnn::ConvArgs& a, const ChanTiling& ct, const TilePlan& tp, dim3 grid, hipStream_t st)
+{
+#define CASE(o, p)                                                                  \
+    if (ct.W == 32 && ct.OT == o && tp.PT == p) {                                     \
+        if (tp.NW == 8) launch_conv_bm_inst<o, p, 8>(a, grid, tp.lds, st);            \
+        else launch_conv_bm_inst<o, p, 4>(a, grid, tp.lds, st);                       \
+        return true;                                                                \
+    }
+    CASE(1, 2) CASE(2, 2) CASE(4, 2) CASE(1, 4) CASE(2, 4)
+#undef CASE
+    return false;
+}
 template <typename T>
 bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, const TilePlan& tp, dim3 grid,
-                      hipStream_t st)
+                      hipStream_t st, bool bm = false)
 {
+    if (bm) return launch_conv_bm(a, ct, tp, grid, st);
 #define CASE(w, o, p)                                                                         \
     if (ct.W == w && ct.OT == o && tp.PT == p) {                                                \
         if (tp.NW == 8) launch_conv_inst<w, o, p, 8, T>(a, grid, tp.lds, st);                   \
@@ -472,6 +492,13 @@ mpcnn_status set_lds_attrs_t()
     ATTR((mpcnn::wgrad_mfma_kernel<7, T>)); ATTR((mpcnn::wgrad_mfma_kernel<8, T>));
     ATTR((mpcnn::wgrad_mfma_kernel<9, T>)); ATTR((mpcnn::wgrad_mfma_kernel<10, T>));
     ATTR((mpcnn::wgrad_mfma_kernel<11, T>));
+    if constexpr (std::is_same<T, mpcnn::bf16>::value) {
+        ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 8, T, true>));
+        ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 8, T, true>));
+        ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 8, T, true>));
+        ATTR((mpcnn::conv_mfma_kernel<32, 1, 4, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 4, 8, T, true>));
+        ATTR((mpcnn::conv_mfma_kernel<32, 1, 2, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 2, 8, T, true>));
+    }
 #undef ATTR
     return MPCNN_OK;
 }
@@ -507,12 +534,22 @@ mpcnn_status refresh_packs(mpcnn_net* net, hipStream_t st)
         const Layer& ly = net->layers[l];
         if (ly.kind == MPCNN_MP) continue;
         const float* Wc = net->d_wread + ly.p_off;
-        if (ly.fwd_mfma)
+        if (ly.fwd_mfma && ly.fwd_bm)
+            LAUNCH("pack_weights", l, 0, 0, 6.0 * ly.fwd_pack_len,
+                   mpcnn::pack_weights_bf16_kernel<<<grid_for((long)ly.fwd_pack_len), 256, 0, st>>>(
+                       Wc, (mpcnn::bf16*)(net->d_packs + ly.fwd_pack_off), ly.k * ly.k, ly.cin, ly.cout,
+                       ly.fwd_rpad, ly.fwd_ct.pad, 0));
+        else if (ly.fwd_mfma)
             LAUNCH("pack_weights", l, 0, 0, 8.0 * ly.fwd_pack_len,
                    mpcnn::pack_weights_kernel<<<grid_for((long)ly.fwd_pack_len), 256, 0, st>>>(
                        Wc, net->d_packs + ly.fwd_pack_off, ly.k * ly.k, ly.cin, ly.cout, ly.fwd_rpad,
                        ly.fwd_ct.pad, 64 / ly.fwd_ct.W, 0));
-        if (ly.dgrad_mfma && l > 0)
+        if (ly.dgrad_mfma && l > 0 && ly.dgrad_bm)
+            LAUNCH("pack_weights", l, 0, 0, 6.0 * ly.dgrad_pack_len,
+                   mpcnn::pack_weights_bf16_kernel<<<grid_for((long)ly.dgrad_pack_len), 256, 0, st>>>(
+                       Wc, (mpcnn::bf16*)(net->d_packs + ly.dgrad_pack_off), ly.k * ly.k, ly.cin, ly.cout,
+                       ly.dgrad_rpad, ly.dgrad_ct.pad, 1));
+        else if (ly.dgrad_mfma && l > 0)
             LAUNCH("pack_weights", l, 0, 0, 8.0 * ly.dgrad_pack_len,
                    mpcnn::pack_weights_kernel<<<grid_for((long)ly.dgrad_pack_len), 256, 0, st>>>(
                        Wc, net->d_packs + ly.dgrad_pack_off, ly.k * ly.k, ly.cin, ly.cout,
@@ -608,7 +645,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 a.mode = ly.tanh_out ? kFwdTanh : kFwdLinear;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
                 LAUNCH("conv_fwd_mfma", l, step, flops, bytes,
-                       launch_conv_mfma<T>(a, ly.fwd_ct, tp, grid, st));
+                       launch_conv_mfma<T>(a, ly.fwd_ct, tp, grid, st, ly.fwd_bm));
             } else {
                 const int og = ceil_div(ly.cout, 4);
                 const long total = (long)B * Ho * Wo * og;
@@ -734,7 +771,7 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.mode = below_tanh ? kDgradTanh : kDgradPlain;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.dgrad_ct.split);
                 LAUNCH("conv_dgrad_mfma", li, dstep, flops, dbytes,
-                       launch_conv_mfma<T>(a, ly.dgrad_ct, tp, grid, st));
+                       launch_conv_mfma<T>(a, ly.dgrad_ct, tp, grid, st, ly.dgrad_bm));
             } else if constexpr (!kF32) {
                 return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             } else {
@@ -880,14 +917,17 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
             ly.fwd_mfma = !last && ly.cin % 4 == 0 && ly.cin >= 8 && ly.cout >= 8;
             ly.dgrad_mfma = l > 0 && ly.cout % 4 == 0 && ly.cout >= 8 && ly.cin >= 8;
             ly.wgrad_mfma = !ly.class_fused;   // any shape: gradient rows are tiled in parameter order
+            // bf16 storage with channel counts that are multiples of 8: the bf16 matrix instruction
+            ly.fwd_bm = net->bf16 && ly.fwd_mfma && ly.cin % 8 == 0;
+            ly.dgrad_bm = net->bf16 && ly.dgrad_mfma && ly.cout % 8 == 0;
             if (ly.fwd_mfma) {
-                ly.fwd_ct = chan_tiling(ly.cout);
+                ly.fwd_ct = ly.fwd_bm ? chan_tiling_w(ly.cout, 32) : chan_tiling(ly.cout);
                 ly.fwd_rpad = ceil_div(ly.cin, 16) * 16;
                 ly.fwd_pack_len = (size_t)ly.k * ly.k * ly.fwd_rpad * ly.fwd_ct.pad;
                 ly.fwd_pack_off = pack; pack += ly.fwd_pack_len;
             }
             if (ly.dgrad_mfma) {
-                ly.dgrad_ct = chan_tiling(ly.cin);
+                ly.dgrad_ct = ly.dgrad_bm ? chan_tiling_w(ly.cin, 32) : chan_tiling(ly.cin);
                 ly.dgrad_rpad = ceil_div(ly.cout, 16) * 16;
                 ly.dgrad_pack_len = (size_t)ly.k * ly.k * ly.dgrad_rpad * ly.dgrad_ct.pad;
                 ly.dgrad_pack_off = pack; pack += ly.dgrad_pack_len;
