@@ -30,6 +30,7 @@
 
 namespace mpcnn {
 
+constexpr int kWgBmMaxTiles = 5;  // row tiles per wave of wgrad_bm_kernel, which owns two column tiles for each
 constexpr int kWgMaxTiles = 11;   // 32x32 result tiles per wave (16 accumulator registers each; two waves share a SIMD's 512)
 constexpr int kWgStageH = 8;      // 128-bit items of the input halo one thread stages per tile
 constexpr int kWgStageD = 8;      // ... of the delta tile
@@ -416,7 +417,7 @@ struct ReduceSeg {
     float* out;
     long plen;          // floats per partial
     int items, n, block0;
-    int tiled, Nt, rows_total, Co;   // tiled: 0 flat, 1 tiled, 2 the per-workgroup loss shares (fp64)
+    int tiled, Nt, rows_total, Co;   // tiled: 0 flat, 1 tiled, 2 the per-workgroup loss shares (fp64), 3 tiled with the bias as row rows_total
 };
 struct ReduceArgs {
     ReduceSeg seg[kMaxReduceSegs];
@@ -498,7 +499,9 @@ __global__ __launch_bounds__(256) void reduce_all_kernel(ReduceArgs a)
 #pragma unroll
         for (int z = 0; z < 4; ++z)
             r[z] = (float)((red[0][col][z] + red[1][col][z]) + (red[2][col][z] + red[3][col][z]));
-        const int tile_items = sg.items - sg.Nt * 8;     // the bias sums follow the result tiles
+        // the bias sums follow the result tiles, or (tiled == 3) are the row after the last
+        const int tile_items = sg.tiled == 3 ? sg.items : sg.items - sg.Nt * 8;
+        const int rows_out = sg.rows_total + (sg.tiled == 3 ? 1 : 0);
         if (e < tile_items) {
             const int tile = e >> 8, r4 = (e >> 6) & 3, l = e & 63;
             const int mt = tile / sg.Nt, nt = tile - mt * sg.Nt;
@@ -506,7 +509,7 @@ __global__ __launch_bounds__(256) void reduce_all_kernel(ReduceArgs a)
             if (oc < sg.Co)
 #pragma unroll
                 for (int z = 0; z < 4; ++z)
-                    if (row0 + z < sg.rows_total) sg.out[(long)(row0 + z) * sg.Co + oc] = r[z];
+                    if (row0 + z < rows_out) sg.out[(long)(row0 + z) * sg.Co + oc] = r[z];
         } else {
             const int oc = 4 * (e - tile_items);
 #pragma unroll

@@ -21,6 +21,7 @@
 #include "kernels_direct.hpp"
 #include "kernels_mfma.hpp"
 #include "kernels_wgrad.hpp"
+#include "kernels_wgrad_bf16.hpp"
 #include "kernels_fused.hpp"
 
 namespace {
@@ -99,6 +100,7 @@ struct Layer {
 struct TilePlan { int PT = 0, NW = 4, Ty = 0, Tx = 0, nty = 0, ntx = 0; size_t lds = 0; bool ok = false; };
 struct WgradPlan {
     bool ok = false;
+    bool bm = false;      // bf16 storage: the bf16 matrix instruction, 16 positions per MFMA
     int Tx = 0, TxP = 0, nty = 0, ntx = 0, tiles_total = 0, tiles_per_slab = 0, slabs = 0;
     int Mt = 0, Nt = 0, wm = 0, wn = 0, wk = 0, mw = 0, gm = 0, gn = 0;
     size_t lds = 0;
@@ -268,7 +270,7 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, co
 
 unsigned magic_of(unsigned x) { return x <= 1 ? 0u : (unsigned)(((1ull << 32) + x - 1) / x); }
 
-WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int out_c)
+WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int out_c, bool bm)
 {
     WgradPlan w;
     const int d = ly.dil, k = ly.k;
@@ -276,6 +278,59 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
     // the kernel forms element offsets inside one image in 32 bits
     const bool fits32 = (size_t)in_r * in_c * ly.cin < (1ull << 31) &&
                         (size_t)out_r * out_c * ly.cout < (1ull << 31) && (k + 3) * d < 65536;
+    // the bf16 instruction's kernel gives a wave pairs of column tiles: not for 32 maps or fewer
+    bm = bm && ly.cout > 32;
+    if (bm && ly.wgrad_mfma && fits32) {
+        // wgrad_bm_kernel.  Every group of workgroups (gm x gn of them cover the result) stages
+        // all tiles again, and a compute unit takes in roughly 7 bytes per cycle, which at
+        // bf16 speed is often the slower side: pick the wave split and the tile width
+        // together, by the time of the busiest workgroup.
+        const int Mt = ceil_div(k * k * ly.cin + 1, 32), Nt = ceil_div(ly.cout, 32), Nu = ceil_div(Nt, 2);
+        const int hh = 4 + k - 1;
+        double best = -1;
+        for (int wn : {4, 2, 1})
+            for (int wm : {1, 2, 4}) {
+                if (wm * wn > 4) continue;
+                const int wk = 4 / (wm * wn);
+                const int gm = ceil_div(Mt, mpcnn::kWgBmMaxTiles * wm), mw = ceil_div(Mt, gm * wm);
+                const int gn = ceil_div(Nu, wn);
+                const int target = std::max(1, kNumCU / (gm * gn));
+                for (int tx = 1; tx <= fw && tx <= 64; ++tx) {
+                    const int nch = ceil_div(tx, 16), txp = 16 * nch;
+                    const mpcnn::BmGeom bg = mpcnn::bm_geom(nch, k, ly.cin, wn);
+                    size_t lds = (size_t)2 * bg.buf_e * 2;
+                    if (wk > 1) lds = std::max(lds, (size_t)2 * mw * 2 * 4096);
+                    const int h_items = hh * (bg.hwp / 2) * ceil_div(ly.cin, 8), d_items = 4 * (txp / 2) * 8 * wn;
+                    if (h_items > mpcnn::kBmStageH * 256 || d_items > mpcnn::kBmStageD * 256 ||
+                        lds > kWgradLdsCap || (bg.hwp + 1) * d >= 65536)
+                        continue;
+                    const int ntx = ceil_div(fw, tx);
+                    const long tiles = (long)B * d * d * ceil_div(fh, 4) * ntx;
+                    if (tiles * std::max(std::max(ntx, ceil_div(fh, 4)), d) >= (1ll << 31)) continue;
+                    const long tps = (tiles + target - 1) / target;
+                    const double t_mul = (4.0 / wk) * nch * 2 * mw * 36.0;          // cycles of the instruction stream
+                    const double t_load = (h_items + d_items) * 32.0 / 7.0;          // cycles to take the tile in
+                    const double cost = (double)tps * (std::max(t_mul, t_load) + 1500.0);
+                    if (best < 0 || cost < best) {
+                        best = cost;
+                        w.wm = wm; w.wn = wn; w.wk = wk; w.mw = mw; w.gm = gm; w.gn = gn;
+                        w.Tx = tx; w.TxP = txp; w.lds = std::max(lds, (size_t)1024);
+                    }
+                }
+            }
+        if (best >= 0) {
+            w.bm = true; w.Mt = Mt; w.Nt = Nt;
+            w.plen = (size_t)Mt * Nt * 1024;
+            const int target = std::max(1, kNumCU / (w.gm * w.gn));
+            w.nty = ceil_div(fh, 4); w.ntx = ceil_div(fw, w.Tx);
+            w.tiles_total = B * d * d * w.nty * w.ntx;
+            w.tiles_per_slab = ceil_div(w.tiles_total, target);
+            w.slabs = ceil_div(w.tiles_total, w.tiles_per_slab);
+            w.ok = true;
+            return w;
+        }
+        w = WgradPlan();
+    }
     if (ly.wgrad_mfma && fits32) {
         // split of the four waves over result rows / columns / tile rows: least padded work,
         // then fewest workgroup groups (each group stages the tiles again)
@@ -326,6 +381,7 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
             return w;
         }
     }
+    w = WgradPlan();
     long rows_total = (long)B * out_r;
     w.rows_per_chunk = (int)std::max<long>(1, (rows_total + kDirectWgradChunks - 1) / kDirectWgradChunks);
     w.chunks = (int)((rows_total + w.rows_per_chunk - 1) / w.rows_per_chunk);
@@ -370,7 +426,7 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         } else if (training) {
             if (ly.dgrad_mfma && l > 0)
                 g->dgrad[l] = plan_conv_tiles(B, in_r, in_c, ly.dil, ly.k, ly.dgrad_rpad, ly.dgrad_ct, ly.dgrad_bm);
-            g->wgrad[l] = plan_wgrad(ly, B, in_r, in_c, r, c);
+            g->wgrad[l] = plan_wgrad(ly, B, in_r, in_c, r, c, net->bf16);
             const WgradPlan& w = g->wgrad[l];
             g->partial_n[l] = w.ok ? w.slabs : w.chunks;
             g->partial_len[l] = w.plen;
@@ -476,6 +532,16 @@ void launch_wgrad_mfma(const mpcnn::WgradArgs& a, dim3 grid, size_t lds, hipStre
     }
 #undef CASE
 }
+void launch_wgrad_bm(const mpcnn::WgradArgs& a, int nch, dim3 grid, size_t lds, hipStream_t st)
+{
+#define CASE(m, c) case 4 * m + c - 5: mpcnn::wgrad_bm_kernel<m, c><<<grid, 512, lds, st>>>(a); return;
+#define ROW(m) CASE(m, 1) CASE(m, 2) CASE(m, 3) CASE(m, 4)
+    switch (4 * a.mw + nch - 5) {
+    ROW(1) ROW(2) ROW(3) ROW(4) ROW(5)
+    }
+#undef ROW
+#undef CASE
+}
 // Kernels that may ask for more than 64 KiB of dynamic LDS must say so once.
 template <typename T>
 mpcnn_status set_lds_attrs_t()
@@ -493,6 +559,10 @@ mpcnn_status set_lds_attrs_t()
     ATTR((mpcnn::wgrad_mfma_kernel<9, T>)); ATTR((mpcnn::wgrad_mfma_kernel<10, T>));
     ATTR((mpcnn::wgrad_mfma_kernel<11, T>));
     if constexpr (std::is_same<T, mpcnn::bf16>::value) {
+#define ROW(m) ATTR((mpcnn::wgrad_bm_kernel<m, 1>)); ATTR((mpcnn::wgrad_bm_kernel<m, 2>)); \
+               ATTR((mpcnn::wgrad_bm_kernel<m, 3>)); ATTR((mpcnn::wgrad_bm_kernel<m, 4>))
+        ROW(1); ROW(2); ROW(3); ROW(4); ROW(5);
+#undef ROW
         ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 8, T, true>));
         ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 8, T, true>));
         ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 8, T, true>));
@@ -742,11 +812,19 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.tiles_total = wp.tiles_total; a.tiles_per_slab = wp.tiles_per_slab;
                 a.Mt = wp.Mt; a.Nt = wp.Nt; a.wm = wp.wm; a.wn = wp.wn; a.wk = wp.wk; a.mw = wp.mw;
                 a.mg_cq = magic_of(ceil_div(Ci, 4)); a.mg_hwp = magic_of(wp.TxP + ly.k - 1);
+                if (wp.bm) {   // items of two positions x 8 channels
+                    a.mg_cq = magic_of(ceil_div(Ci, 8));
+                    a.mg_hwp = magic_of(mpcnn::bm_geom(wp.TxP / 16, ly.k, Ci, wp.wn).hwp / 2);
+                }
                 a.mg_txp = magic_of(wp.TxP); a.mg_ci = magic_of(Ci); a.mg_k = magic_of(ly.k);
                 a.mg_ntx = magic_of(wp.ntx); a.mg_nty = magic_of(wp.nty); a.mg_d = magic_of(ly.dil);
                 dim3 grid((unsigned)wp.slabs, (unsigned)wp.gm, (unsigned)wp.gn);
-                LAUNCH("wgrad_mfma", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
-                       launch_wgrad_mfma<T>(a, grid, wp.lds, st));
+                if (wp.bm)
+                    LAUNCH("wgrad_mfma", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
+                           launch_wgrad_bm(a, wp.TxP / 16, grid, wp.lds, st));
+                else
+                    LAUNCH("wgrad_mfma", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
+                           launch_wgrad_mfma<T>(a, grid, wp.lds, st));
             } else if constexpr (!kF32) {
                 return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             } else {
@@ -799,8 +877,8 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
         sg.out = net->d_grads + ly.p_off;
         sg.plen = (long)g.partial_len[l]; sg.n = g.partial_n[l];
         const WgradPlan& wp = g.wgrad[l];
-        sg.tiled = wp.ok ? 1 : 0;
-        sg.items = wp.ok ? wp.Mt * wp.Nt * 256 + wp.Nt * 8 : (int)ly.p_len;
+        sg.tiled = wp.ok ? (wp.bm ? 3 : 1) : 0;
+        sg.items = wp.ok ? wp.Mt * wp.Nt * 256 + (wp.bm ? 0 : wp.Nt * 8) : (int)ly.p_len;
         sg.Nt = wp.Nt; sg.rows_total = ly.k * ly.k * ly.cin; sg.Co = ly.cout;
         sg.block0 = ra.total_blocks;
         ra.total_blocks += (sg.items + 63) / 64;
