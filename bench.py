@@ -123,6 +123,8 @@ def main():
     dom = by_name[dom_name]
     bound = "mfma" if "mfma" in dom_name else "hbm"
     peak, unit = PEAK[bound]
+    if bound == "mfma" and cfg.dtype == "bf16":
+        peak = 2500.0   # bf16 storage multiplies on the bf16 matrix instruction (fp32 accumulation)
     work = dom["flops"] if bound == "mfma" else dom["bytes"]
     achieved = work / (dom["ms"] * 1e-3) / (1e12 if bound == "mfma" else 1e9)
     traffic = read_traffic(os.path.join(ROOT, "profiles", "traffic_%s.txt" % cfg.name), dom_name)
@@ -174,7 +176,7 @@ def main():
         "metric": "training pixels/sec (fwd+bwd, whole image) on 1 MI355X",
         "value": round(value, 1), "unit": "pixels/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "batch": cfg.batch, "height": cfg.height, "width": cfg.width,
                    "patch": cfg.patch, "valid_pixels_per_step": cfg.valid_pixels,
                    "storage": cfg.dtype,
