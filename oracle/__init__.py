@@ -195,6 +195,70 @@ def armijo_step(f, theta, g, f0, alpha0, scale=1.0, c=1e-4, beta=0.5, max_trials
     return theta.copy(), 0.0, float(f0), max_trials
 
 
+def lbfgs_direction(g, pairs):
+    """Search direction p = -H g of the limited-memory BFGS method (Results, the steel data set:
+    LBFGS is the optimiser used there; the paper gives no details, this is the method's
+    standard two-loop recursion).  pairs = [(s_0, y_0), ...], oldest first, s = difference of
+    two successive parameter vectors, y = difference of their gradients.  H is the inverse
+    Hessian estimate the BFGS update builds from the pairs, starting from
+    H_0 = (s.y / y.y) I of the newest pair; without pairs p = -g."""
+    q = np.array(g, dtype=np.float64)
+    if not pairs:
+        return -q
+    rho = [1.0 / float(np.dot(s, y)) for s, y in pairs]
+    a = [0.0] * len(pairs)
+    for i in range(len(pairs) - 1, -1, -1):           # newest to oldest
+        s, y = pairs[i]
+        a[i] = rho[i] * float(np.dot(s, q))
+        q = q - a[i] * np.asarray(y, dtype=np.float64)
+    s, y = pairs[-1]
+    r = (float(np.dot(s, y)) / float(np.dot(y, y))) * q
+    for i in range(len(pairs)):                       # oldest to newest
+        s, y = pairs[i]
+        b = rho[i] * float(np.dot(y, r))
+        r = r + np.asarray(s, dtype=np.float64) * (a[i] - b)
+    return -r
+
+
+def lbfgs_step(f, theta, g, f0, state, alpha0=1.0, c=1e-4, beta=0.5, max_trials=20, history=8,
+               curvature=1e-10):
+    """One iteration of limited-memory BFGS with a back-tracking line search (same rule as
+    armijo_step, along p instead of -g).  state is a dict the caller keeps between calls
+    (start with {}): the previous parameters and gradient and the stored pairs.
+      1. If there is a previous iterate: s = theta - theta_prev, y = g - g_prev; the pair is
+         stored (the oldest dropped beyond `history`) iff s.y > curvature * |s| |y|.
+      2. p = lbfgs_direction(g, pairs); if g.p >= 0 the pairs are dropped and p = -g.
+      3. alpha = alpha0, beta*alpha0, ...: the first with f(theta + alpha p) <= f0 + c alpha g.p
+         is accepted; theta and g become the previous iterate.
+      4. If no trial passes: parameters unchanged, alpha = 0, history and previous iterate dropped.
+    Returns (new theta, alpha, f(new theta), trials, pairs in use)."""
+    theta = np.asarray(theta, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    pairs = state.setdefault("pairs", [])
+    if state.get("theta_prev") is not None:
+        s, y = theta - state["theta_prev"], g - state["g_prev"]
+        if float(np.dot(s, y)) > curvature * np.sqrt(float(np.dot(s, s)) * float(np.dot(y, y))):
+            pairs.append((s, y))
+            del pairs[:max(0, len(pairs) - history)]
+    p = lbfgs_direction(g, pairs)
+    slope = float(np.dot(g, p))
+    if slope >= 0.0:
+        del pairs[:]
+        p, slope = -g, -float(np.dot(g, g))
+    used = len(pairs)
+    alpha = float(alpha0)
+    for trial in range(1, max_trials + 1):
+        cand = theta + alpha * p
+        fc = float(f(cand))
+        if fc <= f0 + c * alpha * slope:
+            state["theta_prev"], state["g_prev"] = theta.copy(), g.copy()
+            return cand, alpha, fc, trial, used
+        alpha *= beta
+    del pairs[:]
+    state["theta_prev"] = state["g_prev"] = None
+    return theta.copy(), 0.0, float(f0), max_trials, used
+
+
 def window_key(layers, in_ch, patch, B, H, W, layer, b, c, y, x):
     """Key of a pooling window in the whole-image map of MP layer `layer` (see orc_ties)."""
     _, ch, ny, nx = dense_shape(layers, in_ch, patch, B, H, W, layer)[:4]

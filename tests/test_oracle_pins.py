@@ -505,6 +505,96 @@ def test_armijo_rule_by_hand():
     assert loss(params - 2 * alpha * r["grads"]) > r["loss"] - 1e-4 * 2 * alpha * np.dot(r["grads"], r["grads"])
 
 
+def _dense_bfgs_inverse(pairs, n):
+    """Textbook BFGS update of the inverse Hessian estimate, written with dense matrices:
+    H <- (I - rho s y^T) H (I - rho y s^T) + rho s s^T for each pair, oldest first, from
+    H_0 = (s.y / y.y) I of the newest pair."""
+    s, y = pairs[-1]
+    H = (np.dot(s, y) / np.dot(y, y)) * np.eye(n)
+    for s, y in pairs:
+        rho = 1.0 / np.dot(s, y)
+        V = np.eye(n) - rho * np.outer(y, s)
+        H = V.T @ H @ V + rho * np.outer(s, s)
+    return H
+
+
+def test_lbfgs_direction_against_dense_bfgs_and_by_hand():
+    """The two-loop recursion must apply exactly the matrix the BFGS update formula builds
+    (Results, the steel data set: LBFGS)."""
+    # one pair by hand: s = (1,0), y = (2,0): rho = 1/2, H0 = I/2, H = diag(1/2, 1/2); g = (4,6) -> p = -(2,3)
+    p = oracle.lbfgs_direction([4.0, 6.0], [(np.array([1.0, 0.0]), np.array([2.0, 0.0]))])
+    np.testing.assert_allclose(p, [-2.0, -3.0], rtol=0, atol=1e-15)
+    # no pairs: steepest descent
+    np.testing.assert_array_equal(oracle.lbfgs_direction([1.0, -2.0, 3.0], []), [-1.0, 2.0, -3.0])
+    rng = np.random.default_rng(7)
+    n = 9
+    A = rng.normal(size=(n, n)); A = A @ A.T + n * np.eye(n)          # pairs of a convex quadratic: y = A s
+    for m in (1, 2, 5, 9):
+        pairs = []
+        for _ in range(m):
+            s = rng.normal(size=n)
+            pairs.append((s, A @ s))
+        g = rng.normal(size=n)
+        H = _dense_bfgs_inverse(pairs, n)
+        np.testing.assert_allclose(oracle.lbfgs_direction(g, pairs), -H @ g, rtol=1e-11, atol=1e-13)
+        # secant equation of the newest pair: H y = s
+        s, y = pairs[-1]
+        np.testing.assert_allclose(oracle.lbfgs_direction(y, pairs), -s, rtol=1e-10, atol=1e-12)
+    # the order of the pairs matters (a reversed history is another matrix)
+    assert np.abs(oracle.lbfgs_direction(g, pairs[::-1]) + _dense_bfgs_inverse(pairs, n) @ g).max() > 1e-6
+
+
+def test_lbfgs_step_rules_and_convergence():
+    """History bookkeeping, the line-search inequality and the fallback, on functions with known
+    minimisers."""
+    rng = np.random.default_rng(8)
+    n = 6
+    A = rng.normal(size=(n, n)); A = A @ A.T + np.eye(n)
+    b = rng.normal(size=n)
+    f = lambda x: 0.5 * x @ A @ x - b @ x
+    grad = lambda x: A @ x - b
+    x, st = np.zeros(n), {}
+    for it in range(40):
+        g = grad(x)
+        if np.linalg.norm(g) < 1e-8:     # below this the decrease is lost in f's rounding
+            break
+        x_new, alpha, fv, trials, used = oracle.lbfgs_step(f, x, g, f(x), st, history=4)
+        assert used == min(it, 4) and alpha == 0.5 ** (trials - 1)
+        # accepted point satisfies the inequality with the direction actually used
+        p = (x_new - x) / alpha
+        assert fv <= f(x) + 1e-4 * alpha * (g @ p) + 1e-15
+        if trials > 1:   # and the step before it did not
+            assert f(x + 2 * alpha * p) > f(x) + 1e-4 * 2 * alpha * (g @ p)
+        x = x_new
+    np.testing.assert_allclose(x, np.linalg.solve(A, b), rtol=0, atol=1e-9)
+    assert it < 30                                         # far fewer steps than steepest descent needs
+    # history: pairs are (theta_k+1 - theta_k, g_k+1 - g_k), newest last, at most `history`
+    assert len(st["pairs"]) == 4
+    # a pair without positive curvature is not stored
+    st = {"theta_prev": np.array([0.0, 0.0]), "g_prev": np.array([1.0, 0.0]), "pairs": []}
+    q = lambda x: 0.5 * float(x @ x)
+    _, _, _, _, used = oracle.lbfgs_step(q, np.array([1.0, 0.0]), np.array([0.5, 0.0]), 0.5, st)
+    assert used == 0 and st["pairs"] == []                 # s.y = -0.5
+    # nothing acceptable: parameters untouched, alpha = 0, history dropped
+    up = lambda x: 1.0 + float(np.abs(x - 1.0).sum())
+    st = {}
+    th, alpha, fv, trials, used = oracle.lbfgs_step(up, np.array([1.0]), np.array([1.0]), 1.0, st, max_trials=4)
+    assert (th.tolist(), alpha, fv, trials) == ([1.0], 0.0, 1.0, 4) and st["theta_prev"] is None
+    # on the real loss: three iterations decrease it monotonically
+    layers, in_ch, P = NETS["tiny18"]
+    params = rand_params(layers, in_ch, P, 52)
+    img = rng.uniform(0, 1, (1, in_ch, P + 2, P + 1))
+    lab = rng.integers(0, 2, (1, P + 2, P + 1)).astype(np.int32)
+    loss = lambda th: oracle.run(layers, in_ch, P, th, img, lab, want_probs=False)["loss"]
+    st, th, hist = {}, params, []
+    for it in range(3):
+        r = oracle.run(layers, in_ch, P, th, img, lab, want_grads=True)
+        th, alpha, fv, trials, used = oracle.lbfgs_step(loss, th, r["grads"], r["loss"], st, alpha0=1.0)
+        assert alpha > 0 and fv < r["loss"] and used == it
+        hist.append(fv)
+    assert hist[0] > hist[1] > hist[2]
+
+
 def test_mirror_pad_by_hand():
     """Borders synthesised by mirroring, edge pixel repeated; c = (P-1)//2 above/left and
     P-1-c below/right, so that output (i,j) is the patch centred on input (i,j)
