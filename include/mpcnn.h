@@ -214,6 +214,37 @@ mpcnn_status mpcnn_armijo_step(mpcnn_net* net, const float* image_dev, const int
                                int* trials_host);
 
 /*
+ * One iteration of limited-memory BFGS with a back-tracking line search (Results, the steel
+ * data set: LBFGS is the optimiser used there; the paper gives no details, so this is the
+ * method's standard form).  To be called after mpcnn_seg_backward on the same inputs, whose
+ * gradient g the net holds and whose loss the caller passes as f0; the objective is the summed
+ * loss of that batch.
+ *   1. If the call before this one accepted a step: s = theta - theta_prev, y = g - g_prev; the
+ *      pair is stored (the oldest dropped beyond `history`, 1..64) iff s.y > 1e-10 |s| |y|.
+ *   2. p = -H g by the two-loop recursion over the stored pairs, H_0 = (s.y / y.y) I of the
+ *      newest pair (p = -g without pairs); if g.p >= 0 the pairs are dropped and p = -g.
+ *   3. alpha = alpha0, beta*alpha0, ... (at most max_trials values): the first with
+ *      L(theta + alpha p) <= f0 + c alpha g.p is accepted; each trial costs one loss-only forward.
+ *   4. If none passes the parameters are left as they were, *alpha_host = 0, and the history is
+ *      dropped.
+ * Dot products are fp64 sums in a fixed order, the pairs and the direction are fp32 vectors
+ * (2 (history + 1) + 3 parameter-sized device buffers, allocated at the first call; changing
+ * `history` starts afresh).  mpcnn_set_params and mpcnn_lbfgs_reset drop the history.
+ * Synchronous on hip_stream.
+ *   alpha_host, loss_host, trials_host, pairs_host: results on the host (accepted alpha, loss at
+ *   the new parameters, trials made, pairs the direction used); any may be NULL.  ws_dev as for
+ *   mpcnn_seg_loss.
+ * Errors: EINVAL (also: alpha0 <= 0, beta outside (0,1), c outside [0,1), max_trials < 1,
+ * history outside 1..64), ESHAPE, EWORKSPACE, EHIP.
+ */
+mpcnn_status mpcnn_lbfgs_step(mpcnn_net* net, const float* image_dev, const int32_t* labels_dev,
+                              const float* pixw_dev, int B, int H, int W, double f0, int history,
+                              float alpha0, float c, float beta, int max_trials, void* ws_dev,
+                              size_t ws_bytes, void* hip_stream, float* alpha_host, double* loss_host,
+                              int* trials_host, int* pairs_host);
+mpcnn_status mpcnn_lbfgs_reset(mpcnn_net* net);
+
+/*
  * Test hooks: read back what the last forward/backward left in the workspace
  * (which must still be alive).  Synchronous.
  *   mpcnn_get_activation: output of layer `layer`, [B][rows][cols][channels] fp32.

@@ -252,6 +252,8 @@ __global__ __launch_bounds__(512, 1) void wgrad_bm_kernel(WgradArgs a)
         }
     } else {
         // ================= multiplying waves =================
+        // LDS byte address of the buffers (the low half of the array's flat address)
+        const unsigned lds_base = (unsigned)reinterpret_cast<size_t>(lds);
         // byte offset in a buffer of this lane's A operand: its (tap, c) at tile row 0, column 8*lk
         unsigned ap[PM];
 #pragma unroll
@@ -263,12 +265,11 @@ __global__ __launch_bounds__(512, 1) void wgrad_bm_kernel(WgradArgs a)
                 const unsigned ta = magic_div(tap, a.mg_k, a.k), tb = tap - ta * a.k;
                 o = dt_e + c * HPb + (c >> 3) * 8 + ta * hwp + tb;
             }
-            ap[p] = 2u * (o + 8 * lk);
+            ap[p] = lds_base + 2u * (o + 8 * lk);
         }
         const unsigned brow = 64 * nidx + lm;
-        const unsigned boff = 2u * (brow * DPb + (brow >> 3) * 8 + 8 * lk);   // B operand: columns 8*lk.. of row 0
+        const unsigned boff = lds_base + 2u * (brow * DPb + (brow >> 3) * 8 + 8 * lk);   // B operand: columns 8*lk.. of row 0
         constexpr int BJ = 2 * (32 * DPb + 32);                                // bytes to the wave's second column tile
-        const char* ldsb = reinterpret_cast<const char*>(lds);
         const unsigned row_a = 2u * hwp, row_b = 2u * TxP;                     // bytes from a row to the next
 
         // One tile: per row NCH chunks of 16 columns, 2 PM instructions per chunk, column tile

@@ -22,6 +22,7 @@
 #include "kernels_mfma.hpp"
 #include "kernels_wgrad.hpp"
 #include "kernels_wgrad_bf16.hpp"
+#include "kernels_lbfgs.hpp"
 #include "kernels_fused.hpp"
 
 namespace {
@@ -149,7 +150,14 @@ struct mpcnn_net {
     bool bf16 = false;            // activations and deltas stored in bf16 (arithmetic stays fp32)
     float* d_params = nullptr;
     float* d_params0 = nullptr;   // copy of the parameters a safeguarded step starts from
-    double* d_scalar = nullptr;   // two fp64 results of that step's reductions
+    double* d_scalar = nullptr;   // fp64 results of that step's reductions (8)
+    // limited-memory BFGS: pairs in a ring of lb_m + 1 slots (one always free for the candidate)
+    int lb_m = 0, lb_head = 0, lb_count = 0;
+    bool lb_have_prev = false;
+    float *d_lb_S = nullptr, *d_lb_Y = nullptr;            // [lb_m + 1][n_params]
+    float *d_lb_theta_prev = nullptr, *d_lb_g_prev = nullptr, *d_lb_p = nullptr;
+    double *d_lb_part = nullptr, *d_lb_alpha = nullptr;    // partial sums (5 x kLbBlocks), first-loop coefficients
+    std::vector<double> lb_sy, lb_yy;                      // per slot
     float* d_wread = nullptr;     // what the kernels read: d_params, or its copy rounded to bf16 values
     bool wread_stale = true;
     float* d_grads = nullptr;
@@ -928,6 +936,17 @@ void to_host_order(const mpcnn_net* net, const float* dev_order, float* host)
     }
 }
 
+void lbfgs_free(mpcnn_net* net)
+{
+    (void)hipFree(net->d_lb_S); (void)hipFree(net->d_lb_Y);
+    (void)hipFree(net->d_lb_theta_prev); (void)hipFree(net->d_lb_g_prev); (void)hipFree(net->d_lb_p);
+    (void)hipFree(net->d_lb_part); (void)hipFree(net->d_lb_alpha);
+    net->d_lb_S = net->d_lb_Y = net->d_lb_theta_prev = net->d_lb_g_prev = net->d_lb_p = nullptr;
+    net->d_lb_part = net->d_lb_alpha = nullptr;
+    net->lb_m = net->lb_head = net->lb_count = 0;
+    net->lb_have_prev = false;
+}
+
 mpcnn_status read_back(const mpcnn_net* net, const float* dev, float* host, size_t n)
 {
     if (!net || !host) return fail(MPCNN_EINVAL, "null argument");
@@ -1044,6 +1063,7 @@ void mpcnn_net_destroy(mpcnn_net* net)
         if (net->d_wread && net->d_wread != net->d_params) (void)hipFree(net->d_wread);
         (void)hipFree(net->d_params0);
         (void)hipFree(net->d_scalar);
+        lbfgs_free(net);
         (void)hipFree(net->d_params);
         (void)hipFree(net->d_grads);
         (void)hipFree(net->d_packs);
@@ -1093,6 +1113,7 @@ mpcnn_status mpcnn_set_params(mpcnn_net* net, const float* params_host, size_t n
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipMemcpy(net->d_params, tmp.data(), sizeof(float) * n, hipMemcpyHostToDevice));
     net->packs_stale = true; net->wread_stale = true;
+    net->lb_head = net->lb_count = 0; net->lb_have_prev = false;   // a new starting point has no history
     return MPCNN_OK;
 }
 
@@ -1275,7 +1296,7 @@ mpcnn_status mpcnn_armijo_step(mpcnn_net* net, const float* image_dev, const int
     hipStream_t st = (hipStream_t)hip_stream;
     const long n = (long)net->n_params;
     if (!net->d_params0) HIP_TRY(hipMalloc((void**)&net->d_params0, sizeof(float) * n));
-    if (!net->d_scalar) HIP_TRY(hipMalloc((void**)&net->d_scalar, 2 * sizeof(double)));
+    if (!net->d_scalar) HIP_TRY(hipMalloc((void**)&net->d_scalar, 8 * sizeof(double)));
     HIP_TRY(hipMemcpyAsync(net->d_params0, net->d_params, sizeof(float) * n, hipMemcpyDeviceToDevice, st));
     mpcnn::sqnorm_kernel<<<1, 1024, 0, st>>>(net->d_grads, n, net->d_scalar);
     double gg = 0.0;
@@ -1306,6 +1327,145 @@ mpcnn_status mpcnn_armijo_step(mpcnn_net* net, const float* image_dev, const int
     if (alpha_host) *alpha_host = alpha;
     if (loss_host) *loss_host = f;
     if (trials_host) *trials_host = trial;
+    return rc;
+}
+
+mpcnn_status mpcnn_lbfgs_reset(mpcnn_net* net)
+{
+    if (!net) return fail(MPCNN_EINVAL, "null net");
+    net->lb_head = net->lb_count = 0;
+    net->lb_have_prev = false;
+    return MPCNN_OK;
+}
+
+mpcnn_status mpcnn_lbfgs_step(mpcnn_net* net, const float* image_dev, const int32_t* labels_dev,
+                              const float* pixw_dev, int B, int H, int W, double f0, int history,
+                              float alpha0, float c, float beta, int max_trials, void* ws_dev,
+                              size_t ws_bytes, void* hip_stream, float* alpha_host, double* loss_host,
+                              int* trials_host, int* pairs_host)
+{
+    using namespace mpcnn;
+    Geom g;
+    mpcnn_status rc = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &g);
+    if (rc != MPCNN_OK) return rc;
+    if (!labels_dev) return fail(MPCNN_EINVAL, "null labels_dev");
+    if (!(alpha0 > 0.f) || !(beta > 0.f && beta < 1.f) || !(c >= 0.f && c < 1.f) || max_trials < 1 ||
+        history < 1 || history > 64)
+        return fail(MPCNN_EINVAL, "alpha0 = %g, beta = %g, c = %g, max_trials = %d, history = %d", alpha0, beta,
+                    c, max_trials, history);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const long n = (long)net->n_params;
+    const size_t vec = sizeof(float) * n;
+    if (net->lb_m != history) {   // first call, or another history length: start afresh
+        lbfgs_free(net);
+        HIP_TRY(hipMalloc((void**)&net->d_lb_S, vec * (history + 1)));
+        HIP_TRY(hipMalloc((void**)&net->d_lb_Y, vec * (history + 1)));
+        HIP_TRY(hipMalloc((void**)&net->d_lb_theta_prev, vec));
+        HIP_TRY(hipMalloc((void**)&net->d_lb_g_prev, vec));
+        HIP_TRY(hipMalloc((void**)&net->d_lb_p, vec));
+        HIP_TRY(hipMalloc((void**)&net->d_lb_part, sizeof(double) * 5 * kLbBlocks));
+        HIP_TRY(hipMalloc((void**)&net->d_lb_alpha, sizeof(double) * (history + 1)));
+        net->lb_m = history;
+        net->lb_sy.assign(history + 1, 0.0); net->lb_yy.assign(history + 1, 0.0);
+    }
+    if (!net->d_params0) HIP_TRY(hipMalloc((void**)&net->d_params0, vec));
+    if (!net->d_scalar) HIP_TRY(hipMalloc((void**)&net->d_scalar, 8 * sizeof(double)));
+    const int slots = net->lb_m + 1;
+    double* part[2] = {net->d_lb_part, net->d_lb_part + kLbBlocks};
+
+    // 1. the pair (theta - theta_prev, g - g_prev), kept if its curvature s.y is positive
+    if (net->lb_have_prev) {
+        const int slot = (net->lb_head + net->lb_count) % slots;
+        lb_pair_kernel<<<kLbBlocks, 256, 0, st>>>(net->d_params, net->d_lb_theta_prev, net->d_grads, net->d_lb_g_prev,
+                                                  net->d_lb_S + (size_t)slot * n, net->d_lb_Y + (size_t)slot * n,
+                                                  net->d_lb_part + 2 * kLbBlocks, n);
+        lb_sum_kernel<<<1, 256, 0, st>>>(net->d_lb_part + 2 * kLbBlocks, 3, net->d_scalar + 2);
+        double r[3];
+        HIP_TRY(hipMemcpyAsync(r, net->d_scalar + 2, sizeof(r), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        if (r[0] > 1e-10 * std::sqrt(r[2] * r[1])) {
+            net->lb_sy[slot] = r[0]; net->lb_yy[slot] = r[1];
+            if (net->lb_count < net->lb_m) ++net->lb_count;
+            else net->lb_head = (net->lb_head + 1) % slots;   // the oldest pair's slot becomes the free one
+        }
+    }
+
+    // 2. p = -H g by the two-loop recursion, and the slope g.p
+    double slope = 0.0;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        const int M = net->lb_count;
+        auto slot_of = [&](int i) { return (net->lb_head + i) % slots; };   // i = 0 oldest
+        LbArgs a{};
+        a.q = net->d_lb_p; a.n = n; a.alpha = net->d_lb_alpha;
+        int flip = 0;
+        a.mode = 0; a.src = net->d_grads; a.part_out = part[flip];
+        if (M == 0) { a.scale = -1.0; a.u = net->d_grads; }
+        else { a.scale = 1.0; a.u = net->d_lb_S + (size_t)slot_of(M - 1) * n; }
+        lb_update_kernel<<<kLbBlocks, 256, 0, st>>>(a);
+        for (int i = M - 1; i >= 0; --i) {        // newest to oldest
+            const int sl = slot_of(i);
+            a.mode = 1; a.idx = i; a.rho = 1.0 / net->lb_sy[sl];
+            a.v = net->d_lb_Y + (size_t)sl * n;
+            a.part_in = part[flip]; flip ^= 1; a.part_out = part[flip];
+            if (i > 0) { a.scale = 1.0; a.u = net->d_lb_S + (size_t)slot_of(i - 1) * n; }
+            else {                                  // the turn: r = H_0 q
+                const int nw = slot_of(M - 1);
+                a.scale = net->lb_sy[nw] / net->lb_yy[nw];
+                a.u = net->d_lb_Y + (size_t)slot_of(0) * n;
+            }
+            lb_update_kernel<<<kLbBlocks, 256, 0, st>>>(a);
+        }
+        for (int i = 0; i < M; ++i) {              // oldest to newest
+            const int sl = slot_of(i);
+            a.mode = 2; a.idx = i; a.rho = 1.0 / net->lb_sy[sl];
+            a.v = net->d_lb_S + (size_t)sl * n;
+            a.part_in = part[flip]; flip ^= 1; a.part_out = part[flip];
+            if (i + 1 < M) { a.scale = 1.0; a.u = net->d_lb_Y + (size_t)slot_of(i + 1) * n; }
+            else { a.scale = -1.0; a.u = net->d_grads; }
+            lb_update_kernel<<<kLbBlocks, 256, 0, st>>>(a);
+        }
+        lb_sum_kernel<<<1, 256, 0, st>>>(part[flip], 1, net->d_scalar);
+        HIP_TRY(hipMemcpyAsync(&slope, net->d_scalar, sizeof(double), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        if (slope < 0.0 || M == 0) break;
+        net->lb_count = 0;                         // not a descent direction: forget the pairs
+    }
+    const int used = net->lb_count;
+
+    // 3. back-tracking along p
+    HIP_TRY(hipMemcpyAsync(net->d_params0, net->d_params, vec, hipMemcpyDeviceToDevice, st));
+    float alpha = alpha0;
+    double f = f0;
+    int trial = 0;
+    bool ok = false;
+    while (slope < 0.0 && trial < max_trials) {
+        ++trial;
+        step_from_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(net->d_params, net->d_params0, net->d_lb_p,
+                                                                      -alpha, n);
+        net->packs_stale = true; net->wread_stale = true;
+        rc = loss_only(net, g, image_dev, labels_dev, pixw_dev, net->d_scalar + 1, (char*)ws_dev, st);
+        if (rc != MPCNN_OK) break;
+        HIP_TRY(hipMemcpyAsync(&f, net->d_scalar + 1, sizeof(double), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        if (f <= f0 + (double)c * (double)alpha * slope) { ok = true; break; }
+        alpha *= beta;
+    }
+    if (ok) {      // this iterate becomes the previous one
+        std::swap(net->d_params0, net->d_lb_theta_prev);
+        HIP_TRY(hipMemcpyAsync(net->d_lb_g_prev, net->d_grads, vec, hipMemcpyDeviceToDevice, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        net->lb_have_prev = true;
+    } else {       // also after an error: the parameters the call started from, no history
+        HIP_TRY(hipMemcpyAsync(net->d_params, net->d_params0, vec, hipMemcpyDeviceToDevice, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        net->packs_stale = true; net->wread_stale = true;
+        net->lb_count = 0; net->lb_head = 0; net->lb_have_prev = false;
+        alpha = 0.f; f = f0;
+    }
+    if (alpha_host) *alpha_host = alpha;
+    if (loss_host) *loss_host = f;
+    if (trials_host) *trials_host = trial;
+    if (pairs_host) *pairs_host = used;
     return rc;
 }
 

@@ -30,6 +30,7 @@ SYMBOLS = [
     "mpcnn_sgd_step", "mpcnn_get_activation", "mpcnn_get_argmax", "mpcnn_last_error",
     "mpcnn_profile_enable", "mpcnn_profile_read", "mpcnn_workspace_bytes_same", "mpcnn_seg_forward_same",
     "mpcnn_set_loss", "mpcnn_class_balance_weights", "mpcnn_seg_loss", "mpcnn_armijo_step",
+    "mpcnn_lbfgs_step", "mpcnn_lbfgs_reset",
 ]
 
 
@@ -87,6 +88,10 @@ def lib():
         L.mpcnn_armijo_step.argtypes = [vp, vp, vp, vp, i, i, i, C.c_double, C.c_float, C.c_float, C.c_float,
                                         C.c_float, i, vp, sz, vp, C.POINTER(C.c_float), C.POINTER(C.c_double),
                                         C.POINTER(i)]
+        L.mpcnn_lbfgs_step.argtypes = [vp, vp, vp, vp, i, i, i, C.c_double, i, C.c_float, C.c_float, C.c_float,
+                                       i, vp, sz, vp, C.POINTER(C.c_float), C.POINTER(C.c_double),
+                                       C.POINTER(i), C.POINTER(i)]
+        L.mpcnn_lbfgs_reset.argtypes = [vp]
         L.mpcnn_set_loss.argtypes = [vp, i]
         L.mpcnn_class_balance_weights.argtypes = [vp, vp, i, i, i, vp, vp, vp]
         L.mpcnn_seg_backward.argtypes = [vp, vp, vp, vp, i, i, i, vp, vp, vp, sz, vp]
@@ -219,6 +224,22 @@ class Net:
                                        grad_scale, c, beta, max_trials, _ptr(ws), ws.numel(),
                                        _stream_handle(stream), C.byref(a), C.byref(f), C.byref(t)))
         return a.value, f.value, t.value
+
+    def lbfgs_step(self, image, labels, f0, history=8, alpha0=1.0, pixw=None, c=1e-4, beta=0.5,
+                   max_trials=20, ws=None, stream=None):
+        """Limited-memory BFGS iteration after seg_backward on the same inputs
+        -> (alpha, loss, trials, pairs used)."""
+        B, _, H, W = image.shape
+        if ws is None:
+            ws = self.alloc_workspace(B, H, W, False)
+        a, f, t, m = C.c_float(0), C.c_double(0), C.c_int(0), C.c_int(0)
+        _check(lib().mpcnn_lbfgs_step(self._h, _ptr(image), _ptr(labels), _ptr(pixw), B, H, W, f0, history,
+                                      alpha0, c, beta, max_trials, _ptr(ws), ws.numel(),
+                                      _stream_handle(stream), C.byref(a), C.byref(f), C.byref(t), C.byref(m)))
+        return a.value, f.value, t.value, m.value
+
+    def lbfgs_reset(self):
+        _check(lib().mpcnn_lbfgs_reset(self._h))
 
     def set_loss(self, kind: str):
         """"mcce": softmax + cross-entropy (default); "mse": linear outputs, half the squared error."""

@@ -435,6 +435,56 @@ def test_loss_only_forward_and_armijo_step():
         net.close()
 
 
+def test_lbfgs_iterations_follow_the_fp64_method():
+    """Four iterations of limited-memory BFGS from the same start: the library (fp32 vectors, fp64
+    dot products) and the fp64 method make the same trials and stay on the same trajectory."""
+    for cfg in (wl.crop(wl.CONFIGS[0], 2, 33, 30), wl.crop(wl.CONFIGS[1], 1, 64, 70)):
+        img, lab = wl.make_inputs(cfg)
+        params = wl.make_params(cfg)
+        args = (cfg.layers, cfg.in_channels, cfg.patch)
+        img64 = img.astype(np.float64)
+        f = lambda th: oracle.run(*args, th, img64, lab, want_probs=False)["loss"]
+        net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch)
+        net.set_params(params)
+        d_img, d_lab = torch.from_numpy(img).cuda(), torch.from_numpy(lab).cuda()
+        ws = net.alloc_workspace(cfg.batch, cfg.height, cfg.width, True)
+        loss_dev = torch.zeros(1, dtype=torch.float64, device="cuda")
+        th, state, far = params.astype(np.float64), {}, 0.0
+        for it in range(4):
+            ref = oracle.run(*args, th, img64, lab, want_grads=True)
+            th_new, a_ref, f_ref, t_ref, used_ref = oracle.lbfgs_step(f, th, ref["grads"], ref["loss"], state, history=3)
+            # trial counts can only be compared if no trial was a close call
+            p = (th_new - th) / a_ref
+            slope = float(np.dot(ref["grads"], p))
+            for k in range(t_ref):
+                a = 0.5 ** k
+                margin = f(th + a * p) - (ref["loss"] + 1e-4 * a * slope)
+                assert abs(margin) > 2e-5 * abs(ref["loss"]), "iteration %d trial %d is a close call" % (it, k)
+            net.seg_backward(d_img, d_lab, None, None, loss_dev, ws)
+            loss0 = float(loss_dev.item())
+            assert abs(loss0 - ref["loss"]) <= 2e-4 * abs(ref["loss"])
+            alpha, f_new, trials, used = net.lbfgs_step(d_img, d_lab, loss0, history=3)
+            say("case %s iteration %d: %d pairs, %d trials, alpha %g, loss %.6f -> %.6f (fp64 %.6f)"
+                % (cfg.name, it, used, trials, alpha, loss0, f_new, f_ref))
+            assert used == used_ref == min(it, 3)
+            assert trials == t_ref and alpha == np.float32(a_ref)
+            assert abs(f_new - f_ref) <= 2e-4 * abs(f_ref)
+            # fp32 rounding of the gradients is carried along the trajectory: the bar is relative
+            # to the largest step made so far
+            far = max(far, np.abs(th_new - th).max())
+            assert np.abs(net.get_params() - th_new).max() <= 1e-3 * far + 1e-6
+            th = th_new
+        # set_params drops the history; so does a line search nothing can satisfy
+        net.lbfgs_reset()
+        net.seg_backward(d_img, d_lab, None, None, loss_dev, ws)
+        before = net.get_params()
+        alpha, f_keep, trials, used = net.lbfgs_step(d_img, d_lab, float(loss_dev.item()), history=3, alpha0=1e6,
+                                                     c=0.99, max_trials=3)
+        assert alpha == 0.0 and trials == 3 and used == 0 and f_keep == float(loss_dev.item())
+        np.testing.assert_array_equal(net.get_params(), before)
+        net.close()
+
+
 def test_forward_same_size_mirrored_borders():
     """Deployment forward: borders synthesised by mirroring, output as large as the image."""
     for cfg in (wl.crop(wl.CONFIGS[0], 2, 31, 40), wl.crop(wl.CONFIGS[1], 1, 70, 61),
