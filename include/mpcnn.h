@@ -66,7 +66,8 @@ typedef enum { MPCNN_C = 0, MPCNN_MP = 1, MPCNN_FC = 2 } mpcnn_kind;
 typedef enum { MPCNN_F32 = 0, MPCNN_BF16 = 1 } mpcnn_dtype;
 
 /* One layer (Background, layer kinds).  C: `maps` output maps, k x k filters.
- * MP: non-overlapping k x k max-pooling (maps ignored).  FC: `maps` units
+ * MP: non-overlapping k x k max-pooling (maps ignored); windows start at the top left of the
+ * map, rows / columns left over when its side is not a multiple of k are dropped.  FC: `maps` units
  * (k ignored); the last layer must be FC and its `maps` is the class count. */
 typedef struct {
     int kind; /* mpcnn_kind */
@@ -79,8 +80,7 @@ typedef struct {
  * image with `in_channels` channels.  Host-only: allocates no device memory
  * (parameters are allocated on the current device by mpcnn_set_params).
  * Errors: EINVAL (null / counts / kinds), ESHAPE (a layer does not fit; no FC
- * at the end; C or MP after an FC), EUNSUPPORTED (a pool whose input side, in
- * patch coordinates, is not a multiple of k; k*k > 255; more than 16 classes;
+ * at the end; C or MP after an FC), EUNSUPPORTED (a pool with k*k > 255; more than 16 classes;
  * MPCNN_BF16 with a layer the matrix-core and fused kernels do not take: channel
  * counts must be multiples of 4 and, between layers, at least 8; the last FC must
  * have 2-4 classes on at most 256 inputs that are a multiple of 4).

@@ -86,6 +86,7 @@ struct Layer {
     int k;        // kernel side (C, FC) or pooling side (MP)
     int cin, cout;
     int dil;      // spacing of this layer's taps in its input map
+    int drop = 0; // MP: trailing rows / columns of the patch-level map that no window covers (side mod k)
     bool tanh_out;
     size_t p_off; // offset of this layer's [(k*k*cin + 1) x cout] block in the parameter buffer
     size_t p_len;
@@ -420,8 +421,10 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
     for (size_t l = 0; l < L; ++l) {
         const Layer& ly = net->layers[l];
         const int in_r = r, in_c = c;
-        r -= (ly.k - 1) * ly.dil;
-        c -= (ly.k - 1) * ly.dil;
+        // a pool that leaves `drop` trailing rows of every patch's map unused shortens the
+        // whole-image map by as many rows of this spacing
+        r -= (ly.k - 1 + ly.drop) * ly.dil;
+        c -= (ly.k - 1 + ly.drop) * ly.dil;
         if (r < 1 || c < 1) return false;
         g->rows[l] = r; g->cols[l] = c;
         size_t bytes = es * (size_t)B * r * c * ly.cout;
@@ -994,9 +997,8 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
             if (d.k < 1) st = fail(MPCNN_EINVAL, "layer %d: MP needs k >= 1", l);
             else if (seen_fc) st = fail(MPCNN_ESHAPE, "layer %d: MP after FC", l);
             else if (side / d.k < 1) st = fail(MPCNN_ESHAPE, "layer %d: %dx%d pooling on a %dx%d map", l, d.k, d.k, side, side);
-            else if (side % d.k != 0) st = fail(MPCNN_EUNSUPPORTED, "layer %d: map side %d is not a multiple of the pooling side %d", l, side, d.k);
             else if (d.k * d.k > 255) st = fail(MPCNN_EUNSUPPORTED, "layer %d: pooling window too large for byte tap codes", l);
-            else { ly.k = d.k; ly.cout = ch; ly.tanh_out = false; side /= d.k; dil *= d.k; }
+            else { ly.k = d.k; ly.cout = ch; ly.tanh_out = false; ly.drop = side % d.k; side /= d.k; dil *= d.k; }
         } else if (d.kind == MPCNN_FC) {
             if (d.maps < 1) st = fail(MPCNN_EINVAL, "layer %d: FC needs maps >= 1", l);
             else { ly.k = seen_fc ? 1 : side; ly.cout = d.maps; ly.tanh_out = (l != n_layers - 1); side = 1; seen_fc = true; }

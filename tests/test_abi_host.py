@@ -56,6 +56,22 @@ def test_dense_shapes_follow_fragment_rule():
     assert spacings == [1, 2, 2, 4, 4, 4]
 
 
+def test_dense_shapes_with_dropped_rows():
+    """Pools on sides that are not multiples of the pooling side (floor): the whole-image maps
+    have the sizes the oracle gets by laying all patches out."""
+    layers = ((C, 8, 3), (MP, 0, 3), (C, 8, 3), (MP, 0, 2), (FC, 12, 0), (FC, 2, 0))   # 18 -> 16 -> 5 -> 3 -> 1
+    net = mpcnn.Net(layers, 1, 18)
+    img = np.zeros((1, 1, 31, 27))
+    params = np.zeros(net.param_count)
+    for layer in range(len(layers)):
+        d = oracle.dense_layer(layers, 1, 18, params, img, layer)
+        r, c, ch, sp = net.layer_shape(31, 27, layer)
+        assert d["act"].shape == (1, ch, r, c), layer
+        assert d["stride"] == sp
+    assert net.layer_shape(31, 27, len(layers) - 1)[:2] == (31 - 17, 27 - 17)
+    net.close()
+
+
 def test_errors():
     with pytest.raises(mpcnn.MpcnnError) as e:
         mpcnn.Net(((C, 2, 3), (MP, 0, 2)), 1, 8)
@@ -63,9 +79,7 @@ def test_errors():
     with pytest.raises(mpcnn.MpcnnError) as e:
         mpcnn.Net(((C, 2, 9), (FC, 2, 0)), 1, 8)
     assert e.value.status == 2                       # filter larger than the map
-    with pytest.raises(mpcnn.MpcnnError) as e:
-        mpcnn.Net(((C, 2, 2), (MP, 0, 2), (FC, 2, 0)), 1, 8)
-    assert e.value.status == 4                       # 7 is not a multiple of 2
+    mpcnn.Net(((C, 2, 2), (MP, 0, 2), (FC, 2, 0)), 1, 8).close()   # 7 is not a multiple of 2: a row is dropped
     with pytest.raises(mpcnn.MpcnnError) as e:
         mpcnn.Net(((FC, 4, 0), (C, 2, 1), (FC, 2, 0)), 1, 8)
     assert e.value.status == 2

@@ -145,6 +145,10 @@ def check_argmax(cfg, net, img, params, with_oracle=True, layers=None):
         codes = net.get_argmax(B, H, W, li)
         post = net.get_activation(B, H, W, li)
         ref_codes, ref_max = first_max_codes(pre, k, dil)
+        # a pool that drops trailing rows of the patch-level map stores only the windows in use
+        assert codes.shape[1] <= ref_codes.shape[1] and codes.shape[2] <= ref_codes.shape[2]
+        ref_codes = ref_codes[:, :codes.shape[1], :codes.shape[2]]
+        ref_max = ref_max[:, :codes.shape[1], :codes.shape[2]]
         assert codes.shape == ref_codes.shape
         assert np.array_equal(codes, ref_codes), (cfg.name, li, "codes differ from the scan of the GPU's own values")
         assert np.array_equal(post, ref_max), (cfg.name, li, "pooled values")
@@ -227,6 +231,22 @@ def test_generic_net_rgb_three_classes_pool3():
     cfg = replace(wl.CONFIGS[4], name="generic_rgb", layers=layers, patch=26, batch=2, height=39,
                   width=33, dtype="f32", weight_amp=0.3)
     full_parity(cfg, with_pixw=True)
+
+
+def test_pools_that_drop_trailing_rows():
+    """Map sides that are not multiples of the pooling side: the windows start at the top left
+    and the remainder is dropped (floor), as the oracle does patch by patch."""
+    from dataclasses import replace
+    # patch 10 -> 8 -> 7 -> (MP2, one row dropped) 3 -> FC over 3x3
+    layers = ((C, 2, 3), (C, 3, 2), (MP, 0, 2), (FC, 4, 0), (FC, 6, 0), (FC, 2, 0))
+    cfg = replace(wl.CONFIGS[0], name="floor_small", layers=layers, in_channels=2, patch=10, batch=2,
+                  height=23, width=19, weight_amp=0.4)
+    full_parity(cfg, with_pixw=True)
+    # patch 18 -> 16 -> (MP3, one dropped) 5 -> 3 -> (MP2, one dropped) 1 -> FC; matrix-core layers
+    layers = ((C, 8, 3), (MP, 0, 3), (C, 8, 3), (MP, 0, 2), (FC, 12, 0), (FC, 2, 0))
+    cfg = replace(wl.CONFIGS[0], name="floor_two_levels", layers=layers, patch=18, batch=1, height=47,
+                  width=41, weight_amp=0.3)
+    full_parity(cfg)
 
 
 def test_class_layer_variants():
