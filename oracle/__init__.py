@@ -67,13 +67,15 @@ def param_count(layers, in_ch: int, patch: int) -> int:
 
 
 def run(layers, in_ch, patch, params, image, labels=None, pixw=None, sel=None,
-        want_probs=True, want_grads=False, want_dimage=False, tie_tau=0.0, alt=None, loss_fn="mcce"):
+        want_probs=True, want_grads=False, want_dimage=False, tie_tau=0.0, alt=None, loss_fn="mcce",
+        squash="tanh"):
     """Patch-by-patch forward (and backward).  Returns a dict with probs, loss,
     grads, dimage (those asked for).  probs is [B,n_cls,Ho,Wo], or [n_sel,n_cls]
     when `sel` (flat indices into [B,Ho,Wo]) is given.
 
     loss_fn: "mcce" (softmax + cross-entropy) or "mse" (linear outputs, half the squared
     error against the one-hot target; `probs` then holds the linear outputs).
+    squash: "tanh" or "logistic", the squashing function of C and hidden FC layers.
 
     tie_tau > 0: also returns `near_ties`, an int64 array [n,4] of (window key,
     chosen tap, runner-up tap, layer) for every pooling window whose two largest
@@ -132,7 +134,8 @@ def run(layers, in_ch, patch, params, image, labels=None, pixw=None, sel=None,
                          _p(grads, C.c_double), _p(dimage, C.c_double),
                          C.c_double(tie_tau), _p(alt_key, C.c_int64), _p(alt_tap, C.c_uint8), C.c_long(n_alt),
                          _p(amb, C.c_int64), C.c_long(amb_cap if amb is not None else 0),
-                         C.byref(amb_n), C.byref(rejected), {"mcce": 0, "mse": 1}[loss_fn])
+                         C.byref(amb_n), C.byref(rejected), {"mcce": 0, "mse": 1}[loss_fn],
+                         {"tanh": 0, "logistic": 1}[squash])
         if rc != 0:
             raise ValueError("orc_run failed (code %d)" % rc)
         if amb is None or amb_n.value <= amb_cap:
@@ -278,7 +281,7 @@ def dense_shape(layers, in_ch, patch, B, H, W, layer):
     return B, ch.value, ny.value, nx.value, st.value
 
 
-def dense_layer(layers, in_ch, patch, params, image, layer):
+def dense_layer(layers, in_ch, patch, params, image, layer, squash="tanh"):
     """Outputs of layer `layer` of every patch laid over the image.  Returns
     dict(act [B,ch,ny,nx], codes, gap (MP layers, else None), covered [B,ny,nx],
     stride)."""
@@ -302,7 +305,7 @@ def dense_layer(layers, in_ch, patch, params, image, layer):
     rc = lib.orc_dense_layer(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch,
                              patch, _p(params, C.c_double), _p(image, C.c_double), B, H, W,
                              layer, _p(act, C.c_double), _p(codes, C.c_uint8),
-                             _p(gap, C.c_double), _p(covered, C.c_uint8))
+                             _p(gap, C.c_double), _p(covered, C.c_uint8), {"tanh": 0, "logistic": 1}[squash])
     if rc != 0:
         raise ValueError("orc_dense_layer failed (code %d)" % rc)
     return {"act": act, "codes": codes, "gap": gap, "covered": covered.astype(bool),

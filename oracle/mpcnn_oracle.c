@@ -18,6 +18,8 @@
  *   FC  the first FC sees the remaining maps flattened [c][r][s] row-major,
  *       i.e. it is a C layer whose kernel covers the whole map; later FCs are
  *       matrix * vector.  Hidden FCs apply tanh; the last FC feeds a softmax.
+ *   The squashing function of C and hidden FC layers is tanh or, on request, the logistic
+ *   function 1 / (1 + exp(-a)) (Background, layer C: "e.g. tanh or logistic").
  * Loss (Results, first paragraph): multi-class cross-entropy, each pixel on its
  * own, here summed over pixels: L = sum_pix w_pix * -log p_pix[t_pix].
  * Alternative (Method, before the MPF back-propagation): mean squared error with
@@ -43,6 +45,7 @@
 #define ORC_MAXL 32
 enum { ORC_C = 0, ORC_MP = 1, ORC_FC = 2 };
 enum { ORC_LOSS_MCCE = 0, ORC_LOSS_MSE = 1 };
+enum { ORC_ACT_TANH = 0, ORC_ACT_LOGISTIC = 1 };
 
 typedef struct {
     int n_layers, in_ch, patch, n_classes;
@@ -57,6 +60,7 @@ typedef struct {
     long idx_off[ORC_MAXL];
     long act_total, idx_total, n_params;
     int loss_kind;                            /* ORC_LOSS_*: what follows the last FC */
+    int act_kind;                             /* ORC_ACT_*: the squashing function of C and hidden FC layers */
 } orc_plan;
 
 /* Shape inference.  Returns 0, or a negative code naming the first problem. */
@@ -206,7 +210,8 @@ static void orc_patch_forward(const orc_plan *pl, const double *par, double *act
                                 for (int v = 0; v < k; ++v)
                                     acc += W[(((long)o * ci + c) * k + u) * k + v] *
                                            x[((long)c * n + (r + u)) * n + (s + v)];
-                        y[((long)o * m + r) * m + s] = pl->tanh_after[l] ? tanh(acc) : acc;
+                        y[((long)o * m + r) * m + s] = !pl->tanh_after[l] ? acc
+                            : pl->act_kind == ORC_ACT_LOGISTIC ? 1.0 / (1.0 + exp(-acc)) : tanh(acc);
                     }
         }
     }
@@ -257,7 +262,8 @@ static void orc_patch_backward(const orc_plan *pl, const double *par, const doub
                     for (int s = 0; s < m; ++s) {
                         long e = ((long)o * m + r) * m + s;
                         double d = dy[e];
-                        if (pl->tanh_after[l]) d *= 1.0 - y[e] * y[e];
+                        if (pl->tanh_after[l])   /* derivative of the squashing function, from its output */
+                            d *= pl->act_kind == ORC_ACT_LOGISTIC ? y[e] * (1.0 - y[e]) : 1.0 - y[e] * y[e];
                         gb[o] += d;
                         for (int c = 0; c < ci; ++c)
                             for (int u = 0; u < k; ++u)
@@ -325,13 +331,14 @@ int orc_run(const int *kinds, const int *maps, const int *ks, int n_layers, int 
             const int32_t *labels, const double *pixw, const int64_t *sel, long n_sel,
             double *probs, double *loss, double *grads, double *dimage,
             double tie_tau, const int64_t *alt, const uint8_t *alt_tap, long n_alt,
-            int64_t *amb, long amb_cap, long *amb_n, long *rejected, int loss_kind)
+            int64_t *amb, long amb_cap, long *amb_n, long *rejected, int loss_kind, int act_kind)
 {
     orc_plan pl;
     int rc = orc_make_plan(&pl, kinds, maps, ks, n_layers, in_ch, patch);
     if (rc < 0) return rc;
     if (loss_kind != ORC_LOSS_MCCE && loss_kind != ORC_LOSS_MSE) return -12;
-    pl.loss_kind = loss_kind;
+    if (act_kind != ORC_ACT_TANH && act_kind != ORC_ACT_LOGISTIC) return -13;
+    pl.loss_kind = loss_kind; pl.act_kind = act_kind;
     const int P = patch, Ho = H - P + 1, Wo = W - P + 1, ctr = (P - 1) / 2, nc = pl.n_classes;
     if (Ho < 1 || Wo < 1 || B < 1) return -10;
     if ((grads || loss) && !labels) return -11;
@@ -451,11 +458,13 @@ int orc_dense_shape(const int *kinds, const int *maps, const int *ks, int n_laye
  */
 int orc_dense_layer(const int *kinds, const int *maps, const int *ks, int n_layers, int in_ch,
                     int patch, const double *params, const double *image, int B, int H, int W,
-                    int layer, double *act_out, uint8_t *codes, double *gap, uint8_t *covered)
+                    int layer, double *act_out, uint8_t *codes, double *gap, uint8_t *covered, int act_kind)
 {
     orc_plan pl;
     int rc = orc_make_plan(&pl, kinds, maps, ks, n_layers, in_ch, patch);
     if (rc < 0) return rc;
+    if (act_kind != ORC_ACT_TANH && act_kind != ORC_ACT_LOGISTIC) return -13;
+    pl.act_kind = act_kind;
     if (layer < 0 || layer >= n_layers || H < patch || W < patch) return -10;
     const int P = patch, Ho = H - P + 1, Wo = W - P + 1;
     const int st = pl.stride_out[layer], m = pl.side_out[layer], ch = pl.ch_out[layer];

@@ -57,7 +57,7 @@ def split_params(layers, in_ch, patch, params):
     return out
 
 
-def torch_patch_net(layers, in_ch, patch, params_t, x):
+def torch_patch_net(layers, in_ch, patch, params_t, x, squash=torch.tanh):
     """Textbook net on patches x [N,C,P,P] with library ops; returns logits [N,n_cls]."""
     side, ch, off, seen_fc = patch, in_ch, 0, False
     h = x
@@ -73,11 +73,11 @@ def torch_patch_net(layers, in_ch, patch, params_t, x):
         b = params_t[off + nw:off + nw + maps]
         off += nw + maps
         if kind == C:
-            h = torch.tanh(F.conv2d(h, W, b))
+            h = squash(F.conv2d(h, W, b))
         else:
             h = F.linear(h.reshape(h.shape[0], -1), W.reshape(maps, -1), b)
             if li != L - 1:
-                h = torch.tanh(h)
+                h = squash(h)
             h = h.reshape(h.shape[0], maps, 1, 1)
         side = side - kk + 1
         ch = maps
@@ -516,6 +516,43 @@ def _dense_bfgs_inverse(pairs, n):
         V = np.eye(n) - rho * np.outer(y, s)
         H = V.T @ H @ V + rho * np.outer(s, s)
     return H
+
+
+def test_logistic_activation_matches_autograd():
+    """The logistic function as the squashing function of C and hidden FC layers (Background,
+    layer C: tanh or logistic): probs, loss and all gradients of a two-patch batch equal the
+    textbook net with torch.sigmoid; and by hand, sigma(0) = 1/2 with derivative 1/4."""
+    for name in ("tiny18", "rgb_p3"):
+        layers, in_ch, P = NETS[name]
+        rng = np.random.default_rng(17)
+        params = rand_params(layers, in_ch, P, 19) * 2.0
+        img = rng.uniform(0, 1, (2, in_ch, P, P))
+        n_cls = layers[-1][1]
+        lab = rng.integers(0, n_cls, (2, P, P)).astype(np.int32)
+        r = oracle.run(layers, in_ch, P, params, img, lab, want_grads=True, want_dimage=True, squash="logistic")
+        pt = torch.tensor(params, dtype=torch.float64, requires_grad=True)
+        xt = torch.tensor(img, dtype=torch.float64, requires_grad=True)
+        z = torch_patch_net(layers, in_ch, P, pt, xt, squash=torch.sigmoid)
+        c = (P - 1) // 2
+        loss = F.cross_entropy(z, torch.tensor(lab[:, c, c].astype(np.int64)), reduction="sum")
+        loss.backward()
+        np.testing.assert_allclose(r["probs"].reshape(2, n_cls), torch.softmax(z, 1).detach().numpy(), rtol=1e-12, atol=1e-14)
+        assert abs(r["loss"] - loss.item()) <= 1e-12 * abs(loss.item())
+        np.testing.assert_allclose(r["grads"], pt.grad.numpy(), rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(r["dimage"], xt.grad.numpy(), rtol=1e-10, atol=1e-13)
+        # not the tanh net
+        r_t = oracle.run(layers, in_ch, P, params, img, lab, want_grads=True)
+        assert np.abs(r_t["grads"] - r["grads"]).max() > 1e-3
+    # by hand: one hidden unit h = sigma(w x + b) on a 1x1 patch, then a linear layer to 2 outputs with
+    # weights (1, 0), MSE against class 0: x = 2, w = b = 0 -> h = 1/2, outputs (1/2, 0), L = 1/8,
+    # x^ - t = (-1/2, 0), dL/dh = -1/2, through sigma' = h(1-h) = 1/4: dL/db = -1/8, dL/dw = -1/4
+    layers = ((FC, 1, 0), (FC, 2, 0))
+    params = np.array([0.0, 0.0, 1.0, 0.0, 0.0, 0.0])        # w, b | v0, v1, c0, c1
+    r = oracle.run(layers, 1, 1, params, np.array([[[[2.0]]]]), np.array([[[0]]], dtype=np.int32), want_grads=True,
+                   loss_fn="mse", squash="logistic")
+    np.testing.assert_allclose(r["probs"].ravel(), [0.5, 0.0], atol=1e-15)
+    assert abs(r["loss"] - 0.125) < 1e-15
+    np.testing.assert_allclose(r["grads"], [-0.25, -0.125, -0.25, 0.0, -0.5, 0.0], atol=1e-15)
 
 
 def test_lbfgs_direction_against_dense_bfgs_and_by_hand():
