@@ -120,6 +120,12 @@ mpcnn_status mpcnn_get_grads(const mpcnn_net* net, float* grads_host, size_t n);
 typedef enum { MPCNN_LOSS_MCCE = 0, MPCNN_LOSS_MSE = 1 } mpcnn_loss;
 mpcnn_status mpcnn_set_loss(mpcnn_net* net, mpcnn_loss kind);
 
+/* The squashing function of C and hidden FC layers (Background, layer C: "e.g. tanh or
+ * logistic").  TANH (default), or LOGISTIC: y = 1 / (1 + exp(-a)), derivative y (1 - y).
+ * Takes effect at the next forward / backward call.  EINVAL on an unknown kind. */
+typedef enum { MPCNN_TANH = 0, MPCNN_LOGISTIC = 1 } mpcnn_activation;
+mpcnn_status mpcnn_set_activation(mpcnn_net* net, mpcnn_activation kind);
+
 /* Per-class balanced pixel weights (Experiments, steel defects: the loss is minimised per
  * class because the data set is unbalanced):  pixw_dev[b][y][x] = 1 / N_k where the pixel is
  * the centre of a patch (an output pixel) with label k in [0, n_classes), N_k = number of

@@ -43,7 +43,7 @@ __global__ void stage_input_kernel(const float* __restrict__ src, T* __restrict_
 template <bool TANHP>
 __global__ void conv_dgrad_direct_kernel(const float* __restrict__ dY, const float* __restrict__ Wk,
                                          const float* __restrict__ A, float* __restrict__ dA, int B,
-                                         int Hi, int Wi, int Ci, int Ho, int Wo, int Co, int k, int d)
+                                         int Hi, int Wi, int Ci, int Ho, int Wo, int Co, int k, int d, int logistic)
 {
     long total = (long)B * Hi * Wi * Ci;
     for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
@@ -68,7 +68,7 @@ __global__ void conv_dgrad_direct_kernel(const float* __restrict__ dY, const flo
         }
         if (TANHP) {
             float a = A[e];
-            acc *= 1.f - a * a;
+            acc *= squash_slope(a, logistic);
         }
         dA[e] = acc;
     }
@@ -143,7 +143,7 @@ template <bool TANHP>
 __global__ void maxfilter_bwd_direct_kernel(const float* __restrict__ dO,
                                             const uint8_t* __restrict__ code,
                                             const float* __restrict__ A, float* __restrict__ dA,
-                                            int B, int Hi, int Wi, int C, int Ho, int Wo, int p, int d)
+                                            int B, int Hi, int Wi, int C, int Ho, int Wo, int p, int d, int logistic)
 {
     long total = (long)B * Hi * Wi * C;
     for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
@@ -167,7 +167,7 @@ __global__ void maxfilter_bwd_direct_kernel(const float* __restrict__ dO,
         }
         if (TANHP) {
             float a = A[e];
-            acc *= 1.f - a * a;
+            acc *= squash_slope(a, logistic);
         }
         dA[e] = acc;
     }

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void first_layer_kernel(const T* __restrict__ 
     for (int z = 0; z < 4; ++z) {
         const int o = o0 + z < Co ? o0 + z : Co - 1;
         const float s = acc[z] + (w_in_lds ? wl[(rows - 1) * CoP + o] : Wk[(long)(rows - 1) * Co + o]);
-        acc[z] = tanh_out ? fast_tanh(s) : s;
+        acc[z] = tanh_out ? squash(s, tanh_out == 2) : s;   // 0 linear, 1 tanh, 2 logistic
     }
     T* out = Y + m * Co + o0;
     if ((Co & 3) == 0) store4(out, acc);
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const T* __restrict
                                                              const T* __restrict__ A,
                                                              T* __restrict__ dA, RowGrid g,
                                                              int Hi, int Wi, int C, int Ho, int Wo,
-                                                             int p, int d)
+                                                             int p, int d, int logistic)
 {
     int b, y, x, c4;
     if (!rg_locate(g, Wi, &b, &y, &x, &c4)) return;
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const T* __restrict
     if (TANHP) {
         const v4f a = load4(A + e * 4);
 #pragma unroll
-        for (int z = 0; z < 4; ++z) acc[z] *= 1.f - a[z] * a[z];
+        for (int z = 0; z < 4; ++z) acc[z] *= squash_slope(a[z], logistic);
     }
     store4(dA + e * 4, acc);
 }
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
                         g = fmaf(w[v][s][o], dz[o], g);
                         gw[v][s][o] = fmaf(hv[v][s], dz[o], gw[v][s][o]);
                     }
-                    dh[s] = a.tanh_below ? g * (1.f - hv[v][s] * hv[v][s]) : g;
+                    dh[s] = a.tanh_below ? g * squash_slope(hv[v][s], a.tanh_below == 2) : g;   // 0 none, 1 tanh, 2 logistic
                 }
                 if (c < a.K && dh_t) store4(dh_t + m * a.K + c, dh);   // (no delta buffer: loss only)
             }

@@ -26,14 +26,6 @@
 
 namespace mpcnn {
 
-// tanh(x) = 1 - 2 / (exp(2x) + 1) with the hardware exp2 and reciprocal: absolute error
-// about 1e-7; saturates correctly (exp -> inf gives 1, exp -> 0 gives -1).
-__device__ __forceinline__ float fast_tanh(float x)
-{
-    const float e = __builtin_amdgcn_exp2f(2.885390081777927f * x);   // e^(2x) = 2^(2x log2 e)
-    return fmaf(-2.f, __builtin_amdgcn_rcpf(e + 1.f), 1.f);
-}
-
 enum ConvMode { kFwdTanh = 0, kFwdLinear = 1, kDgradTanh = 2, kDgradPlain = 3 };
 
 struct ConvArgs {
@@ -49,6 +41,7 @@ struct ConvArgs {
     int origin;          // halo origin in fragment units relative to the tile: 0 forward, -(k-1) dgrad
     int Ty, Tx, nty, ntx;
     int mode;
+    int logistic;        // squashing function of the Tanh modes: 0 tanh, 1 logistic
 };
 
 // Repack W[tap][c][o] (+ bias row) into the operand order of conv_mfma_kernel, G lane groups:
@@ -348,12 +341,12 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
             for (int w = 1; w < NW; ++w) s += part[it][w];   // fixed wave order
             if (a.mode == kFwdTanh) {
 #pragma unroll
-                for (int z = 0; z < 4; ++z) s[z] = fast_tanh(s[z] + bias4[it][z]);
+                for (int z = 0; z < 4; ++z) s[z] = squash(s[z] + bias4[it][z], a.logistic);
             } else if (a.mode == kFwdLinear) {
                 s += bias4[it];
             } else if (a.mode == kDgradTanh) {
 #pragma unroll
-                for (int z = 0; z < 4; ++z) s[z] *= 1.f - yv[it][z] * yv[it][z];
+                for (int z = 0; z < 4; ++z) s[z] *= squash_slope(yv[it][z], a.logistic);
             }
             if (nv == 4 && (a.Co & 3) == 0) store4(out_t + off, s);
             else for (int z = 0; z < nv; ++z) store1(out_t + off + z, s[z]);

@@ -152,6 +152,7 @@ struct mpcnn_net {
     float* d_params = nullptr;
     float* d_params0 = nullptr;   // copy of the parameters a safeguarded step starts from
     double* d_scalar = nullptr;   // fp64 results of that step's reductions (8)
+    int logistic = 0;             // squashing function of C and hidden FC layers: 0 tanh, 1 logistic
     // limited-memory BFGS: pairs in a ring of lb_m + 1 slots (one always free for the candidate)
     int lb_m = 0, lb_head = 0, lb_count = 0;
     bool lb_have_prev = false;
@@ -699,7 +700,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             a.partial = g.training ? (float*)(ws + g.partial_off[l]) : nullptr;   // loss only: no gradient shares
             a.loss_partial = want_loss ? lp : nullptr;
             a.B = B; a.Ho = Ho; a.Wo = Wo; a.H = g.H; a.W = g.W; a.ctr = (net->patch - 1) / 2;
-            a.K = Ci; a.tanh_below = (l > 0 && net->layers[l - 1].tanh_out) ? 1 : 0;
+            a.K = Ci; a.tanh_below = (l > 0 && net->layers[l - 1].tanh_out) ? 1 + net->logistic : 0;
             a.mse = net->loss_kind == MPCNN_LOSS_MSE;
             const int blocks = class_blocks(M);
             const bool train = labels != nullptr;
@@ -723,7 +724,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout; a.CoPad = ly.fwd_ct.pad;
                 a.k = ly.k; a.d = ly.dil; a.origin = 0;
                 a.Ty = tp.Ty; a.Tx = tp.Tx; a.nty = tp.nty; a.ntx = tp.ntx;
-                a.mode = ly.tanh_out ? kFwdTanh : kFwdLinear;
+                a.mode = ly.tanh_out ? kFwdTanh : kFwdLinear; a.logistic = net->logistic;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
                 LAUNCH("conv_fwd_mfma", l, step, flops, bytes,
                        launch_conv_mfma<T>(a, ly.fwd_ct, tp, grid, st, ly.fwd_bm));
@@ -734,7 +735,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 const int w_in_lds = wbytes <= 48 * 1024;
                 LAUNCH("first_layer", l, step, flops, bytes,
                        first_layer_kernel<T><<<(unsigned)((total + 255) / 256), 256, w_in_lds ? wbytes : 0, st>>>(
-                           in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil, ly.tanh_out ? 1 : 0,
+                           in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil, ly.tanh_out ? 1 + net->logistic : 0,
                            w_in_lds));
             }
         }
@@ -793,21 +794,21 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
             if (quads && below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        (maxfilter_bwd4_kernel<true, T><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
-                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil)));
+                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil, net->logistic)));
             else if (quads)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        (maxfilter_bwd4_kernel<false, T><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
-                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil)));
+                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil, net->logistic)));
             else if constexpr (!kF32)
                 return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             else if (below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        maxfilter_bwd_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
-                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
+                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil, net->logistic));
             else
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        maxfilter_bwd_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
-                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil));
+                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil, net->logistic));
         } else {
             const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k * Ci;
             const int wstep = (li == L - 1) ? 4 : 5, dstep = (li == L - 1) ? 4 : 6;
@@ -857,7 +858,7 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.Ho = Hi; a.Wo = Wi; a.Co = Ci; a.CoPad = ly.dgrad_ct.pad;
                 a.k = ly.k; a.d = ly.dil; a.origin = -(ly.k - 1);
                 a.Ty = tp.Ty; a.Tx = tp.Tx; a.nty = tp.nty; a.ntx = tp.ntx;
-                a.mode = below_tanh ? kDgradTanh : kDgradPlain;
+                a.mode = below_tanh ? kDgradTanh : kDgradPlain; a.logistic = net->logistic;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.dgrad_ct.split);
                 LAUNCH("conv_dgrad_mfma", li, dstep, flops, dbytes,
                        launch_conv_mfma<T>(a, ly.dgrad_ct, tp, grid, st, ly.dgrad_bm));
@@ -868,11 +869,11 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 if (below_tanh)
                     LAUNCH("conv_dgrad_direct", li, dstep, flops, dbytes,
                            conv_dgrad_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
-                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil));
+                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil, net->logistic));
                 else
                     LAUNCH("conv_dgrad_direct", li, dstep, flops, dbytes,
                            conv_dgrad_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
-                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil));
+                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil, net->logistic));
             }
         }
         cur ^= 1;
@@ -1124,6 +1125,14 @@ mpcnn_status mpcnn_set_loss(mpcnn_net* net, mpcnn_loss kind)
     if (!net) return fail(MPCNN_EINVAL, "null net");
     if (kind != MPCNN_LOSS_MCCE && kind != MPCNN_LOSS_MSE) return fail(MPCNN_EINVAL, "unknown loss %d", (int)kind);
     net->loss_kind = kind;
+    return MPCNN_OK;
+}
+
+mpcnn_status mpcnn_set_activation(mpcnn_net* net, mpcnn_activation kind)
+{
+    if (!net) return fail(MPCNN_EINVAL, "null net");
+    if (kind != MPCNN_TANH && kind != MPCNN_LOGISTIC) return fail(MPCNN_EINVAL, "unknown activation %d", (int)kind);
+    net->logistic = kind == MPCNN_LOGISTIC ? 1 : 0;
     return MPCNN_OK;
 }
 

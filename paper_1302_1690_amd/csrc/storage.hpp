@@ -28,4 +28,23 @@ __device__ __forceinline__ float load1(const bf16* p) { return (float)*p; }
 __device__ __forceinline__ void store1(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store1(bf16* p, float v) { *p = (bf16)v; }
 
+// tanh(x) = 1 - 2 / (exp(2x) + 1) with the hardware exp2 and reciprocal: absolute error
+// about 1e-7; saturates correctly (exp -> inf gives 1, exp -> 0 gives -1).
+__device__ __forceinline__ float fast_tanh(float x)
+{
+    const float e = __builtin_amdgcn_exp2f(2.885390081777927f * x);   // e^(2x) = 2^(2x log2 e)
+    return fmaf(-2.f, __builtin_amdgcn_rcpf(e + 1.f), 1.f);
+}
+
+// logistic function 1 / (1 + exp(-x)), same hardware functions (exp -> inf gives 0, exp -> 0 gives 1)
+__device__ __forceinline__ float fast_logistic(float x)
+{
+    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * x);
+    return __builtin_amdgcn_rcpf(e + 1.f);
+}
+// The squashing function of C and hidden FC layers (Background, layer C: tanh or logistic) and
+// its derivative written in terms of its output.
+__device__ __forceinline__ float squash(float x, int logistic) { return logistic ? fast_logistic(x) : fast_tanh(x); }
+__device__ __forceinline__ float squash_slope(float y, int logistic) { return logistic ? y * (1.f - y) : 1.f - y * y; }
+
 }  // namespace mpcnn

@@ -64,13 +64,14 @@ def check_grads(cfg, g_gpu, g_ref, tol=None):
     return worst
 
 
-def run_gpu(cfg, img, lab, params, pixw=None, net=None, loss_fn="mcce"):
+def run_gpu(cfg, img, lab, params, pixw=None, net=None, loss_fn="mcce", squash="tanh"):
     own = net is None
     if own:
         net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch,
                         dtype=mpcnn.BF16 if cfg.dtype == "bf16" else mpcnn.F32)
         net.set_params(params)
         net.set_loss(loss_fn)
+        net.set_activation(squash)
     B, _, H, W = img.shape
     d_img = torch.from_numpy(img).cuda()
     d_lab = torch.from_numpy(lab).cuda()
@@ -96,13 +97,13 @@ TIE_TAU_BF16 = 2.0 ** -7   # bf16 storage: two ulps at 1; values this close may 
 TOL_BF16 = 2e-2
 
 
-def oracle_run_valid_ties(cfg, params, img, lab, pixw, sel, net, loss_fn="mcce"):
+def oracle_run_valid_ties(cfg, params, img, lab, pixw, sel, net, loss_fn="mcce", squash="tanh"):
     """Oracle result to compare with.  Where the oracle's own two best candidates of a
     pooling window are within tau, the order may legitimately differ in the GPU's
     precision; the GPU's choice is adopted there if (the oracle checks this) that tap's
     value is within tau of the maximum, and the oracle re-evaluated."""
     kw = dict(labels=lab, pixw=None if pixw is None else pixw.astype(np.float64), sel=sel,
-              want_grads=True, tie_tau=tau_of(cfg), loss_fn=loss_fn)
+              want_grads=True, tie_tau=tau_of(cfg), loss_fn=loss_fn, squash=squash)
     args = (cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64), img.astype(np.float64))
     ref = oracle.run(*args, **kw)
     near = ref["near_ties"]
@@ -127,7 +128,7 @@ def oracle_run_valid_ties(cfg, params, img, lab, pixw, sel, net, loss_fn="mcce")
     return ref, len(near), len(alt)
 
 
-def check_argmax(cfg, net, img, params, with_oracle=True, layers=None):
+def check_argmax(cfg, net, img, params, with_oracle=True, layers=None, squash="tanh"):
     """(i) The stored tap codes equal a CPU scan, lowest tap first, over the GPU's own
     pre-pool values, bit for bit.  (ii) They equal the fp64 oracle's codes wherever
     the oracle's top-2 gap exceeds TIE_TAU (rounding can flip closer calls)."""
@@ -154,7 +155,7 @@ def check_argmax(cfg, net, img, params, with_oracle=True, layers=None):
         assert np.array_equal(post, ref_max), (cfg.name, li, "pooled values")
         if with_oracle:
             d = oracle.dense_layer(cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64),
-                                   img.astype(np.float64), li)
+                                   img.astype(np.float64), li, squash=squash)
             o_codes = d["codes"].transpose(0, 2, 3, 1)
             o_gap = d["gap"].transpose(0, 2, 3, 1)
             cov = d["covered"][..., None]
@@ -166,7 +167,8 @@ def check_argmax(cfg, net, img, params, with_oracle=True, layers=None):
     return excused
 
 
-def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_layers=True, loss_fn="mcce"):
+def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_layers=True, loss_fn="mcce",
+                squash="tanh"):
     img, lab = wl.make_inputs(cfg)
     params = wl.make_params(cfg)
     pixw = None
@@ -176,13 +178,13 @@ def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_lay
         lab = lab.copy()
         lab[np.random.default_rng(78).random(lab.shape) < 0.1] = -1
     say("case %s B=%d %dx%d" % (cfg.name, cfg.batch, cfg.height, cfg.width))
-    net, probs, loss, grads = run_gpu(cfg, img, lab, params, pixw, loss_fn=loss_fn)
-    ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, pixw, None, net, loss_fn)
+    net, probs, loss, grads = run_gpu(cfg, img, lab, params, pixw, loss_fn=loss_fn, squash=squash)
+    ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, pixw, None, net, loss_fn, squash)
     say("  near-tie windows %d, resolved the other way on the GPU %d" % (n_near, n_alt))
     e_p = np.abs(probs - ref["probs"]).max()
     assert e_p <= tol_of(cfg), (cfg.name, "probs", e_p)
     assert abs(loss - ref["loss"]) <= 0.1 * tol_of(cfg) * abs(ref["loss"]), (loss, ref["loss"])
-    excused = check_argmax(cfg, net, img, params) if check_layers else -1
+    excused = check_argmax(cfg, net, img, params, squash=squash) if check_layers else -1
     say("  argmax excused %d" % excused)
     if check_layers:
         B, _, H, W = img.shape
@@ -190,7 +192,7 @@ def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_lay
             if kind == MP:
                 continue
             d = oracle.dense_layer(cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64),
-                                   img.astype(np.float64), li)
+                                   img.astype(np.float64), li, squash=squash)
             a = net.get_activation(B, H, W, li).transpose(0, 3, 1, 2)
             cov = d["covered"][:, None]
             err = np.abs(a - d["act"])[np.broadcast_to(cov, a.shape)].max()
@@ -247,6 +249,16 @@ def test_pools_that_drop_trailing_rows():
     cfg = replace(wl.CONFIGS[0], name="floor_two_levels", layers=layers, patch=18, batch=1, height=47,
                   width=41, weight_amp=0.3)
     full_parity(cfg)
+
+
+def test_logistic_activation():
+    """The logistic function instead of tanh in every C and hidden FC layer: matrix-core kernels
+    (config 1's net), the direct kernels (tiny net), MSE on top, and bf16 storage."""
+    full_parity(wl.crop(wl.CONFIGS[0], 2, 31, 37), with_pixw=True, squash="logistic")
+    full_parity(wl.crop(wl.CONFIGS[1], 1, 70, 66), squash="logistic")
+    full_parity(wl.crop(wl.CONFIGS[0], 1, 29, 33), loss_fn="mse", squash="logistic")
+    full_parity(wl.Workload("bf16_small_logistic", _NET_BF16_SMALL, 14, 3, 3, 1, 33, 29, 0.25, "ellipses",
+                            dtype="bf16", seed_image=1106, seed_label=2106, seed_param=3106), squash="logistic")
 
 
 def test_class_layer_variants():
