@@ -373,6 +373,21 @@ def test_bf16_small_net_full_oracle():
     full_parity(cfg, with_pixw=True)
 
 
+def test_bf16_channel_counts_off_the_fast_path():
+    """bf16 storage with channel counts that are multiples of 4 but not of 8, and more than 32
+    output maps: the bf16 weight-gradient kernel's element-wise staging (inputs and deltas), the
+    fp32 matrix instructions on bf16 storage for the other two contractions; ragged batch."""
+    layers = ((C, 12, 3), (MP, 0, 2), (C, 36, 3), (MP, 0, 2), (FC, 40, 0), (FC, 3, 0))   # 14 -> 12 -> 6 -> 4 -> 2
+    cfg = wl.Workload("bf16_odd_channels", layers, 14, 3, 3, 2, 51, 38, 0.25, "ellipses", dtype="bf16",
+                      seed_image=1107, seed_label=2107, seed_param=3107)
+    full_parity(cfg, with_pixw=True)
+    # wider maps: two pairs of column tiles (72 output maps), 8-channel items on both sides
+    layers = ((C, 8, 3), (MP, 0, 2), (C, 72, 3), (MP, 0, 2), (FC, 24, 0), (FC, 3, 0))
+    cfg = wl.Workload("bf16_wide", layers, 14, 3, 3, 1, 45, 77, 0.2, "ellipses", dtype="bf16",
+                      seed_image=1108, seed_label=2108, seed_param=3108)
+    full_parity(cfg)
+
+
 def test_cfg4_net_crop_full_oracle_bf16():
     full_parity(wl.crop(wl.CONFIGS[4], 1, 100, 93), check_layers=False)
 
