@@ -72,6 +72,28 @@ def test_dense_shapes_with_dropped_rows():
     net.close()
 
 
+def test_fragment_counts_printed_in_the_paper():
+    """|F_out| = |F_in| k^2 (Method, MPF layer; tests/golden/paper_fragment_counts.txt): the
+    spacing the library plans after the pools, squared, is the number of fragments."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_fragment_counts.txt")
+    rows = [ln.strip() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    assert rows
+    for row in rows:
+        pools, want = row.split("|")
+        pools, want = [int(t) for t in pools.split()], int(want)
+        side = 1
+        for p in reversed(pools):              # backwards from a 1 x 1 output: C 2x2 then MPF p
+            side = side * p + 1
+        layers = []
+        for p in pools:
+            layers += [(C, 2, 2), (MP, 0, p)]
+        layers = tuple(layers + [(FC, 2, 0)])
+        net = mpcnn.Net(layers, 1, side)
+        assert net.layer_shape(side + 3, side + 2, 2 * len(pools) - 1)[3] ** 2 == want
+        net.close()
+
+
 def test_errors():
     with pytest.raises(mpcnn.MpcnnError) as e:
         mpcnn.Net(((C, 2, 3), (MP, 0, 2)), 1, 8)

@@ -12,6 +12,8 @@ none touches the HIP library.  What is pinned:
   * MPF bookkeeping (k^2 offsets, fragment sizes) and the whole-image
     equivalence that the fast path relies on, via dilated library ops.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -630,6 +632,62 @@ def test_lbfgs_step_rules_and_convergence():
         assert alpha > 0 and fv < r["loss"] and used == it
         hist.append(fv)
     assert hist[0] > hist[1] > hist[2]
+
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _golden_rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [ln.strip() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+def test_fragment_counts_printed_in_the_paper():
+    """|F_out| = |F_in| k^2 and the 4 fragments of the 2 x 2 illustration (Method, MPF layer;
+    tests/golden/paper_fragment_counts.txt): the spacing of the oracle's whole-image maps after
+    the pools, squared, is the number of fragments (tests/test_abi_host.py holds the library's
+    plan to the same file)."""
+    for row in _golden_rows("paper_fragment_counts.txt"):
+        pools, want = row.split("|")
+        pools, want = [int(t) for t in pools.split()], int(want)
+        layers, side = [], 1
+        for p in reversed(pools):              # build backwards from a 1 x 1 output: C 2x2 then MPF p
+            side = side * p + 1
+        patch = side
+        for p in pools:
+            layers += [(C, 2, 2), (MP, 0, p)]
+        layers += [(FC, 2, 0)]
+        layers = tuple(layers)
+        img = np.zeros((1, 1, patch + 3, patch + 2))
+        params = np.zeros(oracle.param_count(layers, 1, patch))
+        last_pool = 2 * len(pools) - 1
+        d = oracle.dense_layer(layers, 1, patch, params, img, last_pool)
+        assert d["stride"] ** 2 == want, (pools, d["stride"])
+
+
+def test_patches_per_image_printed_in_the_paper():
+    """With mirrored borders every pixel of the image gets its patch: the steel images, 550 x 240
+    down-sampled by 4, hold "roughly 8.2K patches" (Results; tests/golden/paper_patch_counts.txt)."""
+    for row in _golden_rows("paper_patch_counts.txt"):
+        h, w, down, window, want, tol = [int(t) for t in row.split("|")]
+        H, W = h // down, w // down
+        ext = oracle.mirror_pad(np.zeros((1, 1, H, W)), window)
+        patches = (ext.shape[2] - window + 1) * (ext.shape[3] - window + 1)
+        assert patches == H * W and abs(patches - want) <= tol, patches
+
+
+def test_oracle_values_on_file():
+    """The oracle still computes the values stored by tests/golden/make_oracle_values.py (its own,
+    written once: a guard against silent changes of its arithmetic, not a pin)."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("make_oracle_values", os.path.join(GOLDEN, "make_oracle_values.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = mod.values()
+    stored = dict((k, float(v)) for k, v in (r.split() for r in _golden_rows("oracle_values_tiny.txt")))
+    assert set(now) == set(stored)
+    for k, v in stored.items():
+        assert abs(now[k] - v) <= 1e-12 * max(1.0, abs(v)), (k, now[k], v)
 
 
 def test_mirror_pad_by_hand():
