@@ -186,6 +186,22 @@ mpcnn_status mpcnn_seg_backward(mpcnn_net* net, const float* image_dev, const in
                                 const float* pixw_dev, int B, int H, int W, float* probs_dev,
                                 double* loss_dev, void* ws_dev, size_t ws_bytes, void* hip_stream);
 
+/*
+ * The same pass with the image taken in bands of `band_rows` output rows (the last band may be
+ * shorter): an output pixel depends on its own patch only (Method: every pixel is the output of
+ * the net on the patch around it), so a band of r output rows needs r + P - 1 image rows and
+ * nothing else; gradients and loss are summed over the bands, in order.  For images whose
+ * activations do not fit in memory at once: the workspace is that of one band,
+ * mpcnn_workspace_bytes_banded(net, B, W, band_rows).  Arguments and results as
+ * mpcnn_seg_backward (probs_dev, if given, receives all H-P+1 rows); the test hooks afterwards
+ * see the last band only.  Errors as mpcnn_seg_backward; EINVAL for band_rows < 1.
+ */
+size_t mpcnn_workspace_bytes_banded(const mpcnn_net* net, int B, int W, int band_rows);
+mpcnn_status mpcnn_seg_backward_banded(mpcnn_net* net, const float* image_dev, const int32_t* labels_dev,
+                                       const float* pixw_dev, int B, int H, int W, int band_rows,
+                                       float* probs_dev, double* loss_dev, void* ws_dev, size_t ws_bytes,
+                                       void* hip_stream);
+
 /* Plain gradient step on every parameter: theta -= lr * grad_scale * g
  * (Results, "Membrane Segmentation": weights updated after every image). */
 mpcnn_status mpcnn_sgd_step(mpcnn_net* net, float lr, float grad_scale, void* hip_stream);

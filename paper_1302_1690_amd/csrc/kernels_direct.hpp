@@ -183,7 +183,7 @@ constexpr int kMaxClasses = 16;
 __global__ void softmax_ce_kernel(const float* __restrict__ Z, float* __restrict__ probs,
                                   const int32_t* __restrict__ labels, const float* __restrict__ pixw,
                                   float* __restrict__ dZ, double* __restrict__ loss_partial, int B,
-                                  int Ho, int Wo, int H, int W, int ctr, int n_cls, int mse)
+                                  int Ho, int Wo, int H, int W, int ctr, int n_cls, int mse, int probs_rows)
 {
     __shared__ double red[256];
     long total = (long)B * Ho * Wo;
@@ -218,7 +218,7 @@ __global__ void softmax_ce_kernel(const float* __restrict__ Z, float* __restrict
         float sq = 0.f;
         for (int o = 0; o < n_cls; ++o) {
             float p = mse ? z[o] + zmax : expf(z[o]) * inv;
-            if (probs) probs[(((long)b * n_cls + o) * Ho + i) * Wo + j] = p;
+            if (probs) probs[(((long)b * n_cls + o) * probs_rows + i) * Wo + j] = p;
             const float e = p - (o == t ? 1.f : 0.f);
             if (dZ) dZ[m * n_cls + o] = (t >= 0) ? w * e : 0.f;
             if (o == t) zt = z[o];

@@ -194,6 +194,7 @@ struct ClassArgs {
     float* partial;        // [blocks][(K+1)*NCLS]  (training) this block's share of dW, db
     double* loss_partial;  // [blocks] or null
     int B, Ho, Wo, H, W, ctr, K, tanh_below;
+    int probs_rows;        // rows of the probs array (Ho, or the whole image's when this call covers a band)
     int mse;               // linear outputs + half the squared error instead of softmax + cross-entropy
 };
 
@@ -268,7 +269,7 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
 #pragma unroll
         for (int o = 0; o < NCLS; ++o) {
             pr[o] *= inv;
-            if (a.probs && j == o) a.probs[(((long)b * NCLS + o) * a.Ho + iy) * a.Wo + jx] = pr[o];
+            if (a.probs && j == o) a.probs[(((long)b * NCLS + o) * a.probs_rows + iy) * a.Wo + jx] = pr[o];
         }
         if (TRAIN) {
             const long lp = ((long)b * a.H + (iy + a.ctr)) * a.W + (jx + a.ctr);

@@ -422,6 +422,7 @@ struct ReduceSeg {
 struct ReduceArgs {
     ReduceSeg seg[kMaxReduceSegs];
     int n_seg, total_blocks;
+    int accumulate;     // add to what `out` holds (the image comes in bands) instead of replacing it
 };
 
 __global__ __launch_bounds__(256) void reduce_all_kernel(ReduceArgs a)
@@ -446,7 +447,10 @@ __global__ __launch_bounds__(256) void reduce_all_kernel(ReduceArgs a)
             if ((int)threadIdx.x < w) tree[threadIdx.x] += tree[threadIdx.x + w];
             __syncthreads();
         }
-        if (threadIdx.x == 0) *reinterpret_cast<double*>(sg.out) = tree[0];
+        if (threadIdx.x == 0) {
+            double* o = reinterpret_cast<double*>(sg.out);
+            *o = a.accumulate ? *o + tree[0] : tree[0];
+        }
         return;
     }
     const int e = ((int)blockIdx.x - sg.block0) * 64 + col;
@@ -468,8 +472,10 @@ __global__ __launch_bounds__(256) void reduce_all_kernel(ReduceArgs a)
         }
         red[row][col][0] = s;
         __syncthreads();
-        if (row == 0 && e < sg.items)
-            sg.out[e] = (float)((red[0][col][0] + red[1][col][0]) + (red[2][col][0] + red[3][col][0]));
+        if (row == 0 && e < sg.items) {
+            const float r = (float)((red[0][col][0] + red[1][col][0]) + (red[2][col][0] + red[3][col][0]));
+            sg.out[e] = a.accumulate ? sg.out[e] + r : r;
+        }
         return;
     }
     double s[4] = {0.0, 0.0, 0.0, 0.0};
@@ -509,12 +515,18 @@ __global__ __launch_bounds__(256) void reduce_all_kernel(ReduceArgs a)
             if (oc < sg.Co)
 #pragma unroll
                 for (int z = 0; z < 4; ++z)
-                    if (row0 + z < rows_out) sg.out[(long)(row0 + z) * sg.Co + oc] = r[z];
+                    if (row0 + z < rows_out) {
+                        float* o = sg.out + (long)(row0 + z) * sg.Co + oc;
+                        *o = a.accumulate ? *o + r[z] : r[z];
+                    }
         } else {
             const int oc = 4 * (e - tile_items);
 #pragma unroll
             for (int z = 0; z < 4; ++z)
-                if (oc + z < sg.Co) sg.out[(long)sg.rows_total * sg.Co + oc + z] = r[z];
+                if (oc + z < sg.Co) {
+                    float* o = sg.out + (long)sg.rows_total * sg.Co + oc + z;
+                    *o = a.accumulate ? *o + r[z] : r[z];
+                }
         }
     }
 }

@@ -123,6 +123,8 @@ struct Geom {
     int pad_top = 0, pad_left = 0;    // same-size forward: H, W are the mirrored image's, which starts
     int src_h = 0, src_w = 0;         //   this far above / left of the caller's src_h x src_w image
     bool staged = false;              // the image is copied to channels-last storage first
+    int label_h = 0, probs_rows = 0;  // rows of the label / weight arrays and of the probs array (bands: the whole image's)
+    bool accumulate = false;          // gradients and loss are added to what the net holds (bands after the first)
     size_t staged_off = 0;            // that copy (C0 > 1, or bf16 storage)
     size_t delta_off[2] = {0, 0};     // two delta buffers, each as large as the largest map
     std::vector<size_t> partial_off;  // per parametrised layer: its slab / block partial sums
@@ -472,6 +474,7 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
     }
     g->loss_partial_off = off; off = align_up(off + sizeof(double) * kLossBlocks);
     g->total = off;
+    g->label_h = H; g->probs_rows = r; g->accumulate = false;
     return true;
 }
 
@@ -699,7 +702,8 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             a.labels = labels; a.pixw = pixw; a.dH = dZ;
             a.partial = g.training ? (float*)(ws + g.partial_off[l]) : nullptr;   // loss only: no gradient shares
             a.loss_partial = want_loss ? lp : nullptr;
-            a.B = B; a.Ho = Ho; a.Wo = Wo; a.H = g.H; a.W = g.W; a.ctr = (net->patch - 1) / 2;
+            a.B = B; a.Ho = Ho; a.Wo = Wo; a.H = g.label_h; a.W = g.W; a.ctr = (net->patch - 1) / 2;
+            a.probs_rows = g.probs_rows;
             a.K = Ci; a.tanh_below = (l > 0 && net->layers[l - 1].tanh_out) ? 1 + net->logistic : 0;
             a.mse = net->loss_kind == MPCNN_LOSS_MSE;
             const int blocks = class_blocks(M);
@@ -750,9 +754,9 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
         int blocks = (int)std::min<long>(kLossBlocks, (total + 255) / 256);
         LAUNCH("softmax_ce", L - 1, 3, 0, 4.0 * total * (3.0 * net->n_cls + 2.0),
                softmax_ce_kernel<<<blocks, 256, 0, st>>>(in, probs, labels, pixw, dZ,
-                                                         want_loss ? lp : nullptr, B, Hi, Wi, g.H, g.W,
+                                                         want_loss ? lp : nullptr, B, Hi, Wi, g.label_h, g.W,
                                                          (net->patch - 1) / 2, net->n_cls,
-                                                         net->loss_kind == MPCNN_LOSS_MSE));
+                                                         net->loss_kind == MPCNN_LOSS_MSE, g.probs_rows));
         if (want_loss) net->loss_shares = blocks;
     }
     HIP_TRY(hipGetLastError());
@@ -880,6 +884,7 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
     }
     // one launch adds the partial sums of every layer in a fixed order (Alg. 2)
     ReduceArgs ra{};
+    ra.accumulate = g.accumulate ? 1 : 0;
     double rbytes = 0;
     for (size_t l = 0; l < L; ++l) {
         if (!g.partial_n[l] || ra.n_seg >= kMaxReduceSegs) continue;
@@ -1261,6 +1266,62 @@ mpcnn_status mpcnn_seg_backward(mpcnn_net* net, const float* image_dev, const in
 }
 
 // forward + summed loss, nothing kept (the workspace is a forward-only one)
+// geometry of one band of output rows [row0, row0 + rows) of a B x H x W image
+static bool make_geom_band(const mpcnn_net* net, int B, int H, int W, int row0, int rows, Geom* g)
+{
+    if (!make_geom(net, B, rows + net->patch - 1, W, true, g, true)) return false;
+    g->pad_top = -row0; g->pad_left = 0; g->src_h = H; g->src_w = W;   // the band starts row0 rows down the image
+    g->label_h = H; g->probs_rows = H - net->patch + 1;
+    g->accumulate = row0 > 0;
+    return true;
+}
+
+size_t mpcnn_workspace_bytes_banded(const mpcnn_net* net, int B, int W, int band_rows)
+{
+    Geom g;
+    if (!net || band_rows < 1 || B < 1 || W < net->patch) return 0;
+    if (!make_geom_band(net, B, band_rows + net->patch - 1, W, 0, band_rows, &g)) return 0;
+    return g.total;
+}
+
+mpcnn_status mpcnn_seg_backward_banded(mpcnn_net* net, const float* image_dev, const int32_t* labels_dev,
+                                       const float* pixw_dev, int B, int H, int W, int band_rows,
+                                       float* probs_dev, double* loss_dev, void* ws_dev, size_t ws_bytes,
+                                       void* hip_stream)
+{
+    if (!net || !image_dev || !ws_dev || !labels_dev) return fail(MPCNN_EINVAL, "null argument");
+    if (!net->d_params) return fail(MPCNN_EINVAL, "parameters were never set");
+    if (B < 1 || band_rows < 1) return fail(MPCNN_EINVAL, "B = %d, band_rows = %d", B, band_rows);
+    if (H < net->patch || W < net->patch)
+        return fail(MPCNN_ESHAPE, "image %dx%d smaller than the %dx%d patch", H, W, net->patch, net->patch);
+    if (((uintptr_t)ws_dev & 255u) != 0) return fail(MPCNN_EINVAL, "workspace must be 256-byte aligned");
+    if (((uintptr_t)image_dev & 15u) != 0) return fail(MPCNN_EINVAL, "image must be 16-byte aligned");
+    const int Ho = H - net->patch + 1, Wo = W - net->patch + 1;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    char* ws = (char*)ws_dev;
+    for (int row0 = 0; row0 < Ho; row0 += band_rows) {
+        const int rows = std::min(band_rows, Ho - row0);
+        Geom g;
+        if (!make_geom_band(net, B, H, W, row0, rows, &g))
+            return fail(MPCNN_ESHAPE, "layer plan does not fit a band of %d rows", rows);
+        if (ws_bytes < g.total) return fail(MPCNN_EWORKSPACE, "workspace %zu bytes, need %zu", ws_bytes, g.total);
+        // the band's labels, weights and probabilities start row0 rows down their arrays
+        const int32_t* lab = labels_dev + (size_t)row0 * W;
+        const float* pw = pixw_dev ? pixw_dev + (size_t)row0 * W : nullptr;
+        float* pr = probs_dev ? probs_dev + (size_t)row0 * Wo : nullptr;
+        void* dZ = ws + g.delta_off[0];
+        mpcnn_status st =
+            net->bf16 ? run_forward<mpcnn::bf16>(net, g, image_dev, ws, lab, pw, pr, dZ, loss_dev, stream)
+                      : run_forward<float>(net, g, image_dev, ws, lab, pw, pr, dZ, loss_dev, stream);
+        net->last = g; net->last_ws = ws_dev;
+        if (st != MPCNN_OK) return st;
+        st = net->bf16 ? run_backward<mpcnn::bf16>(net, g, image_dev, ws, stream)
+                       : run_backward<float>(net, g, image_dev, ws, stream);
+        if (st != MPCNN_OK) return st;
+    }
+    return MPCNN_OK;
+}
+
 static mpcnn_status loss_only(mpcnn_net* net, const Geom& g, const float* image_dev, const int32_t* labels_dev,
                               const float* pixw_dev, double* loss_dev, char* ws, hipStream_t st)
 {

@@ -31,6 +31,7 @@ SYMBOLS = [
     "mpcnn_profile_enable", "mpcnn_profile_read", "mpcnn_workspace_bytes_same", "mpcnn_seg_forward_same",
     "mpcnn_set_loss", "mpcnn_class_balance_weights", "mpcnn_seg_loss", "mpcnn_armijo_step",
     "mpcnn_lbfgs_step", "mpcnn_lbfgs_reset", "mpcnn_set_activation",
+    "mpcnn_workspace_bytes_banded", "mpcnn_seg_backward_banded",
 ]
 
 
@@ -93,6 +94,9 @@ def lib():
                                        C.POINTER(i), C.POINTER(i)]
         L.mpcnn_lbfgs_reset.argtypes = [vp]
         L.mpcnn_set_loss.argtypes = [vp, i]
+        L.mpcnn_workspace_bytes_banded.argtypes = [vp, i, i, i]
+        L.mpcnn_workspace_bytes_banded.restype = sz
+        L.mpcnn_seg_backward_banded.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp, sz, vp]
         L.mpcnn_set_activation.argtypes = [vp, i]
         L.mpcnn_class_balance_weights.argtypes = [vp, vp, i, i, i, vp, vp, vp]
         L.mpcnn_seg_backward.argtypes = [vp, vp, vp, vp, i, i, i, vp, vp, vp, sz, vp]
@@ -245,6 +249,22 @@ class Net:
     def set_loss(self, kind: str):
         """"mcce": softmax + cross-entropy (default); "mse": linear outputs, half the squared error."""
         _check(lib().mpcnn_set_loss(self._h, {"mcce": 0, "mse": 1}.get(kind, -1)))
+
+    def seg_backward_banded(self, image, labels, band_rows, pixw=None, probs=None, loss=None, stream=None):
+        """Forward + backward with the image taken in bands of `band_rows` output rows; the
+        workspace (allocated here) is one band's.  Gradients stay in the net."""
+        import torch
+        B, _, H, W = image.shape
+        assert image.is_cuda and image.dtype == torch.float32 and image.is_contiguous()
+        assert labels.dtype == torch.int32 and labels.is_contiguous() and tuple(labels.shape) == (B, H, W)
+        n = lib().mpcnn_workspace_bytes_banded(self._h, B, W, band_rows)
+        if n == 0:
+            raise MpcnnError(2, "no plan for bands of %d rows" % band_rows)
+        ws = torch.empty(n, dtype=torch.uint8, device=image.device)
+        _check(lib().mpcnn_seg_backward_banded(self._h, _ptr(image), _ptr(labels), _ptr(pixw), B, H, W, band_rows,
+                                               _ptr(probs), _ptr(loss), _ptr(ws), ws.numel(),
+                                               _stream_handle(stream)))
+        return probs, loss
 
     def set_activation(self, kind: str):
         """"tanh" (default) or "logistic": the squashing function of C and hidden FC layers."""

@@ -261,6 +261,38 @@ def test_logistic_activation():
                             dtype="bf16", seed_image=1106, seed_label=2106, seed_param=3106), squash="logistic")
 
 
+def test_image_taken_in_bands():
+    """The pass with the image cut into bands of output rows (P-1 rows of halo each), gradients
+    and loss summed over the bands: same results as the oracle's, for band heights that do and do
+    not divide the output height, with pixel weights, for fp32 and bf16 storage."""
+    cases = ((wl.crop(wl.CONFIGS[0], 2, 45, 37), (7, 28, 100)),
+             (wl.crop(wl.CONFIGS[1], 1, 90, 75), (16,)),
+             (wl.Workload("bf16_small_bands", _NET_BF16_SMALL, 14, 3, 3, 2, 40, 44, 0.25, "ellipses", dtype="bf16",
+                          seed_image=1109, seed_label=2109, seed_param=3109), (10,)))
+    for cfg, bands in cases:
+        img, lab = wl.make_inputs(cfg)
+        params = wl.make_params(cfg)
+        pixw = np.random.default_rng(79).uniform(0.25, 2.0, lab.shape).astype(np.float32)
+        net, probs, loss, grads = run_gpu(cfg, img, lab, params, pixw)
+        ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, pixw, None, net)
+        check_grads(cfg, grads, ref["grads"])
+        d_img, d_lab, d_pw = torch.from_numpy(img).cuda(), torch.from_numpy(lab).cuda(), torch.from_numpy(pixw).cuda()
+        for band_rows in bands:
+            p_b = torch.full(probs.shape, -1.0, dtype=torch.float32, device="cuda")
+            l_b = torch.full((1,), 123.0, dtype=torch.float64, device="cuda")   # must be overwritten, not added to
+            net.seg_backward_banded(d_img, d_lab, band_rows, d_pw, p_b, l_b)
+            torch.cuda.synchronize()
+            say("case %s bands of %d rows (%d output rows)" % (cfg.name, band_rows, cfg.out_h))
+            # every position is computed with the same operations whatever the tiling: same bits
+            assert np.array_equal(p_b.cpu().numpy(), probs)
+            assert np.abs(p_b.cpu().numpy() - ref["probs"]).max() <= tol_of(cfg)
+            assert abs(float(l_b.item()) - ref["loss"]) <= 0.1 * tol_of(cfg) * abs(ref["loss"])
+            check_grads(cfg, net.get_grads(), ref["grads"])
+        with pytest.raises(mpcnn.MpcnnError):
+            net.seg_backward_banded(d_img, d_lab, 0)
+        net.close()
+
+
 def test_class_layer_variants():
     """Class layer shapes: 3 and 4 classes on 12 / 20 hidden units (fused kernel, ragged
     channel tail), 6 classes (generic path), hidden width above 128 (wide fused variant)."""
