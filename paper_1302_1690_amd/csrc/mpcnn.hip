@@ -23,6 +23,7 @@
 #include "kernels_wgrad.hpp"
 #include "kernels_wgrad_bf16.hpp"
 #include "kernels_lbfgs.hpp"
+#include "kernels_first_bf16.hpp"
 #include "kernels_fused.hpp"
 
 namespace {
@@ -557,6 +558,13 @@ void launch_wgrad_bm(const mpcnn::WgradArgs& a, int nch, dim3 grid, size_t lds, 
 #undef ROW
 #undef CASE
 }
+void launch_first_bm(const mpcnn::FirstBmArgs& a, unsigned wgs, hipStream_t st)
+{
+    const int nt = a.Co <= 32 ? 1 : 2;
+#define CASE(n, kk) if (nt == n && a.k == kk) { mpcnn::first_layer_bm_kernel<n, kk><<<wgs, 256, 0, st>>>(a); return; }
+    CASE(1, 3) CASE(1, 5) CASE(1, 7) CASE(2, 3) CASE(2, 5) CASE(2, 7)
+#undef CASE
+}
 // Kernels that may ask for more than 64 KiB of dynamic LDS must say so once.
 template <typename T>
 mpcnn_status set_lds_attrs_t()
@@ -732,6 +740,15 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
                 LAUNCH("conv_fwd_mfma", l, step, flops, bytes,
                        launch_conv_mfma<T>(a, ly.fwd_ct, tp, grid, st, ly.fwd_bm));
+            } else if (!kF32 && l == 0 && ly.dil == 1 && Ci <= 4 && ly.cout <= 64 && (ly.k == 3 || ly.k == 5 || ly.k == 7)) {
+                // bf16 storage, the image layer: short reduction on the bf16 matrix instruction
+                FirstBmArgs a{};
+                a.in = (const mpcnn::bf16*)in; a.Wk = Wk; a.out = (mpcnn::bf16*)out;
+                a.B = B; a.Hi = Hi; a.Wi = Wi; a.Ci = Ci; a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout; a.k = ly.k;
+                a.squash = ly.tanh_out ? 1 + net->logistic : 0;
+                a.nty = ceil_div(Ho, kFirstBmTy); a.ntx = ceil_div(Wo, kFirstBmTx);
+                const unsigned wgs = (unsigned)std::min<long>((long)B * a.nty * a.ntx, 4L * kNumCU);
+                LAUNCH("first_layer", l, step, flops, bytes, launch_first_bm(a, wgs, st));
             } else {
                 const int og = ceil_div(ly.cout, 4);
                 const long total = (long)B * Ho * Wo * og;
