@@ -120,9 +120,40 @@ __device__ __forceinline__ bool rg_locate(const RowGrid& g, int width, int* b, i
     return true;
 }
 
-// a2, four channels per thread (C % 4 == 0): O = max over the p*p taps d apart, code = tap of
-// the FIRST maximum in row-major (u,v) order (strict > while scanning), packed 4 codes / store.
-template <typename T>
+// Q quads of channels at consecutive addresses: one 128-bit access for 4 floats or 8 bf16
+template <int Q, typename T>
+__device__ __forceinline__ void load_quads(const T* p, v4f (&v)[Q])
+{
+    if constexpr (Q == 2 && sizeof(T) == 2) {
+        typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+        const bf16x8_t raw = *reinterpret_cast<const bf16x8_t*>(p);
+        v[0] = __builtin_convertvector(raw.lo, v4f);
+        v[1] = __builtin_convertvector(raw.hi, v4f);
+    } else {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) v[q] = load4(p + 4 * q);
+    }
+}
+template <int Q, typename T>
+__device__ __forceinline__ void store_quads(T* p, const v4f (&v)[Q])
+{
+    if constexpr (Q == 2 && sizeof(T) == 2) {
+        typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+        bf16x8_t raw;
+        raw.lo = __builtin_convertvector(v[0], bf16x4);
+        raw.hi = __builtin_convertvector(v[1], bf16x4);
+        *reinterpret_cast<bf16x8_t*>(p) = raw;
+    } else {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) store4(p + 4 * q, v[q]);
+    }
+}
+
+// a2, 4 Q channels per thread (C % 4Q == 0; Q = 2 with bf16 storage keeps the accesses 128 bits
+// wide - these kernels run at a fixed rate of elements, not of bytes): O = max over the p*p taps
+// d apart, code = tap of the FIRST maximum in row-major (u,v) order (strict > while scanning),
+// 4 packed codes per quad.  RowGrid.C4 counts the threads' channel groups.
+template <typename T, int Q>
 __global__ __launch_bounds__(256) void maxfilter_fwd4_kernel(const T* __restrict__ A,
                                                              T* __restrict__ O,
                                                              uint8_t* __restrict__ code, RowGrid g,
@@ -131,25 +162,39 @@ __global__ __launch_bounds__(256) void maxfilter_fwd4_kernel(const T* __restrict
 {
     int b, y, x, c4;
     if (!rg_locate(g, Wo, &b, &y, &x, &c4)) return;
-    const long e = (((long)b * Ho + y) * Wo + x) * g.C4 + c4;
-    const T* base = A + (((long)b * Hi + y) * Wi + x) * C + 4 * c4;
-    v4f best = load4(base);
-    uint32_t bi[4] = {0, 0, 0, 0};
+    const long e = ((((long)b * Ho + y) * Wo + x) * g.C4 + c4) * (4 * Q);
+    const T* base = A + (((long)b * Hi + y) * Wi + x) * C + 4 * Q * c4;
+    v4f best[Q];
+    load_quads<Q>(base, best);
+    uint32_t bi[Q][4];
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+#pragma unroll
+        for (int z = 0; z < 4; ++z) bi[q][z] = 0;
     for (int u = 0; u < p; ++u)
         for (int v = (u == 0 ? 1 : 0); v < p; ++v) {
-            const v4f a = load4(base + ((long)u * d * Wi + v * d) * C);
+            v4f a[Q];
+            load_quads<Q>(base + ((long)u * d * Wi + v * d) * C, a);
             const uint32_t t = u * p + v;
 #pragma unroll
-            for (int z = 0; z < 4; ++z)
-                if (a[z] > best[z]) { best[z] = a[z]; bi[z] = t; }
+            for (int q = 0; q < Q; ++q)
+#pragma unroll
+                for (int z = 0; z < 4; ++z)
+                    if (a[q][z] > best[q][z]) { best[q][z] = a[q][z]; bi[q][z] = t; }
         }
-    store4(O + e * 4, best);   // a value read back unchanged: exact in either storage type
-    if (code) *reinterpret_cast<uint32_t*>(code + e * 4) = bi[0] | (bi[1] << 8) | (bi[2] << 16) | (bi[3] << 24);
+    store_quads<Q>(O + e, best);   // a value read back unchanged: exact in either storage type
+    if (code) {
+        uint32_t packed[Q];
+#pragma unroll
+        for (int q = 0; q < Q; ++q) packed[q] = bi[q][0] | (bi[q][1] << 8) | (bi[q][2] << 16) | (bi[q][3] << 24);
+        if constexpr (Q == 2) *reinterpret_cast<uint2*>(code + e) = make_uint2(packed[0], packed[1]);
+        else *reinterpret_cast<uint32_t*>(code + e) = packed[0];
+    }
 }
 
-// a7, four channels per thread: dA = sum over the windows that chose this element (gather in
-// fixed (u,v) order, no atomics), times (1 - A^2) when A is a tanh output.
-template <bool TANHP, typename T>
+// a7, 4 Q channels per thread: dA = sum over the windows that chose this element (gather in
+// fixed (u,v) order, no atomics), times the squashing function's slope when A is its output.
+template <bool TANHP, typename T, int Q>
 __global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const T* __restrict__ dO,
                                                              const uint8_t* __restrict__ code,
                                                              const T* __restrict__ A,
@@ -159,29 +204,43 @@ __global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const T* __restrict
 {
     int b, y, x, c4;
     if (!rg_locate(g, Wi, &b, &y, &x, &c4)) return;
-    const long e = (((long)b * Hi + y) * Wi + x) * g.C4 + c4;
-    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    const long e = ((((long)b * Hi + y) * Wi + x) * g.C4 + c4) * (4 * Q);
+    v4f acc[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     for (int u = 0; u < p; ++u) {
         const int yy = y - u * d;
         if (yy < 0 || yy >= Ho) continue;
         for (int v = 0; v < p; ++v) {
             const int xx = x - v * d;
             if (xx < 0 || xx >= Wo) continue;
-            const long s = (((long)b * Ho + yy) * Wo + xx) * C + 4 * c4;
-            const uint32_t cd = *reinterpret_cast<const uint32_t*>(code + s);
-            const v4f gr = load4(dO + s);
+            const long s = (((long)b * Ho + yy) * Wo + xx) * C + 4 * Q * c4;
+            uint32_t cd[Q];
+            if constexpr (Q == 2) {
+                const uint2 c2 = *reinterpret_cast<const uint2*>(code + s);
+                cd[0] = c2.x; cd[1] = c2.y;
+            } else {
+                cd[0] = *reinterpret_cast<const uint32_t*>(code + s);
+            }
+            v4f gr[Q];
+            load_quads<Q>(dO + s, gr);
             const uint32_t t = u * p + v;
 #pragma unroll
-            for (int z = 0; z < 4; ++z)
-                if (((cd >> (8 * z)) & 255u) == t) acc[z] += gr[z];
+            for (int q = 0; q < Q; ++q)
+#pragma unroll
+                for (int z = 0; z < 4; ++z)
+                    if (((cd[q] >> (8 * z)) & 255u) == t) acc[q][z] += gr[q][z];
         }
     }
     if (TANHP) {
-        const v4f a = load4(A + e * 4);
+        v4f a[Q];
+        load_quads<Q>(A + e, a);
 #pragma unroll
-        for (int z = 0; z < 4; ++z) acc[z] *= squash_slope(a[z], logistic);
+        for (int q = 0; q < Q; ++q)
+#pragma unroll
+            for (int z = 0; z < 4; ++z) acc[q][z] *= squash_slope(a[q][z], logistic);
     }
-    store4(dA + e * 4, acc);
+    store_quads<Q>(dA + e, acc);
 }
 
 struct ClassArgs {
