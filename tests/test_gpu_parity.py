@@ -647,4 +647,24 @@ def test_error_paths_on_device():
     net.seg_backward(img, lab, ws=ws)               # and a good call still works afterwards
     torch.cuda.synchronize()
     assert np.isfinite(net.get_grads()).all()
+    # the optimiser steps and the banded pass check their arguments before they touch anything
+    before = net.get_params()
+    for bad in (dict(alpha0=0.0), dict(beta=1.0), dict(c=1.0), dict(max_trials=0)):
+        with pytest.raises(mpcnn.MpcnnError) as e:
+            net.armijo_step(img, lab, 1.0, **{"alpha0": 1.0, **bad})
+        assert e.value.status == 1
+        with pytest.raises(mpcnn.MpcnnError) as e:
+            net.lbfgs_step(img, lab, 1.0, **bad)
+        assert e.value.status == 1
+    for history in (0, 65):
+        with pytest.raises(mpcnn.MpcnnError) as e:
+            net.lbfgs_step(img, lab, 1.0, history=history)
+        assert e.value.status == 1
+    with pytest.raises(mpcnn.MpcnnError) as e:
+        net.seg_backward_banded(small, lab[:, :17].contiguous(), 4)
+    assert e.value.status == 2
+    with pytest.raises(mpcnn.MpcnnError) as e:
+        net.set_activation("relu")
+    assert e.value.status == 1
+    np.testing.assert_array_equal(net.get_params(), before)
     net.close()
