@@ -5,8 +5,9 @@ bench's cpu_baseline leg.  It imports nothing from the HIP package, and the HIP
 package imports nothing from here.
 
 Network description: a list of (kind, maps, k) integer triples, kind 0 = C
-(maps, kernel side), 1 = MP (k = pooling side), 2 = FC (maps); plus the number
-of input channels and the patch side P.  Parameters are one flat fp64 vector,
+(maps, kernel side), 1 = MP (k = pooling side; a fourth entry k2 > 0 makes the
+window k rows x k2 columns), 2 = FC (maps); plus the number of input channels
+and the patch side P.  Parameters are one flat fp64 vector,
 layer by layer W[o][c][u][v] then b[o] (Background, layer definitions).
 """
 from __future__ import annotations
@@ -42,11 +43,12 @@ def _load():
 
 
 def _desc(layers):
-    arr = np.asarray(layers, dtype=np.int32).reshape(-1, 3)
+    arr = np.asarray([tuple(l) + (0,) * (4 - len(l)) for l in layers], dtype=np.int32).reshape(-1, 4)
     kinds = np.ascontiguousarray(arr[:, 0])
     maps = np.ascontiguousarray(arr[:, 1])
     ks = np.ascontiguousarray(arr[:, 2])
-    return kinds, maps, ks, len(arr)
+    ks2 = np.ascontiguousarray(arr[:, 3])
+    return kinds, maps, (ks, ks2), len(arr)
 
 
 def _p(a, ct):
@@ -59,7 +61,7 @@ def threads() -> int:
 
 def param_count(layers, in_ch: int, patch: int) -> int:
     kinds, maps, ks, n = _desc(layers)
-    r = _load().orc_param_count(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n,
+    r = _load().orc_param_count(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks[0], C.c_int), _p(ks[1], C.c_int), n,
                                 in_ch, patch)
     if r < 0:
         raise ValueError("bad network description (code %d)" % r)
@@ -126,7 +128,7 @@ def run(layers, in_ch, patch, params, image, labels=None, pixw=None, sel=None,
         for out in (probs, grads, dimage):
             if out is not None:
                 out[...] = 0.0
-        rc = lib.orc_run(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch, patch,
+        rc = lib.orc_run(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks[0], C.c_int), _p(ks[1], C.c_int), n, in_ch, patch,
                          _p(params, C.c_double), _p(image, C.c_double), B, H, W,
                          _p(labels, C.c_int32), _p(pixw, C.c_double), _p(sel, C.c_int64),
                          C.c_long(n_sel), _p(probs, C.c_double),
@@ -273,9 +275,9 @@ def dense_shape(layers, in_ch, patch, B, H, W, layer):
     lib = _load()
     kinds, maps, ks, n = _desc(layers)
     ny, nx, ch, st = C.c_int(), C.c_int(), C.c_int(), C.c_int()
-    rc = lib.orc_dense_shape(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch,
+    rc = lib.orc_dense_shape(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks[0], C.c_int), _p(ks[1], C.c_int), n, in_ch,
                              patch, H, W, layer, C.byref(ny), C.byref(nx), C.byref(ch),
-                             C.byref(st))
+                             C.byref(st), None)
     if rc != 0:
         raise ValueError("orc_dense_shape failed (code %d)" % rc)
     return B, ch.value, ny.value, nx.value, st.value
@@ -284,16 +286,16 @@ def dense_shape(layers, in_ch, patch, B, H, W, layer):
 def dense_layer(layers, in_ch, patch, params, image, layer, squash="tanh"):
     """Outputs of layer `layer` of every patch laid over the image.  Returns
     dict(act [B,ch,ny,nx], codes, gap (MP layers, else None), covered [B,ny,nx],
-    stride)."""
+    stride (rows), stride_cols)."""
     lib = _load()
     kinds, maps, ks, n = _desc(layers)
     params = np.ascontiguousarray(params, dtype=np.float64)
     image = np.ascontiguousarray(image, dtype=np.float64)
     B, Cc, H, W = image.shape
-    ny, nx, ch, st = C.c_int(), C.c_int(), C.c_int(), C.c_int()
-    rc = lib.orc_dense_shape(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch,
+    ny, nx, ch, st, stc = C.c_int(), C.c_int(), C.c_int(), C.c_int(), C.c_int()
+    rc = lib.orc_dense_shape(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks[0], C.c_int), _p(ks[1], C.c_int), n, in_ch,
                              patch, H, W, layer, C.byref(ny), C.byref(nx), C.byref(ch),
-                             C.byref(st))
+                             C.byref(st), C.byref(stc))
     if rc != 0:
         raise ValueError("orc_dense_shape failed (code %d)" % rc)
     shape = (B, ch.value, ny.value, nx.value)
@@ -302,11 +304,11 @@ def dense_layer(layers, in_ch, patch, params, image, layer, squash="tanh"):
     codes = np.zeros(shape, dtype=np.uint8) if is_mp else None
     gap = np.zeros(shape) if is_mp else None
     covered = np.zeros((B, ny.value, nx.value), dtype=np.uint8)
-    rc = lib.orc_dense_layer(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks, C.c_int), n, in_ch,
+    rc = lib.orc_dense_layer(_p(kinds, C.c_int), _p(maps, C.c_int), _p(ks[0], C.c_int), _p(ks[1], C.c_int), n, in_ch,
                              patch, _p(params, C.c_double), _p(image, C.c_double), B, H, W,
                              layer, _p(act, C.c_double), _p(codes, C.c_uint8),
                              _p(gap, C.c_double), _p(covered, C.c_uint8), {"tanh": 0, "logistic": 1}[squash])
     if rc != 0:
         raise ValueError("orc_dense_layer failed (code %d)" % rc)
     return {"act": act, "codes": codes, "gap": gap, "covered": covered.astype(bool),
-            "stride": st.value}
+            "stride": st.value, "stride_cols": stc.value}

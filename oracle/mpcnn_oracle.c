@@ -12,9 +12,11 @@
  * Layer definitions (Background, layers C / MP / FC):
  *   C   y[o][r][s] = tanh(b[o] + sum_{c,u,v} W[o][c][u][v] * x[c][r+u][s+v])
  *       valid, stride 1, no kernel flip, every input map feeds every output map
- *   MP  y[c][r][s] = max_{u,v<p} x[c][p*r+u][p*s+v], non-overlapping windows,
+ *   MP  y[c][r][s] = max_{u<p_row, v<p_col} x[c][p_row*r+u][p_col*s+v], non-overlapping
+ *       p_row x p_col windows (square unless the description says otherwise),
  *       trailing rows/columns that do not fill a window are dropped; the
- *       recorded argmax is the FIRST maximum met in (u,v) row-major order
+ *       recorded argmax is the FIRST maximum met in (u,v) row-major order,
+ *       coded u*p_col + v
  *   FC  the first FC sees the remaining maps flattened [c][r][s] row-major,
  *       i.e. it is a C layer whose kernel covers the whole map; later FCs are
  *       matrix * vector.  Hidden FCs apply tanh; the last FC feeds a softmax.
@@ -49,11 +51,13 @@ enum { ORC_ACT_TANH = 0, ORC_ACT_LOGISTIC = 1 };
 
 typedef struct {
     int n_layers, in_ch, patch, n_classes;
-    int kind[ORC_MAXL], k[ORC_MAXL];          /* k: kernel side (C, FC) or p (MP) */
+    int kind[ORC_MAXL];
+    int kr[ORC_MAXL], kc[ORC_MAXL];           /* kernel rows x columns (C: k x k, first FC: the map) or p_row x p_col (MP) */
     int ch_in[ORC_MAXL], ch_out[ORC_MAXL];
-    int side_in[ORC_MAXL], side_out[ORC_MAXL];
-    int stride_out[ORC_MAXL];                 /* image pixels between neighbours of layer l's output */
-    int reach_out[ORC_MAXL];                  /* (side_out-1)*stride_out .. used for dense maps */
+    int rows_in[ORC_MAXL], cols_in[ORC_MAXL]; /* maps are square until a rectangular pool */
+    int rows_out[ORC_MAXL], cols_out[ORC_MAXL];
+    int stride_r[ORC_MAXL], stride_c[ORC_MAXL]; /* image pixels between neighbours of layer l's output */
+    int reach_r[ORC_MAXL], reach_c[ORC_MAXL];   /* (rows_out-1)*stride_r, (cols_out-1)*stride_c: for dense maps */
     int tanh_after[ORC_MAXL];
     long w_off[ORC_MAXL], b_off[ORC_MAXL];
     long act_off[ORC_MAXL + 1];               /* act 0 = the patch itself, act l+1 = output of layer l */
@@ -65,40 +69,45 @@ typedef struct {
 
 /* Shape inference.  Returns 0, or a negative code naming the first problem. */
 static int orc_make_plan(orc_plan *pl, const int *kinds, const int *maps, const int *ks,
-                         int n_layers, int in_ch, int patch)
+                         const int *ks2, int n_layers, int in_ch, int patch)
 {
     if (n_layers < 1 || n_layers > ORC_MAXL || in_ch < 1 || patch < 1) return -1;
     memset(pl, 0, sizeof *pl);
     pl->n_layers = n_layers; pl->in_ch = in_ch; pl->patch = patch;
-    int side = patch, ch = in_ch, stride = 1, seen_fc = 0;
+    int rows = patch, cols = patch, ch = in_ch, sr = 1, sc = 1, seen_fc = 0;
     long act = (long)in_ch * patch * patch, idx = 0, par = 0;
     pl->act_off[0] = 0;
     for (int l = 0; l < n_layers; ++l) {
-        pl->kind[l] = kinds[l]; pl->ch_in[l] = ch; pl->side_in[l] = side;
+        pl->kind[l] = kinds[l]; pl->ch_in[l] = ch; pl->rows_in[l] = rows; pl->cols_in[l] = cols;
         if (kinds[l] == ORC_C) {
-            if (seen_fc || ks[l] < 1 || maps[l] < 1 || side - ks[l] + 1 < 1) return -2;
-            pl->k[l] = ks[l]; pl->ch_out[l] = maps[l]; pl->side_out[l] = side - ks[l] + 1;
+            if (seen_fc || ks[l] < 1 || maps[l] < 1 || rows - ks[l] + 1 < 1 || cols - ks[l] + 1 < 1) return -2;
+            pl->kr[l] = pl->kc[l] = ks[l]; pl->ch_out[l] = maps[l];
+            pl->rows_out[l] = rows - ks[l] + 1; pl->cols_out[l] = cols - ks[l] + 1;
             pl->tanh_after[l] = 1;
         } else if (kinds[l] == ORC_MP) {
-            if (seen_fc || ks[l] < 1 || side / ks[l] < 1) return -3;
-            pl->k[l] = ks[l]; pl->ch_out[l] = ch; pl->side_out[l] = side / ks[l];
-            stride *= ks[l];
+            /* p_row x p_col sub-regions (Background, layer MP); ks2 = 0 or absent: square */
+            const int pr = ks[l], pc = (ks2 && ks2[l] > 0) ? ks2[l] : ks[l];
+            if (seen_fc || pr < 1 || pc < 1 || rows / pr < 1 || cols / pc < 1 || pr * pc > 255) return -3;
+            pl->kr[l] = pr; pl->kc[l] = pc; pl->ch_out[l] = ch;
+            pl->rows_out[l] = rows / pr; pl->cols_out[l] = cols / pc;
+            sr *= pr; sc *= pc;
         } else if (kinds[l] == ORC_FC) {
             if (maps[l] < 1) return -4;
-            pl->k[l] = seen_fc ? 1 : side; pl->ch_out[l] = maps[l]; pl->side_out[l] = 1;
+            pl->kr[l] = seen_fc ? 1 : rows; pl->kc[l] = seen_fc ? 1 : cols;
+            pl->ch_out[l] = maps[l]; pl->rows_out[l] = pl->cols_out[l] = 1;
             pl->tanh_after[l] = (l != n_layers - 1);
             seen_fc = 1;
         } else return -5;
-        pl->stride_out[l] = stride;
+        pl->stride_r[l] = sr; pl->stride_c[l] = sc;
         if (kinds[l] != ORC_MP) {
-            pl->w_off[l] = par; par += (long)pl->ch_out[l] * ch * pl->k[l] * pl->k[l];
+            pl->w_off[l] = par; par += (long)pl->ch_out[l] * ch * pl->kr[l] * pl->kc[l];
             pl->b_off[l] = par; par += pl->ch_out[l];
         } else {
-            pl->idx_off[l] = idx; idx += (long)pl->ch_out[l] * pl->side_out[l] * pl->side_out[l];
+            pl->idx_off[l] = idx; idx += (long)pl->ch_out[l] * pl->rows_out[l] * pl->cols_out[l];
         }
-        side = pl->side_out[l]; ch = pl->ch_out[l];
-        pl->reach_out[l] = (side - 1) * stride;
-        pl->act_off[l + 1] = act; act += (long)ch * side * side;
+        rows = pl->rows_out[l]; cols = pl->cols_out[l]; ch = pl->ch_out[l];
+        pl->reach_r[l] = (rows - 1) * sr; pl->reach_c[l] = (cols - 1) * sc;
+        pl->act_off[l + 1] = act; act += (long)ch * rows * cols;
     }
     if (kinds[n_layers - 1] != ORC_FC) return -6;
     pl->n_classes = ch; pl->act_total = act; pl->idx_total = idx; pl->n_params = par;
@@ -151,28 +160,29 @@ static void orc_patch_forward(const orc_plan *pl, const double *par, double *act
     for (int l = 0; l < pl->n_layers; ++l) {
         const double *x = act + pl->act_off[l];
         double *y = act + pl->act_off[l + 1];
-        const int n = pl->side_in[l], m = pl->side_out[l], k = pl->k[l];
+        const int nr = pl->rows_in[l], nc = pl->cols_in[l], mr = pl->rows_out[l], mc = pl->cols_out[l];
+        const int kr = pl->kr[l], kc = pl->kc[l];
         const int ci = pl->ch_in[l], co = pl->ch_out[l];
         if (pl->kind[l] == ORC_MP) {
             for (int c = 0; c < co; ++c)
-                for (int r = 0; r < m; ++r)
-                    for (int s = 0; s < m; ++s) {
+                for (int r = 0; r < mr; ++r)
+                    for (int s = 0; s < mc; ++s) {
                         double best = 0, second = 0; int code = -1, code2 = -1;
-                        for (int u = 0; u < k; ++u)
-                            for (int v = 0; v < k; ++v) {
-                                double a = x[((long)c * n + (k * r + u)) * n + (k * s + v)];
+                        for (int u = 0; u < kr; ++u)
+                            for (int v = 0; v < kc; ++v) {
+                                double a = x[((long)c * nr + (kr * r + u)) * nc + (kc * s + v)];
                                 if (code < 0) { best = a; code = 0; second = -INFINITY; }
-                                else if (a > best) { second = best; code2 = code; best = a; code = u * k + v; }
-                                else if (a > second) { second = a; code2 = u * k + v; }
+                                else if (a > best) { second = best; code2 = code; best = a; code = u * kc + v; }
+                                else if (a > second) { second = a; code2 = u * kc + v; }
                             }
-                        long e = ((long)c * m + r) * m + s;
+                        long e = ((long)c * mr + r) * mc + s;
                         y[e] = best;
                         if (ties && code2 >= 0 && (best - second <= ties->tau || ties->n_alt > 0)) {
-                            const int st = pl->stride_out[l];
-                            const long ny = ties->H - pl->patch + pl->reach_out[l] + 1;
-                            const long nx = ties->W - pl->patch + pl->reach_out[l] + 1;
+                            const int str = pl->stride_r[l], stc = pl->stride_c[l];
+                            const long ny = ties->H - pl->patch + pl->reach_r[l] + 1;
+                            const long nx = ties->W - pl->patch + pl->reach_c[l] + 1;
                             int64_t key = ((int64_t)l << 48) +
-                                          (((int64_t)pb * co + c) * ny + (pi + r * st)) * nx + (pj + s * st);
+                                          (((int64_t)pb * co + c) * ny + (pi + r * str)) * nx + (pj + s * stc);
                             if (ties->amb && best - second <= ties->tau) {
 #pragma omp critical(orc_amb)
                                 {
@@ -186,9 +196,9 @@ static void orc_patch_forward(const orc_plan *pl, const double *par, double *act
                             const long at = ties->n_alt > 0 ? orc_key_listed(ties, key) : -1;
                             if (at >= 0) {
                                 const int tap = ties->alt_tap[at];
-                                const int tu = tap / k, tv = tap % k;
-                                if (tap < k * k &&
-                                    best - x[((long)c * n + (k * r + tu)) * n + (k * s + tv)] <= ties->tau)
+                                const int tu = tap / kc, tv = tap % kc;
+                                if (tap < kr * kc &&
+                                    best - x[((long)c * nr + (kr * r + tu)) * nc + (kc * s + tv)] <= ties->tau)
                                     code = tap;
                                 else {
 #pragma omp atomic
@@ -197,20 +207,20 @@ static void orc_patch_forward(const orc_plan *pl, const double *par, double *act
                             }
                         }
                         idx[pl->idx_off[l] + e] = (uint8_t)code;
-                        if (gap) gap[pl->idx_off[l] + e] = (k * k > 1) ? best - second : INFINITY;
+                        if (gap) gap[pl->idx_off[l] + e] = (kr * kc > 1) ? best - second : INFINITY;
                     }
         } else {
             const double *W = par + pl->w_off[l], *b = par + pl->b_off[l];
             for (int o = 0; o < co; ++o)
-                for (int r = 0; r < m; ++r)
-                    for (int s = 0; s < m; ++s) {
+                for (int r = 0; r < mr; ++r)
+                    for (int s = 0; s < mc; ++s) {
                         double acc = b[o];
                         for (int c = 0; c < ci; ++c)
-                            for (int u = 0; u < k; ++u)
-                                for (int v = 0; v < k; ++v)
-                                    acc += W[(((long)o * ci + c) * k + u) * k + v] *
-                                           x[((long)c * n + (r + u)) * n + (s + v)];
-                        y[((long)o * m + r) * m + s] = !pl->tanh_after[l] ? acc
+                            for (int u = 0; u < kr; ++u)
+                                for (int v = 0; v < kc; ++v)
+                                    acc += W[(((long)o * ci + c) * kr + u) * kc + v] *
+                                           x[((long)c * nr + (r + u)) * nc + (s + v)];
+                        y[((long)o * mr + r) * mc + s] = !pl->tanh_after[l] ? acc
                             : pl->act_kind == ORC_ACT_LOGISTIC ? 1.0 / (1.0 + exp(-acc)) : tanh(acc);
                     }
         }
@@ -240,36 +250,37 @@ static void orc_patch_backward(const orc_plan *pl, const double *par, const doub
         const double *y = act + pl->act_off[l + 1];
         double *dy = dlt + pl->act_off[l + 1];
         double *dx = dlt + pl->act_off[l];
-        const int n = pl->side_in[l], m = pl->side_out[l], k = pl->k[l];
+        const int nr = pl->rows_in[l], nc = pl->cols_in[l], mr = pl->rows_out[l], mc = pl->cols_out[l];
+        const int kr = pl->kr[l], kc = pl->kc[l];
         const int ci = pl->ch_in[l], co = pl->ch_out[l];
         const int need_dx = (l > 0) || want_dx;
-        if (need_dx) memset(dx, 0, sizeof(double) * (size_t)ci * n * n);
+        if (need_dx) memset(dx, 0, sizeof(double) * (size_t)ci * nr * nc);
         if (pl->kind[l] == ORC_MP) {
             if (!need_dx) continue;
             for (int c = 0; c < co; ++c)
-                for (int r = 0; r < m; ++r)
-                    for (int s = 0; s < m; ++s) {
-                        long e = ((long)c * m + r) * m + s;
+                for (int r = 0; r < mr; ++r)
+                    for (int s = 0; s < mc; ++s) {
+                        long e = ((long)c * mr + r) * mc + s;
                         int code = idx[pl->idx_off[l] + e];
-                        int u = code / k, v = code % k;
-                        dx[((long)c * n + (k * r + u)) * n + (k * s + v)] += dy[e];
+                        int u = code / kc, v = code % kc;
+                        dx[((long)c * nr + (kr * r + u)) * nc + (kc * s + v)] += dy[e];
                     }
         } else {
             const double *W = par + pl->w_off[l];
             double *gW = g + pl->w_off[l], *gb = g + pl->b_off[l];
             for (int o = 0; o < co; ++o)
-                for (int r = 0; r < m; ++r)
-                    for (int s = 0; s < m; ++s) {
-                        long e = ((long)o * m + r) * m + s;
+                for (int r = 0; r < mr; ++r)
+                    for (int s = 0; s < mc; ++s) {
+                        long e = ((long)o * mr + r) * mc + s;
                         double d = dy[e];
                         if (pl->tanh_after[l])   /* derivative of the squashing function, from its output */
                             d *= pl->act_kind == ORC_ACT_LOGISTIC ? y[e] * (1.0 - y[e]) : 1.0 - y[e] * y[e];
                         gb[o] += d;
                         for (int c = 0; c < ci; ++c)
-                            for (int u = 0; u < k; ++u)
-                                for (int v = 0; v < k; ++v) {
-                                    long wi = (((long)o * ci + c) * k + u) * k + v;
-                                    long xi = ((long)c * n + (r + u)) * n + (s + v);
+                            for (int u = 0; u < kr; ++u)
+                                for (int v = 0; v < kc; ++v) {
+                                    long wi = (((long)o * ci + c) * kr + u) * kc + v;
+                                    long xi = ((long)c * nr + (r + u)) * nc + (s + v);
                                     gW[wi] += d * x[xi];
                                     if (need_dx) dx[xi] += W[wi] * d;
                                 }
@@ -290,11 +301,11 @@ static void orc_crop(const orc_plan *pl, const double *image, int H, int W, int 
 
 /* ------------------------------------------------------------------ C ABI */
 
-long orc_param_count(const int *kinds, const int *maps, const int *ks, int n_layers, int in_ch,
-                     int patch)
+long orc_param_count(const int *kinds, const int *maps, const int *ks, const int *ks2, int n_layers,
+                     int in_ch, int patch)
 {
     orc_plan pl;
-    int rc = orc_make_plan(&pl, kinds, maps, ks, n_layers, in_ch, patch);
+    int rc = orc_make_plan(&pl, kinds, maps, ks, ks2, n_layers, in_ch, patch);
     return rc < 0 ? rc : pl.n_params;
 }
 
@@ -326,7 +337,7 @@ int orc_threads(void)
  *   loss_kind  ORC_LOSS_MCCE: probs = softmax; ORC_LOSS_MSE: probs = the linear outputs.
  *   (the delta at the outputs is w * (probs - onehot) in both cases)
  */
-int orc_run(const int *kinds, const int *maps, const int *ks, int n_layers, int in_ch, int patch,
+int orc_run(const int *kinds, const int *maps, const int *ks, const int *ks2, int n_layers, int in_ch, int patch,
             const double *params, const double *image, int B, int H, int W,
             const int32_t *labels, const double *pixw, const int64_t *sel, long n_sel,
             double *probs, double *loss, double *grads, double *dimage,
@@ -334,7 +345,7 @@ int orc_run(const int *kinds, const int *maps, const int *ks, int n_layers, int 
             int64_t *amb, long amb_cap, long *amb_n, long *rejected, int loss_kind, int act_kind)
 {
     orc_plan pl;
-    int rc = orc_make_plan(&pl, kinds, maps, ks, n_layers, in_ch, patch);
+    int rc = orc_make_plan(&pl, kinds, maps, ks, ks2, n_layers, in_ch, patch);
     if (rc < 0) return rc;
     if (loss_kind != ORC_LOSS_MCCE && loss_kind != ORC_LOSS_MSE) return -12;
     if (act_kind != ORC_ACT_TANH && act_kind != ORC_ACT_LOGISTIC) return -13;
@@ -432,16 +443,17 @@ int orc_run(const int *kinds, const int *maps, const int *ks, int n_layers, int 
 /* Side of the whole-image ("dense") map that layer `layer`'s outputs form when
  * all patches are laid over the image: element (r,s) of patch (i,j) sits at
  * (i + r*stride, j + s*stride).  Returns rows in *ny, columns in *nx. */
-int orc_dense_shape(const int *kinds, const int *maps, const int *ks, int n_layers, int in_ch,
-                    int patch, int H, int W, int layer, int *ny, int *nx, int *ch, int *stride)
+int orc_dense_shape(const int *kinds, const int *maps, const int *ks, const int *ks2, int n_layers, int in_ch,
+                    int patch, int H, int W, int layer, int *ny, int *nx, int *ch, int *stride, int *stride_cols)
 {
     orc_plan pl;
-    int rc = orc_make_plan(&pl, kinds, maps, ks, n_layers, in_ch, patch);
+    int rc = orc_make_plan(&pl, kinds, maps, ks, ks2, n_layers, in_ch, patch);
     if (rc < 0) return rc;
     if (layer < 0 || layer >= n_layers || H < patch || W < patch) return -10;
-    *ny = (H - patch) + pl.reach_out[layer] + 1;
-    *nx = (W - patch) + pl.reach_out[layer] + 1;
-    *ch = pl.ch_out[layer]; *stride = pl.stride_out[layer];
+    *ny = (H - patch) + pl.reach_r[layer] + 1;
+    *nx = (W - patch) + pl.reach_c[layer] + 1;
+    *ch = pl.ch_out[layer]; *stride = pl.stride_r[layer];
+    if (stride_cols) *stride_cols = pl.stride_c[layer];
     return 0;
 }
 
@@ -456,19 +468,20 @@ int orc_dense_shape(const int *kinds, const int *maps, const int *ks, int n_laye
  *   gap     same shape, MP layers only: top-1 minus top-2 of the window (may be NULL)
  *   covered same shape as one channel [B][ny][nx]: 1 where some patch reaches
  */
-int orc_dense_layer(const int *kinds, const int *maps, const int *ks, int n_layers, int in_ch,
+int orc_dense_layer(const int *kinds, const int *maps, const int *ks, const int *ks2, int n_layers, int in_ch,
                     int patch, const double *params, const double *image, int B, int H, int W,
                     int layer, double *act_out, uint8_t *codes, double *gap, uint8_t *covered, int act_kind)
 {
     orc_plan pl;
-    int rc = orc_make_plan(&pl, kinds, maps, ks, n_layers, in_ch, patch);
+    int rc = orc_make_plan(&pl, kinds, maps, ks, ks2, n_layers, in_ch, patch);
     if (rc < 0) return rc;
     if (act_kind != ORC_ACT_TANH && act_kind != ORC_ACT_LOGISTIC) return -13;
     pl.act_kind = act_kind;
     if (layer < 0 || layer >= n_layers || H < patch || W < patch) return -10;
     const int P = patch, Ho = H - P + 1, Wo = W - P + 1;
-    const int st = pl.stride_out[layer], m = pl.side_out[layer], ch = pl.ch_out[layer];
-    const int ny = Ho - 1 + pl.reach_out[layer] + 1, nx = Wo - 1 + pl.reach_out[layer] + 1;
+    const int str = pl.stride_r[layer], stc = pl.stride_c[layer];
+    const int mr = pl.rows_out[layer], mc = pl.cols_out[layer], ch = pl.ch_out[layer];
+    const int ny = Ho - 1 + pl.reach_r[layer] + 1, nx = Wo - 1 + pl.reach_c[layer] + 1;
     const int is_mp = pl.kind[layer] == ORC_MP;
     if (covered) memset(covered, 0, (size_t)B * ny * nx);
     int fail = 0;
@@ -489,13 +502,13 @@ int orc_dense_layer(const int *kinds, const int *maps, const int *ks, int n_laye
                 orc_crop(&pl, image, H, W, b, i, j, act);
                 orc_patch_forward(&pl, params, act, idx, gp, pr, NULL, b, i, j);
                 const double *y = act + pl.act_off[layer + 1];
-                for (int r = 0; r < m; ++r) {
-                    if (!(r == m - 1 || i < st)) continue;
-                    for (int s = 0; s < m; ++s) {
-                        if (!(s == m - 1 || j < st)) continue;
-                        int yy = i + r * st, xx = j + s * st;
+                for (int r = 0; r < mr; ++r) {
+                    if (!(r == mr - 1 || i < str)) continue;
+                    for (int s = 0; s < mc; ++s) {
+                        if (!(s == mc - 1 || j < stc)) continue;
+                        int yy = i + r * str, xx = j + s * stc;
                         for (int c = 0; c < ch; ++c) {
-                            long e = ((long)c * m + r) * m + s;
+                            long e = ((long)c * mr + r) * mc + s;
                             long d = (((long)b * ch + c) * ny + yy) * nx + xx;
                             if (act_out) act_out[d] = y[e];
                             if (is_mp && codes) codes[d] = idx[pl.idx_off[layer] + e];

@@ -30,7 +30,15 @@ NETS = {
     "rgb_p3": (((C, 3, 2), (MP, 0, 3), (C, 4, 2), (FC, 5, 0), (FC, 3, 0)), 3, 11),      # 11->10->3->2
     "cc_floor": (((C, 2, 3), (C, 3, 2), (MP, 0, 2), (FC, 4, 0), (FC, 6, 0), (FC, 2, 0)), 2, 10),  # 10->8->7->3 (floor)
     "fc_only": (((FC, 3, 0),), 2, 4),
+    # rectangular pooling windows (Background, layer MP: p_row x p_col): 12 -> 11x11 -> (2x3, floor) 5x3 -> 4x2 -> FC
+    "rect_2x3": (((C, 3, 2), (MP, 0, 2, 3), (C, 4, 2), (FC, 5, 0), (FC, 2, 0)), 2, 12),
 }
+
+
+def _four(layer):
+    """(kind, maps, k, k2): k2 = columns of a pooling window, k if the description has none."""
+    kind, maps, k = layer[:3]
+    return kind, maps, k, (layer[3] if len(layer) > 3 and layer[3] else k)
 
 
 def rand_params(layers, in_ch, patch, seed, amp=0.5):
@@ -40,19 +48,20 @@ def rand_params(layers, in_ch, patch, seed, amp=0.5):
 
 def split_params(layers, in_ch, patch, params):
     """(W[o,c,k,k], b[o]) per parametrised layer, in the documented order."""
-    out, side, ch, off, seen_fc = [], patch, in_ch, 0, False
-    for kind, maps, k in layers:
+    out, rows, cols, ch, off, seen_fc = [], patch, patch, in_ch, 0, False
+    for kind, maps, k, k2 in (_four(l) for l in layers):
         if kind == MP:
             out.append(None)
-            side //= k
+            rows //= k
+            cols //= k2
             continue
-        kk = k if kind == C else (1 if seen_fc else side)
-        nw = maps * ch * kk * kk
-        W = params[off:off + nw].reshape(maps, ch, kk, kk)
+        kr, kc = (k, k) if kind == C else ((1, 1) if seen_fc else (rows, cols))
+        nw = maps * ch * kr * kc
+        W = params[off:off + nw].reshape(maps, ch, kr, kc)
         b = params[off + nw:off + nw + maps]
         off += nw + maps
         out.append((W, b))
-        side = side - kk + 1
+        rows, cols = rows - kr + 1, cols - kc + 1
         ch = maps
         seen_fc = seen_fc or kind == FC
     assert off == params.size
@@ -61,17 +70,18 @@ def split_params(layers, in_ch, patch, params):
 
 def torch_patch_net(layers, in_ch, patch, params_t, x, squash=torch.tanh):
     """Textbook net on patches x [N,C,P,P] with library ops; returns logits [N,n_cls]."""
-    side, ch, off, seen_fc = patch, in_ch, 0, False
+    rows, cols, ch, off, seen_fc = patch, patch, in_ch, 0, False
     h = x
     L = len(layers)
-    for li, (kind, maps, k) in enumerate(layers):
+    for li, (kind, maps, k, k2) in enumerate(_four(l) for l in layers):
         if kind == MP:
-            h = F.max_pool2d(h, k)          # floor semantics, non-overlapping
-            side //= k
+            h = F.max_pool2d(h, (k, k2))    # floor semantics, non-overlapping
+            rows //= k
+            cols //= k2
             continue
-        kk = k if kind == C else (1 if seen_fc else side)
-        nw = maps * ch * kk * kk
-        W = params_t[off:off + nw].reshape(maps, ch, kk, kk)
+        kr, kc = (k, k) if kind == C else ((1, 1) if seen_fc else (rows, cols))
+        nw = maps * ch * kr * kc
+        W = params_t[off:off + nw].reshape(maps, ch, kr, kc)
         b = params_t[off + nw:off + nw + maps]
         off += nw + maps
         if kind == C:
@@ -81,7 +91,7 @@ def torch_patch_net(layers, in_ch, patch, params_t, x, squash=torch.tanh):
             if li != L - 1:
                 h = squash(h)
             h = h.reshape(h.shape[0], maps, 1, 1)
-        side = side - kk + 1
+        rows, cols = rows - kr + 1, cols - kc + 1
         ch = maps
         seen_fc = seen_fc or kind == FC
     return h.reshape(h.shape[0], -1)
@@ -115,7 +125,7 @@ def test_single_patch_matches_autograd(name):
     np.testing.assert_allclose(r["dimage"], xt.grad.numpy(), rtol=1e-10, atol=1e-13)
 
 
-@pytest.mark.parametrize("name", ["tiny18", "rgb_p3", "cc_floor"])
+@pytest.mark.parametrize("name", ["tiny18", "rgb_p3", "cc_floor", "rect_2x3"])
 def test_image_is_sum_over_crops(name):
     """An H x W image is (H-P+1)(W-P+1) patches; label and weight sit at the
     patch centre (P-1)//2; gradients add up (Alg. 2: gradients are accumulated)."""
@@ -363,30 +373,32 @@ def test_fragment_bookkeeping():
 def _dense_forward_torch(layers, in_ch, patch, params_t, x):
     """Whole-image evaluation with dilated library ops: MP -> stride-1 max
     filter with taps `d` apart, later kernels dilated by the pooling factors."""
-    d, side, ch, off, seen_fc = 1, patch, in_ch, 0, False
+    dr, dc, rows, cols, ch, off, seen_fc = 1, 1, patch, patch, in_ch, 0, False
     h = x
     L = len(layers)
-    for li, (kind, maps, k) in enumerate(layers):
+    for li, (kind, maps, k, k2) in enumerate(_four(l) for l in layers):
         if kind == MP:
-            h = F.max_pool2d(h, k, stride=1, dilation=d)
-            d *= k
-            side //= k
+            h = F.max_pool2d(h, (k, k2), stride=1, dilation=(dr, dc))
+            dr *= k
+            dc *= k2
+            rows //= k
+            cols //= k2
             continue
-        kk = k if kind == C else (1 if seen_fc else side)
-        nw = maps * ch * kk * kk
-        W = params_t[off:off + nw].reshape(maps, ch, kk, kk)
+        kr, kc = (k, k) if kind == C else ((1, 1) if seen_fc else (rows, cols))
+        nw = maps * ch * kr * kc
+        W = params_t[off:off + nw].reshape(maps, ch, kr, kc)
         b = params_t[off + nw:off + nw + maps]
         off += nw + maps
-        h = F.conv2d(h, W, b, dilation=d)
+        h = F.conv2d(h, W, b, dilation=(dr, dc))
         if li != L - 1:
             h = torch.tanh(h)
-        side = side - kk + 1
+        rows, cols = rows - kr + 1, cols - kc + 1
         ch = maps
         seen_fc = seen_fc or kind == FC
     return h
 
 
-@pytest.mark.parametrize("name", ["tiny18", "rgb_p3"])
+@pytest.mark.parametrize("name", ["tiny18", "rgb_p3", "rect_2x3"])
 def test_whole_image_equivalence(name):
     """The invariant of the method: one dilated whole-image pass gives, at every
     pixel, the patch net's output, and its gradient is the sum over patches."""
@@ -688,6 +700,38 @@ def test_oracle_values_on_file():
     assert set(now) == set(stored)
     for k, v in stored.items():
         assert abs(now[k] - v) <= 1e-12 * max(1.0, abs(v)), (k, now[k], v)
+
+
+def test_rectangular_pool_by_hand():
+    """A 2 x 3 window over a 4 x 6 map (Background, layer MP: p_row x p_col sub-regions): the
+    maxima, the tap codes u * p_col + v of the FIRST maximum, and where the deltas go; the
+    whole-image map of the pooled layer is p_row apart in rows and p_col apart in columns, i.e.
+    p_row * p_col fragments (Method, MPF layer: one fragment per offset of the pooling kernel)."""
+    x = np.array([[1., 5., 2., 0., 0., 0.],
+                  [3., 5., 4., 0., 7., 0.],
+                  [9., 1., 1., 2., 2., 2.],
+                  [1., 1., 9., 2., 2., 2.]])
+    layers = ((MP, 0, 2, 3), (FC, 2, 0))                 # patch 4... needs a square patch: 6 x 6, two rows unused
+    img = np.zeros((1, 1, 6, 6)); img[0, 0, :4] = x
+    # FC over the 3 x 2 pooled map [[5, 7], [9, 2], [0, 0]]; weights pick each entry in turn
+    pooled = np.array([[5., 7.], [9., 2.], [0., 0.]])
+    n = oracle.param_count(layers, 1, 6)
+    assert n == 2 * 6 + 2
+    for e in range(4):
+        params = np.zeros(n); params[e] = 1.0            # class-0 logit = pooled entry e (row-major)
+        r = oracle.run(layers, 1, 6, params, img, np.zeros((1, 6, 6), dtype=np.int32), want_grads=True,
+                       want_dimage=True, loss_fn="mse")
+        assert abs(r["probs"][0, 0, 0, 0] - pooled.ravel()[e]) < 1e-15
+        # the delta of class 0 (output - 1) lands on the FIRST maximum of window e
+        want = np.zeros((6, 6))
+        where = {0: (0, 1), 1: (1, 4), 2: (2, 0), 3: (2, 3)}[e]
+        want[where] = pooled.ravel()[e] - 1.0
+        np.testing.assert_allclose(r["dimage"][0, 0], want, atol=1e-15)
+    d = oracle.dense_layer(layers, 1, 6, np.zeros(n), np.zeros((1, 1, 9, 8)), 0)
+    assert (d["stride"], d["stride_cols"]) == (2, 3)
+    assert d["act"].shape == (1, 1, 9 - 6 + (3 - 1) * 2 + 1, 8 - 6 + (2 - 1) * 3 + 1)
+    codes = oracle.dense_layer(layers, 1, 6, np.zeros(n), img, 0)["codes"][0, 0]
+    assert codes[0, 0] == 0 * 3 + 1 and codes[0, 3] == 1 * 3 + 1 and codes[2, 0] == 0 and codes[2, 3] == 0
 
 
 def test_mirror_pad_by_hand():
