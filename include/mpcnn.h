@@ -66,13 +66,17 @@ typedef enum { MPCNN_C = 0, MPCNN_MP = 1, MPCNN_FC = 2 } mpcnn_kind;
 typedef enum { MPCNN_F32 = 0, MPCNN_BF16 = 1 } mpcnn_dtype;
 
 /* One layer (Background, layer kinds).  C: `maps` output maps, k x k filters.
- * MP: non-overlapping k x k max-pooling (maps ignored); windows start at the top left of the
- * map, rows / columns left over when its side is not a multiple of k are dropped.  FC: `maps` units
+ * MP: non-overlapping k x k max-pooling (maps ignored), or k rows x k2 columns ("p_row x p_col
+ * sub-regions"); windows start at the top left of the map, rows / columns left over when a side
+ * is not a multiple of the window's are dropped.  After a rectangular pool the maps of a patch
+ * are no longer square and rows and columns of the whole-image maps are spaced differently; such
+ * layers run on the plain (not the matrix-core) kernels, with fp32 storage only.  FC: `maps` units
  * (k ignored); the last layer must be FC and its `maps` is the class count. */
 typedef struct {
     int kind; /* mpcnn_kind */
     int maps;
     int k;
+    int k2;   /* MP only: columns of the pooling window, 0 = k (square); k is then its rows */
 } mpcnn_layer_desc;
 
 /*

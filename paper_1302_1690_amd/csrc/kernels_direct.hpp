@@ -38,12 +38,14 @@ __global__ void stage_input_kernel(const float* __restrict__ src, T* __restrict_
     }
 }
 
-// a6: dA[b,y,x,c] = sum_{u,v,o} W[u,v,c,o] * dY[b, y-u*d, x-v*d, o]  (terms outside dY dropped),
+// a6: dA[b,y,x,c] = sum_{u<k,v<k2,o} W[u,v,c,o] * dY[b, y-u*d, x-v*d2, o]  (terms outside dY dropped;
+// k2, d2: columns of the kernel and their spacing, which differ from the rows' after a rectangular pool),
 // times (1 - A^2) when A is the tanh output of the layer below.
 template <bool TANHP>
 __global__ void conv_dgrad_direct_kernel(const float* __restrict__ dY, const float* __restrict__ Wk,
                                          const float* __restrict__ A, float* __restrict__ dA, int B,
-                                         int Hi, int Wi, int Ci, int Ho, int Wo, int Co, int k, int d, int logistic)
+                                         int Hi, int Wi, int Ci, int Ho, int Wo, int Co, int k, int k2, int d, int d2,
+                                         int logistic)
 {
     long total = (long)B * Hi * Wi * Ci;
     for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
@@ -58,11 +60,11 @@ __global__ void conv_dgrad_direct_kernel(const float* __restrict__ dY, const flo
         for (int u = 0; u < k; ++u) {
             int yy = y - u * d;
             if (yy < 0 || yy >= Ho) continue;
-            for (int v = 0; v < k; ++v) {
-                int xx = x - v * d;
+            for (int v = 0; v < k2; ++v) {
+                int xx = x - v * d2;
                 if (xx < 0 || xx >= Wo) continue;
                 const float* g = dY + (((long)b * Ho + yy) * Wo + xx) * Co;
-                const float* w = Wk + ((long)(u * k + v) * Ci + c) * Co;
+                const float* w = Wk + ((long)(u * k2 + v) * Ci + c) * Co;
                 for (int o = 0; o < Co; ++o) acc = fmaf(g[o], w[o], acc);
             }
         }
@@ -80,16 +82,17 @@ __global__ void conv_dgrad_direct_kernel(const float* __restrict__ dY, const flo
 // in index order (Alg. 2: the gradient is the sum over all fragments).
 __global__ void conv_wgrad_direct_kernel(const float* __restrict__ A, const float* __restrict__ dY,
                                          float* __restrict__ partial, int B, int Hi, int Wi, int Ci,
-                                         int Ho, int Wo, int Co, int k, int d, int rows_per_chunk)
+                                         int Ho, int Wo, int Co, int k, int k2, int d, int d2,
+                                         int rows_per_chunk)
 {
-    const long KN = ((long)k * k * Ci + 1) * Co;
+    const long KN = ((long)k * k2 * Ci + 1) * Co;
     long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= KN) return;
     int o = (int)(e % Co);
     int kk = (int)(e / Co);
-    const bool is_bias = kk == k * k * Ci;
+    const bool is_bias = kk == k * k2 * Ci;
     int c = kk % Ci, tap = kk / Ci;
-    int u = tap / k, v = tap % k;
+    int u = tap / k2, v = tap % k2;
     long row0 = (long)blockIdx.y * rows_per_chunk;
     long row1 = row0 + rows_per_chunk;
     if (row1 > (long)B * Ho) row1 = (long)B * Ho;
@@ -100,7 +103,7 @@ __global__ void conv_wgrad_direct_kernel(const float* __restrict__ A, const floa
         if (is_bias) {
             for (int x = 0; x < Wo; ++x) acc += g[(long)x * Co];
         } else {
-            const float* a = A + (((long)b * Hi + (y + u * d)) * Wi + v * d) * Ci + c;
+            const float* a = A + (((long)b * Hi + (y + u * d)) * Wi + v * d2) * Ci + c;
             for (int x = 0; x < Wo; ++x) acc = fmaf(g[(long)x * Co], a[(long)x * Ci], acc);
         }
     }
@@ -111,7 +114,7 @@ __global__ void conv_wgrad_direct_kernel(const float* __restrict__ A, const floa
 // maximum in row-major (u,v) order (Alg. 3: MP_fwd on every offset, mpIDXS).
 __global__ void maxfilter_fwd_direct_kernel(const float* __restrict__ A, float* __restrict__ O,
                                             uint8_t* __restrict__ code, int B, int Hi, int Wi, int C,
-                                            int Ho, int Wo, int p, int d)
+                                            int Ho, int Wo, int p, int p2, int d, int d2)
 {
     long total = (long)B * Ho * Wo * C;
     for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
@@ -125,11 +128,11 @@ __global__ void maxfilter_fwd_direct_kernel(const float* __restrict__ A, float* 
         float best = 0.f;
         int bi = -1;
         for (int u = 0; u < p; ++u)
-            for (int v = 0; v < p; ++v) {
-                float a = A[(((long)b * Hi + (y + u * d)) * Wi + (x + v * d)) * C + c];
+            for (int v = 0; v < p2; ++v) {
+                float a = A[(((long)b * Hi + (y + u * d)) * Wi + (x + v * d2)) * C + c];
                 if (bi < 0 || a > best) {
                     best = a;
-                    bi = u * p + v;
+                    bi = u * p2 + v;
                 }
             }
         O[e] = best;
@@ -143,7 +146,8 @@ template <bool TANHP>
 __global__ void maxfilter_bwd_direct_kernel(const float* __restrict__ dO,
                                             const uint8_t* __restrict__ code,
                                             const float* __restrict__ A, float* __restrict__ dA,
-                                            int B, int Hi, int Wi, int C, int Ho, int Wo, int p, int d, int logistic)
+                                            int B, int Hi, int Wi, int C, int Ho, int Wo, int p, int p2, int d, int d2,
+                                            int logistic)
 {
     long total = (long)B * Hi * Wi * C;
     for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
@@ -158,11 +162,11 @@ __global__ void maxfilter_bwd_direct_kernel(const float* __restrict__ dO,
         for (int u = 0; u < p; ++u) {
             int yy = y - u * d;
             if (yy < 0 || yy >= Ho) continue;
-            for (int v = 0; v < p; ++v) {
-                int xx = x - v * d;
+            for (int v = 0; v < p2; ++v) {
+                int xx = x - v * d2;
                 if (xx < 0 || xx >= Wo) continue;
                 long s = (((long)b * Ho + yy) * Wo + xx) * C + c;
-                if (code[s] == (uint8_t)(u * p + v)) acc += dO[s];
+                if (code[s] == (uint8_t)(u * p2 + v)) acc += dO[s];
             }
         }
         if (TANHP) {

@@ -23,12 +23,12 @@ template <typename T>
 __global__ __launch_bounds__(256) void first_layer_kernel(const T* __restrict__ A,
                                                           const float* __restrict__ Wk,
                                                           T* __restrict__ Y, int B, int Hi, int Wi,
-                                                          int Ci, int Ho, int Wo, int Co, int k, int d,
-                                                          int tanh_out, int w_in_lds)
+                                                          int Ci, int Ho, int Wo, int Co, int k, int k2, int d,
+                                                          int d2, int tanh_out, int w_in_lds)
 {
     extern __shared__ __attribute__((aligned(16))) float wl[];   // [(k*k*Ci + 1)][CoP]
     const int OG = (Co + 3) >> 2, CoP = 4 * OG;
-    const int rows = k * k * Ci + 1;
+    const int rows = k * k2 * Ci + 1;
     if (w_in_lds) {
         for (int e = threadIdx.x; e < rows * CoP; e += 256) {
             const int r = e / CoP, o = e - r * CoP;
@@ -48,16 +48,16 @@ __global__ __launch_bounds__(256) void first_layer_kernel(const T* __restrict__ 
     for (int u = 0; u < k; ++u) {
         const T* arow = A + (((long)b * Hi + (y + u * d)) * Wi + x) * Ci;
         for (int c = 0; c < Ci; ++c)
-            for (int v0 = 0; v0 < k; v0 += kFirstLayerBatch) {
+            for (int v0 = 0; v0 < k2; v0 += kFirstLayerBatch) {
                 // no branches around the loads (they would be waited for one by one): taps past
                 // the filter's edge read the last tap again and count as zero
                 float av[kFirstLayerBatch];
                 v4f w[kFirstLayerBatch];
 #pragma unroll
                 for (int j = 0; j < kFirstLayerBatch; ++j) {
-                    const int v = v0 + j < k ? v0 + j : k - 1;
-                    av[j] = load1(arow + (long)v * d * Ci + c);
-                    const int wr = (u * k + v) * Ci + c;
+                    const int v = v0 + j < k2 ? v0 + j : k2 - 1;
+                    av[j] = load1(arow + (long)v * d2 * Ci + c);
+                    const int wr = (u * k2 + v) * Ci + c;
                     if (w_in_lds) w[j] = *reinterpret_cast<const v4f*>(wl + wr * CoP + o0);
                     else {
 #pragma unroll
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void first_layer_kernel(const T* __restrict__ 
                 }
 #pragma unroll
                 for (int j = 0; j < kFirstLayerBatch; ++j) {
-                    const float xj = v0 + j < k ? av[j] : 0.f;
+                    const float xj = v0 + j < k2 ? av[j] : 0.f;
 #pragma unroll
                     for (int z = 0; z < 4; ++z) acc[z] = fmaf(xj, w[j][z], acc[z]);
                 }

@@ -88,6 +88,9 @@ struct Layer {
     int cin, cout;
     int dil;      // spacing of this layer's taps in its input map
     int drop = 0; // MP: trailing rows / columns of the patch-level map that no window covers (side mod k)
+    // columns, where they differ from the rows (a rectangular pool, and every layer after it):
+    int k2 = 0, dil2 = 0, drop2 = 0;
+    bool rect = false;   // k2 != k or dil2 != dil: only the direct kernels take such a layer
     bool tanh_out;
     size_t p_off; // offset of this layer's [(k*k*cin + 1) x cout] block in the parameter buffer
     size_t p_len;
@@ -428,7 +431,7 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         // a pool that leaves `drop` trailing rows of every patch's map unused shortens the
         // whole-image map by as many rows of this spacing
         r -= (ly.k - 1 + ly.drop) * ly.dil;
-        c -= (ly.k - 1 + ly.drop) * ly.dil;
+        c -= (ly.k2 - 1 + ly.drop2) * ly.dil2;
         if (r < 1 || c < 1) return false;
         g->rows[l] = r; g->cols[l] = c;
         size_t bytes = es * (size_t)B * r * c * ly.cout;
@@ -692,18 +695,18 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             uint8_t* code = g.training ? (uint8_t*)(ws + g.code_off[l]) : nullptr;
             long total = (long)B * Ho * Wo * ly.cout;
             mpcnn::RowGrid rg;
-            if (!kF32 && ly.cout % 8 == 0 && row_grid(B, Ho, Wo, ly.cout / 8, &rg))   // bf16: 8 channels per thread (fp32: measured slower)
+            if (!kF32 && !ly.rect && ly.cout % 8 == 0 && row_grid(B, Ho, Wo, ly.cout / 8, &rg))   // bf16: 8 channels per thread (fp32: measured slower)
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
                        (maxfilter_fwd4_kernel<T, kF32 ? 1 : 2><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
                            in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil)));
-            else if (ly.cout % 4 == 0 && row_grid(B, Ho, Wo, ly.cout / 4, &rg))
+            else if (!ly.rect && ly.cout % 4 == 0 && row_grid(B, Ho, Wo, ly.cout / 4, &rg))
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
                        (maxfilter_fwd4_kernel<T, 1><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
                            in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil)));
             else if constexpr (kF32)
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (code ? 9.0 : 8.0),
                        maxfilter_fwd_direct_kernel<<<grid_for(total), 256, 0, st>>>(
-                           in, out, code, B, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil));
+                           in, out, code, B, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2));
             else
                 return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", l);
         } else if (ly.class_fused) {
@@ -728,7 +731,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             if (train && want_loss) net->loss_shares = blocks;
         } else {
             const float* Wk = net->d_wread + ly.p_off;
-            const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k * Ci;
+            const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k2 * Ci;
             const double bytes = es * (n_in + n_out) + 4.0 * ly.p_len;
             const int step = (l == L - 1) ? 3 : 1;
             if (ly.fwd_mfma && g.fwd[l].ok) {
@@ -756,11 +759,12 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             } else {
                 const int og = ceil_div(ly.cout, 4);
                 const long total = (long)B * Ho * Wo * og;
-                const size_t wbytes = sizeof(float) * ((size_t)ly.k * ly.k * Ci + 1) * 4 * og;
+                const size_t wbytes = sizeof(float) * ((size_t)ly.k * ly.k2 * Ci + 1) * 4 * og;
                 const int w_in_lds = wbytes <= 48 * 1024;
                 LAUNCH("first_layer", l, step, flops, bytes,
                        first_layer_kernel<T><<<(unsigned)((total + 255) / 256), 256, w_in_lds ? wbytes : 0, st>>>(
-                           in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil, ly.tanh_out ? 1 + net->logistic : 0,
+                           in, Wk, out, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.k2, ly.dil, ly.dil2,
+                           ly.tanh_out ? 1 + net->logistic : 0,
                            w_in_lds));
             }
         }
@@ -815,8 +819,8 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
             long total = (long)B * Hi * Wi * Ci;
             const double bytes = n_out * (es + 1.0) + n_in * es * (below_tanh ? 2.0 : 1.0);
             mpcnn::RowGrid rg;
-            const bool octs = Ci % 8 == 0 && row_grid(B, Hi, Wi, Ci / 8, &rg);   // 8 channels per thread (measured faster in both storage types)
-            const bool quads = !octs && Ci % 4 == 0 && row_grid(B, Hi, Wi, Ci / 4, &rg);
+            const bool octs = !ly.rect && Ci % 8 == 0 && row_grid(B, Hi, Wi, Ci / 8, &rg);   // 8 channels per thread (measured faster in both storage types)
+            const bool quads = !ly.rect && !octs && Ci % 4 == 0 && row_grid(B, Hi, Wi, Ci / 4, &rg);
             if (octs && below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        (maxfilter_bwd4_kernel<true, T, 2><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
@@ -838,13 +842,13 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
             else if (below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        maxfilter_bwd_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
-                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil, net->logistic));
+                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic));
             else
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        maxfilter_bwd_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
-                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil, net->logistic));
+                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic));
         } else {
-            const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k * Ci;
+            const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k2 * Ci;
             const int wstep = (li == L - 1) ? 4 : 5, dstep = (li == L - 1) ? 4 : 6;
             // parameter gradient: partial sums over slabs of positions, then a fixed-order sum
             const WgradPlan& wp = g.wgrad[li];
@@ -877,7 +881,7 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 dim3 grid((unsigned)((ly.p_len + 255) / 256), (unsigned)wp.chunks);
                 LAUNCH("wgrad_direct", li, wstep, flops, 4.0 * (n_in + n_out + ly.p_len),
                        conv_wgrad_direct_kernel<<<grid, 256, 0, st>>>(A, dY, partial, B, Hi, Wi, Ci, Ho,
-                                                                      Wo, ly.cout, ly.k, ly.dil,
+                                                                      Wo, ly.cout, ly.k, ly.k2, ly.dil, ly.dil2,
                                                                       wp.rows_per_chunk));
             }
             if (li == 0) break;  // the image needs no gradient
@@ -903,11 +907,11 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 if (below_tanh)
                     LAUNCH("conv_dgrad_direct", li, dstep, flops, dbytes,
                            conv_dgrad_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
-                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil, net->logistic));
+                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic));
                 else
                     LAUNCH("conv_dgrad_direct", li, dstep, flops, dbytes,
                            conv_dgrad_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
-                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.dil, net->logistic));
+                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic));
             }
         }
         cur ^= 1;
@@ -949,14 +953,14 @@ void to_device_order(const mpcnn_net* net, const float* host, float* dev_order)
 {
     for (const Layer& ly : net->layers) {
         if (ly.kind == MPCNN_MP) continue;
-        const int k = ly.k, ci = ly.cin, co = ly.cout;
+        const int kk = ly.k * ly.k2, ci = ly.cin, co = ly.cout;
         const float* src = host + ly.p_off;
         float* dst = dev_order + ly.p_off;
         for (int o = 0; o < co; ++o)
             for (int c = 0; c < ci; ++c)
-                for (int t = 0; t < k * k; ++t)
-                    dst[((size_t)t * ci + c) * co + o] = src[((size_t)o * ci + c) * k * k + t];
-        memcpy(dst + (size_t)k * k * ci * co, src + (size_t)k * k * ci * co, sizeof(float) * co);
+                for (int t = 0; t < kk; ++t)
+                    dst[((size_t)t * ci + c) * co + o] = src[((size_t)o * ci + c) * kk + t];
+        memcpy(dst + (size_t)kk * ci * co, src + (size_t)kk * ci * co, sizeof(float) * co);
     }
 }
 
@@ -964,14 +968,14 @@ void to_host_order(const mpcnn_net* net, const float* dev_order, float* host)
 {
     for (const Layer& ly : net->layers) {
         if (ly.kind == MPCNN_MP) continue;
-        const int k = ly.k, ci = ly.cin, co = ly.cout;
+        const int kk = ly.k * ly.k2, ci = ly.cin, co = ly.cout;
         const float* src = dev_order + ly.p_off;
         float* dst = host + ly.p_off;
         for (int o = 0; o < co; ++o)
             for (int c = 0; c < ci; ++c)
-                for (int t = 0; t < k * k; ++t)
-                    dst[((size_t)o * ci + c) * k * k + t] = src[((size_t)t * ci + c) * co + o];
-        memcpy(dst + (size_t)k * k * ci * co, src + (size_t)k * k * ci * co, sizeof(float) * co);
+                for (int t = 0; t < kk; ++t)
+                    dst[((size_t)o * ci + c) * kk + t] = src[((size_t)t * ci + c) * co + o];
+        memcpy(dst + (size_t)kk * ci * co, src + (size_t)kk * ci * co, sizeof(float) * co);
     }
 }
 
@@ -1016,42 +1020,56 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
     mpcnn_net* net = new (std::nothrow) mpcnn_net;
     if (!net) return fail(MPCNN_ENOMEM, "out of host memory");
     net->in_ch = in_channels; net->patch = patch; net->bf16 = dtype == MPCNN_BF16;
-    int side = patch, ch = in_channels, dil = 1;
+    int side = patch, side2 = patch, ch = in_channels, dil = 1, dil2 = 1;   // rows; columns
     bool seen_fc = false;
     size_t off = 0, pack = 0;
     mpcnn_status st = MPCNN_OK;
     for (int l = 0; l < n_layers && st == MPCNN_OK; ++l) {
         const mpcnn_layer_desc& d = layers[l];
         Layer ly{};
-        ly.kind = d.kind; ly.cin = ch; ly.dil = dil;
+        ly.kind = d.kind; ly.cin = ch; ly.dil = dil; ly.dil2 = dil2;
         if (d.kind == MPCNN_C) {
             if (d.maps < 1 || d.k < 1) st = fail(MPCNN_EINVAL, "layer %d: C needs maps >= 1, k >= 1", l);
             else if (seen_fc) st = fail(MPCNN_ESHAPE, "layer %d: C after FC", l);
-            else if (side - d.k + 1 < 1) st = fail(MPCNN_ESHAPE, "layer %d: %dx%d filter on a %dx%d map", l, d.k, d.k, side, side);
-            else { ly.k = d.k; ly.cout = d.maps; ly.tanh_out = true; side -= d.k - 1; }
+            else if (side - d.k + 1 < 1 || side2 - d.k + 1 < 1) st = fail(MPCNN_ESHAPE, "layer %d: %dx%d filter on a %dx%d map", l, d.k, d.k, side, side2);
+            else { ly.k = ly.k2 = d.k; ly.cout = d.maps; ly.tanh_out = true; side -= d.k - 1; side2 -= d.k - 1; }
         } else if (d.kind == MPCNN_MP) {
-            if (d.k < 1) st = fail(MPCNN_EINVAL, "layer %d: MP needs k >= 1", l);
+            const int pc = d.k2 > 0 ? d.k2 : d.k;   // columns of the window
+            if (d.k < 1 || d.k2 < 0) st = fail(MPCNN_EINVAL, "layer %d: MP needs k >= 1, k2 >= 0", l);
             else if (seen_fc) st = fail(MPCNN_ESHAPE, "layer %d: MP after FC", l);
-            else if (side / d.k < 1) st = fail(MPCNN_ESHAPE, "layer %d: %dx%d pooling on a %dx%d map", l, d.k, d.k, side, side);
-            else if (d.k * d.k > 255) st = fail(MPCNN_EUNSUPPORTED, "layer %d: pooling window too large for byte tap codes", l);
-            else { ly.k = d.k; ly.cout = ch; ly.tanh_out = false; ly.drop = side % d.k; side /= d.k; dil *= d.k; }
+            else if (side / d.k < 1 || side2 / pc < 1) st = fail(MPCNN_ESHAPE, "layer %d: %dx%d pooling on a %dx%d map", l, d.k, pc, side, side2);
+            else if (d.k * pc > 255) st = fail(MPCNN_EUNSUPPORTED, "layer %d: pooling window too large for byte tap codes", l);
+            else {
+                ly.k = d.k; ly.k2 = pc; ly.cout = ch; ly.tanh_out = false;
+                ly.drop = side % d.k; ly.drop2 = side2 % pc;
+                side /= d.k; side2 /= pc; dil *= d.k; dil2 *= pc;
+            }
         } else if (d.kind == MPCNN_FC) {
             if (d.maps < 1) st = fail(MPCNN_EINVAL, "layer %d: FC needs maps >= 1", l);
-            else { ly.k = seen_fc ? 1 : side; ly.cout = d.maps; ly.tanh_out = (l != n_layers - 1); side = 1; seen_fc = true; }
+            else {
+                ly.k = seen_fc ? 1 : side; ly.k2 = seen_fc ? 1 : side2;
+                ly.cout = d.maps; ly.tanh_out = (l != n_layers - 1); side = side2 = 1; seen_fc = true;
+            }
         } else st = fail(MPCNN_EINVAL, "layer %d: unknown kind %d", l, d.kind);
         if (st != MPCNN_OK) break;
+        // rows and columns differ (a rectangular pool or anything behind one): the direct kernels
+        ly.rect = ly.k2 != ly.k || (ly.dil2 != ly.dil && (ly.k > 1 || ly.k2 > 1));
+        if (ly.rect && net->bf16) {
+            st = fail(MPCNN_EUNSUPPORTED, "layer %d: rectangular pooling has fp32-storage kernels only", l);
+            break;
+        }
         if (ly.kind != MPCNN_MP) {
             ly.p_off = off;
-            ly.p_len = ((size_t)ly.k * ly.k * ly.cin + 1) * ly.cout;
+            ly.p_len = ((size_t)ly.k * ly.k2 * ly.cin + 1) * ly.cout;
             off += ly.p_len;
             // matrix cores take layers whose reduced channel count is a multiple of 4 and at
             // least 8, and that produce at least 8 channels; the rest run on the direct kernels
             const bool last = l == n_layers - 1;
             ly.class_fused = last && ly.k == 1 && ly.cin % 4 == 0 && ly.cin <= 256 &&
                              ly.cout >= 2 && ly.cout <= 4;
-            ly.fwd_mfma = !last && ly.cin % 4 == 0 && ly.cin >= 8 && ly.cout >= 8;
-            ly.dgrad_mfma = l > 0 && ly.cout % 4 == 0 && ly.cout >= 8 && ly.cin >= 8;
-            ly.wgrad_mfma = !ly.class_fused;   // any shape: gradient rows are tiled in parameter order
+            ly.fwd_mfma = !ly.rect && !last && ly.cin % 4 == 0 && ly.cin >= 8 && ly.cout >= 8;
+            ly.dgrad_mfma = !ly.rect && l > 0 && ly.cout % 4 == 0 && ly.cout >= 8 && ly.cin >= 8;
+            ly.wgrad_mfma = !ly.rect && !ly.class_fused;   // any square shape: gradient rows are tiled in parameter order
             // bf16 storage with channel counts that are multiples of 8: the bf16 matrix instruction
             ly.fwd_bm = net->bf16 && ly.fwd_mfma && ly.cin % 8 == 0;
             ly.dgrad_bm = net->bf16 && ly.dgrad_mfma && ly.cout % 8 == 0;

@@ -42,7 +42,7 @@ class MpcnnError(RuntimeError):
 
 
 class _LayerDesc(C.Structure):
-    _fields_ = [("kind", C.c_int), ("maps", C.c_int), ("k", C.c_int)]
+    _fields_ = [("kind", C.c_int), ("maps", C.c_int), ("k", C.c_int), ("k2", C.c_int)]
 
 
 class KernelStat(C.Structure):
@@ -131,7 +131,8 @@ class Net:
 
     def __init__(self, layers: Sequence[Tuple[int, int, int]], in_channels: int, patch: int,
                  dtype: int = F32):
-        arr = (_LayerDesc * len(layers))(*[_LayerDesc(int(a), int(b), int(c)) for a, b, c in layers])
+        arr = (_LayerDesc * len(layers))(*[_LayerDesc(int(l[0]), int(l[1]), int(l[2]), int(l[3]) if len(l) > 3 else 0)
+                                           for l in layers])
         h = C.c_void_p()
         _check(lib().mpcnn_net_create(arr, len(layers), in_channels, patch, dtype, C.byref(h)))
         self._h = h

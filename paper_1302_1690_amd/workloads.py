@@ -90,17 +90,19 @@ CONFIGS: List[Workload] = [
 
 def param_count(layers, in_channels: int, patch: int) -> int:
     """Number of parameters (all W then b, layer by layer) - bookkeeping only."""
-    side, ch, total, seen_fc = patch, in_channels, 0, False
-    for kind, maps, k in layers:
+    rows, cols, ch, total, seen_fc = patch, patch, in_channels, 0, False
+    for layer in layers:
+        kind, maps, k = layer[:3]
+        k2 = layer[3] if len(layer) > 3 and layer[3] else k     # columns of a pooling window
         if kind == C:
             total += maps * ch * k * k + maps
-            side, ch = side - k + 1, maps
+            rows, cols, ch = rows - k + 1, cols - k + 1, maps
         elif kind == MP:
-            side //= k
+            rows, cols = rows // k, cols // k2
         else:
-            kk = 1 if seen_fc else side
-            total += maps * ch * kk * kk + maps
-            side, ch, seen_fc = 1, maps, True
+            kk = 1 if seen_fc else rows * cols
+            total += maps * ch * kk + maps
+            rows, cols, ch, seen_fc = 1, 1, maps, True
     return total
 
 

@@ -94,6 +94,22 @@ def test_fragment_counts_printed_in_the_paper():
         net.close()
 
 
+def test_dense_shapes_with_rectangular_pools():
+    """p_row x p_col pooling windows: the library's whole-image maps have the sizes and the row
+    spacing of the oracle's (Background, layer MP)."""
+    layers = ((C, 4, 3), (MP, 0, 3, 2), (C, 6, 2), (MP, 0, 2, 3), (FC, 10, 0), (FC, 3, 0))   # 20 -> 18 -> 6x9 -> 5x8 -> 2x2
+    net = mpcnn.Net(layers, 1, 20)
+    assert net.param_count == oracle.param_count(layers, 1, 20) == wl.param_count(layers, 1, 20)
+    img = np.zeros((1, 1, 29, 33))
+    params = np.zeros(net.param_count)
+    for layer in range(len(layers)):
+        d = oracle.dense_layer(layers, 1, 20, params, img, layer)
+        r, c, ch, sp = net.layer_shape(29, 33, layer)
+        assert d["act"].shape == (1, ch, r, c), layer
+        assert d["stride"] == sp
+    net.close()
+
+
 def test_errors():
     with pytest.raises(mpcnn.MpcnnError) as e:
         mpcnn.Net(((C, 2, 3), (MP, 0, 2)), 1, 8)

@@ -23,19 +23,25 @@ def say(msg):
     print(msg, flush=True)
 
 
+def _four(layer):
+    """(kind, maps, k, k2): k2 = columns of a pooling window, k if the description has none."""
+    kind, maps, k = layer[:3]
+    return kind, maps, k, (layer[3] if len(layer) > 3 and layer[3] else k)
+
+
 def param_tensors(layers, in_ch, patch):
     """(name, slice) of every W and b in the flat parameter vector."""
-    out, side, ch, off, seen_fc = [], patch, in_ch, 0, False
-    for li, (kind, maps, k) in enumerate(layers):
+    out, rows, cols, ch, off, seen_fc = [], patch, patch, in_ch, 0, False
+    for li, (kind, maps, k, k2) in enumerate(_four(l) for l in layers):
         if kind == MP:
-            side //= k
+            rows, cols = rows // k, cols // k2
             continue
-        kk = k if kind == C else (1 if seen_fc else side)
-        nw = maps * ch * kk * kk
+        kr, kc = (k, k) if kind == C else ((1, 1) if seen_fc else (rows, cols))
+        nw = maps * ch * kr * kc
         out.append(("W%d" % li, slice(off, off + nw)))
         out.append(("b%d" % li, slice(off + nw, off + nw + maps)))
         off += nw + maps
-        side, ch = side - kk + 1, maps
+        rows, cols, ch = rows - kr + 1, cols - kc + 1, maps
         seen_fc = seen_fc or kind == FC
     return out
 
@@ -84,11 +90,13 @@ def run_gpu(cfg, img, lab, params, pixw=None, net=None, loss_fn="mcce", squash="
     return net, probs.cpu().numpy(), float(loss.item()), net.get_grads()
 
 
-def first_max_codes(a, p, d):
-    """CPU scan of [B,r,c,ch] values: tap code of the first maximum, row-major taps."""
+def first_max_codes(a, p, d, p2=None, d2=None):
+    """CPU scan of [B,r,c,ch] values: tap code of the first maximum, row-major taps
+    (p x p2 window, rows d apart, columns d2 apart)."""
+    p2, d2 = p2 or p, d2 or d
     B, r, c, ch = a.shape
-    ro, co = r - (p - 1) * d, c - (p - 1) * d
-    taps = np.stack([a[:, u * d:u * d + ro, v * d:v * d + co, :] for u in range(p) for v in range(p)])
+    ro, co = r - (p - 1) * d, c - (p2 - 1) * d2
+    taps = np.stack([a[:, u * d:u * d + ro, v * d2:v * d2 + co, :] for u in range(p) for v in range(p2)])
     return np.argmax(taps, axis=0).astype(np.uint8), taps.max(axis=0)
 
 
@@ -134,18 +142,19 @@ def check_argmax(cfg, net, img, params, with_oracle=True, layers=None, squash="t
     the oracle's top-2 gap exceeds TIE_TAU (rounding can flip closer calls)."""
     B, _, H, W = img.shape
     excused = 0
-    dil = 1
-    for li, (kind, maps, k) in enumerate(cfg.layers):
+    dil = dil2 = 1
+    for li, (kind, maps, k, k2) in enumerate(_four(l) for l in cfg.layers):
         if kind != MP:
             continue
         if layers is not None and li not in layers:
             dil *= k
+            dil2 *= k2
             continue
         pre = (np.ascontiguousarray(img.transpose(0, 2, 3, 1)) if li == 0
                else net.get_activation(B, H, W, li - 1))
         codes = net.get_argmax(B, H, W, li)
         post = net.get_activation(B, H, W, li)
-        ref_codes, ref_max = first_max_codes(pre, k, dil)
+        ref_codes, ref_max = first_max_codes(pre, k, dil, k2, dil2)
         # a pool that drops trailing rows of the patch-level map stores only the windows in use
         assert codes.shape[1] <= ref_codes.shape[1] and codes.shape[2] <= ref_codes.shape[2]
         ref_codes = ref_codes[:, :codes.shape[1], :codes.shape[2]]
@@ -164,6 +173,7 @@ def check_argmax(cfg, net, img, params, with_oracle=True, layers=None, squash="t
             assert not (bad & (o_gap > tau)).any(), (cfg.name, li, int((bad & (o_gap > tau)).sum()))
             excused += int(bad.sum())
         dil *= k
+        dil2 *= k2
     return excused
 
 
@@ -188,7 +198,7 @@ def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_lay
     say("  argmax excused %d" % excused)
     if check_layers:
         B, _, H, W = img.shape
-        for li, (kind, maps, k) in enumerate(cfg.layers[:-1]):
+        for li, (kind, maps, k, k2) in enumerate(_four(l) for l in cfg.layers[:-1]):
             if kind == MP:
                 continue
             d = oracle.dense_layer(cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64),
@@ -291,6 +301,26 @@ def test_image_taken_in_bands():
         with pytest.raises(mpcnn.MpcnnError):
             net.seg_backward_banded(d_img, d_lab, 0)
         net.close()
+
+
+def test_rectangular_pooling_windows():
+    """p_row x p_col windows (Background, layer MP): rows and columns of the whole-image maps are
+    then spaced differently and a patch's maps are no longer square; these layers run on the plain
+    kernels.  One rectangular pool behind a matrix-core layer, and two rectangular pools with floor."""
+    from dataclasses import replace
+    # patch 17 -> 15 -> (2x3) 7x5 -> 6x4 -> FC over 6x4
+    layers = ((C, 8, 3), (MP, 0, 2, 3), (C, 8, 2), (FC, 12, 0), (FC, 2, 0))
+    cfg = replace(wl.CONFIGS[0], name="rect_2x3", layers=layers, patch=17, batch=2, height=37, width=41,
+                  weight_amp=0.3)
+    full_parity(cfg, with_pixw=True)
+    # patch 20 -> 18 -> (3x2) 6x9 -> 5x8 -> (2x3, two columns dropped) 2x2 -> FC
+    layers = ((C, 4, 3), (MP, 0, 3, 2), (C, 6, 2), (MP, 0, 2, 3), (FC, 10, 0), (FC, 3, 0))
+    cfg = replace(wl.CONFIGS[4], name="rect_two_levels", layers=layers, patch=20, batch=1, height=44,
+                  width=39, dtype="f32", weight_amp=0.3)
+    full_parity(cfg, ignore_some=True)
+    with pytest.raises(mpcnn.MpcnnError) as e:      # bf16 storage has the matrix-core kernels only
+        mpcnn.Net(((C, 8, 3), (MP, 0, 2, 3), (C, 8, 2), (FC, 12, 0), (FC, 2, 0)), 3, 17, dtype=mpcnn.BF16)
+    assert e.value.status == 4
 
 
 def test_class_layer_variants():
