@@ -102,7 +102,8 @@ size_t mpcnn_param_count(const mpcnn_net* net); /* length of the flat parameter 
  * H x W image: rows, columns, channels, and the spacing in image pixels
  * between elements that are neighbours inside one patch (the product of the
  * pooling factors so far; the MPF offsets of Alg. 3 are the residues modulo
- * this spacing).  Host-only.
+ * this spacing; behind a rectangular pool it is the spacing of the rows, the
+ * columns' being the product of the windows' column counts).  Host-only.
  */
 mpcnn_status mpcnn_layer_shape(const mpcnn_net* net, int H, int W, int layer, int* rows, int* cols,
                                int* channels, int* spacing);
