@@ -405,4 +405,135 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
     }
 }
 
+// Routing through the first pooling layer and the first layer's parameter gradient in one pass
+// (a7 + a5 for the image layer).  The delta at the first convolution's output is needed by that
+// layer's weight gradient only (the image gets no gradient), so it is formed tile by tile in LDS -
+// gathered from the pooled delta by the tap codes, times the squashing function's slope - and
+// multiplied with the image tile right there, instead of being written out and read back.  A
+// workgroup walks tiles of kL0Rows x 16 positions and keeps its sums in registers, thread e owns
+// outputs e, e + 256, .. of the layer's [(k k Ci + 1) x C1] block (bias row last); the per-workgroup
+// sums are added by reduce_all_kernel.  For small blocks (at most 8 outputs per thread).
+constexpr int kL0Rows = 8, kL0Cols = 16, kL0MaxPerThread = 8;
+struct L0Args {
+    const void* in;        // [B][Hi][Wi][Ci] image, channels-last (T)
+    const void* act1;      // [B][H1][W1][C1] output of the first layer (T)
+    const void* dP;        // [B][Hp][Wp][C1] delta at the pooling layer's output (T)
+    const uint8_t* code;   // same shape: tap codes of the pooling layer
+    float* partial;        // [workgroups][(k*k*Ci + 1) * C1]
+    int B, Hi, Wi, Ci, H1, W1, C1, k, Hp, Wp;
+    int nty, ntx;
+    int slope;             // 0: no squashing function, 1 tanh, 2 logistic
+};
+
+template <typename T, int P>   // P = side of the pooling window
+__global__ __launch_bounds__(256) void l0_wgrad_fused_kernel(L0Args a)
+{
+    extern __shared__ __attribute__((aligned(16))) float l0_lds[];
+    constexpr int NP = kL0Rows * kL0Cols;
+    const T* in_t = static_cast<const T*>(a.in);
+    const T* act_t = static_cast<const T*>(a.act1);
+    const T* dp_t = static_cast<const T*>(a.dP);
+    const int hw = kL0Cols + a.k - 1, hh = kL0Rows + a.k - 1;
+    float* dl = l0_lds;                    // [NP][C1]
+    float* hl = l0_lds + NP * a.C1;        // [hh][hw][Ci]
+    const int tid = threadIdx.x;
+    const int rows_total = a.k * a.k * a.Ci, E = (rows_total + 1) * a.C1;
+    const int Q = a.C1 >> 2;
+    float acc[kL0MaxPerThread];
+#pragma unroll
+    for (int j = 0; j < kL0MaxPerThread; ++j) acc[j] = 0.f;
+    // what each of this thread's outputs reads: halo offset of its tap and channel, delta column
+    int hoff[kL0MaxPerThread], ocol[kL0MaxPerThread];
+#pragma unroll
+    for (int j = 0; j < kL0MaxPerThread; ++j) {
+        const int e = tid + 256 * j;
+        hoff[j] = -2; ocol[j] = 0;
+        if (e < E) {
+            const int r = e / a.C1;
+            ocol[j] = e - r * a.C1;
+            if (r == rows_total) hoff[j] = -1;             // the bias row: the input is 1
+            else {
+                const int tap = r / a.Ci, c = r - tap * a.Ci, u = tap / a.k, v = tap - u * a.k;
+                hoff[j] = (u * hw + v) * a.Ci + c;
+            }
+        }
+    }
+    const int tiles = a.B * a.nty * a.ntx;
+    for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        int t = tile;
+        const int txi = t % a.ntx; t /= a.ntx;
+        const int tyi = t % a.nty;
+        const int b = t / a.nty;
+        const int y0 = tyi * kL0Rows, x0 = txi * kL0Cols;
+        // the image tile (clamped at the border: those positions carry a zero delta)
+        for (int e = tid; e < hh * hw * a.Ci; e += 256) {
+            const int c = e % a.Ci, q = e / a.Ci, hx = q % hw, hy = q / hw;
+            int iy = y0 + hy, ix = x0 + hx;
+            iy = iy < a.Hi ? iy : a.Hi - 1;
+            ix = ix < a.Wi ? ix : a.Wi - 1;
+            hl[e] = load1(in_t + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Ci + c);
+        }
+        // the delta tile: gather over the <= P*P windows that contain the element, fixed (u,v)
+        // order.  Every load is issued, at a clamped address, before the first use: the tile is
+        // small and the round trips to memory are what this phase costs.
+#pragma unroll 2
+        for (int it = tid; it < NP * Q; it += 256) {
+            const int pos = it / Q, q4 = it - pos * Q;
+            const int y = y0 + pos / kL0Cols, x = x0 + pos % kL0Cols;
+            const bool inside = y < a.H1 && x < a.W1;
+            const int yc = inside ? y : 0, xc = inside ? x : 0;
+            uint32_t cd[P * P];
+            v4f gr[P * P];
+            bool ok[P * P];
+#pragma unroll
+            for (int u = 0; u < P; ++u)
+#pragma unroll
+                for (int v = 0; v < P; ++v) {
+                    const int yy = yc - u, xx = xc - v;
+                    ok[u * P + v] = inside && yy >= 0 && yy < a.Hp && xx >= 0 && xx < a.Wp;
+                    const int ys = yy < 0 ? 0 : (yy < a.Hp ? yy : a.Hp - 1), xs = xx < 0 ? 0 : (xx < a.Wp ? xx : a.Wp - 1);
+                    const long s = (((long)b * a.Hp + ys) * a.Wp + xs) * a.C1 + 4 * q4;
+                    cd[u * P + v] = *reinterpret_cast<const uint32_t*>(a.code + s);
+                    gr[u * P + v] = load4(dp_t + s);
+                }
+            v4f y1 = {0.f, 0.f, 0.f, 0.f};
+            if (a.slope) y1 = load4(act_t + (((long)b * a.H1 + yc) * a.W1 + xc) * a.C1 + 4 * q4);
+            v4f d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < P * P; ++t)
+#pragma unroll
+                for (int z = 0; z < 4; ++z)
+                    if (ok[t] && ((cd[t] >> (8 * z)) & 255u) == (uint32_t)t) d[z] += gr[t][z];
+            if (a.slope)
+#pragma unroll
+                for (int z = 0; z < 4; ++z) d[z] *= squash_slope(y1[z], a.slope == 2);
+            *reinterpret_cast<v4f*>(dl + pos * a.C1 + 4 * q4) = d;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < kL0MaxPerThread; ++j) {
+            if (hoff[j] < -1) continue;
+            const float* dcol = dl + ocol[j];
+            float s0 = 0.f, s1 = 0.f;
+            if (hoff[j] < 0) {
+                for (int pos = 0; pos < NP; pos += 2) { s0 += dcol[pos * a.C1]; s1 += dcol[(pos + 1) * a.C1]; }
+            } else {
+                const float* hp = hl + hoff[j];
+                for (int py = 0; py < kL0Rows; ++py)
+#pragma unroll
+                    for (int px = 0; px < kL0Cols; px += 2) {
+                        s0 = fmaf(dcol[(py * kL0Cols + px) * a.C1], hp[(py * hw + px) * a.Ci], s0);
+                        s1 = fmaf(dcol[(py * kL0Cols + px + 1) * a.C1], hp[(py * hw + px + 1) * a.Ci], s1);
+                    }
+            }
+            acc[j] += s0 + s1;
+        }
+        __syncthreads();
+    }
+    float* out = a.partial + (long)blockIdx.x * E;
+#pragma unroll
+    for (int j = 0; j < kL0MaxPerThread; ++j)
+        if (hoff[j] >= -1) out[tid + 256 * j] = acc[j];
+}
+
 }  // namespace mpcnn

@@ -459,13 +459,15 @@ __global__ __launch_bounds__(256) void reduce_all_kernel(ReduceArgs a)
     if (!sg.tiled) {
         double s = 0.0;
         if (e < sg.items) {
-            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;  // independent chains: loads in flight
+            // the sum is bound by the round trips to memory: 8 loads in flight, 4 chains
+            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
             int i = i0;
-            for (; i + 3 < i1; i += 4) {
-                s0 += (double)partial[(long)i * plen + e];
-                s1 += (double)partial[(long)(i + 1) * plen + e];
-                s2 += (double)partial[(long)(i + 2) * plen + e];
-                s3 += (double)partial[(long)(i + 3) * plen + e];
+            for (; i + 7 < i1; i += 8) {
+                float u[8];
+#pragma unroll
+                for (int z = 0; z < 8; ++z) u[z] = partial[(long)(i + z) * plen + e];
+                s0 += (double)u[0]; s1 += (double)u[1]; s2 += (double)u[2]; s3 += (double)u[3];
+                s0 += (double)u[4]; s1 += (double)u[5]; s2 += (double)u[6]; s3 += (double)u[7];
             }
             for (; i < i1; ++i) s0 += (double)partial[(long)i * plen + e];
             s = (s0 + s1) + (s2 + s3);
@@ -484,6 +486,15 @@ __global__ __launch_bounds__(256) void reduce_all_kernel(ReduceArgs a)
         const v4f* p4 = reinterpret_cast<const v4f*>(partial) + e;
         const long pl4 = plen >> 2;
         int i = i0;
+        for (; i + 7 < i1; i += 8) {   // bound by the round trips to memory: 8 loads in flight
+            v4f u[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) u[q] = p4[(long)(i + q) * pl4];
+#pragma unroll
+            for (int q = 0; q < 8; q += 2)
+#pragma unroll
+                for (int z = 0; z < 4; ++z) { s[z] += (double)u[q][z]; t[z] += (double)u[q + 1][z]; }
+        }
         for (; i + 1 < i1; i += 2) {
             const v4f u = p4[(long)i * pl4], v = p4[(long)(i + 1) * pl4];
 #pragma unroll

@@ -135,6 +135,11 @@ struct Geom {
     std::vector<int> partial_n;
     std::vector<size_t> partial_len;  // floats per partial result
     size_t loss_partial_off = 0;
+    // first convolution followed by a pool: routing through the pool and the convolution's
+    // parameter gradient run as one kernel (l0_wgrad_fused_kernel), in l0_blocks workgroups
+    bool l0_fused = false;
+    int l0_blocks = 0, l0_nty = 0, l0_ntx = 0;
+    size_t l0_lds = 0;
     size_t total = 0;
 };
 
@@ -451,6 +456,27 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         }
     }
     if (r != H - net->patch + 1 || c != W - net->patch + 1) return false;
+    g->l0_fused = false;
+    if (training && L >= 2) {
+        const Layer& l0 = net->layers[0];
+        const Layer& l1 = net->layers[1];
+        const size_t lds = sizeof(float) * ((size_t)mpcnn::kL0Rows * mpcnn::kL0Cols * l0.cout +
+                                            (size_t)(mpcnn::kL0Rows + l0.k - 1) * (mpcnn::kL0Cols + l0.k - 1) * l0.cin);
+        if (l0.kind != MPCNN_MP && !l0.class_fused && !l0.rect && l0.dil == 1 && l1.kind == MPCNN_MP && !l1.rect &&
+            l1.dil == 1 && l1.k >= 2 && l1.k <= 4 && l0.cout % 4 == 0 && l0.p_len <= (size_t)mpcnn::kL0MaxPerThread * 256 && lds <= 64 * 1024 &&
+            (long)B * ceil_div(g->rows[0], mpcnn::kL0Rows) * ceil_div(g->cols[0], mpcnn::kL0Cols) <= 2 * kNumCU) {
+            // small images only (one tile per workgroup, where the two separate launches are
+            // bound by their round trips to memory): the kernel multiplies on the vector ALU,
+            // and on a large image the matrix-core kernel behind a separate routing pass is faster
+            g->l0_fused = true;
+            g->l0_nty = ceil_div(g->rows[0], mpcnn::kL0Rows); g->l0_ntx = ceil_div(g->cols[0], mpcnn::kL0Cols);
+            g->l0_blocks = B * g->l0_nty * g->l0_ntx;
+            g->l0_lds = lds;
+            g->wgrad[0] = WgradPlan();
+            g->partial_n[0] = g->l0_blocks;
+            g->partial_len[0] = l0.p_len;
+        }
+    }
     if (training) {
         for (size_t l = 0; l < L; ++l) {
             const Layer& ly = net->layers[l];
@@ -816,6 +842,28 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
         if (ly.kind == MPCNN_MP) {
             if (li == 0) break;  // nothing below has parameters
             const uint8_t* code = (const uint8_t*)(ws + g.code_off[li]);
+            if (li == 1 && g.l0_fused) {
+                const Layer& l0 = net->layers[0];
+                L0Args a{};
+                a.in = in0; a.act1 = A; a.dP = dY; a.code = code;
+                a.partial = (float*)(ws + g.partial_off[0]);
+                a.B = B; a.Hi = g.H; a.Wi = g.W; a.Ci = l0.cin; a.H1 = Hi; a.W1 = Wi; a.C1 = Ci;
+                a.k = l0.k; a.Hp = Ho; a.Wp = Wo;
+                a.nty = g.l0_nty; a.ntx = g.l0_ntx;
+                a.slope = below_tanh ? (net->logistic ? 2 : 1) : 0;
+                const double wflops = 2.0 * B * Hi * Wi * Ci * l0.k * l0.k * l0.cin;
+                const double wbytes = n_out * (es + 1.0) + n_in * (below_tanh ? es : 0.0) + es * B * g.H * g.W * l0.cin + 4.0 * l0.p_len;
+                if (ly.k == 2)
+                    LAUNCH("l0_wgrad_fused", 0, 5, wflops, wbytes,
+                           (l0_wgrad_fused_kernel<T, 2><<<(unsigned)g.l0_blocks, 256, g.l0_lds, st>>>(a)));
+                else if (ly.k == 3)
+                    LAUNCH("l0_wgrad_fused", 0, 5, wflops, wbytes,
+                           (l0_wgrad_fused_kernel<T, 3><<<(unsigned)g.l0_blocks, 256, g.l0_lds, st>>>(a)));
+                else
+                    LAUNCH("l0_wgrad_fused", 0, 5, wflops, wbytes,
+                           (l0_wgrad_fused_kernel<T, 4><<<(unsigned)g.l0_blocks, 256, g.l0_lds, st>>>(a)));
+                break;  // the image needs no gradient
+            }
             long total = (long)B * Hi * Wi * Ci;
             const double bytes = n_out * (es + 1.0) + n_in * es * (below_tanh ? 2.0 : 1.0);
             mpcnn::RowGrid rg;
