@@ -261,6 +261,22 @@ def test_pools_that_drop_trailing_rows():
     full_parity(cfg)
 
 
+def test_first_pool_routing_fused_with_image_layer_gradient():
+    """A convolution on the image followed by a pool, on a small image: the routing through that
+    pool and the convolution's parameter gradient are one kernel.  Pool sides 2 and 4, 2 and 3
+    image channels, 5x5 filters, both storage types, the logistic slope."""
+    # patch 14 -> 12 -> (MP4) 3 -> FC over 3x3
+    net4 = ((C, 8, 3), (MP, 0, 4), (FC, 16, 0), (FC, 3, 0))
+    full_parity(wl.Workload("l0_pool4_rgb", net4, 14, 3, 3, 2, 37, 30, 0.3, "ellipses",
+                            seed_image=1111, seed_label=2111, seed_param=3111), with_pixw=True)
+    full_parity(wl.Workload("l0_pool4_rgb_bf16", net4, 14, 3, 3, 1, 33, 41, 0.25, "ellipses", dtype="bf16",
+                            seed_image=1112, seed_label=2112, seed_param=3112))
+    # patch 12 -> 8 -> (MP2) 4 -> 3 -> FC over 3x3; 12 maps of 5x5x2 filters: 612 parameters, 3 per thread
+    net2 = ((C, 12, 5), (MP, 0, 2), (C, 8, 2), (FC, 10, 0), (FC, 2, 0))
+    full_parity(wl.Workload("l0_pool2_two_channels", net2, 12, 2, 2, 2, 29, 50, 0.3, "ellipses",
+                            seed_image=1113, seed_label=2113, seed_param=3113), squash="logistic")
+
+
 def test_logistic_activation():
     """The logistic function instead of tanh in every C and hidden FC layer: matrix-core kernels
     (config 1's net), the direct kernels (tiny net), MSE on top, and bf16 storage."""
