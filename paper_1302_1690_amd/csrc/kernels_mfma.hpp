@@ -354,4 +354,188 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
     }
 }
 
+// The same product with the result tiles dealt out to the waves instead of the reduction
+// (fp32 matrix instruction, 32-wide tiles).  The workgroup's tile is 32*PT positions x 32*OT
+// output channels; each of its OT*PT/MP waves owns MP position tiles of ONE channel tile and
+// runs through all k*k*C/8 reduction steps for them, so no partial tiles meet anywhere: the
+// epilogue goes from the accumulators straight to memory (a lane holds 4 consecutive channels
+// of one position per register quad, one 128-bit store each).  A step feeds only 4*MP MFMAs, so
+// the operands are fetched through a ring D steps deep to cover the weights' trip from L2.
+// Summation order is the step order for every output element, whatever the tiling: equal
+// inputs give bit-equal outputs, and a position's value does not depend on how the map is cut.
+template <int OT, int PT, int MP, typename T>
+__global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
+{
+    static_assert(PT % MP == 0 && (OT * PT / MP == 4 || OT * PT / MP == 8), "4 or 8 waves");
+    constexpr int W = 32, G = 2;
+    constexpr int NW = OT * PT / MP, NT = 64 * NW;
+    constexpr int D = MP == 1 ? 6 : 4;             // steps in flight
+    const T* in_t = static_cast<const T*>(a.in);
+    const T* act_t = static_cast<const T*>(a.act);
+    T* out_t = static_cast<T*>(a.out);
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lt = lane & 31, lg = lane >> 5;
+    const int wo = wave % OT, wp = wave / OT;      // channel tile, first of its MP position tiles is wp*MP
+
+    int bid = blockIdx.x;
+    const int txi = bid % a.ntx; bid /= a.ntx;
+    const int tyi = bid % a.nty; bid /= a.nty;
+    const int rx = bid % a.d; bid /= a.d;
+    const int ry = bid % a.d;
+    const int b = bid / a.d;
+    const int fh = ry < a.Ho ? (a.Ho - ry + a.d - 1) / a.d : 0;  // extent of this residue class
+    const int fw = rx < a.Wo ? (a.Wo - rx + a.d - 1) / a.d : 0;
+    const int ty0 = tyi * a.Ty, tx0 = txi * a.Tx;
+    if (ty0 >= fh || tx0 >= fw) return;  // uniform for the workgroup
+
+    const int hw = a.Tx + a.k - 1, hh = a.Ty + a.k - 1;
+    const int cq = a.CrPad / 4;
+    const int Cs4 = cq + 1;              // pitch of one halo position in 128-bit units (+1: bank spread)
+    const int oc0 = W * (blockIdx.y * OT + wo);   // first channel of this wave's tile
+    v4f* lds4 = reinterpret_cast<v4f*>(lds);
+
+    // ---- stage the halo (as conv_mfma_kernel does): eight loads in flight per thread
+    {
+        const int total = hh * hw * cq;
+        constexpr int U = 8;
+        for (int base = tid; base < total; base += NT * U) {
+            v4f v[U];
+            int dst[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int it = base + NT * u;
+                v[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+                dst[u] = -1;
+                if (it < total) {
+                    const int pos = it / cq, q = it - pos * cq;
+                    const int ha = pos / hw, hb = pos - ha * hw;
+                    const int fy = ty0 + ha + a.origin, fx = tx0 + hb + a.origin;
+                    const int iy = fy * a.d + ry, ix = fx * a.d + rx;
+                    dst[u] = pos * Cs4 + q;
+                    if (fy >= 0 && fx >= 0 && iy < a.Hi && ix < a.Wi && 4 * q < a.Cr)
+                        v[u] = load4(in_t + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + 4 * q);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (dst[u] >= 0) lds4[dst[u]] = v[u];
+        }
+    }
+
+    // ---- the bias of this lane's four channel quads (channels oc0 + 8n + 4lg .. +3)
+    v4f bias4[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        bias4[n] = (v4f){0.f, 0.f, 0.f, 0.f};
+        if (a.mode <= kFwdLinear)
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+                const int c = oc0 + 8 * n + 4 * lg + z;
+                bias4[n][z] = a.bias[c < a.Co ? c : a.Co - 1];
+            }
+    }
+
+    // ---- per-lane halo offsets of the positions this lane feeds as the B operand
+    int lbase[MP];
+#pragma unroll
+    for (int p = 0; p < MP; ++p) {
+        const int m = W * (wp * MP + p) + lt;
+        int ty = m / a.Tx, tx = m - ty * a.Tx;
+        if (ty >= a.Ty) { ty = 0; tx = 0; }  // padding position: any in-bounds address
+        lbase[p] = (ty * hw + tx) * Cs4 + lg;
+    }
+
+    const int nch = a.CrPad / (4 * G);
+    const int steps = a.k * a.k * nch;
+    const int lane_w = lg * a.CoPad + oc0 + lt;   // this lane's offset inside one step of the pack
+
+    { float agpr_hint = 0.f; asm volatile("" : "+a"(agpr_hint)); }
+    v16f acc[MP];
+#pragma unroll
+    for (int p = 0; p < MP; ++p)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[p][r] = 0.f;
+
+    __syncthreads();
+
+    // the ring: slot i holds the operands of step t with t % D == i; fetches run in step order
+    int chunk = 0, ta = 0, tb = 0, tf = 0;
+    v4f wr[D], ar[D][MP];
+    auto fetch = [&](int i) {
+        wr[i] = (a.wpack + (long)tf * G * a.CoPad)[lane_w];
+        const int soff = (ta * hw + tb) * Cs4 + G * chunk;
+#pragma unroll
+        for (int p = 0; p < MP; ++p) ar[i][p] = lds4[lbase[p] + soff];
+        ++tf;
+        if (++chunk == nch) { chunk = 0; if (++tb == a.k) { tb = 0; ++ta; } }
+    };
+    auto mfmas = [&](int i) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int p = 0; p < MP; ++p) acc[p] = mfma_f32<32>(wr[i][s], ar[i][p][s], acc[p]);
+    };
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+        wr[i] = (v4f){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int p = 0; p < MP; ++p) ar[i][p] = (v4f){0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int i = 0; i < D; ++i)
+        if (i < steps) fetch(i);
+    int t = 0;
+    for (; t + 2 * D <= steps; t += D) {          // every step of the group has a successor D ahead
+#pragma unroll
+        for (int i = 0; i < D; ++i) { mfmas(i); fetch(i); }
+    }
+#pragma unroll
+    for (int i = 0; i < D; ++i)
+        if (t + i < steps) { mfmas(i); if (t + i + D < steps) fetch(i); }
+#pragma unroll
+    for (int i = 0; i < D; ++i)
+        if (t + D + i < steps) mfmas(i);
+
+    // ---- epilogue from the accumulators: register 4n + z of position tile p is channel
+    // oc0 + 8n + 4lg + z of position 32*(wp*MP + p) + lt
+#pragma unroll
+    for (int p = 0; p < MP; ++p) {
+        const int m = W * (wp * MP + p) + lt;
+        const int ty = m / a.Tx, tx = m - ty * a.Tx;
+        const int fy = ty0 + ty, fx = tx0 + tx;
+        const bool pos_ok = ty < a.Ty && fy < fh && fx < fw;
+        const long pos_off = (((long)b * a.Ho + (fy * a.d + ry)) * a.Wo + (fx * a.d + rx)) * a.Co;
+        v4f yv[4];
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            const int oc = oc0 + 8 * n + 4 * lg;
+            yv[n] = (v4f){0.f, 0.f, 0.f, 0.f};
+            if (a.mode == kDgradTanh && pos_ok && oc < a.Co) {
+                if ((a.Co & 3) == 0) yv[n] = load4(act_t + pos_off + oc);
+                else for (int z = 0; z < 4; ++z) if (oc + z < a.Co) yv[n][z] = load1(act_t + pos_off + oc + z);
+            }
+        }
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            const int oc = oc0 + 8 * n + 4 * lg;
+            if (!pos_ok || oc >= a.Co) continue;
+            v4f s = (v4f){acc[p][4 * n], acc[p][4 * n + 1], acc[p][4 * n + 2], acc[p][4 * n + 3]};
+            if (a.mode == kFwdTanh) {
+#pragma unroll
+                for (int z = 0; z < 4; ++z) s[z] = squash(s[z] + bias4[n][z], a.logistic);
+            } else if (a.mode == kFwdLinear) {
+                s += bias4[n];
+            } else if (a.mode == kDgradTanh) {
+#pragma unroll
+                for (int z = 0; z < 4; ++z) s[z] *= squash_slope(yv[n][z], a.logistic);
+            }
+            const int nv = a.Co - oc < 4 ? a.Co - oc : 4;
+            if (nv == 4 && (a.Co & 3) == 0) store4(out_t + pos_off + oc, s);
+            else for (int z = 0; z < nv; ++z) store1(out_t + pos_off + oc + z, s[z]);
+        }
+    }
+}
+
 }  // namespace mpcnn

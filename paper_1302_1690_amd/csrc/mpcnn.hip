@@ -103,7 +103,12 @@ struct Layer {
     size_t fwd_pack_off = 0, fwd_pack_len = 0, dgrad_pack_off = 0, dgrad_pack_len = 0;
 };
 
-struct TilePlan { int PT = 0, NW = 4, Ty = 0, Tx = 0, nty = 0, ntx = 0; size_t lds = 0; bool ok = false; };
+struct TilePlan {
+    int PT = 0, NW = 4, Ty = 0, Tx = 0, nty = 0, ntx = 0;
+    int MP = 0;           // > 0: conv_ts_kernel (result tiles dealt out to the waves), MP position tiles per wave
+    size_t lds = 0;
+    bool ok = false;
+};
 struct WgradPlan {
     bool ok = false;
     bool bm = false;      // bf16 storage: the bf16 matrix instruction, 16 positions per MFMA
@@ -164,6 +169,7 @@ struct mpcnn_net {
     float* d_params0 = nullptr;   // copy of the parameters a safeguarded step starts from
     double* d_scalar = nullptr;   // fp64 results of that step's reductions (8)
     int logistic = 0;             // squashing function of C and hidden FC layers: 0 tanh, 1 logistic
+    int hint_pt = 0, hint_mp = 0; // mpcnn_set_conv_tiling: 0 = the planner's choice
     // limited-memory BFGS: pairs in a ring of lb_m + 1 slots (one always free for the candidate)
     int lb_m = 0, lb_head = 0, lb_count = 0;
     bool lb_have_prev = false;
@@ -253,12 +259,48 @@ bool choose_tile(int fh, int fw, int max_pos, int k, size_t pitch_bytes, size_t 
 }
 
 // Tile plan of conv_mfma_kernel for a map of out_r x out_c positions at tap spacing d.
-TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, const ChanTiling& ct, bool bm)
+TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, const ChanTiling& ct, bool bm,
+                         int hint_pt = 0, int hint_mp = 0)
 {
     TilePlan best;
     double best_cost = 0;
     const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
     const size_t pitch = bm ? 16 * (size_t)(rpad / 8 + 1) : sizeof(float) * (rpad + 4);   // one halo position in LDS
+    if (!bm && ct.W == 32) {
+        // conv_ts_kernel: 32*PT positions x 32*OT channels, OT*PT/MP waves.  Cost of the busiest CU:
+        // its workgroups' matrix instructions one after the other, plus, once per round of
+        // co-resident workgroups, what is not hidden behind another's multiplications
+        // (staging the halo at ~8 bytes per cycle, a memory round trip, the stores).
+        const int steps = k * k * (rpad / 8);
+        for (int PT : {2, 4, 8})
+            for (int MP : {1, 2}) {
+                const int NW = ct.OT * PT / MP;
+                if (PT % MP || (NW != 4 && NW != 8)) continue;
+                if ((hint_pt && PT != hint_pt) || (hint_mp && MP != hint_mp)) continue;
+                // measured: a wave with one tile spends ~12 % more per instruction on operand
+                // fetches than one with two
+                const double t_mul1 = (double)steps * 4 * ct.OT * PT * 64 / 4 * (MP == 2 ? 1.0 : 1.12);
+                for (int ty = 1; ty <= std::min(fh, 32 * PT); ++ty)
+                    for (int tx = 1; tx <= std::min(fw, 32 * PT / ty); ++tx) {
+                        const size_t lds = std::max((size_t)(ty + k - 1) * (tx + k - 1) * pitch, (size_t)1024);
+                        if (lds > (size_t)150 * 1024) break;
+                        const int nty = ceil_div(fh, ty), ntx = ceil_div(fw, tx);
+                        const double wgs = (double)B * d * d * nty * ntx * ct.split;
+                        const int together = (int)std::max<size_t>(1, std::min<size_t>(16 / NW, (size_t)(160 * 1024) / lds));
+                        const double per_cu = std::ceil(wgs / kNumCU);
+                        // fewer than 8 waves on the CU leave SIMDs idle in every wait
+                        const double t_mul = t_mul1 * (NW * std::min<double>(together, per_cu) >= 8 ? 1.0 : 1.25);
+                        const double t_rest = 4000.0 + (double)lds / 8;
+                        const double cost = per_cu * t_mul + std::ceil(per_cu / together) * t_rest;
+                        if (!best.ok || cost < best_cost) {
+                            best.PT = PT; best.NW = NW; best.MP = MP; best.Ty = ty; best.Tx = tx;
+                            best.nty = nty; best.ntx = ntx; best.lds = lds; best.ok = true;
+                            best_cost = cost;
+                        }
+                    }
+            }
+        if (best.ok) return best;
+    }
     const int regs_per_tile = ct.W * ct.W / 64;
     for (int PT : {64 / ct.W, 128 / ct.W}) {            // 64 or 128 positions per workgroup
         if (ct.OT * PT * regs_per_tile > (ct.W == 16 ? 64 : 128)) continue;  // accumulator registers per lane
@@ -442,13 +484,13 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         size_t bytes = es * (size_t)B * r * c * ly.cout;
         max_act = std::max(max_act, bytes);
         if (ly.kind == MPCNN_MP) continue;
-        if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.k, ly.fwd_rpad, ly.fwd_ct, ly.fwd_bm);
+        if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.k, ly.fwd_rpad, ly.fwd_ct, ly.fwd_bm, net->hint_pt, net->hint_mp);
         if (training && ly.class_fused) {
             g->partial_n[l] = class_blocks((long)B * r * c);
             g->partial_len[l] = ly.p_len;
         } else if (training) {
             if (ly.dgrad_mfma && l > 0)
-                g->dgrad[l] = plan_conv_tiles(B, in_r, in_c, ly.dil, ly.k, ly.dgrad_rpad, ly.dgrad_ct, ly.dgrad_bm);
+                g->dgrad[l] = plan_conv_tiles(B, in_r, in_c, ly.dil, ly.k, ly.dgrad_rpad, ly.dgrad_ct, ly.dgrad_bm, net->hint_pt, net->hint_mp);
             g->wgrad[l] = plan_wgrad(ly, B, in_r, in_c, r, c, net->bf16);
             const WgradPlan& w = g->wgrad[l];
             g->partial_n[l] = w.ok ? w.slabs : w.chunks;
@@ -529,6 +571,9 @@ inline int grid_for(long total, int block = 256, int cap = 1 << 20)
 }
 
 // ------------------------------------------------------------------ MFMA launches
+// (OT, PT, MP) instances of conv_ts_kernel: OT*PT/MP is 4 or 8 waves
+#define CONV_TS_INSTANCES(X) \
+    X(4, 2, 1) X(4, 2, 2) X(4, 4, 2) X(2, 2, 1) X(2, 4, 1) X(2, 4, 2) X(2, 8, 2) X(1, 4, 1) X(1, 8, 1) X(1, 8, 2)
 template <int W, int OT, int PT, int NW, typename T>
 void launch_conv_inst(const mpcnn::ConvArgs& a, dim3 grid, size_t lds, hipStream_t st)
 {
@@ -553,10 +598,23 @@ bool launch_conv_bm(const mpcnn::ConvArgs& a, const ChanTiling& ct, const TilePl
     return false;
 }
 template <typename T>
+bool launch_conv_ts(const mpcnn::ConvArgs& a, const ChanTiling& ct, const TilePlan& tp, dim3 grid, hipStream_t st)
+{
+#define CASE(o, p, m)                                                                          \
+    if (ct.OT == o && tp.PT == p && tp.MP == m) {                                              \
+        mpcnn::conv_ts_kernel<o, p, m, T><<<grid, 64 * o * p / m, tp.lds, st>>>(a);            \
+        return true;                                                                           \
+    }
+    CONV_TS_INSTANCES(CASE)
+#undef CASE
+    return false;
+}
+template <typename T>
 bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, const TilePlan& tp, dim3 grid,
                       hipStream_t st, bool bm = false)
 {
     if (bm) return launch_conv_bm(a, ct, tp, grid, st);
+    if (tp.MP > 0) return launch_conv_ts<T>(a, ct, tp, grid, st);
 #define CASE(w, o, p)                                                                         \
     if (ct.W == w && ct.OT == o && tp.PT == p) {                                                \
         if (tp.NW == 8) launch_conv_inst<w, o, p, 8, T>(a, grid, tp.lds, st);                   \
@@ -604,6 +662,9 @@ mpcnn_status set_lds_attrs_t()
     ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 8, T>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 8, T>));
     ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 4, T>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 4, 8, T>));
     ATTR((mpcnn::conv_mfma_kernel<16, 4, 4, 8, T>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 2, 8, T>));
+#define TS_ATTR(o, p, m) ATTR((mpcnn::conv_ts_kernel<o, p, m, T>));
+    CONV_TS_INSTANCES(TS_ATTR)
+#undef TS_ATTR
     ATTR((mpcnn::wgrad_mfma_kernel<1, T>)); ATTR((mpcnn::wgrad_mfma_kernel<2, T>));
     ATTR((mpcnn::wgrad_mfma_kernel<3, T>)); ATTR((mpcnn::wgrad_mfma_kernel<4, T>));
     ATTR((mpcnn::wgrad_mfma_kernel<5, T>)); ATTR((mpcnn::wgrad_mfma_kernel<6, T>));
@@ -1234,6 +1295,17 @@ mpcnn_status mpcnn_set_activation(mpcnn_net* net, mpcnn_activation kind)
     if (!net) return fail(MPCNN_EINVAL, "null net");
     if (kind != MPCNN_TANH && kind != MPCNN_LOGISTIC) return fail(MPCNN_EINVAL, "unknown activation %d", (int)kind);
     net->logistic = kind == MPCNN_LOGISTIC ? 1 : 0;
+    return MPCNN_OK;
+}
+
+mpcnn_status mpcnn_set_conv_tiling(mpcnn_net* net, int position_tiles, int tiles_per_wave)
+{
+    if (!net) return fail(MPCNN_EINVAL, "null net");
+    const bool pt_ok = position_tiles == 0 || position_tiles == 2 || position_tiles == 4 || position_tiles == 8;
+    const bool mp_ok = tiles_per_wave == 0 || tiles_per_wave == 1 || tiles_per_wave == 2;
+    if (!pt_ok || !mp_ok)
+        return fail(MPCNN_EINVAL, "conv tiling (%d, %d): position tiles 0/2/4/8, tiles per wave 0/1/2", position_tiles, tiles_per_wave);
+    net->hint_pt = position_tiles; net->hint_mp = tiles_per_wave;
     return MPCNN_OK;
 }
 

@@ -30,7 +30,7 @@ SYMBOLS = [
     "mpcnn_sgd_step", "mpcnn_get_activation", "mpcnn_get_argmax", "mpcnn_last_error",
     "mpcnn_profile_enable", "mpcnn_profile_read", "mpcnn_workspace_bytes_same", "mpcnn_seg_forward_same",
     "mpcnn_set_loss", "mpcnn_class_balance_weights", "mpcnn_seg_loss", "mpcnn_armijo_step",
-    "mpcnn_lbfgs_step", "mpcnn_lbfgs_reset", "mpcnn_set_activation",
+    "mpcnn_lbfgs_step", "mpcnn_lbfgs_reset", "mpcnn_set_activation", "mpcnn_set_conv_tiling",
     "mpcnn_workspace_bytes_banded", "mpcnn_seg_backward_banded",
 ]
 
@@ -98,6 +98,7 @@ def lib():
         L.mpcnn_workspace_bytes_banded.restype = sz
         L.mpcnn_seg_backward_banded.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp, sz, vp]
         L.mpcnn_set_activation.argtypes = [vp, i]
+        L.mpcnn_set_conv_tiling.argtypes = [vp, i, i]
         L.mpcnn_class_balance_weights.argtypes = [vp, vp, i, i, i, vp, vp, vp]
         L.mpcnn_seg_backward.argtypes = [vp, vp, vp, vp, i, i, i, vp, vp, vp, sz, vp]
         L.mpcnn_sgd_step.argtypes = [vp, C.c_float, C.c_float, vp]
@@ -270,6 +271,10 @@ class Net:
     def set_activation(self, kind: str):
         """"tanh" (default) or "logistic": the squashing function of C and hidden FC layers."""
         _check(lib().mpcnn_set_activation(self._h, {"tanh": 0, "logistic": 1}.get(kind, -1)))
+
+    def set_conv_tiling(self, position_tiles: int = 0, tiles_per_wave: int = 0):
+        """Restrict the matrix-core convolution kernel's tiling (0 = the planner's choice)."""
+        _check(lib().mpcnn_set_conv_tiling(self._h, position_tiles, tiles_per_wave))
 
     def class_balance_weights(self, labels, stream=None):
         """labels [B,H,W] int32 cuda -> pixw [B,H,W] fp32 cuda, 1/N_k at output pixels of class k."""

@@ -70,7 +70,7 @@ def check_grads(cfg, g_gpu, g_ref, tol=None):
     return worst
 
 
-def run_gpu(cfg, img, lab, params, pixw=None, net=None, loss_fn="mcce", squash="tanh"):
+def run_gpu(cfg, img, lab, params, pixw=None, net=None, loss_fn="mcce", squash="tanh", tiling=None):
     own = net is None
     if own:
         net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch,
@@ -78,6 +78,8 @@ def run_gpu(cfg, img, lab, params, pixw=None, net=None, loss_fn="mcce", squash="
         net.set_params(params)
         net.set_loss(loss_fn)
         net.set_activation(squash)
+        if tiling is not None:
+            net.set_conv_tiling(*tiling)
     B, _, H, W = img.shape
     d_img = torch.from_numpy(img).cuda()
     d_lab = torch.from_numpy(lab).cuda()
@@ -178,7 +180,7 @@ def check_argmax(cfg, net, img, params, with_oracle=True, layers=None, squash="t
 
 
 def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_layers=True, loss_fn="mcce",
-                squash="tanh"):
+                squash="tanh", tiling=None):
     img, lab = wl.make_inputs(cfg)
     params = wl.make_params(cfg)
     pixw = None
@@ -188,7 +190,7 @@ def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_lay
         lab = lab.copy()
         lab[np.random.default_rng(78).random(lab.shape) < 0.1] = -1
     say("case %s B=%d %dx%d" % (cfg.name, cfg.batch, cfg.height, cfg.width))
-    net, probs, loss, grads = run_gpu(cfg, img, lab, params, pixw, loss_fn=loss_fn, squash=squash)
+    net, probs, loss, grads = run_gpu(cfg, img, lab, params, pixw, loss_fn=loss_fn, squash=squash, tiling=tiling)
     ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, pixw, None, net, loss_fn, squash)
     say("  near-tie windows %d, resolved the other way on the GPU %d" % (n_near, n_alt))
     e_p = np.abs(probs - ref["probs"]).max()
@@ -275,6 +277,27 @@ def test_first_pool_routing_fused_with_image_layer_gradient():
     net2 = ((C, 12, 5), (MP, 0, 2), (C, 8, 2), (FC, 10, 0), (FC, 2, 0))
     full_parity(wl.Workload("l0_pool2_two_channels", net2, 12, 2, 2, 2, 29, 50, 0.3, "ellipses",
                             seed_image=1113, seed_label=2113, seed_param=3113), squash="logistic")
+
+
+def test_every_conv_tiling():
+    """Every instance of the matrix-core convolution kernel (position tiles per workgroup x
+    tiles per wave, for layers of 1, 2 and 4 channel tiles; fp32 and bf16 storage) against the
+    oracle: config 1's net has 32-, 64- and 100-map layers in both directions."""
+    for pt, mp in ((2, 1), (2, 2), (4, 1), (4, 2), (8, 1), (8, 2)):
+        say("conv tiling: %d position tiles, %d per wave" % (pt, mp))
+        full_parity(wl.crop(wl.CONFIGS[1], 1, 75, 81), check_layers=False, tiling=(pt, mp))
+        # bf16 storage, channel counts that keep the layers on the fp32 matrix instruction
+        # (36 -> 100 maps: 4 channel tiles forward, 2 backward; 100 -> 32: 1 tile forward)
+        layers = ((C, 36, 3), (MP, 0, 2), (C, 100, 3), (MP, 0, 2), (FC, 32, 0), (FC, 3, 0))
+        full_parity(wl.Workload("bf16_odd_tiling", layers, 14, 3, 3, 1, 47, 40, 0.25, "ellipses", dtype="bf16",
+                                seed_image=1114, seed_label=2114, seed_param=3114), check_layers=False,
+                    tiling=(pt, mp))
+    net = mpcnn.Net(wl.CONFIGS[0].layers, wl.CONFIGS[0].in_channels, wl.CONFIGS[0].patch)
+    for bad in ((3, 1), (2, 3), (-2, 0), (16, 2)):
+        with pytest.raises(mpcnn.MpcnnError):
+            net.set_conv_tiling(*bad)
+    net.set_conv_tiling(0, 0)
+    net.close()
 
 
 def test_logistic_activation():
