@@ -12,9 +12,10 @@
 // B[position l/32][column l%32].
 //
 // Tile = 4 rows x Tx columns of one residue class (one fragment of the MPF storage).  Its
-// input halo sits in LDS channel-major, [c][halo row][halo col], so the 32 lanes of an A
-// operand (32 consecutive gradient rows = consecutive channels of a tap) hit 32 different
-// banks and successive columns are successive words; the delta tile sits as
+// input halo sits in LDS as [channel quad][halo row][halo col][4 channels] with an odd number
+// of positions per quad plane, so the 32 lanes of an A operand (32 consecutive gradient rows =
+// consecutive channels of a tap) hit 32 different banks, successive columns are 16 bytes apart,
+// and the loading waves write a 128-bit global item with one 128-bit LDS store; the delta tile sits as
 // [tile row][32-column block of the result][col][32].  The number of result tiles per wave (MW) is a template parameter so
 // that the multiply loop has no branches; tiles beyond the gradient's last row tile compute
 // on valid addresses and are never stored.  The four waves split the 32 x 32 result tiles along rows (wm),
@@ -32,7 +33,7 @@ namespace mpcnn {
 
 constexpr int kWgBmMaxTiles = 5;  // row tiles per wave of wgrad_bm_kernel, which owns two column tiles for each
 constexpr int kWgMaxTiles = 11;   // 32x32 result tiles per wave (16 accumulator registers each; two waves share a SIMD's 512)
-constexpr int kWgStageH = 8;      // 128-bit items of the input halo one thread stages per tile
+constexpr int kWgStageH = 8;      // 128-bit items of the input halo one thread stages per tile, or twice as many (template parameter)
 constexpr int kWgStageD = 8;      // ... of the delta tile
 
 struct WgradArgs {
@@ -57,10 +58,10 @@ __device__ __forceinline__ unsigned magic_div(unsigned n, unsigned magic, unsign
     return x == 1 ? n : __umulhi(n, magic);
 }
 
-template <int MW, typename T>
+template <int MW, int HLT, typename T>   // HLT: halo items per loading thread and tile (kWgStageH or twice that)
 __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
 {
-    constexpr int HL = kWgStageH, DL = kWgStageD;
+    constexpr int HL = HLT, DL = kWgStageD;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -75,13 +76,15 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
     const int rpw = a.wk == 4 ? 1 : (a.wk == 2 ? 2 : 4);   // tile rows per wave
     const int hwp = a.TxP + a.k - 1;            // halo row pitch
     const int hh = 4 + a.k - 1;
-    const int HP = (hh * hwp) | 1;              // channel pitch of the halo (floats, odd)
+    const int QP = 4 * ((hh * hwp) | 1);        // pitch of a channel quad's plane in the halo (floats; odd number of positions)
+    const int cq = (a.Ci + 3) >> 2;
     // delta tile [tile row][block of 32 columns of the result][col][32]: a wave's B operands of
     // successive columns are 128 bytes apart whatever wn is; 32 floats of padding per block keep
     // the 128-bit staging writes of neighbouring blocks on different banks
     const int OB = a.TxP * 32 + 32, RB = wn * OB;
     const int dt_f = 4 * RB;                    // delta tile first (128-bit aligned), halo behind it
-    const int buf_f = (dt_f + a.Ci * HP + 3) & ~3;
+    const int buf_f = dt_f + cq * QP;
+    const int trash_f = 2 * buf_f + 16;         // 16 bytes that nobody reads, behind the slack of the second buffer
 
     const int rows_total = a.k * a.k * a.Ci;
     // ---- a multiplying wave's result tiles: rows 32*(mt0 + p), p < np; columns 32*nt
@@ -125,7 +128,6 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
 
     if (loader) {
         // ================= loading waves: global memory -> LDS, one tile ahead =================
-        const int cq = (a.Ci + 3) >> 2;
         const int h_items = hh * hwp * cq;
         const int dq_shift = 3 + (wn >> 1);     // 8 * wn 128-bit items per delta position
         const int d_items = (4 * a.TxP) << dq_shift;
@@ -138,20 +140,26 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
         // outside the input are clamped (any finite value will do there: the matching deltas
         // are zero); delta items outside the class are loaded from a safe address and zeroed on
         // the way to LDS.
+        // Tiles whose halo and delta lie inside the tensors (all but those on the lower / right
+        // border) take every load at a fixed per-thread offset from a per-tile scalar base: these
+        // waves' instructions issue only in the gaps of their SIMD's MFMA stream, one every ~64
+        // cycles, so the count of instructions per item is what bounds the staging.
         unsigned h_yx[HL];   // (halo row * d) << 16 | halo col * d
-        int h_dst[HL];       // channel 4q << 20 | float index in a buffer of that channel at this position, -1 = none
+        int h_dst[HL];       // channel 4q << 20 | float index in a buffer of the item (its quad plane, its position), -1 = none
+        unsigned h_off[HL];  // element offset of the item from the halo's first element (0 if none)
         unsigned d_tyx[DL];  // tile row << 16 | tile col
         int d_rel[DL];       // float offset of the item from the tile's first delta, -1 = never inside
-        int d_dst[DL];       // float index in a buffer, -1 = none
+        int d_dst[DL];       // float index in a buffer (of the 16 unread bytes for items never inside: added to either buffer's base it stays there), -1 = none
 #pragma unroll
         for (int u = 0; u < HL; ++u) {
             const unsigned it = ltid + 256 * u;
-            h_yx[u] = 0; h_dst[u] = -1;
+            h_yx[u] = 0; h_dst[u] = -1; h_off[u] = 0;
             if (it < (unsigned)h_items) {
                 const unsigned pos = magic_div(it, a.mg_cq, cq), q = it - pos * cq;
                 const unsigned ha = magic_div(pos, a.mg_hwp, hwp), hb = pos - ha * hwp;
                 h_yx[u] = ((ha * a.d) << 16) | (hb * a.d);
-                h_dst[u] = (int)((4 * q) << 20 | (dt_f + 4 * q * HP + ha * hwp + hb));
+                h_dst[u] = (int)((4 * q) << 20 | (dt_f + q * QP + 4 * (ha * hwp + hb)));
+                h_off[u] = ((ha * a.d) * a.Wi + hb * a.d) * a.Ci + 4 * q;
             }
         }
 #pragma unroll
@@ -165,8 +173,17 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                 d_tyx[u] = (ty << 16) | tx;
                 d_dst[u] = (int)((q >> 3) * OB + 4 * (q & 7) + ty * RB + tx * 32);
                 if (tx < (unsigned)a.Tx && oc < a.Co) d_rel[u] = (int)((ty * a.d * a.Wo + tx * a.d) * a.Co) + oc;
+                else {
+                    // never inside: zero in both buffers now, and from here on the item's store
+                    // goes to the unread bytes
+                    const v4f z4 = {0.f, 0.f, 0.f, 0.f};
+                    *reinterpret_cast<v4f*>(lds + d_dst[u]) = z4;
+                    *reinterpret_cast<v4f*>(lds + buf_f + d_dst[u]) = z4;
+                    d_dst[u] = -2;
+                }
             }
         }
+        const int halo_h = (hh - 1) * a.d, halo_w = (hwp - 1) * a.d;   // reach of the halo below / right of its first element
         auto stage = [&](int tile, float* buf) {
             const TileGeom t = decode(tile);
             const T* in_b = static_cast<const T*>(a.in) + (long)t.b * a.Hi * a.Wi * a.Ci;
@@ -175,7 +192,18 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
             const int dbase = (y0 * a.Wo + x0) * a.Co;
             v4f hr[HL], dr[DL];
             unsigned okmask = 0;
+            const bool inside = vec_in && vec_dy && t.rows >= 4 && t.cols >= a.Tx &&
+                                y0 + halo_h < a.Hi && x0 + halo_w < a.Wi;     // uniform
             // all loads of the tile first: one trip to memory
+            if (inside) {
+                const T* in_t0 = in_b + (unsigned)(y0 * a.Wi + x0) * a.Ci;
+                const T* dy_t0 = dy_b + dbase;
+#pragma unroll
+                for (int u = 0; u < HL; ++u) hr[u] = load4(in_t0 + h_off[u]);
+#pragma unroll
+                for (int u = 0; u < DL; ++u) dr[u] = load4(dy_t0 + (d_rel[u] < 0 ? 0 : d_rel[u]));
+                okmask = ~0u;
+            } else {
 #pragma unroll
             for (int u = 0; u < HL; ++u) {
                 int iy = y0 + (int)(h_yx[u] >> 16), ix = x0 + (int)(h_yx[u] & 0xffffu);
@@ -201,25 +229,19 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                     for (int z = 0; z < 4; ++z) dr[u][z] = (ok && oc + z < a.Co) ? load1(dy_b + off + z) : 0.f;
                 }
             }
-#pragma unroll
-            for (int u = 0; u < HL; ++u) {
-                if (u < h_full || h_dst[u] >= 0) {      // first test is uniform: whole rounds store unmasked
-                    float* p = buf + (h_dst[u] & 0xfffff);
-                    if (vec_in) {
-                        p[0] = hr[u][0]; p[HP] = hr[u][1]; p[2 * HP] = hr[u][2]; p[3 * HP] = hr[u][3];
-                    } else {
-                        const int q4 = h_dst[u] >> 20;
-#pragma unroll
-                        for (int z = 0; z < 4; ++z)
-                            if (q4 + z < a.Ci) p[z * HP] = hr[u][z];
-                    }
-                }
             }
 #pragma unroll
+            for (int u = 0; u < HL; ++u)
+                if (u < h_full || h_dst[u] >= 0)        // first test is uniform: whole rounds store unmasked
+                    *reinterpret_cast<v4f*>(buf + (h_dst[u] & 0xfffff)) = hr[u];
+            float* const trash = lds + trash_f;
+#pragma unroll
             for (int u = 0; u < DL; ++u) {
-                if (u < d_full || d_dst[u] >= 0) {
+                if (u < d_full || d_dst[u] != -1) {
                     const v4f z4 = {0.f, 0.f, 0.f, 0.f};
-                    *reinterpret_cast<v4f*>(buf + d_dst[u]) = ((okmask >> u) & 1u) ? dr[u] : z4;
+                    float* dst = d_dst[u] == -2 ? trash : buf + d_dst[u];
+                    if (inside) *reinterpret_cast<v4f*>(dst) = dr[u];
+                    else *reinterpret_cast<v4f*>(dst) = ((okmask >> u) & 1u) ? dr[u] : z4;
                 }
             }
         };
@@ -239,11 +261,11 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
 #pragma unroll
     for (int p = 0; p < MW; ++p) {
         const unsigned row = 32u * (mt0 + p) + lm;
-        unsigned o = dt_f + lk;
+        unsigned o = dt_f + 4 * lk;
         if (p < np && row < (unsigned)rows_total) {
             const unsigned tap = magic_div(row, a.mg_ci, a.Ci), c = row - tap * a.Ci;
             const unsigned ta = magic_div(tap, a.mg_k, a.k), tb = tap - ta * a.k;
-            o += c * HP + ta * hwp + tb;
+            o += (c >> 2) * QP + (c & 3) + 4 * (ta * hwp + tb);
         }
         aoff[p] = 4u * o;
     }
@@ -279,7 +301,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
 #pragma unroll
             for (int p = 0; p < MW; ++p) {
                 acc[p] = __builtin_amdgcn_mfma_f32_32x32x2f32(cur[p], bcur, acc[p], 0, 0, 0);
-                nxt[p] = *reinterpret_cast<const float*>(ldsb + aoff[p] + chunk * 8);
+                nxt[p] = *reinterpret_cast<const float*>(ldsb + aoff[p] + chunk * 32);
             }
             bsum += bcur;
         };
@@ -303,11 +325,11 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                 acc[p] = __builtin_amdgcn_mfma_f32_32x32x2f32(aB[p], bB, acc[p], 0, 0, 0);
             bsum += bB;
         };
-        move(4u * (unsigned)(cur * buf_f + r0 * hwp), 0);
+        move(4u * (unsigned)(cur * buf_f) + 16u * (unsigned)(r0 * hwp), 0);
         bA = *reinterpret_cast<const float*>(ldsb + bp);
 #pragma unroll
         for (int p = 0; p < MW; ++p) aA[p] = *reinterpret_cast<const float*>(ldsb + aoff[p]);
-        const unsigned row_a = 4u * hwp, row_b = 4u * RB;   // bytes from a row to the next
+        const unsigned row_a = 16u * hwp, row_b = 4u * RB;   // bytes from a row to the next
         for (int row = r0; row < r1; ++row) {
             const bool jump = row + 1 < r1;   // at the row's end fetch the next row's first chunk
             int left = nch;
@@ -315,17 +337,17 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
             while (left >= 8) {
                 left -= 8;
                 const bool end = left == 0 && jump;
-                block(std::integral_constant<int, 8>(), end ? row_a - pa : 64u, end ? row_b - pb : 2048u);
-                pa += 64; pb += 2048;
+                block(std::integral_constant<int, 8>(), end ? row_a - pa : 256u, end ? row_b - pb : 2048u);
+                pa += 256; pb += 2048;
             }
             if (left & 4) {
                 left -= 4;
                 const bool end = left == 0 && jump;
-                block(std::integral_constant<int, 4>(), end ? row_a - pa : 32u, end ? row_b - pb : 1024u);
-                pa += 32; pb += 1024;
+                block(std::integral_constant<int, 4>(), end ? row_a - pa : 128u, end ? row_b - pb : 1024u);
+                pa += 128; pb += 1024;
             }
             if (left & 2) {
-                block(std::integral_constant<int, 2>(), jump ? row_a - pa : 16u, jump ? row_b - pb : 512u);
+                block(std::integral_constant<int, 2>(), jump ? row_a - pa : 64u, jump ? row_b - pb : 512u);
             }
         }
 #pragma unroll

@@ -116,6 +116,7 @@ struct WgradPlan {
     int Mt = 0, Nt = 0, wm = 0, wn = 0, wk = 0, mw = 0, gm = 0, gn = 0;
     size_t lds = 0;
     size_t plen = 0;      // floats per partial result (tiled layout)
+    int hl = 0;           // halo items per loading thread and tile (fp32 matrix instruction kernel)
     // direct kernel fallback
     int rows_per_chunk = 0, chunks = 0;
 };
@@ -418,23 +419,45 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
         const int cq = ceil_div(ly.cin, 4), hh = 4 + k - 1;
         const int target = std::max(1, kNumCU / (w.gm * w.gn));
         const double col_ticks = (4.0 / w.wk) * w.mw * 32.0;
-        double best = -1;
-        for (int tx = 1; tx <= fw; ++tx) {
-            const int txp = ceil_div(tx, 4) * 4, hwp = txp + k - 1;
-            const size_t buf = ((size_t)4 * w.wn * (txp * 32 + 32) + (size_t)ly.cin * ((hh * hwp) | 1) + 3) & ~(size_t)3;
-            size_t lds = 2 * buf * sizeof(float) + 64;   // slack: the operand prefetch runs one chunk ahead
-            if (w.wk > 1) lds = std::max(lds, (size_t)2 * w.mw * 4096);
-            lds = std::max(lds, (size_t)1024);
-            if (hh * hwp * cq > mpcnn::kWgStageH * 256 || 4 * txp * 8 * w.wn > mpcnn::kWgStageD * 256 ||
-                lds > kWgradLdsCap)
-                continue;
-            const int ntx = ceil_div(fw, tx);
-            const long tiles = (long)B * d * d * ceil_div(fh, 4) * ntx;
-            if (tiles * std::max(std::max(ntx, ceil_div(fh, 4)), d) >= (1ll << 31)) continue;
-            const long tps = (tiles + target - 1) / target;
-            const double cost = (double)tps * (txp * col_ticks + 1500.0);
-            if (best < 0 || cost <= best) { best = cost; w.Tx = tx; w.TxP = txp; w.lds = lds; }
+        // The loading threads hold a tile's items in registers: 8 halo items each, or, where
+        // that keeps the tile narrower than 16 columns (many channels, large filters), 16 -
+        // the wider instance issues 8 more loads per tile whether it needs them or not.
+        // The loading waves issue in the gaps of the MFMA stream, roughly one instruction per
+        // 64 cycles and six per 128-bit item, behind one trip to memory.
+        auto tile_time = [&](int txp, bool with_load) {
+            const double t_load = 3000.0 + 6.0 * 64.0 * ceil_div(hh * (txp + k - 1) * cq + 4 * txp * 8 * w.wn, 256);
+            return (with_load ? std::max(txp * col_ticks, t_load) : txp * col_ticks) + 1500.0;
+        };
+        struct Pick { double cost = -1; int Tx = 0, TxP = 0; size_t lds = 0; long tps = 0; };
+        auto pass = [&](int hl, bool with_load) {
+            Pick pk;
+            for (int tx = 1; tx <= fw; ++tx) {
+                const int txp = ceil_div(tx, 4) * 4, hwp = txp + k - 1;
+                const size_t buf = (size_t)4 * w.wn * (txp * 32 + 32) + (size_t)4 * cq * ((hh * hwp) | 1);
+                size_t lds = 2 * buf * sizeof(float) + 128;  // slack: the operand prefetch runs one chunk ahead; 16 unread bytes behind it
+                if (w.wk > 1) lds = std::max(lds, (size_t)2 * w.mw * 4096);
+                lds = std::max(lds, (size_t)1024);
+                if (hh * hwp * cq > hl * 256 || 4 * txp * 8 * w.wn > mpcnn::kWgStageD * 256 || lds > kWgradLdsCap)
+                    continue;
+                const int ntx = ceil_div(fw, tx);
+                const long tiles = (long)B * d * d * ceil_div(fh, 4) * ntx;
+                if (tiles * std::max(std::max(ntx, ceil_div(fh, 4)), d) >= (1ll << 31)) continue;
+                const long tps = (tiles + target - 1) / target;
+                const double cost = (double)tps * tile_time(txp, with_load);
+                if (pk.cost < 0 || cost <= pk.cost) { pk.cost = cost; pk.Tx = tx; pk.TxP = txp; pk.lds = lds; pk.tps = tps; }
+            }
+            return pk;
+        };
+        Pick pk = pass(mpcnn::kWgStageH, false);
+        w.hl = mpcnn::kWgStageH;
+        if (pk.cost < 0 || (pk.TxP < 16 && pk.Tx < fw)) {
+            const Pick wide = pass(2 * mpcnn::kWgStageH, true);
+            if (wide.cost >= 0 && (pk.cost < 0 || wide.cost < (double)pk.tps * tile_time(pk.TxP, true))) {
+                pk = wide; w.hl = 2 * mpcnn::kWgStageH;
+            }
         }
+        const double best = pk.cost;
+        w.Tx = pk.Tx; w.TxP = pk.TxP; w.lds = pk.lds;
         if (best >= 0) {
             w.nty = ceil_div(fh, 4); w.ntx = ceil_div(fw, w.Tx);
             w.tiles_total = B * d * d * w.nty * w.ntx;
@@ -627,9 +650,12 @@ bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, const Tile
     return false;
 }
 template <typename T>
-void launch_wgrad_mfma(const mpcnn::WgradArgs& a, dim3 grid, size_t lds, hipStream_t st)
+void launch_wgrad_mfma(const mpcnn::WgradArgs& a, int hl, dim3 grid, size_t lds, hipStream_t st)
 {
-#define CASE(m) case m: mpcnn::wgrad_mfma_kernel<m, T><<<grid, 512, lds, st>>>(a); return;
+#define CASE(m) case m:                                                                                   \
+        if (hl > mpcnn::kWgStageH) mpcnn::wgrad_mfma_kernel<m, 2 * mpcnn::kWgStageH, T><<<grid, 512, lds, st>>>(a); \
+        else mpcnn::wgrad_mfma_kernel<m, mpcnn::kWgStageH, T><<<grid, 512, lds, st>>>(a);                         \
+        return;
     switch (a.mw) {
     CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11)
     }
@@ -665,12 +691,9 @@ mpcnn_status set_lds_attrs_t()
 #define TS_ATTR(o, p, m) ATTR((mpcnn::conv_ts_kernel<o, p, m, T>));
     CONV_TS_INSTANCES(TS_ATTR)
 #undef TS_ATTR
-    ATTR((mpcnn::wgrad_mfma_kernel<1, T>)); ATTR((mpcnn::wgrad_mfma_kernel<2, T>));
-    ATTR((mpcnn::wgrad_mfma_kernel<3, T>)); ATTR((mpcnn::wgrad_mfma_kernel<4, T>));
-    ATTR((mpcnn::wgrad_mfma_kernel<5, T>)); ATTR((mpcnn::wgrad_mfma_kernel<6, T>));
-    ATTR((mpcnn::wgrad_mfma_kernel<7, T>)); ATTR((mpcnn::wgrad_mfma_kernel<8, T>));
-    ATTR((mpcnn::wgrad_mfma_kernel<9, T>)); ATTR((mpcnn::wgrad_mfma_kernel<10, T>));
-    ATTR((mpcnn::wgrad_mfma_kernel<11, T>));
+#define WG(m) ATTR((mpcnn::wgrad_mfma_kernel<m, mpcnn::kWgStageH, T>)); ATTR((mpcnn::wgrad_mfma_kernel<m, 2 * mpcnn::kWgStageH, T>));
+    WG(1) WG(2) WG(3) WG(4) WG(5) WG(6) WG(7) WG(8) WG(9) WG(10) WG(11)
+#undef WG
     if constexpr (std::is_same<T, mpcnn::bf16>::value) {
 #define ROW(m) ATTR((mpcnn::wgrad_bm_kernel<m, 1>)); ATTR((mpcnn::wgrad_bm_kernel<m, 2>)); \
                ATTR((mpcnn::wgrad_bm_kernel<m, 3>)); ATTR((mpcnn::wgrad_bm_kernel<m, 4>))
@@ -983,7 +1006,7 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                            launch_wgrad_bm(a, wp.TxP / 16, grid, wp.lds, st));
                 else
                     LAUNCH("wgrad_mfma", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
-                           launch_wgrad_mfma<T>(a, grid, wp.lds, st));
+                           launch_wgrad_mfma<T>(a, wp.hl, grid, wp.lds, st));
             } else if constexpr (!kF32) {
                 return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             } else {

@@ -300,6 +300,20 @@ def test_every_conv_tiling():
     net.close()
 
 
+def test_weight_gradient_of_a_many_channel_layer():
+    """128 input channels under a 3x3 filter: the halo of a weight-gradient tile 16 columns wide
+    no longer fits 8 items per loading thread, so the instance with 16 takes over (the fragments
+    here are 36+ columns wide); full oracle, ragged sizes, at spacings 1 and 2."""
+    # patch 8 -> 6 -> 4 -> (MP2) 2 -> FC over 2x2
+    layers = ((C, 128, 3), (C, 32, 3), (MP, 0, 2), (FC, 8, 0), (FC, 2, 0))
+    full_parity(wl.Workload("wide_halo_d1", layers, 8, 1, 2, 1, 45, 49, 0.12, "ellipses",
+                            seed_image=1115, seed_label=2115, seed_param=3115), check_layers=False)
+    # patch 14 -> 12 -> (MP2) 6 -> 4 -> 2 -> FC over 2x2: the 128-channel layer at spacing 2
+    layers = ((C, 16, 3), (MP, 0, 2), (C, 128, 3), (C, 32, 3), (FC, 8, 0), (FC, 2, 0))
+    full_parity(wl.Workload("wide_halo_d2", layers, 14, 1, 2, 1, 93, 88, 0.12, "ellipses",
+                            seed_image=1116, seed_label=2116, seed_param=3116), check_layers=False)
+
+
 def test_logistic_activation():
     """The logistic function instead of tanh in every C and hidden FC layer: matrix-core kernels
     (config 1's net), the direct kernels (tiny net), MSE on top, and bf16 storage."""
