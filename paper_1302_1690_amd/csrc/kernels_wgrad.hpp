@@ -94,6 +94,9 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
     const int nt = blockIdx.z * wn + nidx;
     const bool active = !loader && np > 0 && nt < a.Nt;
 
+    // MFMA results kept in AccVGPRs (an empty asm operand in one makes the compiler select
+    // that form): the matrix pipe then leaves the ArchVGPR ports to the loading waves
+    if constexpr (MW <= 7) { float agpr_hint = 0.f; asm volatile("" : "+a"(agpr_hint)); }
     v16f acc[MW];
 #pragma unroll
     for (int p = 0; p < MW; ++p)
@@ -204,6 +207,16 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                 for (int u = 0; u < DL; ++u) dr[u] = load4(dy_t0 + (d_rel[u] < 0 ? 0 : d_rel[u]));
                 okmask = ~0u;
             } else {
+            if (vec_in) {
+                // a halo element outside the input meets only zero deltas, so any finite value
+                // will do for it: the offset is merely kept inside this image's tensor
+                const unsigned base = (unsigned)(y0 * a.Wi + x0) * a.Ci, last = (unsigned)(a.Hi * a.Wi * a.Ci) - 4u;
+#pragma unroll
+                for (int u = 0; u < HL; ++u) {
+                    const unsigned off = base + h_off[u];
+                    hr[u] = load4(in_b + (off < last ? off : last));
+                }
+            } else {
 #pragma unroll
             for (int u = 0; u < HL; ++u) {
                 int iy = y0 + (int)(h_yx[u] >> 16), ix = x0 + (int)(h_yx[u] & 0xffffu);
@@ -211,11 +224,9 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                 ix = ix < a.Wi ? ix : a.Wi - 1;
                 const int q4 = h_dst[u] < 0 ? 0 : h_dst[u] >> 20;
                 const unsigned off = (unsigned)(iy * a.Wi + ix) * a.Ci + q4;   // in elements
-                if (vec_in) hr[u] = load4(in_b + off);
-                else {
 #pragma unroll
-                    for (int z = 0; z < 4; ++z) hr[u][z] = q4 + z < a.Ci ? load1(in_b + off + z) : 0.f;
-                }
+                for (int z = 0; z < 4; ++z) hr[u][z] = q4 + z < a.Ci ? load1(in_b + off + z) : 0.f;
+            }
             }
 #pragma unroll
             for (int u = 0; u < DL; ++u) {
