@@ -144,9 +144,9 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
         // are zero); delta items outside the class are loaded from a safe address and zeroed on
         // the way to LDS.
         // Tiles whose halo and delta lie inside the tensors (all but those on the lower / right
-        // border) take every load at a fixed per-thread offset from a per-tile scalar base: these
-        // waves' instructions issue only in the gaps of their SIMD's MFMA stream, one every ~64
-        // cycles, so the count of instructions per item is what bounds the staging.
+        // border) take every load at a fixed per-thread offset from a per-tile scalar base: the
+        // multiplying waves wait for these waves at every tile's barrier, so what a tile costs
+        // here beyond its trip to memory is kept as small as possible.
         unsigned h_yx[HL];   // (halo row * d) << 16 | halo col * d
         int h_dst[HL];       // channel 4q << 20 | float index in a buffer of the item (its quad plane, its position), -1 = none
         unsigned h_off[HL];  // element offset of the item from the halo's first element (0 if none)

@@ -422,8 +422,8 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
         // The loading threads hold a tile's items in registers: 8 halo items each, or, where
         // that keeps the tile narrower than 16 columns (many channels, large filters), 16 -
         // the wider instance issues 8 more loads per tile whether it needs them or not.
-        // The loading waves issue in the gaps of the MFMA stream, roughly one instruction per
-        // 64 cycles and six per 128-bit item, behind one trip to memory.
+        // Staging time of a tile (estimate used to compare the two instances): one trip to
+        // memory plus a few hundred cycles per round of 256 items.
         auto tile_time = [&](int txp, bool with_load) {
             const double t_load = 3000.0 + 6.0 * 64.0 * ceil_div(hh * (txp + k - 1) * cq + 4 * txp * 8 * w.wn, 256);
             return (with_load ? std::max(txp * col_ticks, t_load) : txp * col_ticks) + 1500.0;
