@@ -855,8 +855,11 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 a.Ty = tp.Ty; a.Tx = tp.Tx; a.nty = tp.nty; a.ntx = tp.ntx;
                 a.mode = ly.tanh_out ? kFwdTanh : kFwdLinear; a.logistic = net->logistic;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
+                bool launched = false;
                 LAUNCH("conv_fwd_mfma", l, step, flops, bytes,
-                       launch_conv_mfma<T>(a, ly.fwd_ct, tp, grid, st, ly.fwd_bm));
+                       launched = launch_conv_mfma<T>(a, ly.fwd_ct, tp, grid, st, ly.fwd_bm));
+                if (!launched)   // a plan without a kernel instance: a planner bug, never a silent skip
+                    return fail(MPCNN_EUNSUPPORTED, "layer %zu: no convolution kernel instance for its forward plan", l);
             } else if (!kF32 && l == 0 && ly.dil == 1 && Ci <= 4 && ly.cout <= 64 && (ly.k == 3 || ly.k == 5 || ly.k == 7)) {
                 // bf16 storage, the image layer: short reduction on the bf16 matrix instruction
                 FirstBmArgs a{};
@@ -1030,8 +1033,11 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.Ty = tp.Ty; a.Tx = tp.Tx; a.nty = tp.nty; a.ntx = tp.ntx;
                 a.mode = below_tanh ? kDgradTanh : kDgradPlain; a.logistic = net->logistic;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.dgrad_ct.split);
+                bool launched = false;
                 LAUNCH("conv_dgrad_mfma", li, dstep, flops, dbytes,
-                       launch_conv_mfma<T>(a, ly.dgrad_ct, tp, grid, st, ly.dgrad_bm));
+                       launched = launch_conv_mfma<T>(a, ly.dgrad_ct, tp, grid, st, ly.dgrad_bm));
+                if (!launched)
+                    return fail(MPCNN_EUNSUPPORTED, "layer %zu: no convolution kernel instance for its data-gradient plan", li);
             } else if constexpr (!kF32) {
                 return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             } else {
