@@ -478,6 +478,16 @@ def test_cfg3_full_size_sampled():
     net.close()
 
 
+def test_large_image_sampled():
+    """A 3072 x 3000 image through config 1's net (9 M output pixels, about 140 times the metric's
+    workload; element offsets up to 0.9e9, every layer on many rounds of workgroups): sampled
+    probabilities and summed gradients against the oracle, tap codes of the first pool against
+    a scan."""
+    cfg = wl.crop(wl.CONFIGS[1], 1, 3072, 3000, "_large")
+    net, img, lab, params = sampled_parity(cfg, 96, 17, argmax_layers=(1,))
+    net.close()
+
+
 # ---- bf16 storage (activations and deltas rounded to bf16 when stored, arithmetic in fp32)
 _NET_BF16_SMALL = ((C, 8, 3), (MP, 0, 2), (C, 16, 3), (MP, 0, 2), (FC, 16, 0), (FC, 3, 0))
 
