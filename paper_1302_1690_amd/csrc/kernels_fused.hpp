@@ -289,15 +289,34 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
     for (int o = 0; o < NCLS; ++o) { bias[o] = a.Wk[(long)a.K * NCLS + o]; gb[o] = 0.f; }
     double my_loss = 0.0;
 
-    for (long m = (long)blockIdx.x * 16 + grp; m < M; m += (long)gridDim.x * 16) {
+    // the pass is a chain of dependent steps per position (load, dot products, shuffles, exp,
+    // stores): the next position's h is fetched before the current one is worked on, and the
+    // launch fills the CU with workgroups, so that enough bytes are in flight
+    const long stride = (long)gridDim.x * 16;
+    v4f hn[KV];
+    auto fetch_h = [&](long m) {
+#pragma unroll
+        for (int v = 0; v < KV; ++v) {
+            const int c = 4 * (j + 16 * v);
+            hn[v] = (c < a.K && m < M) ? load4(h_t + m * a.K + c) : (v4f){0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    fetch_h((long)blockIdx.x * 16 + grp);
+    // position m as (image b, row iy, column jx), advanced by the stride's own (images, rows,
+    // columns) instead of dividing a 64-bit index at every position
+    const long m0 = (long)blockIdx.x * 16 + grp;
+    int jx = (int)(m0 % a.Wo), iy = (int)((m0 / a.Wo) % a.Ho), b = (int)(m0 / a.Wo / a.Ho);
+    const int sx = (int)(stride % a.Wo), sy = (int)((stride / a.Wo) % a.Ho), sb = (int)(stride / a.Wo / a.Ho);
+    for (long m = m0; m < M; m += stride) {
         v4f hv[KV];
         float z[NCLS];
 #pragma unroll
         for (int o = 0; o < NCLS; ++o) z[o] = 0.f;
 #pragma unroll
+        for (int v = 0; v < KV; ++v) hv[v] = hn[v];
+        fetch_h(m + stride);
+#pragma unroll
         for (int v = 0; v < KV; ++v) {
-            const int c = 4 * (j + 16 * v);
-            hv[v] = c < a.K ? load4(h_t + m * a.K + c) : (v4f){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -322,9 +341,6 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
 #pragma unroll
             for (int o = 0; o < NCLS; ++o) pr[o] = z[o] + zmax;
         }
-        const int jx = (int)(m % a.Wo);
-        const long qq = m / a.Wo;
-        const int iy = (int)(qq % a.Ho), b = (int)(qq / a.Ho);
 #pragma unroll
         for (int o = 0; o < NCLS; ++o) {
             pr[o] *= inv;
@@ -365,6 +381,11 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
                 if (c < a.K && dh_t) store4(dh_t + m * a.K + c, dh);   // (no delta buffer: loss only)
             }
         }
+        jx += sx;
+        if (jx >= a.Wo) { jx -= a.Wo; ++iy; }
+        iy += sy;
+        if (iy >= a.Ho) { iy -= a.Ho; ++b; }
+        b += sb;
     }
     if (TRAIN) {
         // sum the 16 position groups of the workgroup: 4 per wave by shuffles, waves through LDS

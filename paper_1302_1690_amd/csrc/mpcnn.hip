@@ -47,7 +47,8 @@ mpcnn_status fail(mpcnn_status st, const char* fmt, ...)
                         __FILE__, __LINE__);                                               \
     } while (0)
 
-constexpr int kLossBlocks = 512;          // also the most workgroups of the class-layer kernel
+constexpr int kLossBlocks = 2048;         // most per-workgroup loss shares (= most workgroups of the class-layer kernel)
+constexpr int kSoftmaxBlocks = 512;       // workgroups of the unfused softmax kernel
 constexpr int kDirectWgradChunks = 512;   // split of the position reduction, direct kernel
 constexpr size_t kConvLdsCap = 64 * 1024; // halo bytes per workgroup (two workgroups per CU)
 constexpr size_t kWgradLdsCap = 144 * 1024;
@@ -171,6 +172,7 @@ struct mpcnn_net {
     double* d_scalar = nullptr;   // fp64 results of that step's reductions (8)
     int logistic = 0;             // squashing function of C and hidden FC layers: 0 tanh, 1 logistic
     int hint_pt = 0, hint_mp = 0; // mpcnn_set_conv_tiling: 0 = the planner's choice
+    int class_max_blocks = 512;   // workgroups of the class-layer kernel's training form resident on the chip
     // limited-memory BFGS: pairs in a ring of lb_m + 1 slots (one always free for the candidate)
     int lb_m = 0, lb_head = 0, lb_count = 0;
     bool lb_have_prev = false;
@@ -475,7 +477,14 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
     return w;
 }
 
-int class_blocks(long positions) { return (int)std::min<long>(kLossBlocks, (positions + 15) / 16); }
+// Workgroups of the class-layer kernel: as many as are resident at once (a second, partly
+// filled round would double its time; it is a chain of dependent steps per position and lives
+// on the bytes in flight), fewer on small maps, whose shares the closing reduce has to add.
+int class_blocks(const mpcnn_net* net, long positions)
+{
+    const long want = std::min<long>(net->class_max_blocks, std::max<long>(512, positions / 1024));
+    return (int)std::min<long>(want, (positions + 15) / 16);
+}
 
 bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g, bool mirrored = false)
 {
@@ -509,7 +518,7 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         if (ly.kind == MPCNN_MP) continue;
         if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.k, ly.fwd_rpad, ly.fwd_ct, ly.fwd_bm, net->hint_pt, net->hint_mp);
         if (training && ly.class_fused) {
-            g->partial_n[l] = class_blocks((long)B * r * c);
+            g->partial_n[l] = class_blocks(net, (long)B * r * c);
             g->partial_len[l] = ly.p_len;
         } else if (training) {
             if (ly.dgrad_mfma && l > 0)
@@ -558,7 +567,11 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         for (size_t l = 0; l < L; ++l) {
             if (!g->partial_n[l]) continue;
             g->partial_off[l] = off;
-            off = align_up(off + sizeof(float) * (size_t)g->partial_n[l] * g->partial_len[l]);
+            // (the class layer's share count depends on an occupancy query made when the net
+            // first touches the device: its buffer is sized for the most it can be, so that
+            // the workspace size does not)
+            const size_t n_alloc = net->layers[l].class_fused ? (size_t)kLossBlocks : (size_t)g->partial_n[l];
+            off = align_up(off + sizeof(float) * n_alloc * g->partial_len[l]);
         }
     } else {
         // forward only: layers alternate between two buffers, nothing is kept
@@ -719,6 +732,23 @@ void launch_class_inst(const mpcnn::ClassArgs& a, bool train, int blocks, hipStr
     if (train) mpcnn::class_layer_kernel<NCLS, KV, true, T><<<blocks, 256, 0, st>>>(a);
     else mpcnn::class_layer_kernel<NCLS, KV, false, T><<<blocks, 256, 0, st>>>(a);
 }
+template <int NCLS, int KV, typename T>
+int class_occupancy_inst()
+{
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, mpcnn::class_layer_kernel<NCLS, KV, true, T>, 256, 0) != hipSuccess)
+        n = 0;
+    return n;
+}
+// workgroups of the training form that one CU holds at once (0 if unknown)
+template <typename T>
+int class_occupancy(int ncls, int KV)
+{
+#define CASE(n, v) if (ncls == n && KV == v) return class_occupancy_inst<n, v, T>()
+    CASE(2, 2); CASE(3, 2); CASE(4, 2); CASE(2, 4); CASE(3, 4); CASE(4, 4);
+#undef CASE
+    return 0;
+}
 template <typename T>
 void launch_class(const mpcnn::ClassArgs& a, int ncls, int KV, bool train, int blocks, hipStream_t st)
 {
@@ -831,7 +861,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             a.probs_rows = g.probs_rows;
             a.K = Ci; a.tanh_below = (l > 0 && net->layers[l - 1].tanh_out) ? 1 + net->logistic : 0;
             a.mse = net->loss_kind == MPCNN_LOSS_MSE;
-            const int blocks = class_blocks(M);
+            const int blocks = class_blocks(net, M);
             const bool train = labels != nullptr;
             const double flops = 2.0 * M * Ci * ly.cout * (train ? 3.0 : 1.0);
             const double bytes = es * n_in * (train ? 2.0 : 1.0) + 4.0 * n_out;
@@ -889,7 +919,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
     } else if (!net->layers[L - 1].class_fused) {
         // class logits -> probabilities, deltas, loss
         long total = (long)B * Hi * Wi;
-        int blocks = (int)std::min<long>(kLossBlocks, (total + 255) / 256);
+        int blocks = (int)std::min<long>(kSoftmaxBlocks, (total + 255) / 256);
         LAUNCH("softmax_ce", L - 1, 3, 0, 4.0 * total * (3.0 * net->n_cls + 2.0),
                softmax_ce_kernel<<<blocks, 256, 0, st>>>(in, probs, labels, pixw, dZ,
                                                          want_loss ? lp : nullptr, B, Hi, Wi, g.label_h, g.W,
@@ -1300,6 +1330,12 @@ mpcnn_status mpcnn_set_params(mpcnn_net* net, const float* params_host, size_t n
         else net->d_wread = net->d_params;
         mpcnn_status rc = set_lds_attrs(net->bf16);
         if (rc != MPCNN_OK) return rc;
+        const Layer& last = net->layers.back();
+        if (last.class_fused) {
+            const int kv = last.cin <= 128 ? 2 : 4;
+            const int occ = net->bf16 ? class_occupancy<mpcnn::bf16>(last.cout, kv) : class_occupancy<float>(last.cout, kv);
+            if (occ > 0) net->class_max_blocks = std::min(kLossBlocks, kNumCU * occ);
+        }
     }
     std::vector<float> tmp(n);
     to_device_order(net, params_host, tmp.data());
