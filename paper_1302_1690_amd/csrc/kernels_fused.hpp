@@ -261,11 +261,15 @@ struct ClassArgs {
 // training also delta_z = w (p - onehot), the block's share of the summed cross-entropy,
 // dW += h delta_z^T, db += delta_z, and dH = (W^T delta_z) (1 - h^2)   (Results: MCCE per
 // pixel; Method: first step of back-propagation; Alg. 2 for the sums).
-// 16 lanes share one position: lane j holds channels 4(j+16v)..+3, v < KV; dot products meet
+// 16 lanes share one position: lane j holds KV quads of channels, quad v = channels
+// 4Q(j + 16(v/Q)) + 4(v%Q) .. +3 - with Q = 1 every quad is a 128-bit access of its own (fp32), with
+// Q = 2 two neighbouring quads are one (8 bf16 values; K a multiple of 8); dot products meet
 // by xor-shuffles in a fixed order.  A workgroup walks 16 positions at a time.
-template <int NCLS, int KV, bool TRAIN, typename T>
+template <int NCLS, int KV, bool TRAIN, typename T, int Q = 1>
 __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
 {
+    static_assert(KV % Q == 0, "whole accesses");
+    auto chan = [](int lane16, int v) { return 4 * Q * (lane16 + 16 * (v / Q)) + 4 * (v % Q); };
     const T* h_t = static_cast<const T*>(a.h);
     T* dh_t = static_cast<T*>(a.dH);
     __shared__ float red[4][KV * 4 * NCLS + NCLS][16];
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
         for (int s = 0; s < 4; ++s)
 #pragma unroll
             for (int o = 0; o < NCLS; ++o) {
-                const int c = 4 * (j + 16 * v) + s;
+                const int c = chan(j, v) + s;
                 w[v][s][o] = c < a.K ? a.Wk[(long)c * NCLS + o] : 0.f;
                 gw[v][s][o] = 0.f;
             }
@@ -296,9 +300,11 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
     v4f hn[KV];
     auto fetch_h = [&](long m) {
 #pragma unroll
-        for (int v = 0; v < KV; ++v) {
-            const int c = 4 * (j + 16 * v);
-            hn[v] = (c < a.K && m < M) ? load4(h_t + m * a.K + c) : (v4f){0.f, 0.f, 0.f, 0.f};
+        for (int v = 0; v < KV; v += Q) {
+            const int c = chan(j, v);
+#pragma unroll
+            for (int q = 0; q < Q; ++q) hn[v + q] = (v4f){0.f, 0.f, 0.f, 0.f};
+            if (c < a.K && m < M) load_quads<Q>(h_t + m * a.K + c, *reinterpret_cast<v4f(*)[Q]>(&hn[v]));
         }
     };
     fetch_h((long)blockIdx.x * 16 + grp);
@@ -364,10 +370,9 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
             }
             if (t >= 0 && j == 0)
                 my_loss += a.mse ? (double)wt * 0.5 * (double)sq : (double)wt * ((double)logf(sum) - (double)zt);
+            v4f dh[KV];
 #pragma unroll
             for (int v = 0; v < KV; ++v) {
-                const int c = 4 * (j + 16 * v);
-                v4f dh;
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
                     float g = 0.f;
@@ -376,10 +381,15 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
                         g = fmaf(w[v][s][o], dz[o], g);
                         gw[v][s][o] = fmaf(hv[v][s], dz[o], gw[v][s][o]);
                     }
-                    dh[s] = a.tanh_below ? g * squash_slope(hv[v][s], a.tanh_below == 2) : g;   // 0 none, 1 tanh, 2 logistic
+                    dh[v][s] = a.tanh_below ? g * squash_slope(hv[v][s], a.tanh_below == 2) : g;   // 0 none, 1 tanh, 2 logistic
                 }
-                if (c < a.K && dh_t) store4(dh_t + m * a.K + c, dh);   // (no delta buffer: loss only)
             }
+            if (dh_t)   // (no delta buffer: loss only)
+#pragma unroll
+                for (int v = 0; v < KV; v += Q) {
+                    const int c = chan(j, v);
+                    if (c < a.K) store_quads<Q>(dh_t + m * a.K + c, *reinterpret_cast<const v4f(*)[Q]>(&dh[v]));
+                }
         }
         jx += sx;
         if (jx >= a.Wo) { jx -= a.Wo; ++iy; }
@@ -415,7 +425,7 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
             const float s = (red[0][i][jj] + red[1][i][jj]) + (red[2][i][jj] + red[3][i][jj]);
             if (i < KV * 4 * NCLS) {
                 const int o = i % NCLS, vs = i / NCLS, sidx = vs & 3, v = vs >> 2;
-                const int c = 4 * (jj + 16 * v) + sidx;
+                const int c = chan(jj, v) + sidx;
                 if (c < a.K) out[(long)c * NCLS + o] = s;
             } else if (jj == 0) {
                 out[(long)a.K * NCLS + (i - KV * 4 * NCLS)] = s;

@@ -726,25 +726,36 @@ mpcnn_status set_lds_attrs(bool bf16_storage)
     return bf16_storage ? set_lds_attrs_t<mpcnn::bf16>() : set_lds_attrs_t<float>();
 }
 
+// bf16 storage with a multiple of 8 channels: 8 channels per 128-bit access (Q = 2)
 template <int NCLS, int KV, typename T>
 void launch_class_inst(const mpcnn::ClassArgs& a, bool train, int blocks, hipStream_t st)
 {
-    if (train) mpcnn::class_layer_kernel<NCLS, KV, true, T><<<blocks, 256, 0, st>>>(a);
-    else mpcnn::class_layer_kernel<NCLS, KV, false, T><<<blocks, 256, 0, st>>>(a);
+    constexpr bool kPairs = sizeof(T) == 2;
+    if (kPairs && a.K % 8 == 0) {
+        if (train) mpcnn::class_layer_kernel<NCLS, KV, true, T, kPairs ? 2 : 1><<<blocks, 256, 0, st>>>(a);
+        else mpcnn::class_layer_kernel<NCLS, KV, false, T, kPairs ? 2 : 1><<<blocks, 256, 0, st>>>(a);
+    } else {
+        if (train) mpcnn::class_layer_kernel<NCLS, KV, true, T><<<blocks, 256, 0, st>>>(a);
+        else mpcnn::class_layer_kernel<NCLS, KV, false, T><<<blocks, 256, 0, st>>>(a);
+    }
 }
 template <int NCLS, int KV, typename T>
-int class_occupancy_inst()
+int class_occupancy_inst(int K)
 {
+    constexpr bool kPairs = sizeof(T) == 2;
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, mpcnn::class_layer_kernel<NCLS, KV, true, T>, 256, 0) != hipSuccess)
-        n = 0;
-    return n;
+    hipError_t e;
+    if (kPairs && K % 8 == 0)
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, mpcnn::class_layer_kernel<NCLS, KV, true, T, kPairs ? 2 : 1>, 256, 0);
+    else
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, mpcnn::class_layer_kernel<NCLS, KV, true, T>, 256, 0);
+    return e == hipSuccess ? n : 0;
 }
 // workgroups of the training form that one CU holds at once (0 if unknown)
 template <typename T>
-int class_occupancy(int ncls, int KV)
+int class_occupancy(int ncls, int KV, int K)
 {
-#define CASE(n, v) if (ncls == n && KV == v) return class_occupancy_inst<n, v, T>()
+#define CASE(n, v) if (ncls == n && KV == v) return class_occupancy_inst<n, v, T>(K)
     CASE(2, 2); CASE(3, 2); CASE(4, 2); CASE(2, 4); CASE(3, 4); CASE(4, 4);
 #undef CASE
     return 0;
@@ -1333,7 +1344,7 @@ mpcnn_status mpcnn_set_params(mpcnn_net* net, const float* params_host, size_t n
         const Layer& last = net->layers.back();
         if (last.class_fused) {
             const int kv = last.cin <= 128 ? 2 : 4;
-            const int occ = net->bf16 ? class_occupancy<mpcnn::bf16>(last.cout, kv) : class_occupancy<float>(last.cout, kv);
+            const int occ = net->bf16 ? class_occupancy<mpcnn::bf16>(last.cout, kv, last.cin) : class_occupancy<float>(last.cout, kv, last.cin);
             if (occ > 0) net->class_max_blocks = std::min(kLossBlocks, kNumCU * occ);
         }
     }
