@@ -567,11 +567,24 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         for (size_t l = 0; l < L; ++l) {
             if (!g->partial_n[l]) continue;
             g->partial_off[l] = off;
-            // (the class layer's share count depends on an occupancy query made when the net
-            // first touches the device: its buffer is sized for the most it can be, so that
-            // the workspace size does not)
-            const size_t n_alloc = net->layers[l].class_fused ? (size_t)kLossBlocks : (size_t)g->partial_n[l];
-            off = align_up(off + sizeof(float) * n_alloc * g->partial_len[l]);
+            // The buffers of the partial sums are sized by bounds that do not depend on the map's
+            // size: the number of slabs a plan ends up with is not monotonic in it (a map with a
+            // few tiles more than workgroups gets half as many slabs of two tiles), and a pass
+            // over bands must be able to size its workspace by the tallest band, the last one
+            // being shorter.  (The class layer's share count also depends on an occupancy
+            // query made when the net first touches the device.)
+            const Layer& ly = net->layers[l];
+            size_t alloc_f;
+            if (ly.class_fused) alloc_f = (size_t)kLossBlocks * g->partial_len[l];
+            else {
+                const size_t rows_w = (size_t)ly.k * ly.k2 * ly.cin, Nt = ceil_div(ly.cout, 32);
+                const size_t tiled = std::max((size_t)ceil_div((int)rows_w, 32) * Nt * 1024 + Nt * 32,
+                                              (size_t)ceil_div((int)rows_w + 1, 32) * Nt * 1024);
+                alloc_f = std::max((size_t)kNumCU * tiled,
+                                   (size_t)std::max(kDirectWgradChunks, 2 * kNumCU) * ly.p_len);
+                alloc_f = std::max(alloc_f, (size_t)g->partial_n[l] * g->partial_len[l]);
+            }
+            off = align_up(off + sizeof(float) * alloc_f);
         }
     } else {
         // forward only: layers alternate between two buffers, nothing is kept

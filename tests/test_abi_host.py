@@ -134,3 +134,22 @@ def test_errors():
     with pytest.raises(mpcnn.MpcnnError):
         net.get_params()                              # never set
     assert "never set" in mpcnn.lib().mpcnn_last_error().decode()
+
+
+def test_banded_workspace_grows_with_the_band():
+    """A pass over bands sizes its workspace by the tallest band; the last band is shorter, so
+    the size must not shrink when the band grows (host logic only: no device is touched)."""
+    from paper_1302_1690_amd import mpcnn, workloads as wl
+    L = mpcnn.lib()
+    C, MP, FC = 0, 1, 2
+    nets = [(wl.CONFIGS[1].layers, wl.CONFIGS[1].in_channels, wl.CONFIGS[1].patch, 1, 300),
+            (wl.CONFIGS[3].layers, wl.CONFIGS[3].in_channels, wl.CONFIGS[3].patch, 1, 200),
+            (((C, 8, 7), (MP, 0, 2), (C, 48, 2), (FC, 100, 0), (FC, 3, 0)), 1, 14, 3, 39)]
+    for layers, cin, patch, B, W in nets:
+        net = mpcnn.Net(layers, cin, patch)
+        prev = 0
+        for band in range(1, 120):
+            n = L.mpcnn_workspace_bytes_banded(net._h, B, W, band)
+            assert n >= prev > -1, (layers, band, n, prev)
+            prev = n
+        net.close()

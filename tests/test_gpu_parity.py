@@ -331,7 +331,11 @@ def test_image_taken_in_bands():
     cases = ((wl.crop(wl.CONFIGS[0], 2, 45, 37), (7, 28, 100)),
              (wl.crop(wl.CONFIGS[1], 1, 90, 75), (16,)),
              (wl.Workload("bf16_small_bands", _NET_BF16_SMALL, 14, 3, 3, 2, 40, 44, 0.25, "ellipses", dtype="bf16",
-                          seed_image=1109, seed_label=2109, seed_param=3109), (10,)))
+                          seed_image=1109, seed_label=2109, seed_param=3109), (10,)),
+             # 29 output rows in bands of 20 + 9: the short last band's plans have more slabs of
+             # partial sums than the tall one's (the workspace is sized by the tall one)
+             (wl.Workload("bands_short_last", ((C, 8, 7), (MP, 0, 2), (C, 48, 2), (FC, 100, 0), (FC, 3, 0)), 14, 1, 3,
+                          3, 42, 39, 0.2, "ellipses", seed_image=1117, seed_label=2117, seed_param=3117), (20, 9)))
     for cfg, bands in cases:
         img, lab = wl.make_inputs(cfg)
         params = wl.make_params(cfg)
