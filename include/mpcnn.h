@@ -209,7 +209,8 @@ mpcnn_status mpcnn_seg_backward(mpcnn_net* net, const float* image_dev, const in
  * the net on the patch around it), so a band of r output rows needs r + P - 1 image rows and
  * nothing else; gradients and loss are summed over the bands, in order.  For images whose
  * activations do not fit in memory at once: the workspace is that of one band,
- * mpcnn_workspace_bytes_banded(net, B, W, band_rows).  Arguments and results as
+ * mpcnn_workspace_bytes_banded(net, B, W, band_rows), which is enough for every shorter band
+ * as well (the size never shrinks when band_rows grows).  Arguments and results as
  * mpcnn_seg_backward (probs_dev, if given, receives all H-P+1 rows); the test hooks afterwards
  * see the last band only.  Errors as mpcnn_seg_backward; EINVAL for band_rows < 1.
  */
