@@ -350,8 +350,13 @@ def test_image_taken_in_bands():
             net.seg_backward_banded(d_img, d_lab, band_rows, d_pw, p_b, l_b)
             torch.cuda.synchronize()
             say("case %s bands of %d rows (%d output rows)" % (cfg.name, band_rows, cfg.out_h))
-            # every position is computed with the same operations whatever the tiling: same bits
-            assert np.array_equal(p_b.cpu().numpy(), probs)
+            # fp32 storage: every position is computed with the same operations whatever the
+            # tiling, same bits.  bf16 storage: the bf16 kernels split the reduction over 4 or 8
+            # waves depending on the map's size, so a stored value can round the other way
+            if cfg.dtype == "bf16":
+                assert np.abs(p_b.cpu().numpy() - probs).max() <= 0.1 * tol_of(cfg)
+            else:
+                assert np.array_equal(p_b.cpu().numpy(), probs)
             assert np.abs(p_b.cpu().numpy() - ref["probs"]).max() <= tol_of(cfg)
             assert abs(float(l_b.item()) - ref["loss"]) <= 0.1 * tol_of(cfg) * abs(ref["loss"])
             check_grads(cfg, net.get_grads(), ref["grads"])
@@ -679,10 +684,15 @@ def test_forward_same_size_mirrored_borders():
         err = np.abs(probs - ref).max()
         say("  probs err %.2e" % err)
         assert err <= tol_of(cfg)
-        # the interior equals the plain valid-region forward, bit for bit
+        # the interior equals the plain valid-region forward: bit for bit with fp32 storage, up to
+        # the rounding of stored values with bf16 storage (wave split of the bf16 kernels)
         valid = net.seg_forward(torch.from_numpy(img).cuda()).cpu().numpy()
         c = (cfg.patch - 1) // 2
-        np.testing.assert_array_equal(probs[:, :, c:c + valid.shape[2], c:c + valid.shape[3]], valid)
+        inner = probs[:, :, c:c + valid.shape[2], c:c + valid.shape[3]]
+        if cfg.dtype == "bf16":
+            assert np.abs(inner - valid).max() <= 0.1 * tol_of(cfg)
+        else:
+            np.testing.assert_array_equal(inner, valid)
         # images smaller than the widest border are refused
         small = torch.zeros((1, cfg.in_channels, cfg.patch // 2 - 1, 40), device="cuda")
         with pytest.raises(mpcnn.MpcnnError):
