@@ -6,6 +6,13 @@
 // A layer that follows pooling by a cumulative factor d reads taps d elements
 // apart (Method, MPF layer: the k*k pooling offsets become the residues mod d).
 // Weights are stored [tap = u*k+v][c][o] followed by the bias row [o].
+//
+// The steps of one training pass, as the comments in these files number them:
+//   a0 image to channels-last storage      a1 convolution / FC forward + bias + squashing function
+//   a2 max filter + argmax tap codes        a3 class layer: logits, softmax, loss
+//   a4 its backward (delta of the logits)   a5 parameter gradient of a layer
+//   a6 data gradient of a layer             a7 routing of the delta through a pooling layer
+//   a8 parameter update
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>

@@ -3,6 +3,7 @@
 //   first_layer_kernel   conv + bias + tanh for a layer with very few input channels
 //   maxfilter_fwd4 / maxfilter_bwd4   stride-1 max filter / routing by argmax, 4 channels per thread
 //   class_layer_kernel   last FC (1x1) + softmax + cross-entropy + its own backward
+// (step numbers a0 .. a8 in the comments: see the list at the top of kernels_direct.hpp)
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
