@@ -19,9 +19,10 @@
 
 #include "../../include/mpcnn.h"
 #include "kernels_direct.hpp"
-#include "kernels_mfma.hpp"
-#include "kernels_wgrad.hpp"
-#include "kernels_wgrad_bf16.hpp"
+#include "launchers.hpp"
+#include "kernels_wgrad_bf16.hpp"   // its LDS geometry, which the planner shares (no instance is built here)
+#include "kernels_pack.hpp"
+#include "kernels_reduce.hpp"
 #include "kernels_lbfgs.hpp"
 #include "kernels_first_bf16.hpp"
 #include "kernels_fused.hpp"
@@ -620,82 +621,22 @@ inline int grid_for(long total, int block = 256, int cap = 1 << 20)
 }
 
 // ------------------------------------------------------------------ MFMA launches
-// (OT, PT, MP) instances of conv_ts_kernel: OT*PT/MP is 4 or 8 waves
-#define CONV_TS_INSTANCES(X) \
-    X(4, 2, 1) X(4, 2, 2) X(4, 4, 2) X(2, 2, 1) X(2, 4, 1) X(2, 4, 2) X(2, 8, 2) X(1, 4, 1) X(1, 8, 1) X(1, 8, 2)
-template <int W, int OT, int PT, int NW, typename T>
-void launch_conv_inst(const mpcnn::ConvArgs& a, dim3 grid, size_t lds, hipStream_t st)
-{
-    mpcnn::conv_mfma_kernel<W, OT, PT, NW, T><<<grid, 64 * NW, lds, st>>>(a);
-}
-template <int OT, int PT, int NW>
-void launch_conv_bm_inst(const mpcnn::ConvArgs& a, dim3 grid, size_t lds, hipStream_t st)
-{
-    mpcnn::conv_mfma_kernel<32, OT, PT, NW, mpcnn::bf16, true><<<grid, 64 * NW, lds, st>>>(a);
-}
-// bf16 matrix instruction (32-wide tiles, bf16 storage)
-bool launch_conv_bm(const mpcnn::ConvArgs& a, const ChanTiling& ct, const TilePlan& tp, dim3 grid, hipStream_t st)
-{
-#define CASE(o, p)                                                                  \
-    if (ct.W == 32 && ct.OT == o && tp.PT == p) {                                     \
-        if (tp.NW == 8) launch_conv_bm_inst<o, p, 8>(a, grid, tp.lds, st);            \
-        else launch_conv_bm_inst<o, p, 4>(a, grid, tp.lds, st);                       \
-        return true;                                                                \
-    }
-    CASE(1, 2) CASE(2, 2) CASE(4, 2) CASE(1, 4) CASE(2, 4)
-#undef CASE
-    return false;
-}
-template <typename T>
-bool launch_conv_ts(const mpcnn::ConvArgs& a, const ChanTiling& ct, const TilePlan& tp, dim3 grid, hipStream_t st)
-{
-#define CASE(o, p, m)                                                                          \
-    if (ct.OT == o && tp.PT == p && tp.MP == m) {                                              \
-        mpcnn::conv_ts_kernel<o, p, m, T><<<grid, 64 * o * p / m, tp.lds, st>>>(a);            \
-        return true;                                                                           \
-    }
-    CONV_TS_INSTANCES(CASE)
-#undef CASE
-    return false;
-}
+// (the kernel instances live in launch_*.hip, one translation unit per family)
 template <typename T>
 bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, const TilePlan& tp, dim3 grid,
                       hipStream_t st, bool bm = false)
 {
-    if (bm) return launch_conv_bm(a, ct, tp, grid, st);
-    if (tp.MP > 0) return launch_conv_ts<T>(a, ct, tp, grid, st);
-#define CASE(w, o, p)                                                                         \
-    if (ct.W == w && ct.OT == o && tp.PT == p) {                                                \
-        if (tp.NW == 8) launch_conv_inst<w, o, p, 8, T>(a, grid, tp.lds, st);                   \
-        else launch_conv_inst<w, o, p, 4, T>(a, grid, tp.lds, st);                              \
-        return true;                                                                          \
-    }
-    CASE(16, 1, 4) CASE(16, 2, 4) CASE(16, 4, 4) CASE(16, 1, 8) CASE(16, 2, 8)
-    CASE(32, 1, 2) CASE(32, 2, 2) CASE(32, 4, 2) CASE(32, 1, 4) CASE(32, 2, 4)
-#undef CASE
-    return false;
+    if (bm) return ct.W == 32 && mpcnn::launch_conv_bm(a, ct.OT, tp.PT, tp.NW, tp.MP, grid, tp.lds, st);
+    if constexpr (std::is_same<T, float>::value)
+        return mpcnn::launch_conv_f32(a, ct.W, ct.OT, tp.PT, tp.NW, tp.MP, grid, tp.lds, st);
+    else
+        return mpcnn::launch_conv_b16(a, ct.W, ct.OT, tp.PT, tp.NW, tp.MP, grid, tp.lds, st);
 }
 template <typename T>
-void launch_wgrad_mfma(const mpcnn::WgradArgs& a, int hl, dim3 grid, size_t lds, hipStream_t st)
+bool launch_wgrad_mfma(const mpcnn::WgradArgs& a, int hl, dim3 grid, size_t lds, hipStream_t st)
 {
-#define CASE(m) case m:                                                                                   \
-        if (hl > mpcnn::kWgStageH) mpcnn::wgrad_mfma_kernel<m, 2 * mpcnn::kWgStageH, T><<<grid, 512, lds, st>>>(a); \
-        else mpcnn::wgrad_mfma_kernel<m, mpcnn::kWgStageH, T><<<grid, 512, lds, st>>>(a);                         \
-        return;
-    switch (a.mw) {
-    CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11)
-    }
-#undef CASE
-}
-void launch_wgrad_bm(const mpcnn::WgradArgs& a, int nch, dim3 grid, size_t lds, hipStream_t st)
-{
-#define CASE(m, c) case 4 * m + c - 5: mpcnn::wgrad_bm_kernel<m, c><<<grid, 512, lds, st>>>(a); return;
-#define ROW(m) CASE(m, 1) CASE(m, 2) CASE(m, 3) CASE(m, 4)
-    switch (4 * a.mw + nch - 5) {
-    ROW(1) ROW(2) ROW(3) ROW(4) ROW(5)
-    }
-#undef ROW
-#undef CASE
+    if constexpr (std::is_same<T, float>::value) return mpcnn::launch_wgrad_f32(a, hl, grid, lds, st);
+    else return mpcnn::launch_wgrad_b16(a, hl, grid, lds, st);
 }
 void launch_first_bm(const mpcnn::FirstBmArgs& a, unsigned wgs, hipStream_t st)
 {
@@ -705,38 +646,11 @@ void launch_first_bm(const mpcnn::FirstBmArgs& a, unsigned wgs, hipStream_t st)
 #undef CASE
 }
 // Kernels that may ask for more than 64 KiB of dynamic LDS must say so once.
-template <typename T>
-mpcnn_status set_lds_attrs_t()
-{
-#define ATTR(fn) HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fn), \
-                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024))
-    ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 4, T>)); ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 8, T>));
-    ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 8, T>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 8, T>));
-    ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 4, T>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 4, 8, T>));
-    ATTR((mpcnn::conv_mfma_kernel<16, 4, 4, 8, T>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 2, 8, T>));
-#define TS_ATTR(o, p, m) ATTR((mpcnn::conv_ts_kernel<o, p, m, T>));
-    CONV_TS_INSTANCES(TS_ATTR)
-#undef TS_ATTR
-#define WG(m) ATTR((mpcnn::wgrad_mfma_kernel<m, mpcnn::kWgStageH, T>)); ATTR((mpcnn::wgrad_mfma_kernel<m, 2 * mpcnn::kWgStageH, T>));
-    WG(1) WG(2) WG(3) WG(4) WG(5) WG(6) WG(7) WG(8) WG(9) WG(10) WG(11)
-#undef WG
-    if constexpr (std::is_same<T, mpcnn::bf16>::value) {
-#define ROW(m) ATTR((mpcnn::wgrad_bm_kernel<m, 1>)); ATTR((mpcnn::wgrad_bm_kernel<m, 2>)); \
-               ATTR((mpcnn::wgrad_bm_kernel<m, 3>)); ATTR((mpcnn::wgrad_bm_kernel<m, 4>))
-        ROW(1); ROW(2); ROW(3); ROW(4); ROW(5);
-#undef ROW
-        ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 4, 2, 8, T, true>));
-        ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 2, 8, T, true>));
-        ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 2, 4, 8, T, true>));
-        ATTR((mpcnn::conv_mfma_kernel<32, 1, 4, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 4, 8, T, true>));
-        ATTR((mpcnn::conv_mfma_kernel<32, 1, 2, 4, T, true>)); ATTR((mpcnn::conv_mfma_kernel<32, 1, 2, 8, T, true>));
-    }
-#undef ATTR
-    return MPCNN_OK;
-}
 mpcnn_status set_lds_attrs(bool bf16_storage)
 {
-    return bf16_storage ? set_lds_attrs_t<mpcnn::bf16>() : set_lds_attrs_t<float>();
+    if (bf16_storage) { HIP_TRY(mpcnn::conv_attrs_b16()); HIP_TRY(mpcnn::wgrad_attrs_b16()); }
+    else { HIP_TRY(mpcnn::conv_attrs_f32()); HIP_TRY(mpcnn::wgrad_attrs_f32()); }
+    return MPCNN_OK;
 }
 
 // bf16 storage with a multiple of 8 channels: 8 channels per 128-bit access (Q = 2)
@@ -1058,12 +972,15 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.mg_txp = magic_of(wp.TxP); a.mg_ci = magic_of(Ci); a.mg_k = magic_of(ly.k);
                 a.mg_ntx = magic_of(wp.ntx); a.mg_nty = magic_of(wp.nty); a.mg_d = magic_of(ly.dil);
                 dim3 grid((unsigned)wp.slabs, (unsigned)wp.gm, (unsigned)wp.gn);
+                bool launched = false;
                 if (wp.bm)
                     LAUNCH("wgrad_mfma", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
-                           launch_wgrad_bm(a, wp.TxP / 16, grid, wp.lds, st));
+                           launched = mpcnn::launch_wgrad_bm(a, wp.TxP / 16, grid, wp.lds, st));
                 else
                     LAUNCH("wgrad_mfma", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
-                           launch_wgrad_mfma<T>(a, wp.hl, grid, wp.lds, st));
+                           launched = launch_wgrad_mfma<T>(a, wp.hl, grid, wp.lds, st));
+                if (!launched)
+                    return fail(MPCNN_EUNSUPPORTED, "layer %zu: no weight-gradient kernel instance for its plan", li);
             } else if constexpr (!kF32) {
                 return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             } else {
