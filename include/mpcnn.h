@@ -301,7 +301,8 @@ mpcnn_status mpcnn_get_argmax(const mpcnn_net* net, int layer, uint8_t* host, si
  * mpcnn_seg_forward / mpcnn_seg_backward / mpcnn_sgd_step is bracketed by HIP
  * events recorded on the call's stream.  mpcnn_profile_read waits for them and
  * returns one record per launch site (kernel x layer), summed since the last
- * read: kernel name, layer index, step of the path (1 = conv fwd, 2 = max filter,
+ * read: kernel name (ending in _mfma: fp32 matrix instruction, _bm: bf16 matrix
+ * instruction), layer index, step of the path (1 = conv fwd, 2 = max filter,
  * 3 = class layer + softmax-CE, 4 = class layer backward, 5 = wgrad, 6 = dgrad,
  * 7 = routing, 8 = SGD, 0 = staging / reductions), launches, total milliseconds,
  * and the ALGORITHMIC work of one launch: flops = 2*M*N*K of the contraction

@@ -24,13 +24,43 @@ _LIB = os.path.join(_HERE, "liborc.so")
 _lib = None
 
 
+def _host_tag() -> str:
+    """What `-march=native` means on this machine (the CPU's model and flag list): a library
+    built elsewhere must not be loaded here."""
+    model, flags = "", ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name") and not model:
+                model = line.split(":", 1)[1].strip()
+            elif line.startswith("flags") and not flags:
+                flags = " ".join(sorted(line.split(":", 1)[1].split()))
+            if model and flags:
+                break
+    except OSError:
+        pass
+    import hashlib
+    return hashlib.sha1((model + "|" + flags).encode()).hexdigest()[:16]
+
+
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (plain -O2, OpenMP over patches)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile the oracle with gcc -O3 -march=native (OpenMP over patches).  ISO C mode keeps
+    floating-point contraction off and nothing allows re-association, so the arithmetic is the
+    source's, operation by operation.  The library is rebuilt when the source is newer or when
+    it was built for another CPU (it travels with the tree)."""
+    tag_file = _LIB + ".host"
+    tag = _host_tag()
+    try:
+        same_host = open(tag_file).read().strip() == tag
+    except OSError:
+        same_host = False
+    if force or not same_host or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+        subprocess.check_call(["gcc", "-O3", "-march=native", "-std=c11", "-fopenmp", "-fPIC", "-shared",
                                "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
+        with open(tag_file + ".tmp%d" % os.getpid(), "w") as f:
+            f.write(tag + "\n")
+        os.replace(tag_file + ".tmp%d" % os.getpid(), tag_file)
     return _LIB
 
 

@@ -13,6 +13,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <memory>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -137,6 +139,7 @@ struct Geom {
     bool staged = false;              // the image is copied to channels-last storage first
     int label_h = 0, probs_rows = 0;  // rows of the label / weight arrays and of the probs array (bands: the whole image's)
     bool accumulate = false;          // gradients and loss are added to what the net holds (bands after the first)
+    bool fixed_partials = false;      // partial-sum buffers sized by bounds that hold for every map size (bands)
     size_t staged_off = 0;            // that copy (C0 > 1, or bf16 storage)
     size_t delta_off[2] = {0, 0};     // two delta buffers, each as large as the largest map
     std::vector<size_t> partial_off;  // per parametrised layer: its slab / block partial sums
@@ -157,6 +160,17 @@ struct ProfSite {
     double ms, flops, bytes;
 };
 struct ProfPending { int site; hipEvent_t e0, e1; };
+
+// Plans are kept per (sizes, mode, tiling hints): a call with sizes seen before plans nothing.
+struct GeomKey {
+    int B, H, W, training, same, hint_pt, hint_mp;
+    bool operator==(const GeomKey& o) const
+    {
+        return B == o.B && H == o.H && W == o.W && training == o.training && same == o.same &&
+               hint_pt == o.hint_pt && hint_mp == o.hint_mp;
+    }
+};
+constexpr size_t kGeomCacheSize = 8;
 
 }  // namespace
 
@@ -188,8 +202,10 @@ struct mpcnn_net {
     bool packs_stale = true;
     int device = -1;
     bool lds_attr_set = false;
+    // plans of the sizes seen so far (oldest dropped first)
+    mutable std::vector<std::pair<GeomKey, std::shared_ptr<const Geom>>> geoms;
     // what the last forward / backward left behind (for the test hooks)
-    Geom last;
+    std::shared_ptr<const Geom> last;
     void* last_ws = nullptr;
     // profiling
     bool prof_on = false;
@@ -487,8 +503,10 @@ int class_blocks(const mpcnn_net* net, long positions)
     return (int)std::min<long>(want, (positions + 15) / 16);
 }
 
-bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g, bool mirrored = false)
+bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g, bool mirrored = false,
+               bool fixed_partials = false)
 {
+    g->fixed_partials = fixed_partials;
     if (B < 1 || H < net->patch || W < net->patch) return false;
     const size_t L = net->layers.size();
     g->B = B; g->H = H; g->W = W; g->training = training;
@@ -568,15 +586,17 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         for (size_t l = 0; l < L; ++l) {
             if (!g->partial_n[l]) continue;
             g->partial_off[l] = off;
-            // The buffers of the partial sums are sized by bounds that do not depend on the map's
-            // size: the number of slabs a plan ends up with is not monotonic in it (a map with a
-            // few tiles more than workgroups gets half as many slabs of two tiles), and a pass
-            // over bands must be able to size its workspace by the tallest band, the last one
-            // being shorter.  (The class layer's share count also depends on an occupancy
-            // query made when the net first touches the device.)
+            // A pass over bands sizes the buffers of the partial sums by bounds that do not depend
+            // on the map's size: the number of slabs a plan ends up with is not monotonic in it (a
+            // map with a few tiles more than workgroups gets half as many slabs of two tiles),
+            // and the workspace is sized by the tallest band, the last one being shorter.  A
+            // one-piece pass takes what its plan needs.  (The class layer's share count depends
+            // on an occupancy query made when the net first touches the device, which may be
+            // after the caller asked for the workspace size: always the bound.)
             const Layer& ly = net->layers[l];
             size_t alloc_f;
             if (ly.class_fused) alloc_f = (size_t)kLossBlocks * g->partial_len[l];
+            else if (!fixed_partials) alloc_f = (size_t)g->partial_n[l] * g->partial_len[l];
             else {
                 const size_t rows_w = (size_t)ly.k * ly.k2 * ly.cin, Nt = ceil_div(ly.cout, 32);
                 const size_t tiled = std::max((size_t)ceil_div((int)rows_w, 32) * Nt * 1024 + Nt * 32,
@@ -824,7 +844,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 a.mode = ly.tanh_out ? kFwdTanh : kFwdLinear; a.logistic = net->logistic;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
                 bool launched = false;
-                LAUNCH("conv_fwd_mfma", l, step, flops, bytes,
+                LAUNCH(ly.fwd_bm ? "conv_fwd_bm" : "conv_fwd_mfma", l, step, flops, bytes,
                        launched = launch_conv_mfma<T>(a, ly.fwd_ct, tp, grid, st, ly.fwd_bm));
                 if (!launched)   // a plan without a kernel instance: a planner bug, never a silent skip
                     return fail(MPCNN_EUNSUPPORTED, "layer %zu: no convolution kernel instance for its forward plan", l);
@@ -836,7 +856,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 a.squash = ly.tanh_out ? 1 + net->logistic : 0;
                 a.nty = ceil_div(Ho, kFirstBmTy); a.ntx = ceil_div(Wo, kFirstBmTx);
                 const unsigned wgs = (unsigned)std::min<long>((long)B * a.nty * a.ntx, 4L * kNumCU);
-                LAUNCH("first_layer", l, step, flops, bytes, launch_first_bm(a, wgs, st));
+                LAUNCH("first_layer_bm", l, step, flops, bytes, launch_first_bm(a, wgs, st));
             } else {
                 const int og = ceil_div(ly.cout, 4);
                 const long total = (long)B * Ho * Wo * og;
@@ -974,7 +994,7 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 dim3 grid((unsigned)wp.slabs, (unsigned)wp.gm, (unsigned)wp.gn);
                 bool launched = false;
                 if (wp.bm)
-                    LAUNCH("wgrad_mfma", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
+                    LAUNCH("wgrad_bm", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
                            launched = mpcnn::launch_wgrad_bm(a, wp.TxP / 16, grid, wp.lds, st));
                 else
                     LAUNCH("wgrad_mfma", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
@@ -1005,7 +1025,7 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.mode = below_tanh ? kDgradTanh : kDgradPlain; a.logistic = net->logistic;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.dgrad_ct.split);
                 bool launched = false;
-                LAUNCH("conv_dgrad_mfma", li, dstep, flops, dbytes,
+                LAUNCH(ly.dgrad_bm ? "conv_dgrad_bm" : "conv_dgrad_mfma", li, dstep, flops, dbytes,
                        launched = launch_conv_mfma<T>(a, ly.dgrad_ct, tp, grid, st, ly.dgrad_bm));
                 if (!launched)
                     return fail(MPCNN_EUNSUPPORTED, "layer %zu: no convolution kernel instance for its data-gradient plan", li);
@@ -1110,6 +1130,27 @@ mpcnn_status read_back(const mpcnn_net* net, const float* dev, float* host, size
     HIP_TRY(hipMemcpy(tmp.data(), dev, sizeof(float) * n, hipMemcpyDeviceToHost));
     to_host_order(net, tmp.data(), host);
     return MPCNN_OK;
+}
+
+// The plan for these sizes: from the net's cache, or made now and kept (same != 0: the
+// same-size forward, H x W being the caller's image).  Null if the sizes do not fit the net.
+std::shared_ptr<const Geom> geom_for(const mpcnn_net* net, int B, int H, int W, bool training, bool same)
+{
+    const GeomKey key{B, H, W, training ? 1 : 0, same ? 1 : 0, net->hint_pt, net->hint_mp};
+    for (auto& kv : net->geoms)
+        if (kv.first == key) return kv.second;
+    auto g = std::make_shared<Geom>();
+    if (same) {
+        // the net runs on the image extended by P-1 mirrored rows / columns
+        const int c = (net->patch - 1) / 2;
+        if (!make_geom(net, B, H + net->patch - 1, W + net->patch - 1, false, g.get(), true)) return nullptr;
+        g->pad_top = c; g->pad_left = c; g->src_h = H; g->src_w = W;
+    } else if (!make_geom(net, B, H, W, training, g.get())) {
+        return nullptr;
+    }
+    if (net->geoms.size() >= kGeomCacheSize) net->geoms.erase(net->geoms.begin());
+    net->geoms.emplace_back(key, g);
+    return g;
 }
 
 }  // namespace
@@ -1247,8 +1288,9 @@ mpcnn_status mpcnn_layer_shape(const mpcnn_net* net, int H, int W, int layer, in
 {
     if (!net) return fail(MPCNN_EINVAL, "null net");
     if (layer < 0 || layer >= (int)net->layers.size()) return fail(MPCNN_EINVAL, "layer %d out of range", layer);
-    Geom g;
-    if (!make_geom(net, 1, H, W, false, &g)) return fail(MPCNN_ESHAPE, "image %dx%d smaller than the %d patch", H, W, net->patch);
+    const auto gp = (H >= net->patch && W >= net->patch) ? geom_for(net, 1, H, W, false, false) : nullptr;
+    if (!gp) return fail(MPCNN_ESHAPE, "image %dx%d smaller than the %d patch", H, W, net->patch);
+    const Geom& g = *gp;
     const Layer& ly = net->layers[layer];
     if (rows) *rows = g.rows[layer];
     if (cols) *cols = g.cols[layer];
@@ -1277,6 +1319,7 @@ mpcnn_status mpcnn_set_params(mpcnn_net* net, const float* params_host, size_t n
             const int occ = net->bf16 ? class_occupancy<mpcnn::bf16>(last.cout, kv, last.cin) : class_occupancy<float>(last.cout, kv, last.cin);
             if (occ > 0) net->class_max_blocks = std::min(kLossBlocks, kNumCU * occ);
         }
+        net->geoms.clear();   // plans made before this point counted the class layer's shares differently
     }
     std::vector<float> tmp(n);
     to_device_order(net, params_host, tmp.data());
@@ -1312,6 +1355,7 @@ mpcnn_status mpcnn_set_conv_tiling(mpcnn_net* net, int position_tiles, int tiles
     if (!pt_ok || !mp_ok)
         return fail(MPCNN_EINVAL, "conv tiling (%d, %d): position tiles 0/2/4/8, tiles per wave 0/1/2", position_tiles, tiles_per_wave);
     net->hint_pt = position_tiles; net->hint_mp = tiles_per_wave;
+    net->geoms.clear();
     return MPCNN_OK;
 }
 
@@ -1346,57 +1390,53 @@ mpcnn_status mpcnn_get_grads(const mpcnn_net* net, float* grads_host, size_t n)
 
 size_t mpcnn_workspace_bytes(const mpcnn_net* net, int B, int H, int W, int training)
 {
-    if (!net) return 0;
-    Geom g;
-    if (!make_geom(net, B, H, W, training != 0, &g)) return 0;
-    return g.total;
+    if (!net || B < 1 || H < net->patch || W < net->patch) return 0;
+    const auto g = geom_for(net, B, H, W, training != 0, false);
+    return g ? g->total : 0;
 }
 
 static mpcnn_status check_call(mpcnn_net* net, const float* image, int B, int H, int W, void* ws,
-                               size_t ws_bytes, bool training, Geom* g)
+                               size_t ws_bytes, bool training, std::shared_ptr<const Geom>* g)
 {
     if (!net || !image || !ws) return fail(MPCNN_EINVAL, "null argument");
     if (!net->d_params) return fail(MPCNN_EINVAL, "parameters were never set");
     if (B < 1) return fail(MPCNN_EINVAL, "B = %d", B);
     if (H < net->patch || W < net->patch)
         return fail(MPCNN_ESHAPE, "image %dx%d smaller than the %dx%d patch", H, W, net->patch, net->patch);
-    if (!make_geom(net, B, H, W, training, g)) return fail(MPCNN_ESHAPE, "layer plan does not fit a %dx%d image", H, W);
-    if (ws_bytes < g->total) return fail(MPCNN_EWORKSPACE, "workspace %zu bytes, need %zu", ws_bytes, g->total);
+    *g = geom_for(net, B, H, W, training, false);
+    if (!*g) return fail(MPCNN_ESHAPE, "layer plan does not fit a %dx%d image", H, W);
+    if (ws_bytes < (*g)->total) return fail(MPCNN_EWORKSPACE, "workspace %zu bytes, need %zu", ws_bytes, (*g)->total);
     if (((uintptr_t)ws & 255u) != 0) return fail(MPCNN_EINVAL, "workspace must be 256-byte aligned");
     if (((uintptr_t)image & 15u) != 0) return fail(MPCNN_EINVAL, "image must be 16-byte aligned");
     return MPCNN_OK;
 }
 
-mpcnn_status mpcnn_seg_forward(mpcnn_net* net, const float* image_dev, int B, int H, int W,
-                               float* probs_dev, void* ws_dev, size_t ws_bytes, void* hip_stream)
+static mpcnn_status forward_with(mpcnn_net* net, const std::shared_ptr<const Geom>& g, const float* image_dev,
+                                 float* probs_dev, void* ws_dev, hipStream_t stream)
 {
-    Geom g;
-    mpcnn_status st = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &g);
-    if (st != MPCNN_OK) return st;
-    if (!probs_dev) return fail(MPCNN_EINVAL, "null probs_dev");
-    st = net->bf16 ? run_forward<mpcnn::bf16>(net, g, image_dev, (char*)ws_dev, nullptr, nullptr, probs_dev,
-                                              nullptr, nullptr, (hipStream_t)hip_stream)
-                   : run_forward<float>(net, g, image_dev, (char*)ws_dev, nullptr, nullptr, probs_dev, nullptr,
-                                        nullptr, (hipStream_t)hip_stream);
+    mpcnn_status st = net->bf16 ? run_forward<mpcnn::bf16>(net, *g, image_dev, (char*)ws_dev, nullptr, nullptr, probs_dev,
+                                                           nullptr, nullptr, stream)
+                                : run_forward<float>(net, *g, image_dev, (char*)ws_dev, nullptr, nullptr, probs_dev, nullptr,
+                                                     nullptr, stream);
     net->last = g; net->last_ws = ws_dev;
     return st;
 }
 
-// geometry of the same-size forward: the net runs on the image extended by P-1 mirrored rows / columns
-static bool make_geom_same(const mpcnn_net* net, int B, int H, int W, Geom* g)
+mpcnn_status mpcnn_seg_forward(mpcnn_net* net, const float* image_dev, int B, int H, int W,
+                               float* probs_dev, void* ws_dev, size_t ws_bytes, void* hip_stream)
 {
-    const int c = (net->patch - 1) / 2;
-    if (!make_geom(net, B, H + net->patch - 1, W + net->patch - 1, false, g, true)) return false;
-    g->pad_top = c; g->pad_left = c; g->src_h = H; g->src_w = W;
-    return true;
+    std::shared_ptr<const Geom> g;
+    mpcnn_status st = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &g);
+    if (st != MPCNN_OK) return st;
+    if (!probs_dev) return fail(MPCNN_EINVAL, "null probs_dev");
+    return forward_with(net, g, image_dev, probs_dev, ws_dev, (hipStream_t)hip_stream);
 }
 
 size_t mpcnn_workspace_bytes_same(const mpcnn_net* net, int B, int H, int W)
 {
     if (!net || B < 1 || H < 1 || W < 1) return 0;
-    Geom g;
-    if (!make_geom_same(net, B, H, W, &g)) return 0;
-    return g.total;
+    const auto g = geom_for(net, B, H, W, false, true);
+    return g ? g->total : 0;
 }
 
 mpcnn_status mpcnn_seg_forward_same(mpcnn_net* net, const float* image_dev, int B, int H, int W,
@@ -1408,42 +1448,37 @@ mpcnn_status mpcnn_seg_forward_same(mpcnn_net* net, const float* image_dev, int 
     const int widest = net->patch - 1 - (net->patch - 1) / 2;
     if (H < 1 || W < 1 || H < widest || W < widest)
         return fail(MPCNN_ESHAPE, "image %dx%d smaller than the %d-pixel mirrored border", H, W, widest);
-    Geom g;
-    if (!make_geom_same(net, B, H, W, &g)) return fail(MPCNN_ESHAPE, "layer plan does not fit a %dx%d image", H, W);
-    if (ws_bytes < g.total) return fail(MPCNN_EWORKSPACE, "workspace %zu bytes, need %zu", ws_bytes, g.total);
+    const auto g = geom_for(net, B, H, W, false, true);
+    if (!g) return fail(MPCNN_ESHAPE, "layer plan does not fit a %dx%d image", H, W);
+    if (ws_bytes < g->total) return fail(MPCNN_EWORKSPACE, "workspace %zu bytes, need %zu", ws_bytes, g->total);
     if (((uintptr_t)ws_dev & 255u) != 0) return fail(MPCNN_EINVAL, "workspace must be 256-byte aligned");
-    mpcnn_status st = net->bf16 ? run_forward<mpcnn::bf16>(net, g, image_dev, (char*)ws_dev, nullptr, nullptr,
-                                                           probs_dev, nullptr, nullptr, (hipStream_t)hip_stream)
-                                : run_forward<float>(net, g, image_dev, (char*)ws_dev, nullptr, nullptr, probs_dev,
-                                                     nullptr, nullptr, (hipStream_t)hip_stream);
-    net->last = g; net->last_ws = ws_dev;
-    return st;
+    return forward_with(net, g, image_dev, probs_dev, ws_dev, (hipStream_t)hip_stream);
 }
 
 mpcnn_status mpcnn_seg_backward(mpcnn_net* net, const float* image_dev, const int32_t* labels_dev,
                                 const float* pixw_dev, int B, int H, int W, float* probs_dev,
                                 double* loss_dev, void* ws_dev, size_t ws_bytes, void* hip_stream)
 {
-    Geom g;
-    mpcnn_status st = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, true, &g);
+    std::shared_ptr<const Geom> gp;
+    mpcnn_status st = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, true, &gp);
     if (st != MPCNN_OK) return st;
     if (!labels_dev) return fail(MPCNN_EINVAL, "null labels_dev");
+    const Geom& g = *gp;
     hipStream_t stream = (hipStream_t)hip_stream;
     char* ws = (char*)ws_dev;
     void* dZ = ws + g.delta_off[0];
     st = net->bf16 ? run_forward<mpcnn::bf16>(net, g, image_dev, ws, labels_dev, pixw_dev, probs_dev, dZ, loss_dev, stream)
                    : run_forward<float>(net, g, image_dev, ws, labels_dev, pixw_dev, probs_dev, dZ, loss_dev, stream);
-    net->last = g; net->last_ws = ws_dev;
+    net->last = gp; net->last_ws = ws_dev;
     if (st != MPCNN_OK) return st;
     return net->bf16 ? run_backward<mpcnn::bf16>(net, g, image_dev, ws, stream)
                      : run_backward<float>(net, g, image_dev, ws, stream);
 }
 
-// forward + summed loss, nothing kept (the workspace is a forward-only one)
 // geometry of one band of output rows [row0, row0 + rows) of a B x H x W image
 static bool make_geom_band(const mpcnn_net* net, int B, int H, int W, int row0, int rows, Geom* g)
 {
-    if (!make_geom(net, B, rows + net->patch - 1, W, true, g, true)) return false;
+    if (!make_geom(net, B, rows + net->patch - 1, W, true, g, true, true)) return false;
     g->pad_top = -row0; g->pad_left = 0; g->src_h = H; g->src_w = W;   // the band starts row0 rows down the image
     g->label_h = H; g->probs_rows = H - net->patch + 1;
     g->accumulate = row0 > 0;
@@ -1475,9 +1510,10 @@ mpcnn_status mpcnn_seg_backward_banded(mpcnn_net* net, const float* image_dev, c
     char* ws = (char*)ws_dev;
     for (int row0 = 0; row0 < Ho; row0 += band_rows) {
         const int rows = std::min(band_rows, Ho - row0);
-        Geom g;
-        if (!make_geom_band(net, B, H, W, row0, rows, &g))
+        auto gp = std::make_shared<Geom>();
+        if (!make_geom_band(net, B, H, W, row0, rows, gp.get()))
             return fail(MPCNN_ESHAPE, "layer plan does not fit a band of %d rows", rows);
+        const Geom& g = *gp;
         if (ws_bytes < g.total) return fail(MPCNN_EWORKSPACE, "workspace %zu bytes, need %zu", ws_bytes, g.total);
         // the band's labels, weights and probabilities start row0 rows down their arrays
         const int32_t* lab = labels_dev + (size_t)row0 * W;
@@ -1487,7 +1523,7 @@ mpcnn_status mpcnn_seg_backward_banded(mpcnn_net* net, const float* image_dev, c
         mpcnn_status st =
             net->bf16 ? run_forward<mpcnn::bf16>(net, g, image_dev, ws, lab, pw, pr, dZ, loss_dev, stream)
                       : run_forward<float>(net, g, image_dev, ws, lab, pw, pr, dZ, loss_dev, stream);
-        net->last = g; net->last_ws = ws_dev;
+        net->last = gp; net->last_ws = ws_dev;
         if (st != MPCNN_OK) return st;
         st = net->bf16 ? run_backward<mpcnn::bf16>(net, g, image_dev, ws, stream)
                        : run_backward<float>(net, g, image_dev, ws, stream);
@@ -1496,6 +1532,7 @@ mpcnn_status mpcnn_seg_backward_banded(mpcnn_net* net, const float* image_dev, c
     return MPCNN_OK;
 }
 
+// forward + summed loss, nothing kept (the workspace is a forward-only one)
 static mpcnn_status loss_only(mpcnn_net* net, const Geom& g, const float* image_dev, const int32_t* labels_dev,
                               const float* pixw_dev, double* loss_dev, char* ws, hipStream_t st)
 {
@@ -1520,11 +1557,11 @@ mpcnn_status mpcnn_seg_loss(mpcnn_net* net, const float* image_dev, const int32_
                             const float* pixw_dev, int B, int H, int W, double* loss_dev,
                             void* ws_dev, size_t ws_bytes, void* hip_stream)
 {
-    Geom g;
-    mpcnn_status st = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &g);
+    std::shared_ptr<const Geom> gp;
+    mpcnn_status st = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &gp);
     if (st != MPCNN_OK) return st;
     if (!labels_dev || !loss_dev) return fail(MPCNN_EINVAL, "null argument");
-    return loss_only(net, g, image_dev, labels_dev, pixw_dev, loss_dev, (char*)ws_dev, (hipStream_t)hip_stream);
+    return loss_only(net, *gp, image_dev, labels_dev, pixw_dev, loss_dev, (char*)ws_dev, (hipStream_t)hip_stream);
 }
 
 mpcnn_status mpcnn_armijo_step(mpcnn_net* net, const float* image_dev, const int32_t* labels_dev,
@@ -1533,9 +1570,10 @@ mpcnn_status mpcnn_armijo_step(mpcnn_net* net, const float* image_dev, const int
                                size_t ws_bytes, void* hip_stream, float* alpha_host, double* loss_host,
                                int* trials_host)
 {
-    Geom g;
-    mpcnn_status rc = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &g);
+    std::shared_ptr<const Geom> gp;
+    mpcnn_status rc = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &gp);
     if (rc != MPCNN_OK) return rc;
+    const Geom& g = *gp;
     if (!labels_dev) return fail(MPCNN_EINVAL, "null labels_dev");
     if (!(alpha0 > 0.f) || !(beta > 0.f && beta < 1.f) || !(c >= 0.f && c < 1.f) || max_trials < 1)
         return fail(MPCNN_EINVAL, "alpha0 = %g, beta = %g, c = %g, max_trials = %d", alpha0, beta, c, max_trials);
@@ -1591,9 +1629,10 @@ mpcnn_status mpcnn_lbfgs_step(mpcnn_net* net, const float* image_dev, const int3
                               int* trials_host, int* pairs_host)
 {
     using namespace mpcnn;
-    Geom g;
-    mpcnn_status rc = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &g);
+    std::shared_ptr<const Geom> gp;
+    mpcnn_status rc = check_call(net, image_dev, B, H, W, ws_dev, ws_bytes, false, &gp);
     if (rc != MPCNN_OK) return rc;
+    const Geom& g = *gp;
     if (!labels_dev) return fail(MPCNN_EINVAL, "null labels_dev");
     if (!(alpha0 > 0.f) || !(beta > 0.f && beta < 1.f) || !(c >= 0.f && c < 1.f) || max_trials < 1 ||
         history < 1 || history > 64)
@@ -1732,9 +1771,9 @@ mpcnn_status mpcnn_sgd_step(mpcnn_net* net, float lr, float grad_scale, void* hi
 mpcnn_status mpcnn_get_activation(const mpcnn_net* net, int layer, float* host, size_t n)
 {
     if (!net || !host) return fail(MPCNN_EINVAL, "null argument");
-    if (!net->last_ws || !net->last.training) return fail(MPCNN_EINVAL, "no backward call has been made");
+    if (!net->last_ws || !net->last || !net->last->training) return fail(MPCNN_EINVAL, "no backward call has been made");
     if (layer < 0 || layer >= (int)net->layers.size()) return fail(MPCNN_EINVAL, "layer %d out of range", layer);
-    const Geom& g = net->last;
+    const Geom& g = *net->last;
     size_t elems = (size_t)g.B * g.rows[layer] * g.cols[layer] * net->layers[layer].cout;
     if (n != elems) return fail(MPCNN_EINVAL, "n = %zu, layer holds %zu elements", n, elems);
     HIP_TRY(hipSetDevice(net->device));
@@ -1756,10 +1795,10 @@ mpcnn_status mpcnn_get_activation(const mpcnn_net* net, int layer, float* host, 
 mpcnn_status mpcnn_get_argmax(const mpcnn_net* net, int layer, uint8_t* host, size_t n)
 {
     if (!net || !host) return fail(MPCNN_EINVAL, "null argument");
-    if (!net->last_ws || !net->last.training) return fail(MPCNN_EINVAL, "no backward call has been made");
+    if (!net->last_ws || !net->last || !net->last->training) return fail(MPCNN_EINVAL, "no backward call has been made");
     if (layer < 0 || layer >= (int)net->layers.size() || net->layers[layer].kind != MPCNN_MP)
         return fail(MPCNN_EINVAL, "layer %d is not an MP layer", layer);
-    const Geom& g = net->last;
+    const Geom& g = *net->last;
     size_t elems = (size_t)g.B * g.rows[layer] * g.cols[layer] * net->layers[layer].cout;
     if (n != elems) return fail(MPCNN_EINVAL, "n = %zu, layer holds %zu elements", n, elems);
     HIP_TRY(hipSetDevice(net->device));

@@ -217,3 +217,50 @@ def sample_pixels(wl: Workload, n: int, seed: int) -> np.ndarray:
         for v in rng.integers(0, total, size=n - len(picked)):
             picked.add(int(v))
     return np.array(sorted(picked), dtype=np.int64)
+
+
+def sample_pixels_stratified(wl: Workload, n: int, seed: int, modulus: int = 16, blocks: int = 4) -> np.ndarray:
+    """Seeded subset of about n output pixels, as flat indices into [B, out_h, out_w], laid out so
+    that a fault confined to one part of a kernel's index space cannot hide between samples:
+
+    * every residue class (i mod modulus, j mod modulus) gets the same number of pixels
+      (modulus 16 = the largest tap spacing of the benchmark nets: every fragment of every layer),
+    * the pixels of a class are dealt round-robin over a blocks x blocks grid of image regions and
+      over the images of the batch (so every tile row / tile column of a launch, whatever its
+      tiling, has samples in several classes),
+    * the first and last output row and column of every image carry extra pixels, corners included.
+    """
+    B, oh, ow = wl.batch, wl.out_h, wl.out_w
+    rng = np.random.default_rng(seed)
+    picked = set()
+    m = min(modulus, oh, ow)
+    per = max(1, n // (m * m))
+    turn = 0
+    for ri in range(m):
+        for rj in range(m):
+            for _ in range(per):
+                b = turn % B
+                bi, bj = (turn // B) % blocks, (turn // (B * blocks)) % blocks
+                turn += 1
+                # rows of region bi with residue ri
+                lo_i, hi_i = bi * oh // blocks, (bi + 1) * oh // blocks
+                lo_j, hi_j = bj * ow // blocks, (bj + 1) * ow // blocks
+                rows = np.arange(ri, oh, m)
+                cols = np.arange(rj, ow, m)
+                rows_in = rows[(rows >= lo_i) & (rows < hi_i)]
+                cols_in = cols[(cols >= lo_j) & (cols < hi_j)]
+                i = int(rng.choice(rows_in if rows_in.size else rows))
+                j = int(rng.choice(cols_in if cols_in.size else cols))
+                picked.add((b * oh + i) * ow + j)
+    edge = max(4, n // 64)
+    for b in range(B):
+        base = b * oh * ow
+        for i, j in ((0, 0), (0, ow - 1), (oh - 1, 0), (oh - 1, ow - 1)):
+            picked.add(base + i * ow + j)
+        for j in rng.integers(0, ow, size=edge):
+            picked.add(base + int(j))
+            picked.add(base + (oh - 1) * ow + int(j))
+        for i in rng.integers(0, oh, size=edge):
+            picked.add(base + int(i) * ow)
+            picked.add(base + int(i) * ow + ow - 1)
+    return np.array(sorted(picked), dtype=np.int64)

@@ -4,7 +4,9 @@ patch-by-patch oracle, element by element, on the same seeded inputs.
 Bars: argmax tap codes bit-exact (see `check_argmax`), probabilities within 1e-4
 absolute, gradients within 1e-4 of the tensor's largest entry and in L2 norm,
 per parameter tensor; loss within 1e-5 relative.  With bf16 storage: 2e-2 / 2e-3, and a
-pooling window's two best candidates count as tied when within 2^-7.
+pooling window's two best candidates count as tied when within 2^-7 (more where the
+rounding a layer inherits is larger: `tau_of`).  How many windows may be resolved the other
+way than the oracle's is bounded (`check_tie_budget`).
 """
 import numpy as np
 import pytest
@@ -51,9 +53,86 @@ def tol_of(cfg):
     return TOL_BF16 if cfg.dtype == "bf16" else TOL
 
 
+def bf16_sigma(cfg):
+    """Estimated rms error of each layer's stored output with bf16 storage, from the arithmetic:
+    a stored value is rounded to 8 significant bits (error uniform within half an ulp, rms at
+    most 2^-9 / sqrt(3) for values up to 1); a unit's pre-activation is a sum of K products of
+    weights ~ U[-a, a] (mean square a^2 / 3) with inputs of magnitude up to 1 that carry the layer
+    below's error, the squashing function's slope is at most 1, pooling passes errors through:
+        e_l^2 = (a^2 / 3) K_l e_(l-1)^2 + (2^-9)^2 / 3,      e_image = 0 (generated representable).
+    Returns [e_l for every layer]."""
+    r2 = (2.0 ** -9) ** 2 / 3.0
+    a2 = cfg.weight_amp ** 2 / 3.0
+    rows = cols = cfg.patch
+    ch, e, out, seen_fc = cfg.in_channels, 0.0, [], False
+    for kind, maps, k, k2 in (_four(l) for l in cfg.layers):
+        if kind == MP:
+            rows, cols = rows // k, cols // k2
+        else:
+            kr, kc = (k, k) if kind == C else ((1, 1) if seen_fc else (rows, cols))
+            e = np.sqrt(a2 * kr * kc * ch * e * e + r2)
+            rows, cols, ch = rows - kr + 1, cols - kc + 1, maps
+            seen_fc = seen_fc or kind == FC
+        out.append(float(e))
+    return out
+
+
+def act_bar(cfg, li):
+    """Bar on the stored output of layer li against the oracle's.  fp32: a few ulps of the
+    squashing function.  bf16: five times the estimated rms error (the maximum is taken over
+    10^5 .. 10^7 elements), and never below the 2e-2 that covers the benchmark nets."""
+    if cfg.dtype != "bf16":
+        return 2e-5
+    return max(2e-2, 5.0 * bf16_sigma(cfg)[li])
+
+
 def tau_of(cfg):
-    """Top-2 gap of a pooling window below which either candidate may win on the GPU."""
-    return TIE_TAU_BF16 if cfg.dtype == "bf16" else TIE_TAU
+    """Top-2 gap of a pooling window below which either candidate may win on the GPU: 1e-5 with
+    fp32 storage (activations lie in [-1, 1]: about 100 ulps).  With bf16 storage two ulps at 1
+    (2^-7: values this close may round to a tie or swap), or, where a pooled layer inherits
+    more rounding than that, four times its estimated rms error (two values' errors meet in
+    a comparison)."""
+    if cfg.dtype != "bf16":
+        return TIE_TAU
+    sig = bf16_sigma(cfg)
+    pre_pool = [sig[li - 1] for li, l in enumerate(cfg.layers) if l[0] == MP and li > 0]
+    return max([TIE_TAU_BF16] + [4.0 * s for s in pre_pool])
+
+
+def windows_per_patch(cfg):
+    """Pooling windows one patch has, all MP layers and channels together."""
+    rows = cols = cfg.patch
+    ch, total = cfg.in_channels, 0
+    for kind, maps, k, k2 in (_four(l) for l in cfg.layers):
+        if kind == C:
+            rows, cols, ch = rows - k + 1, cols - k + 1, maps
+        elif kind == MP:
+            rows, cols = rows // k, cols // k2
+            total += ch * rows * cols
+        else:
+            break
+    return total
+
+
+def check_tie_budget(cfg, n_near, n_alt, n_windows):
+    """How many pooling windows may be near-ties, and how many of those the GPU may resolve the
+    other way.  The top-2 gap of a window has a density of 10 .. 25 per unit around zero on these
+    inputs (measured on the oracle: 2.4e-4 of the windows within 1e-5, 0.10 within 2^-7), so
+    at most 40 tau of the windows are near-ties (a check of tau, not of the kernel).  Of those,
+    fp32 arithmetic flips the ones whose gap is below the activations' own error (a few 1e-7
+    against tau = 1e-5: a few percent); bf16 storage makes an exact tie - first tap wins - of
+    a pair less than an ulp apart and can swap what the layers below moved: measured 6 .. 24 %.
+    A kernel that took the later of two close taps would flip about half of all near-ties.
+    Ceilings: 25 % (fp32) and 45 % (bf16) of the near-ties, plus 3 for small counts."""
+    tau = tau_of(cfg)
+    say("  tie budget: %d windows, near-ties %d (%.2e), other way %d (%.2e of the windows, %.1f %% of the near-ties)"
+        % (n_windows, n_near, n_near / max(n_windows, 1), n_alt, n_alt / max(n_windows, 1),
+           100.0 * n_alt / max(n_near, 1)))
+    # (a full image's patches share windows: its count of distinct windows is lower than
+    # patches x windows per patch, so the first bound is only applied to sparse samples)
+    frac = 0.45 if cfg.dtype == "bf16" else 0.25
+    assert n_alt <= frac * n_near + 3, (cfg.name, "near-tie windows resolved the other way", n_alt, n_near)
+    assert n_alt <= frac * 40.0 * tau * n_windows + 3, (cfg.name, "share of all windows", n_alt, n_windows)
 
 
 def check_grads(cfg, g_gpu, g_ref, tol=None):
@@ -192,7 +271,10 @@ def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_lay
     say("case %s B=%d %dx%d" % (cfg.name, cfg.batch, cfg.height, cfg.width))
     net, probs, loss, grads = run_gpu(cfg, img, lab, params, pixw, loss_fn=loss_fn, squash=squash, tiling=tiling)
     ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, pixw, None, net, loss_fn, squash)
-    say("  near-tie windows %d, resolved the other way on the GPU %d" % (n_near, n_alt))
+    n_windows = sum(int(np.prod(oracle.dense_shape(cfg.layers, cfg.in_channels, cfg.patch, cfg.batch, cfg.height,
+                                                   cfg.width, li)[:4]))
+                    for li, l in enumerate(cfg.layers) if l[0] == MP)
+    check_tie_budget(cfg, n_near, n_alt, n_windows)
     e_p = np.abs(probs - ref["probs"]).max()
     assert e_p <= tol_of(cfg), (cfg.name, "probs", e_p)
     assert abs(loss - ref["loss"]) <= 0.1 * tol_of(cfg) * abs(ref["loss"]), (loss, ref["loss"])
@@ -208,9 +290,7 @@ def full_parity(cfg, seed_shift=0, with_pixw=False, ignore_some=False, check_lay
             a = net.get_activation(B, H, W, li).transpose(0, 3, 1, 2)
             cov = d["covered"][:, None]
             err = np.abs(a - d["act"])[np.broadcast_to(cov, a.shape)].max()
-            # fp32: a few ulps of tanh; bf16: each stored value is rounded (half an ulp = 2^-9 at 1)
-            # on top of the rounding inherited from the layers below
-            assert err <= (2e-2 if cfg.dtype == "bf16" else 2e-5), (cfg.name, "activation of layer", li, err)
+            assert err <= act_bar(cfg, li), (cfg.name, "activation of layer", li, err, act_bar(cfg, li))
     e_g = check_grads(cfg, grads, ref["grads"])
     say("  probs err %.2e  grads err %.2e  loss %.6f  argmax excused %d" % (e_p, e_g, loss, excused))
     net.close()
@@ -443,7 +523,7 @@ def sampled_parity(cfg, n_sel, seed, argmax_layers=None):
     as per-pixel loss weights, which makes its summed gradient the sum over S."""
     img, lab = wl.make_inputs(cfg)
     params = wl.make_params(cfg)
-    sel = wl.sample_pixels(cfg, n_sel, seed)
+    sel = wl.sample_pixels_stratified(cfg, n_sel, seed)
     say("case %s sampled %d of %d pixels" % (cfg.name, sel.size, cfg.valid_pixels))
     c = (cfg.patch - 1) // 2
     b, rem = np.divmod(sel, cfg.out_h * cfg.out_w)
@@ -452,7 +532,8 @@ def sampled_parity(cfg, n_sel, seed, argmax_layers=None):
     mask[b, i + c, j + c] = 1.0
     net, probs, loss, grads = run_gpu(cfg, img, lab, params, mask)
     ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, None, sel, net)
-    say("  near-tie windows %d, resolved the other way on the GPU %d" % (n_near, n_alt))
+    check_tie_budget(cfg, n_near, n_alt, sel.size * windows_per_patch(cfg))
+    assert n_near <= 40.0 * tau_of(cfg) * sel.size * windows_per_patch(cfg) + 3, (cfg.name, "near-ties", n_near)
     e_p = np.abs(probs[b, :, i, j] - ref["probs"]).max()
     assert e_p <= tol_of(cfg), e_p
     assert abs(loss - ref["loss"]) <= 0.1 * tol_of(cfg) * abs(ref["loss"]), (loss, ref["loss"])
@@ -465,25 +546,107 @@ def sampled_parity(cfg, n_sel, seed, argmax_layers=None):
 
 
 def test_cfg1_full_size_sampled():
-    net, img, lab, params = sampled_parity(wl.CONFIGS[1], 384, 11)
+    net, img, lab, params = sampled_parity(wl.CONFIGS[1], 512, 11)
     net.close()
 
 
-def test_cfg2_full_size_sampled_and_sgd():
+def sgd_trajectory(cfg, lr, steps, sel, img, lab, params, net=None, d_img=None, d_lab=None, d_mask=None):
+    """`steps` x (forward + backward + SGD step on the MEAN loss of the sampled pixels) on both
+    sides from the same start: the oracle steps in fp64 on the sampled pixels, the GPU on the
+    whole image with the indicator of the sample as loss weights.  Returns per-step losses
+    and final parameters of either side and the oracle's first and last gradients."""
+    args = (cfg.layers, cfg.in_channels, cfg.patch)
+    img64 = img.astype(np.float64)
+    th = params.astype(np.float64)
+    l_ref, g_first, g_last = [], None, None
+    for _ in range(steps):
+        r = oracle.run(*args, th, img64, lab, sel=sel, want_grads=True, want_probs=False)
+        l_ref.append(r["loss"])
+        g_first = r["grads"] if g_first is None else g_first
+        g_last = r["grads"]
+        th = th - (lr / sel.size) * r["grads"]
+    net.set_params(params)
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    l_gpu = []
+    for _ in range(steps):
+        net.seg_backward(d_img, d_lab, d_mask, None, loss)
+        net.sgd_step(lr, 1.0 / sel.size)
+        l_gpu.append(float(loss.item()))
+    torch.cuda.synchronize()
+    return np.array(l_ref), th, np.array(l_gpu), net.get_params().astype(np.float64), g_first, g_last
+
+
+def check_trajectory(cfg, lr, steps, n_sel, seed):
+    """Results, "Membrane Segmentation": the weights are updated after every image.  Strict
+    parity at the first step is `sampled_parity`'s; here the same `steps` updates are made on
+    both sides and compared at 10 x the one-step tolerance: the loss of every step, the
+    total parameter update per tensor.  A stale copy of the weights inside the library
+    (operand packs, bf16 copies) would freeze the loss sequence and the gradients: the checks
+    below require the oracle's own sequence to move by more than the bar."""
+    img, lab = wl.make_inputs(cfg)
+    params = wl.make_params(cfg)
+    sel = wl.sample_pixels_stratified(cfg, n_sel, seed)
+    c = (cfg.patch - 1) // 2
+    b, rem = np.divmod(sel, cfg.out_h * cfg.out_w)
+    i, j = np.divmod(rem, cfg.out_w)
+    mask = np.zeros(lab.shape, dtype=np.float32)
+    mask[b, i + c, j + c] = 1.0
+    net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch, dtype=mpcnn.BF16 if cfg.dtype == "bf16" else mpcnn.F32)
+    d_img, d_lab, d_mask = torch.from_numpy(img).cuda(), torch.from_numpy(lab).cuda(), torch.from_numpy(mask).cuda()
+    tol = 10.0 * tol_of(cfg)
+    l_ref, th_ref, l_gpu, th_gpu, g_first, g_last = sgd_trajectory(cfg, lr, steps, sel, img, lab, params, net, d_img,
+                                                                  d_lab, d_mask)
+    say("case %s: %d SGD steps at lr %g on %d sampled pixels" % (cfg.name, steps, lr, sel.size))
+    say("  loss, oracle: " + " ".join("%.5f" % v for v in l_ref))
+    say("  loss, GPU   : " + " ".join("%.5f" % v for v in l_gpu))
+    # the loss of every step, and that the sequence moves by more than the bar allows to miss
+    assert np.abs(l_gpu - l_ref).max() <= 0.1 * tol * np.abs(l_ref).max(), (l_gpu, l_ref)
+    assert abs(l_ref[1] - l_ref[0]) > 0.2 * tol * abs(l_ref[0]), "pick a larger lr: the loss hardly moves"
+    worst = 0.0
+    for name, sl in param_tensors(cfg.layers, cfg.in_channels, cfg.patch):
+        d_ref, d_gpu = th_ref[sl] - params[sl], th_gpu[sl] - params[sl]
+        e = np.abs(d_gpu - d_ref).max() / np.abs(d_ref).max()
+        worst = max(worst, e)
+        assert e <= tol, (cfg.name, name, "update after %d steps" % steps, e)
+    moved = np.linalg.norm(g_last - g_first) / np.linalg.norm(g_first)
+    say("  parameter update err %.2e (bar %.0e); the oracle's gradient moved by %.2e over the steps" % (worst, tol, moved))
+    net.close()
+    return moved
+
+
+def test_cfg2_full_size_sampled():
+    net, img, lab, params = sampled_parity(wl.CONFIGS[2], 256, 12)
+    # one SGD step: theta' = theta - lr * scale * g, to the last bit but one
     cfg = wl.CONFIGS[2]
-    net, img, lab, params = sampled_parity(cfg, 256, 12)
-    # one SGD step on the mean loss of the sampled pixels: theta' = theta - lr * scale * g
     g = net.get_grads()
     net.sgd_step(cfg.lr, 1.0 / 256)
     torch.cuda.synchronize()
     expect = params.astype(np.float64) - (cfg.lr / 256) * g.astype(np.float64)
     np.testing.assert_allclose(net.get_params(), expect, rtol=0, atol=1e-8)   # one fp32 ulp at 0.05 is 3.7e-9
-    assert np.abs(net.get_params() - params).max() > 0
     net.close()
 
 
+def test_cfg2_ten_sgd_steps():
+    """Config 2 as stated: 10 x (forward + backward + SGD, lr 1e-3 on the mean loss)."""
+    cfg = wl.CONFIGS[2]
+    check_trajectory(cfg, cfg.lr, cfg.sgd_steps, 256, 12)
+    # the same with a step size at which the gradient itself changes by far more than the bar
+    # over the ten steps (a gradient evaluated at stale weights could not pass)
+    moved = check_trajectory(cfg, 0.05, cfg.sgd_steps, 256, 12)
+    assert moved > 0.1
+
+
+def test_bf16_ten_sgd_steps():
+    """The same with bf16 storage: the kernels read a bf16 copy of the parameters that must
+    follow every update of the fp32 originals."""
+    cfg = wl.Workload("bf16_small_sgd", _NET_BF16_SMALL, 14, 3, 3, 2, 90, 77, 0.25, "ellipses", dtype="bf16",
+                      seed_image=1120, seed_label=2120, seed_param=3120)
+    moved = check_trajectory(cfg, 0.05, 10, 256, 19)
+    assert moved > 0.1
+
+
 def test_cfg3_full_size_sampled():
-    net, img, lab, params = sampled_parity(wl.CONFIGS[3], 48, 13)
+    net, img, lab, params = sampled_parity(wl.CONFIGS[3], 1024, 13)
     net.close()
 
 
@@ -493,7 +656,7 @@ def test_large_image_sampled():
     probabilities and summed gradients against the oracle, tap codes of the first pool against
     a scan."""
     cfg = wl.crop(wl.CONFIGS[1], 1, 3072, 3000, "_large")
-    net, img, lab, params = sampled_parity(cfg, 96, 17, argmax_layers=(1,))
+    net, img, lab, params = sampled_parity(cfg, 512, 17, argmax_layers=(1,))
     net.close()
 
 
@@ -529,7 +692,7 @@ def test_cfg4_net_crop_full_oracle_bf16():
 def test_cfg4_full_size_sampled_bf16():
     # the tap codes are checked against a scan of the GPU's own values on the deeper pooling
     # layers (the first one alone would move 3 GB to the host)
-    net, img, lab, params = sampled_parity(wl.CONFIGS[4], 24, 14, argmax_layers=(5, 7))
+    net, img, lab, params = sampled_parity(wl.CONFIGS[4], 512, 14, argmax_layers=(5, 7))
     net.close()
 
 
