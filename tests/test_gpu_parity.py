@@ -115,24 +115,29 @@ def windows_per_patch(cfg):
 
 
 def check_tie_budget(cfg, n_near, n_alt, n_windows):
-    """How many pooling windows may be near-ties, and how many of those the GPU may resolve the
-    other way.  The top-2 gap of a window has a density of 10 .. 25 per unit around zero on these
-    inputs (measured on the oracle: 2.4e-4 of the windows within 1e-5, 0.10 within 2^-7), so
-    at most 40 tau of the windows are near-ties (a check of tau, not of the kernel).  Of those,
-    fp32 arithmetic flips the ones whose gap is below the activations' own error (a few 1e-7
-    against tau = 1e-5: a few percent); bf16 storage makes an exact tie - first tap wins - of
-    a pair less than an ulp apart and can swap what the layers below moved: measured 6 .. 24 %.
-    A kernel that took the later of two close taps would flip about half of all near-ties.
-    Ceilings: 25 % (fp32) and 45 % (bf16) of the near-ties, plus 3 for small counts."""
-    tau = tau_of(cfg)
+    """How many of the near-tie pooling windows the GPU may resolve the other way than the
+    oracle.  How many windows are near-ties at all is a property of the inputs and of tau, not of
+    the kernels: the top-2 gap of a window has a density of 10 .. 40 per unit around zero with
+    tanh on these inputs (measured on the oracle: 2 .. 4e-4 of the windows within 1e-5, 0.10
+    within 2^-7) and far more where the activations crowd together (logistic units behind small
+    weights: 5e-2 within 1e-5); it is printed, not bounded.  Of the near-ties, fp32 arithmetic
+    flips those whose gap is below the activations' own error (a few 1e-7 against tau = 1e-5:
+    a few percent at most); bf16 storage makes an exact tie - first tap wins - of a pair less
+    than an ulp apart whose later tap is the larger, and can swap what the layers below moved:
+    measured 6 .. 24 % with 2x2 windows, 41 % with 3x3 windows over logistic units (where most of
+    a window rounds to one value, the oracle's winner is any of its p*p taps and the GPU's the
+    first).  A kernel that took the later of two close taps, or any tap but the first of equals,
+    would flip about half of all near-ties in fp32.  Ceilings on the flipped share: 25 % (fp32);
+    with bf16 storage 0.8 (1 - 1/p^2) for the largest window p x p - loose, which is why
+    `check_argmax` also predicts the first pool's codes from the oracle's values rounded to bf16.
+    Plus 3 for small counts."""
     say("  tie budget: %d windows, near-ties %d (%.2e), other way %d (%.2e of the windows, %.1f %% of the near-ties)"
         % (n_windows, n_near, n_near / max(n_windows, 1), n_alt, n_alt / max(n_windows, 1),
            100.0 * n_alt / max(n_near, 1)))
-    # (a full image's patches share windows: its count of distinct windows is lower than
-    # patches x windows per patch, so the first bound is only applied to sparse samples)
-    frac = 0.45 if cfg.dtype == "bf16" else 0.25
+    frac = 0.25
+    if cfg.dtype == "bf16":
+        frac = 0.8 * (1.0 - 1.0 / max([_four(l)[2] * _four(l)[3] for l in cfg.layers if l[0] == MP] + [2]))
     assert n_alt <= frac * n_near + 3, (cfg.name, "near-tie windows resolved the other way", n_alt, n_near)
-    assert n_alt <= frac * 40.0 * tau * n_windows + 3, (cfg.name, "share of all windows", n_alt, n_windows)
 
 
 def check_grads(cfg, g_gpu, g_ref, tol=None):
@@ -253,6 +258,24 @@ def check_argmax(cfg, net, img, params, with_oracle=True, layers=None, squash="t
             tau = tau_of(cfg)
             assert not (bad & (o_gap > tau)).any(), (cfg.name, li, int((bad & (o_gap > tau)).sum()))
             excused += int(bad.sum())
+            if cfg.dtype == "bf16" and li <= 1:
+                # bf16 storage, the first pool: its input is the image (exact) or the first layer's
+                # output, which the GPU forms in fp32 from exact inputs and then rounds; so the
+                # stored values equal the oracle's rounded to bf16 unless a value lies within
+                # ~1e-6 of a rounding boundary (2.5e-4 of the values at an ulp of 2^-8), and the
+                # codes must be those of a first-maximum scan over the rounded oracle values
+                if li == 0:
+                    o_pre = img.astype(np.float64)
+                else:
+                    o_pre = oracle.dense_layer(cfg.layers, cfg.in_channels, cfg.patch, params.astype(np.float64),
+                                               img.astype(np.float64), li - 1, squash=squash)["act"]
+                o_pre = wl.round_bf16(o_pre.astype(np.float32)).transpose(0, 2, 3, 1)
+                p_codes, _ = first_max_codes(np.ascontiguousarray(o_pre), k, dil, k2, dil2)
+                p_codes = p_codes[:, :codes.shape[1], :codes.shape[2]]
+                off = int(((codes != p_codes) & cov).sum())
+                say("  first pool, bf16: %d of %d codes differ from the scan of the oracle's rounded values"
+                    % (off, int(np.broadcast_to(cov, codes.shape).sum())))
+                assert off <= 2e-3 * np.broadcast_to(cov, codes.shape).sum() + 3, (cfg.name, li, off)
         dil *= k
         dil2 *= k2
     return excused
@@ -533,7 +556,6 @@ def sampled_parity(cfg, n_sel, seed, argmax_layers=None):
     net, probs, loss, grads = run_gpu(cfg, img, lab, params, mask)
     ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, None, sel, net)
     check_tie_budget(cfg, n_near, n_alt, sel.size * windows_per_patch(cfg))
-    assert n_near <= 40.0 * tau_of(cfg) * sel.size * windows_per_patch(cfg) + 3, (cfg.name, "near-ties", n_near)
     e_p = np.abs(probs[b, :, i, j] - ref["probs"]).max()
     assert e_p <= tol_of(cfg), e_p
     assert abs(loss - ref["loss"]) <= 0.1 * tol_of(cfg) * abs(ref["loss"]), (loss, ref["loss"])
