@@ -169,6 +169,27 @@ mpcnn_status mpcnn_seg_forward(mpcnn_net* net, const float* image_dev, int B, in
                                float* probs_dev, void* ws_dev, size_t ws_bytes, void* hip_stream);
 
 /*
+ * mpcnn_seg_forward for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The caller passes the image
+ * and the output only; the workspace is a fixed array of MPCNN_STATIC_WORKSPACE_BYTES inside the
+ * library's device image (each GPU the library runs on holds its own copy until the process
+ * ends; its address on the net's device is looked up when mpcnn_set_params first touches that
+ * device).  The call allocates nothing and frees nothing, on the device or through the HIP
+ * runtime; per-launch timing (mpcnn_profile_enable) is off during it.  Results are those of
+ * mpcnn_seg_forward, bit for bit.
+ *   - The net's device must be the current device.
+ *   - Sizes with mpcnn_workspace_bytes(net, B, H, W, 0) > MPCNN_STATIC_WORKSPACE_BYTES are
+ *     refused with MPCNN_EWORKSPACE (the message names both figures).
+ *   - All calls on one GPU share that GPU's array (every net, every stream): calls that overlap
+ *     in time race.  Nothing in it has to start at zero: each call writes what it reads.
+ * Errors: EINVAL (null pointer, parameters never set, another device current), ESHAPE,
+ * EWORKSPACE, EHIP.
+ */
+#define MPCNN_STATIC_WORKSPACE_BYTES (64u * 1024u * 1024u)
+mpcnn_status mpcnn_seg_forward_static(mpcnn_net* net, const float* image_dev, int B, int H, int W,
+                                      float* probs_dev, void* hip_stream);
+
+/*
  * Deployment forward that keeps the image size (Experiments, membrane segmentation:
  * pixels outside the boundary of a test image are synthesised by mirroring, which
  * preserves the size of the output):

@@ -29,6 +29,12 @@
 #include "kernels_first_bf16.hpp"
 #include "kernels_fused.hpp"
 
+// Device memory of mpcnn_seg_forward_static: a fixed array in the library's device image, so that
+// the call needs no allocation.  Every GPU the library runs on holds its own copy, at its own
+// address, until the process ends.  In host code the name below is only a handle for
+// hipGetSymbolAddress; the kernels are given the address that call returns.
+static __device__ __align__(256) unsigned char scratch[MPCNN_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -1153,6 +1159,25 @@ std::shared_ptr<const Geom> geom_for(const mpcnn_net* net, int B, int H, int W, 
     return g;
 }
 
+// Address of `scratch` on device `dev`, which must be the current device; looked up once per
+// device and kept.
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+mpcnn_status scratch_address(int dev, void** out)
+{
+    if (dev < 0 || dev >= kMaxDevices) return fail(MPCNN_EINVAL, "device %d: at most %d devices", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(MPCNN_EHIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MPCNN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1320,6 +1345,9 @@ mpcnn_status mpcnn_set_params(mpcnn_net* net, const float* params_host, size_t n
             if (occ > 0) net->class_max_blocks = std::min(kLossBlocks, kNumCU * occ);
         }
         net->geoms.clear();   // plans made before this point counted the class layer's shares differently
+        void* unused = nullptr;   // (the static workspace's address on this device, for later calls)
+        rc = scratch_address(net->device, &unused);
+        if (rc != MPCNN_OK) return rc;
     }
     std::vector<float> tmp(n);
     to_device_order(net, params_host, tmp.data());
@@ -1430,6 +1458,32 @@ mpcnn_status mpcnn_seg_forward(mpcnn_net* net, const float* image_dev, int B, in
     if (st != MPCNN_OK) return st;
     if (!probs_dev) return fail(MPCNN_EINVAL, "null probs_dev");
     return forward_with(net, g, image_dev, probs_dev, ws_dev, (hipStream_t)hip_stream);
+}
+
+mpcnn_status mpcnn_seg_forward_static(mpcnn_net* net, const float* image_dev, int B, int H, int W,
+                                      float* probs_dev, void* hip_stream)
+{
+    if (!net || !image_dev || !probs_dev) return fail(MPCNN_EINVAL, "null argument");
+    if (!net->d_params) return fail(MPCNN_EINVAL, "parameters were never set");
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != net->device)
+        return fail(MPCNN_EINVAL, "device %d is current, the net lives on device %d", dev, net->device);
+    void* ws = nullptr;
+    mpcnn_status st = scratch_address(dev, &ws);
+    if (st != MPCNN_OK) return st;
+    std::shared_ptr<const Geom> g;
+    st = check_call(net, image_dev, B, H, W, ws, (size_t)MPCNN_STATIC_WORKSPACE_BYTES, false, &g);
+    if (st == MPCNN_EWORKSPACE)
+        return fail(MPCNN_EWORKSPACE, "a %d x %dx%d batch needs %zu bytes of workspace, the static one holds %zu",
+                    B, H, W, g->total, (size_t)MPCNN_STATIC_WORKSPACE_BYTES);
+    if (st != MPCNN_OK) return st;
+    // (the per-launch timing hooks create events: not in a call that must not allocate)
+    const bool prof = net->prof_on;
+    net->prof_on = false;
+    st = forward_with(net, g, image_dev, probs_dev, ws, (hipStream_t)hip_stream);
+    net->prof_on = prof;
+    return st;
 }
 
 size_t mpcnn_workspace_bytes_same(const mpcnn_net* net, int B, int H, int W)

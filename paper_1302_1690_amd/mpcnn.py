@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmpcnn.so")
 
 KIND_C, KIND_MP, KIND_FC = 0, 1, 2
+STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024   # MPCNN_STATIC_WORKSPACE_BYTES
 F32, BF16 = 0, 1
 
 STATUS = {0: "MPCNN_OK", 1: "MPCNN_EINVAL", 2: "MPCNN_ESHAPE", 3: "MPCNN_EWORKSPACE",
@@ -31,7 +32,7 @@ SYMBOLS = [
     "mpcnn_profile_enable", "mpcnn_profile_read", "mpcnn_workspace_bytes_same", "mpcnn_seg_forward_same",
     "mpcnn_set_loss", "mpcnn_class_balance_weights", "mpcnn_seg_loss", "mpcnn_armijo_step",
     "mpcnn_lbfgs_step", "mpcnn_lbfgs_reset", "mpcnn_set_activation", "mpcnn_set_conv_tiling",
-    "mpcnn_workspace_bytes_banded", "mpcnn_seg_backward_banded",
+    "mpcnn_workspace_bytes_banded", "mpcnn_seg_backward_banded", "mpcnn_seg_forward_static",
 ]
 
 
@@ -82,6 +83,7 @@ def lib():
         L.mpcnn_workspace_bytes.argtypes = [vp, i, i, i, i]
         L.mpcnn_workspace_bytes.restype = sz
         L.mpcnn_seg_forward.argtypes = [vp, vp, i, i, i, vp, vp, sz, vp]
+        L.mpcnn_seg_forward_static.argtypes = [vp, vp, i, i, i, vp, vp]
         L.mpcnn_workspace_bytes_same.argtypes = [vp, i, i, i]
         L.mpcnn_workspace_bytes_same.restype = sz
         L.mpcnn_seg_forward_same.argtypes = [vp, vp, i, i, i, vp, vp, sz, vp]
@@ -207,6 +209,13 @@ class Net:
                                 dtype=torch.float32, device=image.device)
         _check(lib().mpcnn_seg_forward(self._h, _ptr(image), B, H, W, _ptr(probs), _ptr(ws),
                                        ws.numel(), _stream_handle(stream)))
+        return probs
+
+    def seg_forward_static(self, image, probs, stream=None):
+        """seg_forward on the library's fixed device workspace: no allocation anywhere in the
+        call (the caller supplies `probs`)."""
+        B, _, H, W = image.shape
+        _check(lib().mpcnn_seg_forward_static(self._h, _ptr(image), B, H, W, _ptr(probs), _stream_handle(stream)))
         return probs
 
     def seg_loss(self, image, labels, pixw=None, ws=None, stream=None) -> float:
