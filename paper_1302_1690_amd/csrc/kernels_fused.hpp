@@ -91,8 +91,12 @@ __global__ __launch_bounds__(256) void first_layer_kernel(const T* __restrict__ 
 // Index plumbing of the two max-filter kernels.  A workgroup takes 256 consecutive
 // (column, channel quad) items of one map row.  Workgroups are handed to the 8 XCDs in
 // turn, so the launch index is first turned into a position in eight contiguous bands of
-// rows, one per XCD: the rows a window straddles (d apart) are then read through the same
-// L2 shortly after each other instead of being fetched from memory once per XCD.
+// the row sequence, one per XCD.  The sequence walks an image's rows one residue class
+// (row mod d) after the other - rows r, r + d, r + 2d, ..: the two rows a window straddles
+// (d apart) are then neighbours in the sequence, so the second row of one window is still
+// in that XCD's L2 when it comes up as the first row of the next (in plain row order d rows
+// of the map lie between the two uses, which at d = 8 and 128 channels is more than an L2
+// holds: every row was fetched from memory twice).
 // All divisions are by launch constants: multiply-high with ceil(2^32 / x) (exact for
 // n * x < 2^32, x > 1).
 struct RowGrid {
@@ -101,6 +105,9 @@ struct RowGrid {
     int h;             // rows per image
     int C4;            // channel quads
     unsigned mg_gx, mg_h, mg_c4;
+    int d;             // tap spacing (row order: residue classes mod d, one after the other)
+    int n1, rem;       // the first `rem` classes have n1 = ceil(h / d) rows, the others n1 - 1
+    unsigned mg_n1, mg_n0;
 };
 __device__ __forceinline__ unsigned rg_div(unsigned n, unsigned magic, unsigned x)
 {
@@ -117,7 +124,19 @@ __device__ __forceinline__ bool rg_locate(const RowGrid& g, int width, int* b, i
     if (it >= (unsigned)(width * g.C4)) return false;
     const unsigned xx = rg_div(it, g.mg_c4, g.C4);
     const unsigned bb = rg_div(row, g.mg_h, g.h);
-    *b = (int)bb; *y = (int)(row - bb * g.h); *x = (int)xx; *c4 = (int)(it - xx * g.C4);
+    unsigned t = row - bb * g.h;                     // place in the image's row sequence -> row
+    if (g.d > 1) {
+        const unsigned big = (unsigned)(g.rem * g.n1);
+        if (t < big) {
+            const unsigned r = rg_div(t, g.mg_n1, g.n1);
+            t = r + (t - r * g.n1) * g.d;
+        } else {
+            const unsigned n0 = g.n1 - 1, u = t - big;
+            const unsigned r = rg_div(u, g.mg_n0, n0);
+            t = g.rem + r + (u - r * n0) * g.d;
+        }
+    }
+    *b = (int)bb; *y = (int)t; *x = (int)xx; *c4 = (int)(it - xx * g.C4);
     return true;
 }
 

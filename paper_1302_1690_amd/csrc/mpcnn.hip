@@ -629,7 +629,7 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
 
 // Launch geometry of the max-filter kernels: 256 (column, channel quad) items of one map row
 // per workgroup.  False if the map is too large for their 32-bit index arithmetic.
-bool row_grid(int B, int h, int w, int C4, mpcnn::RowGrid* g)
+bool row_grid(int B, int h, int w, int C4, int d, mpcnn::RowGrid* g)
 {
     const long per_row = (long)w * C4, gx = (per_row + 255) / 256, rows = (long)B * h;
     if (gx * rows >= (1l << 31) || gx * rows * gx >= (1l << 32) || (gx * 256) * C4 >= (1l << 32) ||
@@ -637,6 +637,11 @@ bool row_grid(int B, int h, int w, int C4, mpcnn::RowGrid* g)
         return false;
     g->gx = (int)gx; g->rows = (int)rows; g->h = h; g->C4 = C4;
     g->mg_gx = magic_of((unsigned)gx); g->mg_h = magic_of((unsigned)h); g->mg_c4 = magic_of((unsigned)C4);
+    // row order: residue classes mod d (h rows: the first h mod d classes have one row more)
+    g->d = d < h ? d : 1;
+    g->rem = h % g->d; g->n1 = h / g->d + (g->rem ? 1 : 0);
+    if (g->rem == 0) g->rem = g->d;          // all classes have n1 rows
+    g->mg_n1 = magic_of((unsigned)g->n1); g->mg_n0 = magic_of((unsigned)(g->n1 - 1));
     return true;
 }
 
@@ -799,11 +804,11 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             uint8_t* code = g.training ? (uint8_t*)(ws + g.code_off[l]) : nullptr;
             long total = (long)B * Ho * Wo * ly.cout;
             mpcnn::RowGrid rg;
-            if (!kF32 && !ly.rect && ly.cout % 8 == 0 && row_grid(B, Ho, Wo, ly.cout / 8, &rg))   // bf16: 8 channels per thread (fp32: measured slower)
+            if (!kF32 && !ly.rect && ly.cout % 8 == 0 && row_grid(B, Ho, Wo, ly.cout / 8, ly.dil, &rg))   // bf16: 8 channels per thread (fp32: measured slower)
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
                        (maxfilter_fwd4_kernel<T, kF32 ? 1 : 2><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
                            in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil)));
-            else if (!ly.rect && ly.cout % 4 == 0 && row_grid(B, Ho, Wo, ly.cout / 4, &rg))
+            else if (!ly.rect && ly.cout % 4 == 0 && row_grid(B, Ho, Wo, ly.cout / 4, ly.dil, &rg))
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
                        (maxfilter_fwd4_kernel<T, 1><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
                            in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil)));
@@ -948,8 +953,8 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
             long total = (long)B * Hi * Wi * Ci;
             const double bytes = n_out * (es + 1.0) + n_in * es * (below_tanh ? 2.0 : 1.0);
             mpcnn::RowGrid rg;
-            const bool octs = !ly.rect && Ci % 8 == 0 && row_grid(B, Hi, Wi, Ci / 8, &rg);   // 8 channels per thread (measured faster in both storage types)
-            const bool quads = !ly.rect && !octs && Ci % 4 == 0 && row_grid(B, Hi, Wi, Ci / 4, &rg);
+            const bool octs = !ly.rect && Ci % 8 == 0 && row_grid(B, Hi, Wi, Ci / 8, ly.dil, &rg);   // 8 channels per thread (measured faster in both storage types)
+            const bool quads = !ly.rect && !octs && Ci % 4 == 0 && row_grid(B, Hi, Wi, Ci / 4, ly.dil, &rg);
             if (octs && below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        (maxfilter_bwd4_kernel<true, T, 2><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
