@@ -108,6 +108,13 @@ size_t mpcnn_param_count(const mpcnn_net* net); /* length of the flat parameter 
 mpcnn_status mpcnn_layer_shape(const mpcnn_net* net, int H, int W, int layer, int* rows, int* cols,
                                int* channels, int* spacing);
 
+/* Diagnostic: which kernel, tiling and launch shape the library would use for every layer of a
+ * call with these sizes (the tiling rule is the paper's fragment: a workgroup's tile is a
+ * rectangle of one residue class of the whole-image map), as NUL-terminated text of at most
+ * `cap` bytes in text_host (cut off if longer).  Host-only.  Errors: EINVAL, ESHAPE. */
+mpcnn_status mpcnn_plan_describe(const mpcnn_net* net, int B, int H, int W, int training, char* text_host,
+                                 size_t cap);
+
 /* Copy the flat fp32 parameter vector from / to the host (synchronous).
  * n must equal mpcnn_param_count().  The first mpcnn_set_params allocates the
  * parameter and gradient buffers on the current device. */

@@ -14,7 +14,7 @@ namespace mpcnn {
 // conv_ts_kernel with MP position tiles per wave.  False if no instance is built for the tuple.
 bool launch_conv_f32(const ConvArgs& a, int W, int OT, int PT, int NW, int MP, dim3 grid, size_t lds, hipStream_t st);
 bool launch_conv_b16(const ConvArgs& a, int W, int OT, int PT, int NW, int MP, dim3 grid, size_t lds, hipStream_t st);
-// bf16 storage on the bf16 matrix instruction
+// bf16 storage on the bf16 matrix instruction: conv_ts_kernel<OT, PT, MP, bf16, true>
 bool launch_conv_bm(const ConvArgs& a, int OT, int PT, int NW, int MP, dim3 grid, size_t lds, hipStream_t st);
 
 // Weight gradient (kernels_wgrad.hpp, kernels_wgrad_bf16.hpp); a.mw selects the instance.

@@ -327,6 +327,40 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, co
             }
         if (best.ok) return best;
     }
+    if (bm) {
+        // conv_ts_kernel on the bf16 matrix instruction (32 cycles per instruction, 16 channels
+        // of a tap per step).  The instruction stream of a workgroup is an eighth of the fp32
+        // one, so staging and stores weigh 8 times more: large tiles, MP = 4 where possible (a wave
+        // with 2 position tiles asks the vector cache for twice the weights per instruction: the
+        // cache, not the matrix pipe, then sets the pace), two workgroups per compute unit.
+        const int steps = k * k * (rpad / 16);
+        for (int PT : {2, 4, 8, 16})
+            for (int MP : {2, 4}) {
+                const int NW = ct.OT * PT / MP;
+                if (PT % MP || (NW != 4 && NW != 8)) continue;
+                const double t_mul1 = (double)steps * ct.OT * PT * 32 / 4 * (MP == 4 ? 1.0 : 1.6);
+                for (int ty = 1; ty <= std::min(fh, 32 * PT); ++ty)
+                    for (int tx = 1; tx <= std::min(fw, 32 * PT / ty); ++tx) {
+                        const size_t lds = std::max((size_t)(ty + k - 1) * (tx + k - 1) * pitch, (size_t)1024);
+                        if (lds > (size_t)150 * 1024) break;
+                        const int nty = ceil_div(fh, ty), ntx = ceil_div(fw, tx);
+                        const double wgs = (double)B * d * d * nty * ntx * ct.split;
+                        const int together = (int)std::max<size_t>(1, std::min<size_t>(8 / NW, (size_t)(160 * 1024) / lds));
+                        const double per_cu = std::ceil(wgs / kNumCU);
+                        const double t_rest = 4000.0 + (double)lds / 8 + 32.0 * ct.OT * PT * 16;   // + the stores
+                        // co-resident workgroups hide each other's staging and stores; alone, a
+                        // workgroup pays for them in full
+                        const double cost = together >= 2 ? per_cu * t_mul1 + std::ceil(per_cu / together) * t_rest
+                                                          : per_cu * (t_mul1 + t_rest);
+                        if (!best.ok || cost < best_cost) {
+                            best.PT = PT; best.NW = NW; best.MP = MP; best.Ty = ty; best.Tx = tx;
+                            best.nty = nty; best.ntx = ntx; best.lds = lds; best.ok = true;
+                            best_cost = cost;
+                        }
+                    }
+            }
+        return best;
+    }
     const int regs_per_tile = ct.W * ct.W / 64;
     for (int PT : {64 / ct.W, 128 / ct.W}) {            // 64 or 128 positions per workgroup
         if (ct.OT * PT * regs_per_tile > (ct.W == 16 ? 64 : 128)) continue;  // accumulator registers per lane
@@ -1326,6 +1360,54 @@ mpcnn_status mpcnn_layer_shape(const mpcnn_net* net, int H, int W, int layer, in
     if (cols) *cols = g.cols[layer];
     if (channels) *channels = ly.cout;
     if (spacing) *spacing = ly.kind == MPCNN_MP ? ly.dil * ly.k : ly.dil;
+    return MPCNN_OK;
+}
+
+mpcnn_status mpcnn_plan_describe(const mpcnn_net* net, int B, int H, int W, int training, char* text_host,
+                                 size_t cap)
+{
+    if (!net || !text_host || cap < 1) return fail(MPCNN_EINVAL, "null argument");
+    text_host[0] = 0;
+    if (B < 1 || H < net->patch || W < net->patch) return fail(MPCNN_ESHAPE, "image %dx%d smaller than the %d patch", H, W, net->patch);
+    const auto gp = geom_for(net, B, H, W, training != 0, false);
+    if (!gp) return fail(MPCNN_ESHAPE, "layer plan does not fit a %dx%d image", H, W);
+    const Geom& g = *gp;
+    size_t used = 0;
+    auto put = [&](const char* fmt, ...) {
+        if (used + 1 >= cap) return;
+        va_list ap;
+        va_start(ap, fmt);
+        const int n = vsnprintf(text_host + used, cap - used, fmt, ap);
+        va_end(ap);
+        if (n > 0) used = std::min(cap - 1, used + (size_t)n);
+    };
+    auto conv = [&](const char* what, const Layer& ly, const TilePlan& tp, const ChanTiling& ct, bool bm) {
+        if (!tp.ok) { put("  %s: plain kernel\n", what); return; }
+        put("  %s: %s %d-wide x %d channel tiles x %d groups, %d position tiles (%d per wave), %d waves, tile %d x %d of a "
+            "residue class, %d x %d tiles, %zu B LDS\n", what,
+            bm ? "bf16 MFMA, tile per wave," : (tp.MP > 0 ? "fp32 MFMA, tile per wave," : "fp32 MFMA, split reduction,"),
+            ct.W, ct.OT, ct.split, tp.PT, tp.MP, tp.MP > 0 ? ct.OT * tp.PT / tp.MP : tp.NW, tp.Ty, tp.Tx, tp.nty, tp.ntx, tp.lds);
+    };
+    put("workspace %zu bytes\n", g.total);
+    for (size_t l = 0; l < net->layers.size(); ++l) {
+        const Layer& ly = net->layers[l];
+        put("layer %zu: %s %d -> %d channels, k %d x %d, spacing %d x %d, map %d x %d\n", l,
+            ly.kind == MPCNN_MP ? "MP" : (ly.kind == MPCNN_C ? "C" : "FC"), ly.cin, ly.cout, ly.k, ly.k2, ly.dil, ly.dil2,
+            g.rows[l], g.cols[l]);
+        if (ly.kind == MPCNN_MP) continue;
+        if (ly.class_fused) { put("  fused class layer, %d workgroups\n", g.partial_n[l]); continue; }
+        conv("forward", ly, g.fwd[l], ly.fwd_ct, ly.fwd_bm);
+        if (!training) continue;
+        if (l > 0) conv("data gradient", ly, g.dgrad[l], ly.dgrad_ct, ly.dgrad_bm);
+        const WgradPlan& w = g.wgrad[l];
+        if (l == 0 && g.l0_fused) put("  weight gradient: fused with the routing of the pool above, %d workgroups\n", g.l0_blocks);
+        else if (!w.ok) put("  weight gradient: plain kernel, %d chunks\n", w.chunks);
+        else
+            put("  weight gradient: %s MFMA, %d x %d result tiles, waves %d x %d x %d (rows x columns x tile rows), %d row "
+                "tiles per wave, %d x %d workgroup groups, tile 4 x %d (%d), %d tiles in %d slabs of %d, %zu B LDS\n",
+                w.bm ? "bf16" : "fp32", w.Mt, w.Nt, w.wm, w.wn, w.wk, w.mw, w.gm, w.gn, w.Tx, w.TxP, w.tiles_total, w.slabs,
+                w.tiles_per_slab, w.lds);
+    }
     return MPCNN_OK;
 }
 

@@ -33,6 +33,7 @@ SYMBOLS = [
     "mpcnn_set_loss", "mpcnn_class_balance_weights", "mpcnn_seg_loss", "mpcnn_armijo_step",
     "mpcnn_lbfgs_step", "mpcnn_lbfgs_reset", "mpcnn_set_activation", "mpcnn_set_conv_tiling",
     "mpcnn_workspace_bytes_banded", "mpcnn_seg_backward_banded", "mpcnn_seg_forward_static",
+    "mpcnn_plan_describe",
 ]
 
 
@@ -77,6 +78,7 @@ def lib():
         L.mpcnn_param_count.argtypes = [vp]
         L.mpcnn_param_count.restype = sz
         L.mpcnn_layer_shape.argtypes = [vp, i, i, i] + [C.POINTER(i)] * 4
+        L.mpcnn_plan_describe.argtypes = [vp, i, i, i, i, C.c_char_p, sz]
         L.mpcnn_set_params.argtypes = [vp, vp, sz]
         L.mpcnn_get_params.argtypes = [vp, vp, sz]
         L.mpcnn_get_grads.argtypes = [vp, vp, sz]
@@ -171,6 +173,12 @@ class Net:
 
     def workspace_bytes(self, B: int, H: int, W: int, training: bool) -> int:
         return lib().mpcnn_workspace_bytes(self._h, B, H, W, 1 if training else 0)
+
+    def plan_describe(self, B: int, H: int, W: int, training: bool) -> str:
+        """Text: the kernel, tiling and launch shape of every layer for a call of these sizes."""
+        buf = C.create_string_buffer(1 << 16)
+        _check(lib().mpcnn_plan_describe(self._h, B, H, W, 1 if training else 0, buf, len(buf)))
+        return buf.value.decode()
 
     # ---- parameters
     def set_params(self, params: np.ndarray):
