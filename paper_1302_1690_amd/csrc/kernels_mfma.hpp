@@ -42,6 +42,10 @@ struct ConvArgs {
     int Ty, Tx, nty, ntx;
     int mode;
     int logistic;        // squashing function of the Tanh modes: 0 tanh, 1 logistic
+    // persistent kernels (conv_tp_kernel): number of tiles to walk, and ceil(2^32 / x) of the
+    // divisors they use (n / x == umulhi(n, magic) for n * x < 2^32, x > 1)
+    int tiles_total;
+    unsigned mg_cq, mg_hw, mg_tx, mg_ntx, mg_nty, mg_d;
 };
 
 template <int W> struct MfmaAcc;
@@ -62,14 +66,10 @@ __device__ __forceinline__ typename MfmaAcc<W>::type mfma_f32(float a, float b, 
 // LDS, where all threads add them in wave order, apply the epilogue and store.  With 8
 // waves one workgroup fills a CU (two waves per SIMD that are always in the same phase).  Summation order is the same for every position, so equal inputs
 // give bit-equal outputs (exact pooling ties stay exact).
-// BM (bf16 storage, 32-wide tiles, channel counts that are multiples of 8): the halo stays
-// bf16 in LDS, the pack is bf16, and one v_mfma_f32_32x32x16_bf16 per (output tile, position
-// tile) and step replaces four fp32 MFMAs; a step then covers 16 channels.
-template <int W, int OT, int PT, int NW, typename T, bool BM = false>
+template <int W, int OT, int PT, int NW, typename T>
 __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
 {
-    static_assert(!BM || (W == 32 && sizeof(T) == 2), "bf16 MFMA: bf16 storage and 32-wide tiles");
-    constexpr int CU = BM ? 8 : 4;     // channels per 128-bit halo / pack item
+    constexpr int CU = 4;              // channels per 128-bit halo / pack item
     const T* in_t = static_cast<const T*>(a.in);
     const T* act_t = static_cast<const T*>(a.act);
     T* out_t = static_cast<T*>(a.out);
@@ -123,8 +123,7 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
                     dst[u] = pos * Cs4 + q;
                     if (fy >= 0 && fx >= 0 && iy < a.Hi && ix < a.Wi && CU * q < a.Cr) {
                         const T* src = in_t + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + CU * q;
-                        if constexpr (BM) v[u] = *reinterpret_cast<const v4f*>(src);   // 8 bf16, kept as they are
-                        else v[u] = load4(src);
+                        v[u] = load4(src);
                     }
                 }
             }
@@ -198,23 +197,12 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
         if (++chunk == nch) { chunk = 0; if (++tb == a.k) { tb = 0; ++ta; } }
     };
     auto mfmas = [&](const v4f (&wr)[OT], const v4f (&ar)[PT]) {
-        if constexpr (BM) {
-            typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
             for (int o = 0; o < OT; ++o)
 #pragma unroll
-                for (int p = 0; p < PT; ++p)
-                    acc[o][p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wr[o]),
-                                                                        __builtin_bit_cast(bf16x8, ar[p]),
-                                                                        acc[o][p], 0, 0, 0);
-        } else {
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int o = 0; o < OT; ++o)
-#pragma unroll
-                    for (int p = 0; p < PT; ++p) acc[o][p] = mfma_f32<W>(wr[o][s], ar[p][s], acc[o][p]);
-        }
+                for (int p = 0; p < PT; ++p) acc[o][p] = mfma_f32<W>(wr[o][s], ar[p][s], acc[o][p]);
     };
 #pragma unroll
     for (int o = 0; o < OT; ++o) wA[o] = wB[o] = (v4f){0.f, 0.f, 0.f, 0.f};
@@ -308,23 +296,13 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
 // the operands are fetched through a ring D steps deep to cover the weights' trip from L2.
 // Summation order is the step order for every output element, whatever the tiling: equal
 // inputs give bit-equal outputs, and a position's value does not depend on how the map is cut.
-// BM (bf16 storage, channel counts that are multiples of 8): the halo stays bf16 in LDS (raw
-// 128-bit copies, 8 channels per item), the pack is bf16, and one v_mfma_f32_32x32x16_bf16 per
-// position tile and step contracts 16 channels of a tap.  That instruction takes 32 cycles for
-// 1 KB per operand, so what a step fetches is what bounds the kernel: with MP position tiles
-// per wave a compute unit asks its vector cache for 128 / MP bytes of weights per cycle (it
-// delivers about 58) and its LDS for 128 bytes of activations (it delivers about 170 with two
-// waves per SIMD): MP = 4 where the map is large enough, two workgroups per compute unit so that
-// one multiplies while the other stages its halo or stores its results.
-template <int OT, int PT, int MP, typename T, bool BM = false>
-__global__ __launch_bounds__(64 * OT * PT / MP, BM ? 2 : 1) void conv_ts_kernel(ConvArgs a)
+template <int OT, int PT, int MP, typename T>
+__global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
 {
     static_assert(PT % MP == 0 && (OT * PT / MP == 4 || OT * PT / MP == 8), "4 or 8 waves");
-    static_assert(!BM || sizeof(T) == 2, "bf16 MFMA: bf16 storage");
     constexpr int W = 32, G = 2;
-    constexpr int CU = BM ? 8 : 4;                 // channels per 128-bit halo / pack item
     constexpr int NW = OT * PT / MP, NT = 64 * NW;
-    constexpr int D = BM ? (MP >= 4 ? 4 : 6) : (MP == 1 ? 6 : 4);   // steps in flight
+    constexpr int D = MP == 1 ? 6 : 4;             // steps in flight
     const T* in_t = static_cast<const T*>(a.in);
     const T* act_t = static_cast<const T*>(a.act);
     T* out_t = static_cast<T*>(a.out);
@@ -346,7 +324,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP, BM ? 2 : 1) void conv_ts_kernel(
     if (ty0 >= fh || tx0 >= fw) return;  // uniform for the workgroup
 
     const int hw = a.Tx + a.k - 1, hh = a.Ty + a.k - 1;
-    const int cq = a.CrPad / CU;
+    const int cq = a.CrPad / 4;
     const int Cs4 = cq + 1;              // pitch of one halo position in 128-bit units (+1: bank spread)
     const int oc0 = W * (blockIdx.y * OT + wo);   // first channel of this wave's tile
     v4f* lds4 = reinterpret_cast<v4f*>(lds);
@@ -369,11 +347,8 @@ __global__ __launch_bounds__(64 * OT * PT / MP, BM ? 2 : 1) void conv_ts_kernel(
                     const int fy = ty0 + ha + a.origin, fx = tx0 + hb + a.origin;
                     const int iy = fy * a.d + ry, ix = fx * a.d + rx;
                     dst[u] = pos * Cs4 + q;
-                    if (fy >= 0 && fx >= 0 && iy < a.Hi && ix < a.Wi && CU * q < a.Cr) {
-                        const T* src = in_t + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + CU * q;
-                        if constexpr (BM) v[u] = *reinterpret_cast<const v4f*>(src);   // 8 bf16, kept as they are
-                        else v[u] = load4(src);
-                    }
+                    if (fy >= 0 && fx >= 0 && iy < a.Hi && ix < a.Wi && 4 * q < a.Cr)
+                        v[u] = load4(in_t + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + 4 * q);
                 }
             }
 #pragma unroll
@@ -405,7 +380,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP, BM ? 2 : 1) void conv_ts_kernel(
         lbase[p] = (ty * hw + tx) * Cs4 + lg;
     }
 
-    const int nch = a.CrPad / (CU * G);
+    const int nch = a.CrPad / (4 * G);
     const int steps = a.k * a.k * nch;
     const int lane_w = lg * a.CoPad + oc0 + lt;   // this lane's offset inside one step of the pack
 
@@ -429,29 +404,29 @@ __global__ __launch_bounds__(64 * OT * PT / MP, BM ? 2 : 1) void conv_ts_kernel(
         ++tf;
         if (++chunk == nch) { chunk = 0; if (++tb == a.k) { tb = 0; ++ta; } }
     };
-    auto mfmas = [&](int i) {
-        if constexpr (BM) {
-            typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    // The first D fetches are issued on every path (a reduction shorter than D steps fetches step
+    // 0 again into the slots it does not use): with a fetch count that depended on a branch the
+    // compiler no longer knows how many loads are in flight when the loop starts, and waits for
+    // ALL of them at the top of every round of D steps - the ring then hides nothing.
+    auto fetch_first = [&](int i) {
+        const bool real = i < steps;
+        wr[i] = (a.wpack + (long)(real ? tf : 0) * G * a.CoPad)[lane_w];
+        const int soff = real ? (ta * hw + tb) * Cs4 + G * chunk : 0;
 #pragma unroll
-            for (int p = 0; p < MP; ++p)
-                acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wr[i]),
-                                                                 __builtin_bit_cast(bf16x8, ar[i][p]), acc[p], 0, 0, 0);
-        } else {
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int p = 0; p < MP; ++p) acc[p] = mfma_f32<32>(wr[i][s], ar[i][p][s], acc[p]);
+        for (int p = 0; p < MP; ++p) ar[i][p] = lds4[lbase[p] + soff];
+        if (real) {
+            ++tf;
+            if (++chunk == nch) { chunk = 0; if (++tb == a.k) { tb = 0; ++ta; } }
         }
     };
+    auto mfmas = [&](int i) {
 #pragma unroll
-    for (int i = 0; i < D; ++i) {
-        wr[i] = (v4f){0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int p = 0; p < MP; ++p) ar[i][p] = (v4f){0.f, 0.f, 0.f, 0.f};
-    }
+            for (int p = 0; p < MP; ++p) acc[p] = mfma_f32<32>(wr[i][s], ar[i][p][s], acc[p]);
+    };
 #pragma unroll
-    for (int i = 0; i < D; ++i)
-        if (i < steps) fetch(i);
+    for (int i = 0; i < D; ++i) fetch_first(i);
     int t = 0;
     for (; t + 2 * D <= steps; t += D) {          // every step of the group has a successor D ahead
 #pragma unroll

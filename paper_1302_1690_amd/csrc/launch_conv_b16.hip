@@ -1,5 +1,6 @@
 // Instances of the matrix-core convolution kernels for bf16 storage.
 #include "launchers.hpp"
+#include "kernels_conv_bf16.hpp"
 
 namespace mpcnn {
 namespace {
@@ -36,7 +37,7 @@ bool launch_conv_b16(const ConvArgs& a, int W, int OT, int PT, int NW, int MP, d
     return false;
 }
 
-// bf16 matrix instruction: conv_ts_kernel<.., bf16, true>, (OT, PT, MP) with OT*PT/MP = 4 or 8 waves
+// bf16 matrix instruction: conv_tp_kernel, (OT, PT, MP) with OT*PT/MP = 4 or 8 waves
 #define CONV_BM_INSTANCES(X) \
     X(1, 8, 2) X(1, 16, 2) X(1, 16, 4) X(2, 4, 2) X(2, 8, 2) X(2, 8, 4) X(2, 16, 4) X(4, 2, 2) X(4, 4, 2) X(4, 4, 4) X(4, 8, 4)
 bool launch_conv_bm(const ConvArgs& a, int OT, int PT, int NW, int MP, dim3 grid, size_t lds, hipStream_t st)
@@ -44,7 +45,7 @@ bool launch_conv_bm(const ConvArgs& a, int OT, int PT, int NW, int MP, dim3 grid
     (void)NW;
 #define CASE(o, p, m)                                                                         \
     if (OT == o && PT == p && MP == m) {                                                      \
-        conv_ts_kernel<o, p, m, bf16, true><<<grid, 64 * o * p / m, lds, st>>>(a);            \
+        conv_tp_kernel<o, p, m><<<grid, 64 * o * p / m, lds, st>>>(a);                      \
         return true;                                                                          \
     }
     CONV_BM_INSTANCES(CASE)
@@ -65,7 +66,7 @@ hipError_t conv_attrs_b16()
 #define MF_ATTR(w, o, p) ATTR(conv_mfma_kernel<w, o, p, 4, T>); ATTR(conv_mfma_kernel<w, o, p, 8, T>);
     CONV_MFMA_INSTANCES(MF_ATTR)
 #undef MF_ATTR
-#define BM_ATTR(o, p, m) ATTR(conv_ts_kernel<o, p, m, bf16, true>);
+#define BM_ATTR(o, p, m) ATTR(conv_tp_kernel<o, p, m>);
     CONV_BM_INSTANCES(BM_ATTR)
 #undef BM_ATTR
 #undef ATTR

@@ -22,6 +22,7 @@
 #include "../../include/mpcnn.h"
 #include "kernels_direct.hpp"
 #include "launchers.hpp"
+#include "kernels_conv_bf16.hpp"    // tp_items
 #include "kernels_wgrad_bf16.hpp"   // its LDS geometry, which the planner shares (no instance is built here)
 #include "kernels_pack.hpp"
 #include "kernels_reduce.hpp"
@@ -334,6 +335,8 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, co
         // with 2 position tiles asks the vector cache for twice the weights per instruction: the
         // cache, not the matrix pipe, then sets the pace), two workgroups per compute unit.
         const int steps = k * k * (rpad / 16);
+        // (the kernel forms element offsets inside one image in 32 bits)
+        if ((size_t)(out_r + (k - 1) * d) * (out_c + (k - 1) * d) * rpad >= (1ull << 31)) return best;
         for (int PT : {2, 4, 8, 16})
             for (int MP : {2, 4}) {
                 const int NW = ct.OT * PT / MP;
@@ -343,6 +346,8 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, co
                     for (int tx = 1; tx <= std::min(fw, 32 * PT / ty); ++tx) {
                         const size_t lds = std::max((size_t)(ty + k - 1) * (tx + k - 1) * pitch, (size_t)1024);
                         if (lds > (size_t)150 * 1024) break;
+                        // a thread holds its share of the next tile's halo in registers
+                        if ((long)(ty + k - 1) * (tx + k - 1) * (rpad / 8) > (long)mpcnn::tp_items(MP) * 64 * NW) break;
                         const int nty = ceil_div(fh, ty), ntx = ceil_div(fw, tx);
                         const double wgs = (double)B * d * d * nty * ntx * ct.split;
                         const int together = (int)std::max<size_t>(1, std::min<size_t>(8 / NW, (size_t)(160 * 1024) / lds));
@@ -686,6 +691,16 @@ inline int grid_for(long total, int block = 256, int cap = 1 << 20)
 }
 
 // ------------------------------------------------------------------ MFMA launches
+// conv_tp_kernel: workgroups walk the tiles, two of them per compute unit; its divisors' magic numbers
+void persistent_grid(mpcnn::ConvArgs* a, dim3* grid, int split)
+{
+    a->tiles_total = (int)grid->x;
+    a->mg_cq = magic_of((unsigned)(a->CrPad / 8)); a->mg_hw = magic_of((unsigned)(a->Tx + a->k - 1));
+    a->mg_tx = magic_of((unsigned)a->Tx); a->mg_ntx = magic_of((unsigned)a->ntx);
+    a->mg_nty = magic_of((unsigned)a->nty); a->mg_d = magic_of((unsigned)a->d);
+    grid->x = (unsigned)std::min<long>(grid->x, std::max(1, 2 * kNumCU / split));
+}
+
 // (the kernel instances live in launch_*.hip, one translation unit per family)
 template <typename T>
 bool launch_conv_mfma(const mpcnn::ConvArgs& a, const ChanTiling& ct, const TilePlan& tp, dim3 grid,
@@ -888,6 +903,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 a.Ty = tp.Ty; a.Tx = tp.Tx; a.nty = tp.nty; a.ntx = tp.ntx;
                 a.mode = ly.tanh_out ? kFwdTanh : kFwdLinear; a.logistic = net->logistic;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
+                if (ly.fwd_bm) persistent_grid(&a, &grid, ly.fwd_ct.split);
                 bool launched = false;
                 LAUNCH(ly.fwd_bm ? "conv_fwd_bm" : "conv_fwd_mfma", l, step, flops, bytes,
                        launched = launch_conv_mfma<T>(a, ly.fwd_ct, tp, grid, st, ly.fwd_bm));
@@ -1069,6 +1085,7 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.Ty = tp.Ty; a.Tx = tp.Tx; a.nty = tp.nty; a.ntx = tp.ntx;
                 a.mode = below_tanh ? kDgradTanh : kDgradPlain; a.logistic = net->logistic;
                 dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.dgrad_ct.split);
+                if (ly.dgrad_bm) persistent_grid(&a, &grid, ly.dgrad_ct.split);
                 bool launched = false;
                 LAUNCH(ly.dgrad_bm ? "conv_dgrad_bm" : "conv_dgrad_mfma", li, dstep, flops, dbytes,
                        launched = launch_conv_mfma<T>(a, ly.dgrad_ct, tp, grid, st, ly.dgrad_bm));
