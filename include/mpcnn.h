@@ -70,7 +70,7 @@ typedef enum { MPCNN_F32 = 0, MPCNN_BF16 = 1 } mpcnn_dtype;
  * sub-regions"); windows start at the top left of the map, rows / columns left over when a side
  * is not a multiple of the window's are dropped.  After a rectangular pool the maps of a patch
  * are no longer square and rows and columns of the whole-image maps are spaced differently; such
- * layers run on the plain (not the matrix-core) kernels, with fp32 storage only.  FC: `maps` units
+ * layers run on the plain (not the matrix-core) kernels.  FC: `maps` units
  * (k ignored); the last layer must be FC and its `maps` is the class count. */
 typedef struct {
     int kind; /* mpcnn_kind */
@@ -84,10 +84,10 @@ typedef struct {
  * image with `in_channels` channels.  Host-only: allocates no device memory
  * (parameters are allocated on the current device by mpcnn_set_params).
  * Errors: EINVAL (null / counts / kinds), ESHAPE (a layer does not fit; no FC
- * at the end; C or MP after an FC), EUNSUPPORTED (a pool with k*k > 255; more than 16 classes;
- * MPCNN_BF16 with a layer the matrix-core and fused kernels do not take: channel
- * counts must be multiples of 4 and, between layers, at least 8; the last FC must
- * have 2-4 classes on at most 256 inputs that are a multiple of 4).
+ * at the end; C or MP after an FC), EUNSUPPORTED (a pool with k*k > 255; more than 16 classes).
+ * Every legal net is accepted with either storage type; layers whose shape the matrix-core and
+ * fused kernels do not take (channel counts that are not multiples of 4, fewer than 8 channels,
+ * rectangular pools, class layers with more than 4 classes or 256 inputs) run on plain kernels.
  */
 mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers_host, int n_layers, int in_channels,
                               int patch, mpcnn_dtype dtype, mpcnn_net** out);

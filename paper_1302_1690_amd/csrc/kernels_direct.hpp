@@ -48,9 +48,9 @@ __global__ void stage_input_kernel(const float* __restrict__ src, T* __restrict_
 // a6: dA[b,y,x,c] = sum_{u<k,v<k2,o} W[u,v,c,o] * dY[b, y-u*d, x-v*d2, o]  (terms outside dY dropped;
 // k2, d2: columns of the kernel and their spacing, which differ from the rows' after a rectangular pool),
 // times (1 - A^2) when A is the tanh output of the layer below.
-template <bool TANHP>
-__global__ void conv_dgrad_direct_kernel(const float* __restrict__ dY, const float* __restrict__ Wk,
-                                         const float* __restrict__ A, float* __restrict__ dA, int B,
+template <bool TANHP, typename T = float>
+__global__ void conv_dgrad_direct_kernel(const T* __restrict__ dY, const float* __restrict__ Wk,
+                                         const T* __restrict__ A, T* __restrict__ dA, int B,
                                          int Hi, int Wi, int Ci, int Ho, int Wo, int Co, int k, int k2, int d, int d2,
                                          int logistic)
 {
@@ -70,16 +70,16 @@ __global__ void conv_dgrad_direct_kernel(const float* __restrict__ dY, const flo
             for (int v = 0; v < k2; ++v) {
                 int xx = x - v * d2;
                 if (xx < 0 || xx >= Wo) continue;
-                const float* g = dY + (((long)b * Ho + yy) * Wo + xx) * Co;
+                const T* g = dY + (((long)b * Ho + yy) * Wo + xx) * Co;
                 const float* w = Wk + ((long)(u * k2 + v) * Ci + c) * Co;
-                for (int o = 0; o < Co; ++o) acc = fmaf(g[o], w[o], acc);
+                for (int o = 0; o < Co; ++o) acc = fmaf(load1(g + o), w[o], acc);
             }
         }
         if (TANHP) {
-            float a = A[e];
+            float a = load1(A + e);
             acc *= squash_slope(a, logistic);
         }
-        dA[e] = acc;
+        store1(dA + e, acc);
     }
 }
 
@@ -87,7 +87,8 @@ __global__ void conv_dgrad_direct_kernel(const float* __restrict__ dY, const flo
 //     dY[b,y,x,o] * A[b, y+u*d, x+v*d, c];  row kk = k*k*Ci is the bias row (A = 1).
 // One chunk = `rows_per_chunk` output rows (b,y); a later pass adds the chunks
 // in index order (Alg. 2: the gradient is the sum over all fragments).
-__global__ void conv_wgrad_direct_kernel(const float* __restrict__ A, const float* __restrict__ dY,
+template <typename T = float>
+__global__ void conv_wgrad_direct_kernel(const T* __restrict__ A, const T* __restrict__ dY,
                                          float* __restrict__ partial, int B, int Hi, int Wi, int Ci,
                                          int Ho, int Wo, int Co, int k, int k2, int d, int d2,
                                          int rows_per_chunk)
@@ -106,12 +107,12 @@ __global__ void conv_wgrad_direct_kernel(const float* __restrict__ A, const floa
     float acc = 0.f;
     for (long r = row0; r < row1; ++r) {
         int b = (int)(r / Ho), y = (int)(r % Ho);
-        const float* g = dY + (r * Wo) * Co + o;
+        const T* g = dY + (r * Wo) * Co + o;
         if (is_bias) {
-            for (int x = 0; x < Wo; ++x) acc += g[(long)x * Co];
+            for (int x = 0; x < Wo; ++x) acc += load1(g + (long)x * Co);
         } else {
-            const float* a = A + (((long)b * Hi + (y + u * d)) * Wi + v * d2) * Ci + c;
-            for (int x = 0; x < Wo; ++x) acc = fmaf(g[(long)x * Co], a[(long)x * Ci], acc);
+            const T* a = A + (((long)b * Hi + (y + u * d)) * Wi + v * d2) * Ci + c;
+            for (int x = 0; x < Wo; ++x) acc = fmaf(load1(g + (long)x * Co), load1(a + (long)x * Ci), acc);
         }
     }
     partial[(long)blockIdx.y * KN + e] = acc;
@@ -119,7 +120,8 @@ __global__ void conv_wgrad_direct_kernel(const float* __restrict__ A, const floa
 
 // a2: stride-1 max filter with taps d apart, plus the argmax tap code of the FIRST
 // maximum in row-major (u,v) order (Alg. 3: MP_fwd on every offset, mpIDXS).
-__global__ void maxfilter_fwd_direct_kernel(const float* __restrict__ A, float* __restrict__ O,
+template <typename T = float>
+__global__ void maxfilter_fwd_direct_kernel(const T* __restrict__ A, T* __restrict__ O,
                                             uint8_t* __restrict__ code, int B, int Hi, int Wi, int C,
                                             int Ho, int Wo, int p, int p2, int d, int d2)
 {
@@ -136,23 +138,23 @@ __global__ void maxfilter_fwd_direct_kernel(const float* __restrict__ A, float* 
         int bi = -1;
         for (int u = 0; u < p; ++u)
             for (int v = 0; v < p2; ++v) {
-                float a = A[(((long)b * Hi + (y + u * d)) * Wi + (x + v * d2)) * C + c];
+                float a = load1(A + (((long)b * Hi + (y + u * d)) * Wi + (x + v * d2)) * C + c);
                 if (bi < 0 || a > best) {
                     best = a;
                     bi = u * p2 + v;
                 }
             }
-        O[e] = best;
+        store1(O + e, best);   // a value read back unchanged: exact in either storage type
         if (code) code[e] = (uint8_t)bi;
     }
 }
 
 // a7: routing by argmax as a gather (Alg. 4): an input element collects dO of every
 // window that chose it, in fixed (u,v) order; times (1 - A^2) when A is a tanh output.
-template <bool TANHP>
-__global__ void maxfilter_bwd_direct_kernel(const float* __restrict__ dO,
+template <bool TANHP, typename T = float>
+__global__ void maxfilter_bwd_direct_kernel(const T* __restrict__ dO,
                                             const uint8_t* __restrict__ code,
-                                            const float* __restrict__ A, float* __restrict__ dA,
+                                            const T* __restrict__ A, T* __restrict__ dA,
                                             int B, int Hi, int Wi, int C, int Ho, int Wo, int p, int p2, int d, int d2,
                                             int logistic)
 {
@@ -173,14 +175,14 @@ __global__ void maxfilter_bwd_direct_kernel(const float* __restrict__ dO,
                 int xx = x - v * d2;
                 if (xx < 0 || xx >= Wo) continue;
                 long s = (((long)b * Ho + yy) * Wo + xx) * C + c;
-                if (code[s] == (uint8_t)(u * p2 + v)) acc += dO[s];
+                if (code[s] == (uint8_t)(u * p2 + v)) acc += load1(dO + s);
             }
         }
         if (TANHP) {
-            float a = A[e];
+            float a = load1(A + e);
             acc *= squash_slope(a, logistic);
         }
-        dA[e] = acc;
+        store1(dA + e, acc);
     }
 }
 
@@ -191,9 +193,10 @@ constexpr int kMaxClasses = 16;
 // the summed cross-entropy (Results: MCCE per pixel; Method: first step of back-prop).
 // mse != 0: linear outputs and half the squared error instead (Method: the derivative of
 // the mean squared error w.r.t. the output image is x^ - t); `probs` then gets the outputs.
-__global__ void softmax_ce_kernel(const float* __restrict__ Z, float* __restrict__ probs,
+template <typename T = float>
+__global__ void softmax_ce_kernel(const T* __restrict__ Z, float* __restrict__ probs,
                                   const int32_t* __restrict__ labels, const float* __restrict__ pixw,
-                                  float* __restrict__ dZ, double* __restrict__ loss_partial, int B,
+                                  T* __restrict__ dZ, double* __restrict__ loss_partial, int B,
                                   int Ho, int Wo, int H, int W, int ctr, int n_cls, int mse, int probs_rows)
 {
     __shared__ double red[256];
@@ -208,7 +211,7 @@ __global__ void softmax_ce_kernel(const float* __restrict__ Z, float* __restrict
         float z[kMaxClasses];
         float zmax = -INFINITY;
         for (int o = 0; o < n_cls; ++o) {
-            z[o] = Z[m * n_cls + o];
+            z[o] = load1(Z + m * n_cls + o);
             zmax = fmaxf(zmax, z[o]);
         }
         float sum = 0.f;
@@ -231,7 +234,7 @@ __global__ void softmax_ce_kernel(const float* __restrict__ Z, float* __restrict
             float p = mse ? z[o] + zmax : expf(z[o]) * inv;
             if (probs) probs[(((long)b * n_cls + o) * probs_rows + i) * Wo + j] = p;
             const float e = p - (o == t ? 1.f : 0.f);
-            if (dZ) dZ[m * n_cls + o] = (t >= 0) ? w * e : 0.f;
+            if (dZ) store1(dZ + m * n_cls + o, (t >= 0) ? w * e : 0.f);
             if (o == t) zt = z[o];
             sq += e * e;
         }

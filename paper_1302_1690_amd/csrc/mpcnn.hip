@@ -861,12 +861,10 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
                        (maxfilter_fwd4_kernel<T, 1><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
                            in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil)));
-            else if constexpr (kF32)
-                LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (code ? 9.0 : 8.0),
-                       maxfilter_fwd_direct_kernel<<<grid_for(total), 256, 0, st>>>(
-                           in, out, code, B, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2));
             else
-                return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", l);
+                LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
+                       maxfilter_fwd_direct_kernel<T><<<grid_for(total), 256, 0, st>>>(
+                           in, out, code, B, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2));
         } else if (ly.class_fused) {
             // last FC + softmax + cross-entropy (+ its own backward when labels are given)
             const long M = (long)B * Ho * Wo;
@@ -932,15 +930,12 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
         }
         in = out; Hi = Ho; Wi = Wo; Ci = ly.cout;
     }
-    if constexpr (!kF32) {
-        if (!net->layers[L - 1].class_fused)
-            return fail(MPCNN_EUNSUPPORTED, "the unfused class layer has an fp32-storage kernel only");
-    } else if (!net->layers[L - 1].class_fused) {
+    if (!net->layers[L - 1].class_fused) {
         // class logits -> probabilities, deltas, loss
         long total = (long)B * Hi * Wi;
         int blocks = (int)std::min<long>(kSoftmaxBlocks, (total + 255) / 256);
-        LAUNCH("softmax_ce", L - 1, 3, 0, 4.0 * total * (3.0 * net->n_cls + 2.0),
-               softmax_ce_kernel<<<blocks, 256, 0, st>>>(in, probs, labels, pixw, dZ,
+        LAUNCH("softmax_ce", L - 1, 3, 0, total * ((4.0 + 2.0 * es) * net->n_cls + 8.0),
+               softmax_ce_kernel<T><<<blocks, 256, 0, st>>>(in, probs, labels, pixw, dZ,
                                                          want_loss ? lp : nullptr, B, Hi, Wi, g.label_h, g.W,
                                                          (net->patch - 1) / 2, net->n_cls,
                                                          net->loss_kind == MPCNN_LOSS_MSE, g.probs_rows));
@@ -1021,16 +1016,14 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        (maxfilter_bwd4_kernel<false, T, 1><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
                            dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil, net->logistic)));
-            else if constexpr (!kF32)
-                return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             else if (below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
-                       maxfilter_bwd_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
-                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic));
+                       (maxfilter_bwd_direct_kernel<true, T><<<grid_for(total), 256, 0, st>>>(
+                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic)));
             else
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
-                       maxfilter_bwd_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
-                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic));
+                       (maxfilter_bwd_direct_kernel<false, T><<<grid_for(total), 256, 0, st>>>(
+                           dY, code, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic)));
         } else {
             const double flops = 2.0 * B * Ho * Wo * ly.cout * ly.k * ly.k2 * Ci;
             const int wstep = (li == L - 1) ? 4 : 5, dstep = (li == L - 1) ? 4 : 6;
@@ -1062,12 +1055,10 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                            launched = launch_wgrad_mfma<T>(a, wp.hl, grid, wp.lds, st));
                 if (!launched)
                     return fail(MPCNN_EUNSUPPORTED, "layer %zu: no weight-gradient kernel instance for its plan", li);
-            } else if constexpr (!kF32) {
-                return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             } else {
                 dim3 grid((unsigned)((ly.p_len + 255) / 256), (unsigned)wp.chunks);
-                LAUNCH("wgrad_direct", li, wstep, flops, 4.0 * (n_in + n_out + ly.p_len),
-                       conv_wgrad_direct_kernel<<<grid, 256, 0, st>>>(A, dY, partial, B, Hi, Wi, Ci, Ho,
+                LAUNCH("wgrad_direct", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
+                       conv_wgrad_direct_kernel<T><<<grid, 256, 0, st>>>(A, dY, partial, B, Hi, Wi, Ci, Ho,
                                                                       Wo, ly.cout, ly.k, ly.k2, ly.dil, ly.dil2,
                                                                       wp.rows_per_chunk));
             }
@@ -1091,18 +1082,16 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                        launched = launch_conv_mfma<T>(a, ly.dgrad_ct, tp, grid, st, ly.dgrad_bm));
                 if (!launched)
                     return fail(MPCNN_EUNSUPPORTED, "layer %zu: no convolution kernel instance for its data-gradient plan", li);
-            } else if constexpr (!kF32) {
-                return fail(MPCNN_EUNSUPPORTED, "layer %zu: this shape has an fp32-storage kernel only", li);
             } else {
                 long total = (long)B * Hi * Wi * Ci;
                 if (below_tanh)
                     LAUNCH("conv_dgrad_direct", li, dstep, flops, dbytes,
-                           conv_dgrad_direct_kernel<true><<<grid_for(total), 256, 0, st>>>(
-                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic));
+                           (conv_dgrad_direct_kernel<true, T><<<grid_for(total), 256, 0, st>>>(
+                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic)));
                 else
                     LAUNCH("conv_dgrad_direct", li, dstep, flops, dbytes,
-                           conv_dgrad_direct_kernel<false><<<grid_for(total), 256, 0, st>>>(
-                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic));
+                           (conv_dgrad_direct_kernel<false, T><<<grid_for(total), 256, 0, st>>>(
+                               dY, Wk, A, dA, B, Hi, Wi, Ci, Ho, Wo, ly.cout, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic)));
             }
         }
         cur ^= 1;
@@ -1285,10 +1274,6 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
         if (st != MPCNN_OK) break;
         // rows and columns differ (a rectangular pool or anything behind one): the direct kernels
         ly.rect = ly.k2 != ly.k || (ly.dil2 != ly.dil && (ly.k > 1 || ly.k2 > 1));
-        if (ly.rect && net->bf16) {
-            st = fail(MPCNN_EUNSUPPORTED, "layer %d: rectangular pooling has fp32-storage kernels only", l);
-            break;
-        }
         if (ly.kind != MPCNN_MP) {
             ly.p_off = off;
             ly.p_len = ((size_t)ly.k * ly.k2 * ly.cin + 1) * ly.cout;
@@ -1315,17 +1300,6 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
                 ly.dgrad_rpad = ceil_div(ly.cout, 16) * 16;
                 ly.dgrad_pack_len = (size_t)ly.k * ly.k * ly.dgrad_rpad * ly.dgrad_ct.pad;
                 ly.dgrad_pack_off = pack; pack += ly.dgrad_pack_len;
-            }
-        }
-        // bf16 storage is built for the main kernels only: every layer must take them
-        if (net->bf16) {
-            const bool last = l == n_layers - 1;
-            if (ly.kind == MPCNN_MP ? ly.cout % 4 != 0
-                                    : (last ? !ly.class_fused
-                                            : ((l > 0 && !ly.fwd_mfma) || (l > 0 && !ly.dgrad_mfma) || ly.cout % 4 != 0))) {
-                st = fail(MPCNN_EUNSUPPORTED, "layer %d: bf16 storage needs channel counts that are multiples of 4, "
-                          "at least 8 between layers, and a last FC of 2-4 classes on at most 256 inputs", l);
-                break;
             }
         }
         ch = ly.cout;

@@ -483,9 +483,6 @@ def test_rectangular_pooling_windows():
     cfg = replace(wl.CONFIGS[4], name="rect_two_levels", layers=layers, patch=20, batch=1, height=44,
                   width=39, dtype="f32", weight_amp=0.3)
     full_parity(cfg, ignore_some=True)
-    with pytest.raises(mpcnn.MpcnnError) as e:      # bf16 storage has the matrix-core kernels only
-        mpcnn.Net(((C, 8, 3), (MP, 0, 2, 3), (C, 8, 2), (FC, 12, 0), (FC, 2, 0)), 3, 17, dtype=mpcnn.BF16)
-    assert e.value.status == 4
 
 
 def test_class_layer_variants():
@@ -718,9 +715,28 @@ def test_cfg4_full_size_sampled_bf16():
     net.close()
 
 
-def test_bf16_refuses_shapes_without_a_kernel():
-    with pytest.raises(mpcnn.MpcnnError):
-        mpcnn.Net(wl.CONFIGS[0].layers, 1, 18, dtype=mpcnn.BF16)
+def test_bf16_shapes_off_the_matrix_cores():
+    """bf16 storage with layers the matrix-core and fused kernels do not take: the tiny net (2 and 3
+    maps, an 8-unit class layer input), a class layer of 6 classes, a rectangular pool - all on the
+    plain kernels, which round what they store like the others."""
+    from dataclasses import replace
+    full_parity(replace(wl.crop(wl.CONFIGS[0], 2, 37, 45), name="tiny_bf16", dtype="bf16"), with_pixw=True)
+    layers = ((C, 6, 3), (MP, 0, 2), (C, 10, 2), (FC, 9, 0), (FC, 6, 0))          # 10 -> 8 -> 4 -> 3 -> FC over 3x3
+    cfg = wl.Workload("bf16_odd_everything", layers, 10, 3, 6, 2, 31, 26, 0.3, "ellipses", dtype="bf16",
+                      seed_image=1122, seed_label=2122, seed_param=3122)
+    img, lab = wl.make_inputs(cfg)
+    lab = np.random.default_rng(7).integers(0, 6, lab.shape).astype(np.int32)
+    params = wl.make_params(cfg)
+    net, probs, loss, grads = run_gpu(cfg, img, lab, params)
+    ref, n_near, n_alt = oracle_run_valid_ties(cfg, params, img, lab, None, None, net)
+    assert np.abs(probs - ref["probs"]).max() <= TOL_BF16
+    assert abs(loss - ref["loss"]) <= 0.1 * TOL_BF16 * abs(ref["loss"])
+    check_grads(cfg, grads, ref["grads"])
+    net.close()
+    layers = ((C, 8, 3), (MP, 0, 2, 3), (C, 8, 2), (FC, 12, 0), (FC, 2, 0))      # 17 -> 15 -> (2x3) 7x5 -> 6x4 -> FC
+    cfg = wl.Workload("bf16_rect_2x3", layers, 17, 1, 2, 2, 37, 41, 0.3, "ellipses", dtype="bf16",
+                      seed_image=1123, seed_label=2123, seed_param=3123)
+    full_parity(cfg, with_pixw=True)
 
 
 def test_mse_loss_with_linear_outputs():
