@@ -1,6 +1,7 @@
 // Instances of the matrix-core weight-gradient kernels for bf16 storage.
 #include "launchers.hpp"
 #include "kernels_wgrad_bf16.hpp"
+#include "kernels_wgrad_tr.hpp"
 
 namespace mpcnn {
 namespace {
@@ -34,6 +35,19 @@ bool launch_wgrad_bm(const WgradArgs& a, int nch, dim3 grid, size_t lds, hipStre
     return false;
 }
 
+bool launch_wgrad_tr(const WgradArgs& a, int nch, dim3 grid, size_t lds, hipStream_t st)
+{
+#define CASE(m, c) case 4 * m + c - 5: wgrad_tr_kernel<m, c><<<grid, 512, lds, st>>>(a); return true;
+#define ROW(m) CASE(m, 1) CASE(m, 2) CASE(m, 3) CASE(m, 4)
+    if (nch < 1 || nch > 4 || a.mw < 1 || a.mw > kWgTrMaxTiles) return false;
+    switch (4 * a.mw + nch - 5) {
+    ROW(1) ROW(2) ROW(3) ROW(4) ROW(5)
+    }
+#undef ROW
+#undef CASE
+    return false;
+}
+
 hipError_t wgrad_attrs_b16()
 {
     hipError_t e = hipSuccess;
@@ -44,7 +58,8 @@ hipError_t wgrad_attrs_b16()
 #define WG(m) ATTR(wgrad_mfma_kernel<m, kWgStageH, T>); ATTR(wgrad_mfma_kernel<m, 2 * kWgStageH, T>);
     WGRAD_MW(WG)
 #undef WG
-#define ROW(m) ATTR(wgrad_bm_kernel<m, 1>); ATTR(wgrad_bm_kernel<m, 2>); ATTR(wgrad_bm_kernel<m, 3>); ATTR(wgrad_bm_kernel<m, 4>);
+#define ROW(m) ATTR(wgrad_bm_kernel<m, 1>); ATTR(wgrad_bm_kernel<m, 2>); ATTR(wgrad_bm_kernel<m, 3>); ATTR(wgrad_bm_kernel<m, 4>); \
+               ATTR(wgrad_tr_kernel<m, 1>); ATTR(wgrad_tr_kernel<m, 2>); ATTR(wgrad_tr_kernel<m, 3>); ATTR(wgrad_tr_kernel<m, 4>);
     ROW(1) ROW(2) ROW(3) ROW(4) ROW(5)
 #undef ROW
 #undef ATTR

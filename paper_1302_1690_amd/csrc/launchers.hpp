@@ -21,6 +21,7 @@ bool launch_conv_bm(const ConvArgs& a, int OT, int PT, int NW, int MP, dim3 grid
 bool launch_wgrad_f32(const WgradArgs& a, int hl, dim3 grid, size_t lds, hipStream_t st);
 bool launch_wgrad_b16(const WgradArgs& a, int hl, dim3 grid, size_t lds, hipStream_t st);
 bool launch_wgrad_bm(const WgradArgs& a, int nch, dim3 grid, size_t lds, hipStream_t st);
+bool launch_wgrad_tr(const WgradArgs& a, int nch, dim3 grid, size_t lds, hipStream_t st);   // kernels_wgrad_tr.hpp
 
 // Kernels that may ask for more than 64 KiB of dynamic LDS must say so once per device.
 hipError_t conv_attrs_f32();

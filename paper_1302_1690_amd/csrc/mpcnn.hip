@@ -23,6 +23,7 @@
 #include "kernels_direct.hpp"
 #include "launchers.hpp"
 #include "kernels_conv_bf16.hpp"    // tp_items
+#include "kernels_wgrad_tr.hpp"     // its LDS geometry
 #include "kernels_wgrad_bf16.hpp"   // its LDS geometry, which the planner shares (no instance is built here)
 #include "kernels_pack.hpp"
 #include "kernels_reduce.hpp"
@@ -123,6 +124,7 @@ struct TilePlan {
 struct WgradPlan {
     bool ok = false;
     bool bm = false;      // bf16 storage: the bf16 matrix instruction, 16 positions per MFMA
+    bool tr = false;      // ... with operands from the transposing LDS read (wgrad_tr_kernel)
     int Tx = 0, TxP = 0, nty = 0, ntx = 0, tiles_total = 0, tiles_per_slab = 0, slabs = 0;
     int Mt = 0, Nt = 0, wm = 0, wn = 0, wk = 0, mw = 0, gm = 0, gn = 0;
     size_t lds = 0;
@@ -408,6 +410,55 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
                         (size_t)out_r * out_c * ly.cout < (1ull << 31) && (k + 3) * d < 65536;
     // the bf16 instruction's kernel gives a wave pairs of column tiles: not for 32 maps or fewer
     bm = bm && ly.cout > 32;
+    if (bm && ly.wgrad_mfma && fits32 && ly.cin % 32 == 0) {
+        // wgrad_tr_kernel: the tiles are raw copies in planes of 32 channels.  Same choices as for
+        // wgrad_bm_kernel below: wave split and tile width together, by the busiest workgroup's
+        // time - its matrix instructions, or taking the tiles in, whichever is longer.
+        const int Mt = k * k * ly.cin / 32 + 1, Nt = ceil_div(ly.cout, 32), Nu = ceil_div(Nt, 2);
+        double best = -1;
+        for (int wn : {4, 2, 1})
+            for (int wm : {1, 2, 4}) {
+                if (wm * wn > 4) continue;
+                const int wk = 4 / (wm * wn);
+                const int gm = ceil_div(Mt, mpcnn::kWgTrMaxTiles * wm), mw = ceil_div(Mt, gm * wm);
+                const int gn = ceil_div(Nu, wn);
+                const int target = std::max(1, kNumCU / (gm * gn));
+                for (int tx = 1; tx <= fw && tx <= 64; ++tx) {
+                    const int nch = ceil_div(tx, 16), txp = 16 * nch;
+                    const mpcnn::TrGeom tg = mpcnn::tr_geom(nch, k, ly.cin, wn);
+                    size_t lds = (size_t)2 * tg.buf_b;
+                    if (wk > 1) lds = std::max(lds, (size_t)2 * mw * 2 * 4096);
+                    const int h_items = tg.hh * tg.hwp * (ly.cin / 8), d_items = 4 * txp * 8 * wn;
+                    if (h_items > mpcnn::kTrStageH * 256 || d_items > mpcnn::kTrStageD * 256 ||
+                        lds > kWgradLdsCap || (tg.hwp + 1) * d >= 65536)
+                        continue;
+                    const int ntx = ceil_div(fw, tx);
+                    const long tiles = (long)B * d * d * ceil_div(fh, 4) * ntx;
+                    if (tiles * std::max(std::max(ntx, ceil_div(fh, 4)), d) >= (1ll << 31)) continue;
+                    const long tps = (tiles + target - 1) / target;
+                    const double t_mul = (4.0 / wk) * nch * 2 * mw * 36.0;          // cycles of the instruction stream
+                    const double t_load = (h_items + d_items) * 16.0 / 7.0;          // cycles to take the tile in
+                    const double cost = (double)tps * (std::max(t_mul, t_load) + 1500.0);
+                    if (best < 0 || cost < best) {
+                        best = cost;
+                        w.wm = wm; w.wn = wn; w.wk = wk; w.mw = mw; w.gm = gm; w.gn = gn;
+                        w.Tx = tx; w.TxP = txp; w.lds = std::max(lds, (size_t)1024);
+                    }
+                }
+            }
+        if (best >= 0) {
+            w.bm = true; w.tr = true; w.Mt = Mt; w.Nt = Nt;
+            w.plen = (size_t)Mt * Nt * 1024;
+            const int target = std::max(1, kNumCU / (w.gm * w.gn));
+            w.nty = ceil_div(fh, 4); w.ntx = ceil_div(fw, w.Tx);
+            w.tiles_total = B * d * d * w.nty * w.ntx;
+            w.tiles_per_slab = ceil_div(w.tiles_total, target);
+            w.slabs = ceil_div(w.tiles_total, w.tiles_per_slab);
+            w.ok = true;
+            return w;
+        }
+        w = WgradPlan();
+    }
     if (bm && ly.wgrad_mfma && fits32) {
         // wgrad_bm_kernel.  Every group of workgroups (gm x gn of them cover the result) stages
         // all tiles again, and a compute unit takes in roughly 7 bytes per cycle, which at
@@ -1039,7 +1090,10 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.tiles_total = wp.tiles_total; a.tiles_per_slab = wp.tiles_per_slab;
                 a.Mt = wp.Mt; a.Nt = wp.Nt; a.wm = wp.wm; a.wn = wp.wn; a.wk = wp.wk; a.mw = wp.mw;
                 a.mg_cq = magic_of(ceil_div(Ci, 4)); a.mg_hwp = magic_of(wp.TxP + ly.k - 1);
-                if (wp.bm) {   // items of two positions x 8 channels
+                if (wp.tr) {   // items of one position x 8 channels
+                    a.mg_cq = magic_of(Ci / 8);
+                    a.mg_hwp = magic_of(mpcnn::tr_geom(wp.TxP / 16, ly.k, Ci, wp.wn).hwp);
+                } else if (wp.bm) {   // items of two positions x 8 channels
                     a.mg_cq = magic_of(ceil_div(Ci, 8));
                     a.mg_hwp = magic_of(mpcnn::bm_geom(wp.TxP / 16, ly.k, Ci, wp.wn).hwp / 2);
                 }
@@ -1047,7 +1101,10 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.mg_ntx = magic_of(wp.ntx); a.mg_nty = magic_of(wp.nty); a.mg_d = magic_of(ly.dil);
                 dim3 grid((unsigned)wp.slabs, (unsigned)wp.gm, (unsigned)wp.gn);
                 bool launched = false;
-                if (wp.bm)
+                if (wp.tr)
+                    LAUNCH("wgrad_bm", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
+                           launched = mpcnn::launch_wgrad_tr(a, wp.TxP / 16, grid, wp.lds, st));
+                else if (wp.bm)
                     LAUNCH("wgrad_bm", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
                            launched = mpcnn::launch_wgrad_bm(a, wp.TxP / 16, grid, wp.lds, st));
                 else
@@ -1396,7 +1453,7 @@ mpcnn_status mpcnn_plan_describe(const mpcnn_net* net, int B, int H, int W, int 
         else
             put("  weight gradient: %s MFMA, %d x %d result tiles, waves %d x %d x %d (rows x columns x tile rows), %d row "
                 "tiles per wave, %d x %d workgroup groups, tile 4 x %d (%d), %d tiles in %d slabs of %d, %zu B LDS\n",
-                w.bm ? "bf16" : "fp32", w.Mt, w.Nt, w.wm, w.wn, w.wk, w.mw, w.gm, w.gn, w.Tx, w.TxP, w.tiles_total, w.slabs,
+                w.tr ? "bf16 (transposing reads)" : (w.bm ? "bf16" : "fp32"), w.Mt, w.Nt, w.wm, w.wn, w.wk, w.mw, w.gm, w.gn, w.Tx, w.TxP, w.tiles_total, w.slabs,
                 w.tiles_per_slab, w.lds);
     }
     return MPCNN_OK;
