@@ -212,6 +212,86 @@ __global__ __launch_bounds__(256) void maxfilter_fwd4_kernel(const T* __restrict
     }
 }
 
+// a2 for 2 x 2 windows, 2 x 2 outputs per thread: outputs (y, x), (y, x+d), (y+d, x), (y+d, x+d) share
+// 9 input elements, so a thread loads 9 instead of 16 (every input element is then fetched 2.25
+// times by the threads, not 4: the other fetches were L2 hits, but L2 hits are not free).  A
+// thread's rows y and y+d are neighbours in the row sequence: the sequence walks the rows of
+// one residue class mod d two at a time (y = r + 2 d j), class after class; columns likewise in
+// blocks of 2 d.  Outputs whose row or column lies outside the map are skipped (their loads are
+// clamped to valid addresses).  Same values and codes as maxfilter_fwd4_kernel.
+struct PairGrid {
+    int gx;            // workgroups per row pair
+    int rows;          // B * S, S = row pairs per image
+    int S, C4;         // row pairs per image, channel groups
+    int Sx;            // column pairs per row
+    int d;
+    int nbig, q1;      // the first nbig residue classes have q1 row pairs, the others q1 - 1
+    unsigned mg_gx, mg_S, mg_c4, mg_q1, mg_q0, mg_d;
+};
+template <typename T, int Q>
+__global__ __launch_bounds__(256) void maxfilter_fwd2x2_kernel(const T* __restrict__ A, T* __restrict__ O,
+                                                               uint8_t* __restrict__ code, PairGrid g,
+                                                               int Hi, int Wi, int C, int Ho, int Wo)
+{
+    const unsigned nb = gridDim.x, i = blockIdx.x;
+    const unsigned q = nb >> 3, r8 = nb & 7, xcd = i & 7;
+    const unsigned lb = xcd * q + (xcd < r8 ? xcd : r8) + (i >> 3);   // band of this XCD, then its turn
+    const unsigned row = rg_div(lb, g.mg_gx, g.gx), bx = lb - row * g.gx;
+    const unsigned it = bx * 256 + threadIdx.x;
+    if (it >= (unsigned)(g.Sx * g.C4)) return;
+    const unsigned sx = rg_div(it, g.mg_c4, g.C4), c4 = it - sx * g.C4;
+    const unsigned b = rg_div(row, g.mg_S, g.S);
+    unsigned t = row - b * g.S, rc, j;
+    const unsigned big = (unsigned)(g.nbig * g.q1);
+    if (t < big) { rc = rg_div(t, g.mg_q1, g.q1); j = t - rc * g.q1; }
+    else { const unsigned u = t - big, q0 = g.q1 - 1; const unsigned rr = rg_div(u, g.mg_q0, q0); rc = g.nbig + rr; j = u - rr * q0; }
+    const int d = g.d;
+    const int y0 = (int)(rc + j * 2 * d);
+    const unsigned xb = rg_div(sx, g.mg_d, d);
+    const int x0 = (int)(xb * 2 * d + (sx - xb * d));
+    const bool row1 = y0 + d < Ho, col1 = x0 + d < Wo;
+    // the 3 x 3 inputs (rows y0, +d, +2d; columns x0, +d, +2d), coordinates clamped into the map
+    int ys[3], xs[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        ys[k] = y0 + k * d < Hi ? y0 + k * d : Hi - 1;
+        xs[k] = x0 + k * d < Wi ? x0 + k * d : Wi - 1;
+    }
+    const T* img = A + (long)b * Hi * Wi * C + 4 * Q * c4;
+    v4f in[3][3][Q];
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+#pragma unroll
+        for (int v = 0; v < 3; ++v) load_quads<Q>(img + ((long)ys[u] * Wi + xs[v]) * C, in[u][v]);
+#pragma unroll
+    for (int oy = 0; oy < 2; ++oy)
+#pragma unroll
+        for (int ox = 0; ox < 2; ++ox) {
+            if ((oy && !row1) || (ox && !col1)) continue;
+            v4f best[Q];
+            uint32_t packed[Q];
+#pragma unroll
+            for (int qq = 0; qq < Q; ++qq) {
+                best[qq] = in[oy][ox][qq];
+                uint32_t bi[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int tap = 1; tap < 4; ++tap) {
+                    const v4f a = in[oy + (tap >> 1)][ox + (tap & 1)][qq];
+#pragma unroll
+                    for (int z = 0; z < 4; ++z)
+                        if (a[z] > best[qq][z]) { best[qq][z] = a[z]; bi[z] = tap; }   // strict >: the first maximum wins
+                }
+                packed[qq] = bi[0] | (bi[1] << 8) | (bi[2] << 16) | (bi[3] << 24);
+            }
+            const long e = ((((long)b * Ho + (y0 + oy * d)) * Wo + (x0 + ox * d)) * g.C4 + c4) * (4 * Q);
+            store_quads<Q>(O + e, best);
+            if (code) {
+                if constexpr (Q == 2) *reinterpret_cast<uint2*>(code + e) = make_uint2(packed[0], packed[1]);
+                else *reinterpret_cast<uint32_t*>(code + e) = packed[0];
+            }
+        }
+}
+
 // a7, 4 Q channels per thread: dA = sum over the windows that chose this element (gather in
 // fixed (u,v) order, no atomics), times the squashing function's slope when A is its output.
 template <bool TANHP, typename T, int Q>
@@ -261,6 +341,94 @@ __global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const T* __restrict
             for (int z = 0; z < 4; ++z) acc[q][z] *= squash_slope(a[q][z], logistic);
     }
     store_quads<Q>(dA + e, acc);
+}
+
+// a7 for 2 x 2 windows, 2 x 2 input elements per thread (the layout of maxfilter_fwd2x2_kernel, over
+// the pool's INPUT map): elements (y, x), (y, x+d), (y+d, x), (y+d, x+d) collect from the pooled
+// positions in rows y-d, y, y+d and columns x-d, x, x+d - 9 of them instead of 16.  Same sums in
+// the same (u,v) order as maxfilter_bwd4_kernel.
+template <bool TANHP, typename T, int Q>
+__global__ __launch_bounds__(256) void maxfilter_bwd2x2_kernel(const T* __restrict__ dO,
+                                                               const uint8_t* __restrict__ code,
+                                                               const T* __restrict__ A, T* __restrict__ dA,
+                                                               PairGrid g, int Hi, int Wi, int C, int Ho, int Wo,
+                                                               int logistic)
+{
+    const unsigned nb = gridDim.x, i = blockIdx.x;
+    const unsigned q = nb >> 3, r8 = nb & 7, xcd = i & 7;
+    const unsigned lb = xcd * q + (xcd < r8 ? xcd : r8) + (i >> 3);
+    const unsigned row = rg_div(lb, g.mg_gx, g.gx), bx = lb - row * g.gx;
+    const unsigned it = bx * 256 + threadIdx.x;
+    if (it >= (unsigned)(g.Sx * g.C4)) return;
+    const unsigned sx = rg_div(it, g.mg_c4, g.C4), c4 = it - sx * g.C4;
+    const unsigned b = rg_div(row, g.mg_S, g.S);
+    unsigned t = row - b * g.S, rc, j;
+    const unsigned big = (unsigned)(g.nbig * g.q1);
+    if (t < big) { rc = rg_div(t, g.mg_q1, g.q1); j = t - rc * g.q1; }
+    else { const unsigned u = t - big, q0 = g.q1 - 1; const unsigned rr = rg_div(u, g.mg_q0, q0); rc = g.nbig + rr; j = u - rr * q0; }
+    const int d = g.d;
+    const int y0 = (int)(rc + j * 2 * d);
+    const unsigned xb = rg_div(sx, g.mg_d, d);
+    const int x0 = (int)(xb * 2 * d + (sx - xb * d));
+    // pooled positions in rows y0 - d, y0, y0 + d and columns x0 - d, x0, x0 + d (clamped; `ok` says which exist)
+    int ys[3], xs[3];
+    bool yok[3], xok[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        const int yy = y0 + (k - 1) * d, xx = x0 + (k - 1) * d;
+        yok[k] = yy >= 0 && yy < Ho; xok[k] = xx >= 0 && xx < Wo;
+        ys[k] = yy < 0 ? 0 : (yy < Ho ? yy : Ho - 1);
+        xs[k] = xx < 0 ? 0 : (xx < Wo ? xx : Wo - 1);
+    }
+    const long cb = (long)b * Ho * Wo * C + 4 * Q * c4;
+    v4f gr[3][3][Q];
+    uint32_t cd[3][3][Q];
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+#pragma unroll
+        for (int v = 0; v < 3; ++v) {
+            const long s = cb + ((long)ys[u] * Wo + xs[v]) * C;
+            if constexpr (Q == 2) {
+                const uint2 c2 = *reinterpret_cast<const uint2*>(code + s);
+                cd[u][v][0] = c2.x; cd[u][v][1] = c2.y;
+            } else {
+                cd[u][v][0] = *reinterpret_cast<const uint32_t*>(code + s);
+            }
+            load_quads<Q>(dO + s, gr[u][v]);
+        }
+#pragma unroll
+    for (int iy = 0; iy < 2; ++iy)
+#pragma unroll
+        for (int ix = 0; ix < 2; ++ix) {
+            const int Y = y0 + iy * d, X = x0 + ix * d;
+            if (Y >= Hi || X >= Wi) continue;
+            const long e = ((((long)b * Hi + Y) * Wi + X) * g.C4 + c4) * (4 * Q);
+            v4f acc[Q];
+#pragma unroll
+            for (int qq = 0; qq < Q; ++qq) acc[qq] = (v4f){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int v = 0; v < 2; ++v) {
+                    const int ry = iy + 1 - u, rx = ix + 1 - v;   // the window (Y - u d, X - v d)
+                    if (!yok[ry] || !xok[rx]) continue;
+                    const uint32_t tap = u * 2 + v;
+#pragma unroll
+                    for (int qq = 0; qq < Q; ++qq)
+#pragma unroll
+                        for (int z = 0; z < 4; ++z)
+                            if (((cd[ry][rx][qq] >> (8 * z)) & 255u) == tap) acc[qq][z] += gr[ry][rx][qq][z];
+                }
+            if (TANHP) {
+                v4f a[Q];
+                load_quads<Q>(A + e, a);
+#pragma unroll
+                for (int qq = 0; qq < Q; ++qq)
+#pragma unroll
+                    for (int z = 0; z < 4; ++z) acc[qq][z] *= squash_slope(a[qq][z], logistic);
+            }
+            store_quads<Q>(dA + e, acc);
+        }
 }
 
 struct ClassArgs {

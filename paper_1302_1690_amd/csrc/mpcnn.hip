@@ -735,6 +735,26 @@ bool row_grid(int B, int h, int w, int C4, int d, mpcnn::RowGrid* g)
     return true;
 }
 
+// Launch geometry of maxfilter_fwd2x2_kernel: row pairs (y, y + d) of one residue class mod d, column
+// pairs in blocks of 2 d columns.  False if the map is too large for 32-bit index arithmetic.
+bool pair_grid(int B, int h, int w, int C4, int d, mpcnn::PairGrid* g)
+{
+    const int D2 = 2 * d, q = h / D2, rem = h % D2;
+    const int nbig = std::min(rem, d);
+    const long S = (long)nbig * (q + 1) + (long)(d - nbig) * q;
+    const long Sx = (long)(w / D2) * d + std::min(w % D2, d);
+    if (S < 1 || Sx < 1) return false;
+    const long per_row = Sx * C4, gx = (per_row + 255) / 256, rows = (long)B * S;
+    if (gx * rows >= (1l << 31) || gx * rows * gx >= (1l << 32) || (gx * 256) * C4 >= (1l << 32) ||
+        rows * S >= (1l << 32) || (long)h * D2 >= (1l << 31))
+        return false;
+    g->gx = (int)gx; g->rows = (int)rows; g->S = (int)S; g->C4 = C4; g->Sx = (int)Sx; g->d = d;
+    g->nbig = nbig; g->q1 = q + 1;
+    g->mg_gx = magic_of((unsigned)gx); g->mg_S = magic_of((unsigned)S); g->mg_c4 = magic_of((unsigned)C4);
+    g->mg_q1 = magic_of((unsigned)(q + 1)); g->mg_q0 = magic_of((unsigned)q); g->mg_d = magic_of((unsigned)d);
+    return true;
+}
+
 inline int grid_for(long total, int block = 256, int cap = 1 << 20)
 {
     long g = (total + block - 1) / block;
@@ -904,7 +924,13 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             uint8_t* code = g.training ? (uint8_t*)(ws + g.code_off[l]) : nullptr;
             long total = (long)B * Ho * Wo * ly.cout;
             mpcnn::RowGrid rg;
-            if (!kF32 && !ly.rect && ly.cout % 8 == 0 && row_grid(B, Ho, Wo, ly.cout / 8, ly.dil, &rg))   // bf16: 8 channels per thread (fp32: measured slower)
+            mpcnn::PairGrid pg;
+            constexpr int kQ = kF32 ? 1 : 2;   // channels per thread / 4 (bf16: 8 channels = one 128-bit access)
+            if (!ly.rect && ly.k == 2 && ly.cout % (4 * kQ) == 0 && pair_grid(B, Ho, Wo, ly.cout / (4 * kQ), ly.dil, &pg))
+                LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
+                       (maxfilter_fwd2x2_kernel<T, kQ><<<(unsigned)(pg.gx * pg.rows), 256, 0, st>>>(
+                           in, out, code, pg, Hi, Wi, ly.cout, Ho, Wo)));
+            else if (!kF32 && !ly.rect && ly.cout % 8 == 0 && row_grid(B, Ho, Wo, ly.cout / 8, ly.dil, &rg))   // bf16: 8 channels per thread (fp32: measured slower)
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
                        (maxfilter_fwd4_kernel<T, kF32 ? 1 : 2><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
                            in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil)));
@@ -1049,6 +1075,22 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
             long total = (long)B * Hi * Wi * Ci;
             const double bytes = n_out * (es + 1.0) + n_in * es * (below_tanh ? 2.0 : 1.0);
             mpcnn::RowGrid rg;
+            mpcnn::PairGrid pg;
+            // 2 x 2 windows: 2 x 2 elements per thread, 8 channels each (4 where the count is no multiple of 8);
+            // not where a position is under one 128-byte line and neighbours are adjacent (measured slower)
+            const int pq = Ci % 8 == 0 ? 2 : 1;
+            if (!ly.rect && ly.k == 2 && Ci % 4 == 0 && (ly.dil > 1 || Ci * es >= 128) && pair_grid(B, Hi, Wi, Ci / (4 * pq), ly.dil, &pg)) {
+                const unsigned wgs = (unsigned)(pg.gx * pg.rows);
+#define PAIR_BWD(TP, QQ) LAUNCH("maxfilter_bwd", li, 7, 0, bytes, (maxfilter_bwd2x2_kernel<TP, T, QQ><<<wgs, 256, 0, st>>>( \
+                             dY, code, A, dA, pg, Hi, Wi, Ci, Ho, Wo, net->logistic)))
+                if (below_tanh && pq == 2) PAIR_BWD(true, 2);
+                else if (below_tanh) PAIR_BWD(true, 1);
+                else if (pq == 2) PAIR_BWD(false, 2);
+                else PAIR_BWD(false, 1);
+#undef PAIR_BWD
+                cur ^= 1;
+                continue;
+            }
             const bool octs = !ly.rect && Ci % 8 == 0 && row_grid(B, Hi, Wi, Ci / 8, ly.dil, &rg);   // 8 channels per thread (measured faster in both storage types)
             const bool quads = !ly.rect && !octs && Ci % 4 == 0 && row_grid(B, Hi, Wi, Ci / 4, ly.dil, &rg);
             if (octs && below_tanh)
