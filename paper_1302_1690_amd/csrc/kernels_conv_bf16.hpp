@@ -23,6 +23,8 @@
 // Summation order is the step order for every output element whatever the tiling, as in
 // conv_ts_kernel: equal inputs give bit-equal outputs.
 #pragma once
+#include <type_traits>
+
 #include "kernels_mfma.hpp"
 
 namespace mpcnn {
@@ -232,8 +234,10 @@ __global__ __launch_bounds__(64 * OT * PT / MP, 2) void conv_tp_kernel(ConvArgs 
         if (nxt.live) issue(nxt, pre);
 
         // ---- epilogue from the accumulators: register 4n + z of position tile p is channel
-        // oc0 + 8n + 4lg + z of position 32*(wp*MP + p) + lt
-        if (cur.live) {
+        // oc0 + 8n + 4lg + z of position 32*(wp*MP + p) + lt.  One copy of the code per mode, picked once
+        // per tile: with the mode tested per value the scalar branches cost as much as the arithmetic.
+        auto epilogue = [&](auto mode_tag) {
+            constexpr int mode = decltype(mode_tag)::value;
 #pragma unroll
             for (int p = 0; p < MP; ++p) {
                 const int ty = (int)(e_tyx[p] >> 16), tx = (int)(e_tyx[p] & 0xffffu);
@@ -247,9 +251,9 @@ __global__ __launch_bounds__(64 * OT * PT / MP, 2) void conv_tp_kernel(ConvArgs 
                 for (int n = 0; n < 4; ++n) {
                     const int oc = oc0 + 8 * n + 4 * lg;
                     yv[n] = zero4;
-                    if (pos_ok && oc < a.Co) {
-                        if (a.mode == kDgradTanh) yv[n] = load4(act_t + pos_off + oc);
-                        else if (a.mode <= kFwdLinear) yv[n] = *reinterpret_cast<const v4f*>(a.bias + oc);
+                    if (mode != kDgradPlain && pos_ok && oc < a.Co) {
+                        if (mode == kDgradTanh) yv[n] = load4(act_t + pos_off + oc);
+                        else yv[n] = *reinterpret_cast<const v4f*>(a.bias + oc);
                     }
                 }
 #pragma unroll
@@ -257,18 +261,24 @@ __global__ __launch_bounds__(64 * OT * PT / MP, 2) void conv_tp_kernel(ConvArgs 
                     const int oc = oc0 + 8 * n + 4 * lg;
                     if (!pos_ok || oc >= a.Co) continue;
                     v4f s4 = (v4f){acc[p][4 * n], acc[p][4 * n + 1], acc[p][4 * n + 2], acc[p][4 * n + 3]};
-                    if (a.mode == kFwdTanh) {
+                    if (mode == kFwdTanh) {
 #pragma unroll
                         for (int z = 0; z < 4; ++z) s4[z] = squash(s4[z] + yv[n][z], a.logistic);
-                    } else if (a.mode == kFwdLinear) {
+                    } else if (mode == kFwdLinear) {
                         s4 += yv[n];
-                    } else if (a.mode == kDgradTanh) {
+                    } else if (mode == kDgradTanh) {
 #pragma unroll
                         for (int z = 0; z < 4; ++z) s4[z] *= squash_slope(yv[n][z], a.logistic);
                     }
                     store4(out_t + pos_off + oc, s4);   // (channel counts are multiples of 4)
                 }
             }
+        };
+        if (cur.live) {
+            if (a.mode == kFwdTanh) epilogue(std::integral_constant<int, kFwdTanh>{});
+            else if (a.mode == kDgradTanh) epilogue(std::integral_constant<int, kDgradTanh>{});
+            else if (a.mode == kFwdLinear) epilogue(std::integral_constant<int, kFwdLinear>{});
+            else epilogue(std::integral_constant<int, kDgradPlain>{});
         }
         __syncthreads();   // every wave has left this tile's halo
         if (nxt.live) to_lds(pre);

@@ -437,6 +437,7 @@ struct ClassArgs {
     float* probs;          // [B][NCLS][Ho][Wo] or null
     const int32_t* labels; // [B][H][W]      (training)
     const float* pixw;     // [B][H][W] or null
+    const float* pixw_any; // pixw, or with none the labels (as many elements: fetched with them, not used)
     void* dH;              // [M][K]         (training) delta w.r.t. the pre-activation below (T)
     float* partial;        // [blocks][(K+1)*NCLS]  (training) this block's share of dW, db
     double* loss_partial;  // [blocks] or null
@@ -453,10 +454,48 @@ struct ClassArgs {
 // 4Q(j + 16(v/Q)) + 4(v%Q) .. +3 - with Q = 1 every quad is a 128-bit access of its own (fp32), with
 // Q = 2 two neighbouring quads are one (8 bf16 values; K a multiple of 8); dot products meet
 // by xor-shuffles in a fixed order.  A workgroup walks 16 positions at a time.
+// Q quads as they come from memory (expanded to fp32 only when their turn comes)
+template <int Q, typename T> struct RawQuads { typedef v4f type; };
+template <> struct RawQuads<1, bf16> { typedef bf16x4 type; };
+template <> struct RawQuads<2, bf16> { typedef __bf16 type __attribute__((ext_vector_type(8))); };
+template <int Q>
+__device__ __forceinline__ void expand_quads(const typename RawQuads<Q, float>::type& r, v4f (&v)[Q]) { v[0] = r; }
+template <int Q>
+__device__ __forceinline__ void expand_quads(const typename RawQuads<Q, bf16>::type& r, v4f (&v)[Q])
+{
+    if constexpr (Q == 2) {
+        v[0] = __builtin_convertvector(r.lo, v4f);
+        v[1] = __builtin_convertvector(r.hi, v4f);
+    } else {
+        v[0] = __builtin_convertvector(r, v4f);
+    }
+}
+// Sum over each aligned group of 16 lanes, left in all of them: four rotations inside the row of the
+// data-parallel-primitive modifier (no LDS round trip).  Every lane's additions pair the same partial
+// sums as a butterfly over lane ^ 8, 4, 2, 1 would, so all 16 results are the same bits.
+template <int CTRL>
+__device__ __forceinline__ float row_rotated(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += row_rotated<0x128>(x);   // row_ror:8
+    x += row_rotated<0x124>(x);   // row_ror:4
+    x += row_rotated<0x122>(x);   // row_ror:2
+    x += row_rotated<0x121>(x);   // row_ror:1
+    return x;
+}
+// positions fetched ahead per 16-lane group: the pass keeps only two waves per SIMD, and what bounds it
+// is the number of bytes those waves have in flight (about 40-50 KB per compute unit with these
+// depths); one less where the weights and their sums leave no registers for it
+template <typename T, int NCLS, int KV>
+constexpr int kClassAhead = (sizeof(T) == 2 ? 3 : 2) - (NCLS * KV >= 16 ? 1 : 0);
 template <int NCLS, int KV, bool TRAIN, typename T, int Q = 1>
-__global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
+__global__ __launch_bounds__(256, 2) void class_layer_kernel(ClassArgs a)
 {
     static_assert(KV % Q == 0, "whole accesses");
+    static_assert(Q == 1 || sizeof(T) == 2, "pairs of quads: 2-byte storage only");
     auto chan = [](int lane16, int v) { return 4 * Q * (lane16 + 16 * (v / Q)) + 4 * (v % Q); };
     const T* h_t = static_cast<const T*>(a.h);
     T* dh_t = static_cast<T*>(a.dH);
@@ -480,35 +519,74 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
 #pragma unroll
     for (int o = 0; o < NCLS; ++o) { bias[o] = a.Wk[(long)a.K * NCLS + o]; gb[o] = 0.f; }
     double my_loss = 0.0;
+    // slope of the squashing function below in terms of its output y, as sl0 + y (sl1 + y sl2):
+    // none 1, tanh 1 - y^2, logistic y (1 - y) - the same roundings as the direct forms, no selects
+    const float sl0 = a.tanh_below == 2 ? 0.f : 1.f, sl1 = a.tanh_below == 2 ? 1.f : 0.f,
+                sl2 = a.tanh_below ? -1.f : 0.f;
 
     // the pass is a chain of dependent steps per position (load, dot products, shuffles, exp,
-    // stores): the next position's h is fetched before the current one is worked on, and the
-    // launch fills the CU with workgroups, so that enough bytes are in flight
+    // stores): the h of the next few positions is fetched before the current one is worked on.
+    // The loads sit behind no branch (every path then has the same number in flight and the waits
+    // stay exact): a position past the end reads the last one again, a channel group past K reads
+    // group 0 - its weights are zero, and nothing of it is stored.
+    typedef typename RawQuads<Q, T>::type Raw;
+    constexpr int AH = kClassAhead<T, NCLS, KV>;
     const long stride = (long)gridDim.x * 16;
-    v4f hn[KV];
-    auto fetch_h = [&](long m) {
+    Raw ring[AH][KV / Q];
+    int coff[KV / Q];
 #pragma unroll
-        for (int v = 0; v < KV; v += Q) {
-            const int c = chan(j, v);
-#pragma unroll
-            for (int q = 0; q < Q; ++q) hn[v + q] = (v4f){0.f, 0.f, 0.f, 0.f};
-            if (c < a.K && m < M) load_quads<Q>(h_t + m * a.K + c, *reinterpret_cast<v4f(*)[Q]>(&hn[v]));
-        }
-    };
-    fetch_h((long)blockIdx.x * 16 + grp);
+    for (int v = 0; v < KV / Q; ++v) coff[v] = chan(j, v * Q) < a.K ? chan(j, v * Q) : 0;
     // position m as (image b, row iy, column jx), advanced by the stride's own (images, rows,
-    // columns) instead of dividing a 64-bit index at every position
+    // columns) instead of dividing a 64-bit index at every position; (fb, fy, fx) runs AH steps ahead
     const long m0 = (long)blockIdx.x * 16 + grp;
     int jx = (int)(m0 % a.Wo), iy = (int)((m0 / a.Wo) % a.Ho), b = (int)(m0 / a.Wo / a.Ho);
     const int sx = (int)(stride % a.Wo), sy = (int)((stride / a.Wo) % a.Ho), sb = (int)(stride / a.Wo / a.Ho);
-    for (long m = m0; m < M; m += stride) {
+    int fx = jx, fy = iy, fb = b;
+    // the label and pixel weight travel with h: loads return in issue order, so a label fetched when
+    // its position comes up would have to wait for everything fetched ahead
+    int ring_t[AH];
+    float ring_w[AH];
+    const long jplane = (long)j * a.probs_rows * a.Wo;   // this lane's class plane of the probabilities
+    // element offsets of the position worked on and of the one being fetched, advanced by additions
+    const long hstep = stride * a.K, last_off = (M - 1) * a.K;
+    long hoff = m0 * a.K, foff = hoff;
+    auto fetch_h = [&](long m, Raw (&dst)[KV / Q], int& t, float& wt) {
+        const bool in = m < M;
+        const T* row = h_t + (in ? foff : last_off);
+        foff += hstep;
+#pragma unroll
+        for (int v = 0; v < KV / Q; ++v) dst[v] = *reinterpret_cast<const Raw*>(row + coff[v]);
+        if (TRAIN) {
+            // (image and row in 32 bits: B * H rows exist as an array index on the host already)
+            const long lp = in ? (long)(fb * a.H + fy + a.ctr) * a.W + (fx + a.ctr) : 0;
+            t = a.labels[lp];
+            wt = a.pixw_any[lp];
+        }
+        fx += sx;
+        if (fx >= a.Wo) { fx -= a.Wo; ++fy; }
+        fy += sy;
+        if (fy >= a.Ho) { fy -= a.Ho; ++fb; }
+        fb += sb;
+    };
+#pragma unroll
+    for (int i = 0; i < AH; ++i) fetch_h(m0 + i * stride, ring[i], ring_t[i], ring_w[i]);
+    // (the ring's slots are taken in turn by an unrolled inner loop: moving a slot's registers
+    // along would wait for its load; a turn past the last position works on the last position
+    // again with label "ignore" and stores nothing - no exit from the middle of the round)
+    for (long mo = m0; mo < M; mo += AH * stride)
+#pragma unroll
+    for (int slot = 0; slot < AH; ++slot) {
+        const long m = mo + slot * stride;
+        const bool live = m < M;
         v4f hv[KV];
         float z[NCLS];
 #pragma unroll
         for (int o = 0; o < NCLS; ++o) z[o] = 0.f;
 #pragma unroll
-        for (int v = 0; v < KV; ++v) hv[v] = hn[v];
-        fetch_h(m + stride);
+        for (int v = 0; v < KV / Q; ++v) expand_quads<Q>(ring[slot][v], *reinterpret_cast<v4f(*)[Q]>(&hv[v * Q]));
+        int t = ring_t[slot];
+        const float wt_in = ring_w[slot];
+        fetch_h(m + AH * stride, ring[slot], ring_t[slot], ring_w[slot]);
 #pragma unroll
         for (int v = 0; v < KV; ++v) {
 #pragma unroll
@@ -518,34 +596,35 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
         }
 #pragma unroll
         for (int o = 0; o < NCLS; ++o) {
-            z[o] += __shfl_xor(z[o], 8, 16);
-            z[o] += __shfl_xor(z[o], 4, 16);
-            z[o] += __shfl_xor(z[o], 2, 16);
-            z[o] += __shfl_xor(z[o], 1, 16);
-            z[o] += bias[o];
+            z[o] = row16_sum(z[o]) + bias[o];
         }
         float zmax = z[0];
 #pragma unroll
         for (int o = 1; o < NCLS; ++o) zmax = fmaxf(zmax, z[o]);
         float sum = 0.f, pr[NCLS];
 #pragma unroll
-        for (int o = 0; o < NCLS; ++o) { z[o] -= zmax; pr[o] = expf(z[o]); sum += pr[o]; }
-        const float inv = a.mse ? 1.f : 1.f / sum;
+        for (int o = 0; o < NCLS; ++o) {   // arguments <= 0: the hardware exp2 neither overflows nor needs a range check
+            z[o] -= zmax;
+            pr[o] = __builtin_amdgcn_exp2f(1.4426950408889634f * z[o]);
+            sum += pr[o];
+        }
+        const float inv = a.mse ? 1.f : __builtin_amdgcn_rcpf(sum);
         if (a.mse) {   // the outputs themselves (Method: mean squared error with linear outputs)
 #pragma unroll
             for (int o = 0; o < NCLS; ++o) pr[o] = z[o] + zmax;
         }
 #pragma unroll
-        for (int o = 0; o < NCLS; ++o) {
-            pr[o] *= inv;
-            if (a.probs && j == o) a.probs[(((long)b * NCLS + o) * a.probs_rows + iy) * a.Wo + jx] = pr[o];
+        for (int o = 0; o < NCLS; ++o) pr[o] *= inv;
+        if (a.probs) {   // lane o of the 16 writes class o: one store, at this lane's plane
+            float pj = pr[0];
+#pragma unroll
+            for (int o = 1; o < NCLS; ++o) pj = j == o ? pr[o] : pj;
+            if (j < NCLS && live) a.probs[(long)(b * NCLS * a.probs_rows + iy) * a.Wo + jx + jplane] = pj;
         }
         if (TRAIN) {
-            const long lp = ((long)b * a.H + (iy + a.ctr)) * a.W + (jx + a.ctr);
-            int t = a.labels[lp];
             float wt = 0.f;
-            if (t < 0 || t >= NCLS) t = -1;
-            else wt = a.pixw ? a.pixw[lp] : 1.f;
+            if (t < 0 || t >= NCLS || !live) t = -1;
+            else wt = a.pixw ? wt_in : 1.f;
             float dz[NCLS];
             float zt = 0.f, sq = 0.f;
 #pragma unroll
@@ -569,16 +648,17 @@ __global__ __launch_bounds__(256) void class_layer_kernel(ClassArgs a)
                         g = fmaf(w[v][s][o], dz[o], g);
                         gw[v][s][o] = fmaf(hv[v][s], dz[o], gw[v][s][o]);
                     }
-                    dh[v][s] = a.tanh_below ? g * squash_slope(hv[v][s], a.tanh_below == 2) : g;   // 0 none, 1 tanh, 2 logistic
+                    dh[v][s] = g * fmaf(hv[v][s], fmaf(hv[v][s], sl2, sl1), sl0);
                 }
             }
-            if (dh_t)   // (no delta buffer: loss only)
+            if (dh_t && live)   // (no delta buffer: loss only)
 #pragma unroll
                 for (int v = 0; v < KV; v += Q) {
                     const int c = chan(j, v);
-                    if (c < a.K) store_quads<Q>(dh_t + m * a.K + c, *reinterpret_cast<const v4f(*)[Q]>(&dh[v]));
+                    if (c < a.K) store_quads<Q>(dh_t + hoff + c, *reinterpret_cast<const v4f(*)[Q]>(&dh[v]));
                 }
         }
+        hoff += hstep;
         jx += sx;
         if (jx >= a.Wo) { jx -= a.Wo; ++iy; }
         iy += sy;

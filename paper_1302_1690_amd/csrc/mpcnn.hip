@@ -947,7 +947,7 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
             const long M = (long)B * Ho * Wo;
             ClassArgs a{};
             a.h = in; a.Wk = net->d_wread + ly.p_off; a.probs = probs;
-            a.labels = labels; a.pixw = pixw; a.dH = dZ;
+            a.labels = labels; a.pixw = pixw; a.pixw_any = pixw ? pixw : reinterpret_cast<const float*>(labels); a.dH = dZ;
             a.partial = g.training ? (float*)(ws + g.partial_off[l]) : nullptr;   // loss only: no gradient shares
             a.loss_partial = want_loss ? lp : nullptr;
             a.B = B; a.Ho = Ho; a.Wo = Wo; a.H = g.label_h; a.W = g.W; a.ctr = (net->patch - 1) / 2;

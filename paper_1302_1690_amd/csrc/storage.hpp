@@ -28,23 +28,24 @@ __device__ __forceinline__ float load1(const bf16* p) { return (float)*p; }
 __device__ __forceinline__ void store1(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store1(bf16* p, float v) { *p = (bf16)v; }
 
-// tanh(x) = 1 - 2 / (exp(2x) + 1) with the hardware exp2 and reciprocal: absolute error
-// about 1e-7; saturates correctly (exp -> inf gives 1, exp -> 0 gives -1).
-__device__ __forceinline__ float fast_tanh(float x)
+// The squashing function of C and hidden FC layers (Background, layer C: tanh or logistic) and its
+// derivative written in terms of its output.  Both functions are one formula with three constants
+// picked by the (launch-uniform) flag, so that no branch or select stands between the values:
+//   y = A / (exp2(c x) + 1) + B     tanh: c = 2 log2 e, A = -2, B = 1   (tanh x = 1 - 2 / (e^(2x) + 1))
+//                                   logistic: c = -log2 e, A = 1, B = 0 (1 / (1 + e^(-x)))
+// with the hardware exp2 and reciprocal: absolute error about 1e-7; saturates correctly
+// (exp -> inf gives B, exp -> 0 gives A + B).
+//   dy/dx = l0 + y (l1 - y)         tanh: 1 - y^2;  logistic: y (1 - y)
+__device__ __forceinline__ float squash(float x, int logistic)
 {
-    const float e = __builtin_amdgcn_exp2f(2.885390081777927f * x);   // e^(2x) = 2^(2x log2 e)
-    return fmaf(-2.f, __builtin_amdgcn_rcpf(e + 1.f), 1.f);
+    const float c = logistic ? -1.4426950408889634f : 2.885390081777927f;
+    const float A = logistic ? 1.f : -2.f, B = logistic ? 0.f : 1.f;
+    return fmaf(A, __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(c * x) + 1.f), B);
 }
-
-// logistic function 1 / (1 + exp(-x)), same hardware functions (exp -> inf gives 0, exp -> 0 gives 1)
-__device__ __forceinline__ float fast_logistic(float x)
+__device__ __forceinline__ float squash_slope(float y, int logistic)
 {
-    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * x);
-    return __builtin_amdgcn_rcpf(e + 1.f);
+    const float l0 = logistic ? 0.f : 1.f, l1 = logistic ? 1.f : 0.f;
+    return fmaf(y, fmaf(y, -1.f, l1), l0);
 }
-// The squashing function of C and hidden FC layers (Background, layer C: tanh or logistic) and
-// its derivative written in terms of its output.
-__device__ __forceinline__ float squash(float x, int logistic) { return logistic ? fast_logistic(x) : fast_tanh(x); }
-__device__ __forceinline__ float squash_slope(float y, int logistic) { return logistic ? y * (1.f - y) : 1.f - y * y; }
 
 }  // namespace mpcnn
