@@ -150,7 +150,11 @@ class Net:
             lib().mpcnn_net_destroy(self._h)
             self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except TypeError:     # interpreter shutdown: the module's globals are already gone
+            pass
 
     # ---- host-only queries
     @property
