@@ -409,7 +409,9 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
     const bool fits32 = (size_t)in_r * in_c * ly.cin < (1ull << 31) &&
                         (size_t)out_r * out_c * ly.cout < (1ull << 31) && (k + 3) * d < 65536;
     // the bf16 instruction's kernel gives a wave pairs of column tiles: not for 32 maps or fewer
-    bm = bm && ly.cout > 32;
+    // - except for an image layer's few channels, where that kernel, half of its instructions wasted,
+    // is still ahead of the fp32 instruction's (7 x 7 filters on 2 x 3 x 2048 x 2048, 32 maps: 1.51 -> 1.34 ms)
+    bm = bm && (ly.cout > 32 || ly.cin < 8);
     if (bm && ly.wgrad_mfma && fits32 && ly.cin % 32 == 0) {
         // wgrad_tr_kernel: the tiles are raw copies in planes of 32 channels.  Same choices as for
         // wgrad_bm_kernel below: wave split and tile width together, by the busiest workgroup's
