@@ -1,6 +1,7 @@
 // Bandwidth-bound steps of the whole-image pass, each written so that every tensor is
 // read or written once, in channels-last order [B][rows][cols][C]:
-//   first_layer_kernel   conv + bias + tanh for a layer with very few input channels
+//   first_layer_kernel   conv + bias + tanh for a layer with very few input channels (shapes the
+//                        matrix-instruction kernels of the image layer do not take)
 //   maxfilter_fwd4 / maxfilter_bwd4   stride-1 max filter / routing by argmax, 4 channels per thread
 //   class_layer_kernel   last FC (1x1) + softmax + cross-entropy + its own backward
 // (step numbers a0 .. a8 in the comments: see the list at the top of kernels_direct.hpp)

@@ -29,6 +29,7 @@
 #include "kernels_reduce.hpp"
 #include "kernels_lbfgs.hpp"
 #include "kernels_first_bf16.hpp"
+#include "kernels_first_f32.hpp"
 #include "kernels_fused.hpp"
 
 // Device memory of mpcnn_seg_forward_static: a fixed array in the library's device image, so that
@@ -798,6 +799,22 @@ void launch_first_bm(const mpcnn::FirstBmArgs& a, unsigned wgs, hipStream_t st)
     CASE(1, 3) CASE(1, 5) CASE(1, 7) CASE(2, 3) CASE(2, 5) CASE(2, 7)
 #undef CASE
 }
+// fp32 storage, the image layer on the fp32 matrix instruction: instance by filter side, channels and rows per wave
+bool launch_first_mfma(const mpcnn::FirstMfmaArgs& a0, int k, int ci, int B, hipStream_t st)
+{
+    mpcnn::FirstMfmaArgs a = a0;
+    const int ct = ceil_div(a.Co, 32);
+    int mp = 4;   // rows per wave: as many as still give every compute unit two workgroups
+    while (mp > 1 && (long)B * ceil_div(a.Ho, 4 * mp) * ceil_div(a.Wo, 32) * ct < 2L * kNumCU) mp >>= 1;
+    a.nty = ceil_div(a.Ho, 4 * mp); a.ntx = ceil_div(a.Wo, 32);
+    const dim3 grid((unsigned)(B * a.nty * a.ntx), (unsigned)ct);
+#define CASE(kk, cc, mm) if (k == kk && ci == cc && mp == mm) { mpcnn::first_layer_mfma_kernel<kk, cc, mm><<<grid, 256, 0, st>>>(a); return true; }
+#define CASES(kk, cc) CASE(kk, cc, 1) CASE(kk, cc, 2) CASE(kk, cc, 4)
+    CASES(3, 1) CASES(5, 1) CASES(7, 1) CASES(3, 3) CASES(5, 3) CASES(7, 3)
+#undef CASES
+#undef CASE
+    return false;
+}
 // Kernels that may ask for more than 64 KiB of dynamic LDS must say so once.
 mpcnn_status set_lds_attrs(bool bf16_storage)
 {
@@ -995,6 +1012,16 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 a.nty = ceil_div(Ho, kFirstBmTy); a.ntx = ceil_div(Wo, kFirstBmTx);
                 const unsigned wgs = (unsigned)std::min<long>((long)B * a.nty * a.ntx, 4L * kNumCU);
                 LAUNCH("first_layer_bm", l, step, flops, bytes, launch_first_bm(a, wgs, st));
+            } else if (kF32 && !ly.rect && ly.dil == 1 && (Ci == 1 || Ci == 3) && (ly.k == 3 || ly.k == 5 || ly.k == 7) &&
+                       (long)B * Ho * Wo < (1l << 31) / 32) {
+                // fp32 storage, the image layer: short reduction on the fp32 matrix instruction
+                FirstMfmaArgs a{};
+                a.in = (const float*)in; a.Wk = Wk; a.out = (float*)out;
+                a.B = B; a.Hi = Hi; a.Wi = Wi; a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout;
+                a.squash = ly.tanh_out ? 1 + net->logistic : 0;
+                bool launched = false;
+                LAUNCH("first_layer_mfma", l, step, flops, bytes, launched = launch_first_mfma(a, ly.k, Ci, B, st));
+                if (!launched) return fail(MPCNN_EUNSUPPORTED, "layer %zu: no image-layer kernel instance", l);
             } else {
                 const int og = ceil_div(ly.cout, 4);
                 const long total = (long)B * Ho * Wo * og;
