@@ -417,6 +417,25 @@ def test_weight_gradient_of_a_many_channel_layer():
                             seed_image=1116, seed_label=2116, seed_param=3116), check_layers=False)
 
 
+def test_image_layer_kernel_variants():
+    """The image layer's matrix-instruction kernel with fp32 storage: filter sides 3, 5, 7, one and
+    three input channels, map counts that are no multiple of 4 or of 32, more than 32 maps, images
+    that end inside a tile in both directions, two images; full oracle with per-layer activations."""
+    from dataclasses import replace
+    cases = [  # (k, channels, maps, height, width, batch)
+        (3, 1, 6, 41, 37, 2), (5, 1, 16, 70, 45, 1), (7, 1, 40, 52, 66, 1),
+        (3, 3, 33, 38, 35, 1), (5, 3, 8, 45, 71, 2), (7, 3, 12, 49, 40, 1),
+    ]
+    for i, (k, ci, maps, h, w, b) in enumerate(cases):
+        # patch: k + 5 -> 6 -> (MP2) 3 -> (C 2x2) 2 -> FC over 2x2
+        layers = ((C, maps, k), (MP, 0, 2), (C, 8, 2), (FC, 6, 0), (FC, 2 + (ci == 3), 0))
+        cfg = replace(wl.CONFIGS[0], name="image_layer_k%d_c%d_m%d" % (k, ci, maps), layers=layers, patch=k + 5,
+                      in_channels=ci, n_classes=2 + (ci == 3), batch=b, height=h, width=w, weight_amp=0.2,
+                      shapes="ellipses" if ci == 3 else "rects", seed_image=1300 + i, seed_label=2300 + i,
+                      seed_param=3300 + i)
+        full_parity(cfg)
+
+
 def test_logistic_activation():
     """The logistic function instead of tanh in every C and hidden FC layer: matrix-core kernels
     (config 1's net), the direct kernels (tiny net), MSE on top, and bf16 storage."""
