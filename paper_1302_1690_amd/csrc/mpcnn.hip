@@ -30,6 +30,7 @@
 #include "kernels_lbfgs.hpp"
 #include "kernels_first_bf16.hpp"
 #include "kernels_first_f32.hpp"
+#include "kernels_l0_wgrad.hpp"
 #include "kernels_fused.hpp"
 
 // Device memory of mpcnn_seg_forward_static: a fixed array in the library's device image, so that
@@ -133,6 +134,7 @@ struct WgradPlan {
     int hl = 0;           // halo items per loading thread and tile (fp32 matrix instruction kernel)
     // direct kernel fallback
     int rows_per_chunk = 0, chunks = 0;
+    bool l0m = false;     // the image layer's own kernel (l0_wgrad_mfma_kernel): `chunks` workgroups, flat partial results
 };
 
 // Per-call geometry: dense map sizes, launch plans and workspace offsets.
@@ -672,6 +674,24 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
             g->partial_len[0] = l0.p_len;
         }
     }
+    if (training && !g->l0_fused) {
+        // the image layer's weight gradient on its own matrix-instruction kernel
+        const Layer& l0 = net->layers[0];
+        if (l0.kind != MPCNN_MP && !l0.class_fused && !l0.rect && l0.dil == 1 && (l0.cin == 1 || l0.cin == 3) &&
+            (l0.k == 3 || l0.k == 5 || l0.k == 7)) {
+            WgradPlan w;
+            w.l0m = true;
+            const long tiles = (long)B * ceil_div(g->rows[0], mpcnn::kL0wTy) * ceil_div(g->cols[0], mpcnn::kL0wTx);
+            w.tiles_total = (int)tiles;
+            w.chunks = (int)std::min<long>(tiles, 3L * kNumCU);
+            w.plen = l0.p_len;
+            if (tiles < (1l << 30)) {
+                g->wgrad[0] = w;
+                g->partial_n[0] = w.chunks;
+                g->partial_len[0] = l0.p_len;
+            }
+        }
+    }
     if (training) {
         for (size_t l = 0; l < L; ++l) {
             const Layer& ly = net->layers[l];
@@ -815,6 +835,14 @@ bool launch_first_mfma(const mpcnn::FirstMfmaArgs& a0, int k, int ci, int B, hip
 #define CASES(kk, cc) CASE(kk, cc, 1) CASE(kk, cc, 2) CASE(kk, cc, 4)
     CASES(3, 1) CASES(5, 1) CASES(7, 1) CASES(3, 3) CASES(5, 3) CASES(7, 3)
 #undef CASES
+#undef CASE
+    return false;
+}
+template <typename T>
+bool launch_l0_wgrad(const mpcnn::L0WgradArgs& a, int k, int ci, dim3 grid, hipStream_t st)
+{
+#define CASE(kk, cc) if (k == kk && ci == cc) { mpcnn::l0_wgrad_mfma_kernel<kk, cc, T><<<grid, 256, 0, st>>>(a); return true; }
+    CASE(3, 1) CASE(5, 1) CASE(7, 1) CASE(3, 3) CASE(5, 3) CASE(7, 3)
 #undef CASE
     return false;
 }
@@ -1186,6 +1214,15 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                            launched = launch_wgrad_mfma<T>(a, wp.hl, grid, wp.lds, st));
                 if (!launched)
                     return fail(MPCNN_EUNSUPPORTED, "layer %zu: no weight-gradient kernel instance for its plan", li);
+            } else if (wp.l0m) {
+                L0WgradArgs a{};
+                a.in = A; a.dY = dY; a.partial = partial;
+                a.B = B; a.Hi = Hi; a.Wi = Wi; a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout;
+                a.nty = ceil_div(Ho, mpcnn::kL0wTy); a.ntx = ceil_div(Wo, mpcnn::kL0wTx); a.tiles_total = wp.tiles_total;
+                bool launched = false;
+                LAUNCH("wgrad_image_mfma", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
+                       launched = launch_l0_wgrad<T>(a, ly.k, Ci, dim3((unsigned)wp.chunks, (unsigned)ceil_div(ly.cout, 32)), st));
+                if (!launched) return fail(MPCNN_EUNSUPPORTED, "layer 0: no image-layer weight-gradient kernel instance");
             } else {
                 dim3 grid((unsigned)((ly.p_len + 255) / 256), (unsigned)wp.chunks);
                 LAUNCH("wgrad_direct", li, wstep, flops, es * (n_in + n_out) + 4.0 * ly.p_len,
@@ -1523,6 +1560,7 @@ mpcnn_status mpcnn_plan_describe(const mpcnn_net* net, int B, int H, int W, int 
         if (l > 0) conv("data gradient", ly, g.dgrad[l], ly.dgrad_ct, ly.dgrad_bm);
         const WgradPlan& w = g.wgrad[l];
         if (l == 0 && g.l0_fused) put("  weight gradient: fused with the routing of the pool above, %d workgroups\n", g.l0_blocks);
+        else if (w.l0m) put("  weight gradient: image-layer kernel on the fp32 MFMA, %d tiles of 8 x 32, %d workgroups\n", w.tiles_total, w.chunks);
         else if (!w.ok) put("  weight gradient: plain kernel, %d chunks\n", w.chunks);
         else
             put("  weight gradient: %s MFMA, %d x %d result tiles, waves %d x %d x %d (rows x columns x tile rows), %d row "
