@@ -58,37 +58,72 @@ __global__ __launch_bounds__(256) void l0_wgrad_mfma_kernel(L0WgradArgs a)
         for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
     float bsum = 0.f;
 
-    for (int t = blockIdx.x; t < a.tiles_total; t += gridDim.x) {
+    // A tile's values wait in registers while the tile before it is multiplied: the loads are issued
+    // before the matrix instructions of the current tile and written to LDS after them.
+    constexpr int XN = (HH * HWC + 255) / 256;              // image values per thread
+    float xr[XN];
+    v4f dr[8];                                              // 8 quads of deltas, or 32 single ones
+    const bool quads = (a.Co & 3) == 0;
+    auto fetch = [&](int t) {
         int bid = t;
         const int txi = bid % a.ntx; bid /= a.ntx;
         const int tyi = bid % a.nty;
         const int b = bid / a.nty;
         const int y0 = tyi * TY, x0 = txi * TX;
-        // ---- the image tile (outside the image: zeros) and the delta tile (outside the map, and maps
-        // past the last: zeros - a zero delta contributes nothing whatever the image value)
+        // outside the image: zeros; outside the map, and maps past the last: zeros (a zero delta
+        // contributes nothing whatever the image value)
         const T* img = in_t + (long)b * a.Hi * a.Wi * C;
-        for (int e = tid; e < HH * HWC; e += 256) {
+#pragma unroll
+        for (int i = 0; i < XN; ++i) {
+            const int e = tid + 256 * i;
             const int hy = e / HWC, hx = e - hy * HWC;
             const int iy = y0 + hy, ie = x0 * C + hx;
-            xt[e] = (iy < a.Hi && ie < a.Wi * C) ? load1(img + (long)iy * a.Wi * C + ie) : 0.f;
+            const bool ok = e < HH * HWC && iy < a.Hi && ie < a.Wi * C;
+            xr[i] = load1(img + (ok ? (long)iy * a.Wi * C + ie : 0));
+            if (!ok) xr[i] = 0.f;
         }
         const T* dyb = dy_t + (long)b * a.Ho * a.Wo * a.Co;
-        if ((a.Co & 3) == 0) {
-            for (int e = tid; e < TY * TX * 8; e += 256) {
-                const int pos = e >> 3, q = e & 7;
+        if (quads) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int e = tid + 256 * i, pos = e >> 3, q = e & 7;
                 const int y = y0 + pos / TX, x = x0 + pos % TX;
-                v4f v = {0.f, 0.f, 0.f, 0.f};
-                if (y < a.Ho && x < a.Wo && 4 * q < nco) v = load4(dyb + ((long)y * a.Wo + x) * a.Co + oc0 + 4 * q);
-                *reinterpret_cast<v4f*>(dt + pos * 32 + 4 * q) = v;
+                const bool ok = y < a.Ho && x < a.Wo && 4 * q < nco;
+                dr[i] = load4(dyb + (ok ? ((long)y * a.Wo + x) * a.Co + oc0 + 4 * q : 0));
+                if (!ok) dr[i] = (v4f){0.f, 0.f, 0.f, 0.f};
             }
         } else {
-            for (int e = tid; e < TY * TX * 32; e += 256) {
-                const int pos = e >> 5, o = e & 31;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                const int e = tid + 256 * i, pos = e >> 5, o = e & 31;
                 const int y = y0 + pos / TX, x = x0 + pos % TX;
-                dt[e] = (y < a.Ho && x < a.Wo && o < nco) ? load1(dyb + ((long)y * a.Wo + x) * a.Co + oc0 + o) : 0.f;
+                const bool ok = y < a.Ho && x < a.Wo && o < nco;
+                const float v = load1(dyb + (ok ? ((long)y * a.Wo + x) * a.Co + oc0 + o : 0));
+                dr[i >> 2][i & 3] = ok ? v : 0.f;
             }
         }
+    };
+    auto deposit = [&]() {
+#pragma unroll
+        for (int i = 0; i < XN; ++i)
+            if (tid + 256 * i < HH * HWC) xt[tid + 256 * i] = xr[i];
+        if (quads) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int e = tid + 256 * i;
+                *reinterpret_cast<v4f*>(dt + (e >> 3) * 32 + 4 * (e & 7)) = dr[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 32; ++i) dt[tid + 256 * i] = dr[i >> 2][i & 3];
+        }
+    };
+    fetch(blockIdx.x);                                      // (the launch has no more workgroups than tiles)
+    for (int t = blockIdx.x; t < a.tiles_total; t += gridDim.x) {
+        deposit();
         __syncthreads();
+        const int tn = t + gridDim.x;
+        fetch(tn < a.tiles_total ? tn : t);                 // (a last tile fetches itself again: same loads on every path)
         // ---- this wave's two tile rows: 16 position pairs each, MT matrix instructions per pair
 #pragma unroll
         for (int rw = 0; rw < 2; ++rw) {

@@ -683,7 +683,9 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
             w.l0m = true;
             const long tiles = (long)B * ceil_div(g->rows[0], mpcnn::kL0wTy) * ceil_div(g->cols[0], mpcnn::kL0wTx);
             w.tiles_total = (int)tiles;
-            w.chunks = (int)std::min<long>(tiles, 3L * kNumCU);
+            // two workgroups per compute unit are resident with the largest filter banks (140 registers):
+            // a third, waiting its turn, would walk its tiles alone at the end
+            w.chunks = (int)std::min<long>(tiles, 2L * kNumCU);
             w.plen = l0.p_len;
             if (tiles < (1l << 30)) {
                 g->wgrad[0] = w;
