@@ -87,7 +87,8 @@ typedef struct {
  * at the end; C or MP after an FC), EUNSUPPORTED (a pool with k*k > 255; more than 16 classes).
  * Every legal net is accepted with either storage type; layers whose shape the matrix-core and
  * fused kernels do not take (channel counts that are not multiples of 4, fewer than 8 channels,
- * rectangular pools, class layers with more than 4 classes or 256 inputs) run on plain kernels.
+ * class layers with more than 4 classes or 256 inputs) run on plain kernels; layers behind a
+ * rectangular pool multiply on the fp32 matrix instruction with either storage type.
  */
 mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers_host, int n_layers, int in_channels,
                               int patch, mpcnn_dtype dtype, mpcnn_net** out);

@@ -171,15 +171,15 @@ __device__ __forceinline__ void store_quads(T* p, const v4f (&v)[Q])
 }
 
 // a2, 4 Q channels per thread (C % 4Q == 0; Q = 2 with bf16 storage keeps the accesses 128 bits
-// wide - these kernels run at a fixed rate of elements, not of bytes): O = max over the p*p taps
-// d apart, code = tap of the FIRST maximum in row-major (u,v) order (strict > while scanning),
-// 4 packed codes per quad.  RowGrid.C4 counts the threads' channel groups.
+// wide - these kernels run at a fixed rate of elements, not of bytes): O = max over the p x p2 taps
+// (rows x columns) d rows / d2 columns apart, code = tap of the FIRST maximum in row-major (u,v)
+// order (strict > while scanning), 4 packed codes per quad.  RowGrid.C4 counts the threads' channel groups.
 template <typename T, int Q>
 __global__ __launch_bounds__(256) void maxfilter_fwd4_kernel(const T* __restrict__ A,
                                                              T* __restrict__ O,
                                                              uint8_t* __restrict__ code, RowGrid g,
                                                              int Hi, int Wi, int C, int Ho, int Wo,
-                                                             int p, int d)
+                                                             int p, int p2, int d, int d2)
 {
     int b, y, x, c4;
     if (!rg_locate(g, Wo, &b, &y, &x, &c4)) return;
@@ -193,10 +193,10 @@ __global__ __launch_bounds__(256) void maxfilter_fwd4_kernel(const T* __restrict
 #pragma unroll
         for (int z = 0; z < 4; ++z) bi[q][z] = 0;
     for (int u = 0; u < p; ++u)
-        for (int v = (u == 0 ? 1 : 0); v < p; ++v) {
+        for (int v = (u == 0 ? 1 : 0); v < p2; ++v) {
             v4f a[Q];
-            load_quads<Q>(base + ((long)u * d * Wi + v * d) * C, a);
-            const uint32_t t = u * p + v;
+            load_quads<Q>(base + ((long)u * d * Wi + v * d2) * C, a);
+            const uint32_t t = u * p2 + v;
 #pragma unroll
             for (int q = 0; q < Q; ++q)
 #pragma unroll
@@ -301,7 +301,7 @@ __global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const T* __restrict
                                                              const T* __restrict__ A,
                                                              T* __restrict__ dA, RowGrid g,
                                                              int Hi, int Wi, int C, int Ho, int Wo,
-                                                             int p, int d, int logistic)
+                                                             int p, int p2, int d, int d2, int logistic)
 {
     int b, y, x, c4;
     if (!rg_locate(g, Wi, &b, &y, &x, &c4)) return;
@@ -312,8 +312,8 @@ __global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const T* __restrict
     for (int u = 0; u < p; ++u) {
         const int yy = y - u * d;
         if (yy < 0 || yy >= Ho) continue;
-        for (int v = 0; v < p; ++v) {
-            const int xx = x - v * d;
+        for (int v = 0; v < p2; ++v) {
+            const int xx = x - v * d2;
             if (xx < 0 || xx >= Wo) continue;
             const long s = (((long)b * Ho + yy) * Wo + xx) * C + 4 * Q * c4;
             uint32_t cd[Q];
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(256) void maxfilter_bwd4_kernel(const T* __restrict
             }
             v4f gr[Q];
             load_quads<Q>(dO + s, gr);
-            const uint32_t t = u * p + v;
+            const uint32_t t = u * p2 + v;
 #pragma unroll
             for (int q = 0; q < Q; ++q)
 #pragma unroll

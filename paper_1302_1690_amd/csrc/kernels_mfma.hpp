@@ -37,8 +37,9 @@ struct ConvArgs {
     void* out;           // [B][Ho][Wo][Co]
     int B, Hi, Wi, Cr, CrPad;   // CrPad: Cr rounded up to a multiple of 16
     int Ho, Wo, Co, CoPad;
-    int k, d;
-    int origin;          // halo origin in fragment units relative to the tile: 0 forward, -(k-1) dgrad
+    int k, d;            // filter rows and the spacing of rows
+    int k2, d2;          // filter columns and the spacing of columns (they differ from k, d behind a rectangular pool)
+    int origin, origin2; // halo origin (rows, columns) in fragment units relative to the tile: 0 forward, -(k-1), -(k2-1) dgrad
     int Ty, Tx, nty, ntx;
     int mode;
     int logistic;        // squashing function of the Tanh modes: 0 tanh, 1 logistic
@@ -88,15 +89,15 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
     int bid = blockIdx.x;
     const int txi = bid % a.ntx; bid /= a.ntx;
     const int tyi = bid % a.nty; bid /= a.nty;
-    const int rx = bid % a.d; bid /= a.d;
+    const int rx = bid % a.d2; bid /= a.d2;
     const int ry = bid % a.d;
     const int b = bid / a.d;
     const int fh = ry < a.Ho ? (a.Ho - ry + a.d - 1) / a.d : 0;  // extent of this residue class
-    const int fw = rx < a.Wo ? (a.Wo - rx + a.d - 1) / a.d : 0;
+    const int fw = rx < a.Wo ? (a.Wo - rx + a.d2 - 1) / a.d2 : 0;
     const int ty0 = tyi * a.Ty, tx0 = txi * a.Tx;
     if (ty0 >= fh || tx0 >= fw) return;  // uniform for the workgroup
 
-    const int hw = a.Tx + a.k - 1, hh = a.Ty + a.k - 1;
+    const int hw = a.Tx + a.k2 - 1, hh = a.Ty + a.k - 1;
     const int cq = a.CrPad / CU;
     const int Cs4 = cq + 1;              // pitch of one halo position in 128-bit units (+1: bank spread)
     const int ot0 = blockIdx.y * OT;
@@ -118,8 +119,8 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
                 if (it < total) {
                     const int pos = it / cq, q = it - pos * cq;
                     const int ha = pos / hw, hb = pos - ha * hw;
-                    const int fy = ty0 + ha + a.origin, fx = tx0 + hb + a.origin;
-                    const int iy = fy * a.d + ry, ix = fx * a.d + rx;
+                    const int fy = ty0 + ha + a.origin, fx = tx0 + hb + a.origin2;
+                    const int iy = fy * a.d + ry, ix = fx * a.d2 + rx;
                     dst[u] = pos * Cs4 + q;
                     if (fy >= 0 && fx >= 0 && iy < a.Hi && ix < a.Wi && CU * q < a.Cr) {
                         const T* src = in_t + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + CU * q;
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
     }
 
     const int nch = a.CrPad / (CU * G);
-    const int steps = a.k * a.k * nch;
+    const int steps = a.k * a.k2 * nch;
     const int t0 = steps * wave / NW, t1 = steps * (wave + 1) / NW;
     const int lane_w = lg * a.CoPad + W * ot0 + lt;   // this lane's offset inside one step of the pack
 
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
 
     // step t = tap * nch + chunk; the running tap offset avoids divisions
     int tap = t0 / nch, chunk = t0 - tap * nch;
-    int ta = tap / a.k, tb = tap - ta * a.k;
+    int ta = tap / a.k2, tb = tap - ta * a.k2;
     // Operands are fetched one step ahead into one of two register sets (A, B) that the loop
     // alternates between, so no register is copied and the loop holds next to no vector-ALU
     // work: on this chip such instructions are not overlapped with the MFMAs of the same
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
         const int soff = (ta * hw + tb) * Cs4 + G * chunk;
 #pragma unroll
         for (int p = 0; p < PT; ++p) ar[p] = lds4[lbase[p] + soff];
-        if (++chunk == nch) { chunk = 0; if (++tb == a.k) { tb = 0; ++ta; } }
+        if (++chunk == nch) { chunk = 0; if (++tb == a.k2) { tb = 0; ++ta; } }
     };
     auto mfmas = [&](const v4f (&wr)[OT], const v4f (&ar)[PT]) {
 #pragma unroll
@@ -243,7 +244,7 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
         const int ty = m / a.Tx, tx = m - ty * a.Tx;
         const int fy = ty0 + ty, fx = tx0 + tx;
         const bool pos_ok = ty < a.Ty && fy < fh && fx < fw;
-        const long pos_off = (((long)b * a.Ho + (fy * a.d + ry)) * a.Wo + (fx * a.d + rx)) * a.Co;
+        const long pos_off = (((long)b * a.Ho + (fy * a.d + ry)) * a.Wo + (fx * a.d2 + rx)) * a.Co;
         // all LDS reads (and, for the data gradient, the activation loads) of this thread's
         // items are issued before the first is used, so their latencies overlap
         v4f part[NIT][NW], yv[NIT];
@@ -315,15 +316,15 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
     int bid = blockIdx.x;
     const int txi = bid % a.ntx; bid /= a.ntx;
     const int tyi = bid % a.nty; bid /= a.nty;
-    const int rx = bid % a.d; bid /= a.d;
+    const int rx = bid % a.d2; bid /= a.d2;
     const int ry = bid % a.d;
     const int b = bid / a.d;
     const int fh = ry < a.Ho ? (a.Ho - ry + a.d - 1) / a.d : 0;  // extent of this residue class
-    const int fw = rx < a.Wo ? (a.Wo - rx + a.d - 1) / a.d : 0;
+    const int fw = rx < a.Wo ? (a.Wo - rx + a.d2 - 1) / a.d2 : 0;
     const int ty0 = tyi * a.Ty, tx0 = txi * a.Tx;
     if (ty0 >= fh || tx0 >= fw) return;  // uniform for the workgroup
 
-    const int hw = a.Tx + a.k - 1, hh = a.Ty + a.k - 1;
+    const int hw = a.Tx + a.k2 - 1, hh = a.Ty + a.k - 1;
     const int cq = a.CrPad / 4;
     const int Cs4 = cq + 1;              // pitch of one halo position in 128-bit units (+1: bank spread)
     const int oc0 = W * (blockIdx.y * OT + wo);   // first channel of this wave's tile
@@ -344,8 +345,8 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
                 if (it < total) {
                     const int pos = it / cq, q = it - pos * cq;
                     const int ha = pos / hw, hb = pos - ha * hw;
-                    const int fy = ty0 + ha + a.origin, fx = tx0 + hb + a.origin;
-                    const int iy = fy * a.d + ry, ix = fx * a.d + rx;
+                    const int fy = ty0 + ha + a.origin, fx = tx0 + hb + a.origin2;
+                    const int iy = fy * a.d + ry, ix = fx * a.d2 + rx;
                     dst[u] = pos * Cs4 + q;
                     if (fy >= 0 && fx >= 0 && iy < a.Hi && ix < a.Wi && 4 * q < a.Cr)
                         v[u] = load4(in_t + (((long)b * a.Hi + iy) * a.Wi + ix) * a.Cr + 4 * q);
@@ -381,7 +382,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
     }
 
     const int nch = a.CrPad / (4 * G);
-    const int steps = a.k * a.k * nch;
+    const int steps = a.k * a.k2 * nch;
     const int lane_w = lg * a.CoPad + oc0 + lt;   // this lane's offset inside one step of the pack
 
     { float agpr_hint = 0.f; asm volatile("" : "+a"(agpr_hint)); }
@@ -402,7 +403,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
 #pragma unroll
         for (int p = 0; p < MP; ++p) ar[i][p] = lds4[lbase[p] + soff];
         ++tf;
-        if (++chunk == nch) { chunk = 0; if (++tb == a.k) { tb = 0; ++ta; } }
+        if (++chunk == nch) { chunk = 0; if (++tb == a.k2) { tb = 0; ++ta; } }
     };
     // The first D fetches are issued on every path (a reduction shorter than D steps fetches step
     // 0 again into the slots it does not use): with a fetch count that depended on a branch the
@@ -416,7 +417,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
         for (int p = 0; p < MP; ++p) ar[i][p] = lds4[lbase[p] + soff];
         if (real) {
             ++tf;
-            if (++chunk == nch) { chunk = 0; if (++tb == a.k) { tb = 0; ++ta; } }
+            if (++chunk == nch) { chunk = 0; if (++tb == a.k2) { tb = 0; ++ta; } }
         }
     };
     auto mfmas = [&](int i) {
@@ -447,7 +448,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
         const int ty = m / a.Tx, tx = m - ty * a.Tx;
         const int fy = ty0 + ty, fx = tx0 + tx;
         const bool pos_ok = ty < a.Ty && fy < fh && fx < fw;
-        const long pos_off = (((long)b * a.Ho + (fy * a.d + ry)) * a.Wo + (fx * a.d + rx)) * a.Co;
+        const long pos_off = (((long)b * a.Ho + (fy * a.d + ry)) * a.Wo + (fx * a.d2 + rx)) * a.Co;
         v4f yv[4];
 #pragma unroll
         for (int n = 0; n < 4; ++n) {

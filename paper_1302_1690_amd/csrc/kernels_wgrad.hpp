@@ -42,7 +42,8 @@ struct WgradArgs {
     float* partial;      // [slabs][Mt*Nt result tiles][4][64 lanes][4] then [Nt*32] bias sums
     int B, Hi, Wi, Ci;
     int Ho, Wo, Co;
-    int k, d;
+    int k, d;              // filter rows and the spacing of rows
+    int k2, d2;            // filter columns and the spacing of columns (they differ from k, d behind a rectangular pool)
     int Tx, TxP;           // tile = 4 rows x Tx columns of one residue class; TxP = Tx rounded up to 4
     int nty, ntx;
     int tiles_total, tiles_per_slab;
@@ -50,7 +51,7 @@ struct WgradArgs {
     int wm, wn, wk;        // multiplying waves along result rows, result columns, tile rows (wm*wn*wk = 4)
     int mw;                // row tiles per wave (<= kWgMaxTiles); blockIdx.y covers wm*mw of them
     // ceil(2^32 / x): n / x == umulhi(n, magic) for n * x < 2^32, x > 1
-    unsigned mg_cq, mg_hwp, mg_txp, mg_ci, mg_k, mg_ntx, mg_nty, mg_d;
+    unsigned mg_cq, mg_hwp, mg_txp, mg_ci, mg_k2, mg_ntx, mg_nty, mg_d, mg_d2;
 };
 
 __device__ __forceinline__ unsigned magic_div(unsigned n, unsigned magic, unsigned x)
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
     const int midx = __builtin_amdgcn_readfirstlane((wave / wn) % a.wm);
     const int kidx = __builtin_amdgcn_readfirstlane(wave / (wn * a.wm));
     const int rpw = a.wk == 4 ? 1 : (a.wk == 2 ? 2 : 4);   // tile rows per wave
-    const int hwp = a.TxP + a.k - 1;            // halo row pitch
+    const int hwp = a.TxP + a.k2 - 1;           // halo row pitch
     const int hh = 4 + a.k - 1;
     const int QP = 4 * ((hh * hwp) | 1);        // pitch of a channel quad's plane in the halo (floats; odd number of positions)
     const int cq = (a.Ci + 3) >> 2;
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
     const int buf_f = dt_f + cq * QP;
     const int trash_f = 2 * buf_f + 16;         // 16 bytes that nobody reads, behind the slack of the second buffer
 
-    const int rows_total = a.k * a.k * a.Ci;
+    const int rows_total = a.k * a.k2 * a.Ci;
     // ---- a multiplying wave's result tiles: rows 32*(mt0 + p), p < np; columns 32*nt
     const int mt0 = blockIdx.y * (a.wm * a.mw) + midx * a.mw;
     int np = a.Mt - mt0;
@@ -116,14 +117,14 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
         const int txi = bid - qd * a.ntx; bid = qd;
         qd = magic_div(bid, a.mg_nty, a.nty);
         const int tyi = bid - qd * a.nty; bid = qd;
-        qd = magic_div(bid, a.mg_d, a.d);
-        t.rx = bid - qd * a.d; bid = qd;
+        qd = magic_div(bid, a.mg_d2, a.d2);
+        t.rx = bid - qd * a.d2; bid = qd;
         qd = magic_div(bid, a.mg_d, a.d);
         t.ry = bid - qd * a.d;
         t.b = qd;
         // extent of this residue class
         const int fh = t.ry < a.Ho ? (int)magic_div(a.Ho - t.ry + a.d - 1, a.mg_d, a.d) : 0;
-        const int fw = t.rx < a.Wo ? (int)magic_div(a.Wo - t.rx + a.d - 1, a.mg_d, a.d) : 0;
+        const int fw = t.rx < a.Wo ? (int)magic_div(a.Wo - t.rx + a.d2 - 1, a.mg_d2, a.d2) : 0;
         t.ty0 = tyi * 4; t.tx0 = txi * a.Tx;
         t.rows = fh - t.ty0; t.cols = fw - t.tx0;
         return t;
@@ -160,9 +161,9 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
             if (it < (unsigned)h_items) {
                 const unsigned pos = magic_div(it, a.mg_cq, cq), q = it - pos * cq;
                 const unsigned ha = magic_div(pos, a.mg_hwp, hwp), hb = pos - ha * hwp;
-                h_yx[u] = ((ha * a.d) << 16) | (hb * a.d);
+                h_yx[u] = ((ha * a.d) << 16) | (hb * a.d2);
                 h_dst[u] = (int)((4 * q) << 20 | (dt_f + q * QP + 4 * (ha * hwp + hb)));
-                h_off[u] = ((ha * a.d) * a.Wi + hb * a.d) * a.Ci + 4 * q;
+                h_off[u] = ((ha * a.d) * a.Wi + hb * a.d2) * a.Ci + 4 * q;
             }
         }
 #pragma unroll
@@ -175,7 +176,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                 const int oc = 32 * blockIdx.z * wn + 4 * q;
                 d_tyx[u] = (ty << 16) | tx;
                 d_dst[u] = (int)((q >> 3) * OB + 4 * (q & 7) + ty * RB + tx * 32);
-                if (tx < (unsigned)a.Tx && oc < a.Co) d_rel[u] = (int)((ty * a.d * a.Wo + tx * a.d) * a.Co) + oc;
+                if (tx < (unsigned)a.Tx && oc < a.Co) d_rel[u] = (int)((ty * a.d * a.Wo + tx * a.d2) * a.Co) + oc;
                 else {
                     // never inside: zero in both buffers now, and from here on the item's store
                     // goes to the unread bytes
@@ -186,12 +187,12 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                 }
             }
         }
-        const int halo_h = (hh - 1) * a.d, halo_w = (hwp - 1) * a.d;   // reach of the halo below / right of its first element
+        const int halo_h = (hh - 1) * a.d, halo_w = (hwp - 1) * a.d2;   // reach of the halo below / right of its first element
         auto stage = [&](int tile, float* buf) {
             const TileGeom t = decode(tile);
             const T* in_b = static_cast<const T*>(a.in) + (long)t.b * a.Hi * a.Wi * a.Ci;
             const T* dy_b = static_cast<const T*>(a.dY) + (long)t.b * a.Ho * a.Wo * a.Co;
-            const int y0 = t.ty0 * a.d + t.ry, x0 = t.tx0 * a.d + t.rx;
+            const int y0 = t.ty0 * a.d + t.ry, x0 = t.tx0 * a.d2 + t.rx;
             const int dbase = (y0 * a.Wo + x0) * a.Co;
             v4f hr[HL], dr[DL];
             unsigned okmask = 0;
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
         unsigned o = dt_f + 4 * lk;
         if (p < np && row < (unsigned)rows_total) {
             const unsigned tap = magic_div(row, a.mg_ci, a.Ci), c = row - tap * a.Ci;
-            const unsigned ta = magic_div(tap, a.mg_k, a.k), tb = tap - ta * a.k;
+            const unsigned ta = magic_div(tap, a.mg_k2, a.k2), tb = tap - ta * a.k2;
             o += (c >> 2) * QP + (c & 3) + 4 * (ta * hwp + tb);
         }
         aoff[p] = 4u * o;

@@ -262,7 +262,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_bm_kernel(WgradArgs a)
             unsigned o = g.ones_e;
             if (row < (unsigned)rows_total) {
                 const unsigned tap = magic_div(row, a.mg_ci, a.Ci), c = row - tap * a.Ci;
-                const unsigned ta = magic_div(tap, a.mg_k, a.k), tb = tap - ta * a.k;
+                const unsigned ta = magic_div(tap, a.mg_k2, a.k2), tb = tap - ta * a.k2;   // (square filters only: k2 == k)
                 o = dt_e + c * HPb + (c >> 3) * 8 + ta * hwp + tb;
             }
             ap[p] = lds_base + 2u * (o + 8 * lk);

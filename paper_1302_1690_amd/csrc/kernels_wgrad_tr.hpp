@@ -249,7 +249,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_tr_kernel(WgradArgs a)
             arow[p] = 0;
             if (row < (unsigned)rows_total) {
                 const unsigned tap = magic_div(row, a.mg_ci, a.Ci), c = row - tap * a.Ci;
-                const unsigned ta = magic_div(tap, a.mg_k, a.k), tb = tap - ta * a.k;
+                const unsigned ta = magic_div(tap, a.mg_k2, a.k2), tb = tap - ta * a.k2;   // (square filters only: k2 == k)
                 o = g.halo_b + ((c >> 5) * g.hplane + ta * hwp + tb) * 64;
                 arow[p] = 64u * hwp;
             }

@@ -104,7 +104,7 @@ struct Layer {
     int drop = 0; // MP: trailing rows / columns of the patch-level map that no window covers (side mod k)
     // columns, where they differ from the rows (a rectangular pool, and every layer after it):
     int k2 = 0, dil2 = 0, drop2 = 0;
-    bool rect = false;   // k2 != k or dil2 != dil: only the direct kernels take such a layer
+    bool rect = false;   // k2 != k or dil2 != dil: the fp32 matrix instruction's kernels and the direct kernels take such a layer
     bool tanh_out;
     size_t p_off; // offset of this layer's [(k*k*cin + 1) x cout] block in the parameter buffer
     size_t p_len;
@@ -273,13 +273,13 @@ struct ProfScope {
 // ------------------------------------------------------------------ planning
 // Ty x Tx tile (<= max_pos positions) of a residue class with extents fh x fw: fewest
 // tiles first, then the smallest halo; the halo must fit `lds_cap`.
-bool choose_tile(int fh, int fw, int max_pos, int k, size_t pitch_bytes, size_t extra_bytes,
+bool choose_tile(int fh, int fw, int max_pos, int k, int k2, size_t pitch_bytes, size_t extra_bytes,
                  size_t lds_cap, int* Ty, int* Tx)
 {
     long best_tiles = -1, best_halo = 0;
     for (int ty = 1; ty <= std::min(fh, max_pos); ++ty) {
         for (int tx = 1; tx <= std::min(fw, max_pos / ty); ++tx) {
-            long halo = (long)(ty + k - 1) * (tx + k - 1);
+            long halo = (long)(ty + k - 1) * (tx + k2 - 1);
             if ((size_t)halo * pitch_bytes + extra_bytes > lds_cap) continue;
             long tiles = (long)ceil_div(fh, ty) * ceil_div(fw, tx);
             if (best_tiles < 0 || tiles < best_tiles || (tiles == best_tiles && halo < best_halo)) {
@@ -290,20 +290,21 @@ bool choose_tile(int fh, int fw, int max_pos, int k, size_t pitch_bytes, size_t 
     return best_tiles > 0;
 }
 
-// Tile plan of conv_mfma_kernel for a map of out_r x out_c positions at tap spacing d.
-TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, const ChanTiling& ct, bool bm,
+// Tile plan of the convolution kernels for a map of out_r x out_c positions, a k x k2 filter (rows x columns)
+// with taps d rows / d2 columns apart (k2 != k or d2 != d: a rectangular pool, or a layer behind one).
+TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int d2, int k, int k2, int rpad, const ChanTiling& ct, bool bm,
                          int hint_pt = 0, int hint_mp = 0)
 {
     TilePlan best;
     double best_cost = 0;
-    const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
+    const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d2);
     const size_t pitch = bm ? 16 * (size_t)(rpad / 8 + 1) : sizeof(float) * (rpad + 4);   // one halo position in LDS
     if (!bm && ct.W == 32) {
         // conv_ts_kernel: 32*PT positions x 32*OT channels, OT*PT/MP waves.  Cost of the busiest CU:
         // its workgroups' matrix instructions one after the other, plus, once per round of
         // co-resident workgroups, what is not hidden behind another's multiplications
         // (staging the halo at ~8 bytes per cycle, a memory round trip, the stores).
-        const int steps = k * k * (rpad / 8);
+        const int steps = k * k2 * (rpad / 8);
         for (int PT : {2, 4, 8})
             for (int MP : {1, 2}) {
                 const int NW = ct.OT * PT / MP;
@@ -314,10 +315,10 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, co
                 const double t_mul1 = (double)steps * 4 * ct.OT * PT * 64 / 4 * (MP == 2 ? 1.0 : 1.12);
                 for (int ty = 1; ty <= std::min(fh, 32 * PT); ++ty)
                     for (int tx = 1; tx <= std::min(fw, 32 * PT / ty); ++tx) {
-                        const size_t lds = std::max((size_t)(ty + k - 1) * (tx + k - 1) * pitch, (size_t)1024);
+                        const size_t lds = std::max((size_t)(ty + k - 1) * (tx + k2 - 1) * pitch, (size_t)1024);
                         if (lds > (size_t)150 * 1024) break;
                         const int nty = ceil_div(fh, ty), ntx = ceil_div(fw, tx);
-                        const double wgs = (double)B * d * d * nty * ntx * ct.split;
+                        const double wgs = (double)B * d * d2 * nty * ntx * ct.split;
                         const int together = (int)std::max<size_t>(1, std::min<size_t>(16 / NW, (size_t)(160 * 1024) / lds));
                         const double per_cu = std::ceil(wgs / kNumCU);
                         // fewer than 8 waves on the CU leave SIMDs idle in every wait
@@ -377,20 +378,20 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int k, int rpad, co
         for (int NW : {4, 8}) {
             TilePlan p;
             p.PT = PT; p.NW = NW;
-            if (!choose_tile(fh, fw, ct.W * PT, k, pitch, 0, kConvLdsCap, &p.Ty, &p.Tx)) continue;
+            if (!choose_tile(fh, fw, ct.W * PT, k, k2, pitch, 0, kConvLdsCap, &p.Ty, &p.Tx)) continue;
             p.nty = ceil_div(fh, p.Ty); p.ntx = ceil_div(fw, p.Tx);
-            size_t halo = (size_t)(p.Ty + k - 1) * (p.Tx + k - 1) * pitch;
+            size_t halo = (size_t)(p.Ty + k - 1) * (p.Tx + k2 - 1) * pitch;
             size_t part = (size_t)NW * ct.OT * (ct.W / 4) * (ct.W + 1) * 4 * sizeof(float);
             p.lds = std::max(halo, part);
             if (p.lds > 150 * 1024) continue;
-            if (NW == 8 && k * k * (rpad / (256 / ct.W)) < 16) continue;   // too few reduction steps to split 8 ways
+            if (NW == 8 && k * k2 * (rpad / (256 / ct.W)) < 16) continue;   // too few reduction steps to split 8 ways
             p.ok = true;
             // Measured: two co-resident 4-wave workgroups with large tiles (LDS allows no more than
             // two) only overlap well once their phases have drifted apart, i.e. over many rounds;
             // for a few rounds one 8-wave workgroup per CU is faster.  Small tiles: 4 waves.
-            const double wgs = (double)B * d * d * p.nty * p.ntx * ct.split;
+            const double wgs = (double)B * d * d2 * p.nty * p.ntx * ct.split;
             const double per_cu = wgs / kNumCU;
-            const int steps = k * k * (rpad / (256 / ct.W));
+            const int steps = k * k2 * (rpad / (256 / ct.W));
             const bool want8 = ct.W == 32 && ct.OT * PT >= 4 && steps >= 64 && per_cu < 8;
             if ((NW == 8) != want8) continue;
             const double rounds = NW == 8 ? std::ceil(per_cu) : std::ceil(per_cu / 2);
@@ -406,11 +407,13 @@ unsigned magic_of(unsigned x) { return x <= 1 ? 0u : (unsigned)(((1ull << 32) + 
 WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int out_c, bool bm)
 {
     WgradPlan w;
-    const int d = ly.dil, k = ly.k;
-    const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d);
+    const int d = ly.dil, k = ly.k, d2 = ly.dil2, k2 = ly.k2;   // rows; columns
+    const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d2);
     // the kernel forms element offsets inside one image in 32 bits
     const bool fits32 = (size_t)in_r * in_c * ly.cin < (1ull << 31) &&
                         (size_t)out_r * out_c * ly.cout < (1ull << 31) && (k + 3) * d < 65536;
+    // the bf16 instruction's kernels take square filters at one spacing only
+    bm = bm && !ly.rect;
     // the bf16 instruction's kernel gives a wave pairs of column tiles: not for 32 maps or fewer
     // - except for an image layer's few channels, where that kernel, half of its instructions wasted,
     // is still ahead of the fp32 instruction's (7 x 7 filters on 2 x 3 x 2048 x 2048, 32 maps: 1.51 -> 1.34 ms)
@@ -518,7 +521,7 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
     if (ly.wgrad_mfma && fits32) {
         // split of the four waves over result rows / columns / tile rows: least padded work,
         // then fewest workgroup groups (each group stages the tiles again)
-        const int Mt = ceil_div(k * k * ly.cin, 32), Nt = ceil_div(ly.cout, 32);
+        const int Mt = ceil_div(k * k2 * ly.cin, 32), Nt = ceil_div(ly.cout, 32);
         long best_pad = -1; int best_groups = 0;
         for (int wn : {4, 2, 1})
             for (int wm : {1, 2, 4}) {
@@ -548,14 +551,14 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
         // Staging time of a tile (estimate used to compare the two instances): one trip to
         // memory plus a few hundred cycles per round of 256 items.
         auto tile_time = [&](int txp, bool with_load) {
-            const double t_load = 3000.0 + 6.0 * 64.0 * ceil_div(hh * (txp + k - 1) * cq + 4 * txp * 8 * w.wn, 256);
+            const double t_load = 3000.0 + 6.0 * 64.0 * ceil_div(hh * (txp + k2 - 1) * cq + 4 * txp * 8 * w.wn, 256);
             return (with_load ? std::max(txp * col_ticks, t_load) : txp * col_ticks) + 1500.0;
         };
         struct Pick { double cost = -1; int Tx = 0, TxP = 0; size_t lds = 0; long tps = 0; };
         auto pass = [&](int hl, bool with_load) {
             Pick pk;
             for (int tx = 1; tx <= fw; ++tx) {
-                const int txp = ceil_div(tx, 4) * 4, hwp = txp + k - 1;
+                const int txp = ceil_div(tx, 4) * 4, hwp = txp + k2 - 1;
                 const size_t buf = (size_t)4 * w.wn * (txp * 32 + 32) + (size_t)4 * cq * ((hh * hwp) | 1);
                 size_t lds = 2 * buf * sizeof(float) + 128;  // slack: the operand prefetch runs one chunk ahead; 16 unread bytes behind it
                 if (w.wk > 1) lds = std::max(lds, (size_t)2 * w.mw * 4096);
@@ -563,8 +566,8 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
                 if (hh * hwp * cq > hl * 256 || 4 * txp * 8 * w.wn > mpcnn::kWgStageD * 256 || lds > kWgradLdsCap)
                     continue;
                 const int ntx = ceil_div(fw, tx);
-                const long tiles = (long)B * d * d * ceil_div(fh, 4) * ntx;
-                if (tiles * std::max(std::max(ntx, ceil_div(fh, 4)), d) >= (1ll << 31)) continue;
+                const long tiles = (long)B * d * d2 * ceil_div(fh, 4) * ntx;
+                if (tiles * std::max(std::max(ntx, ceil_div(fh, 4)), std::max(d, d2)) >= (1ll << 31) || (long)hwp * d2 >= 65536) continue;
                 const long tps = (tiles + target - 1) / target;
                 const double cost = (double)tps * tile_time(txp, with_load);
                 if (pk.cost < 0 || cost <= pk.cost) { pk.cost = cost; pk.Tx = tx; pk.TxP = txp; pk.lds = lds; pk.tps = tps; }
@@ -583,7 +586,7 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
         w.Tx = pk.Tx; w.TxP = pk.TxP; w.lds = pk.lds;
         if (best >= 0) {
             w.nty = ceil_div(fh, 4); w.ntx = ceil_div(fw, w.Tx);
-            w.tiles_total = B * d * d * w.nty * w.ntx;
+            w.tiles_total = B * d * d2 * w.nty * w.ntx;
             w.tiles_per_slab = ceil_div(w.tiles_total, target);
             w.slabs = ceil_div(w.tiles_total, w.tiles_per_slab);
             w.ok = true;
@@ -639,13 +642,13 @@ bool make_geom(const mpcnn_net* net, int B, int H, int W, bool training, Geom* g
         size_t bytes = es * (size_t)B * r * c * ly.cout;
         max_act = std::max(max_act, bytes);
         if (ly.kind == MPCNN_MP) continue;
-        if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.k, ly.fwd_rpad, ly.fwd_ct, ly.fwd_bm, net->hint_pt, net->hint_mp);
+        if (ly.fwd_mfma) g->fwd[l] = plan_conv_tiles(B, r, c, ly.dil, ly.dil2, ly.k, ly.k2, ly.fwd_rpad, ly.fwd_ct, ly.fwd_bm, net->hint_pt, net->hint_mp);
         if (training && ly.class_fused) {
             g->partial_n[l] = class_blocks(net, (long)B * r * c);
             g->partial_len[l] = ly.p_len;
         } else if (training) {
             if (ly.dgrad_mfma && l > 0)
-                g->dgrad[l] = plan_conv_tiles(B, in_r, in_c, ly.dil, ly.k, ly.dgrad_rpad, ly.dgrad_ct, ly.dgrad_bm, net->hint_pt, net->hint_mp);
+                g->dgrad[l] = plan_conv_tiles(B, in_r, in_c, ly.dil, ly.dil2, ly.k, ly.k2, ly.dgrad_rpad, ly.dgrad_ct, ly.dgrad_bm, net->hint_pt, net->hint_mp);
             g->wgrad[l] = plan_wgrad(ly, B, in_r, in_c, r, c, net->bf16);
             const WgradPlan& w = g->wgrad[l];
             g->partial_n[l] = w.ok ? w.slabs : w.chunks;
@@ -914,22 +917,22 @@ mpcnn_status refresh_packs(mpcnn_net* net, hipStream_t st)
         if (ly.fwd_mfma && ly.fwd_bm)
             LAUNCH("pack_weights", l, 0, 0, 6.0 * ly.fwd_pack_len,
                    mpcnn::pack_weights_bf16_kernel<<<grid_for((long)ly.fwd_pack_len), 256, 0, st>>>(
-                       Wc, (mpcnn::bf16*)(net->d_packs + ly.fwd_pack_off), ly.k * ly.k, ly.cin, ly.cout,
+                       Wc, (mpcnn::bf16*)(net->d_packs + ly.fwd_pack_off), ly.k * ly.k2, ly.cin, ly.cout,
                        ly.fwd_rpad, ly.fwd_ct.pad, 0));
         else if (ly.fwd_mfma)
             LAUNCH("pack_weights", l, 0, 0, 8.0 * ly.fwd_pack_len,
                    mpcnn::pack_weights_kernel<<<grid_for((long)ly.fwd_pack_len), 256, 0, st>>>(
-                       Wc, net->d_packs + ly.fwd_pack_off, ly.k * ly.k, ly.cin, ly.cout, ly.fwd_rpad,
+                       Wc, net->d_packs + ly.fwd_pack_off, ly.k * ly.k2, ly.cin, ly.cout, ly.fwd_rpad,
                        ly.fwd_ct.pad, 64 / ly.fwd_ct.W, 0));
         if (ly.dgrad_mfma && l > 0 && ly.dgrad_bm)
             LAUNCH("pack_weights", l, 0, 0, 6.0 * ly.dgrad_pack_len,
                    mpcnn::pack_weights_bf16_kernel<<<grid_for((long)ly.dgrad_pack_len), 256, 0, st>>>(
-                       Wc, (mpcnn::bf16*)(net->d_packs + ly.dgrad_pack_off), ly.k * ly.k, ly.cin, ly.cout,
+                       Wc, (mpcnn::bf16*)(net->d_packs + ly.dgrad_pack_off), ly.k * ly.k2, ly.cin, ly.cout,
                        ly.dgrad_rpad, ly.dgrad_ct.pad, 1));
         else if (ly.dgrad_mfma && l > 0)
             LAUNCH("pack_weights", l, 0, 0, 8.0 * ly.dgrad_pack_len,
                    mpcnn::pack_weights_kernel<<<grid_for((long)ly.dgrad_pack_len), 256, 0, st>>>(
-                       Wc, net->d_packs + ly.dgrad_pack_off, ly.k * ly.k, ly.cin, ly.cout,
+                       Wc, net->d_packs + ly.dgrad_pack_off, ly.k * ly.k2, ly.cin, ly.cout,
                        ly.dgrad_rpad, ly.dgrad_ct.pad, 64 / ly.dgrad_ct.W, 1));
     }
     HIP_TRY(hipGetLastError());
@@ -982,14 +985,14 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
                        (maxfilter_fwd2x2_kernel<T, kQ><<<(unsigned)(pg.gx * pg.rows), 256, 0, st>>>(
                            in, out, code, pg, Hi, Wi, ly.cout, Ho, Wo)));
-            else if (!kF32 && !ly.rect && ly.cout % 8 == 0 && row_grid(B, Ho, Wo, ly.cout / 8, ly.dil, &rg))   // bf16: 8 channels per thread (fp32: measured slower)
+            else if (!kF32 && ly.cout % 8 == 0 && row_grid(B, Ho, Wo, ly.cout / 8, ly.dil, &rg))   // bf16: 8 channels per thread (fp32: measured slower)
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
                        (maxfilter_fwd4_kernel<T, kF32 ? 1 : 2><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
-                           in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil)));
-            else if (!ly.rect && ly.cout % 4 == 0 && row_grid(B, Ho, Wo, ly.cout / 4, ly.dil, &rg))
+                           in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2)));
+            else if (ly.cout % 4 == 0 && row_grid(B, Ho, Wo, ly.cout / 4, ly.dil, &rg))
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
                        (maxfilter_fwd4_kernel<T, 1><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
-                           in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.dil)));
+                           in, out, code, rg, Hi, Wi, ly.cout, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2)));
             else
                 LAUNCH("maxfilter_fwd", l, 2, 0, n_out * (2.0 * es + (code ? 1.0 : 0.0)),
                        maxfilter_fwd_direct_kernel<T><<<grid_for(total), 256, 0, st>>>(
@@ -1023,13 +1026,13 @@ mpcnn_status run_forward(mpcnn_net* net, const Geom& g, const float* image, char
                 const TilePlan& tp = g.fwd[l];
                 ConvArgs a{};
                 a.in = in; a.wpack = (const v4f*)(net->d_packs + ly.fwd_pack_off);
-                a.bias = Wk + (size_t)ly.k * ly.k * Ci * ly.cout; a.act = nullptr; a.out = out;
+                a.bias = Wk + (size_t)ly.k * ly.k2 * Ci * ly.cout; a.act = nullptr; a.out = out;
                 a.B = B; a.Hi = Hi; a.Wi = Wi; a.Cr = Ci; a.CrPad = ly.fwd_rpad;
                 a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout; a.CoPad = ly.fwd_ct.pad;
-                a.k = ly.k; a.d = ly.dil; a.origin = 0;
+                a.k = ly.k; a.d = ly.dil; a.origin = 0; a.k2 = ly.k2; a.d2 = ly.dil2; a.origin2 = 0;
                 a.Ty = tp.Ty; a.Tx = tp.Tx; a.nty = tp.nty; a.ntx = tp.ntx;
                 a.mode = ly.tanh_out ? kFwdTanh : kFwdLinear; a.logistic = net->logistic;
-                dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
+                dim3 grid((unsigned)(B * ly.dil * ly.dil2 * tp.nty * tp.ntx), (unsigned)ly.fwd_ct.split);
                 if (ly.fwd_bm) persistent_grid(&a, &grid, ly.fwd_ct.split);
                 bool launched = false;
                 LAUNCH(ly.fwd_bm ? "conv_fwd_bm" : "conv_fwd_mfma", l, step, flops, bytes,
@@ -1153,24 +1156,24 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 cur ^= 1;
                 continue;
             }
-            const bool octs = !ly.rect && Ci % 8 == 0 && row_grid(B, Hi, Wi, Ci / 8, ly.dil, &rg);   // 8 channels per thread (measured faster in both storage types)
-            const bool quads = !ly.rect && !octs && Ci % 4 == 0 && row_grid(B, Hi, Wi, Ci / 4, ly.dil, &rg);
+            const bool octs = Ci % 8 == 0 && row_grid(B, Hi, Wi, Ci / 8, ly.dil, &rg);   // 8 channels per thread (measured faster in both storage types)
+            const bool quads = !octs && Ci % 4 == 0 && row_grid(B, Hi, Wi, Ci / 4, ly.dil, &rg);
             if (octs && below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        (maxfilter_bwd4_kernel<true, T, 2><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
-                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil, net->logistic)));
+                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic)));
             else if (octs)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        (maxfilter_bwd4_kernel<false, T, 2><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
-                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil, net->logistic)));
+                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic)));
             else if (quads && below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        (maxfilter_bwd4_kernel<true, T, 1><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
-                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil, net->logistic)));
+                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic)));
             else if (quads)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        (maxfilter_bwd4_kernel<false, T, 1><<<(unsigned)(rg.gx * rg.rows), 256, 0, st>>>(
-                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.dil, net->logistic)));
+                           dY, code, A, dA, rg, Hi, Wi, Ci, Ho, Wo, ly.k, ly.k2, ly.dil, ly.dil2, net->logistic)));
             else if (below_tanh)
                 LAUNCH("maxfilter_bwd", li, 7, 0, bytes,
                        (maxfilter_bwd_direct_kernel<true, T><<<grid_for(total), 256, 0, st>>>(
@@ -1189,11 +1192,11 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 WgradArgs a{};
                 a.in = A; a.dY = dY; a.partial = partial;
                 a.B = B; a.Hi = Hi; a.Wi = Wi; a.Ci = Ci;
-                a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout; a.k = ly.k; a.d = ly.dil;
+                a.Ho = Ho; a.Wo = Wo; a.Co = ly.cout; a.k = ly.k; a.d = ly.dil; a.k2 = ly.k2; a.d2 = ly.dil2;
                 a.Tx = wp.Tx; a.TxP = wp.TxP; a.nty = wp.nty; a.ntx = wp.ntx;
                 a.tiles_total = wp.tiles_total; a.tiles_per_slab = wp.tiles_per_slab;
                 a.Mt = wp.Mt; a.Nt = wp.Nt; a.wm = wp.wm; a.wn = wp.wn; a.wk = wp.wk; a.mw = wp.mw;
-                a.mg_cq = magic_of(ceil_div(Ci, 4)); a.mg_hwp = magic_of(wp.TxP + ly.k - 1);
+                a.mg_cq = magic_of(ceil_div(Ci, 4)); a.mg_hwp = magic_of(wp.TxP + ly.k2 - 1);
                 if (wp.tr) {   // items of one position x 8 channels
                     a.mg_cq = magic_of(Ci / 8);
                     a.mg_hwp = magic_of(mpcnn::tr_geom(wp.TxP / 16, ly.k, Ci, wp.wn).hwp);
@@ -1201,8 +1204,8 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                     a.mg_cq = magic_of(ceil_div(Ci, 8));
                     a.mg_hwp = magic_of(mpcnn::bm_geom(wp.TxP / 16, ly.k, Ci, wp.wn).hwp / 2);
                 }
-                a.mg_txp = magic_of(wp.TxP); a.mg_ci = magic_of(Ci); a.mg_k = magic_of(ly.k);
-                a.mg_ntx = magic_of(wp.ntx); a.mg_nty = magic_of(wp.nty); a.mg_d = magic_of(ly.dil);
+                a.mg_txp = magic_of(wp.TxP); a.mg_ci = magic_of(Ci); a.mg_k2 = magic_of(ly.k2);
+                a.mg_ntx = magic_of(wp.ntx); a.mg_nty = magic_of(wp.nty); a.mg_d = magic_of(ly.dil); a.mg_d2 = magic_of(ly.dil2);
                 dim3 grid((unsigned)wp.slabs, (unsigned)wp.gm, (unsigned)wp.gn);
                 bool launched = false;
                 if (wp.tr)
@@ -1242,10 +1245,10 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
                 a.bias = nullptr; a.act = A; a.out = dA;
                 a.B = B; a.Hi = Ho; a.Wi = Wo; a.Cr = ly.cout; a.CrPad = ly.dgrad_rpad;
                 a.Ho = Hi; a.Wo = Wi; a.Co = Ci; a.CoPad = ly.dgrad_ct.pad;
-                a.k = ly.k; a.d = ly.dil; a.origin = -(ly.k - 1);
+                a.k = ly.k; a.d = ly.dil; a.origin = -(ly.k - 1); a.k2 = ly.k2; a.d2 = ly.dil2; a.origin2 = -(ly.k2 - 1);
                 a.Ty = tp.Ty; a.Tx = tp.Tx; a.nty = tp.nty; a.ntx = tp.ntx;
                 a.mode = below_tanh ? kDgradTanh : kDgradPlain; a.logistic = net->logistic;
-                dim3 grid((unsigned)(B * ly.dil * ly.dil * tp.nty * tp.ntx), (unsigned)ly.dgrad_ct.split);
+                dim3 grid((unsigned)(B * ly.dil * ly.dil2 * tp.nty * tp.ntx), (unsigned)ly.dgrad_ct.split);
                 if (ly.dgrad_bm) persistent_grid(&a, &grid, ly.dgrad_ct.split);
                 bool launched = false;
                 LAUNCH(ly.dgrad_bm ? "conv_dgrad_bm" : "conv_dgrad_mfma", li, dstep, flops, dbytes,
@@ -1280,7 +1283,7 @@ mpcnn_status run_backward(mpcnn_net* net, const Geom& g, const float* image, cha
         const WgradPlan& wp = g.wgrad[l];
         sg.tiled = wp.ok ? (wp.bm ? 3 : 1) : 0;
         sg.items = wp.ok ? wp.Mt * wp.Nt * 256 + (wp.bm ? 0 : wp.Nt * 8) : (int)ly.p_len;
-        sg.Nt = wp.Nt; sg.rows_total = ly.k * ly.k * ly.cin; sg.Co = ly.cout;
+        sg.Nt = wp.Nt; sg.rows_total = ly.k * ly.k2 * ly.cin; sg.Co = ly.cout;
         sg.block0 = ra.total_blocks;
         ra.total_blocks += (sg.items + 63) / 64;
         rbytes += 4.0 * ((double)sg.plen * sg.n + ly.p_len);
@@ -1442,7 +1445,9 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
             }
         } else st = fail(MPCNN_EINVAL, "layer %d: unknown kind %d", l, d.kind);
         if (st != MPCNN_OK) break;
-        // rows and columns differ (a rectangular pool or anything behind one): the direct kernels
+        // rows and columns differ (a rectangular pool or anything behind one): the kernels on the fp32
+        // matrix instruction take such a layer, the bf16 instruction's kernels and the max-filter
+        // kernels with several elements per thread do not
         ly.rect = ly.k2 != ly.k || (ly.dil2 != ly.dil && (ly.k > 1 || ly.k2 > 1));
         if (ly.kind != MPCNN_MP) {
             ly.p_off = off;
@@ -1453,22 +1458,22 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
             const bool last = l == n_layers - 1;
             ly.class_fused = last && ly.k == 1 && ly.cin % 4 == 0 && ly.cin <= 256 &&
                              ly.cout >= 2 && ly.cout <= 4;
-            ly.fwd_mfma = !ly.rect && !last && ly.cin % 4 == 0 && ly.cin >= 8 && ly.cout >= 8;
-            ly.dgrad_mfma = !ly.rect && l > 0 && ly.cout % 4 == 0 && ly.cout >= 8 && ly.cin >= 8;
-            ly.wgrad_mfma = !ly.rect && !ly.class_fused;   // any square shape: gradient rows are tiled in parameter order
+            ly.fwd_mfma = !last && ly.cin % 4 == 0 && ly.cin >= 8 && ly.cout >= 8;
+            ly.dgrad_mfma = l > 0 && ly.cout % 4 == 0 && ly.cout >= 8 && ly.cin >= 8;
+            ly.wgrad_mfma = !ly.class_fused;   // any shape: gradient rows are tiled in parameter order
             // bf16 storage with channel counts that are multiples of 8: the bf16 matrix instruction
-            ly.fwd_bm = net->bf16 && ly.fwd_mfma && ly.cin % 8 == 0;
-            ly.dgrad_bm = net->bf16 && ly.dgrad_mfma && ly.cout % 8 == 0;
+            ly.fwd_bm = net->bf16 && !ly.rect && ly.fwd_mfma && ly.cin % 8 == 0;
+            ly.dgrad_bm = net->bf16 && !ly.rect && ly.dgrad_mfma && ly.cout % 8 == 0;
             if (ly.fwd_mfma) {
                 ly.fwd_ct = ly.fwd_bm ? chan_tiling_w(ly.cout, 32) : chan_tiling(ly.cout);
                 ly.fwd_rpad = ceil_div(ly.cin, 16) * 16;
-                ly.fwd_pack_len = (size_t)ly.k * ly.k * ly.fwd_rpad * ly.fwd_ct.pad;
+                ly.fwd_pack_len = (size_t)ly.k * ly.k2 * ly.fwd_rpad * ly.fwd_ct.pad;
                 ly.fwd_pack_off = pack; pack += ly.fwd_pack_len;
             }
             if (ly.dgrad_mfma) {
                 ly.dgrad_ct = ly.dgrad_bm ? chan_tiling_w(ly.cin, 32) : chan_tiling(ly.cin);
                 ly.dgrad_rpad = ceil_div(ly.cout, 16) * 16;
-                ly.dgrad_pack_len = (size_t)ly.k * ly.k * ly.dgrad_rpad * ly.dgrad_ct.pad;
+                ly.dgrad_pack_len = (size_t)ly.k * ly.k2 * ly.dgrad_rpad * ly.dgrad_ct.pad;
                 ly.dgrad_pack_off = pack; pack += ly.dgrad_pack_len;
             }
         }

@@ -504,6 +504,25 @@ def test_rectangular_pooling_windows():
     full_parity(cfg, ignore_some=True)
 
 
+def test_rectangular_pools_on_the_matrix_cores():
+    """Layers behind a rectangular pool on the matrix-instruction kernels (two spacings, filters of k x k2
+    taps; Background, layer MP): channel counts those kernels take, maps that span several tiles with ragged
+    ends, two images; fp32 storage, then bf16 storage (there on the fp32 instruction).  The plan must name no
+    plain kernel for a layer behind the first pool."""
+    # patch 27 -> 24 -> (2x3) 12x8 -> 10x6 -> (2x2) 5x3 -> FC over 5x3 (spacing 4 x 6) -> FC
+    layers = ((C, 16, 4), (MP, 0, 2, 3), (C, 32, 3), (MP, 0, 2, 2), (FC, 40, 0), (FC, 2, 0))
+    for dtype in ("f32", "bf16"):
+        cfg = wl.Workload("rect_mfma_" + dtype, layers, 27, 1, 2, 2, 27 + 46, 27 + 61, 0.3, "ellipses", dtype=dtype,
+                          seed_image=1131, seed_label=2131, seed_param=3131)
+        net = mpcnn.Net(cfg.layers, cfg.in_channels, cfg.patch, dtype=mpcnn.BF16 if dtype == "bf16" else mpcnn.F32)
+        plan = net.plan_describe(cfg.batch, cfg.height, cfg.width, True)
+        net.close()
+        behind = plan[plan.index("layer 2:"):]
+        assert "plain kernel" not in behind, plan
+        assert "spacing 2 x 3" in behind and "k 5 x 3, spacing 4 x 6" in behind, plan
+        full_parity(cfg, with_pixw=True, ignore_some=True)
+
+
 def test_class_layer_variants():
     """Class layer shapes: 3 and 4 classes on 12 / 20 hidden units (fused kernel, ragged
     channel tail), 6 classes (generic path), hidden width above 128 (wide fused variant)."""
