@@ -289,19 +289,22 @@ __global__ __launch_bounds__(64 * NW, 2) void conv_mfma_kernel(ConvArgs a)
 }
 
 // The same product with the result tiles dealt out to the waves instead of the reduction
-// (fp32 matrix instruction, 32-wide tiles).  The workgroup's tile is 32*PT positions x 32*OT
-// output channels; each of its OT*PT/MP waves owns MP position tiles of ONE channel tile and
+// (fp32 matrix instruction; W-wide tiles, 32 or - for layers with 16 outputs or fewer - 16).  The
+// workgroup's tile is W*PT positions x W*OT output channels; each of its OT*PT/MP waves owns MP position tiles of ONE channel tile and
 // runs through all k*k*C/8 reduction steps for them, so no partial tiles meet anywhere: the
 // epilogue goes from the accumulators straight to memory (a lane holds 4 consecutive channels
 // of one position per register quad, one 128-bit store each).  A step feeds only 4*MP MFMAs, so
 // the operands are fetched through a ring D steps deep to cover the weights' trip from L2.
 // Summation order is the step order for every output element, whatever the tiling: equal
 // inputs give bit-equal outputs, and a position's value does not depend on how the map is cut.
-template <int OT, int PT, int MP, typename T>
+template <int OT, int PT, int MP, typename T, int W = 32>
 __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
 {
     static_assert(PT % MP == 0 && (OT * PT / MP == 4 || OT * PT / MP == 8), "4 or 8 waves");
-    constexpr int W = 32, G = 2;
+    static_assert(W == 32 || W == 16, "tile side of the matrix instruction");
+    constexpr int G = 64 / W;                      // lane groups = contraction index of one matrix instruction
+    constexpr int NQ = W * W / 256;                // register quads one lane holds of a result tile
+    typedef typename MfmaAcc<W>::type acc_t;
     constexpr int NW = OT * PT / MP, NT = 64 * NW;
     constexpr int D = MP == 1 ? 6 : 4;             // steps in flight
     const T* in_t = static_cast<const T*>(a.in);
@@ -310,7 +313,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lt = lane & 31, lg = lane >> 5;
+    const int lt = lane % W, lg = lane / W;
     const int wo = wave % OT, wp = wave / OT;      // channel tile, first of its MP position tiles is wp*MP
 
     int bid = blockIdx.x;
@@ -358,15 +361,15 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
         }
     }
 
-    // ---- the bias of this lane's four channel quads (channels oc0 + 8n + 4lg .. +3)
-    v4f bias4[4];
+    // ---- the bias of this lane's channel quads (channels oc0 + 4G n + 4lg .. +3)
+    v4f bias4[NQ];
 #pragma unroll
-    for (int n = 0; n < 4; ++n) {
+    for (int n = 0; n < NQ; ++n) {
         bias4[n] = (v4f){0.f, 0.f, 0.f, 0.f};
         if (a.mode <= kFwdLinear)
 #pragma unroll
             for (int z = 0; z < 4; ++z) {
-                const int c = oc0 + 8 * n + 4 * lg + z;
+                const int c = oc0 + 4 * G * n + 4 * lg + z;
                 bias4[n][z] = a.bias[c < a.Co ? c : a.Co - 1];
             }
     }
@@ -386,11 +389,11 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
     const int lane_w = lg * a.CoPad + oc0 + lt;   // this lane's offset inside one step of the pack
 
     { float agpr_hint = 0.f; asm volatile("" : "+a"(agpr_hint)); }
-    v16f acc[MP];
+    acc_t acc[MP];
 #pragma unroll
     for (int p = 0; p < MP; ++p)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[p][r] = 0.f;
+        for (int r = 0; r < 4 * NQ; ++r) acc[p][r] = 0.f;
 
     __syncthreads();
 
@@ -424,7 +427,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int p = 0; p < MP; ++p) acc[p] = mfma_f32<32>(wr[i][s], ar[i][p][s], acc[p]);
+            for (int p = 0; p < MP; ++p) acc[p] = mfma_f32<W>(wr[i][s], ar[i][p][s], acc[p]);
     };
 #pragma unroll
     for (int i = 0; i < D; ++i) fetch_first(i);
@@ -441,7 +444,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
         if (t + D + i < steps) mfmas(i);
 
     // ---- epilogue from the accumulators: register 4n + z of position tile p is channel
-    // oc0 + 8n + 4lg + z of position 32*(wp*MP + p) + lt
+    // oc0 + 4G n + 4lg + z of position W*(wp*MP + p) + lt
 #pragma unroll
     for (int p = 0; p < MP; ++p) {
         const int m = W * (wp * MP + p) + lt;
@@ -449,10 +452,10 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
         const int fy = ty0 + ty, fx = tx0 + tx;
         const bool pos_ok = ty < a.Ty && fy < fh && fx < fw;
         const long pos_off = (((long)b * a.Ho + (fy * a.d + ry)) * a.Wo + (fx * a.d2 + rx)) * a.Co;
-        v4f yv[4];
+        v4f yv[NQ];
 #pragma unroll
-        for (int n = 0; n < 4; ++n) {
-            const int oc = oc0 + 8 * n + 4 * lg;
+        for (int n = 0; n < NQ; ++n) {
+            const int oc = oc0 + 4 * G * n + 4 * lg;
             yv[n] = (v4f){0.f, 0.f, 0.f, 0.f};
             if (a.mode == kDgradTanh && pos_ok && oc < a.Co) {
                 if ((a.Co & 3) == 0) yv[n] = load4(act_t + pos_off + oc);
@@ -460,8 +463,8 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
             }
         }
 #pragma unroll
-        for (int n = 0; n < 4; ++n) {
-            const int oc = oc0 + 8 * n + 4 * lg;
+        for (int n = 0; n < NQ; ++n) {
+            const int oc = oc0 + 4 * G * n + 4 * lg;
             if (!pos_ok || oc >= a.Co) continue;
             v4f s = (v4f){acc[p][4 * n], acc[p][4 * n + 1], acc[p][4 * n + 2], acc[p][4 * n + 3]};
             if (a.mode == kFwdTanh) {

@@ -299,22 +299,25 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int d2, int k, int 
     double best_cost = 0;
     const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d2);
     const size_t pitch = bm ? 16 * (size_t)(rpad / 8 + 1) : sizeof(float) * (rpad + 4);   // one halo position in LDS
-    if (!bm && ct.W == 32) {
-        // conv_ts_kernel: 32*PT positions x 32*OT channels, OT*PT/MP waves.  Cost of the busiest CU:
+    if (!bm && (ct.W == 32 || ct.OT == 1)) {
+        // conv_ts_kernel: W*PT positions x W*OT channels, OT*PT/MP waves (16-wide: one channel tile, 32 cycles
+        // per instruction; 32-wide: 64 cycles).  Cost of the busiest CU:
         // its workgroups' matrix instructions one after the other, plus, once per round of
         // co-resident workgroups, what is not hidden behind another's multiplications
         // (staging the halo at ~8 bytes per cycle, a memory round trip, the stores).
-        const int steps = k * k2 * (rpad / 8);
-        for (int PT : {2, 4, 8})
-            for (int MP : {1, 2}) {
+        const bool w16 = ct.W == 16;
+        const int steps = k * k2 * (rpad / (w16 ? 16 : 8));
+        for (int PT : {2, 4, 8, 16})
+            for (int MP : {1, 2, 4}) {
                 const int NW = ct.OT * PT / MP;
                 if (PT % MP || (NW != 4 && NW != 8)) continue;
+                if (w16 ? PT < 4 : (PT > 8 || MP > 2)) continue;   // (the instances that are built)
                 if ((hint_pt && PT != hint_pt) || (hint_mp && MP != hint_mp)) continue;
                 // measured: a wave with one tile spends ~12 % more per instruction on operand
                 // fetches than one with two
-                const double t_mul1 = (double)steps * 4 * ct.OT * PT * 64 / 4 * (MP == 2 ? 1.0 : 1.12);
-                for (int ty = 1; ty <= std::min(fh, 32 * PT); ++ty)
-                    for (int tx = 1; tx <= std::min(fw, 32 * PT / ty); ++tx) {
+                const double t_mul1 = (double)steps * 4 * ct.OT * PT * (w16 ? 32 : 64) / 4 * (MP >= 2 ? 1.0 : 1.12);
+                for (int ty = 1; ty <= std::min(fh, ct.W * PT); ++ty)
+                    for (int tx = 1; tx <= std::min(fw, ct.W * PT / ty); ++tx) {
                         const size_t lds = std::max((size_t)(ty + k - 1) * (tx + k2 - 1) * pitch, (size_t)1024);
                         if (lds > (size_t)150 * 1024) break;
                         const int nty = ceil_div(fh, ty), ntx = ceil_div(fw, tx);
