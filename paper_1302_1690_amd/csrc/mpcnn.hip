@@ -1565,7 +1565,14 @@ mpcnn_status mpcnn_plan_describe(const mpcnn_net* net, int B, int H, int W, int 
             g.rows[l], g.cols[l]);
         if (ly.kind == MPCNN_MP) continue;
         if (ly.class_fused) { put("  fused class layer, %d workgroups\n", g.partial_n[l]); continue; }
-        conv("forward", ly, g.fwd[l], ly.fwd_ct, ly.fwd_bm);
+        const bool img_sides = ly.dil == 1 && !ly.rect && (ly.k == 3 || ly.k == 5 || ly.k == 7);
+        if (!g.fwd[l].ok && l == 0 && net->bf16 && img_sides && ly.cin <= 4 && ly.cout <= 64)
+            put("  forward: image-layer kernel on the bf16 MFMA\n");
+        else if (!g.fwd[l].ok && !net->bf16 && img_sides && (ly.cin == 1 || ly.cin == 3) &&
+                 (long)B * g.rows[l] * g.cols[l] < (1l << 31) / 32)
+            put("  forward: image-layer kernel on the fp32 MFMA\n");
+        else
+            conv("forward", ly, g.fwd[l], ly.fwd_ct, ly.fwd_bm);
         if (!training) continue;
         if (l > 0) conv("data gradient", ly, g.dgrad[l], ly.dgrad_ct, ly.dgrad_bm);
         const WgradPlan& w = g.wgrad[l];
