@@ -54,13 +54,17 @@ __global__ __launch_bounds__(64 * OT * PT / MP, 2) void conv_tp_kernel(ConvArgs 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lt = lane & 31, lg = lane >> 5;
-    const int wo = wave % OT, wp = wave / OT;      // channel tile, first of its MP position tiles is wp*MP
+    // channel tile, turned by the workgroup's index (a wave whose tile lies past the last channel - 200 maps in
+    // 8 tiles - only stages and waits: it should not sit on the same SIMD in both workgroups of a compute unit);
+    // the first of the wave's MP position tiles is wp*MP
+    const int wo = (wave + (int)(blockIdx.x % OT)) % OT, wp = wave / OT;
 
     const int hw = a.Tx + a.k - 1, hh = a.Ty + a.k - 1;
     const int cq = a.CrPad / CU;
     const int Cs4 = cq + 1;                        // pitch of one halo position in 128-bit units (+1: bank spread)
     const int n_items = hh * hw * cq;              // <= SI * NT (the host's plan sees to it)
     const int oc0 = W * (blockIdx.y * OT + wo);    // first channel of this wave's tile
+    const bool wave_live = oc0 < a.Co;             // uniform for the wave
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
 
     // ---- what this thread stages of every tile: item it = tid + NT*u is channels 8q.. of halo
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP, 2) void conv_tp_kernel(ConvArgs 
         for (int p = 0; p < MP; ++p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[p][r] = 0.f;
-        if (cur.live) {
+        if (cur.live && wave_live) {
             // Two rings.  The weights come from L2 (a layer's pack is far larger than the vector
             // cache), a trip of 1-2 K cycles under load, and a step lasts 32 MP cycles: DW = 8 steps
             // of weights are in flight.  The activations come from LDS: DA = 2.  Slot s % DW (s % DA)
@@ -274,7 +278,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP, 2) void conv_tp_kernel(ConvArgs 
                 }
             }
         };
-        if (cur.live) {
+        if (cur.live && wave_live) {
             if (a.mode == kFwdTanh) epilogue(std::integral_constant<int, kFwdTanh>{});
             else if (a.mode == kDgradTanh) epilogue(std::integral_constant<int, kDgradTanh>{});
             else if (a.mode == kFwdLinear) epilogue(std::integral_constant<int, kFwdLinear>{});

@@ -314,7 +314,10 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lt = lane % W, lg = lane / W;
-    const int wo = wave % OT, wp = wave / OT;      // channel tile, first of its MP position tiles is wp*MP
+    // channel tile (turned by the workgroup's index: where the last tile of the last group holds no channel at
+    // all - 200 maps in 8 tiles - its wave leaves after the staging, and the idle wave should not be the same
+    // SIMD's in every workgroup of a compute unit); the first of the wave's MP position tiles is wp*MP
+    const int wo = (wave + (int)(blockIdx.x % OT)) % OT, wp = wave / OT;
 
     int bid = blockIdx.x;
     const int txi = bid % a.ntx; bid /= a.ntx;
@@ -396,6 +399,8 @@ __global__ __launch_bounds__(64 * OT * PT / MP) void conv_ts_kernel(ConvArgs a)
         for (int r = 0; r < 4 * NQ; ++r) acc[p][r] = 0.f;
 
     __syncthreads();
+
+    if (oc0 >= a.Co) return;             // a tile past the last channel (uniform for the wave; no barrier follows)
 
     // the ring: slot i holds the operands of step t with t % D == i; fetches run in step order
     int chunk = 0, ta = 0, tb = 0, tf = 0;
