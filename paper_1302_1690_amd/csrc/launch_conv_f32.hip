@@ -6,7 +6,7 @@ namespace {
 typedef float T;
 // (OT, PT, MP) instances of conv_ts_kernel: OT*PT/MP is 4 or 8 waves
 #define CONV_TS_INSTANCES(X) \
-    X(4, 2, 1) X(4, 2, 2) X(4, 4, 2) X(2, 2, 1) X(2, 4, 1) X(2, 4, 2) X(2, 8, 2) X(1, 4, 1) X(1, 8, 1) X(1, 8, 2)
+    X(4, 2, 1) X(4, 2, 2) X(4, 4, 2) X(2, 2, 1) X(2, 4, 1) X(2, 4, 2) X(2, 8, 2) X(1, 4, 1) X(1, 8, 1) X(1, 8, 2) X(4, 4, 4) X(4, 8, 4) X(2, 8, 4) X(1, 16, 4)
 // ... and its 16-wide form (layers with 16 outputs or fewer): (PT, MP), PT/MP is 4 or 8 waves
 #define CONV_TS16_INSTANCES(X) X(4, 1) X(8, 1) X(8, 2) X(16, 2) X(16, 4)
 // (W, OT, PT) instances of conv_mfma_kernel, each with 4 and 8 waves

@@ -311,11 +311,16 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int d2, int k, int 
             for (int MP : {1, 2, 4}) {
                 const int NW = ct.OT * PT / MP;
                 if (PT % MP || (NW != 4 && NW != 8)) continue;
-                if (w16 ? PT < 4 : (PT > 8 || MP > 2)) continue;   // (the instances that are built)
+                const bool built4 = (ct.OT == 4 && (PT == 4 || PT == 8)) || (ct.OT == 2 && PT == 8) || (ct.OT == 1 && PT == 16);
+                if (w16 ? PT < 4 : (MP == 4 ? !built4 : PT > 8)) continue;   // (the instances that are built)
+                // four tiles per wave pay where the reduction is long: with 64 steps (2 x 2 taps of 128 channels) the
+                // longer epilogue and the fewer workgroups per compute unit cost more than the weight fetches saved
+                // (measured: 2012 -> 2074 us; 9 taps of 64 channels, 72 steps: 1242 -> 1185 us)
+                if (!w16 && MP == 4 && steps < 72) continue;
                 if ((hint_pt && PT != hint_pt) || (hint_mp && MP != hint_mp)) continue;
                 // measured: a wave with one tile spends ~12 % more per instruction on operand
                 // fetches than one with two
-                const double t_mul1 = (double)steps * 4 * ct.OT * PT * (w16 ? 32 : 64) / 4 * (MP >= 2 ? 1.0 : 1.12);
+                const double t_mul1 = (double)steps * 4 * ct.OT * PT * (w16 ? 32 : 64) / 4 * (MP >= 4 ? 0.94 : (MP >= 2 ? 1.0 : 1.12));   // (a weight fetch per 4 MP instructions: each costs the matrix pipe about 100 cycles)
                 for (int ty = 1; ty <= std::min(fh, ct.W * PT); ++ty)
                     for (int tx = 1; tx <= std::min(fw, ct.W * PT / ty); ++tx) {
                         const size_t lds = std::max((size_t)(ty + k - 1) * (tx + k2 - 1) * pitch, (size_t)1024);
