@@ -139,16 +139,17 @@ mpcnn_status mpcnn_set_loss(mpcnn_net* net, mpcnn_loss kind);
 typedef enum { MPCNN_TANH = 0, MPCNN_LOGISTIC = 1 } mpcnn_activation;
 mpcnn_status mpcnn_set_activation(mpcnn_net* net, mpcnn_activation kind);
 
-/* Tuning knob for the matrix-core convolution kernel of fp32-arithmetic layers with 32-wide
- * channel tiles (forward and data gradient; Method, forward and backward of layer C): a
- * workgroup computes 32 * position_tiles positions of one residue class and each of its waves
- * owns tiles_per_wave of them for one 32-channel tile.  0 leaves either choice to the library's
+/* Tuning knob for the matrix-core convolution kernel of fp32-arithmetic layers (forward and
+ * data gradient; Method, forward and backward of layer C): a workgroup computes 32 *
+ * position_tiles positions of one residue class (16 * position_tiles where a layer's 16 or fewer
+ * outputs put it on 16-wide tiles) and each of its waves owns tiles_per_wave of them for one
+ * channel tile.  0 leaves either choice to the library's
  * planner (the default), which weighs matrix-instruction time against staging per layer and
  * image size.  A pair that no kernel instance serves for a layer's channel count (the waves of
  * a workgroup, channel tiles * position_tiles / tiles_per_wave, must be 4 or 8) leaves that
  * layer on the planner's fallback kernel.  Results do not depend on the tiling: every output
  * element is the same sum in the same order.  Takes effect at the next forward / backward
- * call.  EINVAL unless position_tiles is 0, 2, 4 or 8 and tiles_per_wave 0, 1 or 2. */
+ * call.  EINVAL unless position_tiles is 0, 2, 4, 8 or 16 and tiles_per_wave 0, 1, 2 or 4. */
 mpcnn_status mpcnn_set_conv_tiling(mpcnn_net* net, int position_tiles, int tiles_per_wave);
 
 /* Per-class balanced pixel weights (Experiments, steel defects: the loss is minimised per

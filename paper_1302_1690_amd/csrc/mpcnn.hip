@@ -316,7 +316,7 @@ TilePlan plan_conv_tiles(int B, int out_r, int out_c, int d, int d2, int k, int 
                 // four tiles per wave pay where the reduction is long: with 64 steps (2 x 2 taps of 128 channels) the
                 // longer epilogue and the fewer workgroups per compute unit cost more than the weight fetches saved
                 // (measured: 2012 -> 2074 us; 9 taps of 64 channels, 72 steps: 1242 -> 1185 us)
-                if (!w16 && MP == 4 && steps < 72) continue;
+                if (!w16 && MP == 4 && steps < 72 && hint_mp != 4) continue;
                 if ((hint_pt && PT != hint_pt) || (hint_mp && MP != hint_mp)) continue;
                 // measured: a wave with one tile spends ~12 % more per instruction on operand
                 // fetches than one with two
@@ -1647,10 +1647,11 @@ mpcnn_status mpcnn_set_activation(mpcnn_net* net, mpcnn_activation kind)
 mpcnn_status mpcnn_set_conv_tiling(mpcnn_net* net, int position_tiles, int tiles_per_wave)
 {
     if (!net) return fail(MPCNN_EINVAL, "null net");
-    const bool pt_ok = position_tiles == 0 || position_tiles == 2 || position_tiles == 4 || position_tiles == 8;
-    const bool mp_ok = tiles_per_wave == 0 || tiles_per_wave == 1 || tiles_per_wave == 2;
+    const bool pt_ok = position_tiles == 0 || position_tiles == 2 || position_tiles == 4 || position_tiles == 8 ||
+                       position_tiles == 16;
+    const bool mp_ok = tiles_per_wave == 0 || tiles_per_wave == 1 || tiles_per_wave == 2 || tiles_per_wave == 4;
     if (!pt_ok || !mp_ok)
-        return fail(MPCNN_EINVAL, "conv tiling (%d, %d): position tiles 0/2/4/8, tiles per wave 0/1/2", position_tiles, tiles_per_wave);
+        return fail(MPCNN_EINVAL, "conv tiling (%d, %d): position tiles 0/2/4/8/16, tiles per wave 0/1/2/4", position_tiles, tiles_per_wave);
     net->hint_pt = position_tiles; net->hint_mp = tiles_per_wave;
     net->geoms.clear();
     return MPCNN_OK;

@@ -386,7 +386,7 @@ def test_every_conv_tiling():
     """Every instance of the matrix-core convolution kernel (position tiles per workgroup x
     tiles per wave, for layers of 1, 2 and 4 channel tiles; fp32 and bf16 storage) against the
     oracle: config 1's net has 32-, 64- and 100-map layers in both directions."""
-    for pt, mp in ((2, 1), (2, 2), (4, 1), (4, 2), (8, 1), (8, 2)):
+    for pt, mp in ((2, 1), (2, 2), (4, 1), (4, 2), (8, 1), (8, 2), (4, 4), (8, 4), (16, 2), (16, 4)):
         say("conv tiling: %d position tiles, %d per wave" % (pt, mp))
         full_parity(wl.crop(wl.CONFIGS[1], 1, 75, 81), check_layers=False, tiling=(pt, mp))
         # bf16 storage, channel counts that keep the layers on the fp32 matrix instruction
@@ -396,7 +396,7 @@ def test_every_conv_tiling():
                                 seed_image=1114, seed_label=2114, seed_param=3114), check_layers=False,
                     tiling=(pt, mp))
     net = mpcnn.Net(wl.CONFIGS[0].layers, wl.CONFIGS[0].in_channels, wl.CONFIGS[0].patch)
-    for bad in ((3, 1), (2, 3), (-2, 0), (16, 2)):
+    for bad in ((3, 1), (2, 3), (-2, 0), (32, 2), (8, 8)):
         with pytest.raises(mpcnn.MpcnnError):
             net.set_conv_tiling(*bad)
     net.set_conv_tiling(0, 0)
