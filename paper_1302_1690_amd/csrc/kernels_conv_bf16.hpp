@@ -108,6 +108,10 @@ __global__ __launch_bounds__(64 * OT * PT / MP, 2) void conv_tp_kernel(ConvArgs 
     const int nch = a.CrPad / (CU * G);
     const int steps = a.k * a.k * nch;
     const int lane_w = lg * a.CoPad + oc0 + lt;    // this lane's offset inside one step of the pack
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<v4f*>(a.wpack), 0, steps * G * a.CoPad * 16, 0x00020000);   // (raw data, range-checked)
+    const int wlane = lane_w * 16;                 // bytes
 
     struct Tile { int b, ry, rx, ty0, tx0, fh, fw; bool live; };
     auto decode = [&](int t) {
@@ -180,11 +184,16 @@ __global__ __launch_bounds__(64 * OT * PT / MP, 2) void conv_tp_kernel(ConvArgs 
             // cache), a trip of 1-2 K cycles under load, and a step lasts 32 MP cycles: DW = 8 steps
             // of weights are in flight.  The activations come from LDS: DA = 2.  Slot s % DW (s % DA)
             // holds the operand of step s; fetches run in step order.
+            // (weights through a buffer descriptor: the lane's byte offset is fixed, the step's is a scalar - no
+            // vector-ALU instruction per fetch, which would take an issue slot from the matrix instructions)
             int chunk = 0, ta = 0, tb = 0;
-            const v4f* wq = a.wpack + lane_w;
-            const long wstep = (long)G * a.CoPad;
+            int wq = 0;                                // byte offset of the next step in the pack
+            const int wstep = G * a.CoPad * 16;
             v4f wr[DW], ar[DA][MP];
-            auto fetch_w = [&](int i) { wr[i] = *wq; wq += wstep; };
+            auto fetch_w = [&](int i) {
+                wr[i] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, wq, 0));
+                wq += wstep;
+            };
             auto fetch_a = [&](int i) {
                 const int soff = (ta * hw + tb) * Cs4 + G * chunk;
 #pragma unroll
@@ -203,7 +212,7 @@ __global__ __launch_bounds__(64 * OT * PT / MP, 2) void conv_tp_kernel(ConvArgs 
             // loop starts and would wait for ALL of them at the top of every round.
 #pragma unroll
             for (int i = 0; i < DW; ++i) {
-                wr[i] = *wq;
+                wr[i] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, wq, 0));
                 wq += i + 1 < steps ? wstep : 0;
             }
 #pragma unroll

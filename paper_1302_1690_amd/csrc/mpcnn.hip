@@ -1469,6 +1469,10 @@ mpcnn_status mpcnn_net_create(const mpcnn_layer_desc* layers, int n_layers, int 
             ly.fwd_mfma = !last && ly.cin % 4 == 0 && ly.cin >= 8 && ly.cout >= 8;
             ly.dgrad_mfma = l > 0 && ly.cout % 4 == 0 && ly.cout >= 8 && ly.cin >= 8;
             ly.wgrad_mfma = !ly.class_fused;   // any shape: gradient rows are tiled in parameter order
+            // (the convolution kernels address a layer's weight pack by 32-bit byte offsets)
+            const size_t pack_bound = (size_t)ly.k * ly.k2 * (ceil_div(std::max(ly.cin, ly.cout), 32) * 32 + 32) *
+                                      (ceil_div(std::max(ly.cin, ly.cout), 32) * 32 + 32) * 4;
+            if (pack_bound >= (1ull << 31)) ly.fwd_mfma = ly.dgrad_mfma = false;
             // bf16 storage with channel counts that are multiples of 8: the bf16 matrix instruction
             ly.fwd_bm = net->bf16 && !ly.rect && ly.fwd_mfma && ly.cin % 8 == 0;
             ly.dgrad_bm = net->bf16 && !ly.rect && ly.dgrad_mfma && ly.cout % 8 == 0;
