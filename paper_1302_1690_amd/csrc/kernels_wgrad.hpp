@@ -150,9 +150,9 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
         // here beyond its trip to memory is kept as small as possible.
         unsigned h_yx[HL];   // (halo row * d) << 16 | halo col * d
         int h_dst[HL];       // channel 4q << 20 | float index in a buffer of the item (its quad plane, its position), -1 = none
-        unsigned h_off[HL];  // element offset of the item from the halo's first element (0 if none)
+        unsigned h_off[HL];  // BYTE offset of the item from the halo's first element (0 if none)
         unsigned d_tyx[DL];  // tile row << 16 | tile col
-        int d_rel[DL];       // float offset of the item from the tile's first delta, -1 = never inside
+        int d_rel[DL];       // BYTE offset of the item from the tile's first delta (0 for items never inside)
         int d_dst[DL];       // float index in a buffer (of the 16 unread bytes for items never inside: added to either buffer's base it stays there), -1 = none
 #pragma unroll
         for (int u = 0; u < HL; ++u) {
@@ -163,20 +163,20 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                 const unsigned ha = magic_div(pos, a.mg_hwp, hwp), hb = pos - ha * hwp;
                 h_yx[u] = ((ha * a.d) << 16) | (hb * a.d2);
                 h_dst[u] = (int)((4 * q) << 20 | (dt_f + q * QP + 4 * (ha * hwp + hb)));
-                h_off[u] = ((ha * a.d) * a.Wi + hb * a.d2) * a.Ci + 4 * q;
+                h_off[u] = (((ha * a.d) * a.Wi + hb * a.d2) * a.Ci + 4 * q) * (unsigned)sizeof(T);
             }
         }
 #pragma unroll
         for (int u = 0; u < DL; ++u) {
             const unsigned it = ltid + 256 * u;
-            d_tyx[u] = 0; d_rel[u] = -1; d_dst[u] = -1;
+            d_tyx[u] = 0; d_rel[u] = 0; d_dst[u] = -1;
             if (it < (unsigned)d_items) {
                 const unsigned m = it >> dq_shift, q = it - (m << dq_shift);
                 const unsigned ty = magic_div(m, a.mg_txp, a.TxP), tx = m - ty * a.TxP;
                 const int oc = 32 * blockIdx.z * wn + 4 * q;
                 d_tyx[u] = (ty << 16) | tx;
                 d_dst[u] = (int)((q >> 3) * OB + 4 * (q & 7) + ty * RB + tx * 32);
-                if (tx < (unsigned)a.Tx && oc < a.Co) d_rel[u] = (int)((ty * a.d * a.Wo + tx * a.d2) * a.Co) + oc;
+                if (tx < (unsigned)a.Tx && oc < a.Co) d_rel[u] = ((int)((ty * a.d * a.Wo + tx * a.d2) * a.Co) + oc) * (int)sizeof(T);
                 else {
                     // never inside: zero in both buffers now, and from here on the item's store
                     // goes to the unread bytes
@@ -200,22 +200,30 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                                 y0 + halo_h < a.Hi && x0 + halo_w < a.Wi;     // uniform
             // all loads of the tile first: one trip to memory
             if (inside) {
-                const T* in_t0 = in_b + (unsigned)(y0 * a.Wi + x0) * a.Ci;
-                const T* dy_t0 = dy_b + dbase;
+                // through buffer descriptors of this image's two tensors (the host keeps them under 4 GiB): a
+                // load's address is the thread's fixed byte offset plus a scalar, so these waves, which share
+                // their SIMDs with the multiplying ones, spend no vector-ALU instruction on it
+                const __amdgpu_buffer_rsrc_t in_r = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<T*>(in_b), 0, (int)((unsigned)(a.Hi * a.Wi * a.Ci) * (unsigned)sizeof(T)), 0x00020000);
+                const __amdgpu_buffer_rsrc_t dy_r = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<T*>(dy_b), 0, (int)((unsigned)(a.Ho * a.Wo * a.Co) * (unsigned)sizeof(T)), 0x00020000);
+                const unsigned in_s = (unsigned)(y0 * a.Wi + x0) * a.Ci * (unsigned)sizeof(T);
+                const unsigned dy_s = (unsigned)dbase * (unsigned)sizeof(T);
 #pragma unroll
-                for (int u = 0; u < HL; ++u) hr[u] = load4(in_t0 + h_off[u]);
+                for (int u = 0; u < HL; ++u) hr[u] = buffer_load4<T>(in_r, h_off[u], in_s);
 #pragma unroll
-                for (int u = 0; u < DL; ++u) dr[u] = load4(dy_t0 + (d_rel[u] < 0 ? 0 : d_rel[u]));
+                for (int u = 0; u < DL; ++u) dr[u] = buffer_load4<T>(dy_r, (unsigned)d_rel[u], dy_s);
                 okmask = ~0u;
             } else {
             if (vec_in) {
                 // a halo element outside the input meets only zero deltas, so any finite value
                 // will do for it: the offset is merely kept inside this image's tensor
-                const unsigned base = (unsigned)(y0 * a.Wi + x0) * a.Ci, last = (unsigned)(a.Hi * a.Wi * a.Ci) - 4u;
+                const unsigned base = (unsigned)(y0 * a.Wi + x0) * a.Ci * (unsigned)sizeof(T);
+                const unsigned last = ((unsigned)(a.Hi * a.Wi * a.Ci) - 4u) * (unsigned)sizeof(T);
 #pragma unroll
                 for (int u = 0; u < HL; ++u) {
-                    const unsigned off = base + h_off[u];
-                    hr[u] = load4(in_b + (off < last ? off : last));
+                    const unsigned off = base + h_off[u];                       // in bytes
+                    hr[u] = load4(reinterpret_cast<const T*>(reinterpret_cast<const char*>(in_b) + (off < last ? off : last)));
                 }
             } else {
 #pragma unroll
@@ -231,12 +239,12 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
             }
 #pragma unroll
             for (int u = 0; u < DL; ++u) {
-                const bool ok = d_rel[u] >= 0 && (int)(d_tyx[u] >> 16) < t.rows && (int)(d_tyx[u] & 0xffffu) < t.cols;
+                const bool ok = d_dst[u] >= 0 && (int)(d_tyx[u] >> 16) < t.rows && (int)(d_tyx[u] & 0xffffu) < t.cols;
                 okmask |= ok ? (1u << u) : 0u;
-                const unsigned off = ok ? (unsigned)(dbase + d_rel[u]) : 0u;   // in elements
+                const unsigned off = ok ? (unsigned)(dbase + d_rel[u] / (int)sizeof(T)) : 0u;   // in elements
                 if (vec_dy) dr[u] = load4(dy_b + off);
                 else {
-                    const int oc = ok ? d_rel[u] % a.Co : 0;   // rare path: Co not a multiple of 4
+                    const int oc = ok ? (d_rel[u] / (int)sizeof(T)) % a.Co : 0;   // rare path: Co not a multiple of 4
 #pragma unroll
                     for (int z = 0; z < 4; ++z) dr[u][z] = (ok && oc + z < a.Co) ? load1(dy_b + off + z) : 0.f;
                 }

@@ -145,10 +145,10 @@ __global__ __launch_bounds__(512, 1) void wgrad_tr_kernel(WgradArgs a)
         // items decoded once: they are the same for every tile
         unsigned h_yx[HL];   // (halo row * d) << 16 | halo col * d
         int h_dst[HL];       // byte offset in a buffer, -1 = none
-        unsigned h_off[HL];  // element offset of the item from the halo's first element
+        unsigned h_off[HL];  // byte offset of the item from the halo's first element
         unsigned d_tyx[DL];  // tile row << 16 | tile col
-        int d_rel[DL];       // element offset of the item from the tile's first delta, -1 = never inside
-        int d_dst[DL];       // byte offset in a buffer, -1 = none
+        int d_rel[DL];       // byte offset of the item from the tile's first delta (0 where there is none)
+        int d_dst[DL];       // byte offset in a buffer, -1 = none (or never inside: zeroed once, below)
 #pragma unroll
         for (int u = 0; u < HL; ++u) {
             const unsigned it = ltid + 256 * u;
@@ -158,20 +158,28 @@ __global__ __launch_bounds__(512, 1) void wgrad_tr_kernel(WgradArgs a)
                 const unsigned ha = magic_div(pos, a.mg_hwp, hwp), hb = pos - ha * hwp;
                 h_yx[u] = ((ha * a.d) << 16) | (hb * a.d);
                 h_dst[u] = (int)(g.halo_b + ((q >> 2) * g.hplane + pos) * 64 + (q & 3) * 16);
-                h_off[u] = ((ha * a.d) * a.Wi + hb * a.d) * a.Ci + 8 * q;
+                h_off[u] = (((ha * a.d) * a.Wi + hb * a.d) * a.Ci + 8 * q) * 2u;   // in bytes
             }
         }
 #pragma unroll
         for (int u = 0; u < DL; ++u) {
             const unsigned it = ltid + 256 * u;
-            d_tyx[u] = 0; d_rel[u] = -1; d_dst[u] = -1;
+            d_tyx[u] = 0; d_rel[u] = 0; d_dst[u] = -1;
             if (it < (unsigned)d_items) {
                 const unsigned m = it >> dq_shift, q = it - (m << dq_shift);
                 const unsigned ty = m / TxP, tx = m - ty * TxP;
                 const int oc = 64 * blockIdx.z * wn + 8 * q;
                 d_tyx[u] = (ty << 16) | tx;
                 d_dst[u] = (int)(((q >> 2) * g.dplane + m) * 64 + (q & 3) * 16);
-                if (tx < (unsigned)a.Tx && oc < a.Co) d_rel[u] = (int)((ty * a.d * a.Wo + tx * a.d) * a.Co) + oc;
+                if (tx < (unsigned)a.Tx && oc < a.Co) d_rel[u] = 2 * ((int)((ty * a.d * a.Wo + tx * a.d) * a.Co) + oc);
+                else {
+                    // never inside (a column past the tile's width, a channel past the last): zero in both
+                    // buffers now, never stored again
+                    typedef unsigned z32x4 __attribute__((ext_vector_type(4)));
+                    *reinterpret_cast<z32x4*>(ldsb + d_dst[u]) = (z32x4){0u, 0u, 0u, 0u};
+                    *reinterpret_cast<z32x4*>(ldsb + g.buf_b + d_dst[u]) = (z32x4){0u, 0u, 0u, 0u};
+                    d_dst[u] = -1;
+                }
             }
         }
         typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -195,9 +203,15 @@ __global__ __launch_bounds__(512, 1) void wgrad_tr_kernel(WgradArgs a)
             // all loads of the tile first: one trip to memory.  A halo element outside the input
             // meets only zero deltas, so any finite value will do for it: clamped coordinates.
             if (inside) {
-                const bf16* in_t0 = in_b + (unsigned)(y0 * a.Wi + x0) * a.Ci;
+                // through a buffer descriptor of this image's tensor (under 4 GiB, the host sees to it): the
+                // address is the thread's fixed byte offset plus a scalar - no vector-ALU instruction per load
+                // on these waves, which share their SIMDs with the multiplying ones
+                const __amdgpu_buffer_rsrc_t in_r = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<bf16*>(in_b), 0, (int)((unsigned)(a.Hi * a.Wi * a.Ci) * 2u), 0x00020000);
+                const unsigned in_s = (unsigned)(y0 * a.Wi + x0) * a.Ci * 2u;
 #pragma unroll
-                for (int u = 0; u < HL; ++u) hr[u] = *reinterpret_cast<const u32x4*>(in_t0 + h_off[u]);
+                for (int u = 0; u < HL; ++u)
+                    hr[u] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(in_r, (int)h_off[u], (int)in_s, 0));
             } else {
 #pragma unroll
                 for (int u = 0; u < HL; ++u) {
@@ -209,13 +223,23 @@ __global__ __launch_bounds__(512, 1) void wgrad_tr_kernel(WgradArgs a)
                     hr[u] = *reinterpret_cast<const u32x4*>(in_b + (unsigned)(iy * a.Wi + ix) * a.Ci + 8 * q);
                 }
             }
+            if (vec_dy && t.rows >= 4 && t.cols >= a.Tx) {
+                // the whole tile lies inside its residue class: every item that is ever stored is valid
+                const __amdgpu_buffer_rsrc_t dy_r = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<bf16*>(dy_b), 0, (int)((unsigned)(a.Ho * a.Wo * a.Co) * 2u), 0x00020000);
+                const unsigned dy_s = (unsigned)dbase * 2u;
+#pragma unroll
+                for (int u = 0; u < DL; ++u)
+                    dr[u] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                          dy_r, d_rel[u], (int)dy_s, 0));
+            } else
 #pragma unroll
             for (int u = 0; u < DL; ++u) {
                 const int ty = (int)(d_tyx[u] >> 16), tx = (int)(d_tyx[u] & 0xffffu);
-                const bool ok = d_rel[u] >= 0 && ty < t.rows && tx < t.cols;
-                const unsigned off = ok ? (unsigned)(dbase + d_rel[u]) : 0u;
+                const bool ok = d_dst[u] >= 0 && ty < t.rows && tx < t.cols;
+                const unsigned off = ok ? (unsigned)(dbase + (d_rel[u] >> 1)) : 0u;
                 if (vec_dy) dr[u] = *reinterpret_cast<const u32x4*>(dy_b + off);
-                else dr[u] = load8(dy_b + off, false, ok ? a.Co - d_rel[u] % a.Co : 0);   // (rare: channel count not a multiple of 8)
+                else dr[u] = load8(dy_b + off, false, ok ? a.Co - (d_rel[u] >> 1) % a.Co : 0);   // (rare: channel count not a multiple of 8)
                 if (!ok) dr[u] = (u32x4){0u, 0u, 0u, 0u};
             }
 #pragma unroll

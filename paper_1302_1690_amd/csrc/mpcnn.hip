@@ -418,8 +418,11 @@ WgradPlan plan_wgrad(const Layer& ly, int B, int in_r, int in_c, int out_r, int 
     const int d = ly.dil, k = ly.k, d2 = ly.dil2, k2 = ly.k2;   // rows; columns
     const int fh = ceil_div(out_r, d), fw = ceil_div(out_c, d2);
     // the kernel forms element offsets inside one image in 32 bits
+    // (and, through buffer descriptors, byte offsets inside one image's tensor in 32 bits)
+    const size_t es = bm ? 2 : 4;
     const bool fits32 = (size_t)in_r * in_c * ly.cin < (1ull << 31) &&
-                        (size_t)out_r * out_c * ly.cout < (1ull << 31) && (k + 3) * d < 65536;
+                        (size_t)out_r * out_c * ly.cout < (1ull << 31) && (k + 3) * d < 65536 &&
+                        (size_t)in_r * in_c * ly.cin * es < (1ull << 32) && (size_t)out_r * out_c * ly.cout * es < (1ull << 32);
     // the bf16 instruction's kernels take square filters at one spacing only
     bm = bm && !ly.rect;
     // the bf16 instruction's kernel gives a wave pairs of column tiles: not for 32 maps or fewer

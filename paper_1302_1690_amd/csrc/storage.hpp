@@ -23,6 +23,20 @@ __device__ __forceinline__ void store4(bf16* p, v4f v)
 {
     *reinterpret_cast<bf16x4*>(p) = __builtin_convertvector(v, bf16x4);
 }
+// The same four elements through a buffer descriptor: byte offset = per-lane part + scalar part (no address
+// arithmetic on the vector ALU; out-of-range reads return zeros)
+template <typename T>
+__device__ __forceinline__ v4f buffer_load4(__amdgpu_buffer_rsrc_t rsrc, unsigned lane_bytes, unsigned scalar_bytes)
+{
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    typedef unsigned v2u __attribute__((ext_vector_type(2)));
+    if constexpr (sizeof(T) == 4) {
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_bytes, (int)scalar_bytes, 0));
+    } else {
+        const v2u r = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)lane_bytes, (int)scalar_bytes, 0);
+        return __builtin_convertvector(__builtin_bit_cast(bf16x4, r), v4f);
+    }
+}
 __device__ __forceinline__ float load1(const float* p) { return *p; }
 __device__ __forceinline__ float load1(const bf16* p) { return (float)*p; }
 __device__ __forceinline__ void store1(float* p, float v) { *p = v; }
