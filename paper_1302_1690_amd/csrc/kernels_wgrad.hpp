@@ -85,7 +85,6 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
     const int OB = a.TxP * 32 + 32, RB = wn * OB;
     const int dt_f = 4 * RB;                    // delta tile first (128-bit aligned), halo behind it
     const int buf_f = dt_f + cq * QP;
-    const int trash_f = 2 * buf_f + 16;         // 16 bytes that nobody reads, behind the slack of the second buffer
 
     const int rows_total = a.k * a.k2 * a.Ci;
     // ---- a multiplying wave's result tiles: rows 32*(mt0 + p), p < np; columns 32*nt
@@ -149,11 +148,11 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
         // multiplying waves wait for these waves at every tile's barrier, so what a tile costs
         // here beyond its trip to memory is kept as small as possible.
         unsigned h_yx[HL];   // (halo row * d) << 16 | halo col * d
-        int h_dst[HL];       // channel 4q << 20 | float index in a buffer of the item (its quad plane, its position), -1 = none
+        int h_dst[HL];       // float index in a buffer of the item (its quad plane, its position), -1 = none
         unsigned h_off[HL];  // BYTE offset of the item from the halo's first element (0 if none)
         unsigned d_tyx[DL];  // tile row << 16 | tile col
         int d_rel[DL];       // BYTE offset of the item from the tile's first delta (0 for items never inside)
-        int d_dst[DL];       // float index in a buffer (of the 16 unread bytes for items never inside: added to either buffer's base it stays there), -1 = none
+        int d_dst[DL];       // float index in a buffer (items never inside: in the unread padding of their block), -1 = none
 #pragma unroll
         for (int u = 0; u < HL; ++u) {
             const unsigned it = ltid + 256 * u;
@@ -162,7 +161,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                 const unsigned pos = magic_div(it, a.mg_cq, cq), q = it - pos * cq;
                 const unsigned ha = magic_div(pos, a.mg_hwp, hwp), hb = pos - ha * hwp;
                 h_yx[u] = ((ha * a.d) << 16) | (hb * a.d2);
-                h_dst[u] = (int)((4 * q) << 20 | (dt_f + q * QP + 4 * (ha * hwp + hb)));
+                h_dst[u] = (int)(dt_f + q * QP + 4 * (ha * hwp + hb));
                 h_off[u] = (((ha * a.d) * a.Wi + hb * a.d2) * a.Ci + 4 * q) * (unsigned)sizeof(T);
             }
         }
@@ -183,7 +182,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                     const v4f z4 = {0.f, 0.f, 0.f, 0.f};
                     *reinterpret_cast<v4f*>(lds + d_dst[u]) = z4;
                     *reinterpret_cast<v4f*>(lds + buf_f + d_dst[u]) = z4;
-                    d_dst[u] = -2;
+                    d_dst[u] = (int)((q >> 3) * OB + ty * RB + a.TxP * 32 + 4 * (q & 7));   // the block's 32 floats of padding
                 }
             }
         }
@@ -231,7 +230,8 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
                 int iy = y0 + (int)(h_yx[u] >> 16), ix = x0 + (int)(h_yx[u] & 0xffffu);
                 iy = iy < a.Hi ? iy : a.Hi - 1;
                 ix = ix < a.Wi ? ix : a.Wi - 1;
-                const int q4 = h_dst[u] < 0 ? 0 : h_dst[u] >> 20;
+                const unsigned it = ltid + 256 * u;
+                const int q4 = h_dst[u] < 0 ? 0 : (int)(4 * (it - magic_div(it, a.mg_cq, cq) * cq));
                 const unsigned off = (unsigned)(iy * a.Wi + ix) * a.Ci + q4;   // in elements
 #pragma unroll
                 for (int z = 0; z < 4; ++z) hr[u][z] = q4 + z < a.Ci ? load1(in_b + off + z) : 0.f;
@@ -253,13 +253,12 @@ __global__ __launch_bounds__(512, 1) void wgrad_mfma_kernel(WgradArgs a)
 #pragma unroll
             for (int u = 0; u < HL; ++u)
                 if (u < h_full || h_dst[u] >= 0)        // first test is uniform: whole rounds store unmasked
-                    *reinterpret_cast<v4f*>(buf + (h_dst[u] & 0xfffff)) = hr[u];
-            float* const trash = lds + trash_f;
+                    *reinterpret_cast<v4f*>(buf + h_dst[u]) = hr[u];
 #pragma unroll
             for (int u = 0; u < DL; ++u) {
-                if (u < d_full || d_dst[u] != -1) {
+                if (u < d_full || d_dst[u] >= 0) {
                     const v4f z4 = {0.f, 0.f, 0.f, 0.f};
-                    float* dst = d_dst[u] == -2 ? trash : buf + d_dst[u];
+                    float* dst = buf + d_dst[u];
                     if (inside) *reinterpret_cast<v4f*>(dst) = dr[u];
                     else *reinterpret_cast<v4f*>(dst) = ((okmask >> u) & 1u) ? dr[u] : z4;
                 }
